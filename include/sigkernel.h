@@ -1,0 +1,106 @@
+/*
+ * sigkernel.h - C ABI of the MI355X (gfx950) signature-kernel library.
+ *
+ * What is computed (paper Section 3): for piecewise-linear paths x (L1 points in R^d) and y (L2 points)
+ * the signature kernel k(x,y) = <S(x), S(y)> is the value at the far corner of the solution of the
+ * Goursat PDE d2k/dsdt = <x'(s), y'(t)> k, k(0,.) = k(.,0) = 1 (Section 3.1), discretised by the explicit
+ * scheme Eq. (1)
+ *     k[i+1,j+1] = (k[i+1,j] + k[i,j+1]) A(p) - k[i,j] B(p),  A = 1 + p/2 + p^2/12,  B = 1 - p^2/12,
+ * on the dyadically refined grid of 2^lam1 (L1-1) by 2^lam2 (L2-1) cells, with
+ *     p = 2^-(lam1+lam2) <x[a+1]-x[a], y[b+1]-y[b]>,  a = i >> lam1,  b = j >> lam2
+ * (refinement applied on the fly, Section 3.2 item (3); lam1 != lam2 allowed, item (1)).
+ * The backward entry points return the exact gradients of that discrete scheme with respect to the
+ * path points (Section 3.4: the adjoint recurrence for dF/dk[i,j], the local derivative giving
+ * dF/dDelta, and the linear map from dF/dDelta to dF/dx and dF/dy).
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers to dense row-major arrays owned by the caller; a path batch
+ *    is [count, L, d] with d fastest.  Element type is given by `dt` (float or double) for every array
+ *    of the call.  Outputs are overwritten, never accumulated into.
+ *  - `ws` is caller-owned device scratch of at least sigkernel_workspace_bytes(...) bytes for the same
+ *    arguments, 256-byte aligned; its contents are undefined afterwards.  The library allocates and frees
+ *    nothing.
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue work: no host
+ *    synchronisation, results are complete when the stream reaches the end of the call's work.
+ *    Two calls that share a workspace must be ordered (same stream).
+ *  - Return value: SK_OK (0) or a negative error code; nothing is enqueued on error.  Errors never
+ *    throw or exit.  sigkernel_last_error() gives a thread-local message for the last non-zero return.
+ *  - Empty batches (B = 0, N*M = 0) are a successful no-op.  A path with a single point (L = 1) has no
+ *    increments: k = 1 and all gradients are 0.
+ *  - flags: SK_FLAG_TIME_AUG appends the channel t_i = i/(L-1) to both paths on the fly (Section 4);
+ *    gradients are returned for the original d channels only.
+ */
+#ifndef SIGKERNEL_H
+#define SIGKERNEL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SK_F32 = 0, SK_F64 = 1 } sk_dtype;
+
+enum { SK_FLAG_TIME_AUG = 1 };
+
+enum {
+    SK_OK = 0,
+    SK_ERR_NULL = -1,      /* a required pointer is NULL */
+    SK_ERR_SHAPE = -2,     /* L < 1, d < 1, negative batch, or (L-1) << lam does not fit in 31 bits */
+    SK_ERR_DYADIC = -3,    /* lam1 or lam2 negative or above 20 */
+    SK_ERR_DTYPE = -4,     /* dt is neither SK_F32 nor SK_F64; unknown flag bits */
+    SK_ERR_WORKSPACE = -5, /* ws is NULL, misaligned or smaller than the query says */
+    SK_ERR_HIP = -6        /* a HIP runtime call failed (message has the HIP error string) */
+};
+
+/* Operations for the workspace query. */
+enum { SK_OP_FWD = 0, SK_OP_BWD = 1, SK_OP_GRAM = 2, SK_OP_GRAM_BWD = 3 };
+
+/*
+ * Bytes of device scratch the operation `op` needs.  Pure host arithmetic, no GPU required.
+ * B_or_N is B for SK_OP_FWD / SK_OP_BWD (M ignored) and N for the Gram operations.  Returns 0 for
+ * invalid arguments or empty batches.
+ */
+size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d,
+                                 int lam1, int lam2, int flags, sk_dtype dt);
+
+/*
+ * Forward over a batch of pairs (Algorithm "CPU Algorithm for Signature Kernels", Eq. (1)):
+ *   x[B,L1,d], y[B,L2,d]  ->  k[B],  k[b] = k(x[b], y[b]).
+ */
+int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, int64_t L2, int64_t d,
+                  int lam1, int lam2, int flags, sk_dtype dt, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward over a batch of pairs (Section 3.4 and Algorithm "CPU Algorithm for Backpropagation through
+ * Signature Kernels"): given grad_k[B] = dF/dk[b], writes
+ *   grad_x[B,L1,d] = dF/dx,  grad_y[B,L2,d] = dF/dy   (either may be NULL = not wanted)
+ * and, if k_out != NULL, k_out[B] = k(x[b], y[b]) (the forward values are recomputed inside).
+ */
+int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
+                  int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Gram matrix (the N x M product set of Eq. (1) solves): X[N,L1,d], Y[M,L2,d] -> K[N,M] = k(X[n], Y[m]).
+ * If grad_K[N,M] = dF/dK is not NULL, also
+ *   grad_X[n] = sum_m grad_K[n,m] dk(X[n],Y[m])/dX[n],   grad_Y[m] = sum_n grad_K[n,m] dk(X[n],Y[m])/dY[m]
+ * (either may be NULL).  K may be NULL when grad_K is given.  Y == X (same pointer, N == M, L1 == L2)
+ * selects the symmetric case K(X,X): grad_X then receives the total derivative (both argument slots)
+ * and grad_Y is ignored.
+ */
+int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, void* grad_X, void* grad_Y,
+                   int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags,
+                   sk_dtype dt, void* ws, size_t ws_bytes, void* stream);
+
+/* Thread-local, NUL-terminated message describing the last non-zero return on this thread. */
+const char* sigkernel_last_error(void);
+
+/* Library version string. */
+const char* sigkernel_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIGKERNEL_H */

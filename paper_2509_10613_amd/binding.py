@@ -1,0 +1,164 @@
+"""Thin ctypes binding of libsigkernel.so (the C ABI declared in include/sigkernel.h).
+
+Argument marshalling only: every step of the method runs in the HIP kernels.  PyTorch is used for device
+memory and streams.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsigkernel.so")
+
+SK_F32, SK_F64 = 0, 1
+SK_FLAG_TIME_AUG = 1
+SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
+
+EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram",
+           "sigkernel_last_error", "sigkernel_version"]
+
+_lib = None
+
+
+class SigKernelError(RuntimeError):
+    pass
+
+
+def load():
+    """Load the built library (build it first with ``python -m paper_2509_10613_amd.build`` or
+    ``__graft_entry__.build()``); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise SigKernelError("%s not found: build the HIP library first (python paper_2509_10613_amd/build.py)"
+                             % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    i64, vp, ci = C.c_int64, C.c_void_p, C.c_int
+    lib.sigkernel_workspace_bytes.restype = C.c_size_t
+    lib.sigkernel_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, i64, ci, ci, ci, ci]
+    lib.sigkernel_fwd.restype = ci
+    lib.sigkernel_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t, vp]
+    lib.sigkernel_bwd.restype = ci
+    lib.sigkernel_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t, vp]
+    lib.sigkernel_gram.restype = ci
+    lib.sigkernel_gram.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t,
+                                   vp]
+    lib.sigkernel_last_error.restype = C.c_char_p
+    lib.sigkernel_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _dt(t):
+    if t.dtype == torch.float64:
+        return SK_F64
+    if t.dtype == torch.float32:
+        return SK_F32
+    raise TypeError("float32 or float64 tensors expected, got %s" % t.dtype)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _check(rc):
+    if rc != 0:
+        raise SigKernelError("sigkernel error %d: %s" % (rc, load().sigkernel_last_error().decode()))
+
+
+def _dev(t, name):
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    return t
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def sigkernel_workspace_bytes(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt):
+    return int(load().sigkernel_workspace_bytes(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt))
+
+
+_ws_cache = {}
+
+
+def workspace(nbytes, device):
+    """A cached, 256-byte aligned scratch tensor of at least nbytes on `device` (grown on demand)."""
+    key = str(device)
+    t = _ws_cache.get(key)
+    if t is None or t.numel() < nbytes:
+        t = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        _ws_cache[key] = t
+    return t
+
+
+def sigkernel_fwd(x, y, lam1=0, lam2=0, flags=0, k=None, ws=None):
+    """x[B,L1,d], y[B,L2,d] -> k[B] (device tensors)."""
+    _dev(x, "x"); _dev(y, "y")
+    B, L1, d = x.shape
+    L2 = y.shape[1]
+    assert y.shape[0] == B and y.shape[2] == d and y.dtype == x.dtype
+    dt = _dt(x)
+    if k is None:
+        k = torch.empty((B,), dtype=x.dtype, device=x.device)
+    need = sigkernel_workspace_bytes(SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags, dt)
+    if ws is None:
+        ws = workspace(need, x.device)
+    _check(load().sigkernel_fwd(_ptr(x), _ptr(y), _ptr(k), B, L1, L2, d, lam1, lam2, flags, dt, _ptr(ws),
+                                ws.numel(), _stream()))
+    return k
+
+
+def sigkernel_bwd(x, y, grad_k, lam1=0, lam2=0, flags=0, grad_x=None, grad_y=None, k_out=None, ws=None,
+                  want_x=True, want_y=True):
+    """Returns (k[B], grad_x[B,L1,d], grad_y[B,L2,d]) for upstream gradients grad_k[B]."""
+    _dev(x, "x"); _dev(y, "y"); _dev(grad_k, "grad_k")
+    B, L1, d = x.shape
+    L2 = y.shape[1]
+    assert y.shape[0] == B and y.shape[2] == d and y.dtype == x.dtype and grad_k.dtype == x.dtype
+    dt = _dt(x)
+    if grad_x is None and want_x:
+        grad_x = torch.empty_like(x)
+    if grad_y is None and want_y:
+        grad_y = torch.empty_like(y)
+    if k_out is None:
+        k_out = torch.empty((B,), dtype=x.dtype, device=x.device)
+    need = sigkernel_workspace_bytes(SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, dt)
+    if ws is None:
+        ws = workspace(need, x.device)
+    _check(load().sigkernel_bwd(_ptr(x), _ptr(y), _ptr(grad_k), _ptr(grad_x), _ptr(grad_y), _ptr(k_out), B, L1, L2,
+                                d, lam1, lam2, flags, dt, _ptr(ws), ws.numel(), _stream()))
+    return k_out, grad_x, grad_y
+
+
+def sigkernel_gram(X, Y, grad_K=None, lam1=0, lam2=0, flags=0, K=None, grad_X=None, grad_Y=None, ws=None):
+    """K[N,M] = k(X[n], Y[m]); with grad_K also (grad_X, grad_Y).  Passing the same tensor for X and Y
+    selects the symmetric case (grad_X is the total derivative, grad_Y is None)."""
+    _dev(X, "X"); _dev(Y, "Y")
+    N, L1, d = X.shape
+    M, L2, d2 = Y.shape
+    assert d2 == d and Y.dtype == X.dtype
+    sym = Y.data_ptr() == X.data_ptr()
+    dt = _dt(X)
+    if K is None:
+        K = torch.empty((N, M), dtype=X.dtype, device=X.device)
+    backward = grad_K is not None
+    if backward:
+        _dev(grad_K, "grad_K")
+        assert grad_K.shape == (N, M) and grad_K.dtype == X.dtype
+        if grad_X is None:
+            grad_X = torch.empty_like(X)
+        if grad_Y is None and not sym:
+            grad_Y = torch.empty_like(Y)
+    need = sigkernel_workspace_bytes(SK_OP_GRAM_BWD if backward else SK_OP_GRAM, N, M, L1, L2, d, lam1, lam2, flags,
+                                     dt)
+    if ws is None:
+        ws = workspace(need, X.device)
+    _check(load().sigkernel_gram(_ptr(X), _ptr(Y), _ptr(K), _ptr(grad_K), _ptr(grad_X), _ptr(grad_Y), N, M, L1, L2,
+                                 d, lam1, lam2, flags, dt, _ptr(ws), ws.numel(), _stream()))
+    if backward:
+        return K, grad_X, grad_Y
+    return K

@@ -1,0 +1,212 @@
+// C-ABI entry points (declared in include/sigkernel.h): argument validation, workspace carving and the
+// sequence of kernel launches for each operation.  Everything here is host code; the arithmetic of the
+// method lives in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "sigkernel.h"
+#include "sk_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
+{
+    if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
+    if (flags & ~SK_FLAG_TIME_AUG) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
+    if (lam1 < 0 || lam2 < 0 || lam1 > 20 || lam2 > 20)
+        return fail(SK_ERR_DYADIC, "dyadic orders (%d, %d) outside 0..20", lam1, lam2);
+    if (nx < 0 || ny < 0) return fail(SK_ERR_SHAPE, "negative batch size");
+    if (L1 < 1 || L2 < 1 || d < 1) return fail(SK_ERR_SHAPE, "need L1, L2, d >= 1 (got %lld, %lld, %lld)",
+                                               (long long)L1, (long long)L2, (long long)d);
+    const int64_t lim = (int64_t)1 << 29;
+    if (L1 > lim || L2 > lim || ((L1 - 1) << lam1) >= lim || ((L2 - 1) << lam2) >= lim)
+        return fail(SK_ERR_SHAPE, "refined grid side (L-1) << lambda must stay below 2^29");
+    if (d > 65536) return fail(SK_ERR_SHAPE, "d above 65536");
+    if (nx > ((int64_t)1 << 40) || ny > ((int64_t)1 << 40)) return fail(SK_ERR_SHAPE, "batch too large");
+    return SK_OK;
+}
+
+template <typename T>
+int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
+        void* grad_y, int lam1, int lam2, int flags, void* ws, hipStream_t st)
+{
+    using namespace sk;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    T* dxT = reinterpret_cast<T*>(base + p.off_dxT);
+    T* dyT = reinterpret_cast<T*>(base + p.off_dyT);
+    hipError_t e;
+#define SK_CHECK(call)                                                                         \
+    do {                                                                                       \
+        e = (call);                                                                            \
+        if (e != hipSuccess) return fail(SK_ERR_HIP, "%s: %s", #call, hipGetErrorString(e));   \
+    } while (0)
+
+    SK_CHECK(launch_increments<T>(static_cast<const T*>(x), dxT, p.nx, p.L1, p.d, p.DP, p.rpad, st));
+    if (!p.symmetric)
+        SK_CHECK(launch_increments<T>(static_cast<const T*>(y), dyT, p.ny, p.L2, p.d, p.DP, p.qpad, st));
+
+    SweepArgs<T> a;
+    std::memset(&a, 0, sizeof(a));
+    a.dxT = dxT; a.dyT = dyT;
+    a.xstride = p.xstride; a.ystride = p.ystride;
+    a.rpad = p.rpad; a.qpad = p.qpad; a.DP = p.DP;
+    a.k_out = static_cast<T*>(k);
+    a.grad_k = static_cast<const T*>(grad_k);
+    a.rows = reinterpret_cast<T*>(base + p.off_rows);
+    a.rows_slot = p.rows_slot;
+    a.rowlen = p.rowlen;
+    a.npairs = p.npairs;
+    a.gramM = p.gramM;
+    a.r = p.r; a.q = p.q; a.rs1 = p.rs1; a.rs2 = p.rs2; a.mb = p.mb; a.nb = p.nb; a.ns = p.ns;
+    a.S = p.S; a.nseg = p.nseg; a.d = p.d;
+    const double sc = 1.0 / (double)((int64_t)1 << (lam1 + lam2));
+    a.sc = (T)sc;
+    a.tc = (flags & SK_FLAG_TIME_AUG) ? (T)(sc * (1.0 / (double)(p.L1 - 1)) * (1.0 / (double)(p.L2 - 1))) : T(0);
+    a.y_lds = p.y_lds;
+    a.lds_wave = p.lds_wave;
+    a.ring_off = p.ring_off;
+    if (backward) {
+        a.gdxT = reinterpret_cast<T*>(base + p.off_gdxT);
+        a.gdyT = reinterpret_cast<T*>(base + p.off_gdyT);
+        a.want_gx = grad_x != nullptr || (p.symmetric && grad_x != nullptr);
+        a.want_gy = p.symmetric ? (grad_x != nullptr) : (grad_y != nullptr);
+        a.adj = reinterpret_cast<T*>(base + p.off_adj);
+        a.adj_slot = p.adj_slot;
+        a.ckpt = reinterpret_cast<T*>(base + p.off_ckpt);
+        a.ckpt_slot = p.ckpt_slot;
+        if (a.want_gx) SK_CHECK(launch_fill<T>(a.gdxT, p.nx * p.xstride, T(0), st));
+        if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<T>(a.gdyT, p.ny * p.ystride, T(0), st));
+    }
+    SK_CHECK(launch_sweep<T>(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    if (backward) {
+        if (grad_x)
+            SK_CHECK(launch_finalize<T>(a.gdxT, static_cast<T*>(grad_x), p.nx, p.L1, p.d, p.DP, p.rpad, st));
+        if (grad_y && !p.symmetric)
+            SK_CHECK(launch_finalize<T>(a.gdyT, static_cast<T*>(grad_y), p.ny, p.L2, p.d, p.DP, p.qpad, st));
+    }
+#undef SK_CHECK
+    return SK_OK;
+}
+
+// Degenerate shapes: no increments on one side -> k = 1 and zero gradients.
+template <typename T>
+int run_trivial(int64_t npairs, int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, void* k, void* grad_x,
+                void* grad_y, hipStream_t st)
+{
+    hipError_t e = hipSuccess;
+    if (k) e = sk::launch_fill<T>(static_cast<T*>(k), npairs, T(1), st);
+    if (e == hipSuccess && grad_x) e = sk::launch_fill<T>(static_cast<T*>(grad_x), nx * L1 * d, T(0), st);
+    if (e == hipSuccess && grad_y) e = sk::launch_fill<T>(static_cast<T*>(grad_y), ny * L2 * d, T(0), st);
+    if (e != hipSuccess) return fail(SK_ERR_HIP, "fill: %s", hipGetErrorString(e));
+    return SK_OK;
+}
+
+int check_device()
+{
+    static int state = 0;   // 0 unknown, 1 ok, -1 bad
+    if (state == 1) return SK_OK;
+    int dev = 0, lds = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SK_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (e != hipSuccess) return fail(SK_ERR_HIP, "hipDeviceGetAttribute: %s", hipGetErrorString(e));
+    if ((size_t)lds < sk::kLdsPerCU)
+        return fail(SK_ERR_HIP, "device offers %d bytes of LDS per workgroup, this library is built for %zu (gfx950)",
+                    lds, sk::kLdsPerCU);
+    state = 1;
+    return SK_OK;
+}
+
+int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
+             void* grad_y, int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags,
+             sk_dtype dt, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = validate(nx, ny, L1, L2, d, lam1, lam2, flags, (int)dt);
+    if (rc != SK_OK) return rc;
+    const int64_t npairs = gram ? nx * ny : nx;
+    if (npairs == 0 && !(gram && backward)) return SK_OK;
+    if (!x || !y) return fail(SK_ERR_NULL, "x / y is NULL");
+    if (!backward && !k) return fail(SK_ERR_NULL, "output k is NULL");
+    if (backward && !grad_k) return fail(SK_ERR_NULL, "grad_k is NULL");
+    const bool symmetric = gram && x == y;
+    if (symmetric && (nx != ny || L1 != L2)) return fail(SK_ERR_SHAPE, "Y == X needs N == M and L1 == L2");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int elem = dt == SK_F64 ? 8 : 4;
+    if (symmetric) grad_y = nullptr;
+
+    if (L1 == 1 || L2 == 1 || npairs == 0) {
+        if (dt == SK_F64) return run_trivial<double>(npairs, nx, ny, L1, L2, d, k, grad_x, grad_y, st);
+        return run_trivial<float>(npairs, nx, ny, L1, L2, d, k, grad_x, grad_y, st);
+    }
+    rc = check_device();
+    if (rc != SK_OK) return rc;
+    sk::Plan p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem);
+    if (!p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0)
+        return fail(SK_ERR_WORKSPACE, "workspace pointer is NULL or not 256-byte aligned");
+    if (ws_bytes < p.total)
+        return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, p.total);
+    if (dt == SK_F64)
+        return run<double>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
+    return run<float>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1,
+                                 int lam2, int flags, sk_dtype dt)
+{
+    const bool gram = op == SK_OP_GRAM || op == SK_OP_GRAM_BWD;
+    const bool backward = op == SK_OP_BWD || op == SK_OP_GRAM_BWD;
+    if (op < SK_OP_FWD || op > SK_OP_GRAM_BWD) return 0;
+    const int64_t ny = gram ? M : B_or_N;
+    if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
+    // The symmetric Gram case needs no more than the general one, so the query does not distinguish them.
+    sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4);
+    return p.valid ? p.total : 0;
+}
+
+int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1,
+                  int lam2, int flags, sk_dtype dt, void* ws, size_t ws_bytes, void* stream)
+{
+    return dispatch(false, false, x, y, k, nullptr, nullptr, nullptr, B, B, L1, L2, d, lam1, lam2, flags, dt, ws,
+                    ws_bytes, stream);
+}
+
+int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
+                  int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt, void* ws,
+                  size_t ws_bytes, void* stream)
+{
+    return dispatch(true, false, x, y, k_out, grad_k, grad_x, grad_y, B, B, L1, L2, d, lam1, lam2, flags, dt, ws,
+                    ws_bytes, stream);
+}
+
+int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, void* grad_X, void* grad_Y, int64_t N,
+                   int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,
+                   void* ws, size_t ws_bytes, void* stream)
+{
+    return dispatch(grad_K != nullptr, true, X, Y, K, grad_K, grad_X, grad_Y, N, M, L1, L2, d, lam1, lam2, flags,
+                    dt, ws, ws_bytes, stream);
+}
+
+const char* sigkernel_last_error(void) { return g_err; }
+
+const char* sigkernel_version(void) { return "sigkernel-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

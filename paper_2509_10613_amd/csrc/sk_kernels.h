@@ -1,0 +1,50 @@
+// Kernel argument block and launcher declarations shared by the HIP kernels and the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "sk_plan.h"
+
+namespace sk {
+
+template <typename T>
+struct SweepArgs {
+    const T* dxT;        // [nx][DP][rpad] transposed, zero-padded x increments
+    const T* dyT;        // [ny][DP][qpad]
+    long xstride, ystride;
+    int rpad, qpad, DP;
+    T* k_out;            // [npairs] (may be null in the backward kernel)
+    const T* grad_k;     // [npairs] upstream gradients (backward)
+    T* gdxT;             // gradient accumulators in the layout of dxT / dyT (backward)
+    T* gdyT;
+    int want_gx, want_gy;
+    T* rows;             // per wave slot: ns boundary rows of rowlen elements
+    long rows_slot;
+    int rowlen;
+    T* adj;              // per wave slot: two adjoint boundary rows
+    long adj_slot;
+    T* ckpt;             // per wave slot: ns * nseg checkpoints of the lane state
+    long ckpt_slot;
+    long npairs;
+    long gramM;          // > 0: pair id -> (id / gramM, id % gramM)
+    int r, q;            // coarse cells per side
+    int rs1, rs2;        // residual refinement shifts of block row / column to coarse index
+    int mb, nb;          // block rows / columns
+    int ns;              // strips
+    int S, nseg;         // replay segment length, segments per strip
+    int d;               // channels (runtime loop when the kernel has no compile-time count)
+    T tc;                // scaled product of the two time-channel increments (0 without time augmentation)
+    T sc;                // 2^-(lam1+lam2)
+    int y_lds;
+    size_t lds_wave;     // LDS bytes per wave
+    size_t ring_off;     // byte offset of the replay ring inside a wave's LDS
+};
+
+template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
+template <typename T>
+hipError_t launch_increments(const T* x, T* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
+template <typename T>
+hipError_t launch_finalize(const T* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
+template <typename T>
+hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs<T>& a, int grid, size_t lds, hipStream_t st);
+
+}  // namespace sk

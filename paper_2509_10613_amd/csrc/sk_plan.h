@@ -1,0 +1,127 @@
+// Host-side launch plan for the signature-kernel sweeps: pure arithmetic, no HIP calls, so that the
+// workspace query and the launches agree by construction.
+//
+// Geometry (paper Section 3.1/3.2): the refined grid has m = (L1-1) << lam1 by n = (L2-1) << lam2 cells.
+// The sweep works on square blocks of 2^BL x 2^BL refined cells that share one entry of the increment
+// Gram matrix (BL = min(lam1, lam2, 2)); the block grid has mb = (L1-1) << rs1 rows and
+// nb = (L2-1) << rs2 columns, rs = lam - BL.  A strip is 64 consecutive block rows, one per lane.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+namespace sk {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerWG = 4;            // waves (independent pairs) per workgroup
+constexpr size_t kLdsPerCU = 160 * 1024;  // gfx950: 160 KB of LDS per compute unit / workgroup
+constexpr size_t kLdsPerWave = kLdsPerCU / kWavesPerWG - 1024;
+constexpr int kNumCU = 256;
+constexpr int kMaxBL = 2;
+
+// Channel counts with a dedicated kernel instantiation (increments kept in registers).
+constexpr int kTemplD[] = {2, 3, 4, 5, 6, 8, 16};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+    bool valid = false;
+    bool backward = false;
+    bool symmetric = false;     // Gram with Y == X: one increment buffer, one gradient accumulator
+    int elem = 8;               // sizeof(T)
+    int64_t nx = 0, ny = 0;     // number of x paths and y paths
+    int64_t npairs = 0;
+    int64_t gramM = 0;          // > 0: pair id -> (id / gramM, id % gramM); 0: pair id -> (id, id)
+    int L1 = 0, L2 = 0, d = 0;
+    int BL = 0, rs1 = 0, rs2 = 0;
+    int r = 0, q = 0;           // coarse cells per side
+    int rpad = 0, qpad = 0;
+    int mb = 0, nb = 0;         // block rows / columns
+    int ns = 0;                 // strips per pair
+    int rowlen = 0;             // elements of one boundary row (node columns, padded)
+    int DT = 0;                 // kernel template channel count (0 = runtime loop over d)
+    int DP = 0;                 // channels stored per path in the transposed increment buffers
+    int S = 0, nseg = 0;        // backward: macro-steps per replay segment, segments per strip
+    int y_lds = 0;              // y increments (and their gradient accumulators) staged in LDS
+    size_t lds_wave = 0, lds_bytes = 0, ring_off = 0;
+    int grid = 0;
+    int64_t nslots = 0;
+    int64_t xstride = 0, ystride = 0, rows_slot = 0, ckpt_slot = 0, adj_slot = 0;
+    size_t off_dxT = 0, off_dyT = 0, off_gdxT = 0, off_gdyT = 0, off_rows = 0, off_adj = 0, off_ckpt = 0;
+    size_t total = 0;
+};
+
+inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
+                      int64_t d, int lam1, int lam2, int elem)
+{
+    Plan p;
+    p.backward = backward;
+    p.symmetric = symmetric;
+    p.elem = elem;
+    p.nx = nx;
+    p.ny = ny;
+    p.npairs = gram ? nx * ny : nx;
+    p.gramM = gram ? ny : 0;
+    p.L1 = (int)L1; p.L2 = (int)L2; p.d = (int)d;
+    p.r = (int)L1 - 1; p.q = (int)L2 - 1;
+    if (p.npairs <= 0 || p.r <= 0 || p.q <= 0) return p;   // nothing to sweep
+    int mn = lam1 < lam2 ? lam1 : lam2;
+    p.BL = mn < kMaxBL ? mn : kMaxBL;
+    p.rs1 = lam1 - p.BL; p.rs2 = lam2 - p.BL;
+    p.mb = p.r << p.rs1; p.nb = p.q << p.rs2;
+    p.ns = (p.mb + kWave - 1) / kWave;
+    const int C = 1 << p.BL, R = C;
+    p.rowlen = (int)align_up((size_t)p.nb * C + 1, 64);
+    p.rpad = (int)align_up((size_t)p.r, 64);
+    p.qpad = (int)align_up((size_t)p.q, 64);
+    p.DT = 0;
+    for (int t : kTemplD) if (d <= t) { p.DT = t; break; }
+    p.DP = p.DT ? p.DT : (int)d;
+    p.xstride = (int64_t)p.DP * p.rpad;
+    p.ystride = (int64_t)p.DP * p.qpad;
+
+    // LDS per wave: y increments (+ their gradient accumulators when going backward) and the replay ring.
+    const int NVR = R + C + 1;   // block input edges kept per macro-step in the ring
+    size_t ybytes = (size_t)p.DP * p.qpad * elem * (backward ? 2 : 1);
+    p.y_lds = ybytes <= 20 * 1024 ? 1 : 0;
+    size_t used = p.y_lds ? ybytes : 0;
+    p.ring_off = used;
+    if (backward) {
+        int S = 64;
+        while (S > 4 && used + (size_t)S * kWave * NVR * elem > kLdsPerWave) S >>= 1;
+        p.S = S;
+        p.nseg = (p.nb + kWave - 1 + S - 1) / S;   // strips run nb + (lanes-1) macro-steps at most
+        used += (size_t)S * kWave * NVR * elem;
+    }
+    p.lds_wave = align_up(used, 256);
+    p.lds_bytes = p.lds_wave * kWavesPerWG;
+
+    int wg_per_cu = (int)(kLdsPerCU / (p.lds_bytes ? p.lds_bytes : 1));
+    if (wg_per_cu < 1) wg_per_cu = 1;
+    if (wg_per_cu > 2) wg_per_cu = 2;
+    int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
+    int64_t cap = (int64_t)kNumCU * wg_per_cu;
+    p.grid = (int)(want < cap ? want : cap);
+    p.nslots = (int64_t)p.grid * kWavesPerWG;
+
+    // Workspace layout (all offsets 256-byte aligned).
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    p.off_dxT = take((size_t)nx * p.xstride * elem);
+    p.off_dyT = symmetric ? p.off_dxT : take((size_t)ny * p.ystride * elem);
+    p.rows_slot = (int64_t)p.ns * p.rowlen;
+    p.off_rows = take((size_t)p.nslots * p.rows_slot * elem);
+    if (backward) {
+        p.off_gdxT = take((size_t)nx * p.xstride * elem);
+        p.off_gdyT = symmetric ? p.off_gdxT : take((size_t)ny * p.ystride * elem);
+        p.adj_slot = 2 * (int64_t)p.rowlen;
+        p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
+        const int NVC = R + 1 + C;   // lane state kept per checkpoint
+        p.ckpt_slot = (int64_t)p.ns * p.nseg * NVC * kWave;
+        p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
+    }
+    p.total = off;
+    p.valid = true;
+    return p;
+}
+
+}  // namespace sk

@@ -1,0 +1,235 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the same
+seeded inputs.  Tolerances (written here, used everywhere below):
+
+  fp64: 1e-10, fp32: 1e-4, relative in the sense
+    values    |gpu - ref| <= tol * max(1, |ref|)            per element
+    gradients max|gpu - ref| <= tol * max(1, max|ref|)       per output tensor
+  (gradient entries cross zero, so they are compared against the tensor's scale).
+  fp32 runs are compared with the fp64 oracle evaluated on the fp32-rounded inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_10613_amd import binding as sk
+from paper_2509_10613_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float64: 1e-10, torch.float32: 1e-4}
+
+
+def dev(a, dtype=torch.float64):
+    return torch.tensor(np.asarray(a), dtype=dtype, device="cuda")
+
+
+def host(t):
+    return t.detach().cpu().numpy().astype(np.float64)
+
+
+def rounded(a, dtype):
+    """The inputs as the GPU sees them (fp32 rounding applied), back in float64 for the oracle."""
+    return host(dev(a, dtype))
+
+
+def check_values(got, ref, dtype, what):
+    tol = TOL[dtype]
+    err = np.abs(got - ref) / np.maximum(1.0, np.abs(ref))
+    print("%s: max scaled err %.3e (tol %.0e)" % (what, err.max() if err.size else 0.0, tol), flush=True)
+    assert got.shape == ref.shape
+    assert np.all(np.isfinite(got))
+    assert (err.max() if err.size else 0.0) <= tol, what
+
+
+def check_grads(got, ref, dtype, what):
+    tol = TOL[dtype]
+    scale = max(1.0, np.max(np.abs(ref))) if ref.size else 1.0
+    err = (np.max(np.abs(got - ref)) if ref.size else 0.0) / scale
+    print("%s: max err / scale %.3e (tol %.0e)" % (what, err, tol), flush=True)
+    assert got.shape == ref.shape
+    assert np.all(np.isfinite(got))
+    assert err <= tol, what
+
+
+def run_pairs(X, Y, lam1, lam2, flags, dtype, backward, seed=5):
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    x, y = dev(X, dtype), dev(Y, dtype)
+    k = sk.sigkernel_fwd(x, y, lam1, lam2, flags)
+    torch.cuda.synchronize()
+    kref = oracle.fwd(Xr, Yr, lam1, lam2, flags)
+    check_values(host(k), kref, dtype, "k")
+    if backward:
+        gk = workloads.upstream_weights(seed, (X.shape[0],))
+        gkr = rounded(gk, dtype)
+        k2, gx, gy = sk.sigkernel_bwd(x, y, dev(gk, dtype), lam1, lam2, flags)
+        torch.cuda.synchronize()
+        kr, gxr, gyr = oracle.bwd(Xr, Yr, gkr, lam1, lam2, flags)
+        check_values(host(k2), kr, dtype, "k (from bwd)")
+        check_grads(host(gx), gxr, dtype, "grad_x")
+        check_grads(host(gy), gyr, dtype, "grad_y")
+
+
+def rand_paths(seed, B, L, d, scale=0.3):
+    rng = np.random.default_rng(seed)
+    return np.cumsum(rng.normal(0, scale, size=(B, L, d)), axis=1)
+
+
+# ------------------------------------------------------------------ the five configurations
+def test_c1_forward_fp64():
+    w, X, Y = workloads.make("c1")
+    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=False)
+
+
+def test_c2_forward_backward_fp64_full_size():
+    w, X, Y = workloads.make("c2")
+    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=True)
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_c3_gram_reduced(dtype):
+    w, X, Y = workloads.make("c3", n_x=20, n_y=12)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    W = workloads.upstream_weights(33, (20, 12))
+    Wr = rounded(W, dtype)
+    K = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), None, w.lam, w.lam, w.flags)
+    Kref, gXr, gYr = oracle.gram(Xr, Yr, Wr, w.lam, w.lam, w.flags)
+    check_values(host(K), Kref, dtype, "K")
+    K2, gX, gY = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), dev(W, dtype), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    check_values(host(K2), Kref, dtype, "K (from bwd)")
+    check_grads(host(gX), gXr, dtype, "grad_X")
+    check_grads(host(gY), gYr, dtype, "grad_Y")
+
+
+def test_c4_long_sequences_two_pairs_full_length():
+    w, X, Y = workloads.make("c4", n_x=2, n_y=2)
+    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=True)
+
+
+def test_c5_gram_reduced_and_symmetric():
+    w, X, Y = workloads.make("c5", n_x=40, n_y=24)
+    W = workloads.upstream_weights(55, (40, 24))
+    x, y = dev(X), dev(Y)
+    K, gX, gY = sk.sigkernel_gram(x, y, dev(W), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    Kref, gXr, gYr = oracle.gram(X, Y, W, w.lam, w.lam, w.flags)
+    check_values(host(K), Kref, torch.float64, "K")
+    check_grads(host(gX), gXr, torch.float64, "grad_X")
+    check_grads(host(gY), gYr, torch.float64, "grad_Y")
+    # symmetric case K(X,X): same pointer for both arguments
+    Ws = workloads.upstream_weights(56, (40, 40))
+    Kxx, gXX, none = sk.sigkernel_gram(x, x, dev(Ws), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    Kxr, gXXr, _ = oracle.gram(X, X, Ws, w.lam, w.lam, w.flags)
+    assert none is None
+    check_values(host(Kxx), Kxr, torch.float64, "K(X,X)")
+    check_grads(host(gXX), gXXr, torch.float64, "grad_X total")
+    assert torch.equal(Kxx, Kxx.T)      # k(x,y) = k(y,x) bit for bit
+
+
+# ------------------------------------------------------------------ full-size runs on sampled outputs
+def test_c3_full_size_sampled_entries():
+    w, X, Y = workloads.make("c3")
+    K = host(sk.sigkernel_gram(dev(X), dev(Y), None, w.lam, w.lam, w.flags))
+    rng = np.random.default_rng(9)
+    ns = rng.integers(0, w.n_x, 24)
+    ms = rng.integers(0, w.n_y, 24)
+    ref = oracle.fwd(X[ns], Y[ms], w.lam, w.lam, w.flags)
+    check_values(K[ns, ms], ref, torch.float64, "K sampled")
+    assert np.all(np.isfinite(K))
+
+
+def test_c5_full_size_sampled_entries():
+    w, X, Y = workloads.make("c5")
+    K = host(sk.sigkernel_gram(dev(X), dev(Y), None, w.lam, w.lam, w.flags))
+    rng = np.random.default_rng(10)
+    ns = rng.integers(0, w.n_x, 64)
+    ms = rng.integers(0, w.n_y, 64)
+    ref = oracle.fwd(X[ns], Y[ms], w.lam, w.lam, w.flags)
+    check_values(K[ns, ms], ref, torch.float64, "K sampled")
+    assert np.all(np.isfinite(K))
+
+
+# ------------------------------------------------------------------ shapes, orders, channels, edges
+@pytest.mark.parametrize("L1,L2,d,lam1,lam2,flags", [
+    (2, 2, 1, 0, 0, 0),        # a single cell
+    (2, 9, 3, 0, 0, 1),
+    (33, 17, 2, 0, 0, 0),
+    (66, 70, 4, 0, 0, 1),      # two strips, ragged second strip
+    (130, 40, 3, 0, 0, 0),     # three strips
+    (20, 35, 5, 1, 1, 0),
+    (70, 30, 6, 1, 1, 1),      # 69 coarse rows at block order 1: ragged
+    (12, 50, 8, 2, 2, 0),
+    (40, 9, 7, 2, 2, 1),       # d = 7 runs in the 8-channel kernel
+    (9, 11, 2, 3, 3, 0),       # order above the block order: residual shift on both sides
+    (10, 21, 3, 2, 0, 0),      # unequal orders
+    (21, 10, 3, 0, 3, 1),
+    (15, 14, 16, 1, 2, 0),
+    (11, 13, 11, 0, 0, 0),     # d = 11 runs in the 16-channel kernel
+    (9, 12, 20, 1, 1, 1),      # d = 20: runtime channel loop
+    (14, 7, 37, 0, 1, 0),
+])
+def test_shapes_orders_channels_fp64(L1, L2, d, lam1, lam2, flags):
+    B = 5
+    X = rand_paths(1000 + L1 * 31 + d, B, L1, d, 0.25)
+    Y = rand_paths(2000 + L2 * 17 + d, B, L2, d, 0.25)
+    run_pairs(X, Y, lam1, lam2, flags, torch.float64, backward=True)
+
+
+@pytest.mark.parametrize("L1,L2,d,lam", [(40, 33, 3, 0), (70, 66, 5, 1), (30, 20, 2, 2), (20, 12, 24, 1)])
+def test_shapes_fp32(L1, L2, d, lam):
+    B = 6
+    X = rand_paths(3000 + L1, B, L1, d, 0.2)
+    Y = rand_paths(4000 + L2, B, L2, d, 0.2)
+    run_pairs(X, Y, lam, lam, 0, torch.float32, backward=True)
+
+
+def test_more_pairs_than_wave_slots():
+    # every wave slot handles several pairs in turn, so its scratch rows and checkpoints are reused
+    X = rand_paths(71, 5000, 6, 2, 0.3)
+    Y = rand_paths(72, 5000, 5, 2, 0.3)
+    run_pairs(X, Y, 1, 1, 0, torch.float64, backward=True)
+
+
+def test_degenerate_inputs():
+    x = dev(rand_paths(1, 3, 1, 2))
+    y = dev(rand_paths(2, 3, 6, 2))
+    assert torch.all(sk.sigkernel_fwd(x, y) == 1.0)                       # L1 = 1: no increments
+    k, gx, gy = sk.sigkernel_bwd(x, y, torch.ones(3, dtype=torch.float64, device="cuda"))
+    assert torch.all(k == 1.0) and torch.all(gx == 0.0) and torch.all(gy == 0.0)
+    e = torch.empty((0, 4, 2), dtype=torch.float64, device="cuda")
+    assert sk.sigkernel_fwd(e, e).shape == (0,)                            # empty batch
+    z = torch.zeros((4, 9, 3), dtype=torch.float64, device="cuda")
+    assert torch.all(sk.sigkernel_fwd(z, dev(rand_paths(3, 4, 7, 3)), 1, 1) == 1.0)   # zero path: k = 1 exactly
+    with pytest.raises(sk.SigKernelError):
+        small = torch.empty(256, dtype=torch.uint8, device="cuda")
+        sk.sigkernel_fwd(dev(rand_paths(4, 2, 5, 2)), dev(rand_paths(5, 2, 5, 2)), ws=small)
+
+
+def test_symmetry_and_batch_independence():
+    X = rand_paths(81, 7, 45, 3, 0.3)
+    Y = rand_paths(82, 7, 45, 3, 0.3)
+    x, y = dev(X), dev(Y)
+    kxy = sk.sigkernel_fwd(x, y, 1, 1)
+    kyx = sk.sigkernel_fwd(y, x, 1, 1)
+    assert torch.equal(kxy, kyx)
+    assert torch.equal(sk.sigkernel_fwd(x, y, 2, 1), sk.sigkernel_fwd(y, x, 1, 2))
+    one = sk.sigkernel_fwd(x[3:4].contiguous(), y[3:4].contiguous(), 1, 1)
+    assert one[0] == kxy[3]
+    K = sk.sigkernel_gram(x, y, None, 1, 1)
+    for n, m in [(0, 0), (2, 5), (6, 1)]:
+        assert K[n, m] == sk.sigkernel_fwd(x[n:n + 1].contiguous(), y[m:m + 1].contiguous(), 1, 1)[0]
+
+
+def test_only_one_gradient_requested():
+    X = rand_paths(91, 4, 20, 3)
+    Y = rand_paths(92, 4, 25, 3)
+    gk = np.ones(4)
+    _, gxr, gyr = oracle.bwd(X, Y, gk, 1, 1, 0)
+    _, gx, none = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0, want_y=False)
+    assert none is None
+    check_grads(host(gx), gxr, torch.float64, "grad_x only")
+    _, none, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0, want_x=False)
+    assert none is None
+    check_grads(host(gy), gyr, torch.float64, "grad_y only")
