@@ -40,14 +40,19 @@ int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1
     return SK_OK;
 }
 
+// T is the element type of the caller's arrays.  The sweeps run in double whatever T is: non-packed
+// single-precision vector instructions issue at the same rate as double ones on this chip, and the
+// recurrence of Eq. (1) in single precision loses the low bits of p when forming 1 + p/2 + ..., an error
+// that grows linearly with the number of cells.  Float callers get float storage at the edges only.
 template <typename T>
 int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
         void* grad_y, int lam1, int lam2, int flags, void* ws, hipStream_t st)
 {
     using namespace sk;
+    constexpr bool kIsDouble = sizeof(T) == 8;
     unsigned char* base = static_cast<unsigned char*>(ws);
-    T* dxT = reinterpret_cast<T*>(base + p.off_dxT);
-    T* dyT = reinterpret_cast<T*>(base + p.off_dyT);
+    double* dxT = reinterpret_cast<double*>(base + p.off_dxT);
+    double* dyT = reinterpret_cast<double*>(base + p.off_dyT);
     hipError_t e;
 #define SK_CHECK(call)                                                                         \
     do {                                                                                       \
@@ -59,14 +64,23 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     if (!p.symmetric)
         SK_CHECK(launch_increments<T>(static_cast<const T*>(y), dyT, p.ny, p.L2, p.d, p.DP, p.qpad, st));
 
-    SweepArgs<T> a;
+    SweepArgs<double> a;
     std::memset(&a, 0, sizeof(a));
     a.dxT = dxT; a.dyT = dyT;
     a.xstride = p.xstride; a.ystride = p.ystride;
     a.rpad = p.rpad; a.qpad = p.qpad; a.DP = p.DP;
-    a.k_out = static_cast<T*>(k);
-    a.grad_k = static_cast<const T*>(grad_k);
-    a.rows = reinterpret_cast<T*>(base + p.off_rows);
+    if (kIsDouble) {
+        a.k_out = static_cast<double*>(k);
+        a.grad_k = static_cast<const double*>(grad_k);
+    } else {
+        a.k_out = k ? reinterpret_cast<double*>(base + p.off_kio) : nullptr;
+        if (backward) {
+            double* gk64 = reinterpret_cast<double*>(base + p.off_gkio);
+            SK_CHECK((launch_convert<T, double>(static_cast<const T*>(grad_k), gk64, p.npairs, st)));
+            a.grad_k = gk64;
+        }
+    }
+    a.rows = reinterpret_cast<double*>(base + p.off_rows);
     a.rows_slot = p.rows_slot;
     a.rowlen = p.rowlen;
     a.npairs = p.npairs;
@@ -74,24 +88,25 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.r = p.r; a.q = p.q; a.rs1 = p.rs1; a.rs2 = p.rs2; a.mb = p.mb; a.nb = p.nb; a.ns = p.ns;
     a.S = p.S; a.nseg = p.nseg; a.d = p.d;
     const double sc = 1.0 / (double)((int64_t)1 << (lam1 + lam2));
-    a.sc = (T)sc;
-    a.tc = (flags & SK_FLAG_TIME_AUG) ? (T)(sc * (1.0 / (double)(p.L1 - 1)) * (1.0 / (double)(p.L2 - 1))) : T(0);
+    a.sc = sc;
+    a.tc = (flags & SK_FLAG_TIME_AUG) ? sc * (1.0 / (double)(p.L1 - 1)) * (1.0 / (double)(p.L2 - 1)) : 0.0;
     a.y_lds = p.y_lds;
     a.lds_wave = p.lds_wave;
     a.ring_off = p.ring_off;
     if (backward) {
-        a.gdxT = reinterpret_cast<T*>(base + p.off_gdxT);
-        a.gdyT = reinterpret_cast<T*>(base + p.off_gdyT);
-        a.want_gx = grad_x != nullptr || (p.symmetric && grad_x != nullptr);
+        a.gdxT = reinterpret_cast<double*>(base + p.off_gdxT);
+        a.gdyT = reinterpret_cast<double*>(base + p.off_gdyT);
+        a.want_gx = grad_x != nullptr;
         a.want_gy = p.symmetric ? (grad_x != nullptr) : (grad_y != nullptr);
-        a.adj = reinterpret_cast<T*>(base + p.off_adj);
+        a.adj = reinterpret_cast<double*>(base + p.off_adj);
         a.adj_slot = p.adj_slot;
-        a.ckpt = reinterpret_cast<T*>(base + p.off_ckpt);
+        a.ckpt = reinterpret_cast<double*>(base + p.off_ckpt);
         a.ckpt_slot = p.ckpt_slot;
-        if (a.want_gx) SK_CHECK(launch_fill<T>(a.gdxT, p.nx * p.xstride, T(0), st));
-        if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<T>(a.gdyT, p.ny * p.ystride, T(0), st));
+        if (a.want_gx) SK_CHECK(launch_fill<double>(a.gdxT, p.nx * p.xstride, 0.0, st));
+        if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<double>(a.gdyT, p.ny * p.ystride, 0.0, st));
     }
-    SK_CHECK(launch_sweep<T>(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    SK_CHECK(launch_sweep<double>(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
     if (backward) {
         if (grad_x)
             SK_CHECK(launch_finalize<T>(a.gdxT, static_cast<T*>(grad_x), p.nx, p.L1, p.d, p.DP, p.rpad, st));

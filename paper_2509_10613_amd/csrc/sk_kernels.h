@@ -40,10 +40,11 @@ struct SweepArgs {
 };
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
+template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st);
 template <typename T>
-hipError_t launch_increments(const T* x, T* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
+hipError_t launch_increments(const T* x, double* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
 template <typename T>
-hipError_t launch_finalize(const T* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
+hipError_t launch_finalize(const double* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
 template <typename T>
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs<T>& a, int grid, size_t lds, hipStream_t st);
 

@@ -89,6 +89,14 @@ template <> __device__ __forceinline__ float fmaT<float>(float a, float b, float
 // ------------------------------------------------------------------------------------------------
 // small kernels
 // ------------------------------------------------------------------------------------------------
+template <typename TA, typename TB>
+__global__ void convert_kernel(const TA* __restrict__ in, TB* __restrict__ out, long n)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long st = (long)gridDim.x * blockDim.x;
+    for (; i < n; i += st) out[i] = (TB)in[i];
+}
+
 template <typename T>
 __global__ void fill_kernel(T* p, long n, T v)
 {
@@ -99,9 +107,9 @@ __global__ void fill_kernel(T* p, long n, T v)
 
 // Increments, transposed and padded: out[path][c][a] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d;
 // zero elsewhere (first line of the paper's forward listing).  The difference is taken in double.
-template <typename T>
-__global__ void increments_kernel(const T* __restrict__ x, T* __restrict__ out, long npaths, int L, int d, int DP,
-                                  int rpad)
+template <typename TI>
+__global__ void increments_kernel(const TI* __restrict__ x, double* __restrict__ out, long npaths, int L, int d,
+                                  int DP, int rpad)
 {
     long total = npaths * (long)DP * rpad;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -111,10 +119,10 @@ __global__ void increments_kernel(const T* __restrict__ x, T* __restrict__ out, 
         long t = i / rpad;
         int c = (int)(t % DP);
         long pth = t / DP;
-        T v = T(0);
+        double v = 0.0;
         if (a < L - 1 && c < d) {
-            const T* xp = x + (pth * L + a) * (long)d + c;
-            v = (T)((double)xp[d] - (double)xp[0]);
+            const TI* xp = x + (pth * L + a) * (long)d + c;
+            v = (double)xp[d] - (double)xp[0];
         }
         out[i] = v;
     }
@@ -122,9 +130,9 @@ __global__ void increments_kernel(const T* __restrict__ x, T* __restrict__ out, 
 
 // grad[path][i][c] = g[path][c][i-1] - g[path][c][i] (out-of-range terms zero): the increments are
 // differences of consecutive points, so the gradient of a point collects the two increments it touches.
-template <typename T>
-__global__ void finalize_grad_kernel(const T* __restrict__ g, T* __restrict__ grad, long npaths, int L, int d, int DP,
-                                     int rpad)
+template <typename TO>
+__global__ void finalize_grad_kernel(const double* __restrict__ g, TO* __restrict__ grad, long npaths, int L, int d,
+                                     int DP, int rpad)
 {
     long total = npaths * (long)L * d;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -134,10 +142,10 @@ __global__ void finalize_grad_kernel(const T* __restrict__ g, T* __restrict__ gr
         long t = i / d;
         int pt = (int)(t % L);
         long pth = t / L;
-        const T* gp = g + (pth * DP + c) * (long)rpad;
-        T hi = pt >= 1 ? gp[pt - 1] : T(0);
-        T lo = pt < L - 1 ? gp[pt] : T(0);
-        grad[i] = hi - lo;
+        const double* gp = g + (pth * DP + c) * (long)rpad;
+        double hi = pt >= 1 ? gp[pt - 1] : 0.0;
+        double lo = pt < L - 1 ? gp[pt] : 0.0;
+        grad[i] = (TO)(hi - lo);
     }
 }
 
@@ -560,8 +568,18 @@ hipError_t launch_fill(T* p, long n, T v, hipStream_t st)
     return hipGetLastError();
 }
 
+template <typename TA, typename TB>
+hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    long blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL((convert_kernel<TA, TB>), dim3((unsigned)blocks), dim3(256), 0, st, in, out, n);
+    return hipGetLastError();
+}
+
 template <typename T>
-hipError_t launch_increments(const T* x, T* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st)
+hipError_t launch_increments(const T* x, double* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st)
 {
     long total = npaths * (long)DP * rpad;
     if (total <= 0) return hipSuccess;
@@ -573,7 +591,7 @@ hipError_t launch_increments(const T* x, T* out, long npaths, int L, int d, int 
 }
 
 template <typename T>
-hipError_t launch_finalize(const T* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st)
+hipError_t launch_finalize(const double* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st)
 {
     long total = npaths * (long)L * d;
     if (total <= 0) return hipSuccess;
@@ -639,11 +657,12 @@ hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs<T>& a, in
 
 template hipError_t launch_fill<float>(float*, long, float, hipStream_t);
 template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
-template hipError_t launch_increments<float>(const float*, float*, long, int, int, int, int, hipStream_t);
+template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);
+template hipError_t launch_convert<double, float>(const double*, float*, long, hipStream_t);
+template hipError_t launch_increments<float>(const float*, double*, long, int, int, int, int, hipStream_t);
 template hipError_t launch_increments<double>(const double*, double*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_finalize<float>(const float*, float*, long, int, int, int, int, hipStream_t);
+template hipError_t launch_finalize<float>(const double*, float*, long, int, int, int, int, hipStream_t);
 template hipError_t launch_finalize<double>(const double*, double*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_sweep<float>(bool, int, int, const SweepArgs<float>&, int, size_t, hipStream_t);
 template hipError_t launch_sweep<double>(bool, int, int, const SweepArgs<double>&, int, size_t, hipStream_t);
 
 }  // namespace sk

@@ -27,7 +27,8 @@ struct Plan {
     bool valid = false;
     bool backward = false;
     bool symmetric = false;     // Gram with Y == X: one increment buffer, one gradient accumulator
-    int elem = 8;               // sizeof(T)
+    int elem = 8;               // bytes per element of every internal buffer (sweeps run in double)
+    int io_elem = 8;            // bytes per element of the caller's arrays
     int64_t nx = 0, ny = 0;     // number of x paths and y paths
     int64_t npairs = 0;
     int64_t gramM = 0;          // > 0: pair id -> (id / gramM, id % gramM); 0: pair id -> (id, id)
@@ -47,13 +48,16 @@ struct Plan {
     int64_t nslots = 0;
     int64_t xstride = 0, ystride = 0, rows_slot = 0, ckpt_slot = 0, adj_slot = 0;
     size_t off_dxT = 0, off_dyT = 0, off_gdxT = 0, off_gdyT = 0, off_rows = 0, off_adj = 0, off_ckpt = 0;
+    size_t off_kio = 0, off_gkio = 0;   // float callers: double staging of k and grad_k
     size_t total = 0;
 };
 
 inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
-                      int64_t d, int lam1, int lam2, int elem)
+                      int64_t d, int lam1, int lam2, int io_elem)
 {
     Plan p;
+    const int elem = 8;
+    p.io_elem = io_elem;
     p.backward = backward;
     p.symmetric = symmetric;
     p.elem = elem;
@@ -118,6 +122,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const int NVC = R + 1 + C;   // lane state kept per checkpoint
         p.ckpt_slot = (int64_t)p.ns * p.nseg * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
+    }
+    if (io_elem != elem) {
+        p.off_kio = take((size_t)p.npairs * elem);
+        if (backward) p.off_gkio = take((size_t)p.npairs * elem);
     }
     p.total = off;
     p.valid = true;
