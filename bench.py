@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the signature-kernel hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic paths: one sigkernel_fwd call
+followed by one sigkernel_bwd call (for the Gram workloads: sigkernel_gram without and with grad_K).
+Inputs, outputs and workspace are resident in HBM before the timed region starts.
+
+metric  = PDE cell-updates per second over forward + backward: cells / (t_fwd + t_bwd), where
+          cells = pairs * 2^lam (L-1) * 2^lam (L-1) is counted once per step (each of the two calls
+          sweeps every cell at least once; the backward call also replays the forward values).
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X: 256 CUs x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+
+
+def algorithmic_flops_per_cell(d, time_aug, lam, backward):
+    """Flops the method needs per refined cell (paper Eq. (1) and Section 3.4), independent of how this
+    library schedules them: the stencil on every refined cell, and the coefficient polynomials plus the
+    d-channel contractions once per coarse cell (4^lam refined cells).
+      forward : 4 (stencil) + (7 (A, B) + 2 (d + time)) / 4^lam
+      backward: 6 (adjoint recurrence) + 9 (local derivative and accumulation)
+                + (10 (A, B, A', B') + 2 (d + time) (Delta) + 4 d (map to dx and dy)) / 4^lam
+    The forward values the backward call recomputes are a design cost and are not counted."""
+    de = d + (1 if time_aug else 0)
+    per_coarse = 4.0 ** lam
+    if not backward:
+        return 4.0 + (7.0 + 2.0 * de) / per_coarse
+    return 15.0 + (10.0 + 2.0 * de + 4.0 * d) / per_coarse
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", help="c2 (headline), or c1/c3/c4/c5 for the other configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (pairs are independent; see DESIGN.md for how the "
+              "path would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2509_10613_amd import binding as sk
+    from paper_2509_10613_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w, X, Y = workloads.make(args.workload)
+    lam, flags = w.lam, w.flags
+    x = torch.tensor(X, device=dev)
+    y = torch.tensor(Y, device=dev)
+    cells = w.pairs * w.cells_per_pair
+    gram = w.kind == "gram"
+    f64 = sk.SK_F64
+
+    if gram:
+        W = torch.tensor(workloads.upstream_weights(77, (w.n_x, w.n_y)), device=dev)
+        K = torch.empty((w.n_x, w.n_y), dtype=torch.float64, device=dev)
+        gX = torch.empty_like(x)
+        gY = torch.empty_like(y)
+        need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags, f64),
+                   sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM_BWD, w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags, f64))
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+        def fwd_call():
+            sk.sigkernel_gram(x, y, None, lam, lam, flags, K=K, ws=ws)
+
+        def bwd_call():
+            sk.sigkernel_gram(x, y, W, lam, lam, flags, K=K, grad_X=gX, grad_Y=gY, ws=ws)
+    else:
+        gk = torch.tensor(workloads.upstream_weights(77, (w.n_x,)), device=dev)
+        k = torch.empty((w.n_x,), dtype=torch.float64, device=dev)
+        k2 = torch.empty_like(k)
+        gx = torch.empty_like(x)
+        gy = torch.empty_like(y)
+        need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags, f64),
+                   sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags, f64))
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+        def fwd_call():
+            sk.sigkernel_fwd(x, y, lam, lam, flags, k=k, ws=ws)
+
+        def bwd_call():
+            sk.sigkernel_bwd(x, y, gk, lam, lam, flags, grad_x=gx, grad_y=gy, k_out=k2, ws=ws)
+
+    def step():
+        fwd_call()
+        if w.backward:
+            bwd_call()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps steps, sweep kernels bracketed by HIP events on the launch stream
+    sk.sigkernel_event_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sk.sigkernel_event_timing(False)
+    fwd_ms, nf, bwd_ms, nb = sk.sigkernel_event_timing_read()
+    sec_per_step = (t1 - t0) / args.steps
+
+    # separate timings of the two calls (reported, not the headline)
+    def time_call(fn, n):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) / n
+
+    n_sep = max(3, args.steps // 4)
+    t_fwd = time_call(fwd_call, n_sep)
+    t_bwd = time_call(bwd_call, n_sep) if w.backward else None
+
+    # roofline of the dominant kernel (the backward sweep when there is one)
+    dom_back = bool(w.backward and nb > 0)
+    dom_ms = (bwd_ms / nb) if dom_back else (fwd_ms / max(nf, 1))
+    flops = cells * algorithmic_flops_per_cell(w.d, bool(flags & 1), lam, dom_back)
+    achieved = flops / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "alu", "kernel": "sweep_bwd_kernel" if dom_back else "sweep_fwd_kernel",
+                "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "avg_launch_ms": dom_ms,
+                "flops_per_launch": flops, "traffic": None}
+    fwd_kernel_ms = fwd_ms / max(nf, 1)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nx = min(w.n_x, 128 if not gram else 12)
+        ny = min(w.n_y, 128 if not gram else 12)
+        Xs, Ys = X[:nx], Y[:ny]
+        sample_pairs = nx * ny if gram else nx
+        reps, spent = 0, 0.0
+        while spent < args.cpu_seconds and reps < 50:
+            a = time.perf_counter()
+            if gram:
+                oracle.gram(Xs, Ys, None, lam, lam, flags)
+                if w.backward:
+                    oracle.gram(Xs, Ys, np.ones((nx, ny)), lam, lam, flags)
+            else:
+                oracle.fwd(Xs, Ys, lam, lam, flags)
+                if w.backward:
+                    oracle.bwd(Xs, Ys, np.ones(nx), lam, lam, flags)
+            spent += time.perf_counter() - a
+            reps += 1
+        cpu = {"value": sample_pairs * w.cells_per_pair * reps / spent, "unit": "cells/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": "%d pairs of %s (fwd%s), %d repetitions, %.1f s" % (sample_pairs, w.name,
+                                                                             "+bwd" if w.backward else "", reps, spent)}
+
+    out = {
+        "metric": "PDE cell-updates/s (fwd+bwd), fp64, 1 MI355X",
+        "value": cells / sec_per_step,
+        "unit": "cells/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s, %d pairs, L=%d, d=%d, dyadic order %d%s, fp64, fwd%s" % (
+            w.name, w.kind, w.pairs, w.L, w.d, lam, ", time-augmented" if flags & 1 else "",
+            "+bwd" if w.backward else ""), "cells_per_step": cells},
+        "evals_per_s": w.pairs / sec_per_step,
+        "fwd_call_ms": t_fwd * 1e3,
+        "bwd_call_ms": None if t_bwd is None else t_bwd * 1e3,
+        "fwd_cells_per_s": cells / t_fwd,
+        "bwd_cells_per_s": None if t_bwd is None else cells / t_bwd,
+        "fwd_sweep_kernel_ms": fwd_kernel_ms,
+        "bwd_sweep_kernel_ms": (bwd_ms / nb) if nb else None,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -94,6 +94,16 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
                    int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags,
                    sk_dtype dt, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Benchmark support (no passage of the paper): while enabled, every sweep-kernel launch made by the
+ * three entry points above is bracketed by a HIP event pair recorded on the caller's stream.
+ * sigkernel_event_timing_read waits for the recorded launches to finish, returns the summed elapsed
+ * milliseconds and the launch counts of the forward and the backward sweep kernels since the last
+ * read (any pointer may be NULL), and releases the events.  Not for use under stream capture.
+ */
+int sigkernel_event_timing(int enable);
+int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches);
+
 /* Thread-local, NUL-terminated message describing the last non-zero return on this thread. */
 const char* sigkernel_last_error(void);
 

@@ -16,7 +16,7 @@ SK_FLAG_TIME_AUG = 1
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram",
-           "sigkernel_last_error", "sigkernel_version"]
+           "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version"]
 
 _lib = None
 
@@ -45,6 +45,11 @@ def load():
     lib.sigkernel_gram.restype = ci
     lib.sigkernel_gram.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t,
                                    vp]
+    lib.sigkernel_event_timing.restype = ci
+    lib.sigkernel_event_timing.argtypes = [ci]
+    lib.sigkernel_event_timing_read.restype = ci
+    lib.sigkernel_event_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(ci), C.POINTER(C.c_double),
+                                                C.POINTER(ci)]
     lib.sigkernel_last_error.restype = C.c_char_p
     lib.sigkernel_version.restype = C.c_char_p
     _lib = lib
@@ -80,6 +85,18 @@ def _stream():
 
 def sigkernel_workspace_bytes(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt):
     return int(load().sigkernel_workspace_bytes(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt))
+
+
+def sigkernel_event_timing(enable):
+    _check(load().sigkernel_event_timing(1 if enable else 0))
+
+
+def sigkernel_event_timing_read():
+    """Returns (fwd_ms, fwd_launches, bwd_ms, bwd_launches) summed since the last read."""
+    f, b = C.c_double(0), C.c_double(0)
+    nf, nb = C.c_int(0), C.c_int(0)
+    _check(load().sigkernel_event_timing_read(C.byref(f), C.byref(nf), C.byref(b), C.byref(nb)))
+    return f.value, nf.value, b.value, nb.value
 
 
 _ws_cache = {}

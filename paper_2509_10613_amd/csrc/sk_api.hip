@@ -6,6 +6,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "sigkernel.h"
 #include "sk_kernels.h"
@@ -22,6 +24,13 @@ int fail(int code, const char* fmt, ...)
     va_end(ap);
     return code;
 }
+
+// Optional HIP-event timing of the sweep kernels (for benchmarks): one event pair per sweep launch,
+// recorded on the caller's stream while enabled.
+struct TimedLaunch { hipEvent_t start, stop; int backward; };
+std::mutex g_timing_mu;
+bool g_timing_on = false;
+std::vector<TimedLaunch> g_timed;
 
 int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
 {
@@ -105,7 +114,24 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         if (a.want_gx) SK_CHECK(launch_fill<double>(a.gdxT, p.nx * p.xstride, 0.0, st));
         if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<double>(a.gdyT, p.ny * p.ystride, 0.0, st));
     }
+    bool timed = false;
+    TimedLaunch tl{};
+    {
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        timed = g_timing_on;
+    }
+    if (timed) {
+        SK_CHECK(hipEventCreate(&tl.start));
+        SK_CHECK(hipEventCreate(&tl.stop));
+        tl.backward = backward ? 1 : 0;
+        SK_CHECK(hipEventRecord(tl.start, st));
+    }
     SK_CHECK(launch_sweep<double>(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    if (timed) {
+        SK_CHECK(hipEventRecord(tl.stop, st));
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        g_timed.push_back(tl);
+    }
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
     if (backward) {
         if (grad_x)
@@ -218,6 +244,39 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
 {
     return dispatch(grad_K != nullptr, true, X, Y, K, grad_K, grad_X, grad_Y, N, M, L1, L2, d, lam1, lam2, flags,
                     dt, ws, ws_bytes, stream);
+}
+
+int sigkernel_event_timing(int enable)
+{
+    std::lock_guard<std::mutex> lk(g_timing_mu);
+    g_timing_on = enable != 0;
+    return SK_OK;
+}
+
+int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches)
+{
+    std::vector<TimedLaunch> v;
+    {
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        v.swap(g_timed);
+    }
+    double ms[2] = {0.0, 0.0};
+    int cnt[2] = {0, 0};
+    int rc = SK_OK;
+    for (auto& t : v) {
+        hipError_t e = hipEventSynchronize(t.stop);
+        float f = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&f, t.start, t.stop);
+        if (e != hipSuccess) rc = fail(SK_ERR_HIP, "event timing: %s", hipGetErrorString(e));
+        else { ms[t.backward] += f; cnt[t.backward] += 1; }
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    if (fwd_ms) *fwd_ms = ms[0];
+    if (fwd_launches) *fwd_launches = cnt[0];
+    if (bwd_ms) *bwd_ms = ms[1];
+    if (bwd_launches) *bwd_launches = cnt[1];
+    return rc;
 }
 
 const char* sigkernel_last_error(void) { return g_err; }

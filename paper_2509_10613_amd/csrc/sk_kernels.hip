@@ -82,6 +82,15 @@ __device__ __forceinline__ void scratch_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
+// Pointers into LDS keep their address space in the type, so that every access is a ds_* instruction.
+#define SK_LDS __attribute__((address_space(3)))
+
+template <typename T>
+__device__ __forceinline__ void lds_atomic_add(SK_LDS T* p, T v)
+{
+    (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 template <typename T> __device__ __forceinline__ T fmaT(T a, T b, T c);
 template <> __device__ __forceinline__ double fmaT<double>(double a, double b, double c) { return fma(a, b, c); }
 template <> __device__ __forceinline__ float fmaT<float>(float a, float b, float c) { return fmaf(a, b, c); }
@@ -152,6 +161,32 @@ __global__ void finalize_grad_kernel(const double* __restrict__ g, TO* __restric
 // ------------------------------------------------------------------------------------------------
 // sweep building blocks
 // ------------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ T wave_from_above_or(T v, T edge)   // lane i receives v of lane i-1; lane 0 gets edge
+{
+    constexpr int NW = sizeof(T) / 4;
+    int w[NW], o[NW];
+    __builtin_memcpy(w, &v, sizeof(T));
+    __builtin_memcpy(o, &edge, sizeof(T));
+#pragma unroll
+    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_update_dpp(o[i], w[i], 0x138, 0xf, 0xf, false);
+    __builtin_memcpy(&v, w, sizeof(T));
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_from_below_or(T v, T edge)   // lane i receives v of lane i+1; lane 63 gets edge
+{
+    constexpr int NW = sizeof(T) / 4;
+    int w[NW], o[NW];
+    __builtin_memcpy(w, &v, sizeof(T));
+    __builtin_memcpy(o, &edge, sizeof(T));
+#pragma unroll
+    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_update_dpp(o[i], w[i], 0x130, 0xf, 0xf, false);
+    __builtin_memcpy(&v, w, sizeof(T));
+    return v;
+}
+
 template <typename T, int BL, int D>
 struct Sweep {
     static constexpr int R = 1 << BL;
@@ -165,18 +200,23 @@ struct Sweep {
     // per pair
     const T* dxrow = nullptr;   // transposed x increments of the pair: [c][rpad]
     const T* dyg = nullptr;     // transposed y increments in global memory: [c][qpad]
-    const T* dyl = nullptr;     // the same staged in LDS (when a.y_lds)
+    const SK_LDS T* dyl = nullptr;   // the same staged in LDS (when a.y_lds)
     // per strip
     int s = 0, lb = 0, arow = 0;
-    bool rowvalid = false;
+    int nbl = 0;                // a.nb for lanes that own a block row, 0 otherwise
     T dxr[DN];
     const T* rowprev = nullptr;
     T* rowcur = nullptr;
     // forward lane state
     T left[R + 1];
     T bot[C];
-    T topc[C];
-    int topchunk = -1;
+    // top edge feed of lane 0: lane q of topc holds the boundary-row values of block column
+    // (column of lane 0 at the current step) + q; the register rotates by one lane per step and is
+    // refilled every 64 steps from topn, which is loaded one chunk ahead.
+    T topc[C], topn[C];
+    int chunk_end = 0;
+    // y increments of the block this lane processes at the coming step (loaded one step ahead)
+    T ycur[DN];
 
     __device__ __forceinline__ Sweep(const SweepArgs<T>& a_, int lane_) : a(a_), lane(lane_) {}
 
@@ -184,7 +224,7 @@ struct Sweep {
     {
         s = s_;
         const int I = s * kWave + lane;
-        rowvalid = I < a.mb;
+        nbl = I < a.mb ? a.nb : 0;
         int rem = a.mb - s * kWave - 1;
         lb = rem < kWave - 1 ? rem : kWave - 1;
         int ar = I >> a.rs1;
@@ -195,16 +235,31 @@ struct Sweep {
         }
         rowprev = s > 0 ? rows + (long)(s - 1) * a.rowlen : nullptr;
         rowcur = rows + (long)s * a.rowlen;
-        reset_state();
-    }
-
-    __device__ __forceinline__ void reset_state()
-    {
 #pragma unroll
         for (int i = 0; i <= R; ++i) left[i] = T(1);
 #pragma unroll
-        for (int i = 0; i < C; ++i) { bot[i] = T(1); topc[i] = T(1); }
-        topchunk = -1;
+        for (int i = 0; i < C; ++i) bot[i] = T(1);
+    }
+
+    __device__ __forceinline__ bool rowvalid() const { return nbl != 0; }
+
+    // y increments of block column J (clamped into range so that every lane may load)
+    __device__ __forceinline__ void fetch_y(int J, T (&yv)[DN]) const
+    {
+        if constexpr (D > 0) {
+            int Jc = J < 0 ? 0 : J;
+            Jc = Jc < a.nb ? Jc : a.nb - 1;
+            const int b = Jc >> a.rs2;
+            if (a.y_lds) {
+#pragma unroll
+                for (int c = 0; c < D; ++c) yv[c] = dyl[c * a.qpad + b];
+            } else {
+#pragma unroll
+                for (int c = 0; c < D; ++c) yv[c] = dyg[(long)c * a.qpad + b];
+            }
+        } else {
+            yv[0] = T(0);
+        }
     }
 
     __device__ __forceinline__ T load_y(int c, int b) const
@@ -213,15 +268,14 @@ struct Sweep {
     }
 
     // p = 2^-(lam1+lam2) <dx[a], dy[b]> (+ the time channel's constant product), Eq. (1) third line.
-    __device__ __forceinline__ T inner(int b, T (&yv)[DN]) const
+    __device__ __forceinline__ T inner(int b, const T (&yv)[DN]) const
     {
         T p = a.tc;
         if constexpr (D > 0) {
 #pragma unroll
-            for (int c = 0; c < D; ++c) { yv[c] = load_y(c, b); p = fmaT(dxr[c], yv[c], p); }
+            for (int c = 0; c < D; ++c) p = fmaT(dxr[c], yv[c], p);
         } else {
             for (int c = 0; c < a.d; ++c) p = fmaT(a.sc * dxrow[(long)c * a.rpad + arow], load_y(c, b), p);
-            yv[0] = T(0);
         }
         return p;
     }
@@ -239,29 +293,44 @@ struct Sweep {
                 e[rr + 1][cc + 1] = fmaT(e[rr + 1][cc] + e[rr][cc + 1], Ac, -(e[rr][cc] * Bc));
     }
 
-    __device__ __forceinline__ void load_top_chunk(int Tstep)
+    __device__ __forceinline__ void load_top(int Jbase, T (&dst)[C]) const
     {
-        topchunk = Tstep >> 6;
-        const int Jq = (Tstep & ~63) + lane;
+        const int Jq = Jbase + lane;
 #pragma unroll
         for (int cc = 0; cc < C; ++cc)
-            topc[cc] = (rowprev != nullptr && Jq < a.nb) ? ld_scratch(rowprev + (long)Jq * C + 1 + cc) : T(1);
+            dst[cc] = (rowprev != nullptr && Jq < a.nb) ? ld_scratch(rowprev + (long)Jq * C + 1 + cc) : T(1);
+    }
+
+    // Call before the first forward_step of a run of consecutive steps starting at T0.
+    __device__ __forceinline__ void prime(int T0)
+    {
+        load_top(T0, topc);
+        load_top(T0 + kWave, topn);
+        chunk_end = T0 + kWave;
+        fetch_y(T0 - lane, ycur);
     }
 
     // One forward macro-step.  Returns whether this lane processed a block; e, p, yv describe it.
     template <bool WRITE_ROW>
     __device__ __forceinline__ bool forward_step(int Tstep, T (&e)[R + 1][C + 1], T& p, T (&yv)[DN])
     {
-        if ((Tstep >> 6) != topchunk && Tstep < a.nb) load_top_chunk(Tstep);
+        if (Tstep == chunk_end) {
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) topc[cc] = topn[cc];
+            load_top(Tstep + kWave, topn);
+            chunk_end = Tstep + kWave;
+        }
         T recv[C];
 #pragma unroll
         for (int cc = 0; cc < C; ++cc) {
-            T v = wave_from_above(bot[cc]);
-            T tv = read_lane(topc[cc], Tstep & 63);
-            recv[cc] = lane == 0 ? tv : v;
+            recv[cc] = wave_from_above_or(bot[cc], topc[cc]);
+            topc[cc] = wave_from_below(topc[cc]);
         }
         const int J = Tstep - lane;
-        const bool active = rowvalid && J >= 0 && J < a.nb;
+#pragma unroll
+        for (int c = 0; c < DN; ++c) yv[c] = ycur[c];
+        fetch_y(J + 1, ycur);   // for the next step; consumed one iteration later
+        const bool active = (unsigned)J < (unsigned)nbl;
         if (active) {
             e[0][0] = left[0];
 #pragma unroll
@@ -286,7 +355,7 @@ struct Sweep {
 };
 
 // ------------------------------------------------------------------------------------------------
-// forward kernel: one wave per pair, WPB independent waves per workgroup
+// forward kernel: one wave per pair, kWavesPerWG independent waves per workgroup
 // ------------------------------------------------------------------------------------------------
 template <typename T, int BL, int D>
 __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs<T> a)
@@ -298,7 +367,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs
     const int w = threadIdx.x >> 6;
     const long slot = (long)blockIdx.x * kWavesPerWG + w;
     const long nslots = (long)gridDim.x * kWavesPerWG;
-    T* ylds = reinterpret_cast<T*>(smem + (size_t)w * a.lds_wave);
+    SK_LDS T* ylds = (SK_LDS T*)(smem + (size_t)w * a.lds_wave);
     T* rows = a.rows + slot * a.rows_slot;
     SW sw(a, lane);
 
@@ -316,17 +385,22 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs
             sw.begin_strip(s, rows);
             const int NT = sw.strip_steps();
             const bool last = s == a.ns - 1;
-            for (int Tstep = 0; Tstep < NT; ++Tstep) {
-                T e[R + 1][C + 1];
-                T p;
-                T yv[SW::DN];
-                bool act = last ? sw.template forward_step<false>(Tstep, e, p, yv)
-                                : sw.template forward_step<true>(Tstep, e, p, yv);
-                (void)act;
-            }
+            sw.prime(0);
             if (last) {
+                for (int Tstep = 0; Tstep < NT; ++Tstep) {
+                    T e[R + 1][C + 1];
+                    T p;
+                    T yv[SW::DN];
+                    sw.template forward_step<false>(Tstep, e, p, yv);
+                }
                 if (lane == sw.lb) a.k_out[pid] = sw.bot[C - 1];
             } else {
+                for (int Tstep = 0; Tstep < NT; ++Tstep) {
+                    T e[R + 1][C + 1];
+                    T p;
+                    T yv[SW::DN];
+                    sw.template forward_step<true>(Tstep, e, p, yv);
+                }
                 scratch_fence();
             }
         }
@@ -347,9 +421,9 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
     const long slot = (long)blockIdx.x * kWavesPerWG + w;
     const long nslots = (long)gridDim.x * kWavesPerWG;
     unsigned char* mylds = smem + (size_t)w * a.lds_wave;
-    T* ylds = reinterpret_cast<T*>(mylds);
-    T* glds = ylds + (size_t)a.DP * a.qpad;                       // gradient accumulators for dy
-    T* ring = reinterpret_cast<T*>(mylds + a.ring_off);
+    SK_LDS T* ylds = (SK_LDS T*)mylds;
+    SK_LDS T* glds = ylds + (size_t)a.DP * a.qpad;                // gradient accumulators for dy
+    SK_LDS T* ring = (SK_LDS T*)(mylds + a.ring_off);
     T* rows = a.rows + slot * a.rows_slot;
     T* adj = a.adj + slot * a.adj_slot;
     T* ckpt = a.ckpt + slot * a.ckpt_slot;
@@ -374,18 +448,20 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
         for (int s = 0; s < a.ns; ++s) {
             sw.begin_strip(s, rows);
             const int NT = sw.strip_steps();
-            for (int Tstep = 0; Tstep < NT; ++Tstep) {
-                if (Tstep % S == 0) {
-                    T* cp = ckpt + ((long)(s * a.nseg + Tstep / S) * NVC) * kWave + lane;
+            sw.prime(0);
+            for (int T0 = 0; T0 < NT; T0 += S) {
+                T* cp = ckpt + ((long)(s * a.nseg + T0 / S) * NVC) * kWave + lane;
 #pragma unroll
-                    for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
+                for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
 #pragma unroll
-                    for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
+                for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
+                const int T1 = T0 + S < NT ? T0 + S : NT;
+                for (int Tstep = T0; Tstep < T1; ++Tstep) {
+                    T e[R + 1][C + 1];
+                    T p;
+                    T yv[DN];
+                    sw.template forward_step<true>(Tstep, e, p, yv);
                 }
-                T e[R + 1][C + 1];
-                T p;
-                T yv[DN];
-                sw.template forward_step<true>(Tstep, e, p, yv);
             }
             if (s == a.ns - 1 && lane == sw.lb && a.k_out) a.k_out[pid] = sw.bot[C - 1];
             scratch_fence();
@@ -396,22 +472,37 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
             sw.begin_strip(s, rows);
             const int NT = sw.strip_steps();
             const int lb = sw.lb;
-            const bool has_below = s < a.ns - 1;
+            const bool has_below = s < a.ns - 1;   // then lb == 63
             const T* adjr = adj + (long)((s + 1) & 1) * a.rowlen;   // written by the strip below
             T* adjw = adj + (long)(s & 1) * a.rowlen;
             // adjoint lane state
             T accL[R + 1];
             T up[C];
             T corner = T(0);
-            T adjc[C];
-            int adjchunk = -1;
+            // bottom edge feed of lane 63 (adjoint messages of the strip below): lane q of adjc holds
+            // the entry of block column (column of lane 63 at the current step) - (63 - q); it rotates
+            // by one lane per step and is refilled every 64 steps from adjn, loaded one chunk ahead.
+            T adjc[C], adjn[C];
+            int adj_end = 0;
             T gacc[DN];
 #pragma unroll
             for (int i = 0; i <= R; ++i) accL[i] = T(0);
 #pragma unroll
-            for (int i = 0; i < C; ++i) { up[i] = T(0); adjc[i] = T(0); }
+            for (int i = 0; i < C; ++i) { up[i] = T(0); adjc[i] = T(0); adjn[i] = T(0); }
 #pragma unroll
             for (int i = 0; i < DN; ++i) gacc[i] = T(0);
+            auto load_adj = [&](int Jb, T (&dst)[C]) {
+                const int Jq = Jb - (kWave - 1 - lane);
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc)
+                    dst[cc] = (has_below && Jq >= 0 && Jq < a.nb) ? ld_scratch(adjr + (long)Jq * C + 1 + cc) : T(0);
+            };
+            {
+                const int Jb0 = NT - 1 - lb;   // block column of lane lb at the first reverse step
+                load_adj(Jb0, adjc);
+                load_adj(Jb0 - kWave, adjn);
+                adj_end = NT - 1 - kWave;
+            }
 
             const int nsegs = (NT + S - 1) / S;
             for (int g = nsegs - 1; g >= 0; --g) {
@@ -424,7 +515,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                     for (int i = 0; i <= R; ++i) sw.left[i] = ld_scratch(cp + i * kWave);
 #pragma unroll
                     for (int i = 0; i < C; ++i) sw.bot[i] = ld_scratch(cp + (R + 1 + i) * kWave);
-                    sw.topchunk = -1;
+                    sw.prime(T0);
                 }
                 for (int Tstep = T0; Tstep < T1; ++Tstep) {
                     T e[R + 1][C + 1];
@@ -433,42 +524,53 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                     // keep the block input edges (forward_step leaves e[0][*] and e[*][0] untouched)
                     const bool act = sw.template forward_step<false>(Tstep, e, p, yv);
                     if (act) {
-                        T* rp = ring + ((long)(Tstep - T0) * NVR) * kWave + lane;
+                        SK_LDS T* rp = ring + ((Tstep - T0) * NVR) * kWave + lane;
 #pragma unroll
                         for (int cc = 0; cc <= C; ++cc) rp[cc * kWave] = e[0][cc];
 #pragma unroll
                         for (int rr = 1; rr <= R; ++rr) rp[(C + rr) * kWave] = e[rr][0];
                     }
                 }
-                // walk the segment backwards
-                for (int Tstep = T1 - 1; Tstep >= T0; --Tstep) {
-                    const int Jb = Tstep - lb;   // block column of the strip's last lane
-                    if (has_below && Jb >= 0 && (Jb >> 6) != adjchunk) {
-                        adjchunk = Jb >> 6;
-                        const int Jq = (Jb & ~63) + lane;
+                // walk the segment backwards; ring entries and y increments are fetched one step ahead
+                T ein[NVR], ynx[DN];
+                {
+                    const SK_LDS T* rp = ring + ((T1 - 1 - T0) * NVR) * kWave + lane;
 #pragma unroll
-                        for (int cc = 0; cc < C; ++cc)
-                            adjc[cc] = Jq < a.nb ? ld_scratch(adjr + (long)Jq * C + 1 + cc) : T(0);
+                    for (int v = 0; v < NVR; ++v) ein[v] = rp[v * kWave];
+                    sw.fetch_y(T1 - 1 - lane, ynx);
+                }
+                for (int Tstep = T1 - 1; Tstep >= T0; --Tstep) {
+                    if (Tstep == adj_end) {
+#pragma unroll
+                        for (int cc = 0; cc < C; ++cc) adjc[cc] = adjn[cc];
+                        load_adj(Tstep - lb - kWave, adjn);
+                        adj_end = Tstep - kWave;
                     }
                     T recv[C];
 #pragma unroll
                     for (int cc = 0; cc < C; ++cc) {
-                        T v = wave_from_below(up[cc]);
-                        T tv = read_lane(adjc[cc], Jb & 63);
-                        recv[cc] = lane == lb ? (has_below ? tv : T(0)) : v;
+                        recv[cc] = wave_from_below_or(up[cc], adjc[cc]);
+                        adjc[cc] = wave_from_above(adjc[cc]);
                     }
                     const int J = Tstep - lane;
-                    const bool active = sw.rowvalid && J >= 0 && J < a.nb;
+                    T e[R + 1][C + 1];
+                    T yv[DN];
+#pragma unroll
+                    for (int cc = 0; cc <= C; ++cc) e[0][cc] = ein[cc];
+#pragma unroll
+                    for (int rr = 1; rr <= R; ++rr) e[rr][0] = ein[C + rr];
+#pragma unroll
+                    for (int c = 0; c < DN; ++c) yv[c] = ynx[c];
+                    if (Tstep > T0) {
+                        const SK_LDS T* rp = ring + ((Tstep - 1 - T0) * NVR) * kWave + lane;
+#pragma unroll
+                        for (int v = 0; v < NVR; ++v) ein[v] = rp[v * kWave];
+                        sw.fetch_y(J - 1, ynx);
+                    }
+                    const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
                         // forward values of the block: edges from the ring, interior by Eq. (1)
-                        T e[R + 1][C + 1];
-                        const T* rp = ring + ((long)(Tstep - T0) * NVR) * kWave + lane;
-#pragma unroll
-                        for (int cc = 0; cc <= C; ++cc) e[0][cc] = rp[cc * kWave];
-#pragma unroll
-                        for (int rr = 1; rr <= R; ++rr) e[rr][0] = rp[(C + rr) * kWave];
                         const int b = J >> a.rs2;
-                        T yv[DN];
                         const T p = sw.inner(b, yv);
                         SW::block_forward(e, p);
                         const T q2 = p * p;
@@ -515,11 +617,13 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
 #pragma unroll
                             for (int c = 0; c < D; ++c) gacc[c] = fmaT(accP, yv[c], gacc[c]);
                             if (a.want_gy) {
+                                if (a.y_lds) {
 #pragma unroll
-                                for (int c = 0; c < D; ++c) {
-                                    const T val = accP * sw.dxr[c];
-                                    if (a.y_lds) unsafeAtomicAdd(&glds[c * a.qpad + b], val);
-                                    else unsafeAtomicAdd(&gdy[(long)c * a.qpad + b], val);
+                                    for (int c = 0; c < D; ++c) lds_atomic_add(&glds[c * a.qpad + b], accP * sw.dxr[c]);
+                                } else {
+#pragma unroll
+                                    for (int c = 0; c < D; ++c)
+                                        unsafeAtomicAdd(&gdy[(long)c * a.qpad + b], accP * sw.dxr[c]);
                                 }
                             }
                         } else {
@@ -529,7 +633,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                                     unsafeAtomicAdd(&gdx[(long)c * a.rpad + sw.arow], ap * sw.load_y(c, b));
                                 if (a.want_gy) {
                                     const T val = ap * sw.dxrow[(long)c * a.rpad + sw.arow];
-                                    if (a.y_lds) unsafeAtomicAdd(&glds[c * a.qpad + b], val);
+                                    if (a.y_lds) lds_atomic_add(&glds[c * a.qpad + b], val);
                                     else unsafeAtomicAdd(&gdy[(long)c * a.qpad + b], val);
                                 }
                             }
@@ -538,7 +642,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                 }
             }
             if constexpr (D > 0) {
-                if (a.want_gx && sw.rowvalid) {
+                if (a.want_gx && sw.rowvalid()) {
 #pragma unroll
                     for (int c = 0; c < D; ++c) unsafeAtomicAdd(&gdx[(long)c * a.rpad + sw.arow], gacc[c] * a.sc);
                 }
