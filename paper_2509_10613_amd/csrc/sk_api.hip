@@ -73,11 +73,11 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     if (!p.symmetric)
         SK_CHECK(launch_increments<T>(static_cast<const T*>(y), dyT, p.ny, p.L2, p.d, p.DP, p.qpad, st));
 
-    SweepArgs<double> a;
+    SweepArgs a;
     std::memset(&a, 0, sizeof(a));
-    a.dxT = dxT; a.dyT = dyT;
+    a.dx = dxT; a.dy = dyT;
     a.xstride = p.xstride; a.ystride = p.ystride;
-    a.rpad = p.rpad; a.qpad = p.qpad; a.DP = p.DP;
+    a.rpad = p.rpad; a.qpad = p.qpad; a.DS = p.DP;
     if (kIsDouble) {
         a.k_out = static_cast<double*>(k);
         a.grad_k = static_cast<const double*>(grad_k);
@@ -100,19 +100,19 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.sc = sc;
     a.tc = (flags & SK_FLAG_TIME_AUG) ? sc * (1.0 / (double)(p.L1 - 1)) * (1.0 / (double)(p.L2 - 1)) : 0.0;
     a.y_lds = p.y_lds;
-    a.lds_wave = p.lds_wave;
-    a.ring_off = p.ring_off;
+    a.lds_wave = (unsigned)p.lds_wave;
+    a.ring_off = (unsigned)p.ring_off;
     if (backward) {
-        a.gdxT = reinterpret_cast<double*>(base + p.off_gdxT);
-        a.gdyT = reinterpret_cast<double*>(base + p.off_gdyT);
+        a.gdx = reinterpret_cast<double*>(base + p.off_gdxT);
+        a.gdy = reinterpret_cast<double*>(base + p.off_gdyT);
         a.want_gx = grad_x != nullptr;
         a.want_gy = p.symmetric ? (grad_x != nullptr) : (grad_y != nullptr);
         a.adj = reinterpret_cast<double*>(base + p.off_adj);
         a.adj_slot = p.adj_slot;
         a.ckpt = reinterpret_cast<double*>(base + p.off_ckpt);
         a.ckpt_slot = p.ckpt_slot;
-        if (a.want_gx) SK_CHECK(launch_fill<double>(a.gdxT, p.nx * p.xstride, 0.0, st));
-        if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<double>(a.gdyT, p.ny * p.ystride, 0.0, st));
+        if (a.want_gx) SK_CHECK(launch_fill<double>(a.gdx, p.nx * p.xstride, 0.0, st));
+        if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<double>(a.gdy, p.ny * p.ystride, 0.0, st));
     }
     bool timed = false;
     TimedLaunch tl{};
@@ -126,7 +126,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         tl.backward = backward ? 1 : 0;
         SK_CHECK(hipEventRecord(tl.start, st));
     }
-    SK_CHECK(launch_sweep<double>(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     if (timed) {
         SK_CHECK(hipEventRecord(tl.stop, st));
         std::lock_guard<std::mutex> lk(g_timing_mu);
@@ -135,9 +135,9 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
     if (backward) {
         if (grad_x)
-            SK_CHECK(launch_finalize<T>(a.gdxT, static_cast<T*>(grad_x), p.nx, p.L1, p.d, p.DP, p.rpad, st));
+            SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.d, p.DP, p.rpad, st));
         if (grad_y && !p.symmetric)
-            SK_CHECK(launch_finalize<T>(a.gdyT, static_cast<T*>(grad_y), p.ny, p.L2, p.d, p.DP, p.qpad, st));
+            SK_CHECK(launch_finalize<T>(a.gdy, static_cast<T*>(grad_y), p.ny, p.L2, p.d, p.DP, p.qpad, st));
     }
 #undef SK_CHECK
     return SK_OK;

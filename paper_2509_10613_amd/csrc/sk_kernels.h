@@ -6,23 +6,24 @@
 
 namespace sk {
 
-template <typename T>
+using real = double;   // arithmetic type of every sweep
+
 struct SweepArgs {
-    const T* dxT;        // [nx][DP][rpad] transposed, zero-padded x increments
-    const T* dyT;        // [ny][DP][qpad]
+    const real* dx;      // [nx][rpad][DS] zero-padded x increments
+    const real* dy;      // [ny][qpad][DS]
     long xstride, ystride;
-    int rpad, qpad, DP;
-    T* k_out;            // [npairs] (may be null in the backward kernel)
-    const T* grad_k;     // [npairs] upstream gradients (backward)
-    T* gdxT;             // gradient accumulators in the layout of dxT / dyT (backward)
-    T* gdyT;
+    int rpad, qpad, DS;
+    real* k_out;         // [npairs] (may be null in the backward kernel)
+    const real* grad_k;  // [npairs] upstream gradients (backward)
+    real* gdx;           // gradient accumulators in the layout of dx / dy (backward)
+    real* gdy;
     int want_gx, want_gy;
-    T* rows;             // per wave slot: ns boundary rows of rowlen elements
+    real* rows;          // per wave slot: ns boundary rows of rowlen elements
     long rows_slot;
     int rowlen;
-    T* adj;              // per wave slot: two adjoint boundary rows
+    real* adj;           // per wave slot: two adjoint boundary rows
     long adj_slot;
-    T* ckpt;             // per wave slot: ns * nseg checkpoints of the lane state
+    real* ckpt;          // per wave slot: ns * nseg checkpoints of the lane state
     long ckpt_slot;
     long npairs;
     long gramM;          // > 0: pair id -> (id / gramM, id % gramM)
@@ -32,20 +33,19 @@ struct SweepArgs {
     int ns;              // strips
     int S, nseg;         // replay segment length, segments per strip
     int d;               // channels (runtime loop when the kernel has no compile-time count)
-    T tc;                // scaled product of the two time-channel increments (0 without time augmentation)
-    T sc;                // 2^-(lam1+lam2)
+    real tc;             // scaled product of the two time-channel increments (0 without time augmentation)
+    real sc;             // 2^-(lam1+lam2)
     int y_lds;
-    size_t lds_wave;     // LDS bytes per wave
-    size_t ring_off;     // byte offset of the replay ring inside a wave's LDS
+    unsigned lds_wave;   // LDS bytes per wave
+    unsigned ring_off;   // byte offset of the replay ring inside a wave's LDS
 };
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
 template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st);
 template <typename T>
-hipError_t launch_increments(const T* x, double* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
+hipError_t launch_increments(const T* x, real* out, long npaths, int L, int d, int DS, int rows, hipStream_t st);
 template <typename T>
-hipError_t launch_finalize(const double* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st);
-template <typename T>
-hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs<T>& a, int grid, size_t lds, hipStream_t st);
+hipError_t launch_finalize(const real* g, T* grad, long npaths, int L, int d, int DS, int rows, hipStream_t st);
+hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 
 }  // namespace sk

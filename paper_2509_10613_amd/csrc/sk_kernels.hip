@@ -16,64 +16,61 @@
 // (Section 3.4).  Forward values are not stored: the forward pass writes the wavefront state every S
 // macro-steps (a checkpoint), and the reverse pass replays one segment of S steps at a time into an LDS
 // ring (block input edges only), then walks that segment backwards, re-deriving the block interior.
+//
+// All sweeps run in double precision (see sk_api.hip for why float callers are converted at the edges).
 #include <hip/hip_runtime.h>
 
 #include "sk_kernels.h"
 
 namespace sk {
 
+// Pointers into LDS keep their address space in the type, so that every access is a ds_* instruction.
+#define SK_LDS __attribute__((address_space(3)))
+
 // ------------------------------------------------------------------------------------------------
 // lane exchange helpers (must be called with all 64 lanes active)
 // ------------------------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ T wave_from_above(T v)   // lane i receives lane i-1; lane 0 keeps its own
+// lane i receives v of lane i-1; lane 0 receives edge (its own lane's value of that argument)
+__device__ __forceinline__ real wave_from_above_or(real v, real edge)
 {
-    constexpr int NW = sizeof(T) / 4;
-    int w[NW];
-    __builtin_memcpy(w, &v, sizeof(T));
-#pragma unroll
-    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_update_dpp(w[i], w[i], 0x138, 0xf, 0xf, false);
-    __builtin_memcpy(&v, w, sizeof(T));
-    return v;
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    int elo = __double2loint(edge), ehi = __double2hiint(edge);
+    lo = __builtin_amdgcn_update_dpp(elo, lo, 0x138, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(ehi, hi, 0x138, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
 }
-
-template <typename T>
-__device__ __forceinline__ T wave_from_below(T v)   // lane i receives lane i+1; lane 63 keeps its own
+// lane i receives v of lane i+1; lane 63 receives edge
+__device__ __forceinline__ real wave_from_below_or(real v, real edge)
 {
-    constexpr int NW = sizeof(T) / 4;
-    int w[NW];
-    __builtin_memcpy(w, &v, sizeof(T));
-#pragma unroll
-    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_update_dpp(w[i], w[i], 0x130, 0xf, 0xf, false);
-    __builtin_memcpy(&v, w, sizeof(T));
-    return v;
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    int elo = __double2loint(edge), ehi = __double2hiint(edge);
+    lo = __builtin_amdgcn_update_dpp(elo, lo, 0x130, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(ehi, hi, 0x130, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
 }
-
-template <typename T>
-__device__ __forceinline__ T read_lane(T v, int lane)   // wave-uniform lane index
+// shifts of the feed registers: the lane that has no source receives zero
+__device__ __forceinline__ real wave_shift_down(real v)   // lane i receives lane i+1
 {
-    constexpr int NW = sizeof(T) / 4;
-    int w[NW];
-    __builtin_memcpy(w, &v, sizeof(T));
-#pragma unroll
-    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_readlane(w[i], lane);
-    __builtin_memcpy(&v, w, sizeof(T));
-    return v;
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x130, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x130, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ real wave_shift_up(real v)     // lane i receives lane i-1
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x138, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x138, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
 }
 
 // Device-scope load that bypasses the per-CU vector cache: used for data this wave wrote to global
 // scratch earlier in the same kernel.
-__device__ __forceinline__ double ld_scratch(const double* p)
+__device__ __forceinline__ real ld_scratch(const real* p)
 {
     unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
                                              __HIP_MEMORY_SCOPE_AGENT);
     return __longlong_as_double((long long)u);
-}
-__device__ __forceinline__ float ld_scratch(const float* p)
-{
-    unsigned int u = __hip_atomic_load(reinterpret_cast<const unsigned int*>(p), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-    return __uint_as_float(u);
 }
 
 __device__ __forceinline__ void scratch_fence()
@@ -82,18 +79,10 @@ __device__ __forceinline__ void scratch_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
-// Pointers into LDS keep their address space in the type, so that every access is a ds_* instruction.
-#define SK_LDS __attribute__((address_space(3)))
-
-template <typename T>
-__device__ __forceinline__ void lds_atomic_add(SK_LDS T* p, T v)
+__device__ __forceinline__ void lds_atomic_add(SK_LDS real* p, real v)
 {
     (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-
-template <typename T> __device__ __forceinline__ T fmaT(T a, T b, T c);
-template <> __device__ __forceinline__ double fmaT<double>(double a, double b, double c) { return fma(a, b, c); }
-template <> __device__ __forceinline__ float fmaT<float>(float a, float b, float c) { return fmaf(a, b, c); }
 
 // ------------------------------------------------------------------------------------------------
 // small kernels
@@ -114,34 +103,34 @@ __global__ void fill_kernel(T* p, long n, T v)
     for (; i < n; i += st) p[i] = v;
 }
 
-// Increments, transposed and padded: out[path][c][a] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d;
-// zero elsewhere (first line of the paper's forward listing).  The difference is taken in double.
+// Increments, padded: out[path][a][c] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d; zero elsewhere
+// (first line of the paper's forward listing).  rows = padded row count, DS = padded channel count.
 template <typename TI>
-__global__ void increments_kernel(const TI* __restrict__ x, double* __restrict__ out, long npaths, int L, int d,
-                                  int DP, int rpad)
+__global__ void increments_kernel(const TI* __restrict__ x, real* __restrict__ out, long npaths, int L, int d,
+                                  int DS, int rows)
 {
-    long total = npaths * (long)DP * rpad;
+    long total = npaths * (long)rows * DS;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     long st = (long)gridDim.x * blockDim.x;
     for (; i < total; i += st) {
-        int a = (int)(i % rpad);
-        long t = i / rpad;
-        int c = (int)(t % DP);
-        long pth = t / DP;
-        double v = 0.0;
+        int c = (int)(i % DS);
+        long t = i / DS;
+        int a = (int)(t % rows);
+        long pth = t / rows;
+        real v = 0.0;
         if (a < L - 1 && c < d) {
             const TI* xp = x + (pth * L + a) * (long)d + c;
-            v = (double)xp[d] - (double)xp[0];
+            v = (real)xp[d] - (real)xp[0];
         }
         out[i] = v;
     }
 }
 
-// grad[path][i][c] = g[path][c][i-1] - g[path][c][i] (out-of-range terms zero): the increments are
+// grad[path][i][c] = g[path][i-1][c] - g[path][i][c] (out-of-range terms zero): the increments are
 // differences of consecutive points, so the gradient of a point collects the two increments it touches.
 template <typename TO>
-__global__ void finalize_grad_kernel(const double* __restrict__ g, TO* __restrict__ grad, long npaths, int L, int d,
-                                     int DP, int rpad)
+__global__ void finalize_grad_kernel(const real* __restrict__ g, TO* __restrict__ grad, long npaths, int L, int d,
+                                     int DS, int rows)
 {
     long total = npaths * (long)L * d;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -151,9 +140,9 @@ __global__ void finalize_grad_kernel(const double* __restrict__ g, TO* __restric
         long t = i / d;
         int pt = (int)(t % L);
         long pth = t / L;
-        const double* gp = g + (pth * DP + c) * (long)rpad;
-        double hi = pt >= 1 ? gp[pt - 1] : 0.0;
-        double lo = pt < L - 1 ? gp[pt] : 0.0;
+        const real* gp = g + (pth * rows) * (long)DS + c;
+        real hi = pt >= 1 ? gp[(long)(pt - 1) * DS] : 0.0;
+        real lo = pt < L - 1 ? gp[(long)pt * DS] : 0.0;
         grad[i] = (TO)(hi - lo);
     }
 }
@@ -161,175 +150,136 @@ __global__ void finalize_grad_kernel(const double* __restrict__ g, TO* __restric
 // ------------------------------------------------------------------------------------------------
 // sweep building blocks
 // ------------------------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ T wave_from_above_or(T v, T edge)   // lane i receives v of lane i-1; lane 0 gets edge
-{
-    constexpr int NW = sizeof(T) / 4;
-    int w[NW], o[NW];
-    __builtin_memcpy(w, &v, sizeof(T));
-    __builtin_memcpy(o, &edge, sizeof(T));
-#pragma unroll
-    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_update_dpp(o[i], w[i], 0x138, 0xf, 0xf, false);
-    __builtin_memcpy(&v, w, sizeof(T));
-    return v;
-}
-
-template <typename T>
-__device__ __forceinline__ T wave_from_below_or(T v, T edge)   // lane i receives v of lane i+1; lane 63 gets edge
-{
-    constexpr int NW = sizeof(T) / 4;
-    int w[NW], o[NW];
-    __builtin_memcpy(w, &v, sizeof(T));
-    __builtin_memcpy(o, &edge, sizeof(T));
-#pragma unroll
-    for (int i = 0; i < NW; ++i) w[i] = __builtin_amdgcn_update_dpp(o[i], w[i], 0x130, 0xf, 0xf, false);
-    __builtin_memcpy(&v, w, sizeof(T));
-    return v;
-}
-
-template <typename T, int BL, int D>
+template <int BL, int D, bool YLDS>
 struct Sweep {
     static constexpr int R = 1 << BL;
     static constexpr int C = 1 << BL;
     static constexpr int DN = D > 0 ? D : 1;
+    // Row stride (in doubles) of the increment arrays: odd, so that the 64 lanes of a wave, reading rows
+    // one apart, spread over all LDS banks.
+    static constexpr int DSc = D | 1;
     static constexpr int NVR = R + C + 1;   // ring: top edge (C+1) + left edge below the corner (R)
     static constexpr int NVC = R + 1 + C;   // checkpoint: left edge (R+1) + own bottom edge (C)
 
-    const SweepArgs<T>& a;
+    const SweepArgs& a;
     const int lane;
     // per pair
-    const T* dxrow = nullptr;   // transposed x increments of the pair: [c][rpad]
-    const T* dyg = nullptr;     // transposed y increments in global memory: [c][qpad]
-    const SK_LDS T* dyl = nullptr;   // the same staged in LDS (when a.y_lds)
+    const real* dxp = nullptr;          // x increments of the pair: [rpad][DS]
+    const real* dyg = nullptr;          // y increments in global memory: [qpad][DS]
+    const SK_LDS real* dyl = nullptr;   // the same staged in LDS (YLDS)
     // per strip
     int s = 0, lb = 0, arow = 0;
-    int nbl = 0;                // a.nb for lanes that own a block row, 0 otherwise
-    T dxr[DN];
-    const T* rowprev = nullptr;
-    T* rowcur = nullptr;
+    int nbl = 0;                        // a.nb for lanes that own a block row, 0 otherwise
+    int lbw = -1;                       // lane that writes the strip's bottom row (-1: nobody)
+    real dxr[DN];
+    const real* rowprev = nullptr;
+    real* rowcur = nullptr;
     // forward lane state
-    T left[R + 1];
-    T bot[C];
-    // top edge feed of lane 0: lane q of topc holds the boundary-row values of block column
-    // (column of lane 0 at the current step) + q; the register rotates by one lane per step and is
-    // refilled every 64 steps from topn, which is loaded one chunk ahead.
-    T topc[C], topn[C];
-    int chunk_end = 0;
-    // y increments of the block this lane processes at the coming step (loaded one step ahead)
-    T ycur[DN];
+    real left[R + 1];
+    real bot[C];
+    // Top edge feed of lane 0: lane q of topc holds the boundary-row values of block column
+    // (column of lane 0 at the current step) + q; the register shifts down by one lane per step.
+    real topc[C];
 
-    __device__ __forceinline__ Sweep(const SweepArgs<T>& a_, int lane_) : a(a_), lane(lane_) {}
+    __device__ __forceinline__ Sweep(const SweepArgs& a_, int lane_) : a(a_), lane(lane_) {}
 
-    __device__ __forceinline__ void begin_strip(int s_, T* rows)
+    __device__ __forceinline__ void begin_strip(int s_, real* rows, bool write_row)
     {
         s = s_;
         const int I = s * kWave + lane;
         nbl = I < a.mb ? a.nb : 0;
         int rem = a.mb - s * kWave - 1;
         lb = rem < kWave - 1 ? rem : kWave - 1;
+        lbw = write_row ? lb : -1;
         int ar = I >> a.rs1;
         arow = ar < a.r ? ar : a.r - 1;
         if constexpr (D > 0) {
+            const real* xp = dxp + (long)arow * DSc;
 #pragma unroll
-            for (int c = 0; c < D; ++c) dxr[c] = a.sc * dxrow[(long)c * a.rpad + arow];
+            for (int c = 0; c < D; ++c) dxr[c] = a.sc * xp[c];
         }
         rowprev = s > 0 ? rows + (long)(s - 1) * a.rowlen : nullptr;
         rowcur = rows + (long)s * a.rowlen;
 #pragma unroll
-        for (int i = 0; i <= R; ++i) left[i] = T(1);
+        for (int i = 0; i <= R; ++i) left[i] = 1.0;
 #pragma unroll
-        for (int i = 0; i < C; ++i) bot[i] = T(1);
+        for (int i = 0; i < C; ++i) bot[i] = 1.0;
     }
 
     __device__ __forceinline__ bool rowvalid() const { return nbl != 0; }
 
     // y increments of block column J (clamped into range so that every lane may load)
-    __device__ __forceinline__ void fetch_y(int J, T (&yv)[DN]) const
+    __device__ __forceinline__ void fetch_y(int J, real (&yv)[DN]) const
     {
         if constexpr (D > 0) {
             int Jc = J < 0 ? 0 : J;
             Jc = Jc < a.nb ? Jc : a.nb - 1;
             const int b = Jc >> a.rs2;
-            if (a.y_lds) {
+            if constexpr (YLDS) {
+                const SK_LDS real* yp = dyl + b * DSc;
 #pragma unroll
-                for (int c = 0; c < D; ++c) yv[c] = dyl[c * a.qpad + b];
+                for (int c = 0; c < D; ++c) yv[c] = yp[c];
             } else {
+                const real* yp = dyg + (long)b * DSc;
 #pragma unroll
-                for (int c = 0; c < D; ++c) yv[c] = dyg[(long)c * a.qpad + b];
+                for (int c = 0; c < D; ++c) yv[c] = yp[c];
             }
         } else {
-            yv[0] = T(0);
+            yv[0] = 0.0;
         }
     }
 
-    __device__ __forceinline__ T load_y(int c, int b) const
-    {
-        return a.y_lds ? dyl[c * a.qpad + b] : dyg[(long)c * a.qpad + b];
-    }
-
     // p = 2^-(lam1+lam2) <dx[a], dy[b]> (+ the time channel's constant product), Eq. (1) third line.
-    __device__ __forceinline__ T inner(int b, const T (&yv)[DN]) const
+    __device__ __forceinline__ real inner(int b, const real (&yv)[DN]) const
     {
-        T p = a.tc;
+        real p = a.tc;
         if constexpr (D > 0) {
 #pragma unroll
-            for (int c = 0; c < D; ++c) p = fmaT(dxr[c], yv[c], p);
+            for (int c = 0; c < D; ++c) p = fma(dxr[c], yv[c], p);
         } else {
-            for (int c = 0; c < a.d; ++c) p = fmaT(a.sc * dxrow[(long)c * a.rpad + arow], load_y(c, b), p);
+            const real* xp = dxp + (long)arow * a.DS;
+            const real* yp = dyg + (long)b * a.DS;
+            for (int c = 0; c < a.d; ++c) p = fma(a.sc * xp[c], yp[c], p);
         }
         return p;
     }
 
     // Eq. (1) on the R x C cells of one block; e[0][*] and e[*][0] are given.
-    static __device__ __forceinline__ void block_forward(T (&e)[R + 1][C + 1], T p)
+    static __device__ __forceinline__ void block_forward(real (&e)[R + 1][C + 1], real p)
     {
-        const T q2 = p * p;
-        const T Bc = fmaT(q2, T(-1.0 / 12.0), T(1));
-        const T Ac = fmaT(p, T(0.5), fmaT(q2, T(1.0 / 12.0), T(1)));
+        const real q2 = p * p;
+        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
 #pragma unroll
         for (int rr = 0; rr < R; ++rr)
 #pragma unroll
             for (int cc = 0; cc < C; ++cc)
-                e[rr + 1][cc + 1] = fmaT(e[rr + 1][cc] + e[rr][cc + 1], Ac, -(e[rr][cc] * Bc));
+                e[rr + 1][cc + 1] = fma(e[rr + 1][cc] + e[rr][cc + 1], Ac, -(e[rr][cc] * Bc));
     }
 
-    __device__ __forceinline__ void load_top(int Jbase, T (&dst)[C]) const
+    // Boundary-row values of block columns Jbase + lane (ones for the first strip and past the end).
+    __device__ __forceinline__ void load_top(int Jbase, real (&dst)[C]) const
     {
         const int Jq = Jbase + lane;
+        const bool ok = rowprev != nullptr && Jq >= 0 && Jq < a.nb;
 #pragma unroll
-        for (int cc = 0; cc < C; ++cc)
-            dst[cc] = (rowprev != nullptr && Jq < a.nb) ? ld_scratch(rowprev + (long)Jq * C + 1 + cc) : T(1);
+        for (int cc = 0; cc < C; ++cc) dst[cc] = ok ? ld_scratch(rowprev + (long)Jq * C + 1 + cc) : 1.0;
     }
 
-    // Call before the first forward_step of a run of consecutive steps starting at T0.
-    __device__ __forceinline__ void prime(int T0)
+    // One forward macro-step: consumes ycur (the y increments of this lane's block at this step) and
+    // fetches those of the next step into ynext.  Returns whether this lane processed a block.
+    __device__ __forceinline__ bool forward_step(int Tstep, const real (&ycur)[DN], real (&ynext)[DN],
+                                                 real (&e)[R + 1][C + 1])
     {
-        load_top(T0, topc);
-        load_top(T0 + kWave, topn);
-        chunk_end = T0 + kWave;
-        fetch_y(T0 - lane, ycur);
-    }
-
-    // One forward macro-step.  Returns whether this lane processed a block; e, p, yv describe it.
-    template <bool WRITE_ROW>
-    __device__ __forceinline__ bool forward_step(int Tstep, T (&e)[R + 1][C + 1], T& p, T (&yv)[DN])
-    {
-        if (Tstep == chunk_end) {
-#pragma unroll
-            for (int cc = 0; cc < C; ++cc) topc[cc] = topn[cc];
-            load_top(Tstep + kWave, topn);
-            chunk_end = Tstep + kWave;
-        }
-        T recv[C];
+        real recv[C];
 #pragma unroll
         for (int cc = 0; cc < C; ++cc) {
+            const real tnext = wave_shift_down(topc[cc]);
             recv[cc] = wave_from_above_or(bot[cc], topc[cc]);
-            topc[cc] = wave_from_below(topc[cc]);
+            topc[cc] = tnext;
         }
         const int J = Tstep - lane;
-#pragma unroll
-        for (int c = 0; c < DN; ++c) yv[c] = ycur[c];
-        fetch_y(J + 1, ycur);   // for the next step; consumed one iteration later
+        fetch_y(J + 1, ynext);
         const bool active = (unsigned)J < (unsigned)nbl;
         if (active) {
             e[0][0] = left[0];
@@ -337,70 +287,106 @@ struct Sweep {
             for (int cc = 0; cc < C; ++cc) e[0][cc + 1] = recv[cc];
 #pragma unroll
             for (int rr = 1; rr <= R; ++rr) e[rr][0] = left[rr];
-            p = inner(J >> a.rs2, yv);
+            const real p = inner(J >> a.rs2, ycur);
             block_forward(e, p);
 #pragma unroll
             for (int rr = 0; rr <= R; ++rr) left[rr] = e[rr][C];
 #pragma unroll
             for (int cc = 0; cc < C; ++cc) bot[cc] = e[R][cc + 1];
-            if (WRITE_ROW && lane == lb) {
+            if (lane == lbw) {
+                real* wp = rowcur + (J * C + 1);
 #pragma unroll
-                for (int cc = 0; cc < C; ++cc) rowcur[(long)J * C + 1 + cc] = bot[cc];
+                for (int cc = 0; cc < C; ++cc) wp[cc] = bot[cc];
             }
         }
         return active;
     }
 
     __device__ __forceinline__ int strip_steps() const { return a.nb + lb; }
+
+    // Steps [T0, T1) of the forward sweep of the current strip, T1 - T0 <= 64 and topc loaded for T0.
+    // f(Tstep, active, e) is called after every step.
+    template <class F>
+    __device__ __forceinline__ void forward_run(int T0, int T1, F&& f)
+    {
+        real ya[DN], yb[DN];
+        fetch_y(T0 - lane, ya);
+        int Tstep = T0;
+        for (; Tstep + 2 <= T1; Tstep += 2) {
+            {
+                real e[R + 1][C + 1];
+                const bool act = forward_step(Tstep, ya, yb, e);
+                f(Tstep, act, e);
+            }
+            {
+                real e[R + 1][C + 1];
+                const bool act = forward_step(Tstep + 1, yb, ya, e);
+                f(Tstep + 1, act, e);
+            }
+        }
+        if (Tstep < T1) {
+            real e[R + 1][C + 1];
+            const bool act = forward_step(Tstep, ya, yb, e);
+            f(Tstep, act, e);
+        }
+    }
 };
+
+struct NoHook {
+    template <class E> __device__ __forceinline__ void operator()(int, bool, E&) const {}
+};
+
+__device__ __forceinline__ void pair_ids(const SweepArgs& a, long pid, long& xi, long& yi)
+{
+    xi = a.gramM ? pid / a.gramM : pid;
+    yi = a.gramM ? pid % a.gramM : pid;
+}
 
 // ------------------------------------------------------------------------------------------------
 // forward kernel: one wave per pair, kWavesPerWG independent waves per workgroup
 // ------------------------------------------------------------------------------------------------
-template <typename T, int BL, int D>
-__global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs<T> a)
+template <int BL, int D, bool YLDS>
+__global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using SW = Sweep<T, BL, D>;
-    constexpr int R = SW::R, C = SW::C;
+    using SW = Sweep<BL, D, YLDS>;
+    constexpr int C = SW::C;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const long slot = (long)blockIdx.x * kWavesPerWG + w;
     const long nslots = (long)gridDim.x * kWavesPerWG;
-    SK_LDS T* ylds = (SK_LDS T*)(smem + (size_t)w * a.lds_wave);
-    T* rows = a.rows + slot * a.rows_slot;
+    SK_LDS real* ylds = (SK_LDS real*)(smem + (size_t)w * a.lds_wave);
+    real* rows = a.rows + slot * a.rows_slot;
     SW sw(a, lane);
 
     for (long pid = slot; pid < a.npairs; pid += nslots) {
-        const long xi = a.gramM ? pid / a.gramM : pid;
-        const long yi = a.gramM ? pid % a.gramM : pid;
-        sw.dxrow = a.dxT + xi * a.xstride;
-        sw.dyg = a.dyT + yi * a.ystride;
+        long xi, yi;
+        pair_ids(a, pid, xi, yi);
+        sw.dxp = a.dx + xi * a.xstride;
+        sw.dyg = a.dy + yi * a.ystride;
         sw.dyl = ylds;
-        if (a.y_lds) {
-            const int n = a.DP * a.qpad;
+        if constexpr (YLDS) {
+            const int n = a.q * a.DS;
             for (int t = lane; t < n; t += kWave) ylds[t] = sw.dyg[t];
         }
         for (int s = 0; s < a.ns; ++s) {
-            sw.begin_strip(s, rows);
-            const int NT = sw.strip_steps();
             const bool last = s == a.ns - 1;
-            sw.prime(0);
-            if (last) {
-                for (int Tstep = 0; Tstep < NT; ++Tstep) {
-                    T e[R + 1][C + 1];
-                    T p;
-                    T yv[SW::DN];
-                    sw.template forward_step<false>(Tstep, e, p, yv);
+            sw.begin_strip(s, rows, !last);
+            const int NT = sw.strip_steps();
+            real topn[C];
+            sw.load_top(0, sw.topc);
+            for (int Tc = 0; Tc < NT; Tc += kWave) {
+                if (Tc > 0) {
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) sw.topc[cc] = topn[cc];
                 }
+                sw.load_top(Tc + kWave, topn);   // one chunk ahead
+                const int Te = Tc + kWave < NT ? Tc + kWave : NT;
+                sw.forward_run(Tc, Te, NoHook());
+            }
+            if (last) {
                 if (lane == sw.lb) a.k_out[pid] = sw.bot[C - 1];
             } else {
-                for (int Tstep = 0; Tstep < NT; ++Tstep) {
-                    T e[R + 1][C + 1];
-                    T p;
-                    T yv[SW::DN];
-                    sw.template forward_step<true>(Tstep, e, p, yv);
-                }
                 scratch_fence();
             }
         }
@@ -410,57 +396,63 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs
 // ------------------------------------------------------------------------------------------------
 // backward kernel: forward with checkpoints, then reverse sweep with segment replay
 // ------------------------------------------------------------------------------------------------
-template <typename T, int BL, int D>
-__global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs<T> a)
+template <int BL, int D, bool YLDS>
+__global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using SW = Sweep<T, BL, D>;
+    using SW = Sweep<BL, D, YLDS>;
     constexpr int R = SW::R, C = SW::C, NVR = SW::NVR, NVC = SW::NVC, DN = SW::DN;
+    // fetch ring entries and y increments one reverse step ahead, unless the block is so large that the
+    // second register set would not fit
+    constexpr bool LOOKAHEAD = BL < 2;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const long slot = (long)blockIdx.x * kWavesPerWG + w;
     const long nslots = (long)gridDim.x * kWavesPerWG;
     unsigned char* mylds = smem + (size_t)w * a.lds_wave;
-    SK_LDS T* ylds = (SK_LDS T*)mylds;
-    SK_LDS T* glds = ylds + (size_t)a.DP * a.qpad;                // gradient accumulators for dy
-    SK_LDS T* ring = (SK_LDS T*)(mylds + a.ring_off);
-    T* rows = a.rows + slot * a.rows_slot;
-    T* adj = a.adj + slot * a.adj_slot;
-    T* ckpt = a.ckpt + slot * a.ckpt_slot;
+    SK_LDS real* ylds = (SK_LDS real*)mylds;
+    SK_LDS real* glds = ylds + (size_t)a.q * a.DS;              // gradient accumulators for dy (YLDS)
+    SK_LDS real* ring = (SK_LDS real*)(mylds + a.ring_off);
+    real* rows = a.rows + slot * a.rows_slot;
+    real* adj = a.adj + slot * a.adj_slot;
+    real* ckpt = a.ckpt + slot * a.ckpt_slot;
     const int S = a.S;
     SW sw(a, lane);
 
     for (long pid = slot; pid < a.npairs; pid += nslots) {
-        const long xi = a.gramM ? pid / a.gramM : pid;
-        const long yi = a.gramM ? pid % a.gramM : pid;
-        sw.dxrow = a.dxT + xi * a.xstride;
-        sw.dyg = a.dyT + yi * a.ystride;
+        long xi, yi;
+        pair_ids(a, pid, xi, yi);
+        sw.dxp = a.dx + xi * a.xstride;
+        sw.dyg = a.dy + yi * a.ystride;
         sw.dyl = ylds;
-        T* gdx = a.gdxT + xi * a.xstride;
-        T* gdy = a.gdyT + yi * a.ystride;
-        if (a.y_lds) {
-            const int n = a.DP * a.qpad;
-            for (int t = lane; t < n; t += kWave) { ylds[t] = sw.dyg[t]; glds[t] = T(0); }
+        real* gdx = a.gdx + xi * a.xstride;
+        real* gdy = a.gdy + yi * a.ystride;
+        if constexpr (YLDS) {
+            const int n = a.q * a.DS;
+            for (int t = lane; t < n; t += kWave) { ylds[t] = sw.dyg[t]; glds[t] = 0.0; }
         }
-        const T gk = a.grad_k[pid];
+        const real gk = a.grad_k[pid];
 
         // ---- phase 1: forward, boundary rows of every strip and a checkpoint every S macro-steps ----
         for (int s = 0; s < a.ns; ++s) {
-            sw.begin_strip(s, rows);
+            sw.begin_strip(s, rows, true);
             const int NT = sw.strip_steps();
-            sw.prime(0);
-            for (int T0 = 0; T0 < NT; T0 += S) {
-                T* cp = ckpt + ((long)(s * a.nseg + T0 / S) * NVC) * kWave + lane;
+            real topn[C];
+            sw.load_top(0, sw.topc);
+            for (int Tc = 0; Tc < NT; Tc += kWave) {
+                if (Tc > 0) {
 #pragma unroll
-                for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
+                    for (int cc = 0; cc < C; ++cc) sw.topc[cc] = topn[cc];
+                }
+                sw.load_top(Tc + kWave, topn);
+                const int Te = Tc + kWave < NT ? Tc + kWave : NT;
+                for (int T0 = Tc; T0 < Te; T0 += S) {
+                    real* cp = ckpt + ((long)(s * a.nseg + T0 / S) * NVC) * kWave + lane;
 #pragma unroll
-                for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
-                const int T1 = T0 + S < NT ? T0 + S : NT;
-                for (int Tstep = T0; Tstep < T1; ++Tstep) {
-                    T e[R + 1][C + 1];
-                    T p;
-                    T yv[DN];
-                    sw.template forward_step<true>(Tstep, e, p, yv);
+                    for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
+#pragma unroll
+                    for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
+                    sw.forward_run(T0, T0 + S < Te ? T0 + S : Te, NoHook());
                 }
             }
             if (s == a.ns - 1 && lane == sw.lb && a.k_out) a.k_out[pid] = sw.bot[C - 1];
@@ -469,33 +461,33 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
 
         // ---- phase 2: strips bottom-up, segments right-to-left ----
         for (int s = a.ns - 1; s >= 0; --s) {
-            sw.begin_strip(s, rows);
+            sw.begin_strip(s, rows, false);
             const int NT = sw.strip_steps();
             const int lb = sw.lb;
             const bool has_below = s < a.ns - 1;   // then lb == 63
-            const T* adjr = adj + (long)((s + 1) & 1) * a.rowlen;   // written by the strip below
-            T* adjw = adj + (long)(s & 1) * a.rowlen;
+            const real* adjr = adj + (long)((s + 1) & 1) * a.rowlen;   // written by the strip below
+            real* adjw = adj + (long)(s & 1) * a.rowlen;
             // adjoint lane state
-            T accL[R + 1];
-            T up[C];
-            T corner = T(0);
-            // bottom edge feed of lane 63 (adjoint messages of the strip below): lane q of adjc holds
-            // the entry of block column (column of lane 63 at the current step) - (63 - q); it rotates
-            // by one lane per step and is refilled every 64 steps from adjn, loaded one chunk ahead.
-            T adjc[C], adjn[C];
+            real accL[R + 1];
+            real up[C];
+            real corner = 0.0;
+            // Bottom edge feed of lane 63 (adjoint messages of the strip below): lane q of adjc holds the
+            // entry of block column (column of lane 63 at the current step) - (63 - q); it shifts up by
+            // one lane per step and is refilled every 64 steps from adjn, loaded one chunk ahead.
+            real adjc[C], adjn[C];
             int adj_end = 0;
-            T gacc[DN];
+            real gacc[DN];
 #pragma unroll
-            for (int i = 0; i <= R; ++i) accL[i] = T(0);
+            for (int i = 0; i <= R; ++i) accL[i] = 0.0;
 #pragma unroll
-            for (int i = 0; i < C; ++i) { up[i] = T(0); adjc[i] = T(0); adjn[i] = T(0); }
+            for (int i = 0; i < C; ++i) up[i] = 0.0;
 #pragma unroll
-            for (int i = 0; i < DN; ++i) gacc[i] = T(0);
-            auto load_adj = [&](int Jb, T (&dst)[C]) {
+            for (int i = 0; i < DN; ++i) gacc[i] = 0.0;
+            auto load_adj = [&](int Jb, real (&dst)[C]) {
                 const int Jq = Jb - (kWave - 1 - lane);
+                const bool ok = has_below && Jq >= 0 && Jq < a.nb;
 #pragma unroll
-                for (int cc = 0; cc < C; ++cc)
-                    dst[cc] = (has_below && Jq >= 0 && Jq < a.nb) ? ld_scratch(adjr + (long)Jq * C + 1 + cc) : T(0);
+                for (int cc = 0; cc < C; ++cc) dst[cc] = ok ? ld_scratch(adjr + (long)Jq * C + 1 + cc) : 0.0;
             };
             {
                 const int Jb0 = NT - 1 - lb;   // block column of lane lb at the first reverse step
@@ -505,103 +497,103 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
             }
 
             const int nsegs = (NT + S - 1) / S;
+            // checkpoint and top feed of a segment are loaded one segment ahead
+            real cpn[NVC], topn[C];
+            auto load_segment = [&](int g) {
+                const real* cp = ckpt + ((long)(s * a.nseg + g) * NVC) * kWave + lane;
+#pragma unroll
+                for (int i = 0; i < NVC; ++i) cpn[i] = ld_scratch(cp + i * kWave);
+                sw.load_top(g * S, topn);
+            };
+            load_segment(nsegs - 1);
             for (int g = nsegs - 1; g >= 0; --g) {
                 const int T0 = g * S;
                 const int T1 = T0 + S < NT ? T0 + S : NT;
                 // restore the forward lane state at T0 and replay the segment into the ring
-                {
-                    const T* cp = ckpt + ((long)(s * a.nseg + g) * NVC) * kWave + lane;
 #pragma unroll
-                    for (int i = 0; i <= R; ++i) sw.left[i] = ld_scratch(cp + i * kWave);
+                for (int i = 0; i <= R; ++i) sw.left[i] = cpn[i];
 #pragma unroll
-                    for (int i = 0; i < C; ++i) sw.bot[i] = ld_scratch(cp + (R + 1 + i) * kWave);
-                    sw.prime(T0);
-                }
-                for (int Tstep = T0; Tstep < T1; ++Tstep) {
-                    T e[R + 1][C + 1];
-                    T p;
-                    T yv[DN];
-                    // keep the block input edges (forward_step leaves e[0][*] and e[*][0] untouched)
-                    const bool act = sw.template forward_step<false>(Tstep, e, p, yv);
+                for (int i = 0; i < C; ++i) { sw.bot[i] = cpn[R + 1 + i]; sw.topc[i] = topn[i]; }
+                if (g > 0) load_segment(g - 1);
+                sw.forward_run(T0, T1, [&](int Tstep, bool act, real (&e)[R + 1][C + 1]) {
                     if (act) {
-                        SK_LDS T* rp = ring + ((Tstep - T0) * NVR) * kWave + lane;
+                        // keep the block input edges (the step leaves e[0][*] and e[*][0] untouched)
+                        SK_LDS real* rp = ring + ((Tstep - T0) * NVR) * kWave + lane;
 #pragma unroll
                         for (int cc = 0; cc <= C; ++cc) rp[cc * kWave] = e[0][cc];
 #pragma unroll
                         for (int rr = 1; rr <= R; ++rr) rp[(C + rr) * kWave] = e[rr][0];
                     }
-                }
+                });
+
                 // walk the segment backwards; ring entries and y increments are fetched one step ahead
-                T ein[NVR], ynx[DN];
-                {
-                    const SK_LDS T* rp = ring + ((T1 - 1 - T0) * NVR) * kWave + lane;
+                auto fetch_ring = [&](int Tstep, real (&ein)[NVR]) {
+                    const SK_LDS real* rp = ring + ((Tstep - T0) * NVR) * kWave + lane;
 #pragma unroll
                     for (int v = 0; v < NVR; ++v) ein[v] = rp[v * kWave];
-                    sw.fetch_y(T1 - 1 - lane, ynx);
-                }
-                for (int Tstep = T1 - 1; Tstep >= T0; --Tstep) {
+                };
+                auto reverse_step = [&](int Tstep, const real (&ein)[NVR], const real (&yv)[DN], real (&einn)[NVR],
+                                        real (&yvn)[DN]) {
                     if (Tstep == adj_end) {
 #pragma unroll
                         for (int cc = 0; cc < C; ++cc) adjc[cc] = adjn[cc];
                         load_adj(Tstep - lb - kWave, adjn);
                         adj_end = Tstep - kWave;
                     }
-                    T recv[C];
+                    real recv[C];
 #pragma unroll
                     for (int cc = 0; cc < C; ++cc) {
+                        const real anext = wave_shift_up(adjc[cc]);
                         recv[cc] = wave_from_below_or(up[cc], adjc[cc]);
-                        adjc[cc] = wave_from_above(adjc[cc]);
+                        adjc[cc] = anext;
                     }
                     const int J = Tstep - lane;
-                    T e[R + 1][C + 1];
-                    T yv[DN];
-#pragma unroll
-                    for (int cc = 0; cc <= C; ++cc) e[0][cc] = ein[cc];
-#pragma unroll
-                    for (int rr = 1; rr <= R; ++rr) e[rr][0] = ein[C + rr];
-#pragma unroll
-                    for (int c = 0; c < DN; ++c) yv[c] = ynx[c];
-                    if (Tstep > T0) {
-                        const SK_LDS T* rp = ring + ((Tstep - 1 - T0) * NVR) * kWave + lane;
-#pragma unroll
-                        for (int v = 0; v < NVR; ++v) ein[v] = rp[v * kWave];
-                        sw.fetch_y(J - 1, ynx);
+                    if constexpr (LOOKAHEAD) {
+                        if (Tstep > T0) {
+                            fetch_ring(Tstep - 1, einn);
+                            sw.fetch_y(J - 1, yvn);
+                        }
                     }
                     const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
                         // forward values of the block: edges from the ring, interior by Eq. (1)
+                        real e[R + 1][C + 1];
+#pragma unroll
+                        for (int cc = 0; cc <= C; ++cc) e[0][cc] = ein[cc];
+#pragma unroll
+                        for (int rr = 1; rr <= R; ++rr) e[rr][0] = ein[C + rr];
                         const int b = J >> a.rs2;
-                        const T p = sw.inner(b, yv);
+                        const real p = sw.inner(b, yv);
                         SW::block_forward(e, p);
-                        const T q2 = p * p;
-                        const T Bc = fmaT(q2, T(-1.0 / 12.0), T(1));
-                        const T Ac = fmaT(p, T(0.5), fmaT(q2, T(1.0 / 12.0), T(1)));
-                        const T dA = fmaT(p, T(1.0 / 6.0), T(0.5));   // A'(p)
-                        const T dB = p * T(1.0 / 6.0);                // -B'(p)
+                        const real q2 = p * p;
+                        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+                        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                        const real dA = fma(p, 1.0 / 6.0, 0.5);   // A'(p)
+                        const real dB = p * (1.0 / 6.0);          // -B'(p)
                         // adjoints of the block's nodes (first relation of Section 3.4, scatter form)
-                        T gn[R + 1][C + 1];
+                        real gn[R + 1][C + 1];
 #pragma unroll
                         for (int rr = 0; rr <= R; ++rr)
 #pragma unroll
-                            for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = T(0);
+                            for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = 0.0;
 #pragma unroll
                         for (int rr = 1; rr <= R; ++rr) gn[rr][C] = accL[rr];
 #pragma unroll
                         for (int cc = 0; cc < C; ++cc) gn[R][cc + 1] += recv[cc];
                         gn[0][C] = corner;
                         if (s == a.ns - 1 && lane == lb && J == a.nb - 1) gn[R][C] = gk;
-                        T accP = T(0);
+                        real accP = 0.0;
 #pragma unroll
                         for (int rr = R - 1; rr >= 0; --rr)
 #pragma unroll
                             for (int cc = C - 1; cc >= 0; --cc) {
-                                const T go = gn[rr + 1][cc + 1];
-                                gn[rr + 1][cc] = fmaT(go, Ac, gn[rr + 1][cc]);
-                                gn[rr][cc + 1] = fmaT(go, Ac, gn[rr][cc + 1]);
-                                gn[rr][cc] = fmaT(-go, Bc, gn[rr][cc]);
+                                const real go = gn[rr + 1][cc + 1];
+                                gn[rr + 1][cc] = fma(go, Ac, gn[rr + 1][cc]);
+                                gn[rr][cc + 1] = fma(go, Ac, gn[rr][cc + 1]);
+                                gn[rr][cc] = fma(-go, Bc, gn[rr][cc]);
                                 // second relation of Section 3.4: dF/dp of this cell
-                                const T loc = fmaT(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
-                                accP = fmaT(go, loc, accP);
+                                const real loc = fma(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
+                                accP = fma(go, loc, accP);
                             }
 #pragma unroll
                         for (int cc = 0; cc < C; ++cc) up[cc] = gn[0][cc + 1];
@@ -609,51 +601,71 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
 #pragma unroll
                         for (int rr = 1; rr <= R; ++rr) accL[rr] = gn[rr][0];
                         if (lane == 0 && s > 0) {
+                            real* wp = adjw + (J * C + 1);
 #pragma unroll
-                            for (int cc = 0; cc < C; ++cc) adjw[(long)J * C + 1 + cc] = up[cc];
+                            for (int cc = 0; cc < C; ++cc) wp[cc] = up[cc];
                         }
                         // map to the increments (the linear transformation of Section 3.4)
                         if constexpr (D > 0) {
 #pragma unroll
-                            for (int c = 0; c < D; ++c) gacc[c] = fmaT(accP, yv[c], gacc[c]);
+                            for (int c = 0; c < D; ++c) gacc[c] = fma(accP, yv[c], gacc[c]);
                             if (a.want_gy) {
-                                if (a.y_lds) {
+                                if constexpr (YLDS) {
+                                    SK_LDS real* gp = glds + b * SW::DSc;
 #pragma unroll
-                                    for (int c = 0; c < D; ++c) lds_atomic_add(&glds[c * a.qpad + b], accP * sw.dxr[c]);
+                                    for (int c = 0; c < D; ++c) lds_atomic_add(gp + c, accP * sw.dxr[c]);
                                 } else {
+                                    real* gp = gdy + (long)b * SW::DSc;
 #pragma unroll
-                                    for (int c = 0; c < D; ++c)
-                                        unsafeAtomicAdd(&gdy[(long)c * a.qpad + b], accP * sw.dxr[c]);
+                                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gp + c, accP * sw.dxr[c]);
                                 }
                             }
                         } else {
-                            const T ap = accP * a.sc;
+                            const real ap = accP * a.sc;
+                            const real* xp = sw.dxp + (long)sw.arow * a.DS;
+                            const real* yp = sw.dyg + (long)b * a.DS;
                             for (int c = 0; c < a.d; ++c) {
-                                if (a.want_gx)
-                                    unsafeAtomicAdd(&gdx[(long)c * a.rpad + sw.arow], ap * sw.load_y(c, b));
-                                if (a.want_gy) {
-                                    const T val = ap * sw.dxrow[(long)c * a.rpad + sw.arow];
-                                    if (a.y_lds) lds_atomic_add(&glds[c * a.qpad + b], val);
-                                    else unsafeAtomicAdd(&gdy[(long)c * a.qpad + b], val);
-                                }
+                                if (a.want_gx) unsafeAtomicAdd(&gdx[(long)sw.arow * a.DS + c], ap * yp[c]);
+                                if (a.want_gy) unsafeAtomicAdd(&gdy[(long)b * a.DS + c], ap * xp[c]);
                             }
                         }
+                    }
+                };
+                if constexpr (LOOKAHEAD) {
+                    real ea[NVR], eb[NVR], ya[DN], yb[DN];
+                    fetch_ring(T1 - 1, ea);
+                    sw.fetch_y(T1 - 1 - lane, ya);
+                    int Tstep = T1 - 1;
+                    for (; Tstep - 1 >= T0; Tstep -= 2) {
+                        reverse_step(Tstep, ea, ya, eb, yb);
+                        reverse_step(Tstep - 1, eb, yb, ea, ya);
+                    }
+                    if (Tstep >= T0) reverse_step(Tstep, ea, ya, eb, yb);
+                } else {
+                    for (int Tstep = T1 - 1; Tstep >= T0; --Tstep) {
+                        real ea[NVR], ya[DN];
+                        fetch_ring(Tstep, ea);
+                        sw.fetch_y(Tstep - lane, ya);
+                        reverse_step(Tstep, ea, ya, ea, ya);
                     }
                 }
             }
             if constexpr (D > 0) {
                 if (a.want_gx && sw.rowvalid()) {
+                    real* gp = gdx + (long)sw.arow * SW::DSc;
 #pragma unroll
-                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(&gdx[(long)c * a.rpad + sw.arow], gacc[c] * a.sc);
+                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gp + c, gacc[c] * a.sc);
                 }
             }
             scratch_fence();
         }
-        if (a.y_lds && a.want_gy) {
-            const int n = a.DP * a.qpad;
-            for (int t = lane; t < n; t += kWave) {
-                const T v = glds[t];
-                if (v != T(0)) unsafeAtomicAdd(&gdy[t], v);
+        if constexpr (YLDS) {
+            if (a.want_gy) {
+                const int n = a.q * a.DS;
+                for (int t = lane; t < n; t += kWave) {
+                    const real v = glds[t];
+                    if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+                }
             }
         }
     }
@@ -683,78 +695,88 @@ hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st)
 }
 
 template <typename T>
-hipError_t launch_increments(const T* x, double* out, long npaths, int L, int d, int DP, int rpad, hipStream_t st)
+hipError_t launch_increments(const T* x, real* out, long npaths, int L, int d, int DS, int rows, hipStream_t st)
 {
-    long total = npaths * (long)DP * rpad;
+    long total = npaths * (long)DS * rows;
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(increments_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, x, out, npaths, L, d, DP,
-                       rpad);
+    hipLaunchKernelGGL(increments_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, x, out, npaths, L, d, DS,
+                       rows);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_finalize(const double* g, T* grad, long npaths, int L, int d, int DP, int rpad, hipStream_t st)
+hipError_t launch_finalize(const real* g, T* grad, long npaths, int L, int d, int DS, int rows, hipStream_t st)
 {
     long total = npaths * (long)L * d;
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(finalize_grad_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, g, grad, npaths, L, d, DP,
-                       rpad);
+    hipLaunchKernelGGL(finalize_grad_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, g, grad, npaths, L, d, DS,
+                       rows);
     return hipGetLastError();
 }
 
-template <typename T, int BL, int D>
-hipError_t launch_sweep_one(bool backward, const SweepArgs<T>& a, int grid, size_t lds, hipStream_t st)
+template <int BL, int D, bool YLDS>
+hipError_t launch_sweep_one(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     hipError_t e;
     if (backward) {
         static bool attr_done = false;
         if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwd_kernel<T, BL, D>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwd_kernel<BL, D, YLDS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        hipLaunchKernelGGL((sweep_bwd_kernel<T, BL, D>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+        hipLaunchKernelGGL((sweep_bwd_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     } else {
         static bool attr_done = false;
         if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_fwd_kernel<T, BL, D>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_fwd_kernel<BL, D, YLDS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        hipLaunchKernelGGL((sweep_fwd_kernel<T, BL, D>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+        hipLaunchKernelGGL((sweep_fwd_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     }
     return hipGetLastError();
 }
 
-template <typename T, int BL>
-hipError_t launch_sweep_bl(bool backward, int DT, const SweepArgs<T>& a, int grid, size_t lds, hipStream_t st)
+template <int BL, int D>
+hipError_t launch_sweep_y(bool backward, bool ylds, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if constexpr (D > 0) {
+        if (ylds) return launch_sweep_one<BL, D, true>(backward, a, grid, lds, st);
+    }
+    return launch_sweep_one<BL, D, false>(backward, a, grid, lds, st);
+}
+
+template <int BL>
+hipError_t launch_sweep_bl(bool backward, int DT, bool ylds, const SweepArgs& a, int grid, size_t lds,
+                           hipStream_t st)
 {
     switch (DT) {
-        case 0: return launch_sweep_one<T, BL, 0>(backward, a, grid, lds, st);
-        case 2: return launch_sweep_one<T, BL, 2>(backward, a, grid, lds, st);
-        case 3: return launch_sweep_one<T, BL, 3>(backward, a, grid, lds, st);
-        case 4: return launch_sweep_one<T, BL, 4>(backward, a, grid, lds, st);
-        case 5: return launch_sweep_one<T, BL, 5>(backward, a, grid, lds, st);
-        case 6: return launch_sweep_one<T, BL, 6>(backward, a, grid, lds, st);
-        case 8: return launch_sweep_one<T, BL, 8>(backward, a, grid, lds, st);
-        case 16: return launch_sweep_one<T, BL, 16>(backward, a, grid, lds, st);
+        case 0: return launch_sweep_y<BL, 0>(backward, ylds, a, grid, lds, st);
+        case 2: return launch_sweep_y<BL, 2>(backward, ylds, a, grid, lds, st);
+        case 3: return launch_sweep_y<BL, 3>(backward, ylds, a, grid, lds, st);
+        case 4: return launch_sweep_y<BL, 4>(backward, ylds, a, grid, lds, st);
+        case 5: return launch_sweep_y<BL, 5>(backward, ylds, a, grid, lds, st);
+        case 6: return launch_sweep_y<BL, 6>(backward, ylds, a, grid, lds, st);
+        case 8: return launch_sweep_y<BL, 8>(backward, ylds, a, grid, lds, st);
+        case 16: return launch_sweep_y<BL, 16>(backward, ylds, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }
 
-template <typename T>
-hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs<T>& a, int grid, size_t lds, hipStream_t st)
+hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
+    const bool ylds = a.y_lds != 0;
     switch (BL) {
-        case 0: return launch_sweep_bl<T, 0>(backward, DT, a, grid, lds, st);
-        case 1: return launch_sweep_bl<T, 1>(backward, DT, a, grid, lds, st);
-        case 2: return launch_sweep_bl<T, 2>(backward, DT, a, grid, lds, st);
+        case 0: return launch_sweep_bl<0>(backward, DT, ylds, a, grid, lds, st);
+        case 1: return launch_sweep_bl<1>(backward, DT, ylds, a, grid, lds, st);
+        case 2: return launch_sweep_bl<2>(backward, DT, ylds, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -763,10 +785,9 @@ template hipError_t launch_fill<float>(float*, long, float, hipStream_t);
 template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
 template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);
 template hipError_t launch_convert<double, float>(const double*, float*, long, hipStream_t);
-template hipError_t launch_increments<float>(const float*, double*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_increments<double>(const double*, double*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_finalize<float>(const double*, float*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_finalize<double>(const double*, double*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_sweep<double>(bool, int, int, const SweepArgs<double>&, int, size_t, hipStream_t);
+template hipError_t launch_increments<float>(const float*, real*, long, int, int, int, int, hipStream_t);
+template hipError_t launch_increments<double>(const double*, real*, long, int, int, int, int, hipStream_t);
+template hipError_t launch_finalize<float>(const real*, float*, long, int, int, int, int, hipStream_t);
+template hipError_t launch_finalize<double>(const real*, double*, long, int, int, int, int, hipStream_t);
 
 }  // namespace sk

@@ -40,7 +40,7 @@ struct Plan {
     int ns = 0;                 // strips per pair
     int rowlen = 0;             // elements of one boundary row (node columns, padded)
     int DT = 0;                 // kernel template channel count (0 = runtime loop over d)
-    int DP = 0;                 // channels stored per path in the transposed increment buffers
+    int DP = 0;                 // channels stored per increment row (d padded to the kernel's count)
     int S = 0, nseg = 0;        // backward: macro-steps per replay segment, segments per strip
     int y_lds = 0;              // y increments (and their gradient accumulators) staged in LDS
     size_t lds_wave = 0, lds_bytes = 0, ring_off = 0;
@@ -79,14 +79,14 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     p.qpad = (int)align_up((size_t)p.q, 64);
     p.DT = 0;
     for (int t : kTemplD) if (d <= t) { p.DT = t; break; }
-    p.DP = p.DT ? p.DT : (int)d;
+    p.DP = p.DT ? (p.DT | 1) : (int)d;   // odd row stride: LDS bank spread (see Sweep::DSc)
     p.xstride = (int64_t)p.DP * p.rpad;
     p.ystride = (int64_t)p.DP * p.qpad;
 
     // LDS per wave: y increments (+ their gradient accumulators when going backward) and the replay ring.
     const int NVR = R + C + 1;   // block input edges kept per macro-step in the ring
     size_t ybytes = (size_t)p.DP * p.qpad * elem * (backward ? 2 : 1);
-    p.y_lds = ybytes <= 20 * 1024 ? 1 : 0;
+    p.y_lds = (p.DT != 0 && ybytes <= 20 * 1024) ? 1 : 0;
     size_t used = p.y_lds ? ybytes : 0;
     p.ring_off = used;
     if (backward) {
