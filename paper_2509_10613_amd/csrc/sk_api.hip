@@ -102,6 +102,12 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.y_lds = p.y_lds;
     a.lds_wave = (unsigned)p.lds_wave;
     a.ring_off = (unsigned)p.ring_off;
+    a.coop = p.coop; a.nw = p.nw; a.RB = p.RB; a.CH = p.CH;
+    a.coop_off_gdy = (unsigned)p.coop_off_gdy; a.coop_off_flags = (unsigned)p.coop_off_flags;
+    a.coop_off_obox = (unsigned)p.coop_off_obox; a.coop_off_ring = (unsigned)p.coop_off_ring;
+    a.coop_ring_stride = (unsigned)p.coop_ring_stride;
+    a.err = reinterpret_cast<int*>(base + p.off_err);
+    if (p.coop) SK_CHECK(launch_fill<float>(reinterpret_cast<float*>(a.err), 1, 0.0f, st));
     if (backward) {
         a.gdx = reinterpret_cast<double*>(base + p.off_gdxT);
         a.gdy = reinterpret_cast<double*>(base + p.off_gdyT);

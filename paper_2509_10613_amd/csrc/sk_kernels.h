@@ -38,6 +38,12 @@ struct SweepArgs {
     int y_lds;
     unsigned lds_wave;   // LDS bytes per wave
     unsigned ring_off;   // byte offset of the replay ring inside a wave's LDS
+    // cooperative mode (one workgroup per pair, strips pipelined over its nw waves)
+    int coop;
+    int nw;              // waves per workgroup
+    int RB, CH;          // outbox ring length and hand-over chunk, in block columns (powers of two)
+    unsigned coop_off_gdy, coop_off_flags, coop_off_obox, coop_off_ring, coop_ring_stride;   // LDS bytes
+    int* err;            // device int, set to 1 if a bounded wait between waves ran out
 };
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);

@@ -268,15 +268,23 @@ struct Sweep {
 
     // One forward macro-step: consumes ycur (the y increments of this lane's block at this step) and
     // fetches those of the next step into ynext.  Returns whether this lane processed a block.
+    // EDGE = false: the top edge of lane 0 comes from the shifting register topc.
+    // EDGE = true : it is given in edge[] (same value in every lane), and the bottom edge of lane lbo is
+    //               also written to the outbox ring obox (cooperative mode).
+    template <bool EDGE>
     __device__ __forceinline__ bool forward_step(int Tstep, const real (&ycur)[DN], real (&ynext)[DN],
-                                                 real (&e)[R + 1][C + 1])
+                                                 real (&e)[R + 1][C + 1], const real (&edge)[C])
     {
         real recv[C];
 #pragma unroll
         for (int cc = 0; cc < C; ++cc) {
-            const real tnext = wave_shift_down(topc[cc]);
-            recv[cc] = wave_from_above_or(bot[cc], topc[cc]);
-            topc[cc] = tnext;
+            if constexpr (EDGE) {
+                recv[cc] = wave_from_above_or(bot[cc], edge[cc]);
+            } else {
+                const real tnext = wave_shift_down(topc[cc]);
+                recv[cc] = wave_from_above_or(bot[cc], topc[cc]);
+                topc[cc] = tnext;
+            }
         }
         const int J = Tstep - lane;
         fetch_y(J + 1, ynext);
@@ -298,6 +306,13 @@ struct Sweep {
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) wp[cc] = bot[cc];
             }
+            if constexpr (EDGE) {
+                if (lane == lbo) {
+                    SK_LDS real* op = obox + (J & rbmask) * C;
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) op[cc] = bot[cc];
+                }
+            }
         }
         return active;
     }
@@ -310,24 +325,162 @@ struct Sweep {
     __device__ __forceinline__ void forward_run(int T0, int T1, F&& f)
     {
         real ya[DN], yb[DN];
+        real none[C];
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) none[cc] = 0.0;
         fetch_y(T0 - lane, ya);
         int Tstep = T0;
         for (; Tstep + 2 <= T1; Tstep += 2) {
             {
                 real e[R + 1][C + 1];
-                const bool act = forward_step(Tstep, ya, yb, e);
+                const bool act = forward_step<false>(Tstep, ya, yb, e, none);
                 f(Tstep, act, e);
             }
             {
                 real e[R + 1][C + 1];
-                const bool act = forward_step(Tstep + 1, yb, ya, e);
+                const bool act = forward_step<false>(Tstep + 1, yb, ya, e, none);
                 f(Tstep + 1, act, e);
             }
         }
         if (Tstep < T1) {
             real e[R + 1][C + 1];
-            const bool act = forward_step(Tstep, ya, yb, e);
+            const bool act = forward_step<false>(Tstep, ya, yb, e, none);
             f(Tstep, act, e);
+        }
+    }
+
+    // ---- cooperative mode: the strips of one pair run on different waves of one workgroup and hand
+    // their boundary rows over through small rings in LDS ----
+    SK_LDS real* obox = nullptr;         // this wave's outbox ring: (rbmask + 1) columns x C values
+    const SK_LDS real* ibox = nullptr;   // outbox of the wave that runs the upstream strip (or all ones)
+    int rbmask = 0;
+    int lbo = -1;                        // lane that writes the outbox (-1: nobody)
+
+    __device__ __forceinline__ void read_edge(int col, real (&dst)[C]) const
+    {
+        int cidx = col < a.nb ? col : a.nb - 1;
+        const SK_LDS real* ip = ibox + (cidx & rbmask) * C;
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) dst[cc] = ip[cc];
+    }
+
+    // Steps [T0, T1) with the top edge of lane 0 read from ibox one step ahead; edge holds the values
+    // for step T0 on entry and those for step T1 on exit.
+    template <class F>
+    __device__ __forceinline__ void forward_run_coop(int T0, int T1, real (&edge)[C], F&& f)
+    {
+        real ya[DN], yb[DN], eb[C];
+        fetch_y(T0 - lane, ya);
+        int Tstep = T0;
+        for (; Tstep + 2 <= T1; Tstep += 2) {
+            {
+                real e[R + 1][C + 1];
+                read_edge(Tstep + 1, eb);
+                const bool act = forward_step<true>(Tstep, ya, yb, e, edge);
+                f(Tstep, act, e);
+            }
+            {
+                real e[R + 1][C + 1];
+                read_edge(Tstep + 2, edge);
+                const bool act = forward_step<true>(Tstep + 1, yb, ya, e, eb);
+                f(Tstep + 1, act, e);
+            }
+        }
+        if (Tstep < T1) {
+            real e[R + 1][C + 1];
+            read_edge(Tstep + 1, eb);
+            const bool act = forward_step<true>(Tstep, ya, yb, e, edge);
+            f(Tstep, act, e);
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) edge[cc] = eb[cc];
+        }
+    }
+
+    // Adjoints of one block (first relation of Section 3.4 in scatter form) and its dF/dp (second
+    // relation).  ein: block input edges of the forward values; recv: adjoint messages from the block
+    // row below; accL / corner / up: adjoint state carried to the left neighbour block and upwards.
+    __device__ __forceinline__ real reverse_block(const real (&ein)[NVR], real p, const real (&recv)[C], bool seed,
+                                                  real gk, real (&accL)[R + 1], real& corner, real (&up)[C]) const
+    {
+        real e[R + 1][C + 1];
+#pragma unroll
+        for (int cc = 0; cc <= C; ++cc) e[0][cc] = ein[cc];
+#pragma unroll
+        for (int rr = 1; rr <= R; ++rr) e[rr][0] = ein[C + rr];
+        block_forward(e, p);
+        const real q2 = p * p;
+        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+        const real dA = fma(p, 1.0 / 6.0, 0.5);   // A'(p)
+        const real dB = p * (1.0 / 6.0);          // -B'(p)
+        real gn[R + 1][C + 1];
+#pragma unroll
+        for (int rr = 0; rr <= R; ++rr)
+#pragma unroll
+            for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = 0.0;
+#pragma unroll
+        for (int rr = 1; rr <= R; ++rr) gn[rr][C] = accL[rr];
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) gn[R][cc + 1] += recv[cc];
+        gn[0][C] = corner;
+        if (seed) gn[R][C] = gk;
+        real accP = 0.0;
+#pragma unroll
+        for (int rr = R - 1; rr >= 0; --rr)
+#pragma unroll
+            for (int cc = C - 1; cc >= 0; --cc) {
+                const real go = gn[rr + 1][cc + 1];
+                gn[rr + 1][cc] = fma(go, Ac, gn[rr + 1][cc]);
+                gn[rr][cc + 1] = fma(go, Ac, gn[rr][cc + 1]);
+                gn[rr][cc] = fma(-go, Bc, gn[rr][cc]);
+                const real loc = fma(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
+                accP = fma(go, loc, accP);
+            }
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) up[cc] = gn[0][cc + 1];
+        corner = gn[0][0];
+#pragma unroll
+        for (int rr = 1; rr <= R; ++rr) accL[rr] = gn[rr][0];
+        return accP;
+    }
+
+    // The linear map of Section 3.4 for one block: accP = sum of dF/dp over the block's cells.
+    __device__ __forceinline__ void accumulate_grads(real accP, int b, const real (&yv)[DN], real (&gacc)[DN],
+                                                     SK_LDS real* glds, real* gdx, real* gdy) const
+    {
+        if constexpr (D > 0) {
+#pragma unroll
+            for (int c = 0; c < D; ++c) gacc[c] = fma(accP, yv[c], gacc[c]);
+            if (a.want_gy) {
+                if constexpr (YLDS) {
+                    SK_LDS real* gp = glds + b * DSc;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) lds_atomic_add(gp + c, accP * dxr[c]);
+                } else {
+                    real* gp = gdy + (long)b * DSc;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gp + c, accP * dxr[c]);
+                }
+            }
+        } else {
+            const real ap = accP * a.sc;
+            const real* xp = dxp + (long)arow * a.DS;
+            const real* yp = dyg + (long)b * a.DS;
+            for (int c = 0; c < a.d; ++c) {
+                if (a.want_gx) unsafeAtomicAdd(&gdx[(long)arow * a.DS + c], ap * yp[c]);
+                if (a.want_gy) unsafeAtomicAdd(&gdy[(long)b * a.DS + c], ap * xp[c]);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void flush_gdx(const real (&gacc)[DN], real* gdx) const
+    {
+        if constexpr (D > 0) {
+            if (a.want_gx && rowvalid()) {
+                real* gp = gdx + (long)arow * DSc;
+#pragma unroll
+                for (int c = 0; c < D; ++c) unsafeAtomicAdd(gp + c, gacc[c] * a.sc);
+            }
         }
     }
 };
@@ -556,79 +709,16 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                     }
                     const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
-                        // forward values of the block: edges from the ring, interior by Eq. (1)
-                        real e[R + 1][C + 1];
-#pragma unroll
-                        for (int cc = 0; cc <= C; ++cc) e[0][cc] = ein[cc];
-#pragma unroll
-                        for (int rr = 1; rr <= R; ++rr) e[rr][0] = ein[C + rr];
                         const int b = J >> a.rs2;
                         const real p = sw.inner(b, yv);
-                        SW::block_forward(e, p);
-                        const real q2 = p * p;
-                        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
-                        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                        const real dA = fma(p, 1.0 / 6.0, 0.5);   // A'(p)
-                        const real dB = p * (1.0 / 6.0);          // -B'(p)
-                        // adjoints of the block's nodes (first relation of Section 3.4, scatter form)
-                        real gn[R + 1][C + 1];
-#pragma unroll
-                        for (int rr = 0; rr <= R; ++rr)
-#pragma unroll
-                            for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = 0.0;
-#pragma unroll
-                        for (int rr = 1; rr <= R; ++rr) gn[rr][C] = accL[rr];
-#pragma unroll
-                        for (int cc = 0; cc < C; ++cc) gn[R][cc + 1] += recv[cc];
-                        gn[0][C] = corner;
-                        if (s == a.ns - 1 && lane == lb && J == a.nb - 1) gn[R][C] = gk;
-                        real accP = 0.0;
-#pragma unroll
-                        for (int rr = R - 1; rr >= 0; --rr)
-#pragma unroll
-                            for (int cc = C - 1; cc >= 0; --cc) {
-                                const real go = gn[rr + 1][cc + 1];
-                                gn[rr + 1][cc] = fma(go, Ac, gn[rr + 1][cc]);
-                                gn[rr][cc + 1] = fma(go, Ac, gn[rr][cc + 1]);
-                                gn[rr][cc] = fma(-go, Bc, gn[rr][cc]);
-                                // second relation of Section 3.4: dF/dp of this cell
-                                const real loc = fma(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
-                                accP = fma(go, loc, accP);
-                            }
-#pragma unroll
-                        for (int cc = 0; cc < C; ++cc) up[cc] = gn[0][cc + 1];
-                        corner = gn[0][0];
-#pragma unroll
-                        for (int rr = 1; rr <= R; ++rr) accL[rr] = gn[rr][0];
+                        const bool seed = s == a.ns - 1 && lane == lb && J == a.nb - 1;
+                        const real accP = sw.reverse_block(ein, p, recv, seed, gk, accL, corner, up);
                         if (lane == 0 && s > 0) {
                             real* wp = adjw + (J * C + 1);
 #pragma unroll
                             for (int cc = 0; cc < C; ++cc) wp[cc] = up[cc];
                         }
-                        // map to the increments (the linear transformation of Section 3.4)
-                        if constexpr (D > 0) {
-#pragma unroll
-                            for (int c = 0; c < D; ++c) gacc[c] = fma(accP, yv[c], gacc[c]);
-                            if (a.want_gy) {
-                                if constexpr (YLDS) {
-                                    SK_LDS real* gp = glds + b * SW::DSc;
-#pragma unroll
-                                    for (int c = 0; c < D; ++c) lds_atomic_add(gp + c, accP * sw.dxr[c]);
-                                } else {
-                                    real* gp = gdy + (long)b * SW::DSc;
-#pragma unroll
-                                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gp + c, accP * sw.dxr[c]);
-                                }
-                            }
-                        } else {
-                            const real ap = accP * a.sc;
-                            const real* xp = sw.dxp + (long)sw.arow * a.DS;
-                            const real* yp = sw.dyg + (long)b * a.DS;
-                            for (int c = 0; c < a.d; ++c) {
-                                if (a.want_gx) unsafeAtomicAdd(&gdx[(long)sw.arow * a.DS + c], ap * yp[c]);
-                                if (a.want_gy) unsafeAtomicAdd(&gdy[(long)b * a.DS + c], ap * xp[c]);
-                            }
-                        }
+                        sw.accumulate_grads(accP, b, yv, gacc, glds, gdx, gdy);
                     }
                 };
                 if constexpr (LOOKAHEAD) {
@@ -650,13 +740,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                     }
                 }
             }
-            if constexpr (D > 0) {
-                if (a.want_gx && sw.rowvalid()) {
-                    real* gp = gdx + (long)sw.arow * SW::DSc;
-#pragma unroll
-                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gp + c, gacc[c] * a.sc);
-                }
-            }
+            sw.flush_gdx(gacc, gdx);
             scratch_fence();
         }
         if constexpr (YLDS) {
@@ -664,6 +748,472 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                 const int n = a.q * a.DS;
                 for (int t = lane; t < n; t += kWave) {
                     const real v = glds[t];
+                    if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// cooperative kernels: one workgroup per pair, the strips of the pair pipelined over its waves
+// ------------------------------------------------------------------------------------------------
+// The strips of a pair are processed in rounds of nw consecutive strips, one per wave, separated by
+// workgroup barriers.  Inside a round wave w hands the row below its last block row to wave w + 1
+// through an outbox ring in LDS; two monotonic flags per wave carry the progress: prod = block columns
+// written to the own outbox, cons = block columns read from the upstream outbox.  Wave w only ever
+// waits for wave w - 1 (data) and wave w + 1 (ring space), both of which run concurrently and never wait
+// for a later round, so the waits cannot form a cycle; every wait is bounded all the same and raises an
+// error flag instead of spinning for ever.  The first wave of a round takes its top row from the global
+// boundary row that the last wave of the previous round wrote (staged through a small private ring so
+// that the step code is the same), or all ones in the very first round.
+struct Link {
+    SK_LDS int* prod_me;
+    SK_LDS int* cons_me;
+    const SK_LDS int* prod_up;
+    const SK_LDS int* cons_dn;
+    bool has_up, has_dn;
+    int nb, RB, lane;
+    int* err;
+    bool* dead;   // set once a wait of this wave has run out: later waits return at once
+
+    __device__ __forceinline__ void setup(int w, bool up, bool dn, SK_LDS int* prod, SK_LDS int* cons, int nb_,
+                                          int RB_, int lane_, int* err_, bool* dead_)
+    {
+        nb = nb_; RB = RB_; lane = lane_; err = err_; dead = dead_;
+        has_up = up;
+        has_dn = dn;
+        prod_me = prod + w;
+        cons_me = cons + w;
+        prod_up = prod + (w > 0 ? w - 1 : 0);
+        cons_dn = cons + w + 1;
+    }
+    __device__ __forceinline__ void spin_until(const SK_LDS int* f, int need) const
+    {
+        if (*dead) return;
+        for (int it = 0; it < (1 << 22); ++it) {
+            const int v = __hip_atomic_load(f, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (v >= need) return;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        *dead = true;
+        if (lane == 0) atomicExch(err, 1);   // give up: the results are invalid but the kernel ends
+    }
+    __device__ __forceinline__ void wait_cols(int count) const
+    {
+        if (has_up) spin_until(prod_up, count < nb ? count : nb);
+    }
+    __device__ __forceinline__ void consumed(int count) const
+    {
+        if (has_up)
+            __hip_atomic_store(cons_me, count < nb ? count : nb, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    // before writing outbox columns below `upto`: the ring slots they reuse must have been read
+    __device__ __forceinline__ void reserve(int upto) const
+    {
+        if (!has_dn) return;
+        const int need = (upto < nb ? upto : nb) - RB;
+        if (need > 0) spin_until(cons_dn, need);
+    }
+    __device__ __forceinline__ void publish(int count) const
+    {
+        if (has_dn && count > 0)
+            __hip_atomic_store(prod_me, count < nb ? count : nb, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+};
+
+template <int BL, bool BWD> struct CoopCfg {
+    // waves per workgroup the kernel is compiled for: 8 (two per SIMD) unless the backward kernel's
+    // register need at the largest block size asks for a whole SIMD's register file per wave
+    static constexpr int kMaxWaves = (BWD && BL == 2) ? 4 : 8;
+};
+
+struct CoopLds {
+    SK_LDS real* y;
+    SK_LDS real* gy;
+    SK_LDS int* prod;
+    SK_LDS int* cons;
+    SK_LDS real* ones;
+    SK_LDS real* zeros;
+    SK_LDS real* stage;  // this wave's private staging ring (global boundary row -> LDS)
+    SK_LDS real* obox;   // this wave's outbox
+    SK_LDS real* oboxes;
+    SK_LDS real* ring;   // this wave's replay ring
+};
+
+__device__ __forceinline__ CoopLds carve_coop_lds(unsigned char* smem, const SweepArgs& a, int w, int Cc)
+{
+    CoopLds l;
+    const int rs = a.RB * Cc;
+    l.y = (SK_LDS real*)smem;
+    l.gy = (SK_LDS real*)(smem + a.coop_off_gdy);
+    l.prod = (SK_LDS int*)(smem + a.coop_off_flags);
+    l.cons = l.prod + 32;
+    l.ones = (SK_LDS real*)(smem + a.coop_off_obox);
+    l.zeros = l.ones + rs;
+    l.oboxes = l.zeros + rs;
+    l.obox = l.oboxes + w * rs;
+    l.stage = l.oboxes + (a.nw + w) * rs;
+    l.ring = (SK_LDS real*)(smem + a.coop_off_ring + (size_t)w * a.coop_ring_stride);
+    return l;
+}
+
+// Staging of a global boundary row into a private LDS ring, CH block columns per chunk, loaded one chunk
+// ahead: lets the first wave of a round read its edge values exactly like the other waves do.
+// src(J, cc) gives the global address of value cc of ring column J, or nullptr past the end.
+template <int C>
+struct Stager {
+    real pre[C];
+    SK_LDS real* ring;
+    int rbmask, CH, lane;
+
+    template <class Src>
+    __device__ __forceinline__ void load(int col0, Src&& src)
+    {
+        const int J = col0 + lane;
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) {
+            const real* g = lane < CH ? src(J, cc) : nullptr;
+            pre[cc] = g ? ld_scratch(g) : 0.0;
+        }
+    }
+    __device__ __forceinline__ void store(int col0)
+    {
+        if (lane < CH) {
+            SK_LDS real* rp = ring + ((col0 + lane) & rbmask) * C;
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) rp[cc] = pre[cc];
+        }
+    }
+    // columns [0, 2 CH) into the ring, [2 CH, 3 CH) into registers
+    template <class Src>
+    __device__ __forceinline__ void prime(Src&& src)
+    {
+        load(0, src);
+        store(0);
+        load(CH, src);
+        store(CH);
+        load(2 * CH, src);
+    }
+    // at the start of the chunk beginning at column Tc > 0
+    template <class Src>
+    __device__ __forceinline__ void advance(int Tc, Src&& src)
+    {
+        store(Tc + CH);
+        load(Tc + 2 * CH, src);
+    }
+};
+
+template <int BL, int D, bool YLDS>
+__global__ __launch_bounds__((CoopCfg<BL, false>::kMaxWaves) * 64) void sweep_fwd_coop_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using SW = Sweep<BL, D, YLDS>;
+    constexpr int C = SW::C;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int nw = a.nw;
+    CoopLds l = carve_coop_lds(smem, a, w, C);
+    real* rows = a.rows + (long)blockIdx.x * a.rows_slot;
+    SW sw(a, lane);
+    sw.rbmask = a.RB - 1;
+    const int CH = a.CH;
+    bool dead = false;
+
+    for (int t = threadIdx.x; t < a.RB * C; t += blockDim.x) { l.ones[t] = 1.0; l.zeros[t] = 0.0; }
+    for (long pid = blockIdx.x; pid < a.npairs; pid += gridDim.x) {
+        long xi, yi;
+        pair_ids(a, pid, xi, yi);
+        sw.dxp = a.dx + xi * a.xstride;
+        sw.dyg = a.dy + yi * a.ystride;
+        sw.dyl = l.y;
+        __syncthreads();   // the previous pair is done with y
+        if constexpr (YLDS) {
+            const int n = a.q * a.DS;
+            for (int t = threadIdx.x; t < n; t += blockDim.x) l.y[t] = sw.dyg[t];
+        }
+        for (int s0 = 0; s0 < a.ns; s0 += nw) {
+            if (s0 > 0) scratch_fence();   // boundary row of the previous round
+            __syncthreads();
+            if (threadIdx.x < 64) l.prod[threadIdx.x] = 0;
+            __syncthreads();
+            const int s = s0 + w;
+            if (s >= a.ns) continue;
+            const bool last = s == a.ns - 1;
+            // the last wave of a round leaves its bottom row in global memory for the next round
+            sw.begin_strip(s, rows, !last && w == nw - 1);
+            Link lk;
+            lk.setup(w, w > 0, !last && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
+            sw.obox = l.obox;
+            sw.lbo = lk.has_dn ? sw.lb : -1;
+            const bool staged = w == 0 && s > 0;
+            sw.ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C : (staged ? l.stage : l.ones);
+            Stager<C> stg;
+            stg.ring = l.stage; stg.rbmask = sw.rbmask; stg.CH = CH; stg.lane = lane;
+            auto src = [&](int J, int cc) -> const real* {
+                return J < a.nb ? sw.rowprev + (long)J * C + 1 + cc : nullptr;
+            };
+            if (staged) stg.prime(src);
+            const int NT = sw.strip_steps();
+            real edge[C];
+            lk.wait_cols(CH + 1);
+            sw.read_edge(0, edge);
+            for (int Tc = 0; Tc < NT; Tc += CH) {
+                const int Te = Tc + CH < NT ? Tc + CH : NT;
+                if (Tc > 0) {
+                    if (Tc < a.nb) {
+                        lk.consumed(Tc);
+                        lk.wait_cols(Tc + CH + 1);
+                        if (staged) stg.advance(Tc, src);
+                    }
+                    lk.publish(Tc - sw.lb);
+                }
+                lk.reserve(Tc - sw.lb + CH);
+                sw.forward_run_coop(Tc, Te, edge, NoHook());
+            }
+            lk.publish(a.nb);
+            lk.consumed(a.nb);
+            if (last && lane == sw.lb) a.k_out[pid] = *(volatile int*)a.err ? __builtin_nan("") : sw.bot[C - 1];
+        }
+    }
+}
+
+template <int BL, int D, bool YLDS>
+__global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd_coop_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using SW = Sweep<BL, D, YLDS>;
+    constexpr int R = SW::R, C = SW::C, NVR = SW::NVR, NVC = SW::NVC, DN = SW::DN;
+    constexpr bool LOOKAHEAD = BL < 2;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int nw = a.nw;
+    CoopLds l = carve_coop_lds(smem, a, w, C);
+    real* rows = a.rows + (long)blockIdx.x * a.rows_slot;
+    real* adj = a.adj + (long)blockIdx.x * a.adj_slot;
+    real* ckpt = a.ckpt + (long)blockIdx.x * a.ckpt_slot;
+    const int S = a.S;
+    const int CH = a.CH < S ? a.CH : S;   // checkpoints fall on chunk starts
+    SW sw(a, lane);
+    sw.rbmask = a.RB - 1;
+    bool dead = false;
+
+    for (int t = threadIdx.x; t < a.RB * C; t += blockDim.x) { l.ones[t] = 1.0; l.zeros[t] = 0.0; }
+    for (long pid = blockIdx.x; pid < a.npairs; pid += gridDim.x) {
+        long xi, yi;
+        pair_ids(a, pid, xi, yi);
+        sw.dxp = a.dx + xi * a.xstride;
+        sw.dyg = a.dy + yi * a.ystride;
+        sw.dyl = l.y;
+        real* gdx = a.gdx + xi * a.xstride;
+        real* gdy = a.gdy + yi * a.ystride;
+        __syncthreads();
+        if constexpr (YLDS) {
+            const int n = a.q * a.DS;
+            for (int t = threadIdx.x; t < n; t += blockDim.x) { l.y[t] = sw.dyg[t]; l.gy[t] = 0.0; }
+        }
+        const real gk = a.grad_k[pid];
+
+        // ---- phase 1: forward in rounds; boundary rows of every strip and checkpoints to global ----
+        for (int s0 = 0; s0 < a.ns; s0 += nw) {
+            if (s0 > 0) scratch_fence();
+            __syncthreads();
+            if (threadIdx.x < 64) l.prod[threadIdx.x] = 0;
+            __syncthreads();
+            const int s = s0 + w;
+            if (s >= a.ns) continue;
+            const bool last = s == a.ns - 1;
+            sw.begin_strip(s, rows, true);
+            Link lk;
+            lk.setup(w, w > 0, !last && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
+            sw.obox = l.obox;
+            sw.lbo = lk.has_dn ? sw.lb : -1;
+            const bool staged = w == 0 && s > 0;
+            sw.ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C : (staged ? l.stage : l.ones);
+            Stager<C> stg;
+            stg.ring = l.stage; stg.rbmask = sw.rbmask; stg.CH = CH; stg.lane = lane;
+            auto src = [&](int J, int cc) -> const real* {
+                return J < a.nb ? sw.rowprev + (long)J * C + 1 + cc : nullptr;
+            };
+            if (staged) stg.prime(src);
+            const int NT = sw.strip_steps();
+            real edge[C];
+            lk.wait_cols(CH + 1);
+            sw.read_edge(0, edge);
+            for (int Tc = 0; Tc < NT; Tc += CH) {
+                const int Te = Tc + CH < NT ? Tc + CH : NT;
+                if (Tc > 0) {
+                    if (Tc < a.nb) {
+                        lk.consumed(Tc);
+                        lk.wait_cols(Tc + CH + 1);
+                        if (staged) stg.advance(Tc, src);
+                    }
+                    lk.publish(Tc - sw.lb);
+                }
+                lk.reserve(Tc - sw.lb + CH);
+                if (Tc % S == 0) {
+                    real* cp = ckpt + ((long)(s * a.nseg + Tc / S) * NVC) * kWave + lane;
+#pragma unroll
+                    for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
+#pragma unroll
+                    for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
+                }
+                sw.forward_run_coop(Tc, Te, edge, NoHook());
+            }
+            lk.publish(a.nb);
+            lk.consumed(a.nb);
+            if (last && lane == sw.lb && a.k_out) a.k_out[pid] = sw.bot[C - 1];
+        }
+
+        // ---- phase 2: strips bottom-up in rounds (processing index i = ns - 1 - s) ----
+        for (int i0 = 0; i0 < a.ns; i0 += nw) {
+            scratch_fence();   // phase 1 output, or the adjoint boundary row of the previous round
+            __syncthreads();
+            if (threadIdx.x < 64) l.prod[threadIdx.x] = 0;
+            __syncthreads();
+            const int i = i0 + w;
+            if (i >= a.ns) continue;
+            const int s = a.ns - 1 - i;
+            sw.begin_strip(s, rows, false);
+            Link lk;
+            lk.setup(w, w > 0, s > 0 && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
+            SK_LDS real* obox = l.obox;
+            const int NT = sw.strip_steps();
+            const int lb = sw.lb;
+            const int lane_out = lk.has_dn ? 0 : -1;                   // lane 0 -> outbox of this wave
+            const int lane_outg = (s > 0 && w == nw - 1) ? 0 : -1;     // lane 0 -> global row for the next round
+            const bool staged = w == 0 && i > 0;
+            sw.ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C : (staged ? l.stage : l.zeros);
+            // adjoint boundary rows in global memory, indexed by reverse column (nb - 1 - J)
+            const real* adjr = adj + (long)(((i0 / nw) + 1) & 1) * a.rowlen;
+            real* adjw = adj + (long)((i0 / nw) & 1) * a.rowlen;
+            Stager<C> stg;
+            stg.ring = l.stage; stg.rbmask = sw.rbmask; stg.CH = CH; stg.lane = lane;
+            auto src = [&](int c, int cc) -> const real* { return c < a.nb ? adjr + (long)c * C + cc : nullptr; };
+            if (staged) stg.prime(src);
+            real accL[R + 1];
+            real up[C];
+            real corner = 0.0;
+            real gacc[DN];
+#pragma unroll
+            for (int k = 0; k <= R; ++k) accL[k] = 0.0;
+#pragma unroll
+            for (int k = 0; k < C; ++k) up[k] = 0.0;
+#pragma unroll
+            for (int k = 0; k < DN; ++k) gacc[k] = 0.0;
+
+            const int nsegs = (NT + S - 1) / S;
+            real cpn[NVC], topn[C];
+            auto load_segment = [&](int g) {
+                const real* cp = ckpt + ((long)(s * a.nseg + g) * NVC) * kWave + lane;
+#pragma unroll
+                for (int k = 0; k < NVC; ++k) cpn[k] = ld_scratch(cp + k * kWave);
+                sw.load_top(g * S, topn);
+            };
+            load_segment(nsegs - 1);
+            real edge[C];   // adjoint messages for lane 63 at the coming reverse step
+            lk.wait_cols(CH + 1);
+            sw.read_edge(0, edge);
+            for (int g = nsegs - 1; g >= 0; --g) {
+                const int T0 = g * S;
+                const int T1 = T0 + S < NT ? T0 + S : NT;
+#pragma unroll
+                for (int k = 0; k <= R; ++k) sw.left[k] = cpn[k];
+#pragma unroll
+                for (int k = 0; k < C; ++k) { sw.bot[k] = cpn[R + 1 + k]; sw.topc[k] = topn[k]; }
+                if (g > 0) load_segment(g - 1);
+                sw.forward_run(T0, T1, [&](int Tstep, bool act, real (&e)[R + 1][C + 1]) {
+                    if (act) {
+                        SK_LDS real* rp = l.ring + ((Tstep - T0) * NVR) * kWave + lane;
+#pragma unroll
+                        for (int cc = 0; cc <= C; ++cc) rp[cc * kWave] = e[0][cc];
+#pragma unroll
+                        for (int rr = 1; rr <= R; ++rr) rp[(C + rr) * kWave] = e[rr][0];
+                    }
+                });
+                auto fetch_ring = [&](int Tstep, real (&ein)[NVR]) {
+                    const SK_LDS real* rp = l.ring + ((Tstep - T0) * NVR) * kWave + lane;
+#pragma unroll
+                    for (int v = 0; v < NVR; ++v) ein[v] = rp[v * kWave];
+                };
+                // reverse time t = NT - 1 - Tstep: lane lb needs reverse column t, lane 0 writes t - lb
+                auto reverse_step = [&](int Tstep, const real (&ein)[NVR], const real (&yv)[DN], real (&einn)[NVR],
+                                        real (&yvn)[DN]) {
+                    const int t = NT - 1 - Tstep;
+                    if ((t & (CH - 1)) == 0) {
+                        if (t > 0) {
+                            if (t < a.nb) {
+                                lk.consumed(t);
+                                lk.wait_cols(t + CH + 1);
+                                if (staged) stg.advance(t, src);
+                            }
+                            lk.publish(t - lb);
+                        }
+                        lk.reserve(t - lb + CH);
+                    }
+                    real recv[C];
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_below_or(up[cc], edge[cc]);
+                    sw.read_edge(t + 1, edge);   // for the next reverse step
+                    const int J = Tstep - lane;
+                    if constexpr (LOOKAHEAD) {
+                        if (Tstep > T0) {
+                            fetch_ring(Tstep - 1, einn);
+                            sw.fetch_y(J - 1, yvn);
+                        }
+                    }
+                    const bool active = (unsigned)J < (unsigned)sw.nbl;
+                    if (active) {
+                        const int b = J >> a.rs2;
+                        const real p = sw.inner(b, yv);
+                        const bool seed = s == a.ns - 1 && lane == lb && J == a.nb - 1;
+                        const real accP = sw.reverse_block(ein, p, recv, seed, gk, accL, corner, up);
+                        if (lane == lane_out) {
+                            SK_LDS real* op = obox + ((a.nb - 1 - J) & sw.rbmask) * C;
+#pragma unroll
+                            for (int cc = 0; cc < C; ++cc) op[cc] = up[cc];
+                        }
+                        if (lane == lane_outg) {
+                            real* wp = adjw + (long)(a.nb - 1 - J) * C;
+#pragma unroll
+                            for (int cc = 0; cc < C; ++cc) wp[cc] = up[cc];
+                        }
+                        sw.accumulate_grads(accP, b, yv, gacc, l.gy, gdx, gdy);
+                    }
+                };
+                if constexpr (LOOKAHEAD) {
+                    real ea[NVR], eb[NVR], ya[DN], yb[DN];
+                    fetch_ring(T1 - 1, ea);
+                    sw.fetch_y(T1 - 1 - lane, ya);
+                    int Tstep = T1 - 1;
+                    for (; Tstep - 1 >= T0; Tstep -= 2) {
+                        reverse_step(Tstep, ea, ya, eb, yb);
+                        reverse_step(Tstep - 1, eb, yb, ea, ya);
+                    }
+                    if (Tstep >= T0) reverse_step(Tstep, ea, ya, eb, yb);
+                } else {
+                    for (int Tstep = T1 - 1; Tstep >= T0; --Tstep) {
+                        real ea[NVR], ya[DN];
+                        fetch_ring(Tstep, ea);
+                        sw.fetch_y(Tstep - lane, ya);
+                        reverse_step(Tstep, ea, ya, ea, ya);
+                    }
+                }
+            }
+            lk.publish(a.nb);
+            lk.consumed(a.nb);
+            if (*(volatile int*)a.err) {
+#pragma unroll
+                for (int k = 0; k < DN; ++k) gacc[k] = __builtin_nan("");
+            }
+            sw.flush_gdx(gacc, gdx);
+        }
+        __syncthreads();
+        if constexpr (YLDS) {
+            if (a.want_gy) {
+                const int n = a.q * a.DS;
+                for (int t = threadIdx.x; t < n; t += blockDim.x) {
+                    const real v = l.gy[t];
                     if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
                 }
             }
@@ -719,9 +1269,38 @@ hipError_t launch_finalize(const real* g, T* grad, long npaths, int L, int d, in
 }
 
 template <int BL, int D, bool YLDS>
+hipError_t launch_sweep_coop(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    hipError_t e;
+    const int maxw = backward ? CoopCfg<BL, true>::kMaxWaves : CoopCfg<BL, false>::kMaxWaves;
+    if (a.nw < 1 || a.nw > maxw) return hipErrorInvalidValue;
+    if (backward) {
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwd_coop_kernel<BL, D, YLDS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((sweep_bwd_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
+    } else {
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_fwd_coop_kernel<BL, D, YLDS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((sweep_fwd_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <int BL, int D, bool YLDS>
 hipError_t launch_sweep_one(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     hipError_t e;
+    if (a.coop) return launch_sweep_coop<BL, D, YLDS>(backward, a, grid, lds, st);
     if (backward) {
         static bool attr_done = false;
         if (!attr_done) {

@@ -49,8 +49,14 @@ struct Plan {
     int64_t xstride = 0, ystride = 0, rows_slot = 0, ckpt_slot = 0, adj_slot = 0;
     size_t off_dxT = 0, off_dyT = 0, off_gdxT = 0, off_gdyT = 0, off_rows = 0, off_adj = 0, off_ckpt = 0;
     size_t off_kio = 0, off_gkio = 0;   // float callers: double staging of k and grad_k
+    size_t off_err = 0;                 // one int: a bounded wait between cooperating waves ran out
     size_t total = 0;
+    // cooperative mode: one workgroup per pair, its strips pipelined over nw waves
+    int coop = 0, nw = 0, RB = 0, CH = 0;
+    size_t coop_off_gdy = 0, coop_off_flags = 0, coop_off_obox = 0, coop_off_ring = 0, coop_ring_stride = 0;
 };
+
+constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
 inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
                       int64_t d, int lam1, int lam2, int io_elem)
@@ -83,29 +89,71 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     p.xstride = (int64_t)p.DP * p.rpad;
     p.ystride = (int64_t)p.DP * p.qpad;
 
-    // LDS per wave: y increments (+ their gradient accumulators when going backward) and the replay ring.
     const int NVR = R + C + 1;   // block input edges kept per macro-step in the ring
-    size_t ybytes = (size_t)p.DP * p.qpad * elem * (backward ? 2 : 1);
-    p.y_lds = (p.DT != 0 && ybytes <= 20 * 1024) ? 1 : 0;
-    size_t used = p.y_lds ? ybytes : 0;
-    p.ring_off = used;
-    if (backward) {
-        int S = 64;
-        while (S > 4 && used + (size_t)S * kWave * NVR * elem > kLdsPerWave) S >>= 1;
-        p.S = S;
-        p.nseg = (p.nb + kWave - 1 + S - 1) / S;   // strips run nb + (lanes-1) macro-steps at most
-        used += (size_t)S * kWave * NVR * elem;
-    }
-    p.lds_wave = align_up(used, 256);
-    p.lds_bytes = p.lds_wave * kWavesPerWG;
+    const size_t ring_step = (size_t)kWave * NVR * elem;
+    p.coop = (p.ns >= 2 && p.npairs <= kCoopMaxPairs) ? 1 : 0;
+    if (p.coop) {
+        // Workgroup-shared LDS: y (+ gradient accumulators), flags, ones/zeros/outbox rings; then one replay
+        // ring per wave.
+        const int maxw = (backward && p.BL == 2) ? 4 : 8;
+        p.nw = p.ns < maxw ? p.ns : maxw;
+        p.RB = 32;
+        p.CH = 8;
+        const size_t ycopy = (size_t)p.q * p.DP * elem;
+        const size_t fixed = 512 + (size_t)(2 * p.nw + 2) * p.RB * C * elem;
+        const size_t budget = kLdsPerCU - 1024;
+        const size_t ring_min = backward ? (size_t)p.nw * 4 * ring_step : 0;
+        const size_t yneed = ycopy * (backward ? 2 : 1);
+        p.y_lds = (p.DT != 0 && align_up(yneed, 256) + fixed + ring_min <= budget) ? 1 : 0;
+        size_t used = p.y_lds ? align_up(ycopy, 256) : 0;
+        p.coop_off_gdy = used;
+        if (p.y_lds && backward) used += align_up(ycopy, 256);
+        p.coop_off_flags = used;
+        used += 512;
+        p.coop_off_obox = used;   // ones, zeros, nw outboxes, nw staging rings
+        used += (size_t)(2 * p.nw + 2) * p.RB * C * elem;
+        used = align_up(used, 256);
+        p.coop_off_ring = used;
+        if (backward) {
+            int S = 64;
+            while (S > 4 && used + (size_t)p.nw * S * ring_step > budget) S >>= 1;
+            p.S = S;
+            p.nseg = (p.nb + kWave - 1 + S - 1) / S;
+            p.coop_ring_stride = (size_t)S * ring_step;
+            used += (size_t)p.nw * p.coop_ring_stride;
+        }
+        p.lds_wave = 0;
+        p.lds_bytes = align_up(used, 256);
+        int wg_per_cu = (int)(kLdsPerCU / p.lds_bytes);
+        if (wg_per_cu < 1) wg_per_cu = 1;
+        if (wg_per_cu * p.nw > 8) wg_per_cu = 8 / p.nw > 0 ? 8 / p.nw : 1;
+        int64_t cap = (int64_t)kNumCU * wg_per_cu;
+        p.grid = (int)(p.npairs < cap ? p.npairs : cap);
+        p.nslots = p.grid;
+    } else {
+        // LDS per wave: y increments (+ their gradient accumulators when going backward) and the replay ring.
+        size_t ybytes = (size_t)p.DP * p.qpad * elem * (backward ? 2 : 1);
+        p.y_lds = (p.DT != 0 && ybytes <= 20 * 1024) ? 1 : 0;
+        size_t used = p.y_lds ? ybytes : 0;
+        p.ring_off = used;
+        if (backward) {
+            int S = 64;
+            while (S > 4 && used + (size_t)S * ring_step > kLdsPerWave) S >>= 1;
+            p.S = S;
+            p.nseg = (p.nb + kWave - 1 + S - 1) / S;   // strips run nb + (lanes-1) macro-steps at most
+            used += (size_t)S * ring_step;
+        }
+        p.lds_wave = align_up(used, 256);
+        p.lds_bytes = p.lds_wave * kWavesPerWG;
 
-    int wg_per_cu = (int)(kLdsPerCU / (p.lds_bytes ? p.lds_bytes : 1));
-    if (wg_per_cu < 1) wg_per_cu = 1;
-    if (wg_per_cu > 2) wg_per_cu = 2;
-    int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
-    int64_t cap = (int64_t)kNumCU * wg_per_cu;
-    p.grid = (int)(want < cap ? want : cap);
-    p.nslots = (int64_t)p.grid * kWavesPerWG;
+        int wg_per_cu = (int)(kLdsPerCU / (p.lds_bytes ? p.lds_bytes : 1));
+        if (wg_per_cu < 1) wg_per_cu = 1;
+        if (wg_per_cu > 2) wg_per_cu = 2;
+        int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
+        int64_t cap = (int64_t)kNumCU * wg_per_cu;
+        p.grid = (int)(want < cap ? want : cap);
+        p.nslots = (int64_t)p.grid * kWavesPerWG;
+    }
 
     // Workspace layout (all offsets 256-byte aligned).
     size_t off = 0;
@@ -127,6 +175,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.off_kio = take((size_t)p.npairs * elem);
         if (backward) p.off_gkio = take((size_t)p.npairs * elem);
     }
+    p.off_err = take(256);
     p.total = off;
     p.valid = true;
     return p;
