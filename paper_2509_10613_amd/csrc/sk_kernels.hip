@@ -170,7 +170,9 @@ struct Sweep {
     // per strip
     int s = 0, lb = 0, arow = 0;
     int nbl = 0;                        // a.nb for lanes that own a block row, 0 otherwise
-    int lbw = -1;                       // lane that writes the strip's bottom row (-1: nobody)
+    int nbm1 = 0;                       // a.nb - 1
+    int lbw = -1;                       // lane that writes the strip's bottom row to global (-1: nobody)
+    int lbany = -1;                     // lb if the bottom row goes anywhere (global row or outbox)
     real dxr[DN];
     const real* rowprev = nullptr;
     real* rowcur = nullptr;
@@ -188,9 +190,12 @@ struct Sweep {
         s = s_;
         const int I = s * kWave + lane;
         nbl = I < a.mb ? a.nb : 0;
+        nbm1 = a.nb - 1;
         int rem = a.mb - s * kWave - 1;
         lb = rem < kWave - 1 ? rem : kWave - 1;
         lbw = write_row ? lb : -1;
+        lbany = lbw;
+        lbo = -1;
         int ar = I >> a.rs1;
         arow = ar < a.r ? ar : a.r - 1;
         if constexpr (D > 0) {
@@ -212,11 +217,10 @@ struct Sweep {
     __device__ __forceinline__ void fetch_y(int J, real (&yv)[DN]) const
     {
         if constexpr (D > 0) {
-            int Jc = J < 0 ? 0 : J;
-            Jc = Jc < a.nb ? Jc : a.nb - 1;
+            const int Jc = min(max(J, 0), nbm1);
             const int b = Jc >> a.rs2;
             if constexpr (YLDS) {
-                const SK_LDS real* yp = dyl + b * DSc;
+                const SK_LDS real* yp = dyl + __mul24(b, DSc);
 #pragma unroll
                 for (int c = 0; c < D; ++c) yv[c] = yp[c];
             } else {
@@ -301,16 +305,18 @@ struct Sweep {
             for (int rr = 0; rr <= R; ++rr) left[rr] = e[rr][C];
 #pragma unroll
             for (int cc = 0; cc < C; ++cc) bot[cc] = e[R][cc + 1];
-            if (lane == lbw) {
-                real* wp = rowcur + (J * C + 1);
+            if (lane == lbany) {   // the strip's last lane hands its bottom edge on
+                if (lbw >= 0) {
+                    real* wp = rowcur + (J * C + 1);
 #pragma unroll
-                for (int cc = 0; cc < C; ++cc) wp[cc] = bot[cc];
-            }
-            if constexpr (EDGE) {
-                if (lane == lbo) {
-                    SK_LDS real* op = obox + (J & rbmask) * C;
+                    for (int cc = 0; cc < C; ++cc) wp[cc] = bot[cc];
+                }
+                if constexpr (EDGE) {
+                    if (lbo >= 0) {
+                        SK_LDS real* op = obox + (J & rbmask) * C;
 #pragma unroll
-                    for (int cc = 0; cc < C; ++cc) op[cc] = bot[cc];
+                        for (int cc = 0; cc < C; ++cc) op[cc] = bot[cc];
+                    }
                 }
             }
         }
@@ -805,7 +811,7 @@ struct Link {
     }
     __device__ __forceinline__ void consumed(int count) const
     {
-        if (has_up)
+        if (has_up && RB < nb)
             __hip_atomic_store(cons_me, count < nb ? count : nb, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     // before writing outbox columns below `upto`: the ring slots they reuse must have been read
@@ -946,6 +952,7 @@ __global__ __launch_bounds__((CoopCfg<BL, false>::kMaxWaves) * 64) void sweep_fw
             lk.setup(w, w > 0, !last && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
             sw.obox = l.obox;
             sw.lbo = lk.has_dn ? sw.lb : -1;
+            if (sw.lbo >= 0) sw.lbany = sw.lb;
             const bool staged = w == 0 && s > 0;
             sw.ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C : (staged ? l.stage : l.ones);
             Stager<C> stg;
@@ -1028,6 +1035,7 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
             lk.setup(w, w > 0, !last && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
             sw.obox = l.obox;
             sw.lbo = lk.has_dn ? sw.lb : -1;
+            if (sw.lbo >= 0) sw.lbany = sw.lb;
             const bool staged = w == 0 && s > 0;
             sw.ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C : (staged ? l.stage : l.ones);
             Stager<C> stg;

@@ -97,7 +97,13 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         // ring per wave.
         const int maxw = (backward && p.BL == 2) ? 4 : 8;
         p.nw = p.ns < maxw ? p.ns : maxw;
+        // Outbox rings long enough for a whole row need no back-pressure; otherwise 32 columns.
         p.RB = 32;
+        {
+            int full = 32;
+            while (full < p.nb + 1) full <<= 1;
+            if ((size_t)(2 * p.nw + 2) * full * C * elem <= 40 * 1024) p.RB = full;
+        }
         p.CH = 8;
         const size_t ycopy = (size_t)p.q * p.DP * elem;
         const size_t fixed = 512 + (size_t)(2 * p.nw + 2) * p.RB * C * elem;
