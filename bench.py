@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--workload", default="c2", help="c2 (headline), or c1/c3/c4/c5 for the other configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy, so that a rocprofv3 --pmc run of this command "
+                         "holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (pairs are independent; see DESIGN.md for how the "
@@ -103,6 +106,13 @@ def main():
         if w.backward:
             bwd_call()
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -142,6 +152,14 @@ def main():
                 "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "avg_launch_ms": dom_ms,
                 "flops_per_launch": flops, "traffic": None}
     fwd_kernel_ms = fwd_ms / max(nf, 1)
+    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (if any)
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            tj = json.load(f)
+        ent = tj.get(w.name, {}).get(roofline["kernel"])
+        if ent is not None:
+            roofline["traffic"] = ent
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -151,7 +169,7 @@ def main():
         Xs, Ys = X[:nx], Y[:ny]
         sample_pairs = nx * ny if gram else nx
         reps, spent = 0, 0.0
-        while spent < args.cpu_seconds and reps < 50:
+        while spent < args.cpu_seconds and reps < 2000:
             a = time.perf_counter()
             if gram:
                 oracle.gram(Xs, Ys, None, lam, lam, flags)

@@ -69,10 +69,6 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         if (e != hipSuccess) return fail(SK_ERR_HIP, "%s: %s", #call, hipGetErrorString(e));   \
     } while (0)
 
-    SK_CHECK(launch_increments<T>(static_cast<const T*>(x), dxT, p.nx, p.L1, p.d, p.DP, p.rpad, st));
-    if (!p.symmetric)
-        SK_CHECK(launch_increments<T>(static_cast<const T*>(y), dyT, p.ny, p.L2, p.d, p.DP, p.qpad, st));
-
     SweepArgs a;
     std::memset(&a, 0, sizeof(a));
     a.dx = dxT; a.dy = dyT;
@@ -106,8 +102,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.coop_off_gdy = (unsigned)p.coop_off_gdy; a.coop_off_flags = (unsigned)p.coop_off_flags;
     a.coop_off_obox = (unsigned)p.coop_off_obox; a.coop_off_ring = (unsigned)p.coop_off_ring;
     a.coop_ring_stride = (unsigned)p.coop_ring_stride;
-    a.err = reinterpret_cast<int*>(base + p.off_err);
-    if (p.coop) SK_CHECK(launch_fill<float>(reinterpret_cast<float*>(a.err), 1, 0.0f, st));
+
     if (backward) {
         a.gdx = reinterpret_cast<double*>(base + p.off_gdxT);
         a.gdy = reinterpret_cast<double*>(base + p.off_gdyT);
@@ -117,9 +112,13 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.adj_slot = p.adj_slot;
         a.ckpt = reinterpret_cast<double*>(base + p.off_ckpt);
         a.ckpt_slot = p.ckpt_slot;
-        if (a.want_gx) SK_CHECK(launch_fill<double>(a.gdx, p.nx * p.xstride, 0.0, st));
-        if (a.want_gy && !p.symmetric) SK_CHECK(launch_fill<double>(a.gdy, p.ny * p.ystride, 0.0, st));
     }
+    a.err = reinterpret_cast<int*>(base + p.off_err);
+    // one preparation launch: increments of both sides, cleared gradient accumulators, cleared error flag
+    SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, p.L1,
+                               p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
+                               (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, p.L2, p.qpad, p.d,
+                               p.DP, a.err, st));
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -140,10 +139,9 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     }
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
     if (backward) {
-        if (grad_x)
-            SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.d, p.DP, p.rpad, st));
-        if (grad_y && !p.symmetric)
-            SK_CHECK(launch_finalize<T>(a.gdy, static_cast<T*>(grad_y), p.ny, p.L2, p.d, p.DP, p.qpad, st));
+        SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.rpad, a.gdy,
+                                    p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, p.L2, p.qpad, p.d, p.DP,
+                                    st));
     }
 #undef SK_CHECK
     return SK_OK;

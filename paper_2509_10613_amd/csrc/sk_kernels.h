@@ -48,10 +48,13 @@ struct SweepArgs {
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
 template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st);
+// dx/dy null = that side is not (re)computed (symmetric Gram); gdx/gdy null = no accumulator to clear.
 template <typename T>
-hipError_t launch_increments(const T* x, real* out, long npaths, int L, int d, int DS, int rows, hipStream_t st);
+hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
+                          long ny, int L2, int qpad, int d, int DS, int* err, hipStream_t st);
 template <typename T>
-hipError_t launch_finalize(const real* g, T* grad, long npaths, int L, int d, int DS, int rows, hipStream_t st);
+hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
+                           int L2, int qpad, int d, int DS, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 
 }  // namespace sk

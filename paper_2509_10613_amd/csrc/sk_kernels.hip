@@ -103,47 +103,68 @@ __global__ void fill_kernel(T* p, long n, T v)
     for (; i < n; i += st) p[i] = v;
 }
 
-// Increments, padded: out[path][a][c] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d; zero elsewhere
-// (first line of the paper's forward listing).  rows = padded row count, DS = padded channel count.
+// One set of paths for the preparation / finalisation kernels.
+template <typename T>
+struct PathSet {
+    const T* x;      // [npaths][L][d] caller's points
+    T* grad;         // [npaths][L][d] caller's gradient output (finalisation)
+    real* inc;       // [npaths][rows][DS] increments (preparation)
+    real* ginc;      // [npaths][rows][DS] gradient accumulators (zeroed by preparation, read by finalisation)
+    long npaths;
+    int L, rows;
+};
+
+// Preparation, one launch per call: increments of both path sets, padded with zeros
+// (inc[path][a][c] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d: first line of the paper's
+// forward listing), the gradient accumulators cleared, and the error flag cleared.
 template <typename TI>
-__global__ void increments_kernel(const TI* __restrict__ x, real* __restrict__ out, long npaths, int L, int d,
-                                  int DS, int rows)
+__global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, int* err)
 {
-    long total = npaths * (long)rows * DS;
+    const long nx = px.inc ? px.npaths * (long)px.rows * DS : 0;
+    const long ny = py.inc ? py.npaths * (long)py.rows * DS : 0;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    long st = (long)gridDim.x * blockDim.x;
-    for (; i < total; i += st) {
-        int c = (int)(i % DS);
-        long t = i / DS;
-        int a = (int)(t % rows);
-        long pth = t / rows;
+    const long st = (long)gridDim.x * blockDim.x;
+    if (i == 0 && err) *err = 0;
+    for (; i < nx + ny; i += st) {
+        const bool second = i >= nx;
+        const PathSet<TI>& p = second ? py : px;
+        const long j = second ? i - nx : i;
+        const int c = (int)(j % DS);
+        const long t = j / DS;
+        const int a = (int)(t % p.rows);
+        const long pth = t / p.rows;
         real v = 0.0;
-        if (a < L - 1 && c < d) {
-            const TI* xp = x + (pth * L + a) * (long)d + c;
+        if (a < p.L - 1 && c < d) {
+            const TI* xp = p.x + (pth * p.L + a) * (long)d + c;
             v = (real)xp[d] - (real)xp[0];
         }
-        out[i] = v;
+        p.inc[j] = v;
+        if (p.ginc) p.ginc[j] = 0.0;
     }
 }
 
-// grad[path][i][c] = g[path][i-1][c] - g[path][i][c] (out-of-range terms zero): the increments are
-// differences of consecutive points, so the gradient of a point collects the two increments it touches.
+// Finalisation, one launch per backward call: grad[path][i][c] = g[path][i-1][c] - g[path][i][c]
+// (out-of-range terms zero).  The increments are differences of consecutive points, so the gradient of
+// a point collects the two increments it touches.
 template <typename TO>
-__global__ void finalize_grad_kernel(const real* __restrict__ g, TO* __restrict__ grad, long npaths, int L, int d,
-                                     int DS, int rows)
+__global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS)
 {
-    long total = npaths * (long)L * d;
+    const long nx = px.grad ? px.npaths * (long)px.L * d : 0;
+    const long ny = py.grad ? py.npaths * (long)py.L * d : 0;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    long st = (long)gridDim.x * blockDim.x;
-    for (; i < total; i += st) {
-        int c = (int)(i % d);
-        long t = i / d;
-        int pt = (int)(t % L);
-        long pth = t / L;
-        const real* gp = g + (pth * rows) * (long)DS + c;
-        real hi = pt >= 1 ? gp[(long)(pt - 1) * DS] : 0.0;
-        real lo = pt < L - 1 ? gp[(long)pt * DS] : 0.0;
-        grad[i] = (TO)(hi - lo);
+    const long st = (long)gridDim.x * blockDim.x;
+    for (; i < nx + ny; i += st) {
+        const bool second = i >= nx;
+        const PathSet<TO>& p = second ? py : px;
+        const long j = second ? i - nx : i;
+        const int c = (int)(j % d);
+        const long t = j / d;
+        const int pt = (int)(t % p.L);
+        const long pth = t / p.L;
+        const real* gp = p.ginc + (pth * p.rows) * (long)DS + c;
+        const real hi = pt >= 1 ? gp[(long)(pt - 1) * DS] : 0.0;
+        const real lo = pt < p.L - 1 ? gp[(long)pt * DS] : 0.0;
+        p.grad[j] = (TO)(hi - lo);
     }
 }
 
@@ -1253,26 +1274,30 @@ hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st)
 }
 
 template <typename T>
-hipError_t launch_increments(const T* x, real* out, long npaths, int L, int d, int DS, int rows, hipStream_t st)
+hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
+                          long ny, int L2, int qpad, int d, int DS, int* err, hipStream_t st)
 {
-    long total = npaths * (long)DS * rows;
-    if (total <= 0) return hipSuccess;
+    PathSet<T> px{x, nullptr, dx, gdx, nx, L1, rpad};
+    PathSet<T> py{y, nullptr, dy, gdy, ny, L2, qpad};
+    long total = (dx ? nx * (long)rpad * DS : 0) + (dy ? ny * (long)qpad * DS : 0);
+    if (total <= 0) total = 1;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(increments_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, x, out, npaths, L, d, DS,
-                       rows);
+    hipLaunchKernelGGL(prepare_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_finalize(const real* g, T* grad, long npaths, int L, int d, int DS, int rows, hipStream_t st)
+hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
+                           int L2, int qpad, int d, int DS, hipStream_t st)
 {
-    long total = npaths * (long)L * d;
+    PathSet<T> px{nullptr, grad_x, nullptr, const_cast<real*>(gdx), nx, L1, rpad};
+    PathSet<T> py{nullptr, grad_y, nullptr, const_cast<real*>(gdy), ny, L2, qpad};
+    long total = (grad_x ? nx * (long)L1 * d : 0) + (grad_y ? ny * (long)L2 * d : 0);
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(finalize_grad_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, g, grad, npaths, L, d, DS,
-                       rows);
+    hipLaunchKernelGGL(finalize_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS);
     return hipGetLastError();
 }
 
@@ -1372,9 +1397,13 @@ template hipError_t launch_fill<float>(float*, long, float, hipStream_t);
 template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
 template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);
 template hipError_t launch_convert<double, float>(const double*, float*, long, hipStream_t);
-template hipError_t launch_increments<float>(const float*, real*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_increments<double>(const double*, real*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_finalize<float>(const real*, float*, long, int, int, int, int, hipStream_t);
-template hipError_t launch_finalize<double>(const real*, double*, long, int, int, int, int, hipStream_t);
+template hipError_t launch_prepare<float>(const float*, real*, real*, long, int, int, const float*, real*, real*, long,
+                                          int, int, int, int, int*, hipStream_t);
+template hipError_t launch_prepare<double>(const double*, real*, real*, long, int, int, const double*, real*, real*,
+                                           long, int, int, int, int, int*, hipStream_t);
+template hipError_t launch_finalize<float>(const real*, float*, long, int, int, const real*, float*, long, int, int, int,
+                                           int, hipStream_t);
+template hipError_t launch_finalize<double>(const real*, double*, long, int, int, const real*, double*, long, int, int,
+                                            int, int, hipStream_t);
 
 }  // namespace sk
