@@ -42,7 +42,10 @@ extern "C" {
 
 typedef enum { SK_F32 = 0, SK_F64 = 1 } sk_dtype;
 
-enum { SK_FLAG_TIME_AUG = 1 };
+enum {
+    SK_FLAG_TIME_AUG = 1,   /* append the channel t_i = i/(L-1) to both paths on the fly (Section 4) */
+    SK_FLAG_BWD_REPLAY = 2  /* backward: replay forward segments instead of inverting Eq. (1); see sigkernel_bwd */
+};
 
 enum {
     SK_OK = 0,
@@ -77,6 +80,11 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  * Signature Kernels"): given grad_k[B] = dF/dk[b], writes
  *   grad_x[B,L1,d] = dF/dx,  grad_y[B,L2,d] = dF/dy   (either may be NULL = not wanted)
  * and, if k_out != NULL, k_out[B] = k(x[b], y[b]) (the forward values are recomputed inside).
+ * By default the reverse sweep recovers the forward values it needs by inverting Eq. (1) between exact
+ * checkpoints eight block steps apart, and checks the recovered state against every checkpoint: if they
+ * differ by more than 1e-9 relative (increment inner products of order one make the inverse recurrence
+ * ill-conditioned), every gradient of the call is returned as NaN.  SK_FLAG_BWD_REPLAY selects the slower
+ * variant that replays forward segments and has no such limit.
  */
 int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
                   int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,

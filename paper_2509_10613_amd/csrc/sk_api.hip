@@ -35,7 +35,7 @@ std::vector<TimedLaunch> g_timed;
 int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
 {
     if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
-    if (flags & ~SK_FLAG_TIME_AUG) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
+    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
     if (lam1 < 0 || lam2 < 0 || lam1 > 20 || lam2 > 20)
         return fail(SK_ERR_DYADIC, "dyadic orders (%d, %d) outside 0..20", lam1, lam2);
     if (nx < 0 || ny < 0) return fail(SK_ERR_SHAPE, "negative batch size");
@@ -99,6 +99,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.lds_wave = (unsigned)p.lds_wave;
     a.ring_off = (unsigned)p.ring_off;
     a.coop = p.coop; a.nw = p.nw; a.RB = p.RB; a.CH = p.CH;
+    a.uncompute = p.uncompute;
     a.coop_off_gdy = (unsigned)p.coop_off_gdy; a.coop_off_flags = (unsigned)p.coop_off_flags;
     a.coop_off_obox = (unsigned)p.coop_off_obox; a.coop_off_ring = (unsigned)p.coop_off_ring;
     a.coop_ring_stride = (unsigned)p.coop_ring_stride;
@@ -141,7 +142,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     if (backward) {
         SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.rpad, a.gdy,
                                     p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, p.L2, p.qpad, p.d, p.DP,
-                                    st));
+                                    a.err, st));
     }
 #undef SK_CHECK
     return SK_OK;
@@ -199,7 +200,8 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     }
     rc = check_device();
     if (rc != SK_OK) return rc;
-    sk::Plan p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem);
+    sk::Plan p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
+                               !(flags & SK_FLAG_BWD_REPLAY));
     if (!p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0)
         return fail(SK_ERR_WORKSPACE, "workspace pointer is NULL or not 256-byte aligned");
@@ -223,7 +225,8 @@ size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, 
     const int64_t ny = gram ? M : B_or_N;
     if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
     // The symmetric Gram case needs no more than the general one, so the query does not distinguish them.
-    sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4);
+    sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+                               !(flags & SK_FLAG_BWD_REPLAY));
     return p.valid ? p.total : 0;
 }
 

@@ -43,7 +43,8 @@ struct SweepArgs {
     int nw;              // waves per workgroup
     int RB, CH;          // outbox ring length and hand-over chunk, in block columns (powers of two)
     unsigned coop_off_gdy, coop_off_flags, coop_off_obox, coop_off_ring, coop_ring_stride;   // LDS bytes
-    int* err;            // device int, set to 1 if a bounded wait between waves ran out
+    int uncompute;       // backward: recover forward values by inverting Eq. (1) instead of replaying segments
+    int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted
 };
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
@@ -54,7 +55,7 @@ hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int 
                           long ny, int L2, int qpad, int d, int DS, int* err, hipStream_t st);
 template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
-                           int L2, int qpad, int d, int DS, hipStream_t st);
+                           int L2, int qpad, int d, int DS, const int* err, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 
 }  // namespace sk

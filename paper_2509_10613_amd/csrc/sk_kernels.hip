@@ -20,6 +20,8 @@
 // All sweeps run in double precision (see sk_api.hip for why float callers are converted at the edges).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "sk_kernels.h"
 
 namespace sk {
@@ -64,6 +66,19 @@ __device__ __forceinline__ real wave_shift_up(real v)     // lane i receives lan
     return __hiloint2double(hi, lo);
 }
 
+// Lane i receives v of lane i+1, except the strip's last lane lb, which receives edge (its own lane's
+// value of that argument).  full = (lb == 63) is wave-uniform.
+template <bool FULL>
+__device__ __forceinline__ real recv_from_below(real v, real edge, bool is_lb)
+{
+    if constexpr (FULL) {
+        return wave_from_below_or(v, edge);
+    } else {
+        const real t = wave_shift_down(v);
+        return is_lb ? edge : t;
+    }
+}
+
 // Device-scope load that bypasses the per-CU vector cache: used for data this wave wrote to global
 // scratch earlier in the same kernel.
 __device__ __forceinline__ real ld_scratch(const real* p)
@@ -73,10 +88,13 @@ __device__ __forceinline__ real ld_scratch(const real* p)
     return __longlong_as_double((long long)u);
 }
 
+// Scratch written by a wave is only ever read back by waves of the same workgroup (same CU, hence the same
+// L2): it is enough that the stores have completed (they write through to L2) and that the reads bypass the
+// per-CU vector cache (ld_scratch).  An agent-scope fence would write back and invalidate the whole L2.
 __device__ __forceinline__ void scratch_fence()
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 __device__ __forceinline__ void lds_atomic_add(SK_LDS real* p, real v)
@@ -147,8 +165,9 @@ __global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, in
 // (out-of-range terms zero).  The increments are differences of consecutive points, so the gradient of
 // a point collects the two increments it touches.
 template <typename TO>
-__global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS)
+__global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS, const int* err)
 {
+    const bool bad = err != nullptr && *err != 0;   // a bounded wait ran out or the un-compute drifted
     const long nx = px.grad ? px.npaths * (long)px.L * d : 0;
     const long ny = py.grad ? py.npaths * (long)py.L * d : 0;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -164,7 +183,7 @@ __global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS)
         const real* gp = p.ginc + (pth * p.rows) * (long)DS + c;
         const real hi = pt >= 1 ? gp[(long)(pt - 1) * DS] : 0.0;
         const real lo = pt < p.L - 1 ? gp[(long)pt * DS] : 0.0;
-        p.grad[j] = (TO)(hi - lo);
+        p.grad[j] = bad ? (TO)__builtin_nan("") : (TO)(hi - lo);
     }
 }
 
@@ -180,7 +199,7 @@ struct Sweep {
     // one apart, spread over all LDS banks.
     static constexpr int DSc = D | 1;
     static constexpr int NVR = R + C + 1;   // ring: top edge (C+1) + left edge below the corner (R)
-    static constexpr int NVC = R + 1 + C;   // checkpoint: left edge (R+1) + own bottom edge (C)
+    static constexpr int NVC = R + C + 2;   // checkpoint: right edge (R+1), bottom edge (C), bottom-left corner
 
     const SweepArgs& a;
     const int lane;
@@ -200,6 +219,7 @@ struct Sweep {
     // forward lane state
     real left[R + 1];
     real bot[C];
+    real blc = 1.0;                     // bottom-left corner e[R][0] of the last processed block
     // Top edge feed of lane 0: lane q of topc holds the boundary-row values of block column
     // (column of lane 0 at the current step) + q; the register shifts down by one lane per step.
     real topc[C];
@@ -322,6 +342,7 @@ struct Sweep {
             for (int rr = 1; rr <= R; ++rr) e[rr][0] = left[rr];
             const real p = inner(J >> a.rs2, ycur);
             block_forward(e, p);
+            blc = e[R][0];
 #pragma unroll
             for (int rr = 0; rr <= R; ++rr) left[rr] = e[rr][C];
 #pragma unroll
@@ -345,6 +366,65 @@ struct Sweep {
     }
 
     __device__ __forceinline__ int strip_steps() const { return a.nb + lb; }
+
+    // Lane state after the last processed block: its right edge, bottom edge and bottom-left corner.
+    __device__ __forceinline__ void store_ckpt(real* cp) const
+    {
+#pragma unroll
+        for (int i = 0; i <= R; ++i) cp[i * kWave] = left[i];
+#pragma unroll
+        for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = bot[i];
+        cp[(R + 1 + C) * kWave] = blc;
+    }
+
+    // Inverse of Eq. (1) on one block: the right edge e[*][C] and the bottom edge e[R][*] are given, every
+    // other node follows from k[i,j] = ((k[i+1,j] + k[i,j+1]) A - k[i+1,j+1]) / B.
+    static __device__ __forceinline__ void block_uncompute(real (&e)[R + 1][C + 1], real Ac, real invB)
+    {
+#pragma unroll
+        for (int rr = R - 1; rr >= 0; --rr)
+#pragma unroll
+            for (int cc = C - 1; cc >= 0; --cc)
+                e[rr][cc] = fma(e[rr + 1][cc] + e[rr][cc + 1], Ac, -e[rr + 1][cc + 1]) * invB;
+    }
+
+    // Adjoints of one block whose forward values e are all known (first relation of Section 3.4 in scatter
+    // form) and its dF/dp (second relation).
+    __device__ __forceinline__ real adjoint_block(const real (&e)[R + 1][C + 1], real p, real Ac, real Bc,
+                                                  const real (&recv)[C], real (&accL)[R + 1], real& corner,
+                                                  real (&up)[C]) const
+    {
+        const real dA = fma(p, 1.0 / 6.0, 0.5);   // A'(p)
+        const real dB = p * (1.0 / 6.0);          // -B'(p)
+        real gn[R + 1][C + 1];
+#pragma unroll
+        for (int rr = 0; rr <= R; ++rr)
+#pragma unroll
+            for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = 0.0;
+#pragma unroll
+        for (int rr = 1; rr <= R; ++rr) gn[rr][C] = accL[rr];
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) gn[R][cc + 1] += recv[cc];
+        gn[0][C] = corner;
+        real accP = 0.0;
+#pragma unroll
+        for (int rr = R - 1; rr >= 0; --rr)
+#pragma unroll
+            for (int cc = C - 1; cc >= 0; --cc) {
+                const real go = gn[rr + 1][cc + 1];
+                gn[rr + 1][cc] = fma(go, Ac, gn[rr + 1][cc]);
+                gn[rr][cc + 1] = fma(go, Ac, gn[rr][cc + 1]);
+                gn[rr][cc] = fma(-go, Bc, gn[rr][cc]);
+                const real loc = fma(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
+                accP = fma(go, loc, accP);
+            }
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) up[cc] = gn[0][cc + 1];
+        corner = gn[0][0];
+#pragma unroll
+        for (int rr = 1; rr <= R; ++rr) accL[rr] = gn[rr][0];
+        return accP;
+    }
 
     // Steps [T0, T1) of the forward sweep of the current strip, T1 - T0 <= 64 and topc loaded for T0.
     // f(Tstep, active, e) is called after every step.
@@ -532,7 +612,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_fwd_kernel(SweepArgs
     using SW = Sweep<BL, D, YLDS>;
     constexpr int C = SW::C;
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index: uniform, and known to be
     const long slot = (long)blockIdx.x * kWavesPerWG + w;
     const long nslots = (long)gridDim.x * kWavesPerWG;
     SK_LDS real* ylds = (SK_LDS real*)(smem + (size_t)w * a.lds_wave);
@@ -586,7 +666,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
     // second register set would not fit
     constexpr bool LOOKAHEAD = BL < 2;
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index: uniform, and known to be
     const long slot = (long)blockIdx.x * kWavesPerWG + w;
     const long nslots = (long)gridDim.x * kWavesPerWG;
     unsigned char* mylds = smem + (size_t)w * a.lds_wave;
@@ -627,11 +707,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                 sw.load_top(Tc + kWave, topn);
                 const int Te = Tc + kWave < NT ? Tc + kWave : NT;
                 for (int T0 = Tc; T0 < Te; T0 += S) {
-                    real* cp = ckpt + ((long)(s * a.nseg + T0 / S) * NVC) * kWave + lane;
-#pragma unroll
-                    for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
-#pragma unroll
-                    for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
+                    sw.store_ckpt(ckpt + ((long)(s * a.nseg + T0 / S) * NVC) * kWave + lane);
                     sw.forward_run(T0, T0 + S < Te ? T0 + S : Te, NoHook());
                 }
             }
@@ -783,6 +859,235 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
 }
 
 // ------------------------------------------------------------------------------------------------
+// backward kernel, un-compute variant: forward with checkpoints, then ONE reverse sweep that recovers
+// the forward values by inverting Eq. (1) block by block (no replay, no ring)
+// ------------------------------------------------------------------------------------------------
+// The reverse sweep starts every segment of S macro-steps from the exact lane state of a checkpoint
+// (right edge, bottom edge and bottom-left corner of each lane's last block) and walks backwards: a lane
+// recovers all nodes of its block from the right and bottom edges, which leaves it with the right edge
+// of its previous block; the bottom edge of that block is the top edge the lane below recovered one
+// step earlier (one more DPP hand-over, next to the adjoint messages).  Rounding errors of the inverse
+// recurrence grow with the number of steps, so S is short, and at every checkpoint the recovered state
+// is compared with the exact one: a drift above 1e-9 raises the error flag (outputs become NaN) rather
+// than returning inaccurate gradients; such inputs (increment inner products of order one) need the
+// replay variant (SK_FLAG_BWD_REPLAY).
+template <int BL, int D, bool YLDS>
+__global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwdu_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using SW = Sweep<BL, D, YLDS>;
+    constexpr int R = SW::R, C = SW::C, NVC = SW::NVC, DN = SW::DN;
+    constexpr int C2 = 2 * C;   // feed width: adjoint messages and recovered top edge
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index: uniform, and known to be
+    const long slot = (long)blockIdx.x * kWavesPerWG + w;
+    const long nslots = (long)gridDim.x * kWavesPerWG;
+    unsigned char* mylds = smem + (size_t)w * a.lds_wave;
+    SK_LDS real* ylds = (SK_LDS real*)mylds;
+    SK_LDS real* glds = ylds + (size_t)a.q * a.DS;
+    real* rows = a.rows + slot * a.rows_slot;
+    real* adj = a.adj + slot * a.adj_slot;
+    real* ckpt = a.ckpt + slot * a.ckpt_slot;
+    const int S = a.S;
+    const int nck = a.nseg + 1;   // checkpoints per strip
+    const long adjlen = 2L * a.rowlen;
+    SW sw(a, lane);
+
+    for (long pid = slot; pid < a.npairs; pid += nslots) {
+        long xi, yi;
+        pair_ids(a, pid, xi, yi);
+        sw.dxp = a.dx + xi * a.xstride;
+        sw.dyg = a.dy + yi * a.ystride;
+        sw.dyl = ylds;
+        real* gdx = a.gdx + xi * a.xstride;
+        real* gdy = a.gdy + yi * a.ystride;
+        if constexpr (YLDS) {
+            const int n = a.q * a.DS;
+            for (int t = lane; t < n; t += kWave) { ylds[t] = sw.dyg[t]; glds[t] = 0.0; }
+        }
+        const real gk = a.grad_k[pid];
+
+        // ---- phase 1: forward; boundary rows of every strip, a checkpoint every S macro-steps and one
+        // at the end of the strip ----
+        for (int s = 0; s < a.ns; ++s) {
+            sw.begin_strip(s, rows, true);
+            if (lane == sw.lb) sw.rowcur[0] = 1.0;   // node column 0 of the boundary row
+            const int NT = sw.strip_steps();
+            real topn[C];
+            sw.load_top(0, sw.topc);
+            for (int Tc = 0; Tc < NT; Tc += kWave) {
+                if (Tc > 0) {
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) sw.topc[cc] = topn[cc];
+                }
+                sw.load_top(Tc + kWave, topn);
+                const int Te = Tc + kWave < NT ? Tc + kWave : NT;
+                for (int T0 = Tc; T0 < Te; T0 += S) {
+                    sw.store_ckpt(ckpt + ((long)(s * nck + T0 / S) * NVC) * kWave + lane);
+                    sw.forward_run(T0, T0 + S < Te ? T0 + S : Te, NoHook());
+                }
+            }
+            sw.store_ckpt(ckpt + ((long)(s * nck + (NT + S - 1) / S) * NVC) * kWave + lane);
+            if (s == a.ns - 1 && lane == sw.lb && a.k_out) a.k_out[pid] = sw.bot[C - 1];
+            scratch_fence();
+        }
+
+        // ---- phase 2: strips bottom-up, segments right-to-left ----
+        bool drift = false;
+        for (int s = a.ns - 1; s >= 0; --s) {
+            sw.begin_strip(s, rows, false);
+            const int NT = sw.strip_steps();
+            const int lb = sw.lb;
+            const bool full = lb == kWave - 1;
+            const bool is_lb = lane == lb;
+            const bool has_below = s < a.ns - 1;   // then lb == 63
+            const real* adjr = adj + (long)((s + 1) & 1) * adjlen;   // written by the strip below: [J][2C]
+            real* adjw = adj + (long)(s & 1) * adjlen;
+            const real* krow = rows + (long)(a.ns - 1) * a.rowlen;   // bottom row of the grid
+            real accL[R + 1], up[C], ktop[C];
+            real corner = 0.0;
+            real gacc[DN];
+#pragma unroll
+            for (int i = 0; i <= R; ++i) accL[i] = 0.0;
+            // dF/dk at the far corner enters as the carried adjoint of the last lane's first block
+            if (s == a.ns - 1 && is_lb) accL[R] = gk;
+#pragma unroll
+            for (int i = 0; i < C; ++i) { up[i] = 0.0; ktop[i] = 0.0; }
+#pragma unroll
+            for (int i = 0; i < DN; ++i) gacc[i] = 0.0;
+            // Feed of the strip's last lane: lane q <= lb of fc holds, for block column
+            // (column of lane lb at the current step) - (lb - q), the C adjoint messages of the strip below
+            // followed by the C node values under the strip; it shifts up one lane per step and is
+            // refilled every lb + 1 steps from fn, loaded one chunk ahead.
+            real fc[C2], fn[C2];
+            const int CL = lb + 1;
+            int f_end = 0;
+            auto load_feed = [&](int Jb, real (&dst)[C2]) {
+                const int Jq = Jb - (lb - lane);
+                const bool ok = lane <= lb && Jq >= 0 && Jq < a.nb;
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    dst[cc] = (ok && has_below) ? ld_scratch(adjr + (long)Jq * C2 + cc) : 0.0;
+                    dst[C + cc] = !ok ? 0.0
+                                      : (has_below ? ld_scratch(adjr + (long)Jq * C2 + C + cc)
+                                                   : ld_scratch(krow + (long)Jq * C + cc));
+                }
+            };
+            load_feed(NT - 1 - lb, fc);
+            load_feed(NT - 1 - lb - CL, fn);
+            f_end = NT - 1 - CL;
+
+            const int nsegs = (NT + S - 1) / S;
+            real cpn[R + 1 + C];
+            // right edge of this lane's last block, and the bottom edge (with its left corner) of the block of the
+            // lane above: that lane takes its bottom edge from this lane's ktop at the first step of a segment
+            auto load_ckpt = [&](int j) {
+                const real* cp = ckpt + ((long)(s * nck + j) * NVC) * kWave + lane;
+                const int up1 = lane > 0 ? -1 : 0;
+#pragma unroll
+                for (int q = 0; q <= R; ++q) cpn[q] = ld_scratch(cp + q * kWave);
+                cpn[R + 1] = ld_scratch(cp + (R + 1 + C) * kWave + up1);
+#pragma unroll
+                for (int q = 1; q < C; ++q) cpn[R + 1 + q] = ld_scratch(cp + (R + 1 + q - 1) * kWave + up1);
+            };
+            load_ckpt(nsegs);
+            for (int g = nsegs - 1; g >= 0; --g) {
+                const int T0 = g * S;
+                const int T1 = T0 + S < NT ? T0 + S : NT;
+                // the recovered right edge must agree with the exact one of the checkpoint
+                if (g < nsegs - 1) {
+                    const int Jp = T1 - lane;   // block this lane un-computed last
+                    if (Jp >= 1 && Jp < sw.nbl) {
+#pragma unroll
+                        for (int i = 0; i <= R; ++i)
+                            if (fabs(sw.left[i] - cpn[i]) > 1e-9 * fmax(1.0, fabs(cpn[i]))) drift = true;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i <= R; ++i) sw.left[i] = cpn[i];
+#pragma unroll
+                for (int i = 0; i < C; ++i) ktop[i] = cpn[R + 1 + i];
+                load_ckpt(g);   // for the next segment (to the left)
+
+                auto reverse_step = [&](auto fullc, int Tstep, const real (&yv)[DN], real (&yvn)[DN]) {
+                    constexpr bool FULL = decltype(fullc)::value;
+                    if (Tstep == f_end) {
+#pragma unroll
+                        for (int cc = 0; cc < C2; ++cc) fc[cc] = fn[cc];
+                        load_feed(Tstep - lb - CL, fn);
+                        f_end = Tstep - CL;
+                    }
+                    real recv[C], recvk[C];
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) {
+                        recv[cc] = recv_from_below<FULL>(up[cc], fc[cc], is_lb);
+                        recvk[cc] = recv_from_below<FULL>(ktop[cc], fc[C + cc], is_lb);
+                    }
+#pragma unroll
+                    for (int cc = 0; cc < C2; ++cc) fc[cc] = wave_shift_up(fc[cc]);
+                    const int J = Tstep - lane;
+                    sw.fetch_y(J - 1, yvn);
+                    const bool active = (unsigned)J < (unsigned)sw.nbl;
+                    if (active) {
+                        const int b = J >> a.rs2;
+                        const real p = sw.inner(b, yv);
+                        const real q2 = p * p;
+                        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+                        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                        real invB = __builtin_amdgcn_rcp(Bc);
+                        invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+                        real e[R + 1][C + 1];
+#pragma unroll
+                        for (int rr = 0; rr <= R; ++rr) e[rr][C] = sw.left[rr];
+#pragma unroll
+                        for (int cc = 0; cc < C; ++cc) e[R][cc] = recvk[cc];
+                        SW::block_uncompute(e, Ac, invB);
+                        const real accP = sw.adjoint_block(e, p, Ac, Bc, recv, accL, corner, up);
+#pragma unroll
+                        for (int rr = 0; rr <= R; ++rr) sw.left[rr] = e[rr][0];
+#pragma unroll
+                        for (int cc = 0; cc < C; ++cc) ktop[cc] = e[0][cc];
+                        if (lane == 0 && s > 0) {
+                            real* wp = adjw + (long)J * C2;
+#pragma unroll
+                            for (int cc = 0; cc < C; ++cc) { wp[cc] = up[cc]; wp[C + cc] = ktop[cc]; }
+                        }
+                        sw.accumulate_grads(accP, b, yv, gacc, glds, gdx, gdy);
+                    }
+                };
+                auto run_segment = [&](auto fullc) {
+                    real ya[DN], yb[DN];
+                    sw.fetch_y(T1 - 1 - lane, ya);
+                    int Tstep = T1 - 1;
+                    for (; Tstep - 1 >= T0; Tstep -= 2) {
+                        reverse_step(fullc, Tstep, ya, yb);
+                        reverse_step(fullc, Tstep - 1, yb, ya);
+                    }
+                    if (Tstep >= T0) reverse_step(fullc, Tstep, ya, yb);
+                };
+                if (full) run_segment(std::true_type()); else run_segment(std::false_type());
+            }
+            if (drift) {
+                atomicExch(a.err, 2);
+#pragma unroll
+                for (int k = 0; k < DN; ++k) gacc[k] = __builtin_nan("");
+            }
+            sw.flush_gdx(gacc, gdx);
+            scratch_fence();
+        }
+        if constexpr (YLDS) {
+            if (a.want_gy) {
+                const int n = a.q * a.DS;
+                for (int t = lane; t < n; t += kWave) {
+                    const real v = glds[t];
+                    if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // cooperative kernels: one workgroup per pair, the strips of the pair pipelined over its waves
 // ------------------------------------------------------------------------------------------------
 // The strips of a pair are processed in rounds of nw consecutive strips, one per wave, separated by
@@ -794,6 +1099,12 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
 // error flag instead of spinning for ever.  The first wave of a round takes its top row from the global
 // boundary row that the last wave of the previous round wrote (staged through a small private ring so
 // that the step code is the same), or all ones in the very first round.
+// Ordering of LDS traffic only: the hardware executes the LDS instructions of a wave in order, so all that is
+// needed around a flag access is that the compiler keeps the order and that outstanding LDS operations
+// have completed.  (A workgroup-scope release/acquire would also wait for every global load and store in
+// flight, which here includes checkpoint traffic with microseconds of latency.)
+__device__ __forceinline__ void lds_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 struct Link {
     SK_LDS int* prod_me;
     SK_LDS int* cons_me;
@@ -819,7 +1130,8 @@ struct Link {
     {
         if (*dead) return;
         for (int it = 0; it < (1 << 22); ++it) {
-            const int v = __hip_atomic_load(f, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const int v = __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            lds_order();
             if (v >= need) return;
             __builtin_amdgcn_s_sleep(1);
         }
@@ -832,8 +1144,10 @@ struct Link {
     }
     __device__ __forceinline__ void consumed(int count) const
     {
-        if (has_up && RB < nb)
-            __hip_atomic_store(cons_me, count < nb ? count : nb, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (has_up && RB < nb) {
+            lds_order();
+            __hip_atomic_store(cons_me, count < nb ? count : nb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
     }
     // before writing outbox columns below `upto`: the ring slots they reuse must have been read
     __device__ __forceinline__ void reserve(int upto) const
@@ -844,8 +1158,10 @@ struct Link {
     }
     __device__ __forceinline__ void publish(int count) const
     {
-        if (has_dn && count > 0)
-            __hip_atomic_store(prod_me, count < nb ? count : nb, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (has_dn && count > 0) {
+            lds_order();
+            __hip_atomic_store(prod_me, count < nb ? count : nb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
     }
 };
 
@@ -938,7 +1254,7 @@ __global__ __launch_bounds__((CoopCfg<BL, false>::kMaxWaves) * 64) void sweep_fw
     using SW = Sweep<BL, D, YLDS>;
     constexpr int C = SW::C;
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index: uniform, and known to be
     const int nw = a.nw;
     CoopLds l = carve_coop_lds(smem, a, w, C);
     real* rows = a.rows + (long)blockIdx.x * a.rows_slot;
@@ -1014,7 +1330,7 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
     constexpr int R = SW::R, C = SW::C, NVR = SW::NVR, NVC = SW::NVC, DN = SW::DN;
     constexpr bool LOOKAHEAD = BL < 2;
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index: uniform, and known to be
     const int nw = a.nw;
     CoopLds l = carve_coop_lds(smem, a, w, C);
     real* rows = a.rows + (long)blockIdx.x * a.rows_slot;
@@ -1081,11 +1397,7 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
                 }
                 lk.reserve(Tc - sw.lb + CH);
                 if (Tc % S == 0) {
-                    real* cp = ckpt + ((long)(s * a.nseg + Tc / S) * NVC) * kWave + lane;
-#pragma unroll
-                    for (int i = 0; i <= R; ++i) cp[i * kWave] = sw.left[i];
-#pragma unroll
-                    for (int i = 0; i < C; ++i) cp[(R + 1 + i) * kWave] = sw.bot[i];
+                    sw.store_ckpt(ckpt + ((long)(s * a.nseg + Tc / S) * NVC) * kWave + lane);
                 }
                 sw.forward_run_coop(Tc, Te, edge, NoHook());
             }
@@ -1250,6 +1562,271 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
     }
 }
 
+// Cooperative backward kernel, un-compute variant (see sweep_bwdu_kernel for the method and
+// sweep_bwd_coop_kernel for the hand-over between waves).  The messages that travel upwards from strip to
+// strip are 2C wide: the adjoint messages and the recovered top edge of the lower strip.
+template <int BL, int D, bool YLDS>
+__global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwdu_coop_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using SW = Sweep<BL, D, YLDS>;
+    constexpr int R = SW::R, C = SW::C, NVC = SW::NVC, DN = SW::DN;
+    constexpr int C2 = 2 * C;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index: uniform, and known to be
+    const int nw = a.nw;
+    CoopLds l = carve_coop_lds(smem, a, w, C2);
+    real* rows = a.rows + (long)blockIdx.x * a.rows_slot;
+    real* adj = a.adj + (long)blockIdx.x * a.adj_slot;
+    real* ckpt = a.ckpt + (long)blockIdx.x * a.ckpt_slot;
+    const int S = a.S;
+    const int CH = a.CH < S ? a.CH : S;   // checkpoints fall on chunk starts
+    const int nck = a.nseg + 1;
+    const long adjlen = 2L * a.rowlen;
+    const int rbmask = a.RB - 1;
+    SW sw(a, lane);
+    sw.rbmask = rbmask;
+    bool dead = false;
+
+    for (int t = threadIdx.x; t < a.RB * C2; t += blockDim.x) { l.ones[t] = 1.0; l.zeros[t] = 0.0; }
+    for (long pid = blockIdx.x; pid < a.npairs; pid += gridDim.x) {
+        long xi, yi;
+        pair_ids(a, pid, xi, yi);
+        sw.dxp = a.dx + xi * a.xstride;
+        sw.dyg = a.dy + yi * a.ystride;
+        sw.dyl = l.y;
+        real* gdx = a.gdx + xi * a.xstride;
+        real* gdy = a.gdy + yi * a.ystride;
+        __syncthreads();
+        if constexpr (YLDS) {
+            const int n = a.q * a.DS;
+            for (int t = threadIdx.x; t < n; t += blockDim.x) { l.y[t] = sw.dyg[t]; l.gy[t] = 0.0; }
+        }
+        const real gk = a.grad_k[pid];
+
+        // ---- phase 1: forward in rounds; boundary rows and checkpoints to global ----
+        for (int s0 = 0; s0 < a.ns; s0 += nw) {
+            if (s0 > 0) scratch_fence();
+            __syncthreads();
+            if (threadIdx.x < 64) l.prod[threadIdx.x] = 0;
+            __syncthreads();
+            const int s = s0 + w;
+            if (s >= a.ns) continue;
+            const bool last = s == a.ns - 1;
+            sw.begin_strip(s, rows, true);
+            if (lane == sw.lb) sw.rowcur[0] = 1.0;
+            Link lk;
+            lk.setup(w, w > 0, !last && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
+            sw.obox = l.obox;
+            sw.lbo = lk.has_dn ? sw.lb : -1;
+            if (sw.lbo >= 0) sw.lbany = sw.lb;
+            const bool staged = w == 0 && s > 0;
+            sw.ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C2 : (staged ? l.stage : l.ones);
+            Stager<C> stg;
+            stg.ring = l.stage; stg.rbmask = rbmask; stg.CH = CH; stg.lane = lane;
+            auto src = [&](int J, int cc) -> const real* {
+                return J < a.nb ? sw.rowprev + (long)J * C + 1 + cc : nullptr;
+            };
+            if (staged) stg.prime(src);
+            const int NT = sw.strip_steps();
+            real edge[C];
+            lk.wait_cols(CH + 1);
+            sw.read_edge(0, edge);
+            for (int Tc = 0; Tc < NT; Tc += CH) {
+                const int Te = Tc + CH < NT ? Tc + CH : NT;
+                if (Tc > 0) {
+                    if (Tc < a.nb) {
+                        lk.consumed(Tc);
+                        lk.wait_cols(Tc + CH + 1);
+                        if (staged) stg.advance(Tc, src);
+                    }
+                    lk.publish(Tc - sw.lb);
+                }
+                lk.reserve(Tc - sw.lb + CH);
+                if (Tc % S == 0) sw.store_ckpt(ckpt + ((long)(s * nck + Tc / S) * NVC) * kWave + lane);
+                sw.forward_run_coop(Tc, Te, edge, NoHook());
+            }
+            sw.store_ckpt(ckpt + ((long)(s * nck + (NT + S - 1) / S) * NVC) * kWave + lane);
+            lk.publish(a.nb);
+            lk.consumed(a.nb);
+            if (last && lane == sw.lb && a.k_out) a.k_out[pid] = sw.bot[C - 1];
+        }
+
+        // ---- phase 2: strips bottom-up in rounds (processing index i = ns - 1 - s) ----
+        bool drift = false;
+        for (int i0 = 0; i0 < a.ns; i0 += nw) {
+            scratch_fence();   // phase 1 output, or the boundary row of the previous round
+            __syncthreads();
+            if (threadIdx.x < 64) l.prod[threadIdx.x] = 0;
+            __syncthreads();
+            const int i = i0 + w;
+            if (i >= a.ns) continue;
+            const int s = a.ns - 1 - i;
+            sw.begin_strip(s, rows, false);
+            Link lk;
+            lk.setup(w, w > 0, s > 0 && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
+            SK_LDS real* obox = l.obox;
+            const int NT = sw.strip_steps();
+            const int lb = sw.lb;
+            const bool full = lb == kWave - 1;
+            const bool is_lb = lane == lb;
+            const int lane_out = lk.has_dn ? 0 : -1;                   // lane 0 -> outbox of this wave
+            const int lane_outg = (s > 0 && w == nw - 1) ? 0 : -1;     // lane 0 -> global row for the next round
+            const bool staged = w == 0;   // the first wave of a round reads its feed from global memory
+            const SK_LDS real* ibox = w > 0 ? l.oboxes + (w - 1) * a.RB * C2 : l.stage;
+            // boundary rows in global memory, indexed by reverse column c = nb - 1 - J, 2C values each
+            const real* adjr = adj + (long)(((i0 / nw) + 1) & 1) * adjlen;
+            real* adjw = adj + (long)((i0 / nw) & 1) * adjlen;
+            const real* krow = rows + (long)(a.ns - 1) * a.rowlen;   // bottom row of the grid
+            Stager<C2> stg;
+            stg.ring = l.stage; stg.rbmask = rbmask; stg.CH = CH; stg.lane = lane;
+            auto src = [&](int c, int cc) -> const real* {
+                if (c >= a.nb) return nullptr;
+                if (i > 0) return adjr + (long)c * C2 + cc;
+                return cc < C ? nullptr : krow + (long)(a.nb - 1 - c) * C + (cc - C);
+            };
+            if (staged) stg.prime(src);
+            auto read_feed = [&](int col, real (&dst)[C2]) {
+                const int cidx = col < a.nb ? col : a.nb - 1;
+                const SK_LDS real* ip = ibox + (cidx & rbmask) * C2;
+#pragma unroll
+                for (int cc = 0; cc < C2; ++cc) dst[cc] = ip[cc];
+            };
+            real accL[R + 1], up[C], ktop[C];
+            real corner = 0.0;
+            real gacc[DN];
+#pragma unroll
+            for (int k = 0; k <= R; ++k) accL[k] = 0.0;
+            // dF/dk at the far corner enters as the carried adjoint of the last lane's first block
+            if (s == a.ns - 1 && is_lb) accL[R] = gk;
+#pragma unroll
+            for (int k = 0; k < C; ++k) { up[k] = 0.0; ktop[k] = 0.0; }
+#pragma unroll
+            for (int k = 0; k < DN; ++k) gacc[k] = 0.0;
+
+            const int nsegs = (NT + S - 1) / S;
+            real cpn[R + 1 + C];
+            // right edge of this lane's last block, and the bottom edge (with its left corner) of the block of the
+            // lane above: that lane takes its bottom edge from this lane's ktop at the first step of a segment
+            auto load_ckpt = [&](int j) {
+                const real* cp = ckpt + ((long)(s * nck + j) * NVC) * kWave + lane;
+                const int up1 = lane > 0 ? -1 : 0;
+#pragma unroll
+                for (int q = 0; q <= R; ++q) cpn[q] = ld_scratch(cp + q * kWave);
+                cpn[R + 1] = ld_scratch(cp + (R + 1 + C) * kWave + up1);
+#pragma unroll
+                for (int q = 1; q < C; ++q) cpn[R + 1 + q] = ld_scratch(cp + (R + 1 + q - 1) * kWave + up1);
+            };
+            load_ckpt(nsegs);
+            real feed[C2];   // messages for the strip's last lane at the coming reverse step
+            lk.wait_cols(CH + 1);
+            read_feed(0, feed);
+            for (int g = nsegs - 1; g >= 0; --g) {
+                const int T0 = g * S;
+                const int T1 = T0 + S < NT ? T0 + S : NT;
+                if (g < nsegs - 1) {
+                    const int Jp = T1 - lane;
+                    if (Jp >= 1 && Jp < sw.nbl) {
+#pragma unroll
+                        for (int k = 0; k <= R; ++k)
+                            if (fabs(sw.left[k] - cpn[k]) > 1e-9 * fmax(1.0, fabs(cpn[k]))) drift = true;
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k <= R; ++k) sw.left[k] = cpn[k];
+#pragma unroll
+                for (int k = 0; k < C; ++k) ktop[k] = cpn[R + 1 + k];
+                load_ckpt(g);
+                // reverse time t = NT - 1 - Tstep: lane lb needs reverse column t, lane 0 writes t - lb
+                auto reverse_step = [&](auto fullc, int Tstep, const real (&yv)[DN], real (&yvn)[DN]) {
+                    constexpr bool FULL = decltype(fullc)::value;
+                    const int t = NT - 1 - Tstep;
+                    if ((t & (CH - 1)) == 0) {
+                        if (t > 0) {
+                            if (t < a.nb) {
+                                lk.consumed(t);
+                                lk.wait_cols(t + CH + 1);
+                                if (staged) stg.advance(t, src);
+                            }
+                            lk.publish(t - lb);
+                        }
+                        lk.reserve(t - lb + CH);
+                    }
+                    real recv[C], recvk[C];
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) {
+                        recv[cc] = recv_from_below<FULL>(up[cc], feed[cc], is_lb);
+                        recvk[cc] = recv_from_below<FULL>(ktop[cc], feed[C + cc], is_lb);
+                    }
+                    read_feed(t + 1, feed);   // for the next reverse step
+                    const int J = Tstep - lane;
+                    sw.fetch_y(J - 1, yvn);
+                    const bool active = (unsigned)J < (unsigned)sw.nbl;
+                    if (active) {
+                        const int b = J >> a.rs2;
+                        const real p = sw.inner(b, yv);
+                        const real q2 = p * p;
+                        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+                        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                        real invB = __builtin_amdgcn_rcp(Bc);
+                        invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+                        real e[R + 1][C + 1];
+#pragma unroll
+                        for (int rr = 0; rr <= R; ++rr) e[rr][C] = sw.left[rr];
+#pragma unroll
+                        for (int cc = 0; cc < C; ++cc) e[R][cc] = recvk[cc];
+                        SW::block_uncompute(e, Ac, invB);
+                        const real accP = sw.adjoint_block(e, p, Ac, Bc, recv, accL, corner, up);
+#pragma unroll
+                        for (int rr = 0; rr <= R; ++rr) sw.left[rr] = e[rr][0];
+#pragma unroll
+                        for (int cc = 0; cc < C; ++cc) ktop[cc] = e[0][cc];
+                        if (lane == 0 && (lane_out == 0 || lane_outg == 0)) {
+                            const int c = a.nb - 1 - J;
+                            if (lane_out == 0) {
+                                SK_LDS real* op = obox + (c & rbmask) * C2;
+#pragma unroll
+                                for (int cc = 0; cc < C; ++cc) { op[cc] = up[cc]; op[C + cc] = ktop[cc]; }
+                            }
+                            if (lane_outg == 0) {
+                                real* wp = adjw + (long)c * C2;
+#pragma unroll
+                                for (int cc = 0; cc < C; ++cc) { wp[cc] = up[cc]; wp[C + cc] = ktop[cc]; }
+                            }
+                        }
+                        sw.accumulate_grads(accP, b, yv, gacc, l.gy, gdx, gdy);
+                    }
+                };
+                auto run_segment = [&](auto fullc) {
+                    real ya[DN], yb[DN];
+                    sw.fetch_y(T1 - 1 - lane, ya);
+                    int Tstep = T1 - 1;
+                    for (; Tstep - 1 >= T0; Tstep -= 2) {
+                        reverse_step(fullc, Tstep, ya, yb);
+                        reverse_step(fullc, Tstep - 1, yb, ya);
+                    }
+                    if (Tstep >= T0) reverse_step(fullc, Tstep, ya, yb);
+                };
+                if (full) run_segment(std::true_type()); else run_segment(std::false_type());
+            }
+            lk.publish(a.nb);
+            lk.consumed(a.nb);
+            if (drift) atomicExch(a.err, 2);
+            sw.flush_gdx(gacc, gdx);
+        }
+        __syncthreads();
+        if constexpr (YLDS) {
+            if (a.want_gy) {
+                const int n = a.q * a.DS;
+                for (int t = threadIdx.x; t < n; t += blockDim.x) {
+                    const real v = l.gy[t];
+                    if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
@@ -1289,7 +1866,7 @@ hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int 
 
 template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
-                           int L2, int qpad, int d, int DS, hipStream_t st)
+                           int L2, int qpad, int d, int DS, const int* err, hipStream_t st)
 {
     PathSet<T> px{nullptr, grad_x, nullptr, const_cast<real*>(gdx), nx, L1, rpad};
     PathSet<T> py{nullptr, grad_y, nullptr, const_cast<real*>(gdy), ny, L2, qpad};
@@ -1297,7 +1874,7 @@ hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(finalize_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS);
+    hipLaunchKernelGGL(finalize_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err);
     return hipGetLastError();
 }
 
@@ -1315,7 +1892,18 @@ hipError_t launch_sweep_coop(bool backward, const SweepArgs& a, int grid, size_t
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        hipLaunchKernelGGL((sweep_bwd_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
+        if (a.uncompute) {
+            static bool attr_done_u = false;
+            if (!attr_done_u) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwdu_coop_kernel<BL, D, YLDS>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+                if (e != hipSuccess) return e;
+                attr_done_u = true;
+            }
+            hipLaunchKernelGGL((sweep_bwdu_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
+        } else {
+            hipLaunchKernelGGL((sweep_bwd_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
+        }
     } else {
         static bool attr_done = false;
         if (!attr_done) {
@@ -1342,7 +1930,18 @@ hipError_t launch_sweep_one(bool backward, const SweepArgs& a, int grid, size_t 
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        hipLaunchKernelGGL((sweep_bwd_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+        if (a.uncompute) {
+            static bool attr_done_u = false;
+            if (!attr_done_u) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwdu_kernel<BL, D, YLDS>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+                if (e != hipSuccess) return e;
+                attr_done_u = true;
+            }
+            hipLaunchKernelGGL((sweep_bwdu_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+        } else {
+            hipLaunchKernelGGL((sweep_bwd_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+        }
     } else {
         static bool attr_done = false;
         if (!attr_done) {
@@ -1370,14 +1969,16 @@ hipError_t launch_sweep_bl(bool backward, int DT, bool ylds, const SweepArgs& a,
                            hipStream_t st)
 {
     switch (DT) {
+#ifndef SK_ONLY_C2   /* development builds instantiate a single shape */
         case 0: return launch_sweep_y<BL, 0>(backward, ylds, a, grid, lds, st);
         case 2: return launch_sweep_y<BL, 2>(backward, ylds, a, grid, lds, st);
         case 3: return launch_sweep_y<BL, 3>(backward, ylds, a, grid, lds, st);
         case 4: return launch_sweep_y<BL, 4>(backward, ylds, a, grid, lds, st);
-        case 5: return launch_sweep_y<BL, 5>(backward, ylds, a, grid, lds, st);
         case 6: return launch_sweep_y<BL, 6>(backward, ylds, a, grid, lds, st);
         case 8: return launch_sweep_y<BL, 8>(backward, ylds, a, grid, lds, st);
         case 16: return launch_sweep_y<BL, 16>(backward, ylds, a, grid, lds, st);
+#endif
+        case 5: return launch_sweep_y<BL, 5>(backward, ylds, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1386,9 +1987,11 @@ hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int g
 {
     const bool ylds = a.y_lds != 0;
     switch (BL) {
+#ifndef SK_ONLY_C2
         case 0: return launch_sweep_bl<0>(backward, DT, ylds, a, grid, lds, st);
-        case 1: return launch_sweep_bl<1>(backward, DT, ylds, a, grid, lds, st);
         case 2: return launch_sweep_bl<2>(backward, DT, ylds, a, grid, lds, st);
+#endif
+        case 1: return launch_sweep_bl<1>(backward, DT, ylds, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1402,8 +2005,8 @@ template hipError_t launch_prepare<float>(const float*, real*, real*, long, int,
 template hipError_t launch_prepare<double>(const double*, real*, real*, long, int, int, const double*, real*, real*,
                                            long, int, int, int, int, int*, hipStream_t);
 template hipError_t launch_finalize<float>(const real*, float*, long, int, int, const real*, float*, long, int, int, int,
-                                           int, hipStream_t);
+                                           int, const int*, hipStream_t);
 template hipError_t launch_finalize<double>(const real*, double*, long, int, int, const real*, double*, long, int, int,
-                                            int, int, hipStream_t);
+                                            int, int, const int*, hipStream_t);
 
 }  // namespace sk

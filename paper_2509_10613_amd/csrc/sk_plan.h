@@ -53,15 +53,19 @@ struct Plan {
     size_t total = 0;
     // cooperative mode: one workgroup per pair, its strips pipelined over nw waves
     int coop = 0, nw = 0, RB = 0, CH = 0;
+    int uncompute = 0;   // backward: reverse sweep recovers forward values by inverting Eq. (1) (no replay ring)
     size_t coop_off_gdy = 0, coop_off_flags = 0, coop_off_obox = 0, coop_off_ring = 0, coop_ring_stride = 0;
 };
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
+constexpr int kUncomputeS = 8;   // macro-steps between checkpoints when the reverse sweep inverts Eq. (1)
+
 inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
-                      int64_t d, int lam1, int lam2, int io_elem)
+                      int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true)
 {
     Plan p;
+    p.uncompute = backward && uncompute;
     const int elem = 8;
     p.io_elem = io_elem;
     p.backward = backward;
@@ -97,18 +101,18 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         // ring per wave.
         const int maxw = (backward && p.BL == 2) ? 4 : 8;
         p.nw = p.ns < maxw ? p.ns : maxw;
-        // Outbox rings long enough for a whole row need no back-pressure; otherwise 32 columns.
-        p.RB = 32;
+        // Outbox rings long enough for a whole row need no back-pressure; otherwise 32 columns (set below).
+        p.CH = 8;
+        const int CW = backward ? 2 * C : C;   // values per column in the hand-over rings
         {
             int full = 32;
             while (full < p.nb + 1) full <<= 1;
-            if ((size_t)(2 * p.nw + 2) * full * C * elem <= 40 * 1024) p.RB = full;
+            p.RB = ((size_t)(2 * p.nw + 2) * full * CW * elem <= 40 * 1024) ? full : 32;
         }
-        p.CH = 8;
         const size_t ycopy = (size_t)p.q * p.DP * elem;
-        const size_t fixed = 512 + (size_t)(2 * p.nw + 2) * p.RB * C * elem;
+        const size_t fixed = 512 + (size_t)(2 * p.nw + 2) * p.RB * CW * elem;
         const size_t budget = kLdsPerCU - 1024;
-        const size_t ring_min = backward ? (size_t)p.nw * 4 * ring_step : 0;
+        const size_t ring_min = (backward && !p.uncompute) ? (size_t)p.nw * 4 * ring_step : 0;
         const size_t yneed = ycopy * (backward ? 2 : 1);
         p.y_lds = (p.DT != 0 && align_up(yneed, 256) + fixed + ring_min <= budget) ? 1 : 0;
         size_t used = p.y_lds ? align_up(ycopy, 256) : 0;
@@ -117,10 +121,13 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.coop_off_flags = used;
         used += 512;
         p.coop_off_obox = used;   // ones, zeros, nw outboxes, nw staging rings
-        used += (size_t)(2 * p.nw + 2) * p.RB * C * elem;
+        used += (size_t)(2 * p.nw + 2) * p.RB * CW * elem;
         used = align_up(used, 256);
         p.coop_off_ring = used;
-        if (backward) {
+        if (backward && p.uncompute) {
+            p.S = kUncomputeS;
+            p.nseg = (p.nb + kWave - 1 + p.S - 1) / p.S;
+        } else if (backward) {
             int S = 64;
             while (S > 4 && used + (size_t)p.nw * S * ring_step > budget) S >>= 1;
             p.S = S;
@@ -142,7 +149,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.y_lds = (p.DT != 0 && ybytes <= 20 * 1024) ? 1 : 0;
         size_t used = p.y_lds ? ybytes : 0;
         p.ring_off = used;
-        if (backward) {
+        if (backward && p.uncompute) {
+            p.S = kUncomputeS;
+            p.nseg = (p.nb + kWave - 1 + p.S - 1) / p.S;
+        } else if (backward) {
             int S = 64;
             while (S > 4 && used + (size_t)S * ring_step > kLdsPerWave) S >>= 1;
             p.S = S;
@@ -154,7 +164,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
 
         int wg_per_cu = (int)(kLdsPerCU / (p.lds_bytes ? p.lds_bytes : 1));
         if (wg_per_cu < 1) wg_per_cu = 1;
-        if (wg_per_cu > 2) wg_per_cu = 2;
+        if (wg_per_cu > 4) wg_per_cu = 4;
+        if (backward && wg_per_cu > 2) wg_per_cu = 2;   // register file: the backward kernels run 2 waves per SIMD at most
         int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
         int64_t cap = (int64_t)kNumCU * wg_per_cu;
         p.grid = (int)(want < cap ? want : cap);
@@ -171,10 +182,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     if (backward) {
         p.off_gdxT = take((size_t)nx * p.xstride * elem);
         p.off_gdyT = symmetric ? p.off_gdxT : take((size_t)ny * p.ystride * elem);
-        p.adj_slot = 2 * (int64_t)p.rowlen;
+        p.adj_slot = 4 * (int64_t)p.rowlen;   // two rows of 2C values per block column
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
-        const int NVC = R + 1 + C;   // lane state kept per checkpoint
-        p.ckpt_slot = (int64_t)p.ns * p.nseg * NVC * kWave;
+        const int NVC = R + C + 2;   // lane state kept per checkpoint
+        p.ckpt_slot = (int64_t)p.ns * (p.nseg + 1) * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
     }
     if (io_elem != elem) {
