@@ -1613,8 +1613,10 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
             const int s = s0 + w;
             if (s >= a.ns) continue;
             const bool last = s == a.ns - 1;
-            sw.begin_strip(s, rows, true);
-            if (lane == sw.lb) sw.rowcur[0] = 1.0;
+            // global boundary rows are needed below the last wave of a round (next round's top feed) and
+            // below the last strip (bottom row of the grid, where the reverse sweep starts)
+            sw.begin_strip(s, rows, last || w == nw - 1);
+            if (last && lane == sw.lb) sw.rowcur[0] = 1.0;
             Link lk;
             lk.setup(w, w > 0, !last && w < nw - 1, l.prod, l.cons, a.nb, a.RB, lane, a.err, &dead);
             sw.obox = l.obox;

@@ -233,3 +233,58 @@ def test_only_one_gradient_requested():
     _, none, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0, want_x=False)
     assert none is None
     check_grads(host(gy), gyr, torch.float64, "grad_y only")
+
+
+# ------------------------------------------------------------------ the two backward variants
+@pytest.mark.parametrize("L1,L2,d,lam,B", [(70, 66, 5, 1, 6), (130, 40, 3, 0, 5), (200, 180, 8, 2, 3), (33, 65, 20, 1, 4)])
+def test_backward_replay_variant(L1, L2, d, lam, B):
+    # SK_FLAG_BWD_REPLAY: forward segments are replayed instead of inverting Eq. (1)
+    X = rand_paths(5000 + L1, B, L1, d, 0.2)
+    Y = rand_paths(6000 + L2, B, L2, d, 0.2)
+    gk = workloads.upstream_weights(11, (B,))
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, lam, lam, 0)
+    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), lam, lam, sk.SK_FLAG_BWD_REPLAY)
+    torch.cuda.synchronize()
+    check_values(host(k), kr, torch.float64, "k (replay)")
+    check_grads(host(gx), gxr, torch.float64, "grad_x (replay)")
+    check_grads(host(gy), gyr, torch.float64, "grad_y (replay)")
+
+
+def test_backward_replay_variant_many_pairs():
+    w, X, Y = workloads.make("c3", n_x=40, n_y=40)     # 1600 pairs: one wave per pair
+    W = workloads.upstream_weights(34, (40, 40))
+    Kref, gXr, gYr = oracle.gram(X, Y, W, w.lam, w.lam, w.flags)
+    K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), w.lam, w.lam, w.flags | sk.SK_FLAG_BWD_REPLAY)
+    torch.cuda.synchronize()
+    check_values(host(K), Kref, torch.float64, "K (replay)")
+    check_grads(host(gX), gXr, torch.float64, "grad_X (replay)")
+    check_grads(host(gY), gYr, torch.float64, "grad_Y (replay)")
+    K2, gX2, gY2 = sk.sigkernel_gram(dev(X), dev(Y), dev(W), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    check_grads(host(gX2), gXr, torch.float64, "grad_X (default)")
+    check_grads(host(gY2), gYr, torch.float64, "grad_Y (default)")
+
+
+@pytest.mark.parametrize("scale", [0.5, 1.5, 4.0])
+def test_inverse_recurrence_never_fails_silently(scale):
+    # Large increments make the inverse of Eq. (1) ill-conditioned.  The default backward must then either
+    # still meet the tolerance or return NaN everywhere (its drift check); the replay variant has no limit.
+    B, L, d = 4, 150, 3
+    X = rand_paths(7001, B, L, d, 0.1) * scale
+    Y = rand_paths(7002, B, L, d, 0.1) * scale
+    gk = np.ones(B)
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, 1, 1, 0)
+    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0)
+    torch.cuda.synchronize()
+    gx, gy = host(gx), host(gy)
+    if np.any(np.isnan(gx)) or np.any(np.isnan(gy)):
+        print("scale %g: inverse recurrence drifted, gradients are NaN" % scale, flush=True)
+        assert np.all(np.isnan(gx)) and np.all(np.isnan(gy))
+    else:
+        assert np.max(np.abs(gx - gxr)) <= 1e-10 * max(1.0, np.max(np.abs(gxr)))
+        assert np.max(np.abs(gy - gyr)) <= 1e-10 * max(1.0, np.max(np.abs(gyr)))
+    k2, gx2, gy2 = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, sk.SK_FLAG_BWD_REPLAY)
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(host(gx2))) and np.all(np.isfinite(host(gy2)))
+    check_grads(host(gx2), gxr, torch.float64, "grad_x (replay, scale %g)" % scale)
+    check_grads(host(gy2), gyr, torch.float64, "grad_y (replay, scale %g)" % scale)
