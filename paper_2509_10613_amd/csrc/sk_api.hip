@@ -103,6 +103,12 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.coop_off_gdy = (unsigned)p.coop_off_gdy; a.coop_off_flags = (unsigned)p.coop_off_flags;
     a.coop_off_obox = (unsigned)p.coop_off_obox; a.coop_off_ring = (unsigned)p.coop_off_ring;
     a.coop_ring_stride = (unsigned)p.coop_ring_stride;
+    a.lock = p.lock; a.lk_M = p.lk_M; a.lk_ns = p.lk_ns; a.lk_NT = p.lk_NT; a.lk_padb = p.lk_padb;
+    a.lk_rowlen = p.lk_rowlen;
+    a.lk_off_y = (unsigned)p.lk_off_y; a.lk_off_gy = (unsigned)p.lk_off_gy; a.lk_off_cring = (unsigned)p.lk_off_cring;
+    a.lk_off_gp = (unsigned)p.lk_off_gp; a.lk_off_krows = (unsigned)p.lk_off_krows;
+    a.lk_off_arows = (unsigned)p.lk_off_arows; a.lk_off_dump = (unsigned)p.lk_off_dump;
+    a.lk_cring_stride = (unsigned)p.lk_cring_stride; a.lk_gp_stride = (unsigned)p.lk_gp_stride;
 
     if (backward) {
         a.gdx = reinterpret_cast<double*>(base + p.off_gdxT);
@@ -132,7 +138,8 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         tl.backward = backward ? 1 : 0;
         SK_CHECK(hipEventRecord(tl.start, st));
     }
-    SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     if (timed) {
         SK_CHECK(hipEventRecord(tl.stop, st));
         std::lock_guard<std::mutex> lk(g_timing_mu);

@@ -1,0 +1,99 @@
+// Device-side helpers shared by the sweep kernels: LDS-typed pointers, lane exchange by DPP, scratch loads
+// and fences, LDS atomics.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "sk_kernels.h"
+
+namespace sk {
+
+// Pointers into LDS keep their address space in the type, so that every access is a ds_* instruction.
+#define SK_LDS __attribute__((address_space(3)))
+
+// ------------------------------------------------------------------------------------------------
+// lane exchange helpers (must be called with all 64 lanes active)
+// ------------------------------------------------------------------------------------------------
+// lane i receives v of lane i-1; lane 0 receives edge (its own lane's value of that argument)
+__device__ __forceinline__ real wave_from_above_or(real v, real edge)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    int elo = __double2loint(edge), ehi = __double2hiint(edge);
+    lo = __builtin_amdgcn_update_dpp(elo, lo, 0x138, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(ehi, hi, 0x138, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+// lane i receives v of lane i+1; lane 63 receives edge
+__device__ __forceinline__ real wave_from_below_or(real v, real edge)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    int elo = __double2loint(edge), ehi = __double2hiint(edge);
+    lo = __builtin_amdgcn_update_dpp(elo, lo, 0x130, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(ehi, hi, 0x130, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+// shifts of the feed registers: the lane that has no source receives zero
+__device__ __forceinline__ real wave_shift_down(real v)   // lane i receives lane i+1
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x130, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x130, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ real wave_shift_up(real v)     // lane i receives lane i-1
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x138, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x138, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Lane i receives v of lane i+1, except the strip's last lane lb, which receives edge (its own lane's
+// value of that argument).  full = (lb == 63) is wave-uniform.
+template <bool FULL>
+__device__ __forceinline__ real recv_from_below(real v, real edge, bool is_lb)
+{
+    if constexpr (FULL) {
+        return wave_from_below_or(v, edge);
+    } else {
+        const real t = wave_shift_down(v);
+        return is_lb ? edge : t;
+    }
+}
+
+// Device-scope load that bypasses the per-CU vector cache: used for data this wave wrote to global
+// scratch earlier in the same kernel.
+__device__ __forceinline__ real ld_scratch(const real* p)
+{
+    unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+    return __longlong_as_double((long long)u);
+}
+
+// Scratch written by a wave is only ever read back by waves of the same workgroup (same CU, hence the same
+// L2): it is enough that the stores have completed (they write through to L2) and that the reads bypass the
+// per-CU vector cache (ld_scratch).  An agent-scope fence would write back and invalidate the whole L2.
+__device__ __forceinline__ void scratch_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ void lds_atomic_add(SK_LDS real* p, real v)
+{
+    (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Ordering of LDS traffic only: the hardware executes the LDS instructions of a wave in order, so all that is
+// needed around a flag access is that the compiler keeps the order and that outstanding LDS operations
+// have completed.  (A workgroup-scope release/acquire would also wait for every global load and store in
+// flight, which here includes checkpoint traffic with microseconds of latency.)
+__device__ __forceinline__ void lds_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+
+__device__ __forceinline__ void pair_ids(const SweepArgs& a, long pid, long& xi, long& yi)
+{
+    xi = a.gramM ? pid / a.gramM : pid;
+    yi = a.gramM ? pid % a.gramM : pid;
+}
+
+}  // namespace sk

@@ -44,6 +44,16 @@ struct SweepArgs {
     int RB, CH;          // outbox ring length and hand-over chunk, in block columns (powers of two)
     unsigned coop_off_gdy, coop_off_flags, coop_off_obox, coop_off_ring, coop_ring_stride;   // LDS bytes
     int uncompute;       // backward: recover forward values by inverting Eq. (1) instead of replaying segments
+    // lock-step mode (one workgroup per pair: a stencil wave and a coefficient wave per strip, all waves
+    // advancing in barrier-separated chunks of macro-steps)
+    int lock;
+    int lk_M;            // block rows per lane
+    int lk_ns;           // strips of 64 * lk_M block rows
+    int lk_NT;           // macro-steps per strip (a multiple of 8)
+    int lk_padb;         // virtual block rows above the grid (the strips are aligned to its bottom)
+    int lk_rowlen;       // doubles per hand-over row in LDS
+    unsigned lk_off_y, lk_off_gy, lk_off_cring, lk_off_gp, lk_off_krows, lk_off_arows, lk_off_dump;   // LDS bytes
+    unsigned lk_cring_stride, lk_gp_stride;   // LDS bytes per strip
     int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted
 };
 
@@ -57,5 +67,8 @@ template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
                            int L2, int qpad, int d, int DS, const int* err, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
+// lock-step mode (a.lock != 0), defined in sk_lockstep.hip
+hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
+                                 hipStream_t st);
 
 }  // namespace sk

@@ -1,0 +1,697 @@
+// Lock-step cooperative sweeps (gfx950): one workgroup per path pair, used when the batch is too small to
+// fill the chip, so that the time of a call is the latency of one pair's chain of macro-steps.
+//
+// Same decomposition of Eq. (1) as the other sweep kernels (blocks of 2^BL x 2^BL refined cells sharing
+// one increment inner product p, a lane per block row, lanes on an anti-diagonal, bottom edges handed from
+// lane to lane by DPP; Section 3.3), with three changes that shorten the chain:
+//
+//  * Two waves per strip.  The stencil wave carries the recurrence and nothing else: per macro-step it reads
+//    the coefficients A(p), B(p) of its blocks from a ring in LDS, receives the edge of the lane above, and
+//    applies Eq. (1).  The coefficient wave of the strip computes p (the contraction of the lane's x
+//    increments with the column's y increments, Eq. (1) third line), A and B one chunk of macro-steps ahead
+//    and, in the reverse sweep, also maps dF/dp to the increment gradients one chunk behind (the linear map
+//    of Section 3.4).  Nothing on the coefficient wave's side depends on the recurrence.
+//  * M block rows per lane (a lane's column of M blocks is swept top to bottom inside one macro-step), so
+//    a strip covers 64 M block rows: fewer strips, fewer lane exchanges per cell.
+//  * No flags and no waits.  All waves of the workgroup advance in chunks of CH macro-steps separated by
+//    workgroup barriers; strip s + 1 runs LAG >= 63 + CH macro-steps behind strip s, so every value it reads
+//    from the hand-over row of strip s was written in an earlier chunk.  Hand-over rows hold a whole row
+//    of the grid in LDS (this mode is only planned when that fits).
+//
+// Every lane computes at every macro-step; there is no activity mask.  A lane whose column index
+// J = T - lane is outside [0, nb) gets p = 0 from the coefficient wave, i.e. A = B = 1: with the boundary
+// value 1 on all its inputs Eq. (1) returns exactly 1, so a lane that has not started yet carries the
+// boundary condition k = 1 by itself; a lane that has run past the last column computes values nobody
+// uses.  The strips are aligned to the bottom of the grid: the block rows that pad the first strip sit
+// above row 0, get p = 0 as well, and so hand the boundary row k[0, .] = 1 down to the first real row.
+//
+// Backward (Section 3.4): phase 1 is the forward sweep with a checkpoint of the lane state every 8
+// macro-steps; the hand-over rows stay in LDS.  Phase 2 is its exact mirror image in time: at mirrored step
+// T a lane recovers the nodes of its block column by inverting Eq. (1) from the right and bottom edges
+// (bottom edge: the top edge the lane below recovered one step earlier; for the strip's last lane the
+// exact row kept from phase 1), scatters the adjoint (first relation of Section 3.4) and forms dF/dp per
+// block (second relation).  Every 8 steps the forward state is replaced by the exact checkpoint, after
+// comparing the two: a relative difference above 1e-9 raises the error flag, and the finalisation then
+// returns NaN gradients instead of inaccurate ones.  Outside the grid the adjoint is exactly zero (the
+// seed dF/dk enters through the adjoint hand-over row under the last strip), and the products of zero with
+// the finite values computed there stay zero.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "sk_dev.h"
+#include "sk_kernels.h"
+
+namespace sk {
+
+#ifndef LK_EXP
+#define LK_EXP 0
+#endif
+typedef double real2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void chunk_barrier()
+{
+    // LDS traffic of this wave has completed; global traffic (checkpoints) may stay in flight
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ int clamp_col(int J, int hi)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(r) : "v"(J), "v"(hi));
+    return r;
+}
+
+template <int BL, int D, int M>
+struct Lock {
+    static constexpr int C = 1 << BL;
+    static constexpr int RR = M << BL;        // refined rows per lane
+    static constexpr int DSc = D | 1;         // row stride of the increment arrays (doubles)
+    static constexpr int NVC = RR + C + 2;    // checkpoint: right edge (RR+1), bottom edge (C), bottom-left corner
+    static constexpr int PADF = kWave * C;    // doubles in front of node column 0 of a hand-over row
+    static constexpr int CH1 = kLockCH1, CH2 = kLockCH2;
+    static constexpr int CR1 = CH1 * M * kWave * 2;   // doubles per half of the coefficient ring, forward
+    static constexpr int CR2 = CH2 * M * kWave * 4;   // ... reverse sweep
+    static constexpr int GPH = CH2 * M * kWave;       // doubles per half of the dF/dp ring
+
+    // ---------------- coefficient wave ----------------
+    struct Coef {
+        real dxr[M][D];
+        int nbl[M];
+        int lane, nbm1, rs2;
+        real tc;
+        const SK_LDS real* ylds;
+
+        __device__ __forceinline__ void setup(const SweepArgs& a, int strip, int lane_, const real* dxp,
+                                              const SK_LDS real* y)
+        {
+            lane = lane_; nbm1 = a.nb - 1; rs2 = a.rs2; tc = a.tc; ylds = y;
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int I = (strip * kWave + lane) * M + m - a.lk_padb;   // block row; < 0: above the grid
+                nbl[m] = I >= 0 ? a.nb : 0;
+                const real* xp = dxp + (long)((I >= 0 ? I : 0) >> a.rs1) * DSc;
+#pragma unroll
+                for (int c = 0; c < D; ++c) dxr[m][c] = I >= 0 ? a.sc * xp[c] : 0.0;
+            }
+        }
+        // y increments of the block column this lane is at in macro-step T
+        __device__ __forceinline__ void fetch(int T, int& J, int& b, real (&y)[D]) const
+        {
+            J = T - lane;
+            b = clamp_col(J, nbm1) >> rs2;
+            const SK_LDS real* yp = ylds + __mul24(b, DSc);
+#pragma unroll
+            for (int c = 0; c < D; ++c) y[c] = yp[c];
+        }
+        // p of block m (Eq. (1), third line); 0 outside the grid
+        __device__ __forceinline__ real inner(int m, int J, const real (&y)[D]) const
+        {
+            real p = tc;
+#pragma unroll
+            for (int c = 0; c < D; ++c) p = fma(dxr[m][c], y[c], p);
+            return (unsigned)J < (unsigned)nbl[m] ? p : 0.0;
+        }
+        // forward: (A, B) of the chunk of CH1 macro-steps starting at T0
+        __device__ __forceinline__ void produce_fwd(int T0, SK_LDS real* half) const
+        {
+            SK_LDS real* wp = half + lane * 2;
+            int J[2], b[2];
+            real y[2][D];
+            fetch(T0, J[0], b[0], y[0]);
+#pragma unroll
+            for (int i = 0; i < CH1; ++i) {
+                if (i + 1 < CH1) fetch(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);   // one step ahead
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const real p = inner(m, J[i & 1], y[i & 1]);
+                    const real q2 = p * p;
+                    const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+                    const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                    *(SK_LDS real2*)(wp + (i * M + m) * (kWave * 2)) = real2{Ac, Bc};
+                }
+            }
+        }
+        // reverse: (A, B, 1/B, p/6) of the chunk of CH2 macro-steps starting at T0
+        __device__ __forceinline__ void produce_rev(int T0, SK_LDS real* half) const
+        {
+            SK_LDS real* wp = half + lane * 4;
+            int J[2], b[2];
+            real y[2][D];
+            fetch(T0, J[0], b[0], y[0]);
+#pragma unroll
+            for (int i = 0; i < CH2; ++i) {
+                if (i + 1 < CH2) fetch(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const real p = inner(m, J[i & 1], y[i & 1]);
+                    const real q2 = p * p;
+                    const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+                    const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                    real invB = __builtin_amdgcn_rcp(Bc);
+                    invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+                    SK_LDS real* ep = wp + (i * M + m) * (kWave * 4);
+                    *(SK_LDS real2*)(ep) = real2{Ac, Bc};
+                    *(SK_LDS real2*)(ep + 2) = real2{invB, p * (1.0 / 6.0)};
+                }
+            }
+        }
+        // reverse: the linear map of Section 3.4 for the chunk starting at T0, from the dF/dp ring
+        __device__ __forceinline__ void consume_gp(int T0, const SK_LDS real* half, real (&gacc)[M][D],
+                                                   SK_LDS real* gy, bool want_gx, bool want_gy) const
+        {
+            const SK_LDS real* rp = half + lane;
+            int J[2], b[2];
+            real y[2][D], gv[2][M];
+            auto load = [&](int i) {
+                fetch(T0 + i, J[i & 1], b[i & 1], y[i & 1]);
+#pragma unroll
+                for (int m = 0; m < M; ++m) gv[i & 1][m] = rp[(i * M + m) * kWave];
+            };
+            load(0);
+#pragma unroll
+            for (int i = 0; i < CH2; ++i) {
+                if (i + 1 < CH2) load(i + 1);
+                real gp[M];
+#pragma unroll
+                for (int m = 0; m < M; ++m) gp[m] = (unsigned)J[i & 1] < (unsigned)nbl[m] ? gv[i & 1][m] : 0.0;
+                if (want_gx) {
+#pragma unroll
+                    for (int m = 0; m < M; ++m)
+#pragma unroll
+                        for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp[m], y[i & 1][c], gacc[m][c]);
+                }
+                if (want_gy) {
+                    SK_LDS real* gq = gy + __mul24(b[i & 1], DSc);
+#pragma unroll
+                    for (int c = 0; c < D; ++c) {
+                        real t = gp[0] * dxr[0][c];
+#pragma unroll
+                        for (int m = 1; m < M; ++m) t = fma(gp[m], dxr[m][c], t);
+                        lds_atomic_add(gq + c, t);
+                    }
+                }
+            }
+        }
+    };
+
+    // ---------------- stencil wave, forward ----------------
+    struct Fwd {
+        real left[RR + 1];   // right edge of the last block column, left[0] its top corner
+        real bot[C];         // bottom edge (without the left corner)
+        real blc;            // bottom-left corner
+
+        __device__ __forceinline__ void init()
+        {
+#pragma unroll
+            for (int i = 0; i <= RR; ++i) left[i] = 1.0;
+#pragma unroll
+            for (int i = 0; i < C; ++i) bot[i] = 1.0;
+            blc = 1.0;
+        }
+        // one macro-step: Eq. (1) on the RR x C cells of this lane's block column
+        __device__ __forceinline__ void step(const real (&recv)[C], const real (&Ac)[M], const real (&Bc)[M])
+        {
+            real top[C + 1];
+            top[0] = left[0];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) top[cc + 1] = recv[cc];
+#pragma unroll
+            for (int rr = 0; rr < RR; ++rr) {
+                const int m = rr >> BL;
+                real cur[C + 1];
+                cur[0] = left[rr + 1];
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) cur[cc + 1] = fma(cur[cc] + top[cc + 1], Ac[m], -(top[cc] * Bc[m]));
+                left[rr + 1] = cur[C];
+#pragma unroll
+                for (int cc = 0; cc <= C; ++cc) top[cc] = cur[cc];
+            }
+            blc = top[0];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) bot[cc] = top[cc + 1];
+            left[0] = recv[C - 1];
+        }
+        // chunk of CH1 macro-steps starting at T0
+        __device__ __forceinline__ void chunk(int T0, int lane, const SK_LDS real* half, const SK_LDS real* rowprev,
+                                              SK_LDS real* rowcur, SK_LDS real* dump)
+        {
+            const SK_LDS real* cp = half + lane * 2;
+            const SK_LDS real* ip = rowprev + T0 * C + 1;                          // lane 0's top edge
+            SK_LDS real* op = lane == kWave - 1 ? rowcur + (T0 - (kWave - 1)) * C + 1 : dump + lane * C;
+            constexpr int PF = 2;   // coefficient and edge reads are issued PF macro-steps ahead
+            real2 ab[CH1][M];
+            real edge[CH1][C];
+            auto load = [&](int i) {
+#pragma unroll
+                for (int m = 0; m < M; ++m) ab[i][m] = *(const SK_LDS real2*)(cp + (i * M + m) * (kWave * 2));
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) edge[i][cc] = ip[i * C + cc];
+            };
+#pragma unroll
+            for (int i = 0; i < PF; ++i) load(i);
+#pragma unroll
+            for (int i = 0; i < CH1; ++i) {
+                if (i + PF < CH1) load(i + PF);
+                real Ac[M], Bc[M];
+#pragma unroll
+                for (int m = 0; m < M; ++m) { Ac[m] = ab[i][m].x; Bc[m] = ab[i][m].y; }
+                real recv[C];
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(bot[cc], edge[i][cc]);
+                step(recv, Ac, Bc);
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) op[i * C + cc] = bot[cc];
+            }
+        }
+        __device__ __forceinline__ void store_ckpt(real* cp) const
+        {
+#pragma unroll
+            for (int i = 0; i <= RR; ++i) cp[i * kWave] = left[i];
+#pragma unroll
+            for (int i = 0; i < C; ++i) cp[(RR + 1 + i) * kWave] = bot[i];
+            cp[(RR + 1 + C) * kWave] = blc;
+        }
+    };
+
+    // ---------------- stencil wave, reverse ----------------
+    struct Rev {
+        real kR[RR + 1];     // forward values on the right edge of the block column to un-compute next
+        real ktop[C];        // recovered top edge, handed to the lane above
+        real accL[RR + 1];   // partial adjoints of the left edge nodes (index 0 unused)
+        real corner;         // partial adjoint of the top-left node
+        real up[C];          // adjoint contributions to the top edge nodes, handed to the lane above
+
+        __device__ __forceinline__ void init()
+        {
+#pragma unroll
+            for (int i = 0; i <= RR; ++i) { kR[i] = 1.0; accL[i] = 0.0; }
+#pragma unroll
+            for (int i = 0; i < C; ++i) { ktop[i] = 1.0; up[i] = 0.0; }
+            corner = 0.0;
+        }
+        __device__ __forceinline__ void step(const real (&recv)[C], const real (&recvk)[C], const real (&Ac)[M],
+                                             const real (&Bc)[M], const real (&iB)[M], const real (&p6)[M],
+                                             real (&accP)[M])
+        {
+            real e[RR + 1][C + 1], gn[RR + 1][C + 1];
+#pragma unroll
+            for (int rr = 0; rr <= RR; ++rr) e[rr][C] = kR[rr];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) e[RR][cc] = recvk[cc];
+#pragma unroll
+            for (int rr = 0; rr <= RR; ++rr)
+#pragma unroll
+                for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = 0.0;
+#pragma unroll
+            for (int rr = 1; rr <= RR; ++rr) gn[rr][C] = accL[rr];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) gn[RR][cc + 1] += recv[cc];
+            gn[0][C] = corner;
+#pragma unroll
+            for (int m = 0; m < M; ++m) accP[m] = 0.0;
+#pragma unroll
+            for (int rr = RR - 1; rr >= 0; --rr) {
+                const int m = rr >> BL;
+                const real dA = p6[m] + 0.5;   // A'(p)
+                const real dB = p6[m];         // -B'(p)
+#pragma unroll
+                for (int cc = C - 1; cc >= 0; --cc) {
+                    const real s = e[rr + 1][cc] + e[rr][cc + 1];
+                    e[rr][cc] = fma(s, Ac[m], -e[rr + 1][cc + 1]) * iB[m];   // Eq. (1) solved for its oldest term
+                    const real go = gn[rr + 1][cc + 1];
+                    gn[rr + 1][cc] = fma(go, Ac[m], gn[rr + 1][cc]);
+                    gn[rr][cc + 1] = fma(go, Ac[m], gn[rr][cc + 1]);
+                    gn[rr][cc] = fma(-go, Bc[m], gn[rr][cc]);
+                    const real loc = fma(s, dA, e[rr][cc] * dB);
+                    accP[m] = fma(go, loc, accP[m]);
+                }
+            }
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) { up[cc] = gn[0][cc + 1]; ktop[cc] = e[0][cc]; }
+            corner = gn[0][0];
+#pragma unroll
+            for (int rr = 1; rr <= RR; ++rr) accL[rr] = gn[rr][0];
+#pragma unroll
+            for (int rr = 0; rr <= RR; ++rr) kR[rr] = e[rr][0];
+        }
+        // chunk of CH2 mirrored macro-steps T0 + CH2 - 1 down to T0
+        __device__ __forceinline__ void chunk(int T0, int lane, const SK_LDS real* half, const SK_LDS real* arow_in,
+                                              const SK_LDS real* krow, SK_LDS real* arow_out, SK_LDS real* dump,
+                                              SK_LDS real* gphalf)
+        {
+            const SK_LDS real* cp = half + lane * 4;
+            const SK_LDS real* ap = arow_in + (T0 - (kWave - 1)) * C;   // feeds of the strip's last lane
+            const SK_LDS real* kp = krow + (T0 - (kWave - 1)) * C;
+            SK_LDS real* op = lane == 0 ? arow_out + T0 * C : dump + lane * C;
+            SK_LDS real* gw = gphalf + lane;
+            constexpr int PF = 2;
+            real2 ab[CH2][M], ip6[CH2][M];
+            real ea[CH2][C], ek[CH2][C];
+            auto load = [&](int i) {
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const SK_LDS real* ep = cp + (i * M + m) * (kWave * 4);
+                    ab[i][m] = *(const SK_LDS real2*)(ep);
+                    ip6[i][m] = *(const SK_LDS real2*)(ep + 2);
+                }
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) { ea[i][cc] = ap[i * C + cc]; ek[i][cc] = kp[i * C + cc]; }
+            };
+#pragma unroll
+            for (int i = CH2 - 1; i > CH2 - 1 - PF; --i) load(i);
+#pragma unroll
+            for (int i = CH2 - 1; i >= 0; --i) {
+                if (i - PF >= 0) load(i - PF);
+                real Ac[M], Bc[M], iB[M], p6[M], accP[M];
+#pragma unroll
+                for (int m = 0; m < M; ++m) { Ac[m] = ab[i][m].x; Bc[m] = ab[i][m].y; iB[m] = ip6[i][m].x; p6[m] = ip6[i][m].y; }
+                real recv[C], recvk[C];
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    recv[cc] = wave_from_below_or(up[cc], ea[i][cc]);
+                    recvk[cc] = wave_from_below_or(ktop[cc], ek[i][cc]);
+                }
+                step(recv, recvk, Ac, Bc, iB, p6, accP);
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) op[i * C + cc] = up[cc];
+#pragma unroll
+                for (int m = 0; m < M; ++m) gw[(i * M + m) * kWave] = accP[m];
+            }
+        }
+    };
+};
+
+// LDS carve-up shared by both kernels
+struct LockLds {
+    SK_LDS real* y;
+    SK_LDS real* gy;
+    SK_LDS real* cring;   // this strip's coefficient ring
+    SK_LDS real* gp;      // this strip's dF/dp ring
+    SK_LDS real* krows;
+    SK_LDS real* arows;
+    SK_LDS real* dump;
+};
+
+__device__ __forceinline__ LockLds carve_lock_lds(unsigned char* smem, const SweepArgs& a, int strip)
+{
+    LockLds l;
+    l.y = (SK_LDS real*)(smem + a.lk_off_y);
+    l.gy = (SK_LDS real*)(smem + a.lk_off_gy);
+    l.cring = (SK_LDS real*)(smem + a.lk_off_cring + (size_t)strip * a.lk_cring_stride);
+    l.gp = (SK_LDS real*)(smem + a.lk_off_gp + (size_t)strip * a.lk_gp_stride);
+    l.krows = (SK_LDS real*)(smem + a.lk_off_krows);
+    l.arows = (SK_LDS real*)(smem + a.lk_off_arows);
+    l.dump = (SK_LDS real*)(smem + a.lk_off_dump);
+    return l;
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+template <int BL, int D, int M>
+__global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_fwd_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using LK = Lock<BL, D, M>;
+    constexpr int C = LK::C, CH = LK::CH1;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ns = a.lk_ns;
+    const bool helper = w >= ns;
+    const int strip = helper ? w - ns : w;
+    const LockLds l = carve_lock_lds(smem, a, strip);
+    const long pid = blockIdx.x;
+    long xi, yi;
+    pair_ids(a, pid, xi, yi);
+    const real* dxp = a.dx + xi * a.xstride;
+    const real* dyg = a.dy + yi * a.ystride;
+    const int rowlen = a.lk_rowlen;
+
+    for (int t = threadIdx.x; t < a.q * LK::DSc; t += blockDim.x) l.y[t] = dyg[t];
+    for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) l.krows[t] = 1.0;
+    __syncthreads();
+
+    const int nck = a.lk_NT / CH;
+    const int lagc = kLockLag1 / CH;
+    const int niter = nck + (ns - 1) * lagc;
+    const SK_LDS real* rowprev = l.krows + strip * rowlen + LK::PADF;   // row above the strip (ones for strip 0)
+    SK_LDS real* rowcur = l.krows + (strip + 1) * rowlen + LK::PADF;
+
+    typename LK::Fwd f;
+    typename LK::Coef cf;
+    if (helper) cf.setup(a, strip, lane, dxp, l.y);
+    else f.init();
+
+    for (int g = -1; g < niter; ++g) {
+        const int lc = g - strip * lagc;
+        if (!helper) {
+#if LK_EXP != 2
+            if (lc >= 0 && lc < nck) f.chunk(lc * CH, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump);
+#endif
+        } else {
+            const int hc = lc + 1;
+#if LK_EXP != 1
+            if (hc >= 0 && hc < nck) cf.produce_fwd(hc * CH, l.cring + (hc & 1) * LK::CR1);
+#endif
+        }
+        chunk_barrier();
+    }
+    // k[m, n]: the last node of the last strip's bottom row
+    if (threadIdx.x == 0) a.k_out[pid] = l.krows[ns * rowlen + LK::PADF + a.nb * C];
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward
+// ------------------------------------------------------------------------------------------------
+template <int BL, int D, int M>
+__global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using LK = Lock<BL, D, M>;
+    constexpr int C = LK::C, RR = LK::RR, NVC = LK::NVC, CH1 = LK::CH1, CH2 = LK::CH2;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ns = a.lk_ns;
+    const bool helper = w >= ns;
+    const int strip = helper ? w - ns : w;
+    const LockLds l = carve_lock_lds(smem, a, strip);
+    const long pid = blockIdx.x;
+    long xi, yi;
+    pair_ids(a, pid, xi, yi);
+    const real* dxp = a.dx + xi * a.xstride;
+    const real* dyg = a.dy + yi * a.ystride;
+    real* gdx = a.gdx + xi * a.xstride;
+    real* gdy = a.gdy + yi * a.ystride;
+    const int rowlen = a.lk_rowlen;
+    const int nckS = a.lk_NT / kLockS;   // checkpoints per strip: nckS + 1
+    real* ckpt = a.ckpt + pid * a.ckpt_slot + (long)strip * (nckS + 1) * NVC * kWave + lane;
+
+    for (int t = threadIdx.x; t < a.q * LK::DSc; t += blockDim.x) { l.y[t] = dyg[t]; l.gy[t] = 0.0; }
+    for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) { l.krows[t] = 1.0; l.arows[t] = 0.0; }
+    __syncthreads();
+    // dF/dk[m, n] enters through the adjoint row under the last strip
+    if (threadIdx.x == 0) l.arows[ns * rowlen + LK::PADF + (a.nb - 1) * C + (C - 1)] = a.grad_k[pid];
+
+    const SK_LDS real* rowprev = l.krows + strip * rowlen + LK::PADF;
+    SK_LDS real* rowcur = l.krows + (strip + 1) * rowlen + LK::PADF;
+    const SK_LDS real* arow_in = l.arows + (strip + 1) * rowlen + LK::PADF;   // written by the strip below
+    SK_LDS real* arow_out = l.arows + strip * rowlen + LK::PADF;               // read by the strip above
+
+    typename LK::Coef cf;
+    if (helper) cf.setup(a, strip, lane, dxp, l.y);
+
+    // ---- phase 1: forward with checkpoints ----
+    {
+        typename LK::Fwd f;
+        f.init();
+        const int nck = a.lk_NT / CH1;
+        const int lagc = kLockLag1 / CH1;
+        const int niter = nck + (ns - 1) * lagc;
+        for (int g = -1; g < niter; ++g) {
+            const int lc = g - strip * lagc;
+            if (!helper) {
+                if (lc >= 0 && lc < nck) {
+                    f.store_ckpt(ckpt + (long)lc * NVC * kWave);   // kLockS == CH1: one checkpoint per chunk
+                    f.chunk(lc * CH1, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump);
+                    if (lc == nck - 1) f.store_ckpt(ckpt + (long)nck * NVC * kWave);
+                }
+            } else {
+                const int hc = lc + 1;
+                if (hc >= 0 && hc < nck) cf.produce_fwd(hc * CH1, l.cring + (hc & 1) * LK::CR1);
+            }
+            chunk_barrier();
+        }
+    }
+    if (threadIdx.x == 0 && a.k_out) a.k_out[pid] = l.krows[ns * rowlen + LK::PADF + a.nb * C];
+    __syncthreads();   // also completes the checkpoint stores before they are read back
+
+    // ---- phase 2: the mirror image ----
+    {
+        typename LK::Rev rv;
+        rv.init();
+        real gacc[M][D];
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+#pragma unroll
+            for (int c = 0; c < D; ++c) gacc[m][c] = 0.0;
+        const int nck = a.lk_NT / CH2;
+        const int lagc = kLockLag2 / CH2;
+        const int niter = nck + (ns - 1) * lagc;
+        const int rs = ns - 1 - strip;   // strips start bottom-up
+        bool drift = false;
+        // checkpoint prefetch, two segments ahead: buffer (idx & 1) holds checkpoint idx
+        real cb[2][NVC];
+        const int up1 = lane > 0 ? -1 : 0;   // lane l also needs the bottom edge of lane l - 1
+        auto load_ckpt = [&](int idx, real (&dst)[NVC]) {
+            const real* cp = ckpt + (long)idx * NVC * kWave;
+#pragma unroll
+            for (int q = 0; q <= RR; ++q) dst[q] = ld_scratch(cp + q * kWave);
+            dst[RR + 1] = ld_scratch(cp + (RR + 1 + C) * kWave + up1);                                // corner
+#pragma unroll
+            for (int q = 1; q < C; ++q) dst[RR + 1 + q] = ld_scratch(cp + (RR + 1 + q - 1) * kWave + up1);
+        };
+        if (!helper) {
+            if (nckS & 1) { load_ckpt(nckS, cb[1]); load_ckpt(nckS - 1, cb[0]); }
+            else { load_ckpt(nckS, cb[0]); load_ckpt(nckS - 1, cb[1]); }
+        }
+        auto rev_chunk = [&](auto restore_c, auto buf_c, int fc, int rc) {
+            constexpr bool RESTORE = decltype(restore_c)::value;
+            constexpr int BUF = decltype(buf_c)::value;
+            if constexpr (RESTORE) {
+                const int idx = (fc + 1) / 2;
+                if (rc > 0) {
+#pragma unroll
+                    for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
+                        if (!(fma(fabs(cb[BUF][i]), -1e-9, fabs(rv.kR[i] - cb[BUF][i])) <= 1e-9)) drift = true;
+                }
+#pragma unroll
+                for (int i = 0; i <= RR; ++i) rv.kR[i] = cb[BUF][i];
+#pragma unroll
+                for (int i = 0; i < C; ++i) rv.ktop[i] = cb[BUF][RR + 1 + i];
+                if (idx >= 2) load_ckpt(idx - 2, cb[BUF]);
+            }
+            rv.chunk(fc * CH2, lane, l.cring + (rc & 1) * LK::CR2, arow_in, rowcur, arow_out, l.dump,
+                     l.gp + (rc & 1) * LK::GPH);
+        };
+        for (int g = -1; g <= niter; ++g) {
+            const int rc = g - rs * lagc;
+            if (!helper) {
+                if (LK_EXP != 3 && rc >= 0 && rc < nck) {
+                    const int fc = nck - 1 - rc;
+                    if (fc & 1) {
+                        if (((fc + 1) / 2) & 1) rev_chunk(std::true_type(), std::integral_constant<int, 1>(), fc, rc);
+                        else rev_chunk(std::true_type(), std::integral_constant<int, 0>(), fc, rc);
+                    } else {
+                        rev_chunk(std::false_type(), std::integral_constant<int, 0>(), fc, rc);
+                    }
+                }
+            } else {
+                const int hc = rc + 1, gc = rc - 1;
+                if (LK_EXP != 4 && hc >= 0 && hc < nck) cf.produce_rev((nck - 1 - hc) * CH2, l.cring + (hc & 1) * LK::CR2);
+                if (LK_EXP != 4 && LK_EXP != 5 && gc >= 0 && gc < nck)
+                    cf.consume_gp((nck - 1 - gc) * CH2, l.gp + (gc & 1) * LK::GPH, gacc, l.gy, a.want_gx != 0,
+                                  a.want_gy != 0);
+            }
+            chunk_barrier();
+        }
+        if (!helper) {
+            if (drift) atomicExch(a.err, 2);
+        } else if (a.want_gx) {
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int I = (strip * kWave + lane) * M + m - a.lk_padb;
+                if (I >= 0) {
+                    real* gq = gdx + (long)(I >> a.rs1) * LK::DSc;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (a.want_gy) {
+        const int n = a.q * LK::DSc;
+        for (int t = threadIdx.x; t < n; t += blockDim.x) {
+            const real v = l.gy[t];
+            if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+template <int BL, int D, int M>
+hipError_t launch_lock_one(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    hipError_t e;
+    const int threads = 2 * a.lk_ns * kWave;
+    if (backward) {
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M>), dim3(grid), dim3(threads), lds, st, a);
+    } else {
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL((lock_fwd_kernel<BL, D, M>), dim3(grid), dim3(threads), lds, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <int BL, int D>
+hipError_t launch_lock_m(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.lk_M == 1) {
+#ifndef SK_ONLY_C2
+        return launch_lock_one<BL, D, 1>(backward, a, grid, lds, st);
+#endif
+    } else if (a.lk_M == 2) {
+        if constexpr (BL < 2) return launch_lock_one<BL, D, 2>(backward, a, grid, lds, st);
+        else if (!backward) return launch_lock_one<BL, D, 2>(backward, a, grid, lds, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int BL>
+hipError_t launch_lock_bl(bool backward, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    switch (DT) {
+#ifndef SK_ONLY_C2   /* development builds instantiate a single shape */
+        case 2: return launch_lock_m<BL, 2>(backward, a, grid, lds, st);
+        case 3: return launch_lock_m<BL, 3>(backward, a, grid, lds, st);
+        case 4: return launch_lock_m<BL, 4>(backward, a, grid, lds, st);
+        case 6: return launch_lock_m<BL, 6>(backward, a, grid, lds, st);
+        case 8: return launch_lock_m<BL, 8>(backward, a, grid, lds, st);
+        case 16: return launch_lock_m<BL, 16>(backward, a, grid, lds, st);
+#endif
+        case 5: return launch_lock_m<BL, 5>(backward, a, grid, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
+                                 hipStream_t st)
+{
+    if (a.lk_ns < 1 || a.lk_ns > kLockMaxStrips || (a.lk_NT & 7) != 0) return hipErrorInvalidValue;
+    switch (BL) {
+#ifndef SK_ONLY_C2
+        case 0: return launch_lock_bl<0>(backward, DT, a, grid, lds, st);
+        case 2: return launch_lock_bl<2>(backward, DT, a, grid, lds, st);
+#endif
+        case 1: return launch_lock_bl<1>(backward, DT, a, grid, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sk

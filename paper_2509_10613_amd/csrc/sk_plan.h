@@ -55,7 +55,18 @@ struct Plan {
     int coop = 0, nw = 0, RB = 0, CH = 0;
     int uncompute = 0;   // backward: reverse sweep recovers forward values by inverting Eq. (1) (no replay ring)
     size_t coop_off_gdy = 0, coop_off_flags = 0, coop_off_obox = 0, coop_off_ring = 0, coop_ring_stride = 0;
+    // lock-step mode: one workgroup per pair, per strip one stencil wave and one coefficient wave
+    int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
+    size_t lk_off_y = 0, lk_off_gy = 0, lk_off_cring = 0, lk_off_gp = 0, lk_off_krows = 0, lk_off_arows = 0,
+           lk_off_dump = 0, lk_cring_stride = 0, lk_gp_stride = 0;
 };
+
+// Lock-step mode constants: chunk lengths (macro-steps between workgroup barriers) of the forward and the
+// reverse sweep, checkpoint spacing, and the lag between consecutive strips.  A value written to a hand-over
+// row in one chunk is read by the neighbouring strip in a later chunk if lag >= 63 + chunk.
+constexpr int kLockCH1 = 8, kLockCH2 = 4, kLockS = 8;
+constexpr int kLockLag1 = 72, kLockLag2 = 68;
+constexpr int kLockMaxStrips = 4;
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
@@ -172,6 +183,48 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.nslots = (int64_t)p.grid * kWavesPerWG;
     }
 
+    // Lock-step mode replaces the modes above when every pair can have a workgroup of its own resident at
+    // once: the chip is then under-filled and the time of a call is the latency of one pair's chain of
+    // macro-steps, which this mode shortens (fewer instructions in the wave that carries the recurrence,
+    // fewer strips, no waits).
+    if (p.DT != 0 && (!backward || p.uncompute)) {
+        const int maxM = (backward && p.BL == 2) ? 1 : 2;
+        int M = 1;
+        while (M < maxM && (p.mb + kWave * M - 1) / (kWave * M) > 2) M *= 2;
+        const int lns = (p.mb + kWave * M - 1) / (kWave * M);
+        const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
+        const int lrow = (int)align_up((size_t)kWave * C + (size_t)NT * C + C + 2, 2);
+        size_t used = 0;
+        auto lds_take = [&](size_t bytes) { size_t o = used; used = align_up(used + bytes, 256); return o; };
+        const size_t ycopy = (size_t)p.q * p.DP * elem;
+        const size_t o_y = lds_take(ycopy);
+        const size_t o_gy = backward ? lds_take(ycopy) : 0;
+        const size_t cstride = (size_t)16384 * M;   // 2 chunks x (8 steps x 16 B | 4 steps x 32 B) x 64 lanes x M
+        const size_t o_cr = lds_take(cstride * lns);
+        const size_t gstride = (size_t)2 * kLockCH2 * M * kWave * elem;
+        const size_t o_gp = backward ? lds_take(gstride * lns) : 0;
+        const size_t o_kr = lds_take((size_t)(lns + 1) * lrow * elem);
+        const size_t o_ar = backward ? lds_take((size_t)(lns + 1) * lrow * elem) : 0;
+        const size_t o_dump = lds_take((size_t)(kWave + 8) * C * elem);
+        int wgpc = used ? (int)(kLdsPerCU / used) : 0;
+        if (wgpc * 2 * lns > 16) wgpc = 16 / (2 * lns);
+        if (lns <= kLockMaxStrips && used <= kLdsPerCU - 1024 && wgpc >= 1 && p.npairs <= (int64_t)kNumCU * wgpc) {
+            p.lock = 1; p.coop = 0;
+            p.lk_M = M; p.lk_ns = lns; p.lk_NT = NT; p.lk_rowlen = lrow;
+            p.lk_padb = lns * kWave * M - p.mb;
+            p.lk_off_y = o_y; p.lk_off_gy = o_gy; p.lk_off_cring = o_cr; p.lk_off_gp = o_gp;
+            p.lk_off_krows = o_kr; p.lk_off_arows = o_ar; p.lk_off_dump = o_dump;
+            p.lk_cring_stride = cstride; p.lk_gp_stride = gstride;
+            p.y_lds = 1;
+            p.lds_wave = 0;
+            p.lds_bytes = align_up(used, 256);
+            p.grid = (int)p.npairs;
+            p.nslots = p.npairs;
+            p.S = kLockS;
+            p.nseg = NT / kLockS;
+        }
+    }
+
     // Workspace layout (all offsets 256-byte aligned).
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -184,8 +237,9 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.off_gdyT = symmetric ? p.off_gdxT : take((size_t)ny * p.ystride * elem);
         p.adj_slot = 4 * (int64_t)p.rowlen;   // two rows of 2C values per block column
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
-        const int NVC = R + C + 2;   // lane state kept per checkpoint
-        p.ckpt_slot = (int64_t)p.ns * (p.nseg + 1) * NVC * kWave;
+        // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
+        const int NVC = p.lock ? p.lk_M * R + C + 2 : R + C + 2;
+        p.ckpt_slot = (int64_t)(p.lock ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
     }
     if (io_elem != elem) {
