@@ -44,9 +44,6 @@
 
 namespace sk {
 
-#ifndef LK_EXP
-#define LK_EXP 0
-#endif
 typedef double real2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void chunk_barrier()
@@ -78,73 +75,110 @@ struct Lock {
     struct Coef {
         real dxr[M][D];
         int nbl[M];
-        int lane, nbm1, rs2;
-        real tc;
+        int lane, nb, nbm1, rs2;
+        real tcm[M];   // the time channel's constant product; 0 for block rows above the grid
         const SK_LDS real* ylds;
 
         __device__ __forceinline__ void setup(const SweepArgs& a, int strip, int lane_, const real* dxp,
                                               const SK_LDS real* y)
         {
-            lane = lane_; nbm1 = a.nb - 1; rs2 = a.rs2; tc = a.tc; ylds = y;
+            lane = lane_; nb = a.nb; nbm1 = a.nb - 1; rs2 = a.rs2; ylds = y;
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 const int I = (strip * kWave + lane) * M + m - a.lk_padb;   // block row; < 0: above the grid
                 nbl[m] = I >= 0 ? a.nb : 0;
+                tcm[m] = I >= 0 ? a.tc : 0.0;
                 const real* xp = dxp + (long)((I >= 0 ? I : 0) >> a.rs1) * DSc;
 #pragma unroll
                 for (int c = 0; c < D; ++c) dxr[m][c] = I >= 0 ? a.sc * xp[c] : 0.0;
             }
         }
+        // A chunk of macro-steps [T0, T0 + n) is interior if every lane's column T - lane lies inside the grid:
+        // then no clamping and no masking is needed (rows above the grid have zero increments and a zero
+        // time constant, hence p = 0 anyway).
+        __device__ __forceinline__ bool interior(int T0, int n) const { return T0 >= kWave - 1 && T0 + n <= nb; }
         // y increments of the block column this lane is at in macro-step T
+        template <bool EDGE>
         __device__ __forceinline__ void fetch(int T, int& J, int& b, real (&y)[D]) const
         {
             J = T - lane;
-            b = clamp_col(J, nbm1) >> rs2;
+            b = (EDGE ? clamp_col(J, nbm1) : J) >> rs2;
             const SK_LDS real* yp = ylds + __mul24(b, DSc);
 #pragma unroll
             for (int c = 0; c < D; ++c) y[c] = yp[c];
         }
         // p of block m (Eq. (1), third line); 0 outside the grid
+        template <bool EDGE>
         __device__ __forceinline__ real inner(int m, int J, const real (&y)[D]) const
         {
-            real p = tc;
+            real p = tcm[m];
 #pragma unroll
             for (int c = 0; c < D; ++c) p = fma(dxr[m][c], y[c], p);
-            return (unsigned)J < (unsigned)nbl[m] ? p : 0.0;
+            if constexpr (EDGE) return (unsigned)J < (unsigned)nbl[m] ? p : 0.0;
+            else return p;
         }
         // forward: (A, B) of the chunk of CH1 macro-steps starting at T0
-        __device__ __forceinline__ void produce_fwd(int T0, SK_LDS real* half) const
+        // part 0: every macro-step of the chunk; part 1 / 2: the even / odd ones (two coefficient waves share a
+        // strip).  The y reads of all steps are issued before the arithmetic (PFY steps at a time).
+        __device__ __forceinline__ void produce_fwd(int T0, SK_LDS real* half, int part) const
+        {
+            const bool in = interior(T0, CH1);
+            if (part == 0) {
+                if (in) produce_fwd_t<false, 0, 1>(T0, half); else produce_fwd_t<true, 0, 1>(T0, half);
+            } else if (part == 1) {
+                if (in) produce_fwd_t<false, 0, 2>(T0, half); else produce_fwd_t<true, 0, 2>(T0, half);
+            } else {
+                if (in) produce_fwd_t<false, 1, 2>(T0, half); else produce_fwd_t<true, 1, 2>(T0, half);
+            }
+        }
+        template <bool EDGE, int I0, int IS>
+        __device__ __forceinline__ void produce_fwd_t(int T0, SK_LDS real* half) const
         {
             SK_LDS real* wp = half + lane * 2;
-            int J[2], b[2];
-            real y[2][D];
-            fetch(T0, J[0], b[0], y[0]);
+            constexpr int NSTEP = (CH1 - I0 + IS - 1) / IS;   // steps handled by this wave
+            constexpr int PFY = D <= 8 ? 4 : 2;               // steps whose y reads are in flight together
 #pragma unroll
-            for (int i = 0; i < CH1; ++i) {
-                if (i + 1 < CH1) fetch(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);   // one step ahead
+            for (int g0 = 0; g0 < NSTEP; g0 += PFY) {
+                int J[PFY], b[PFY];
+                real y[PFY][D];
 #pragma unroll
-                for (int m = 0; m < M; ++m) {
-                    const real p = inner(m, J[i & 1], y[i & 1]);
-                    const real q2 = p * p;
-                    const real Bc = fma(q2, -1.0 / 12.0, 1.0);
-                    const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                    *(SK_LDS real2*)(wp + (i * M + m) * (kWave * 2)) = real2{Ac, Bc};
+                for (int u = 0; u < PFY; ++u)
+                    if (g0 + u < NSTEP) fetch<EDGE>(T0 + I0 + (g0 + u) * IS, J[u], b[u], y[u]);
+#pragma unroll
+                for (int u = 0; u < PFY; ++u) {
+                    if (g0 + u < NSTEP) {
+                        const int i = I0 + (g0 + u) * IS;
+#pragma unroll
+                        for (int m = 0; m < M; ++m) {
+                            const real p = inner<EDGE>(m, J[u], y[u]);
+                            const real q2 = p * p;
+                            const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+                            const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                            *(SK_LDS real2*)(wp + (i * M + m) * (kWave * 2)) = real2{Ac, Bc};
+                        }
+                    }
                 }
             }
         }
         // reverse: (A, B, 1/B, p/6) of the chunk of CH2 macro-steps starting at T0
         __device__ __forceinline__ void produce_rev(int T0, SK_LDS real* half) const
         {
+            if (interior(T0, CH2)) produce_rev_t<false>(T0, half);
+            else produce_rev_t<true>(T0, half);
+        }
+        template <bool EDGE>
+        __device__ __forceinline__ void produce_rev_t(int T0, SK_LDS real* half) const
+        {
             SK_LDS real* wp = half + lane * 4;
             int J[2], b[2];
             real y[2][D];
-            fetch(T0, J[0], b[0], y[0]);
+            fetch<EDGE>(T0, J[0], b[0], y[0]);
 #pragma unroll
             for (int i = 0; i < CH2; ++i) {
-                if (i + 1 < CH2) fetch(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);
+                if (i + 1 < CH2) fetch<EDGE>(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    const real p = inner(m, J[i & 1], y[i & 1]);
+                    const real p = inner<EDGE>(m, J[i & 1], y[i & 1]);
                     const real q2 = p * p;
                     const real Bc = fma(q2, -1.0 / 12.0, 1.0);
                     const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
@@ -156,40 +190,92 @@ struct Lock {
                 }
             }
         }
-        // reverse: the linear map of Section 3.4 for the chunk starting at T0, from the dF/dp ring
-        __device__ __forceinline__ void consume_gp(int T0, const SK_LDS real* half, real (&gacc)[M][D],
-                                                   SK_LDS real* gy, bool want_gx, bool want_gy) const
+        // reverse: the linear map of Section 3.4 for the chunk starting at T0, from the dF/dp ring.
+        // x side: this lane's rows accumulate in registers.
+        __device__ __forceinline__ void consume_gx(int T0, const SK_LDS real* half, real (&gacc)[M][D]) const
+        {
+            if (interior(T0, CH2)) consume_gx_t<false>(T0, half, gacc);
+            else consume_gx_t<true>(T0, half, gacc);
+        }
+        template <bool EDGE>
+        __device__ __forceinline__ void consume_gx_t(int T0, const SK_LDS real* half, real (&gacc)[M][D]) const
         {
             const SK_LDS real* rp = half + lane;
-            int J[2], b[2];
-            real y[2][D], gv[2][M];
-            auto load = [&](int i) {
-                fetch(T0 + i, J[i & 1], b[i & 1], y[i & 1]);
+            constexpr int PFY = D <= 8 ? CH2 : 2;
 #pragma unroll
-                for (int m = 0; m < M; ++m) gv[i & 1][m] = rp[(i * M + m) * kWave];
-            };
-            load(0);
+            for (int g0 = 0; g0 < CH2; g0 += PFY) {
+                int J[PFY], b[PFY];
+                real y[PFY][D], gv[PFY][M];
+#pragma unroll
+                for (int u = 0; u < PFY; ++u) {
+                    fetch<EDGE>(T0 + g0 + u, J[u], b[u], y[u]);
+#pragma unroll
+                    for (int m = 0; m < M; ++m) gv[u][m] = rp[((g0 + u) * M + m) * kWave];
+                }
+#pragma unroll
+                for (int u = 0; u < PFY; ++u)
+#pragma unroll
+                    for (int m = 0; m < M; ++m) {
+                        // outside the grid dF/dp is not zero on the left (the adjoint has left the grid there);
+                        // rows above the grid are never flushed
+                        const real gp = (!EDGE || (unsigned)J[u] < (unsigned)nbl[m]) ? gv[u][m] : 0.0;
+#pragma unroll
+                        for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp, y[u][c], gacc[m][c]);
+                    }
+            }
+        }
+        // y side: the column's accumulator row in LDS.
+        __device__ __forceinline__ void consume_gy(int T0, const SK_LDS real* half, SK_LDS real* gy) const
+        {
+            // rs2 == 0: the 64 lanes are at 64 different columns, so a plain read-modify-write of the column's
+            // accumulator row cannot collide inside the wave; the wave of the neighbouring strip works
+            // kLockLag2 columns away in the same chunk.
+            const bool plain = rs2 == 0;
+            if (interior(T0, CH2)) {
+                if (plain) consume_gy_t<false, true>(T0, half, gy); else consume_gy_t<false, false>(T0, half, gy);
+            } else {
+                if (plain) consume_gy_t<true, true>(T0, half, gy); else consume_gy_t<true, false>(T0, half, gy);
+            }
+        }
+        template <bool EDGE, bool PLAIN>
+        __device__ __forceinline__ void consume_gy_t(int T0, const SK_LDS real* half, SK_LDS real* gy) const
+        {
+            const SK_LDS real* rp = half + lane;
+            real gv[CH2][M];
+#pragma unroll
+            for (int i = 0; i < CH2; ++i)
+#pragma unroll
+                for (int m = 0; m < M; ++m) gv[i][m] = rp[(i * M + m) * kWave];
 #pragma unroll
             for (int i = 0; i < CH2; ++i) {
-                if (i + 1 < CH2) load(i + 1);
-                real gp[M];
+                const int J = T0 + i - lane;
+                const int b = (EDGE ? clamp_col(J, nbm1) : J) >> rs2;
+                SK_LDS real* gq = gy + __mul24(b, DSc);
+                real t[D];
 #pragma unroll
-                for (int m = 0; m < M; ++m) gp[m] = (unsigned)J[i & 1] < (unsigned)nbl[m] ? gv[i & 1][m] : 0.0;
-                if (want_gx) {
+                for (int c = 0; c < D; ++c) {
+                    // rows above the grid have zero increments
+                    real v = 0.0;
 #pragma unroll
-                    for (int m = 0; m < M; ++m)
-#pragma unroll
-                        for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp[m], y[i & 1][c], gacc[m][c]);
-                }
-                if (want_gy) {
-                    SK_LDS real* gq = gy + __mul24(b[i & 1], DSc);
-#pragma unroll
-                    for (int c = 0; c < D; ++c) {
-                        real t = gp[0] * dxr[0][c];
-#pragma unroll
-                        for (int m = 1; m < M; ++m) t = fma(gp[m], dxr[m][c], t);
-                        lds_atomic_add(gq + c, t);
+                    for (int m = 0; m < M; ++m) {
+                        const real gp = (!EDGE || (unsigned)J < (unsigned)nbl[m]) ? gv[i][m] : 0.0;
+                        v = m == 0 ? gp * dxr[0][c] : fma(gp, dxr[m][c], v);
                     }
+                    t[c] = v;
+                }
+                if constexpr (PLAIN) {
+                    // lanes whose column was clamped into the grid must not touch a row that another lane owns;
+                    // the step after this one reads what this one wrote (the lane above moves to this column)
+                    if (!EDGE || (unsigned)J < (unsigned)nb) {
+                        real o[D];
+#pragma unroll
+                        for (int c = 0; c < D; ++c) o[c] = gq[c];
+#pragma unroll
+                        for (int c = 0; c < D; ++c) gq[c] = o[c] + t[c];
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < D; ++c) lds_atomic_add(gq + c, t[c]);
                 }
             }
         }
@@ -382,6 +468,25 @@ struct Lock {
     };
 };
 
+// Roles of the waves of a workgroup.  Waves w and w + 4 of a workgroup share a SIMD, so the stencil waves
+// (which carry the serial chain) get the low indices and, for up to two strips, a SIMD of their own; the
+// coefficient and gradient waves of two strips share the other two SIMDs.
+// Role kRoleCoef computes the coefficients of the strip; kRoleAux is its second helper wave: in forward
+// sweeps it takes over half of the coefficient work (then kRoleCoef does the other half), in the reverse sweep
+// it maps dF/dp to the increment gradients.
+enum { kRoleStencil = 0, kRoleCoef = 1, kRoleAux = 2, kRoleIdle = 3 };
+__host__ __device__ inline int lock_waves(int ns) { return ns == 1 ? 3 : (ns == 2 ? 8 : 12); }
+__device__ __forceinline__ void lock_role(int w, int ns, int& role, int& strip)
+{
+    role = kRoleIdle;
+    strip = 0;
+    if (w < ns) { role = kRoleStencil; strip = w; return; }
+    const int c0 = ns <= 2 ? ns : 4;                    // first coefficient wave
+    if (w >= c0 && w < c0 + ns) { role = kRoleCoef; strip = w - c0; return; }
+    const int g0 = ns == 1 ? 2 : (ns == 2 ? 6 : 8);     // first auxiliary wave
+    if (w >= g0 && w < g0 + ns) { role = kRoleAux; strip = w - g0; }
+}
+
 // LDS carve-up shared by both kernels
 struct LockLds {
     SK_LDS real* y;
@@ -410,7 +515,7 @@ __device__ __forceinline__ LockLds carve_lock_lds(unsigned char* smem, const Swe
 // forward
 // ------------------------------------------------------------------------------------------------
 template <int BL, int D, int M>
-__global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_fwd_kernel(SweepArgs a)
+__global__ __launch_bounds__(12 * kWave) void lock_fwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     using LK = Lock<BL, D, M>;
@@ -418,8 +523,8 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_fwd_kernel(Sw
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ns = a.lk_ns;
-    const bool helper = w >= ns;
-    const int strip = helper ? w - ns : w;
+    int role, strip;
+    lock_role(w, ns, role, strip);
     const LockLds l = carve_lock_lds(smem, a, strip);
     const long pid = blockIdx.x;
     long xi, yi;
@@ -440,20 +545,18 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_fwd_kernel(Sw
 
     typename LK::Fwd f;
     typename LK::Coef cf;
-    if (helper) cf.setup(a, strip, lane, dxp, l.y);
+    constexpr int kSplit = 1;   // two coefficient waves per strip
+    if (role == kRoleCoef || role == kRoleAux) cf.setup(a, strip, lane, dxp, l.y);
     else f.init();
 
     for (int g = -1; g < niter; ++g) {
         const int lc = g - strip * lagc;
-        if (!helper) {
-#if LK_EXP != 2
+        if (role == kRoleStencil) {
             if (lc >= 0 && lc < nck) f.chunk(lc * CH, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump);
-#endif
-        } else {
+        } else if (role == kRoleCoef || (kSplit && role == kRoleAux)) {
             const int hc = lc + 1;
-#if LK_EXP != 1
-            if (hc >= 0 && hc < nck) cf.produce_fwd(hc * CH, l.cring + (hc & 1) * LK::CR1);
-#endif
+            if (hc >= 0 && hc < nck)
+                cf.produce_fwd(hc * CH, l.cring + (hc & 1) * LK::CR1, kSplit ? (role == kRoleCoef ? 1 : 2) : 0);
         }
         chunk_barrier();
     }
@@ -464,17 +567,24 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_fwd_kernel(Sw
 // ------------------------------------------------------------------------------------------------
 // backward
 // ------------------------------------------------------------------------------------------------
+#ifdef LK_PROF
+#define LKP_T() __builtin_readcyclecounter()
+#endif
 template <int BL, int D, int M>
-__global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(SweepArgs a)
+__global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
 {
+#ifdef LK_PROF
+    long long pw[2] = {0, 0}, pb[2] = {0, 0}, pt0 = LKP_T(), ptm = 0;
+#endif
     extern __shared__ __align__(16) unsigned char smem[];
     using LK = Lock<BL, D, M>;
     constexpr int C = LK::C, RR = LK::RR, NVC = LK::NVC, CH1 = LK::CH1, CH2 = LK::CH2;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ns = a.lk_ns;
-    const bool helper = w >= ns;
-    const int strip = helper ? w - ns : w;
+    int role, strip;
+    lock_role(w, ns, role, strip);
+    const bool stencil = role == kRoleStencil;
     const LockLds l = carve_lock_lds(smem, a, strip);
     const long pid = blockIdx.x;
     long xi, yi;
@@ -499,7 +609,8 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(Sw
     SK_LDS real* arow_out = l.arows + strip * rowlen + LK::PADF;               // read by the strip above
 
     typename LK::Coef cf;
-    if (helper) cf.setup(a, strip, lane, dxp, l.y);
+    constexpr int kSplit = 1;   // two coefficient waves per strip in the forward phase
+    if (role == kRoleCoef || role == kRoleAux) cf.setup(a, strip, lane, dxp, l.y);
 
     // ---- phase 1: forward with checkpoints ----
     {
@@ -510,19 +621,33 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(Sw
         const int niter = nck + (ns - 1) * lagc;
         for (int g = -1; g < niter; ++g) {
             const int lc = g - strip * lagc;
-            if (!helper) {
+#ifdef LK_PROF
+            const long long ta = LKP_T();
+#endif
+            if (stencil) {
                 if (lc >= 0 && lc < nck) {
                     f.store_ckpt(ckpt + (long)lc * NVC * kWave);   // kLockS == CH1: one checkpoint per chunk
                     f.chunk(lc * CH1, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump);
                     if (lc == nck - 1) f.store_ckpt(ckpt + (long)nck * NVC * kWave);
                 }
-            } else {
+            } else if (role == kRoleCoef || (kSplit && role == kRoleAux)) {
                 const int hc = lc + 1;
-                if (hc >= 0 && hc < nck) cf.produce_fwd(hc * CH1, l.cring + (hc & 1) * LK::CR1);
+                if (hc >= 0 && hc < nck)
+                    cf.produce_fwd(hc * CH1, l.cring + (hc & 1) * LK::CR1, kSplit ? (role == kRoleCoef ? 1 : 2) : 0);
             }
+#ifdef LK_PROF
+            const long long tb = LKP_T();
             chunk_barrier();
+            const long long tc2 = LKP_T();
+            pw[0] += tb - ta; pb[0] += tc2 - tb;
+#else
+            chunk_barrier();
+#endif
         }
     }
+#ifdef LK_PROF
+    ptm = LKP_T();
+#endif
     if (threadIdx.x == 0 && a.k_out) a.k_out[pid] = l.krows[ns * rowlen + LK::PADF + a.nb * C];
     __syncthreads();   // also completes the checkpoint stores before they are read back
 
@@ -551,7 +676,7 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(Sw
 #pragma unroll
             for (int q = 1; q < C; ++q) dst[RR + 1 + q] = ld_scratch(cp + (RR + 1 + q - 1) * kWave + up1);
         };
-        if (!helper) {
+        if (stencil) {
             if (nckS & 1) { load_ckpt(nckS, cb[1]); load_ckpt(nckS - 1, cb[0]); }
             else { load_ckpt(nckS, cb[0]); load_ckpt(nckS - 1, cb[1]); }
         }
@@ -576,8 +701,11 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(Sw
         };
         for (int g = -1; g <= niter; ++g) {
             const int rc = g - rs * lagc;
-            if (!helper) {
-                if (LK_EXP != 3 && rc >= 0 && rc < nck) {
+#ifdef LK_PROF
+            const long long ta = LKP_T();
+#endif
+            if (stencil) {
+                if (rc >= 0 && rc < nck) {
                     const int fc = nck - 1 - rc;
                     if (fc & 1) {
                         if (((fc + 1) / 2) & 1) rev_chunk(std::true_type(), std::integral_constant<int, 1>(), fc, rc);
@@ -586,18 +714,35 @@ __global__ __launch_bounds__(2 * kLockMaxStrips * kWave) void lock_bwd_kernel(Sw
                         rev_chunk(std::false_type(), std::integral_constant<int, 0>(), fc, rc);
                     }
                 }
-            } else {
+            } else if (role == kRoleCoef) {
                 const int hc = rc + 1, gc = rc - 1;
-                if (LK_EXP != 4 && hc >= 0 && hc < nck) cf.produce_rev((nck - 1 - hc) * CH2, l.cring + (hc & 1) * LK::CR2);
-                if (LK_EXP != 4 && LK_EXP != 5 && gc >= 0 && gc < nck)
-                    cf.consume_gp((nck - 1 - gc) * CH2, l.gp + (gc & 1) * LK::GPH, gacc, l.gy, a.want_gx != 0,
-                                  a.want_gy != 0);
+                if (hc >= 0 && hc < nck) cf.produce_rev((nck - 1 - hc) * CH2, l.cring + (hc & 1) * LK::CR2);
+                if (a.want_gx && gc >= 0 && gc < nck)
+                    cf.consume_gx((nck - 1 - gc) * CH2, l.gp + (gc & 1) * LK::GPH, gacc);
+            } else if (role == kRoleAux) {
+                const int gc = rc - 1;
+                if (a.want_gy && gc >= 0 && gc < nck) cf.consume_gy((nck - 1 - gc) * CH2, l.gp + (gc & 1) * LK::GPH, l.gy);
             }
+#ifdef LK_PROF
+            const long long tb = LKP_T();
             chunk_barrier();
+            const long long tc2 = LKP_T();
+            pw[1] += tb - ta; pb[1] += tc2 - tb;
+#else
+            chunk_barrier();
+#endif
         }
-        if (!helper) {
+#ifdef LK_PROF
+        if (blockIdx.x == 0 && lane == 0 && a.k_out) {
+            const long long te = LKP_T();
+            real* o = a.k_out + 32 + w * 8;
+            o[0] = (real)pw[0]; o[1] = (real)pb[0]; o[2] = (real)pw[1]; o[3] = (real)pb[1];
+            o[4] = (real)(ptm - pt0); o[5] = (real)(te - ptm); o[6] = role; o[7] = strip;
+        }
+#endif
+        if (stencil) {
             if (drift) atomicExch(a.err, 2);
-        } else if (a.want_gx) {
+        } else if (role == kRoleCoef && a.want_gx) {
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 const int I = (strip * kWave + lane) * M + m - a.lk_padb;
@@ -626,7 +771,7 @@ template <int BL, int D, int M>
 hipError_t launch_lock_one(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     hipError_t e;
-    const int threads = 2 * a.lk_ns * kWave;
+    const int threads = lock_waves(a.lk_ns) * kWave;
     if (backward) {
         static bool attr_done = false;
         if (!attr_done) {
@@ -683,7 +828,8 @@ hipError_t launch_lock_bl(bool backward, int DT, const SweepArgs& a, int grid, s
 hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
                                  hipStream_t st)
 {
-    if (a.lk_ns < 1 || a.lk_ns > kLockMaxStrips || (a.lk_NT & 7) != 0) return hipErrorInvalidValue;
+    if (a.lk_ns < 1 || a.lk_ns > (backward ? kLockMaxStripsBwd : kLockMaxStrips) || (a.lk_NT & 7) != 0)
+        return hipErrorInvalidValue;
     switch (BL) {
 #ifndef SK_ONLY_C2
         case 0: return launch_lock_bl<0>(backward, DT, a, grid, lds, st);

@@ -66,7 +66,8 @@ struct Plan {
 // row in one chunk is read by the neighbouring strip in a later chunk if lag >= 63 + chunk.
 constexpr int kLockCH1 = 8, kLockCH2 = 4, kLockS = 8;
 constexpr int kLockLag1 = 72, kLockLag2 = 68;
-constexpr int kLockMaxStrips = 4;
+constexpr int kLockMaxStrips = 4;      // forward: a stencil and a coefficient wave per strip
+constexpr int kLockMaxStripsBwd = 2;   // backward: plus a gradient wave per strip
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
@@ -206,9 +207,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const size_t o_kr = lds_take((size_t)(lns + 1) * lrow * elem);
         const size_t o_ar = backward ? lds_take((size_t)(lns + 1) * lrow * elem) : 0;
         const size_t o_dump = lds_take((size_t)(kWave + 8) * C * elem);
+        const int waves = lns == 1 ? 3 : (lns == 2 ? 8 : 12);
         int wgpc = used ? (int)(kLdsPerCU / used) : 0;
-        if (wgpc * 2 * lns > 16) wgpc = 16 / (2 * lns);
-        if (lns <= kLockMaxStrips && used <= kLdsPerCU - 1024 && wgpc >= 1 && p.npairs <= (int64_t)kNumCU * wgpc) {
+        if (wgpc * waves > 16) wgpc = 16 / waves;
+        if (lns <= (backward ? kLockMaxStripsBwd : kLockMaxStrips) && used <= kLdsPerCU - 1024 && wgpc >= 1 && p.npairs <= (int64_t)kNumCU * wgpc) {
             p.lock = 1; p.coop = 0;
             p.lk_M = M; p.lk_ns = lns; p.lk_NT = NT; p.lk_rowlen = lrow;
             p.lk_padb = lns * kWave * M - p.mb;

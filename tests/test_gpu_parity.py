@@ -169,6 +169,10 @@ def test_c5_full_size_sampled_entries():
     (11, 13, 11, 0, 0, 0),     # d = 11 runs in the 16-channel kernel
     (9, 12, 20, 1, 1, 1),      # d = 20: runtime channel loop
     (14, 7, 37, 0, 1, 0),
+    (300, 50, 3, 0, 0, 0),     # small batches of long paths: three, four and two strips of 128 block rows
+    (500, 40, 2, 0, 0, 1),
+    (140, 20, 3, 2, 2, 0),
+    (100, 300, 4, 1, 1, 1),    # many more columns than rows
 ])
 def test_shapes_orders_channels_fp64(L1, L2, d, lam1, lam2, flags):
     B = 5
