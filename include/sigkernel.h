@@ -83,8 +83,9 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  * By default the reverse sweep recovers the forward values it needs by inverting Eq. (1) between exact
  * checkpoints eight block steps apart, and checks the recovered state against every checkpoint: if they
  * differ by more than 1e-9 of the largest forward value met along the row (increment inner products of
- * order one make the inverse recurrence ill-conditioned), every gradient of the call is returned as NaN.  SK_FLAG_BWD_REPLAY selects the slower
- * variant that replays forward segments and has no such limit.
+ * order one make the inverse recurrence ill-conditioned), the gradients of that pair - or, depending on the
+ * launch mode, every gradient of the call - are returned as NaN, never as inaccurate numbers.
+ * SK_FLAG_BWD_REPLAY selects the slower variant that replays forward segments and has no such limit.
  */
 int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
                   int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,

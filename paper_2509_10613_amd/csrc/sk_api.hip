@@ -109,6 +109,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.lk_off_gp = (unsigned)p.lk_off_gp; a.lk_off_krows = (unsigned)p.lk_off_krows;
     a.lk_off_arows = (unsigned)p.lk_off_arows; a.lk_off_dump = (unsigned)p.lk_off_dump;
     a.lk_cring_stride = (unsigned)p.lk_cring_stride; a.lk_gp_stride = (unsigned)p.lk_gp_stride;
+    a.lk_off_ck = (unsigned)p.lk_off_ck; a.lk_ck_stride = (unsigned)p.lk_ck_stride;
 
     if (backward) {
         a.gdx = reinterpret_cast<double*>(base + p.off_gdxT);
@@ -121,7 +122,18 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.ckpt_slot = p.ckpt_slot;
     }
     a.err = reinterpret_cast<int*>(base + p.off_err);
+    // Lock-step mode on a batch of pairs of double paths works on the caller's arrays directly.
+    const bool fused = p.lock && p.gramM == 0 && kIsDouble;
+    if (fused) {
+        a.fused = 1;
+        a.xraw = static_cast<const double*>(x);
+        a.yraw = static_cast<const double*>(y);
+        a.gxraw = static_cast<double*>(grad_x);
+        a.gyraw = static_cast<double*>(grad_y);
+        a.L1 = p.L1; a.L2 = p.L2;
+    }
     // one preparation launch: increments of both sides, cleared gradient accumulators, cleared error flag
+    if (!fused)
     SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, p.L1,
                                p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
                                (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, p.L2, p.qpad, p.d,
@@ -146,7 +158,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         g_timed.push_back(tl);
     }
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
-    if (backward) {
+    if (backward && !fused) {
         SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.rpad, a.gdy,
                                     p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, p.L2, p.qpad, p.d, p.DP,
                                     a.err, st));

@@ -54,6 +54,15 @@ struct SweepArgs {
     int lk_rowlen;       // doubles per hand-over row in LDS
     unsigned lk_off_y, lk_off_gy, lk_off_cring, lk_off_gp, lk_off_krows, lk_off_arows, lk_off_dump;   // LDS bytes
     unsigned lk_cring_stride, lk_gp_stride;   // LDS bytes per strip
+    unsigned lk_off_ck, lk_ck_stride;         // checkpoint staging (backward)
+    // lock-step mode on a batch of pairs of double paths: the kernels read the caller's points and write the
+    // caller's gradients themselves (no preparation and finalisation launches, no global accumulators)
+    int fused;
+    const real* xraw;    // [npairs][L1][d]
+    const real* yraw;    // [npairs][L2][d]
+    real* gxraw;         // [npairs][L1][d] or null
+    real* gyraw;         // [npairs][L2][d] or null
+    int L1, L2;
     int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted
 };
 

@@ -88,9 +88,16 @@ struct Lock {
                 const int I = (strip * kWave + lane) * M + m - a.lk_padb;   // block row; < 0: above the grid
                 nbl[m] = I >= 0 ? a.nb : 0;
                 tcm[m] = I >= 0 ? a.tc : 0.0;
-                const real* xp = dxp + (long)((I >= 0 ? I : 0) >> a.rs1) * DSc;
+                const int arow = (I >= 0 ? I : 0) >> a.rs1;
+                if (a.fused) {   // dxp: the pair's points [L1][d]; increments are formed here
+                    const real* xp = dxp + (long)arow * a.d;
 #pragma unroll
-                for (int c = 0; c < D; ++c) dxr[m][c] = I >= 0 ? a.sc * xp[c] : 0.0;
+                    for (int c = 0; c < D; ++c) dxr[m][c] = (I >= 0 && c < a.d) ? a.sc * (xp[a.d + c] - xp[c]) : 0.0;
+                } else {
+                    const real* xp = dxp + (long)arow * DSc;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) dxr[m][c] = I >= 0 ? a.sc * xp[c] : 0.0;
+                }
             }
         }
         // A chunk of macro-steps [T0, T0 + n) is interior if every lane's column T - lane lies inside the grid:
@@ -431,7 +438,7 @@ struct Lock {
             const SK_LDS real* kp = krow + (T0 - (kWave - 1)) * C;
             SK_LDS real* op = lane == 0 ? arow_out + T0 * C : dump + lane * C;
             SK_LDS real* gw = gphalf + lane;
-            constexpr int PF = 2;
+            constexpr int PF = 1;   // reads one macro-step ahead: deeper prefetch costs more registers than it hides
             real2 ab[CH2][M], ip6[CH2][M];
             real ea[CH2][C], ek[CH2][C];
             auto load = [&](int i) {
@@ -496,6 +503,7 @@ struct LockLds {
     SK_LDS real* krows;
     SK_LDS real* arows;
     SK_LDS real* dump;
+    SK_LDS real* ck;      // this strip's checkpoint staging buffer (backward)
 };
 
 __device__ __forceinline__ LockLds carve_lock_lds(unsigned char* smem, const SweepArgs& a, int strip)
@@ -508,7 +516,30 @@ __device__ __forceinline__ LockLds carve_lock_lds(unsigned char* smem, const Swe
     l.krows = (SK_LDS real*)(smem + a.lk_off_krows);
     l.arows = (SK_LDS real*)(smem + a.lk_off_arows);
     l.dump = (SK_LDS real*)(smem + a.lk_off_dump);
+    l.ck = (SK_LDS real*)(smem + a.lk_off_ck + (size_t)strip * a.lk_ck_stride);
     return l;
+}
+
+// y increments of the pair into LDS ([q][DSc], channels beyond d zero), from the increment workspace or, in
+// fused mode, from the caller's points (first line of the paper's forward listing).
+template <int DSc, bool ZERO_G>
+__device__ __forceinline__ void stage_y(const SweepArgs& a, long yi, SK_LDS real* y, SK_LDS real* gy)
+{
+    const int n = a.q * DSc;
+    if (a.fused) {
+        const real* yp = a.yraw + yi * (long)a.L2 * a.d;
+        for (int t = threadIdx.x; t < n; t += blockDim.x) {
+            const int b = t / DSc, c = t - b * DSc;
+            y[t] = c < a.d ? yp[(long)(b + 1) * a.d + c] - yp[(long)b * a.d + c] : 0.0;
+            if (ZERO_G) gy[t] = 0.0;
+        }
+    } else {
+        const real* dyg = a.dy + yi * a.ystride;
+        for (int t = threadIdx.x; t < n; t += blockDim.x) {
+            y[t] = dyg[t];
+            if (ZERO_G) gy[t] = 0.0;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -529,11 +560,10 @@ __global__ __launch_bounds__(12 * kWave) void lock_fwd_kernel(SweepArgs a)
     const long pid = blockIdx.x;
     long xi, yi;
     pair_ids(a, pid, xi, yi);
-    const real* dxp = a.dx + xi * a.xstride;
-    const real* dyg = a.dy + yi * a.ystride;
+    const real* dxp = a.fused ? a.xraw + xi * (long)a.L1 * a.d : a.dx + xi * a.xstride;
     const int rowlen = a.lk_rowlen;
 
-    for (int t = threadIdx.x; t < a.q * LK::DSc; t += blockDim.x) l.y[t] = dyg[t];
+    stage_y<LK::DSc, false>(a, yi, l.y, l.y);
     for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) l.krows[t] = 1.0;
     __syncthreads();
 
@@ -583,15 +613,14 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     const long pid = blockIdx.x;
     long xi, yi;
     pair_ids(a, pid, xi, yi);
-    const real* dxp = a.dx + xi * a.xstride;
-    const real* dyg = a.dy + yi * a.ystride;
-    real* gdx = a.gdx + xi * a.xstride;
-    real* gdy = a.gdy + yi * a.ystride;
+    const real* dxp = a.fused ? a.xraw + xi * (long)a.L1 * a.d : a.dx + xi * a.xstride;
+    real* gdx = a.fused ? nullptr : a.gdx + xi * a.xstride;
+    real* gdy = a.fused ? nullptr : a.gdy + yi * a.ystride;
     const int rowlen = a.lk_rowlen;
     const int nckS = a.lk_NT / kLockS;   // checkpoints per strip: nckS + 1
     real* ckpt = a.ckpt + pid * a.ckpt_slot + (long)strip * (nckS + 1) * NVC * kWave + lane;
 
-    for (int t = threadIdx.x; t < a.q * LK::DSc; t += blockDim.x) { l.y[t] = dyg[t]; l.gy[t] = 0.0; }
+    stage_y<LK::DSc, true>(a, yi, l.y, l.gy);
     for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) { l.krows[t] = 1.0; l.arows[t] = 0.0; }
     __syncthreads();
     // dF/dk[m, n] enters through the adjoint row under the last strip
@@ -650,40 +679,43 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
         // and are checked against their own largest entry).
         bool drift = false;
         real kscale = 1.0;
-        // checkpoint prefetch, two segments ahead: buffer (idx & 1) holds checkpoint idx
-        real cb[2][NVC];
-        const int up1 = lane > 0 ? -1 : 0;   // lane l also needs the bottom edge of lane l - 1
-        auto load_ckpt = [&](int idx, real (&dst)[NVC]) {
+        // Checkpoints reach the stencil wave through LDS: the coefficient wave of the strip loads checkpoint idx
+        // from global memory three chunks before it is needed, writes it into half (idx & 1) of the strip's
+        // staging buffer two chunks later, and the stencil wave reads it after the next barrier.  Stored per
+        // lane: the lane's right edge (RR + 1 values), then the bottom edge of the lane above with its left
+        // corner (C values), which that lane takes over this lane's top edge hand-over.
+        constexpr int NVS = RR + 1 + C;
+        SK_LDS real* ckl = l.ck + lane;
+        real ckr[NVS];
+        const int up1 = lane > 0 ? -1 : 0;
+        auto load_ckpt = [&](int idx) {
             const real* cp = ckpt + (long)idx * NVC * kWave;
 #pragma unroll
-            for (int q = 0; q <= RR; ++q) dst[q] = ld_scratch(cp + q * kWave);
-            dst[RR + 1] = ld_scratch(cp + (RR + 1 + C) * kWave + up1);                                // corner
+            for (int q = 0; q <= RR; ++q) ckr[q] = ld_scratch(cp + q * kWave);
+            ckr[RR + 1] = ld_scratch(cp + (RR + 1 + C) * kWave + up1);                                // corner
 #pragma unroll
-            for (int q = 1; q < C; ++q) dst[RR + 1 + q] = ld_scratch(cp + (RR + 1 + q - 1) * kWave + up1);
+            for (int q = 1; q < C; ++q) ckr[RR + 1 + q] = ld_scratch(cp + (RR + 1 + q - 1) * kWave + up1);
         };
-        if (stencil) {
-            if (nckS & 1) { load_ckpt(nckS, cb[1]); load_ckpt(nckS - 1, cb[0]); }
-            else { load_ckpt(nckS, cb[0]); load_ckpt(nckS - 1, cb[1]); }
-        }
-        auto rev_chunk = [&](auto restore_c, auto buf_c, int fc, int rc) {
+        if (role == kRoleCoef) load_ckpt(nckS);
+        auto rev_chunk = [&](auto restore_c, int fc, int rc) {
             constexpr bool RESTORE = decltype(restore_c)::value;
-            constexpr int BUF = decltype(buf_c)::value;
             if constexpr (RESTORE) {
                 const int idx = (fc + 1) / 2;
+                const SK_LDS real* cs = ckl + (idx & 1) * (NVS * kWave);
+                real cv[NVS];
 #pragma unroll
-                for (int i = 0; i <= RR; ++i) kscale = fmax(kscale, fabs(cb[BUF][i]));
+                for (int i = 0; i < NVS; ++i) cv[i] = cs[i * kWave];
+#pragma unroll
+                for (int i = 0; i <= RR; ++i) kscale = fmax(kscale, fabs(cv[i]));
                 if (rc > 0) {
 #pragma unroll
                     for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
-                    {
-                        if (!(fabs(rv.kR[i] - cb[BUF][i]) <= 1e-9 * kscale)) drift = true;
-                    }
+                        if (!(fabs(rv.kR[i] - cv[i]) <= 1e-9 * kscale)) drift = true;
                 }
 #pragma unroll
-                for (int i = 0; i <= RR; ++i) rv.kR[i] = cb[BUF][i];
+                for (int i = 0; i <= RR; ++i) rv.kR[i] = cv[i];
 #pragma unroll
-                for (int i = 0; i < C; ++i) rv.ktop[i] = cb[BUF][RR + 1 + i];
-                if (idx >= 2) load_ckpt(idx - 2, cb[BUF]);
+                for (int i = 0; i < C; ++i) rv.ktop[i] = cv[RR + 1 + i];
             }
             rv.chunk(fc * CH2, lane, l.cring + (rc & 1) * LK::CR2, arow_in, rowcur, arow_out, l.dump,
                      l.gp + (rc & 1) * LK::GPH);
@@ -693,15 +725,21 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
             if (stencil) {
                 if (rc >= 0 && rc < nck) {
                     const int fc = nck - 1 - rc;
-                    if (fc & 1) {
-                        if (((fc + 1) / 2) & 1) rev_chunk(std::true_type(), std::integral_constant<int, 1>(), fc, rc);
-                        else rev_chunk(std::true_type(), std::integral_constant<int, 0>(), fc, rc);
-                    } else {
-                        rev_chunk(std::false_type(), std::integral_constant<int, 0>(), fc, rc);
-                    }
+                    if (fc & 1) rev_chunk(std::true_type(), fc, rc);
+                    else rev_chunk(std::false_type(), fc, rc);
                 }
             } else if (role == kRoleCoef) {
                 const int hc = rc + 1, gc = rc - 1;
+                // the stencil wave restores checkpoint idx in reverse chunk nck - 2 idx: stage it one chunk before
+                if (rc >= -1 && ((nck - rc - 1) & 1) == 0) {
+                    const int idx = (nck - rc - 1) / 2;
+                    if (idx >= 1) {
+                        SK_LDS real* cs = ckl + (idx & 1) * (NVS * kWave);
+#pragma unroll
+                        for (int i = 0; i < NVS; ++i) cs[i * kWave] = ckr[i];
+                        if (idx >= 2) load_ckpt(idx - 1);
+                    }
+                }
                 if (hc >= 0 && hc < nck) cf.produce_rev((nck - 1 - hc) * CH2, l.cring + (hc & 1) * LK::CR2);
                 if (a.want_gx && gc >= 0 && gc < nck)
                     cf.consume_gx((nck - 1 - gc) * CH2, l.gp + (gc & 1) * LK::GPH, gacc);
@@ -711,26 +749,76 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
             }
             chunk_barrier();
         }
-        if (stencil) {
-            if (drift) atomicExch(a.err, 2);
-        } else if (role == kRoleCoef && a.want_gx) {
+        if (!a.fused) {
+            if (stencil) {
+                if (drift) atomicExch(a.err, 2);
+            } else if (role == kRoleCoef && a.want_gx) {
 #pragma unroll
-            for (int m = 0; m < M; ++m) {
-                const int I = (strip * kWave + lane) * M + m - a.lk_padb;
-                if (I >= 0) {
-                    real* gq = gdx + (long)(I >> a.rs1) * LK::DSc;
+                for (int m = 0; m < M; ++m) {
+                    const int I = (strip * kWave + lane) * M + m - a.lk_padb;
+                    if (I >= 0) {
+                        real* gq = gdx + (long)(I >> a.rs1) * LK::DSc;
 #pragma unroll
-                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                        for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                    }
+                }
+            }
+        } else {
+            // Fused finalisation.  The coefficient rings are free now: their memory collects the gradients
+            // with respect to the x increments, [r][DSc].
+            SK_LDS real* gxl = (SK_LDS real*)(smem + a.lk_off_cring);
+            SK_LDS int* bad = (SK_LDS int*)l.dump;
+            for (int t = threadIdx.x; t < a.r * LK::DSc; t += blockDim.x) gxl[t] = 0.0;
+            if (threadIdx.x == 0) *bad = 0;
+            __syncthreads();
+            if (stencil) {
+                if (drift) *bad = 1;
+            } else if (role == kRoleCoef && a.want_gx) {
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const int I = (strip * kWave + lane) * M + m - a.lk_padb;
+                    if (I >= 0) {
+                        SK_LDS real* gq = gxl + (I >> a.rs1) * LK::DSc;
+#pragma unroll
+                        for (int c = 0; c < D; ++c) lds_atomic_add(gq + c, gacc[m][c] * a.sc);
+                    }
                 }
             }
         }
     }
     __syncthreads();
-    if (a.want_gy) {
-        const int n = a.q * LK::DSc;
-        for (int t = threadIdx.x; t < n; t += blockDim.x) {
-            const real v = l.gy[t];
-            if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+    if (!a.fused) {
+        if (a.want_gy) {
+            const int n = a.q * LK::DSc;
+            for (int t = threadIdx.x; t < n; t += blockDim.x) {
+                const real v = l.gy[t];
+                if (v != 0.0) unsafeAtomicAdd(&gdy[t], v);
+            }
+        }
+    } else {
+        // The increments are differences of consecutive points, so the gradient of a point collects the two
+        // increments it touches (the linear map of Section 3.4).  A drifted un-compute poisons the pair.
+        const SK_LDS real* gxl = (const SK_LDS real*)(smem + a.lk_off_cring);
+        const bool bad = *(const SK_LDS int*)l.dump != 0;
+        const real nan = __builtin_nan("");
+        const int d = a.d;
+        if (a.gxraw) {
+            real* go = a.gxraw + xi * (long)a.L1 * d;
+            for (int t = threadIdx.x; t < a.L1 * d; t += blockDim.x) {
+                const int pt = t / d, c = t - pt * d;
+                const real hi = pt >= 1 ? gxl[(pt - 1) * LK::DSc + c] : 0.0;
+                const real lo = pt < a.L1 - 1 ? gxl[pt * LK::DSc + c] : 0.0;
+                go[t] = bad ? nan : hi - lo;
+            }
+        }
+        if (a.gyraw) {
+            real* go = a.gyraw + yi * (long)a.L2 * d;
+            for (int t = threadIdx.x; t < a.L2 * d; t += blockDim.x) {
+                const int pt = t / d, c = t - pt * d;
+                const real hi = pt >= 1 ? l.gy[(pt - 1) * LK::DSc + c] : 0.0;
+                const real lo = pt < a.L2 - 1 ? l.gy[pt * LK::DSc + c] : 0.0;
+                go[t] = bad ? nan : hi - lo;
+            }
         }
     }
 }

@@ -58,7 +58,7 @@ struct Plan {
     // lock-step mode: one workgroup per pair, per strip one stencil wave and one coefficient wave
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
     size_t lk_off_y = 0, lk_off_gy = 0, lk_off_cring = 0, lk_off_gp = 0, lk_off_krows = 0, lk_off_arows = 0,
-           lk_off_dump = 0, lk_cring_stride = 0, lk_gp_stride = 0;
+           lk_off_dump = 0, lk_cring_stride = 0, lk_gp_stride = 0, lk_off_ck = 0, lk_ck_stride = 0;
 };
 
 // Lock-step mode constants: chunk lengths (macro-steps between workgroup barriers) of the forward and the
@@ -207,6 +207,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const size_t o_kr = lds_take((size_t)(lns + 1) * lrow * elem);
         const size_t o_ar = backward ? lds_take((size_t)(lns + 1) * lrow * elem) : 0;
         const size_t o_dump = lds_take((size_t)(kWave + 8) * C * elem);
+        const size_t kstride = (size_t)2 * (M * R + 1 + C) * kWave * elem;   // two staged checkpoints per strip
+        const size_t o_ck = backward ? lds_take(kstride * lns) : 0;
         const int waves = lns == 1 ? 3 : (lns == 2 ? 8 : 12);
         int wgpc = used ? (int)(kLdsPerCU / used) : 0;
         if (wgpc * waves > 16) wgpc = 16 / waves;
@@ -217,6 +219,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
             p.lk_off_y = o_y; p.lk_off_gy = o_gy; p.lk_off_cring = o_cr; p.lk_off_gp = o_gp;
             p.lk_off_krows = o_kr; p.lk_off_arows = o_ar; p.lk_off_dump = o_dump;
             p.lk_cring_stride = cstride; p.lk_gp_stride = gstride;
+            p.lk_off_ck = o_ck; p.lk_ck_stride = kstride;
             p.y_lds = 1;
             p.lds_wave = 0;
             p.lds_bytes = align_up(used, 256);

@@ -281,12 +281,17 @@ def test_inverse_recurrence_never_fails_silently(scale):
     k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0)
     torch.cuda.synchronize()
     gx, gy = host(gx), host(gy)
-    if np.any(np.isnan(gx)) or np.any(np.isnan(gy)):
-        print("scale %g: inverse recurrence drifted, gradients are NaN" % scale, flush=True)
-        assert np.all(np.isnan(gx)) and np.all(np.isnan(gy))
-    else:
-        assert np.max(np.abs(gx - gxr)) <= 1e-10 * max(1.0, np.max(np.abs(gxr)))
-        assert np.max(np.abs(gy - gyr)) <= 1e-10 * max(1.0, np.max(np.abs(gyr)))
+    # a pair whose check failed is NaN in every entry of both gradients (the whole call may be); every other
+    # pair meets the tolerance
+    bad = np.isnan(gx).any(axis=(1, 2)) | np.isnan(gy).any(axis=(1, 2))
+    if bad.any():
+        print("scale %g: inverse recurrence drifted for %d of %d pairs, their gradients are NaN" % (scale, bad.sum(), B),
+              flush=True)
+        assert np.all(np.isnan(gx[bad])) and np.all(np.isnan(gy[bad]))
+    good = ~bad
+    if good.any():
+        assert np.max(np.abs(gx[good] - gxr[good])) <= 1e-10 * max(1.0, np.max(np.abs(gxr)))
+        assert np.max(np.abs(gy[good] - gyr[good])) <= 1e-10 * max(1.0, np.max(np.abs(gyr)))
     k2, gx2, gy2 = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, sk.SK_FLAG_BWD_REPLAY)
     torch.cuda.synchronize()
     assert np.all(np.isfinite(host(gx2))) and np.all(np.isfinite(host(gy2)))
