@@ -147,7 +147,16 @@ def main():
     dom_ms = (bwd_ms / nb) if dom_back else (fwd_ms / max(nf, 1))
     flops = cells * algorithmic_flops_per_cell(w.d, bool(flags & 1), lam, dom_back)
     achieved = flops / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "alu", "kernel": "sweep_bwd_kernel" if dom_back else "sweep_fwd_kernel",
+    # the sweep kernel's name as a profiler reports it, from the library's own launch plan
+    if gram:
+        desc = sk.sigkernel_describe(sk.SK_OP_GRAM_BWD if dom_back else sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, lam,
+                                     lam, flags, f64)
+    else:
+        desc = sk.sigkernel_describe(sk.SK_OP_BWD if dom_back else sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags,
+                                     f64)
+    plan = dict(kv.split("=", 1) for kv in desc.split(" ") if "=" in kv and not kv.startswith("kernel="))
+    kname = desc.split("kernel=", 1)[1].split(" grid=", 1)[0] if "kernel=" in desc else "?"
+    roofline = {"bound": "alu", "kernel": kname, "launch": plan,
                 "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "avg_launch_ms": dom_ms,
                 "flops_per_launch": flops, "traffic": None}
@@ -157,7 +166,7 @@ def main():
     if os.path.exists(tfile):
         with open(tfile) as f:
             tj = json.load(f)
-        ent = tj.get(w.name, {}).get(roofline["kernel"])
+        ent = tj.get(w.name, {}).get("backward sweep" if dom_back else "forward sweep")
         if ent is not None:
             roofline["traffic"] = ent
 

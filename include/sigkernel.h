@@ -113,6 +113,16 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
 int sigkernel_event_timing(int enable);
 int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches);
 
+/*
+ * Diagnostics (no passage of the paper): writes a NUL-terminated, human-readable description of the launch
+ * the library would make for this operation and shape into out (host memory, out_bytes >= 1; truncated if
+ * too small): the launch mode, the name of the sweep kernel as a profiler reports it, grid and workgroup
+ * size, LDS bytes per workgroup and the workspace size.  Same arguments as sigkernel_workspace_bytes.
+ * Pure host arithmetic: no GPU call.  Returns SK_OK or a negative error code.
+ */
+int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
+                       int flags, sk_dtype dt, char* out, size_t out_bytes);
+
 /* Thread-local, NUL-terminated message describing the last non-zero return on this thread. */
 const char* sigkernel_last_error(void);
 

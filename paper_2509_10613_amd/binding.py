@@ -16,7 +16,7 @@ SK_FLAG_TIME_AUG = 1
 SK_FLAG_BWD_REPLAY = 2
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
-EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram",
+EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",
            "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version"]
 
 _lib = None
@@ -39,6 +39,8 @@ def load():
     i64, vp, ci = C.c_int64, C.c_void_p, C.c_int
     lib.sigkernel_workspace_bytes.restype = C.c_size_t
     lib.sigkernel_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, i64, ci, ci, ci, ci]
+    lib.sigkernel_describe.restype = ci
+    lib.sigkernel_describe.argtypes = [ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, C.c_char_p, C.c_size_t]
     lib.sigkernel_fwd.restype = ci
     lib.sigkernel_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t, vp]
     lib.sigkernel_bwd.restype = ci
@@ -86,6 +88,13 @@ def _stream():
 
 def sigkernel_workspace_bytes(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt):
     return int(load().sigkernel_workspace_bytes(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt))
+
+
+def sigkernel_describe(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt):
+    """The launch the library would make for this operation and shape, as 'key=value' text (no GPU call)."""
+    buf = C.create_string_buffer(512)
+    _check(load().sigkernel_describe(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt, buf, len(buf)))
+    return buf.value.decode()
 
 
 def sigkernel_event_timing(enable):

@@ -305,6 +305,46 @@ int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_m
     return rc;
 }
 
+int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
+                       int flags, sk_dtype dt, char* out, size_t out_bytes)
+{
+    if (!out || out_bytes == 0) return fail(SK_ERR_NULL, "out is NULL or empty");
+    out[0] = 0;
+    if (op < SK_OP_FWD || op > SK_OP_GRAM_BWD) return fail(SK_ERR_SHAPE, "unknown operation %d", op);
+    const bool gram = op == SK_OP_GRAM || op == SK_OP_GRAM_BWD;
+    const bool backward = op == SK_OP_BWD || op == SK_OP_GRAM_BWD;
+    const int64_t ny = gram ? M : B_or_N;
+    int rc = validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt);
+    if (rc != SK_OK) return rc;
+    sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+                               !(flags & SK_FLAG_BWD_REPLAY));
+    if (!p.valid) {
+        std::snprintf(out, out_bytes, "mode=trivial (no cells to sweep)");
+        return SK_OK;
+    }
+    char kern[96];
+    int threads;
+    const char* mode;
+    if (p.lock) {
+        mode = "lock-step";
+        std::snprintf(kern, sizeof(kern), "lock_%s_kernel<%d, %d, %d>", backward ? "bwd" : "fwd", p.BL, p.DT, p.lk_M);
+        threads = (p.lk_ns == 1 ? 3 : (p.lk_ns == 2 ? 8 : 12)) * sk::kWave;
+    } else {
+        const char* base = !backward ? "sweep_fwd" : (p.uncompute ? "sweep_bwdu" : "sweep_bwd");
+        mode = p.coop ? "cooperative" : "wave-per-pair";
+        std::snprintf(kern, sizeof(kern), "%s%s_kernel<%d, %d, %s>", base, p.coop ? "_coop" : "", p.BL, p.DT,
+                      (p.y_lds && p.DT) ? "true" : "false");
+        threads = (p.coop ? p.nw : sk::kWavesPerWG) * sk::kWave;
+    }
+    const bool fused = p.lock && !gram && dt == SK_F64;
+    std::snprintf(out, out_bytes,
+                  "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
+                  "workspace_bytes=%zu",
+                  mode, kern, p.grid, threads, p.lds_bytes, p.lock ? p.lk_ns : p.ns, p.lock ? p.lk_M : 1,
+                  fused ? 1 : 0, p.total);
+    return SK_OK;
+}
+
 const char* sigkernel_last_error(void) { return g_err; }
 
 const char* sigkernel_version(void) { return "sigkernel-mi355x 0.1 (gfx950)"; }

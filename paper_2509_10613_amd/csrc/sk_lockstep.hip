@@ -71,6 +71,29 @@ struct Lock {
     static constexpr int CR2 = CH2 * M * kWave * 4;   // ... reverse sweep
     static constexpr int GPH = CH2 * M * kWave;       // doubles per half of the dF/dp ring
 
+    // dF/dp ring: [macro-step][lane][M], so that a lane's M values move in one LDS instruction
+    static __device__ __forceinline__ void gp_store(SK_LDS real* half, int i, int lane, const real (&v)[M])
+    {
+        SK_LDS real* q = half + (i * kWave + lane) * M;
+        if constexpr (M == 2) {
+            *(SK_LDS real2*)q = real2{v[0], v[1]};
+        } else {
+#pragma unroll
+            for (int m = 0; m < M; ++m) q[m] = v[m];
+        }
+    }
+    static __device__ __forceinline__ void gp_load(const SK_LDS real* half, int i, int lane, real (&v)[M])
+    {
+        const SK_LDS real* q = half + (i * kWave + lane) * M;
+        if constexpr (M == 2) {
+            const real2 t = *(const SK_LDS real2*)q;
+            v[0] = t.x; v[1] = t.y;
+        } else {
+#pragma unroll
+            for (int m = 0; m < M; ++m) v[m] = q[m];
+        }
+    }
+
     // ---------------- coefficient wave ----------------
     struct Coef {
         real dxr[M][D];
@@ -207,7 +230,6 @@ struct Lock {
         template <bool EDGE>
         __device__ __forceinline__ void consume_gx_t(int T0, const SK_LDS real* half, real (&gacc)[M][D]) const
         {
-            const SK_LDS real* rp = half + lane;
             constexpr int PFY = D <= 8 ? CH2 : 2;
 #pragma unroll
             for (int g0 = 0; g0 < CH2; g0 += PFY) {
@@ -216,8 +238,7 @@ struct Lock {
 #pragma unroll
                 for (int u = 0; u < PFY; ++u) {
                     fetch<EDGE>(T0 + g0 + u, J[u], b[u], y[u]);
-#pragma unroll
-                    for (int m = 0; m < M; ++m) gv[u][m] = rp[((g0 + u) * M + m) * kWave];
+                    gp_load(half, g0 + u, lane, gv[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < PFY; ++u)
@@ -247,12 +268,9 @@ struct Lock {
         template <bool EDGE, bool PLAIN>
         __device__ __forceinline__ void consume_gy_t(int T0, const SK_LDS real* half, SK_LDS real* gy) const
         {
-            const SK_LDS real* rp = half + lane;
             real gv[CH2][M];
 #pragma unroll
-            for (int i = 0; i < CH2; ++i)
-#pragma unroll
-                for (int m = 0; m < M; ++m) gv[i][m] = rp[(i * M + m) * kWave];
+            for (int i = 0; i < CH2; ++i) gp_load(half, i, lane, gv[i]);
 #pragma unroll
             for (int i = 0; i < CH2; ++i) {
                 const int J = T0 + i - lane;
@@ -437,7 +455,6 @@ struct Lock {
             const SK_LDS real* ap = arow_in + (T0 - (kWave - 1)) * C;   // feeds of the strip's last lane
             const SK_LDS real* kp = krow + (T0 - (kWave - 1)) * C;
             SK_LDS real* op = lane == 0 ? arow_out + T0 * C : dump + lane * C;
-            SK_LDS real* gw = gphalf + lane;
             constexpr int PF = 1;   // reads one macro-step ahead: deeper prefetch costs more registers than it hides
             real2 ab[CH2][M], ip6[CH2][M];
             real ea[CH2][C], ek[CH2][C];
@@ -468,8 +485,7 @@ struct Lock {
                 step(recv, recvk, Ac, Bc, iB, p6, accP);
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) op[i * C + cc] = up[cc];
-#pragma unroll
-                for (int m = 0; m < M; ++m) gw[(i * M + m) * kWave] = accP[m];
+                gp_store(gphalf, i, lane, accP);
             }
         }
     };
@@ -827,40 +843,46 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
 // launchers
 // ------------------------------------------------------------------------------------------------
 template <int BL, int D, int M>
-hipError_t launch_lock_one(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+hipError_t launch_lock_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    hipError_t e;
-    const int threads = lock_waves(a.lk_ns) * kWave;
-    if (backward) {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
-        hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M>), dim3(grid), dim3(threads), lds, st, a);
-    } else {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
-        hipLaunchKernelGGL((lock_fwd_kernel<BL, D, M>), dim3(grid), dim3(threads), lds, st, a);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+        if (e != hipSuccess) return e;
+        attr_done = true;
     }
+    hipLaunchKernelGGL((lock_fwd_kernel<BL, D, M>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
     return hipGetLastError();
 }
 
+template <int BL, int D, int M>
+hipError_t launch_lock_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
+    return hipGetLastError();
+}
+
+// Two block rows per lane are only built where the registers allow it (lock_max_rows in sk_plan.h).
 template <int BL, int D>
 hipError_t launch_lock_m(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    if (a.lk_M == 1) {
-        return launch_lock_one<BL, D, 1>(backward, a, grid, lds, st);
-    } else if (a.lk_M == 2) {
-        if constexpr (BL < 2) return launch_lock_one<BL, D, 2>(backward, a, grid, lds, st);
-        else if (!backward) return launch_lock_one<BL, D, 2>(backward, a, grid, lds, st);
+    if (a.lk_M > lock_max_rows(backward, BL, D)) return hipErrorInvalidValue;
+    if (backward) {
+        if constexpr (lock_max_rows(true, BL, D) >= 1) {
+            if (a.lk_M == 1) return launch_lock_bwd<BL, D, 1>(a, grid, lds, st);
+        }
+        if constexpr (lock_max_rows(true, BL, D) >= 2) return launch_lock_bwd<BL, D, 2>(a, grid, lds, st);
+    } else {
+        if (a.lk_M == 1) return launch_lock_fwd<BL, D, 1>(a, grid, lds, st);
+        if constexpr (lock_max_rows(false, BL, D) >= 2) return launch_lock_fwd<BL, D, 2>(a, grid, lds, st);
     }
     return hipErrorInvalidValue;
 }

@@ -69,6 +69,16 @@ constexpr int kLockLag1 = 72, kLockLag2 = 68;
 constexpr int kLockMaxStrips = 4;      // forward: a stencil and a coefficient wave per strip
 constexpr int kLockMaxStripsBwd = 2;   // backward: plus a gradient wave per strip
 
+// Block rows per lane the lock-step kernels are built for: two, unless the lane state would not fit the
+// register file (largest blocks or most channels in the backward kernel; both together in the forward one);
+// zero: no lock-step kernel for this combination.
+constexpr int lock_max_rows(bool backward, int BL, int DT)
+{
+    if (DT == 0) return 0;
+    if (backward) return (BL >= 2 && DT >= 16) ? 0 : ((BL >= 2 || DT >= 16) ? 1 : 2);
+    return (BL >= 2 && DT >= 16) ? 1 : 2;
+}
+
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
 constexpr int kUncomputeS = 8;   // macro-steps between checkpoints when the reverse sweep inverts Eq. (1)
@@ -188,8 +198,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     // once: the chip is then under-filled and the time of a call is the latency of one pair's chain of
     // macro-steps, which this mode shortens (fewer instructions in the wave that carries the recurrence,
     // fewer strips, no waits).
-    if (p.DT != 0 && (!backward || p.uncompute)) {
-        const int maxM = (backward && p.BL == 2) ? 1 : 2;
+    if (lock_max_rows(backward, p.BL, p.DT) > 0 && (!backward || p.uncompute)) {
+        const int maxM = lock_max_rows(backward, p.BL, p.DT);
         int M = 1;
         while (M < maxM && (p.mb + kWave * M - 1) / (kWave * M) > 2) M *= 2;
         const int lns = (p.mb + kWave * M - 1) / (kWave * M);

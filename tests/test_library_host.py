@@ -62,3 +62,62 @@ def test_workspace_query(lib):
     f32 = q(binding.SK_OP_BWD, 16, 0, 64, 64, 3, 1, 1, 0, binding.SK_F32)
     f64b = q(binding.SK_OP_BWD, 16, 0, 64, 64, 3, 1, 1, 0, f64)
     assert f64b <= f32 <= f64b + 4096
+
+
+def _plan(op, *shape):
+    text = binding.sigkernel_describe(op, *shape)
+    kernel = text.split("kernel=", 1)[1].split(" grid=", 1)[0]
+    rest = text.replace("kernel=" + kernel + " ", "")
+    d = dict(kv.split("=", 1) for kv in rest.split(" ") if "=" in kv)
+    d["kernel"] = kernel
+    return d
+
+
+def test_launch_plan_of_the_five_configurations(lib):
+    f64, f32 = binding.SK_F64, binding.SK_F32
+    # c2 (128 pairs, L = 256, order 1): the chip is under-filled -> one workgroup per pair in lock step,
+    # two strips of 128 block rows, eight waves, everything resident at once, caller's arrays used directly
+    p = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
+    assert p["mode"] == "lock-step" and p["kernel"] == "lock_bwd_kernel<1, 5, 2>"
+    assert (p["grid"], p["threads"], p["strips"], p["rows_per_lane"], p["fused"]) == ("128", "512", "2", "2", "1")
+    assert int(p["lds_bytes"]) <= 160 * 1024
+    p = _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
+    assert p["kernel"] == "lock_fwd_kernel<1, 5, 2>" and p["fused"] == "1"
+    assert _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f32)["fused"] == "0"   # float callers are converted
+    # c1: tiny, one strip: stencil, coefficient and auxiliary wave
+    p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
+    assert p["mode"] == "lock-step" and p["threads"] == "192" and p["strips"] == "1"
+    # c3 / c5 (Gram matrices with 65536 / 1048576 pairs): one wave per pair fills the chip
+    p = _plan(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64)
+    assert p["mode"] == "wave-per-pair" and p["kernel"] == "sweep_bwdu_kernel<1, 3, true>"
+    p = _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
+    assert p["mode"] == "wave-per-pair" and p["kernel"] == "sweep_fwd_kernel<0, 16, true>"
+    # c4 (32 pairs, 2047 block rows each): too long for whole hand-over rows in LDS -> cooperative mode with rings
+    p = _plan(binding.SK_OP_BWD, 32, 0, 2048, 2048, 8, 2, 2, 0, f64)
+    assert p["mode"] == "cooperative" and p["grid"] == "32"
+    # the replay variant of the backward pass never runs in lock step
+    p = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | binding.SK_FLAG_BWD_REPLAY, f64)
+    assert p["mode"] == "cooperative" and p["kernel"].startswith("sweep_bwd_coop_kernel")
+
+
+def test_launch_plan_stays_inside_the_hardware_limits(lib):
+    f64 = binding.SK_F64
+    for op in (binding.SK_OP_FWD, binding.SK_OP_BWD):
+        for B in (1, 7, 128, 256, 300, 1024, 5000):
+            for L in (2, 9, 65, 129, 300, 700, 3000):
+                for d in (1, 3, 5, 8, 16, 20):
+                    for lam in (0, 1, 2, 3):
+                        if ((L - 1) << lam) >= (1 << 14):
+                            continue
+                        p = _plan(op, B, 0, L, max(2, L // 2), d, lam, lam, 0, f64)
+                        assert int(p["lds_bytes"]) <= 160 * 1024, p
+                        assert 64 <= int(p["threads"]) <= 1024 and int(p["threads"]) % 64 == 0, p
+                        assert 1 <= int(p["grid"]), p
+                        if p["mode"] == "lock-step":
+                            assert int(p["grid"]) == B and int(p["strips"]) <= (4 if op == binding.SK_OP_FWD else 2), p
+                            assert d <= 16, p
+    buf = C.create_string_buffer(8)
+    assert lib.sigkernel_describe(binding.SK_OP_FWD, 4, 0, 8, 8, 2, 0, 0, 0, f64, buf, 8) == 0
+    assert len(buf.value) == 7                                  # truncated, still NUL-terminated
+    assert lib.sigkernel_describe(99, 4, 0, 8, 8, 2, 0, 0, 0, f64, buf, 8) == -2
+    assert lib.sigkernel_describe(binding.SK_OP_FWD, 4, 0, 8, 8, 2, 0, 0, 0, f64, None, 8) == -1
