@@ -55,6 +55,8 @@ struct SweepArgs {
     unsigned lk_off_y, lk_off_gy, lk_off_cring, lk_off_gp, lk_off_krows, lk_off_arows, lk_off_dump;   // LDS bytes
     unsigned lk_cring_stride, lk_gp_stride;   // LDS bytes per strip
     unsigned lk_off_ck, lk_ck_stride;         // checkpoint staging (backward)
+    int solo;            // 1: solo kernels (one wave per pair, a single strip of 64 * lk_M block rows; uses lk_M,
+                         // lk_NT, lk_padb and, as offsets inside a wave's LDS, lk_off_gy / lk_off_krows / lk_off_dump)
     // lock-step mode on a batch of pairs of double paths: the kernels read the caller's points and write the
     // caller's gradients themselves (no preparation and finalisation launches, no global accumulators)
     int fused;
@@ -76,6 +78,8 @@ template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
                            int L2, int qpad, int d, int DS, const int* err, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
+// solo mode (a.solo != 0), defined in sk_solo.hip
+hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // lock-step mode (a.lock != 0), defined in sk_lockstep.hip
 hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
                                  hipStream_t st);

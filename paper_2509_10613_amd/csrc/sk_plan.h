@@ -56,6 +56,7 @@ struct Plan {
     int uncompute = 0;   // backward: reverse sweep recovers forward values by inverting Eq. (1) (no replay ring)
     size_t coop_off_gdy = 0, coop_off_flags = 0, coop_off_obox = 0, coop_off_ring = 0, coop_ring_stride = 0;
     // lock-step mode: one workgroup per pair, per strip one stencil wave and one coefficient wave
+    int solo = 0;   // one wave per pair, a single strip of 64 * lk_M block rows (many pairs of short paths)
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
     size_t lk_off_y = 0, lk_off_gy = 0, lk_off_cring = 0, lk_off_gp = 0, lk_off_krows = 0, lk_off_arows = 0,
            lk_off_dump = 0, lk_cring_stride = 0, lk_gp_stride = 0, lk_off_ck = 0, lk_ck_stride = 0;
@@ -76,6 +77,14 @@ constexpr int lock_max_rows(bool backward, int BL, int DT)
 {
     if (DT == 0) return 0;
     if (backward) return (BL >= 2 && DT >= 16) ? 0 : ((BL >= 2 || DT >= 16) ? 1 : 2);
+    return (BL >= 2 && DT >= 16) ? 1 : 2;
+}
+
+// Block rows per lane of the solo kernels (one wave does the stencil, the coefficients and the gradients).
+constexpr int solo_max_rows(bool backward, int BL, int DT)
+{
+    if (DT == 0) return 0;
+    if (backward) return (BL <= 1 && DT <= 8) ? 2 : 1;
     return (BL >= 2 && DT >= 16) ? 1 : 2;
 }
 
@@ -240,6 +249,36 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         }
     }
 
+    // Solo mode: enough pairs to fill the chip, and all block rows of a pair fit one strip of 64 M rows.
+    if (!p.lock && solo_max_rows(backward, p.BL, p.DT) > 0 && (!backward || p.uncompute)) {
+        const int M = p.mb > kWave ? 2 : 1;
+        const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
+        size_t used = 0;
+        auto lds_take = [&](size_t bytes) { size_t o = used; used = align_up(used + bytes, 256); return o; };
+        const size_t ycopy = (size_t)p.q * p.DP * elem;
+        lds_take(ycopy);
+        const size_t o_gy = backward ? lds_take(ycopy) : 0;
+        const size_t o_kr = backward ? lds_take(((size_t)kWave * C + (size_t)NT * C + 2) * elem) : 0;
+        const size_t o_dump = backward ? lds_take((size_t)kWave * C * elem) : 0;
+        const int maxwg = backward ? 2 : 4;   // register file: the backward kernel runs two waves per SIMD at most
+        if (M <= solo_max_rows(backward, p.BL, p.DT) && p.mb <= kWave * M && used * kWavesPerWG <= kLdsPerCU / 2) {
+            p.solo = 1; p.coop = 0;
+            p.lk_M = M; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave * M - p.mb;
+            p.lk_off_y = 0; p.lk_off_gy = o_gy; p.lk_off_krows = o_kr; p.lk_off_dump = o_dump;
+            p.y_lds = 1;
+            p.lds_wave = used;
+            p.lds_bytes = used * kWavesPerWG;
+            int wgpc = (int)(kLdsPerCU / p.lds_bytes);
+            if (wgpc > maxwg) wgpc = maxwg;
+            const int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
+            const int64_t cap = (int64_t)kNumCU * wgpc;
+            p.grid = (int)(want < cap ? want : cap);
+            p.nslots = (int64_t)p.grid * kWavesPerWG;
+            p.S = kLockS;
+            p.nseg = NT / kLockS;
+        }
+    }
+
     // Workspace layout (all offsets 256-byte aligned).
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -253,8 +292,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.adj_slot = 4 * (int64_t)p.rowlen;   // two rows of 2C values per block column
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
         // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
-        const int NVC = p.lock ? p.lk_M * R + C + 2 : R + C + 2;
-        p.ckpt_slot = (int64_t)(p.lock ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
+        const int NVC = (p.lock || p.solo) ? p.lk_M * R + C + 2 : R + C + 2;
+        p.ckpt_slot = (int64_t)((p.lock || p.solo) ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
     }
     if (io_elem != elem) {

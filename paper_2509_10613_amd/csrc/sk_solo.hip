@@ -1,0 +1,406 @@
+// Solo sweeps (gfx950): one wavefront per path pair, for launches with enough pairs to fill the chip (the
+// Gram matrices) whose block rows fit one strip of 64 M lanes-rows.  The wavefront does everything itself,
+// with the per-lane building blocks of sk_lane.h:
+//
+//  * M block rows per lane, so a pair of up to 64 M block rows is a single strip: no hand-over rows, and the
+//    pipeline skew of 63 macro-steps is paid once per pair instead of once per 64 block rows;
+//  * no lane is ever masked (a lane whose column is outside the grid works with p = 0, A = B = 1), and
+//    the macro-steps whose 64 columns all lie inside the grid run without clamping or selects;
+//  * pairs are handed to the waves in y-major order: a wave works through a contiguous run of the pair
+//    sequence, so in a Gram matrix consecutive pairs share the y path, which then stays in LDS together
+//    with its gradient accumulator (one flush per run instead of one per pair).
+//
+// Backward (Section 3.4): forward sweep with a checkpoint of the lane state every 8 macro-steps and the
+// pair's bottom row kept in LDS, then the mirrored reverse sweep that recovers the forward values by
+// inverting Eq. (1) between checkpoints (see sk_lane.h), with the same drift guard as the other kernels:
+// a recovered state that differs from the exact checkpoint by more than 1e-9 of the lane's largest forward
+// value raises the call's error flag, and the finalisation returns NaN gradients.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "sk_dev.h"
+#include "sk_kernels.h"
+#include "sk_lane.h"
+
+namespace sk {
+
+// Pair q of the launch's sequence: y-major in Gram mode (q = m N + n), the identity for pair batches.
+__device__ __forceinline__ void solo_pair(const SweepArgs& a, long q, long& xi, long& yi, long& pid)
+{
+    if (a.gramM) {
+        const long N = a.npairs / a.gramM;
+        yi = q / N;
+        xi = q - yi * N;
+        pid = xi * a.gramM + yi;
+    } else {
+        xi = yi = pid = q;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+template <int BL, int D, int M>
+__global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo_fwd_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using LK = Lock<BL, D, M>;
+    constexpr int C = LK::C;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long slot = (long)blockIdx.x * kWavesPerWG + w;
+    const long nslots = (long)gridDim.x * kWavesPerWG;
+    SK_LDS real* ylds = (SK_LDS real*)(smem + (size_t)w * a.lds_wave);
+    const long q0 = slot * a.npairs / nslots, q1 = (slot + 1) * a.npairs / nslots;
+    const int nb = a.nb;
+    const int NT = nb + kWave - 1;
+    long cur_y = -1;
+
+    typename LK::Coef cf;
+    typename LK::Fwd f;
+    for (long q = q0; q < q1; ++q) {
+        long xi, yi, pid;
+        solo_pair(a, q, xi, yi, pid);
+        if (yi != cur_y) {
+            const real* dyg = a.dy + yi * a.ystride;
+            for (int t = lane; t < a.q * LK::DSc; t += kWave) ylds[t] = dyg[t];
+            cur_y = yi;
+        }
+        cf.setup(a, 0, lane, a.dx + xi * a.xstride, ylds);
+        f.init();
+
+        auto step = [&](auto edge_c, int J, const real (&y)[D]) {
+            constexpr bool EDGE = decltype(edge_c)::value;
+            real Ac[M], Bc[M];
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const real p = cf.template inner<EDGE>(m, J, y);
+                const real q2 = p * p;
+                Bc[m] = fma(q2, -1.0 / 12.0, 1.0);
+                Ac[m] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+            }
+            real recv[C];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(f.bot[cc], 1.0);
+            f.step(recv, Ac, Bc);
+        };
+        // macro-steps [T0, T1), the y increments fetched one step ahead
+        auto run = [&](auto edge_c, int T0, int T1) {
+            constexpr bool EDGE = decltype(edge_c)::value;
+            if (T0 >= T1) return;
+            int Ja, Jb, ba, bb;
+            real ya[D], yb[D];
+            cf.template fetch<EDGE>(T0, Ja, ba, ya);
+            int T = T0;
+            for (; T + 2 <= T1; T += 2) {
+                cf.template fetch<EDGE>(T + 1, Jb, bb, yb);
+                step(edge_c, Ja, ya);
+                cf.template fetch<EDGE>(T + 2 < T1 ? T + 2 : T + 1, Ja, ba, ya);
+                step(edge_c, Jb, yb);
+            }
+            if (T < T1) step(edge_c, Ja, ya);
+        };
+        const int Ti = nb > kWave - 1 ? kWave - 1 : NT;   // end of the leading edge range
+        run(std::true_type(), 0, Ti);
+        if (nb > kWave - 1) {
+            run(std::false_type(), kWave - 1, nb);
+            run(std::true_type(), nb, NT);
+        }
+        if (lane == kWave - 1) a.k_out[pid] = f.bot[C - 1];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward
+// ------------------------------------------------------------------------------------------------
+// (second launch bound: wavefronts per SIMD the register allocation has to leave room for)
+template <int BL, int D, int M>
+__global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    using LK = Lock<BL, D, M>;
+    constexpr int C = LK::C, RR = LK::RR, NVC = LK::NVC, S = kLockS;
+    constexpr int NVS = RR + 1 + C;
+    // the macro-steps of a segment are unrolled in pairs (the y buffers alternate) when a lane holds many channels:
+    // a full unroll keeps too much alive
+    constexpr int kUnroll = D * M > 16 ? 2 : S;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long slot = (long)blockIdx.x * kWavesPerWG + w;
+    const long nslots = (long)gridDim.x * kWavesPerWG;
+    unsigned char* mylds = smem + (size_t)w * a.lds_wave;
+    SK_LDS real* ylds = (SK_LDS real*)mylds;
+    SK_LDS real* gyl = (SK_LDS real*)(mylds + a.lk_off_gy);
+    SK_LDS real* krow = (SK_LDS real*)(mylds + a.lk_off_krows) + LK::PADF;   // bottom row, by node column
+    SK_LDS real* dump = (SK_LDS real*)(mylds + a.lk_off_dump);
+    real* ckpt = a.ckpt + slot * a.ckpt_slot + lane;
+    const long q0 = slot * a.npairs / nslots, q1 = (slot + 1) * a.npairs / nslots;
+    const int nb = a.nb;
+    const int NT = a.lk_NT;           // macro-steps, a multiple of S
+    const int nseg = NT / S;
+    const int ny = a.q * LK::DSc;
+    const bool plain = a.rs2 == 0;    // 64 lanes at 64 different y rows: plain read-modify-write is safe
+    long cur_y = -1;
+    real* gdy_cur = nullptr;
+    bool drift = false;
+
+    typename LK::Coef cf;
+    auto flush_gy = [&]() {
+        if (gdy_cur && a.want_gy) {
+            for (int t = lane; t < ny; t += kWave) {
+                const real v = gyl[t];
+                if (v != 0.0) unsafeAtomicAdd(&gdy_cur[t], v);
+            }
+        }
+    };
+
+    for (long q = q0; q < q1; ++q) {
+        long xi, yi, pid;
+        solo_pair(a, q, xi, yi, pid);
+        if (yi != cur_y) {
+            flush_gy();
+            const real* dyg = a.dy + yi * a.ystride;
+            for (int t = lane; t < ny; t += kWave) { ylds[t] = dyg[t]; gyl[t] = 0.0; }
+            cur_y = yi;
+            gdy_cur = a.gdy + yi * a.ystride;
+        }
+        cf.setup(a, 0, lane, a.dx + xi * a.xstride, ylds);
+        const real gk = a.grad_k[pid];
+
+        // ---- phase 1: forward, a checkpoint every S macro-steps, the bottom row into LDS ----
+        {
+            typename LK::Fwd f;
+            f.init();
+            for (int t = lane; t < LK::PADF + 1; t += kWave) krow[t - LK::PADF] = 1.0;   // columns left of the grid
+            SK_LDS real* const op0 = lane == kWave - 1 ? krow + (0 - (kWave - 1)) * C + 1 : dump + lane * C;
+            const int ostep = lane == kWave - 1 ? C : 0;
+            auto seg = [&](auto edge_c, int T0) {
+                constexpr bool EDGE = decltype(edge_c)::value;
+                SK_LDS real* op = op0 + T0 * ostep;
+                int J[2], b[2];
+                real y[2][D];
+                cf.template fetch<EDGE>(T0, J[0], b[0], y[0]);
+#pragma unroll kUnroll
+                for (int i = 0; i < S; ++i) {
+                    if (i + 1 < S) cf.template fetch<EDGE>(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);
+                    real Ac[M], Bc[M];
+#pragma unroll
+                    for (int m = 0; m < M; ++m) {
+                        const real p = cf.template inner<EDGE>(m, J[i & 1], y[i & 1]);
+                        const real q2 = p * p;
+                        Bc[m] = fma(q2, -1.0 / 12.0, 1.0);
+                        Ac[m] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                    }
+                    real recv[C];
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(f.bot[cc], 1.0);
+                    f.step(recv, Ac, Bc);
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) op[i * ostep + cc] = f.bot[cc];
+                }
+            };
+            for (int g = 0; g < nseg; ++g) {
+                f.store_ckpt(ckpt + (long)g * NVC * kWave);
+                if (cf.interior(g * S, S)) seg(std::false_type(), g * S);
+                else seg(std::true_type(), g * S);
+            }
+            f.store_ckpt(ckpt + (long)nseg * NVC * kWave);
+        }
+        if (a.k_out && lane == 0) a.k_out[pid] = krow[nb * C];
+        scratch_fence();   // the checkpoints are read back below
+
+        // ---- phase 2: the mirror image ----
+        {
+            typename LK::Rev rv;
+            rv.init();
+            real gacc[M][D];
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+#pragma unroll
+                for (int c = 0; c < D; ++c) gacc[m][c] = 0.0;
+            real kscale = 1.0;
+            const int up1 = lane > 0 ? -1 : 0;   // the bottom edge of the lane above travels with this lane's top edge
+            real cpn[NVS];
+            auto load_ckpt = [&](int idx) {
+                const real* cp = ckpt + (long)idx * NVC * kWave;
+#pragma unroll
+                for (int i = 0; i <= RR; ++i) cpn[i] = ld_scratch(cp + i * kWave);
+                cpn[RR + 1] = ld_scratch(cp + (RR + 1 + C) * kWave + up1);
+#pragma unroll
+                for (int i = 1; i < C; ++i) cpn[RR + 1 + i] = ld_scratch(cp + (RR + 1 + i - 1) * kWave + up1);
+            };
+            const int Tseed = nb - 1 + kWave - 1;   // macro-step in which the last lane is at the last column
+            auto seg = [&](auto edge_c, int T0) {
+                constexpr bool EDGE = decltype(edge_c)::value;
+                const SK_LDS real* kp = krow + (T0 - (kWave - 1)) * C;
+                int J[2], b[2];
+                real y[2][D];
+                cf.template fetch<EDGE>(T0 + S - 1, J[(S - 1) & 1], b[(S - 1) & 1], y[(S - 1) & 1]);
+#pragma unroll kUnroll
+                for (int i = S - 1; i >= 0; --i) {
+                    if (i >= 1) cf.template fetch<EDGE>(T0 + i - 1, J[(i - 1) & 1], b[(i - 1) & 1], y[(i - 1) & 1]);
+                    real Ac[M], Bc[M], iB[M], p6[M], accP[M];
+#pragma unroll
+                    for (int m = 0; m < M; ++m) {
+                        const real p = cf.template inner<EDGE>(m, J[i & 1], y[i & 1]);
+                        const real q2 = p * p;
+                        Bc[m] = fma(q2, -1.0 / 12.0, 1.0);
+                        Ac[m] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                        real r = __builtin_amdgcn_rcp(Bc[m]);
+                        iB[m] = fma(fma(-Bc[m], r, 1.0), r, r);
+                        p6[m] = p * (1.0 / 6.0);
+                    }
+                    // dF/dk[m, n] enters under the last lane at the last column
+                    const real seed = (T0 + i == Tseed) ? gk : 0.0;
+                    real recv[C], recvk[C];
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) {
+                        recv[cc] = wave_from_below_or(rv.up[cc], cc == C - 1 ? seed : 0.0);
+                        recvk[cc] = wave_from_below_or(rv.ktop[cc], kp[i * C + cc]);
+                    }
+                    rv.step(recv, recvk, Ac, Bc, iB, p6, accP);
+                    // the linear map of Section 3.4
+                    real gp[M];
+#pragma unroll
+                    for (int m = 0; m < M; ++m)
+                        gp[m] = (!EDGE || (unsigned)J[i & 1] < (unsigned)cf.nbl[m]) ? accP[m] : 0.0;
+                    if (a.want_gx) {
+#pragma unroll
+                        for (int m = 0; m < M; ++m)
+#pragma unroll
+                            for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp[m], y[i & 1][c], gacc[m][c]);
+                    }
+                    if (a.want_gy) {
+                        SK_LDS real* gq = gyl + __mul24(b[i & 1], LK::DSc);
+                        real t[D];
+#pragma unroll
+                        for (int c = 0; c < D; ++c) {
+                            real v = gp[0] * cf.dxr[0][c];
+#pragma unroll
+                            for (int m = 1; m < M; ++m) v = fma(gp[m], cf.dxr[m][c], v);
+                            t[c] = v;
+                        }
+                        if (plain) {
+                            if (!EDGE || (unsigned)J[i & 1] < (unsigned)nb) {
+#pragma unroll
+                                for (int c = 0; c < D; ++c) gq[c] += t[c];
+                            }
+                        } else {
+#pragma unroll
+                            for (int c = 0; c < D; ++c) lds_atomic_add(gq + c, t[c]);
+                        }
+                    }
+                }
+            };
+            load_ckpt(nseg);
+            for (int g = nseg - 1; g >= 0; --g) {
+#pragma unroll
+                for (int i = 0; i <= RR; ++i) kscale = fmax(kscale, fabs(cpn[i]));
+                if (g < nseg - 1) {
+#pragma unroll
+                    for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
+                        if (!(fabs(rv.kR[i] - cpn[i]) <= 1e-9 * kscale)) drift = true;
+                }
+#pragma unroll
+                for (int i = 0; i <= RR; ++i) rv.kR[i] = cpn[i];
+#pragma unroll
+                for (int i = 0; i < C; ++i) rv.ktop[i] = cpn[RR + 1 + i];
+                if (g >= 1) load_ckpt(g);   // for the next segment (to the left)
+                if (cf.interior(g * S, S)) seg(std::false_type(), g * S);
+                else seg(std::true_type(), g * S);
+            }
+            if (a.want_gx) {
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const int I = lane * M + m - a.lk_padb;
+                    if (I >= 0) {
+                        real* gq = a.gdx + xi * a.xstride + (long)(I >> a.rs1) * LK::DSc;
+#pragma unroll
+                        for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                    }
+                }
+            }
+        }
+        scratch_fence();   // the next pair overwrites the checkpoints
+    }
+    flush_gy();
+    if (drift) atomicExch(a.err, 2);
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+template <int BL, int D, int M>
+hipError_t launch_solo_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_fwd_kernel<BL, D, M>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((solo_fwd_kernel<BL, D, M>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+    return hipGetLastError();
+}
+
+template <int BL, int D, int M>
+hipError_t launch_solo_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((solo_bwd_kernel<BL, D, M>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+    return hipGetLastError();
+}
+
+template <int BL, int D>
+hipError_t launch_solo_m(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.lk_M > solo_max_rows(backward, BL, D)) return hipErrorInvalidValue;
+    if (backward) {
+        if (a.lk_M == 1) return launch_solo_bwd<BL, D, 1>(a, grid, lds, st);
+        if constexpr (solo_max_rows(true, BL, D) >= 2) return launch_solo_bwd<BL, D, 2>(a, grid, lds, st);
+    } else {
+        if (a.lk_M == 1) return launch_solo_fwd<BL, D, 1>(a, grid, lds, st);
+        if constexpr (solo_max_rows(false, BL, D) >= 2) return launch_solo_fwd<BL, D, 2>(a, grid, lds, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int BL>
+hipError_t launch_solo_bl(bool backward, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    switch (DT) {
+#ifndef SK_ONLY_C2   /* development builds instantiate a single shape */
+        case 2: return launch_solo_m<BL, 2>(backward, a, grid, lds, st);
+        case 4: return launch_solo_m<BL, 4>(backward, a, grid, lds, st);
+        case 5: return launch_solo_m<BL, 5>(backward, a, grid, lds, st);
+        case 6: return launch_solo_m<BL, 6>(backward, a, grid, lds, st);
+        case 8: return launch_solo_m<BL, 8>(backward, a, grid, lds, st);
+#endif
+        case 3: return launch_solo_m<BL, 3>(backward, a, grid, lds, st);
+        case 16: return launch_solo_m<BL, 16>(backward, a, grid, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.lk_M < 1 || (backward && (a.lk_NT % kLockS) != 0)) return hipErrorInvalidValue;
+    switch (BL) {
+        case 0: return launch_solo_bl<0>(backward, DT, a, grid, lds, st);
+        case 1: return launch_solo_bl<1>(backward, DT, a, grid, lds, st);
+#ifndef SK_ONLY_C2
+        case 2: return launch_solo_bl<2>(backward, DT, a, grid, lds, st);
+#endif
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sk

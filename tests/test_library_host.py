@@ -87,11 +87,18 @@ def test_launch_plan_of_the_five_configurations(lib):
     # c1: tiny, one strip: stencil, coefficient and auxiliary wave
     p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
     assert p["mode"] == "lock-step" and p["threads"] == "192" and p["strips"] == "1"
-    # c3 / c5 (Gram matrices with 65536 / 1048576 pairs): one wave per pair fills the chip
+    # c3 / c5 (Gram matrices with 65536 / 1048576 pairs of short paths): one wave per pair fills the chip, and
+    # a pair is a single strip (127 block rows at two per lane, 63 at one per lane)
     p = _plan(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64)
-    assert p["mode"] == "wave-per-pair" and p["kernel"] == "sweep_bwdu_kernel<1, 3, true>"
+    assert p["mode"] == "solo" and p["kernel"] == "solo_bwd_kernel<1, 3, 2>" and p["strips"] == "1"
     p = _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
-    assert p["mode"] == "wave-per-pair" and p["kernel"] == "sweep_fwd_kernel<0, 16, true>"
+    assert p["mode"] == "solo" and p["kernel"] == "solo_fwd_kernel<0, 16, 1>"
+    # many pairs of longer paths (more than 128 block rows): strips chained through global rows
+    p = _plan(binding.SK_OP_BWD, 4096, 0, 300, 300, 4, 0, 0, 0, f64)
+    assert p["mode"] == "wave-per-pair" and p["kernel"].startswith("sweep_bwdu_kernel<0, 4,") and p["strips"] == "5"
+    # more than 16 channels: runtime channel loop, y increments in global memory
+    p = _plan(binding.SK_OP_FWD, 4096, 0, 40, 40, 20, 1, 1, 0, f64)
+    assert p["mode"] == "wave-per-pair" and p["kernel"] == "sweep_fwd_kernel<1, 0, false>"
     # c4 (32 pairs, 2047 block rows each): too long for whole hand-over rows in LDS -> cooperative mode with rings
     p = _plan(binding.SK_OP_BWD, 32, 0, 2048, 2048, 8, 2, 2, 0, f64)
     assert p["mode"] == "cooperative" and p["grid"] == "32"
