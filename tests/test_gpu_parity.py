@@ -128,6 +128,35 @@ def test_c5_gram_reduced_and_symmetric():
     assert torch.equal(Kxx, Kxx.T)      # k(x,y) = k(y,x) bit for bit
 
 
+@pytest.mark.parametrize("name,nx,ny,dtype", [("c3", 64, 40, torch.float64), ("c3", 60, 44, torch.float32),
+                                              ("c5", 80, 70, torch.float64)])
+def test_gram_with_thousands_of_pairs(name, nx, ny, dtype):
+    # enough pairs that every wave works through a run of them (the y path and its gradient accumulator stay
+    # in LDS over the run), gradients included; then the symmetric case at the same size
+    w, X, Y = workloads.make(name, n_x=nx, n_y=ny)
+    assert "mode=solo" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, w.L, w.L, w.d, w.lam, w.lam, w.flags,
+                                                sk.SK_F64)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    W = workloads.upstream_weights(57, (nx, ny))
+    K, gX, gY = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), dev(W, dtype), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    Kref, gXr, gYr = oracle.gram(Xr, Yr, rounded(W, dtype), w.lam, w.lam, w.flags)
+    check_values(host(K), Kref, dtype, "K")
+    check_grads(host(gX), gXr, dtype, "grad_X")
+    check_grads(host(gY), gYr, dtype, "grad_Y")
+    Kf = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), None, w.lam, w.lam, w.flags)
+    check_values(host(Kf), Kref, dtype, "K (forward only)")
+    Ws = workloads.upstream_weights(58, (nx, nx))
+    x = dev(X, dtype)
+    Kxx, gXX, none = sk.sigkernel_gram(x, x, dev(Ws, dtype), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    Kxr, gXXr, _ = oracle.gram(Xr, Xr, rounded(Ws, dtype), w.lam, w.lam, w.flags)
+    assert none is None
+    check_values(host(Kxx), Kxr, dtype, "K(X,X)")
+    check_grads(host(gXX), gXXr, dtype, "grad_X total")
+    assert torch.equal(Kxx, Kxx.T)
+
+
 # ------------------------------------------------------------------ full-size runs on sampled outputs
 def test_c3_full_size_sampled_entries():
     w, X, Y = workloads.make("c3")
