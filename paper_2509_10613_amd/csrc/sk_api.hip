@@ -104,6 +104,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.coop_off_obox = (unsigned)p.coop_off_obox; a.coop_off_ring = (unsigned)p.coop_off_ring;
     a.coop_ring_stride = (unsigned)p.coop_ring_stride;
     a.solo = p.solo;
+    a.tile = p.tile;
     a.lock = p.lock; a.lk_M = p.lk_M; a.lk_ns = p.lk_ns; a.lk_NT = p.lk_NT; a.lk_padb = p.lk_padb;
     a.lk_rowlen = p.lk_rowlen;
     a.lk_off_y = (unsigned)p.lk_off_y; a.lk_off_gy = (unsigned)p.lk_off_gy; a.lk_off_cring = (unsigned)p.lk_off_cring;
@@ -152,6 +153,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         SK_CHECK(hipEventRecord(tl.start, st));
     }
     if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     if (timed) {
@@ -327,7 +329,11 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     char kern[96];
     int threads;
     const char* mode;
-    if (p.solo) {
+    if (p.tile) {
+        mode = "tile";
+        std::snprintf(kern, sizeof(kern), "tile_%s_kernel<%d>", backward ? "bwd" : "fwd", p.DT / 4);
+        threads = sk::kWavesPerWG * sk::kWave;
+    } else if (p.solo) {
         mode = "solo";
         std::snprintf(kern, sizeof(kern), "solo_%s_kernel<%d, %d, %d>", backward ? "bwd" : "fwd", p.BL, p.DT, p.lk_M);
         threads = sk::kWavesPerWG * sk::kWave;
@@ -346,8 +352,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
                   "workspace_bytes=%zu",
-                  mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo) ? p.lk_ns : p.ns,
-                  (p.lock || p.solo) ? p.lk_M : 1,
+                  mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile) ? p.lk_ns : p.ns,
+                  (p.lock || p.solo || p.tile) ? p.lk_M : 1,
                   fused ? 1 : 0, p.total);
     return SK_OK;
 }

@@ -57,6 +57,8 @@ struct SweepArgs {
     unsigned lk_off_ck, lk_ck_stride;         // checkpoint staging (backward)
     int solo;            // 1: solo kernels (one wave per pair, a single strip of 64 * lk_M block rows; uses lk_M,
                          // lk_NT, lk_padb and, as offsets inside a wave's LDS, lk_off_gy / lk_off_krows / lk_off_dump)
+    int tile;            // 1: tile kernels (one wave per pair, increment Gram matrix in LDS, contractions by MFMA; uses
+                         // lk_NT, lk_padb, lk_off_krows / lk_off_dump as offsets inside a wave's LDS)
     // lock-step mode on a batch of pairs of double paths: the kernels read the caller's points and write the
     // caller's gradients themselves (no preparation and finalisation launches, no global accumulators)
     int fused;
@@ -80,6 +82,8 @@ hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // solo mode (a.solo != 0), defined in sk_solo.hip
 hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
+// tile mode (a.tile != 0), defined in sk_tile.hip
+hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // lock-step mode (a.lock != 0), defined in sk_lockstep.hip
 hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
                                  hipStream_t st);

@@ -56,6 +56,7 @@ struct Plan {
     int uncompute = 0;   // backward: reverse sweep recovers forward values by inverting Eq. (1) (no replay ring)
     size_t coop_off_gdy = 0, coop_off_flags = 0, coop_off_obox = 0, coop_off_ring = 0, coop_ring_stride = 0;
     // lock-step mode: one workgroup per pair, per strip one stencil wave and one coefficient wave
+    int tile = 0;   // one wave per pair, at most 64 x 64 cells, contractions on the matrix cores (sk_tile.hip)
     int solo = 0;   // one wave per pair, a single strip of 64 * lk_M block rows (many pairs of short paths)
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
     size_t lk_off_y = 0, lk_off_gy = 0, lk_off_cring = 0, lk_off_gp = 0, lk_off_krows = 0, lk_off_arows = 0,
@@ -87,6 +88,11 @@ constexpr int solo_max_rows(bool backward, int BL, int DT)
     if (backward) return (BL <= 1 && DT <= 8) ? 2 : 1;
     return (BL >= 2 && DT >= 16) ? 1 : 2;
 }
+
+// Tile mode: the increment Gram matrix of a pair as a 64 x 64 array of doubles in LDS, column stride
+// kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most
+// two-way bank conflicted), kTileCols columns (-1 .. 64: a zero guard column on either side).
+constexpr int kTileStride = 66, kTileCols = 66;
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
@@ -279,6 +285,29 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         }
     }
 
+    // Tile mode: many pairs of at most 64 x 64 unrefined cells with 8 or 16 channels; the contractions over
+    // the channels and over the rows / columns run as MFMA tiles, the sweep reads one number per cell from LDS.
+    if (!p.lock && p.BL == 0 && p.rs1 == 0 && p.rs2 == 0 && (p.DT == 8 || p.DT == 16) && p.mb > kWave / 2 &&
+        p.mb <= kWave && p.nb > kWave / 2 && p.nb <= kWave && (!backward || p.uncompute)) {
+        const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
+        size_t used = 0;
+        auto lds_take = [&](size_t bytes) { size_t o = used; used = align_up(used + bytes, 256); return o; };
+        lds_take((size_t)kTileCols * kTileStride * elem);
+        const size_t o_kr = backward ? lds_take(((size_t)kWave + (size_t)NT + 2) * elem) : 0;
+        const size_t o_dump = backward ? lds_take((size_t)kWave * elem) : 0;
+        p.tile = 1; p.solo = 0; p.coop = 0;
+        p.lk_M = 1; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave - p.mb;
+        p.lk_off_y = 0; p.lk_off_gy = 0; p.lk_off_krows = o_kr; p.lk_off_dump = o_dump;
+        p.y_lds = 0;
+        p.lds_wave = used;
+        p.lds_bytes = used * kWavesPerWG;   // one workgroup per compute unit
+        const int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
+        p.grid = (int)(want < kNumCU ? want : kNumCU);
+        p.nslots = (int64_t)p.grid * kWavesPerWG;
+        p.S = kLockS;
+        p.nseg = NT / kLockS;
+    }
+
     // Workspace layout (all offsets 256-byte aligned).
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -292,8 +321,9 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.adj_slot = 4 * (int64_t)p.rowlen;   // two rows of 2C values per block column
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
         // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
-        const int NVC = (p.lock || p.solo) ? p.lk_M * R + C + 2 : R + C + 2;
-        p.ckpt_slot = (int64_t)((p.lock || p.solo) ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
+        const bool lean = p.lock || p.solo || p.tile;
+        const int NVC = lean ? p.lk_M * R + C + 2 : R + C + 2;
+        p.ckpt_slot = (int64_t)(lean ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
     }
     if (io_elem != elem) {

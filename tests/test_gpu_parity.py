@@ -134,8 +134,8 @@ def test_gram_with_thousands_of_pairs(name, nx, ny, dtype):
     # enough pairs that every wave works through a run of them (the y path and its gradient accumulator stay
     # in LDS over the run), gradients included; then the symmetric case at the same size
     w, X, Y = workloads.make(name, n_x=nx, n_y=ny)
-    assert "mode=solo" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, w.L, w.L, w.d, w.lam, w.lam, w.flags,
-                                                sk.SK_F64)
+    mode = "mode=tile" if name == "c5" else "mode=solo"   # c5: contractions on the matrix cores
+    assert mode in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, w.L, w.L, w.d, w.lam, w.lam, w.flags, sk.SK_F64)
     Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
     W = workloads.upstream_weights(57, (nx, ny))
     K, gX, gY = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), dev(W, dtype), w.lam, w.lam, w.flags)
@@ -155,6 +155,63 @@ def test_gram_with_thousands_of_pairs(name, nx, ny, dtype):
     check_values(host(Kxx), Kxr, dtype, "K(X,X)")
     check_grads(host(gXX), gXXr, dtype, "grad_X total")
     assert torch.equal(Kxx, Kxx.T)
+
+
+@pytest.mark.parametrize("L1,L2,d,flags,dtype", [(64, 64, 16, 0, torch.float64), (40, 60, 16, 1, torch.float64),
+                                                  (65, 34, 7, 1, torch.float64), (50, 65, 12, 0, torch.float32),
+                                                  (34, 34, 8, 0, torch.float64)])
+def test_tile_mode_shapes(L1, L2, d, flags, dtype):
+    # tile kernels (increment Gram matrix of a pair in LDS, contractions by MFMA): unequal lengths, channel
+    # counts that do not fill the operand registers, time augmentation, float callers, the largest grid (64 x 64)
+    nx, ny = 37, 31   # more pairs than lock-step mode takes
+    rng = np.random.default_rng(700 + L1 + d)
+    X = np.cumsum(rng.normal(0.0, (1.0 / (d * L1)) ** 0.5, (nx, L1, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L2)) ** 0.5, (ny, L2, d)), axis=1)
+    assert "mode=tile" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L1, L2, d, 0, 0, flags, sk.SK_F64)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    W = workloads.upstream_weights(59, (nx, ny))
+    K, gX, gY = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), dev(W, dtype), 0, 0, flags)
+    Kf = sk.sigkernel_gram(dev(X, dtype), dev(Y, dtype), None, 0, 0, flags)
+    torch.cuda.synchronize()
+    Kref, gXr, gYr = oracle.gram(Xr, Yr, rounded(W, dtype), 0, 0, flags)
+    check_values(host(K), Kref, dtype, "K")
+    check_values(host(Kf), Kref, dtype, "K (forward only)")
+    check_grads(host(gX), gXr, dtype, "grad_X")
+    check_grads(host(gY), gYr, dtype, "grad_Y")
+
+
+def test_tile_mode_pair_batch():
+    # a batch of pairs (not a Gram matrix) large enough to leave lock-step mode: every pair brings its own y path
+    B, L, d = 1100, 48, 16
+    rng = np.random.default_rng(77)
+    X = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (B, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (B, L, d)), axis=1)
+    assert "mode=tile" in sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L, L, d, 0, 0, 0, sk.SK_F64)
+    gk = workloads.upstream_weights(60, (B,))
+    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 0, 0, 0)
+    kf = sk.sigkernel_fwd(dev(X), dev(Y), 0, 0, 0)
+    torch.cuda.synchronize()
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, 0, 0, 0)
+    check_values(host(k), kr, torch.float64, "k")
+    check_values(host(kf), kr, torch.float64, "k (forward only)")
+    check_grads(host(gx), gxr, torch.float64, "grad_x")
+    check_grads(host(gy), gyr, torch.float64, "grad_y")
+
+
+def test_short_paths_with_many_channels_stay_solo():
+    # 16 channels but fewer than 33 cells per side: the solo kernels (channel contraction on the vector units)
+    nx, ny, L, d = 70, 60, 30, 16
+    rng = np.random.default_rng(78)
+    X = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (nx, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (ny, L, d)), axis=1)
+    assert "solo_bwd_kernel<0, 16, 1>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
+    W = workloads.upstream_weights(61, (nx, ny))
+    K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), 0, 0, 0)
+    torch.cuda.synchronize()
+    Kref, gXr, gYr = oracle.gram(X, Y, W, 0, 0, 0)
+    check_values(host(K), Kref, torch.float64, "K")
+    check_grads(host(gX), gXr, torch.float64, "grad_X")
+    check_grads(host(gY), gYr, torch.float64, "grad_Y")
 
 
 # ------------------------------------------------------------------ full-size runs on sampled outputs

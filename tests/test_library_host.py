@@ -87,12 +87,21 @@ def test_launch_plan_of_the_five_configurations(lib):
     # c1: tiny, one strip: stencil, coefficient and auxiliary wave
     p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
     assert p["mode"] == "lock-step" and p["threads"] == "192" and p["strips"] == "1"
-    # c3 / c5 (Gram matrices with 65536 / 1048576 pairs of short paths): one wave per pair fills the chip, and
-    # a pair is a single strip (127 block rows at two per lane, 63 at one per lane)
+    # c3 (Gram matrix with 65536 pairs of short paths): one wave per pair fills the chip, and a pair is a single
+    # strip (127 block rows at two per lane)
     p = _plan(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64)
     assert p["mode"] == "solo" and p["kernel"] == "solo_bwd_kernel<1, 3, 2>" and p["strips"] == "1"
+    # c5 (1048576 pairs, 63 x 63 unrefined cells, 16 channels): the channel contraction dominates -> tile mode,
+    # increment Gram matrix of a pair in LDS, contractions on the matrix cores, one workgroup per compute unit
     p = _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
-    assert p["mode"] == "solo" and p["kernel"] == "solo_fwd_kernel<0, 16, 1>"
+    assert p["mode"] == "tile" and p["kernel"] == "tile_fwd_kernel<4>" and p["grid"] == "256"
+    p = _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
+    assert p["mode"] == "tile" and p["kernel"] == "tile_bwd_kernel<4>" and int(p["lds_bytes"]) <= 160 * 1024
+    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 7, 0, 0, 1, f64)["kernel"] == "tile_bwd_kernel<2>"
+    # the same shape with few channels, with dyadic refinement, or with very short paths stays with the solo kernels
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 3, 0, 0, 0, f64)["mode"] == "solo"
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 1, 1, 0, f64)["mode"] == "solo"
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 30, 64, 16, 0, 0, 0, f64)["mode"] == "solo"
     # many pairs of longer paths (more than 128 block rows): strips chained through global rows
     p = _plan(binding.SK_OP_BWD, 4096, 0, 300, 300, 4, 0, 0, 0, f64)
     assert p["mode"] == "wave-per-pair" and p["kernel"].startswith("sweep_bwdu_kernel<0, 4,") and p["strips"] == "5"
