@@ -26,8 +26,12 @@ def build(force: bool = False, verbose: bool = False, extra_flags=()) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
 
+    hdrs = [os.path.join(CSRC, f) for f in HEADERS] + [os.path.join(ROOT, "include", "sigkernel.h")]
+
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        if not force and not extra_flags and not _stale(obj, [os.path.join(CSRC, src)] + hdrs):
+            return obj   # this object is newer than its source and every header
         cmd = ["hipcc"] + FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

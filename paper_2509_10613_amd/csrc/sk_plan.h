@@ -93,6 +93,7 @@ constexpr int solo_max_rows(bool backward, int BL, int DT)
 // kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most
 // two-way bank conflicted), kTileCols columns (-1 .. 64: a zero guard column on either side).
 constexpr int kTileStride = 66, kTileCols = 66;
+constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
@@ -293,11 +294,12 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         size_t used = 0;
         auto lds_take = [&](size_t bytes) { size_t o = used; used = align_up(used + bytes, 256); return o; };
         lds_take((size_t)kTileCols * kTileStride * elem);
-        const size_t o_kr = backward ? lds_take(((size_t)kWave + (size_t)NT + 2) * elem) : 0;
-        const size_t o_dump = backward ? lds_take((size_t)kWave * elem) : 0;
+        // backward: compact checkpoints (two doubles per lane) every kTileCkChunks chunks of 8 macro-steps
+        const int nck = backward ? (NT / kLockS - 1) / kTileCkChunks : 0;
+        const size_t o_ck = nck ? lds_take((size_t)nck * 2 * kWave * elem) : 0;
         p.tile = 1; p.solo = 0; p.coop = 0;
         p.lk_M = 1; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave - p.mb;
-        p.lk_off_y = 0; p.lk_off_gy = 0; p.lk_off_krows = o_kr; p.lk_off_dump = o_dump;
+        p.lk_off_y = 0; p.lk_off_gy = 0; p.lk_off_krows = 0; p.lk_off_dump = 0; p.lk_off_ck = o_ck;
         p.y_lds = 0;
         p.lds_wave = used;
         p.lds_bytes = used * kWavesPerWG;   // one workgroup per compute unit
@@ -323,7 +325,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
         const bool lean = p.lock || p.solo || p.tile;
         const int NVC = lean ? p.lk_M * R + C + 2 : R + C + 2;
-        p.ckpt_slot = (int64_t)(lean ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
+        p.ckpt_slot = p.tile ? 0 : (int64_t)(lean ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
     }
     if (io_elem != elem) {

@@ -20,9 +20,10 @@
 //
 // P is addressed as P[(b + 1) * 66 + a] (a = lane-space row, b = column): the even column stride keeps the
 // three access patterns (row-contiguous, skewed by the sweep, and transposed for G^T) at most two-way bank
-// conflicted.  Columns -1 and nb hold zeros: a lane whose column T - lane is outside the grid is clamped
-// onto them and works with p = 0, A = B = 1, which carries the boundary value 1 forward and a zero adjoint
-// backward; no lane is ever masked.  The rows of a pair are aligned to the bottom of the wave (row a of the
+// conflicted.  Column nb holds zeros: a lane whose column J = T - lane is outside the grid on either side
+// reads it (min of J as an unsigned number and nb) and works with p = 0, A = B = 1, which carries the
+// boundary value 1 forward and a zero adjoint backward; no lane is ever masked.  Column -1 takes the dF/dp
+// of lanes left of the grid, which nobody reads.  The rows of a pair are aligned to the bottom of the wave (row a of the
 // pair sits in lane a + 64 - mb), so the result leaves through lane 63.
 #include <hip/hip_runtime.h>
 
@@ -49,12 +50,18 @@ __device__ __forceinline__ void tile_pair(const SweepArgs& a, long q, long& xi, 
     }
 }
 
-__device__ __forceinline__ int clamp_range(int J, int lo, int hi)
+// Column a lane reads p from: J inside the grid, else the zero column nb (J < 0 is a huge unsigned number).
+__device__ __forceinline__ int read_col(int J, int nb) { return (int)min((unsigned)J, (unsigned)nb); }
+// Column a lane writes dF/dp to: J inside the grid, the zero column nb to its right (the value is zero
+// there), the unread column -1 to its left.
+__device__ __forceinline__ int write_col(int J, int nb)
 {
     int r;
-    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(J), "v"(lo), "v"(hi));
+    asm("v_med3_i32 %0, %1, -1, %2" : "=v"(r) : "v"(J), "s"(nb));
     return r;
 }
+
+constexpr int kTilePF = 8;   // the sweeps read p this many macro-steps ahead (LDS latency off the serial chain)
 
 template <int KC>
 struct Tile {
@@ -64,24 +71,38 @@ struct Tile {
     // (zero for rows above the grid).  A tile of Delta^T is sum_kc mfma(yb[J][kc], xb[I][kc]).
     static __device__ __forceinline__ void load_b(const real* inc, int DS, int rowoff, int lane, real (&v)[4][KC])
     {
-        const int n16 = lane & 15, g16 = lane >> 4;
+        int n16 = lane & 15;
+        const int g16 = lane >> 4;
+        asm volatile("" : "+v"(n16));   // addresses are formed per call, not kept alive as loop invariants
 #pragma unroll
         for (int T = 0; T < 4; ++T) {
             const int row = 16 * T + n16 - rowoff;
             const real* rp = inc + (long)(row >= 0 ? row : 0) * DS + g16;
+            real t[KC];
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) v[T][kc] = row >= 0 ? rp[4 * kc] : 0.0;
+            for (int kc = 0; kc < KC; ++kc) t[kc] = rp[4 * kc];
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) v[T][kc] = row >= 0 ? t[kc] : 0.0;
         }
     }
     // Operand layout of the linear map: v[kk] = inc[4 kk + lane / 16 - rowoff][lane % 16] (B operand, the
     // contraction runs over the rows of the path, the 16 output columns are the channels).
     static __device__ __forceinline__ void load_c(const real* inc, int DS, int rowoff, int lane, real (&v)[16])
     {
-        const int n16 = lane & 15, g16 = lane >> 4;
+        const int n16 = lane & 15;
+        int g16 = lane >> 4;
+        asm volatile("" : "+v"(g16));   // addresses are formed per call, not kept alive as loop invariants
+        const int ch = n16 < D ? n16 : 0;
+        real t[16];
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk) {
             const int row = 4 * kk + g16 - rowoff;
-            v[kk] = (row >= 0 && n16 < D) ? inc[(long)(row >= 0 ? row : 0) * DS + (n16 < D ? n16 : 0)] : 0.0;
+            t[kk] = inc[(long)(row >= 0 ? row : 0) * DS + ch];
+        }
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int row = 4 * kk + g16 - rowoff;
+            v[kk] = (row >= 0 && n16 < D) ? t[kk] : 0.0;
         }
     }
     // Delta tiles into P.  Result register r of lane l of tile (J, I) is Delta[a = 16 I + l % 16][b = 16 J + l / 16 + 4 r].
@@ -137,9 +158,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_fwd_kernel(SweepAr
     long cur_y = -1;
     real yb[4][KC];
 
-    // guard columns -1 and 64
-    P[lane] = 0.0;
-    P[(kTileCols - 1) * kTileStride + lane] = 0.0;
+    P[(kTileCols - 1) * kTileStride + lane] = 0.0;   // column 64: the zero column of a pair with 64 columns
 
     typename LK::Fwd f;
     for (long q = q0; q < q1; ++q) {
@@ -154,17 +173,30 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_fwd_kernel(SweepAr
         TL::gram_tiles(P, yb, xb, lane, padb, nb, a.tc);
 
         f.init();
-        auto readp = [&](int T) { return P[__mul24(clamp_range(T - lane, -1, nb), kTileStride) + pbase]; };
-        real pn = readp(0);
-#pragma unroll 2
-        for (int T = 0; T < NT; ++T) {
-            const real p = pn;
-            pn = readp(T + 1);
+        auto readp = [&](int J) { return P[__mul24(read_col(J, nb), kTileStride) + pbase]; };
+        auto step = [&](real p) {
             real Ac[1], Bc[1], recv[1];
             TL::coef_fwd(p, Ac[0], Bc[0]);
             recv[0] = wave_from_above_or(f.bot[0], 1.0);
             f.step(recv, Ac, Bc);
+        };
+        real pq[kTilePF];
+        int Jn = -lane;   // column of the next macro-step to fetch p for
+#pragma unroll
+        for (int i = 0; i < kTilePF; ++i) pq[i] = readp(Jn + i);
+        Jn += kTilePF;
+        int T0 = 0;
+        for (; T0 + kTilePF <= NT; T0 += kTilePF, Jn += kTilePF) {
+#pragma unroll
+            for (int i = 0; i < kTilePF; ++i) {
+                const real p = pq[i];
+                pq[i] = readp(Jn + i);   // past the last step: the zero column, unused
+                step(p);
+            }
         }
+#pragma unroll
+        for (int i = 0; i < kTilePF; ++i)
+            if (T0 + i < NT) step(pq[i]);
         if (lane == kWave - 1) a.k_out[pid] = f.bot[0];
     }
 }
@@ -178,8 +210,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
     extern __shared__ __align__(16) unsigned char smem[];
     using TL = Tile<KC>;
     using LK = Lock<0, 4 * KC, 1>;
-    constexpr int C = 1, RR = 1, NVC = LK::NVC, S = kLockS;
-    constexpr int NVS = RR + 1 + C;
+    constexpr int S = kLockS;          // macro-steps per unrolled chunk
+    constexpr int CK = kTileCkChunks;  // chunks between checkpoints
     const int lane = threadIdx.x & 63;
     const int n16 = lane & 15, g16 = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -187,20 +219,27 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
     const long nslots = (long)gridDim.x * kWavesPerWG;
     unsigned char* mylds = smem + (size_t)w * a.lds_wave;
     SK_LDS real* P = (SK_LDS real*)mylds;
-    SK_LDS real* krow = (SK_LDS real*)(mylds + a.lk_off_krows) + LK::PADF;   // bottom row, by node column
-    SK_LDS real* dump = (SK_LDS real*)(mylds + a.lk_off_dump);
-    real* ckpt = a.ckpt + slot * a.ckpt_slot + lane;
+    // Checkpoints of the forward sweep, in LDS: per lane the last two values of its row, k[a + 1][J] and
+    // k[a + 1][J - 1] (J the column the lane is about to process); the row above is the neighbouring lane's.
+    SK_LDS real* ckl = (SK_LDS real*)(mylds + a.lk_off_ck) + lane;
+    // The bottom row of the pair (the last lane's outputs, which no lane recovers in the reverse sweep) sits
+    // in the spare slot 64 of P's columns, by node column c = -1 .. 64 (every node left of the grid is 1).
+    SK_LDS real* const krow = P + kTileStride + kWave;
+    // Macro-steps run from 0 to NT - 1 with NT a multiple of S; the sweep proper ends at the last one (the last lane at
+    // the last column), so that the reverse sweep starts with the seed in place, and begins tpad steps late.
+    const int NT = a.lk_NT;
+    const int tpad = NT - (a.nb + kWave - 1);   // 0 .. S - 1
     const long q0 = slot * a.npairs / nslots, q1 = (slot + 1) * a.npairs / nslots;
     const int nb = a.nb, padb = a.lk_padb;
-    const int NT = a.lk_NT;           // macro-steps, a multiple of S
-    const int nseg = NT / S;
+    const int nch = NT / S;
     const int pbase = kTileStride + lane;
+    const bool last = lane == kWave - 1;
     long cur_y = -1;
     real* gdy_cur = nullptr;
     bool drift = false;
 
-    P[lane] = 0.0;
-    P[(kTileCols - 1) * kTileStride + lane] = 0.0;
+    P[(kTileCols - 1) * kTileStride + lane] = 0.0;   // column 64: the zero column of a pair with 64 columns
+    if (last) krow[-kTileStride] = 1.0;              // node column -1 (stands for all nodes left of the grid)
 
     real yb[4][KC], yc[16];
     real4 gy[4];
@@ -216,8 +255,17 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                 }
         }
     };
-    auto readp = [&](int T) { return P[__mul24(clamp_range(T - lane, -1, nb), kTileStride) + pbase]; };
+    auto readp = [&](int J) { return P[__mul24(read_col(J, nb), kTileStride) + pbase]; };
 
+    // Operands of the pair in work, loaded while the previous pair was in the linear map.
+    real xb[4][KC];
+    real gk = 0.0;
+    if (q0 < q1) {
+        long xi, yi, pid;
+        tile_pair(a, q0, xi, yi, pid);
+        TL::load_b(a.dx + xi * a.xstride, a.DS, padb, lane, xb);
+        gk = a.grad_k[pid];
+    }
     for (long q = q0; q < q1; ++q) {
         long xi, yi, pid;
         tile_pair(a, q, xi, yi, pid);
@@ -231,98 +279,120 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
             cur_y = yi;
             gdy_cur = a.gdy + yi * a.ystride;
         }
-        const real* dxg = a.dx + xi * a.xstride;
-        {
-            real xb[4][KC];
-            TL::load_b(dxg, a.DS, padb, lane, xb);
-            TL::gram_tiles(P, yb, xb, lane, padb, nb, a.tc);
-        }
-        const real gk = a.grad_k[pid];
+        TL::gram_tiles(P, yb, xb, lane, padb, nb, a.tc);
 
-        // ---- phase 1: forward, a checkpoint every S macro-steps, the bottom row into LDS ----
+        // ---- phase 1: forward; a checkpoint every CK chunks and the bottom row into LDS ----
+        real kR0, kR1;   // exact state the reverse sweep starts from: k[a][J], k[a + 1][J]
         {
             typename LK::Fwd f;
             f.init();
-            for (int t = lane; t < LK::PADF + 1; t += kWave) krow[t - LK::PADF] = 1.0;   // columns left of the grid
-            SK_LDS real* const op0 = lane == kWave - 1 ? krow + (0 - (kWave - 1)) * C + 1 : dump + lane * C;
-            const int ostep = lane == kWave - 1 ? C : 0;
-            real pn = readp(0);
-            for (int g = 0; g < nseg; ++g) {
-                f.store_ckpt(ckpt + (long)g * NVC * kWave);
-                SK_LDS real* op = op0 + g * S * ostep;
+            real pq[S];
+            int Jn = -tpad - lane;   // column of the next macro-step to fetch p for
+#pragma unroll
+            for (int i = 0; i < S; ++i) pq[i] = readp(Jn + i);
+            Jn += S;
+            int cl = -tpad - (kWave - 1) + 1;   // node column the last lane writes in the chunk's first macro-step
+            for (int g = 0; g < nch; ++g, Jn += S, cl += S) {
+                if (g > 0 && g % CK == 0) {
+                    SK_LDS real* cp = ckl + (g / CK - 1) * (2 * kWave);
+                    cp[0] = f.left[1];
+                    cp[kWave] = f.blc;
+                }
 #pragma unroll
                 for (int i = 0; i < S; ++i) {
-                    const real p = pn;
-                    pn = readp(g * S + i + 1);
+                    const real p = pq[i];
+                    pq[i] = readp(Jn + i);   // past the last step: the zero column, unused
                     real Ac[1], Bc[1], recv[1];
                     TL::coef_fwd(p, Ac[0], Bc[0]);
                     recv[0] = wave_from_above_or(f.bot[0], 1.0);
                     f.step(recv, Ac, Bc);
-                    op[i * ostep] = f.bot[0];
+                    const int c = cl + i > -1 ? cl + i : -1;   // wave-uniform
+                    if (last) krow[c * kTileStride] = f.bot[0];
                 }
             }
-            f.store_ckpt(ckpt + (long)nseg * NVC * kWave);
+            kR0 = f.left[0];
+            kR1 = f.left[1];
         }
-        if (a.k_out && lane == 0) a.k_out[pid] = krow[nb * C];
-        scratch_fence();   // the checkpoints are read back below
+        if (a.k_out && lane == 0) a.k_out[pid] = krow[nb * kTileStride];
 
         // ---- phase 2: the mirror image; G = dF/dp replaces p in place ----
         {
             typename LK::Rev rv;
             rv.init();
+            // dF/dk[m, n] is the adjoint of the bottom right node of the last lane's first block in this direction
+            if (last) rv.accL[1] = gk;
+            rv.kR[0] = kR0;
+            rv.kR[1] = kR1;
+            rv.ktop[0] = kR0;
             real kscale = 1.0;
-            const int up1 = lane > 0 ? -1 : 0;   // the bottom edge of the lane above travels with this lane's top edge
-            real cpn[NVS];
-            auto load_ckpt = [&](int idx) {
-                const real* cp = ckpt + (long)idx * NVC * kWave;
+            // p of the macro-steps of a chunk is read one chunk ahead (P is overwritten with G behind the sweep
+            // only: a lane writes column J after it has read columns J - S .. J)
+            real pq[S], kq[S];
+            int Jb = (nch - 1) * S - tpad - lane;   // column of this lane in the first macro-step of the chunk
 #pragma unroll
-                for (int i = 0; i <= RR; ++i) cpn[i] = ld_scratch(cp + i * kWave);
-                cpn[RR + 1] = ld_scratch(cp + (RR + 1 + C) * kWave + up1);
-            };
-            const int Tseed = nb - 1 + kWave - 1;   // macro-step in which the last lane is at the last column
-            load_ckpt(nseg);
-            for (int g = nseg - 1; g >= 0; --g) {
+            for (int i = 0; i < S; ++i) pq[i] = readp(Jb + i);
+            int cl = (nch - 1) * S - tpad - (kWave - 1);   // node column under the last lane's block, first macro-step
+            for (int g = nch - 1; g >= 0; --g, Jb -= S, cl -= S) {
 #pragma unroll
-                for (int i = 0; i <= RR; ++i) kscale = fmax(kscale, fabs(cpn[i]));
-                if (g < nseg - 1) {
-#pragma unroll
-                    for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
-                        if (!(fabs(rv.kR[i] - cpn[i]) <= 1e-9 * kscale)) drift = true;
+                for (int i = 0; i < S; ++i) {   // the last lane's bottom edge, before any store of this chunk
+                    const int c = cl + i > -1 ? cl + i : -1;
+                    kq[i] = krow[c * kTileStride];
                 }
 #pragma unroll
-                for (int i = 0; i <= RR; ++i) rv.kR[i] = cpn[i];
-                rv.ktop[0] = cpn[RR + 1];
-                if (g >= 1) load_ckpt(g);   // for the next segment (to the left)
-                const int T0 = g * S;
-                const SK_LDS real* kp = krow + (T0 - (kWave - 1)) * C;
-                real pn = readp(T0 + S - 1);
-#pragma unroll
                 for (int i = S - 1; i >= 0; --i) {
-                    const int J = T0 + i - lane;
-                    const real p = pn;
-                    if (i >= 1) pn = readp(T0 + i - 1);
+                    const int J = Jb + i;
+                    const real p = pq[i];
+                    pq[i] = readp(J - S);   // left of the grid: the zero column
                     real Ac[1], Bc[1], iB[1], p6[1], accP[1];
                     TL::coef_fwd(p, Ac[0], Bc[0]);
                     const real r = __builtin_amdgcn_rcp(Bc[0]);
                     iB[0] = fma(fma(-Bc[0], r, 1.0), r, r);
                     p6[0] = p * (1.0 / 6.0);
-                    // dF/dk[m, n] enters under the last lane at the last column
-                    const real seed = (T0 + i == Tseed) ? gk : 0.0;
                     real recv[1], recvk[1];
-                    recv[0] = wave_from_below_or(rv.up[0], seed);
-                    recvk[0] = wave_from_below_or(rv.ktop[0], kp[i * C]);
+                    recv[0] = wave_shift_down(rv.up[0]);   // nothing enters under the last lane
+                    recvk[0] = wave_from_below_or(rv.ktop[0], kq[i]);
                     rv.step(recv, recvk, Ac, Bc, iB, p6, accP);
-                    // outside the grid the zeros of the guard columns stay; to the left of the grid dF/dp is not
-                    // zero (the adjoint has left the grid there) and must not be kept
-                    if ((unsigned)J < (unsigned)nb) P[__mul24(J, kTileStride) + pbase] = accP[0];
+                    // right of the grid dF/dp is an exact zero (the adjoint is zero there) and lands in the zero
+                    // column; left of the grid it is not zero (the adjoint has left the grid) and lands in the
+                    // column nobody reads
+                    P[__mul24(write_col(J, nb), kTileStride) + pbase] = accP[0];
+                }
+                if (g > 0 && g % CK == 0) {
+                    // the recovered state against the exact one, which replaces it: rounding errors of the inverse
+                    // recurrence cannot build up over more than CK chunks, and a drift raises the error flag
+                    const SK_LDS real* cp = ckl + (g / CK - 1) * (2 * kWave);
+                    const real e1 = cp[0];
+                    const real e0 = wave_from_above_or(cp[kWave], 1.0);   // the lane above's k[a][J]; row 0 has the boundary above it
+                    kscale = fmax(kscale, fmax(fabs(e0), fabs(e1)));
+                    // written so that a NaN counts as drift
+                    if (!(fabs(rv.kR[0] - e0) <= 1e-9 * kscale) || !(fabs(rv.kR[1] - e1) <= 1e-9 * kscale)) drift = true;
+                    rv.kR[0] = e0;
+                    rv.kR[1] = e1;
+                    rv.ktop[0] = e0;
                 }
             }
+        }
+
+        // Loads for the second half of the linear map and for the next pair, issued here so that the first half
+        // of the map covers their latency (during the sweeps the registers are needed elsewhere).
+        const real* dxg = a.dx + xi * a.xstride;
+        real xc[16], xbn[4][KC], gkn = 0.0;
+        if (a.want_gy) TL::load_c(dxg, a.DS, padb, lane, xc);
+        if (q + 1 < q1) {
+            long xin, yin, pidn;
+            tile_pair(a, q + 1, xin, yin, pidn);
+            TL::load_b(a.dx + xin * a.xstride, a.DS, padb, lane, xbn);
+            gkn = a.grad_k[pidn];
         }
 
         // ---- the linear map of Section 3.4 on the matrix cores ----
         if (a.want_gx) {
             // dF/d(dx)[a, c] = sum_b G[a, b] dy[b, c]: A operand G[16 I + l % 16][4 kb + l / 16], B operand yc[kb]
-            real* gq = a.gdx + xi * a.xstride;
+            // (the lane's part of the address goes through an opaque move: computed here, once per pair, from one
+            // register, instead of sixteen loop-invariant addresses kept alive over the whole pair loop)
+            int lrow = g16 - padb;
+            asm volatile("" : "+v"(lrow));
+            real* gq = a.gdx + xi * a.xstride + (long)lrow * a.DS + n16;
 #pragma unroll
             for (int I = 0; I < 4; ++I) {
                 real4 acc = {0.0, 0.0, 0.0, 0.0};
@@ -332,15 +402,13 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                     acc = __builtin_amdgcn_mfma_f64_16x16x4f64(gp[4 * kb * kTileStride], yc[kb], acc, 0, 0, 0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int arow = 16 * I + g16 + 4 * r - padb;
-                    if (arow >= 0 && n16 < a.d) unsafeAtomicAdd(&gq[(long)arow * a.DS + n16], acc[r]);
+                    const int up = 16 * I + 4 * r;   // rows above the lane's first one
+                    if (lrow + up >= 0 && n16 < a.d) unsafeAtomicAdd(&gq[(long)up * a.DS], acc[r]);
                 }
             }
         }
         if (a.want_gy) {
             // dF/d(dy)[b, c] = sum_a G[a, b] dx[a, c]: A operand G[4 ka + l / 16][16 J + l % 16], B operand xc[ka]
-            real xc[16];
-            TL::load_c(dxg, a.DS, padb, lane, xc);
 #pragma unroll
             for (int J = 0; J < 4; ++J) {
                 const SK_LDS real* gp = P + (16 * J + n16 + 1) * kTileStride + g16;
@@ -349,7 +417,11 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                     gy[J] = __builtin_amdgcn_mfma_f64_16x16x4f64(gp[4 * ka], xc[ka], gy[J], 0, 0, 0);
             }
         }
-        scratch_fence();   // the next pair overwrites the checkpoints
+#pragma unroll
+        for (int T = 0; T < 4; ++T)
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) xb[T][kc] = xbn[T][kc];
+        gk = gkn;
     }
     flush_gy();
     if (drift) atomicExch(a.err, 2);
@@ -379,7 +451,9 @@ hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid
     // what the kernels assume about the launch
     if (a.lk_M != 1 || a.rs1 != 0 || a.rs2 != 0 || a.mb > kWave || a.nb > kWave || a.mb < 1 || a.nb < 1 ||
         a.lk_padb != kWave - a.mb || a.rpad < kWave || a.qpad < kWave || a.DS <= DT || a.d > DT ||
-        (backward && ((a.lk_NT % kLockS) != 0 || a.lk_NT < a.nb + kWave - 1)))
+        (backward && ((a.lk_NT % kLockS) != 0 || a.lk_NT < a.nb + kWave - 1 || a.lk_NT >= a.nb + kWave - 1 + kLockS ||
+                      (size_t)a.lk_off_ck + (size_t)((a.lk_NT / kLockS - 1) / kTileCkChunks) * 2 * kWave * sizeof(real) >
+                          a.lds_wave)))
         return hipErrorInvalidValue;
     switch (DT) {
         case 8: return launch_tile_k<2>(backward, a, grid, lds, st);
