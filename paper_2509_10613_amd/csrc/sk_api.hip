@@ -105,6 +105,9 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.coop_ring_stride = (unsigned)p.coop_ring_stride;
     a.solo = p.solo;
     a.tile = p.tile;
+    a.band = p.band; a.bd_nbands = p.bd_nbands;
+    a.bd_off_y = (unsigned)p.bd_off_y; a.bd_off_gy = (unsigned)p.bd_off_gy; a.bd_off_rings = (unsigned)p.bd_off_rings;
+    a.bd_flags = reinterpret_cast<int*>(base + p.off_flags);
     a.lock = p.lock; a.lk_M = p.lk_M; a.lk_ns = p.lk_ns; a.lk_NT = p.lk_NT; a.lk_padb = p.lk_padb;
     a.lk_rowlen = p.lk_rowlen;
     a.lk_off_y = (unsigned)p.lk_off_y; a.lk_off_gy = (unsigned)p.lk_off_gy; a.lk_off_cring = (unsigned)p.lk_off_cring;
@@ -139,7 +142,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, p.L1,
                                p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
                                (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, p.L2, p.qpad, p.d,
-                               p.DP, a.err, st));
+                               p.DP, a.err, 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags, st));
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -152,7 +155,8 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         tl.backward = backward ? 1 : 0;
         SK_CHECK(hipEventRecord(tl.start, st));
     }
-    if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    if (p.band) SK_CHECK(launch_sweep_band(backward ? 1 : 0, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
@@ -329,7 +333,11 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     char kern[96];
     int threads;
     const char* mode;
-    if (p.tile) {
+    if (p.band) {
+        mode = "band";
+        std::snprintf(kern, sizeof(kern), "band_%s_kernel<%d, %d>", backward ? "bwd" : "fwd", p.BL, p.DT);
+        threads = (sk::kBandStrips + 1) * sk::kWave;
+    } else if (p.tile) {
         mode = "tile";
         std::snprintf(kern, sizeof(kern), "tile_%s_kernel<%d>", backward ? "bwd" : "fwd", p.DT / 4);
         threads = sk::kWavesPerWG * sk::kWave;
@@ -352,8 +360,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
                   "workspace_bytes=%zu",
-                  mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile) ? p.lk_ns : p.ns,
-                  (p.lock || p.solo || p.tile) ? p.lk_M : 1,
+                  mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
+                  (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
                   fused ? 1 : 0, p.total);
     return SK_OK;
 }

@@ -57,6 +57,10 @@ struct SweepArgs {
     unsigned lk_off_ck, lk_ck_stride;         // checkpoint staging (backward)
     int solo;            // 1: solo kernels (one wave per pair, a single strip of 64 * lk_M block rows; uses lk_M,
                          // lk_NT, lk_padb and, as offsets inside a wave's LDS, lk_off_gy / lk_off_krows / lk_off_dump)
+    int band;            // 1: band kernels (a pair's strips spread over bd_nbands workgroups; uses lk_ns, lk_NT, lk_padb)
+    int bd_nbands;
+    int* bd_flags;       // [2][npairs][bd_nbands] progress counters (forward, reverse), zero at launch
+    unsigned bd_off_y, bd_off_gy, bd_off_rings;   // LDS bytes
     int tile;            // 1: tile kernels (one wave per pair, increment Gram matrix in LDS, contractions by MFMA; uses
                          // lk_NT, lk_padb, lk_off_krows / lk_off_dump as offsets inside a wave's LDS)
     // lock-step mode on a batch of pairs of double paths: the kernels read the caller's points and write the
@@ -75,7 +79,10 @@ template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* 
 // dx/dy null = that side is not (re)computed (symmetric Gram); gdx/gdy null = no accumulator to clear.
 template <typename T>
 hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
-                          long ny, int L2, int qpad, int d, int DS, int* err, hipStream_t st);
+                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, hipStream_t st);
+// band mode (a.band != 0), defined in sk_band.hip; phase 0: forward sweep, 1: forward sweep of the backward
+// pass (checkpoints), 2: reverse sweep
+hipError_t launch_sweep_band(int phase, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
                            int L2, int qpad, int d, int DS, const int* err, hipStream_t st);

@@ -61,13 +61,15 @@ struct PathSet {
 // (inc[path][a][c] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d: first line of the paper's
 // forward listing), the gradient accumulators cleared, and the error flag cleared.
 template <typename TI>
-__global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, int* err)
+__global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, int* err, int nclear)
 {
     const long nx = px.inc ? px.npaths * (long)px.rows * DS : 0;
     const long ny = py.inc ? py.npaths * (long)py.rows * DS : 0;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const long st = (long)gridDim.x * blockDim.x;
-    if (i == 0 && err) *err = 0;
+    if (err) {   // the error flag and the nclear - 1 ints behind it (progress counters)
+        for (long t = i; t < nclear; t += st) err[t] = 0;
+    }
     for (; i < nx + ny; i += st) {
         const bool second = i >= nx;
         const PathSet<TI>& p = second ? py : px;
@@ -1775,7 +1777,7 @@ hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st)
 
 template <typename T>
 hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
-                          long ny, int L2, int qpad, int d, int DS, int* err, hipStream_t st)
+                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, hipStream_t st)
 {
     PathSet<T> px{x, nullptr, dx, gdx, nx, L1, rpad};
     PathSet<T> py{y, nullptr, dy, gdy, ny, L2, qpad};
@@ -1783,7 +1785,7 @@ hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int 
     if (total <= 0) total = 1;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(prepare_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err);
+    hipLaunchKernelGGL(prepare_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err, nclear);
     return hipGetLastError();
 }
 
@@ -1924,9 +1926,9 @@ template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
 template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);
 template hipError_t launch_convert<double, float>(const double*, float*, long, hipStream_t);
 template hipError_t launch_prepare<float>(const float*, real*, real*, long, int, int, const float*, real*, real*, long,
-                                          int, int, int, int, int*, hipStream_t);
+                                          int, int, int, int, int*, int, hipStream_t);
 template hipError_t launch_prepare<double>(const double*, real*, real*, long, int, int, const double*, real*, real*,
-                                           long, int, int, int, int, int*, hipStream_t);
+                                           long, int, int, int, int, int*, int, hipStream_t);
 template hipError_t launch_finalize<float>(const real*, float*, long, int, int, const real*, float*, long, int, int, int,
                                            int, const int*, hipStream_t);
 template hipError_t launch_finalize<double>(const real*, double*, long, int, int, const real*, double*, long, int, int,

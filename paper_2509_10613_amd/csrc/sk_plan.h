@@ -56,6 +56,9 @@ struct Plan {
     int uncompute = 0;   // backward: reverse sweep recovers forward values by inverting Eq. (1) (no replay ring)
     size_t coop_off_gdy = 0, coop_off_flags = 0, coop_off_obox = 0, coop_off_ring = 0, coop_ring_stride = 0;
     // lock-step mode: one workgroup per pair, per strip one stencil wave and one coefficient wave
+    int band = 0, bd_nbands = 0;   // bands of kBandStrips strips on different compute units (sk_band.hip)
+    size_t bd_off_y = 0, bd_off_gy = 0, bd_off_rings = 0, off_flags = 0;
+    int nflags = 0;
     int tile = 0;   // one wave per pair, at most 64 x 64 cells, contractions on the matrix cores (sk_tile.hip)
     int solo = 0;   // one wave per pair, a single strip of 64 * lk_M block rows (many pairs of short paths)
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
@@ -94,6 +97,10 @@ constexpr int solo_max_rows(bool backward, int BL, int DT)
 // two-way bank conflicted), kTileCols columns (-1 .. 64: a zero guard column on either side).
 constexpr int kTileStride = 66, kTileCols = 66;
 constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
+
+// Band mode: strips per workgroup, block columns per hand-over ring, coarse y columns per y ring (powers of
+// two), chunks the data-moving wave works ahead, and the bound on its polls of another workgroup's counter.
+constexpr int kBandStrips = 4, kBandRing = 64, kBandYRing = 512, kBandLead = 2, kBandSpin = 1 << 22;
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
@@ -310,6 +317,31 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.nseg = NT / kLockS;
     }
 
+    // Band mode: few pairs of long paths.  The strips of a pair are spread over workgroups (bands of kBandStrips
+    // strips) that all run at once; chosen when that fills more of the chip than one workgroup per pair does.
+    if (!p.lock && !p.tile && !p.solo && !backward && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips) {
+        const int nbands = (p.ns + kBandStrips - 1) / kBandStrips;
+        if (p.npairs * nbands <= kNumCU) {
+            const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
+            size_t used = 0;
+            auto lds_take = [&](size_t bytes) { size_t o = used; used = align_up(used + bytes, 256); return o; };
+            const size_t ybytes = (size_t)kBandYRing * p.DP * elem;
+            p.bd_off_y = lds_take(ybytes);
+            p.bd_off_gy = backward ? lds_take(ybytes) : 0;
+            p.bd_off_rings = lds_take((size_t)(kBandStrips + 1) * kBandRing * C * elem * (backward ? 2 : 1));
+            p.band = 1; p.coop = 0; p.bd_nbands = nbands;
+            p.lk_M = 1; p.lk_ns = p.ns; p.lk_NT = NT; p.lk_padb = p.ns * kWave - p.mb;
+            p.y_lds = 1;
+            p.lds_wave = 0;
+            p.lds_bytes = used;
+            p.grid = (int)(p.npairs * nbands);
+            p.nslots = p.npairs;
+            p.S = kLockS;
+            p.nseg = NT / kLockS;
+            p.nflags = (int)(2 * p.npairs * nbands);
+        }
+    }
+
     // Workspace layout (all offsets 256-byte aligned).
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -323,7 +355,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.adj_slot = 4 * (int64_t)p.rowlen;   // two rows of 2C values per block column
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
         // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
-        const bool lean = p.lock || p.solo || p.tile;
+        const bool lean = p.lock || p.solo || p.tile || p.band;
         const int NVC = lean ? p.lk_M * R + C + 2 : R + C + 2;
         p.ckpt_slot = p.tile ? 0 : (int64_t)(lean ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
@@ -333,6 +365,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         if (backward) p.off_gkio = take((size_t)p.npairs * elem);
     }
     p.off_err = take(256);
+    p.off_flags = take((size_t)p.nflags * sizeof(int) + 4);   // directly behind the error flag: cleared with it
     p.total = off;
     p.valid = true;
     return p;
