@@ -335,7 +335,11 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     const char* mode;
     if (p.band) {
         mode = "band";
-        std::snprintf(kern, sizeof(kern), "band_%s_kernel<%d, %d>", backward ? "bwd" : "fwd", p.BL, p.DT);
+        // backward: two launches, the forward sweep with checkpoints and then the reverse sweep (the larger one)
+        if (backward)
+            std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true>+band_rev_kernel<%d, %d>", p.BL, p.DT, p.BL, p.DT);
+        else
+            std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, false>", p.BL, p.DT);
         threads = (sk::kBandStrips + 1) * sk::kWave;
     } else if (p.tile) {
         mode = "tile";

@@ -100,7 +100,7 @@ constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between 
 
 // Band mode: strips per workgroup, block columns per hand-over ring, coarse y columns per y ring (powers of
 // two), chunks the data-moving wave works ahead, and the bound on its polls of another workgroup's counter.
-constexpr int kBandStrips = 4, kBandRing = 64, kBandYRing = 512, kBandLead = 2, kBandSpin = 1 << 22;
+constexpr int kBandStrips = 4, kBandRing = 64, kBandYRing = 512, kBandLead = 2, kBandSpin = 1 << 22, kBandSlack = 8, kBandLeadRev = 3;
 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
@@ -129,7 +129,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     p.mb = p.r << p.rs1; p.nb = p.q << p.rs2;
     p.ns = (p.mb + kWave - 1) / kWave;
     const int C = 1 << p.BL, R = C;
-    p.rowlen = (int)align_up((size_t)p.nb * C + 1, 64);
+    p.rowlen = (int)align_up((size_t)(p.nb + 8) * C + 1, 64);   // a few block columns beyond the grid (band mode)
     p.rpad = (int)align_up((size_t)p.r, 64);
     p.qpad = (int)align_up((size_t)p.q, 64);
     p.DT = 0;
@@ -319,7 +319,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
 
     // Band mode: few pairs of long paths.  The strips of a pair are spread over workgroups (bands of kBandStrips
     // strips) that all run at once; chosen when that fills more of the chip than one workgroup per pair does.
-    if (!p.lock && !p.tile && !p.solo && !backward && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips) {
+    if (!p.lock && !p.tile && !p.solo && (!backward || p.uncompute) && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips) {
         const int nbands = (p.ns + kBandStrips - 1) / kBandStrips;
         if (p.npairs * nbands <= kNumCU) {
             const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
@@ -328,7 +328,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
             const size_t ybytes = (size_t)kBandYRing * p.DP * elem;
             p.bd_off_y = lds_take(ybytes);
             p.bd_off_gy = backward ? lds_take(ybytes) : 0;
-            p.bd_off_rings = lds_take((size_t)(kBandStrips + 1) * kBandRing * C * elem * (backward ? 2 : 1));
+            // forward: hand-over rings; backward: adjoint rings, forward-value rings, checkpoint staging
+            p.bd_off_rings = lds_take(((size_t)(kBandStrips + 1) * kBandRing * C +
+                                       (backward ? (size_t)kBandStrips * kBandRing * C +
+                                                       (size_t)kBandStrips * 2 * (R + 1 + C) * kWave : 0)) * elem);
             p.band = 1; p.coop = 0; p.bd_nbands = nbands;
             p.lk_M = 1; p.lk_ns = p.ns; p.lk_NT = NT; p.lk_padb = p.ns * kWave - p.mb;
             p.y_lds = 1;
@@ -352,7 +355,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     if (backward) {
         p.off_gdxT = take((size_t)nx * p.xstride * elem);
         p.off_gdyT = symmetric ? p.off_gdxT : take((size_t)ny * p.ystride * elem);
-        p.adj_slot = 4 * (int64_t)p.rowlen;   // two rows of 2C values per block column
+        p.adj_slot = (p.band && p.bd_nbands > 4 ? p.bd_nbands : 4) * (int64_t)p.rowlen;   // two rows of 2C values per block column; band mode: one row per band
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
         // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
         const bool lean = p.lock || p.solo || p.tile || p.band;

@@ -108,9 +108,18 @@ def test_launch_plan_of_the_five_configurations(lib):
     # more than 16 channels: runtime channel loop, y increments in global memory
     p = _plan(binding.SK_OP_FWD, 4096, 0, 40, 40, 20, 1, 1, 0, f64)
     assert p["mode"] == "wave-per-pair" and p["kernel"] == "sweep_fwd_kernel<1, 0, false>"
-    # c4 (32 pairs, 2047 block rows each): too long for whole hand-over rows in LDS -> cooperative mode with rings
+    # c4 (32 pairs, 2047 block rows = 32 strips each): bands of four strips on different compute units, eight
+    # bands per pair, all 256 workgroups resident at once; four strip waves and a data-moving wave each
     p = _plan(binding.SK_OP_BWD, 32, 0, 2048, 2048, 8, 2, 2, 0, f64)
-    assert p["mode"] == "cooperative" and p["grid"] == "32"
+    assert p["mode"] == "band" and p["kernel"] == "band_fwd_kernel<2, 8, true>+band_rev_kernel<2, 8>" and p["grid"] == "256"
+    assert p["threads"] == "320" and p["strips"] == "32" and int(p["lds_bytes"]) <= 160 * 1024
+    p = _plan(binding.SK_OP_FWD, 32, 0, 2048, 2048, 8, 2, 2, 0, f64)
+    assert p["mode"] == "band" and p["kernel"] == "band_fwd_kernel<2, 8, false>" and p["grid"] == "256"
+    # more long pairs than the chip has room for bands: one workgroup per pair, its strips in rounds
+    p = _plan(binding.SK_OP_BWD, 64, 0, 2048, 2048, 8, 2, 2, 0, f64)
+    assert p["mode"] == "cooperative" and p["grid"] == "64"
+    # 16 channels have no band kernel
+    assert _plan(binding.SK_OP_FWD, 8, 0, 2048, 2048, 16, 2, 2, 0, f64)["mode"] == "cooperative"
     # the replay variant of the backward pass never runs in lock step
     p = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | binding.SK_FLAG_BWD_REPLAY, f64)
     assert p["mode"] == "cooperative" and p["kernel"].startswith("sweep_bwd_coop_kernel")
