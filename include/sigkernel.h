@@ -44,7 +44,11 @@ typedef enum { SK_F32 = 0, SK_F64 = 1 } sk_dtype;
 
 enum {
     SK_FLAG_TIME_AUG = 1,   /* append the channel t_i = i/(L-1) to both paths on the fly (Section 4) */
-    SK_FLAG_BWD_REPLAY = 2  /* backward: replay forward segments instead of inverting Eq. (1); see sigkernel_bwd */
+    SK_FLAG_BWD_REPLAY = 2, /* backward: replay forward segments instead of inverting Eq. (1); see sigkernel_bwd */
+    SK_FLAG_SHORT_WAITS = 4 /* diagnostic: a workgroup that waits for another one's progress gives up after a single
+                               poll.  Exercises the path a wait that runs out takes: every kernel still ends normally
+                               and the results of the call are NaN.  Only launches whose workgroups wait for each
+                               other are affected (a few pairs of very long paths). */
 };
 
 enum {

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(HERE, "libsigkernel.so")
 SK_F32, SK_F64 = 0, 1
 SK_FLAG_TIME_AUG = 1
 SK_FLAG_BWD_REPLAY = 2
+SK_FLAG_SHORT_WAITS = 4
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",

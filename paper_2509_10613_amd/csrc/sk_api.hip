@@ -35,7 +35,7 @@ std::vector<TimedLaunch> g_timed;
 int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
 {
     if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
-    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
+    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY | SK_FLAG_SHORT_WAITS)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
     if (lam1 < 0 || lam2 < 0 || lam1 > 20 || lam2 > 20)
         return fail(SK_ERR_DYADIC, "dyadic orders (%d, %d) outside 0..20", lam1, lam2);
     if (nx < 0 || ny < 0) return fail(SK_ERR_SHAPE, "negative batch size");
@@ -108,6 +108,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.band = p.band; a.bd_nbands = p.bd_nbands;
     a.bd_off_y = (unsigned)p.bd_off_y; a.bd_off_gy = (unsigned)p.bd_off_gy; a.bd_off_rings = (unsigned)p.bd_off_rings;
     a.bd_flags = reinterpret_cast<int*>(base + p.off_flags);
+    a.bd_spin = (flags & SK_FLAG_SHORT_WAITS) ? 1 : kBandSpin;
     a.lock = p.lock; a.lk_M = p.lk_M; a.lk_ns = p.lk_ns; a.lk_NT = p.lk_NT; a.lk_padb = p.lk_padb;
     a.lk_rowlen = p.lk_rowlen;
     a.lk_off_y = (unsigned)p.lk_off_y; a.lk_off_gy = (unsigned)p.lk_off_gy; a.lk_off_cring = (unsigned)p.lk_off_cring;

@@ -59,10 +59,10 @@ __device__ __forceinline__ void st_agent_int(int* p, int v)
 __device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Polls *ctr until it is at least `want` (bounded).  Returns the last value read (below `want`: the wait ran out).
-__device__ __forceinline__ int wait_progress(const int* ctr, int want)
+__device__ __forceinline__ int wait_progress(const int* ctr, int want, int limit)
 {
     int v = ld_agent_int(ctr);
-    for (int spin = 0; v < want && spin < kBandSpin; ++spin) {
+    for (int spin = 1; v < want && spin < limit; ++spin) {
         __builtin_amdgcn_s_sleep(4);
         v = ld_agent_int(ctr);
     }
@@ -133,6 +133,7 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(
         typename LK::Fwd f;
         cf.setup(a, active ? sg : 0, lane, a.dx + xi * a.xstride, yring);
         f.init();
+        real kfin = 0.0;   // k[m, n], in the last lane of the pair's last strip
         const SK_LDS real* rin = rings + w * (kBandRing * C);
         SK_LDS real* rout = rings + (w + 1) * (kBandRing * C);
         real* ckpt = CKPT ? a.ckpt + pid * a.ckpt_slot + (long)sg * (nck + 1) * NVC * kWave + lane : nullptr;
@@ -171,7 +172,7 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(
                     if (!EDGE || Jw >= 0) {
 #pragma unroll
                         for (int cc = 0; cc < C; ++cc) rout[(Jw & RM) * C + cc] = f.bot[cc];
-                        if (EDGE && laststrip && Jw == nb - 1 && a.k_out) a.k_out[pid] = f.bot[C - 1];
+                        if (EDGE && Jw == nb - 1) kfin = f.bot[C - 1];
                     }
                 }
             }
@@ -187,6 +188,10 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(
             }
             band_barrier();
         }
+        // A wait that ran out in this band or in one above it (their counters were read after their flag was set)
+        // leaves rows that were never written behind: the value is not to be trusted.
+        if (laststrip && active && lane == kWave - 1 && a.k_out)
+            a.k_out[pid] = ld_agent_int(a.err) != 0 ? __builtin_nan("") : kfin;
     } else {
         // ---------------- the data-moving wave ----------------
         const real* dyg = a.dy + yi * a.ystride;
@@ -245,7 +250,7 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(
                         // not in every iteration (a read is a round trip to the memory side)
                         int want = need + kBandSlack;
                         if (want > nck) want = nck;
-                        seen = wait_progress(progprev, want);
+                        seen = wait_progress(progprev, want, a.bd_spin);
                         if (seen < need) {
                             dead = true;
                             if (lane == 0) atomicExch(a.err, 1);
@@ -566,7 +571,7 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(
                     if (seen < need && !dead) {
                         int want = need + kBandSlack;
                         if (want > nck) want = nck;
-                        seen = wait_progress(progprev, want);
+                        seen = wait_progress(progprev, want, a.bd_spin);
                         if (seen < need) {
                             dead = true;
                             if (lane == 0) atomicExch(a.err, 1);

@@ -59,6 +59,7 @@ struct SweepArgs {
                          // lk_NT, lk_padb and, as offsets inside a wave's LDS, lk_off_gy / lk_off_krows / lk_off_dump)
     int band;            // 1: band kernels (a pair's strips spread over bd_nbands workgroups; uses lk_ns, lk_NT, lk_padb)
     int bd_nbands;
+    int bd_spin;         // polls of another workgroup's counter before a wait gives up
     int* bd_flags;       // [2][npairs][bd_nbands] progress counters (forward, reverse), zero at launch
     unsigned bd_off_y, bd_off_gy, bd_off_rings;   // LDS bytes
     int tile;            // 1: tile kernels (one wave per pair, increment Gram matrix in LDS, contractions by MFMA; uses

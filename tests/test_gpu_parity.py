@@ -214,6 +214,53 @@ def test_short_paths_with_many_channels_stay_solo():
     check_grads(host(gY), gYr, torch.float64, "grad_Y")
 
 
+@pytest.mark.parametrize("B,L1,L2,d,lam1,lam2,flags", [(4, 600, 600, 8, 2, 2, 0), (8, 700, 500, 5, 1, 1, 1),
+                                                        (5, 400, 330, 3, 0, 0, 0), (2, 300, 900, 2, 2, 1, 0),
+                                                        (6, 1000, 1000, 6, 0, 2, 1), (3, 321, 450, 4, 1, 0, 0)])
+def test_band_mode_shapes(B, L1, L2, d, lam1, lam2, flags):
+    # band kernels (few pairs of long paths: the strips of a pair spread over workgroups that run as one pipeline,
+    # rows and progress counters crossing workgroups): two to four bands, a last band with fewer than four
+    # strips, unequal lengths and dyadic orders (block columns shared by several refined columns), time
+    # augmentation; forward alone and the two launches of the backward pass, twice in a row (the counters are
+    # cleared by every call)
+    rng = np.random.default_rng(800 + L1 + d)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L1) ** 0.5, (B, L1, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L2) ** 0.5, (B, L2, d)), axis=1)
+    assert "mode=band" in sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, sk.SK_F64)
+    gk = workloads.upstream_weights(62, (B,))
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, lam1, lam2, flags)
+    for rep in range(2):
+        kf = sk.sigkernel_fwd(dev(X), dev(Y), lam1, lam2, flags)
+        k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), lam1, lam2, flags)
+        torch.cuda.synchronize()
+        check_values(host(kf), kr, torch.float64, "k (forward only)")
+        check_values(host(k), kr, torch.float64, "k")
+        check_grads(host(gx), gxr, torch.float64, "grad_x")
+        check_grads(host(gy), gyr, torch.float64, "grad_y")
+
+
+def test_band_mode_wait_that_runs_out_gives_nan_and_ends():
+    # SK_FLAG_SHORT_WAITS lets a band give up on the band above it after one poll: the kernels must still end, the
+    # results must be NaN (never a number computed from rows that were not there), and the next call is clean
+    B, L, d = 3, 600, 3
+    rng = np.random.default_rng(91)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (B, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (B, L, d)), axis=1)
+    assert "mode=band" in sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L, L, d, 1, 1, sk.SK_FLAG_SHORT_WAITS, sk.SK_F64)
+    gk = workloads.upstream_weights(63, (B,))
+    kf = sk.sigkernel_fwd(dev(X), dev(Y), 1, 1, sk.SK_FLAG_SHORT_WAITS)
+    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, sk.SK_FLAG_SHORT_WAITS)
+    torch.cuda.synchronize()
+    assert np.all(np.isnan(host(kf))) and np.all(np.isnan(host(k)))
+    assert np.all(np.isnan(host(gx))) and np.all(np.isnan(host(gy)))
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, 1, 1, 0)
+    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0)
+    torch.cuda.synchronize()
+    check_values(host(k), kr, torch.float64, "k after a failed call")
+    check_grads(host(gx), gxr, torch.float64, "grad_x after a failed call")
+    check_grads(host(gy), gyr, torch.float64, "grad_y after a failed call")
+
+
 # ------------------------------------------------------------------ full-size runs on sampled outputs
 def test_c3_full_size_sampled_entries():
     w, X, Y = workloads.make("c3")
