@@ -28,7 +28,12 @@
  *  - Empty batches (B = 0, N*M = 0) are a successful no-op.  A path with a single point (L = 1) has no
  *    increments: k = 1 and all gradients are 0.
  *  - flags: SK_FLAG_TIME_AUG appends the channel t_i = i/(L-1) to both paths on the fly (Section 4);
- *    gradients are returned for the original d channels only.
+ *    gradients are returned for the original d channels only.  SK_FLAG_LEAD_LAG applies the lead-lag transform
+ *    of Section 4 to both paths on the fly: a path of L points in R^d is treated as the path of 2L - 1 points in
+ *    R^2d with lead_i = x[k] for i in {2k - 1, 2k} and lag_i = x[k] for i in {2k, 2k + 1} (lead channels first);
+ *    the transformed paths are never formed, their increments are written by the preparation kernel, and the
+ *    gradients come back with respect to the original points.  With both flags the time channel is that of
+ *    the transformed path, t_i = i/(2L - 2).  Dyadic orders then refine the 2 (L - 1) steps of the transformed path.
  */
 #ifndef SIGKERNEL_H
 #define SIGKERNEL_H
@@ -45,6 +50,7 @@ typedef enum { SK_F32 = 0, SK_F64 = 1 } sk_dtype;
 enum {
     SK_FLAG_TIME_AUG = 1,   /* append the channel t_i = i/(L-1) to both paths on the fly (Section 4) */
     SK_FLAG_BWD_REPLAY = 2, /* backward: replay forward segments instead of inverting Eq. (1); see sigkernel_bwd */
+    SK_FLAG_LEAD_LAG = 8,   /* lead-lag transform of both paths on the fly (Section 4) */
     SK_FLAG_SHORT_WAITS = 4 /* diagnostic: a workgroup that waits for another one's progress gives up after a single
                                poll.  Exercises the path a wait that runs out takes: every kernel still ends normally
                                and the results of the call are NaN.  Only launches whose workgroups wait for each

@@ -15,6 +15,7 @@ import numpy as np
 from .build import LIB, build
 
 FLAG_TIME_AUG = 1
+FLAG_LEAD_LAG = 8   # same bit as SK_FLAG_LEAD_LAG of the library
 
 _lib = None
 
@@ -91,8 +92,37 @@ def pair_debug(x, y, lam1=0, lam2=0, flags=0, dtype=np.float64, want_G=True):
     return k, Delta, grid, G
 
 
+def lead_lag(x):
+    """The lead-lag transform of Section 4, written out point by point: a path of L points in R^d becomes the path of
+    2L - 1 points in R^2d with  lead_i = x[k] for i in {2k - 1, 2k},  lag_i = x[k] for i in {2k, 2k + 1};
+    the lead channels come first.  Works on [..., L, d] arrays."""
+    x = np.asarray(x)
+    L, d = x.shape[-2], x.shape[-1]
+    out = np.empty(x.shape[:-2] + (2 * L - 1, 2 * d), dtype=x.dtype)
+    for i in range(2 * L - 1):
+        k_lead = (i + 1) // 2      # i = 2k or i = 2k - 1
+        k_lag = i // 2             # i = 2k or i = 2k + 1
+        out[..., i, :d] = x[..., k_lead, :]
+        out[..., i, d:] = x[..., k_lag, :]
+    return out
+
+
+def lead_lag_pullback(g):
+    """Chain rule through lead_lag: the gradient of a point collects the gradients of every transformed point and
+    half that is a copy of it.  g[..., 2L - 1, 2d] -> [..., L, d]."""
+    g = np.asarray(g)
+    L, d = (g.shape[-2] + 1) // 2, g.shape[-1] // 2
+    out = np.zeros(g.shape[:-2] + (L, d), dtype=g.dtype)
+    for i in range(2 * L - 1):
+        out[..., (i + 1) // 2, :] += g[..., i, :d]
+        out[..., i // 2, :] += g[..., i, d:]
+    return out
+
+
 def fwd(x, y, lam1=0, lam2=0, flags=0, dtype=np.float64):
     """x[B,L1,d], y[B,L2,d] -> k[B]."""
+    if flags & FLAG_LEAD_LAG:   # transform first, then the (optional) time augmentation of the transformed paths
+        return fwd(lead_lag(_arr(x, dtype)), lead_lag(_arr(y, dtype)), lam1, lam2, flags & ~FLAG_LEAD_LAG, dtype)
     x = _arr(x, dtype)
     y = _arr(y, dtype)
     B, L1, d = x.shape
@@ -106,6 +136,10 @@ def fwd(x, y, lam1=0, lam2=0, flags=0, dtype=np.float64):
 
 def bwd(x, y, grad_k, lam1=0, lam2=0, flags=0, dtype=np.float64):
     """Returns (k[B], grad_x[B,L1,d], grad_y[B,L2,d]) for upstream gradients grad_k[B]."""
+    if flags & FLAG_LEAD_LAG:
+        k, gx, gy = bwd(lead_lag(_arr(x, dtype)), lead_lag(_arr(y, dtype)), grad_k, lam1, lam2,
+                        flags & ~FLAG_LEAD_LAG, dtype)
+        return k, lead_lag_pullback(gx), lead_lag_pullback(gy)
     x = _arr(x, dtype)
     y = _arr(y, dtype)
     gk = _arr(grad_k, dtype)
@@ -125,6 +159,13 @@ def gram(X, Y, grad_K=None, lam1=0, lam2=0, flags=0, dtype=np.float64):
     """K[N,M] = k(X[n], Y[m]).  With grad_K[N,M] also returns (grad_X, grad_Y); passing the same array
     object for X and Y selects the symmetric case, where grad_X is the total derivative and grad_Y is None."""
     sym = Y is X
+    if flags & FLAG_LEAD_LAG:
+        Xl = lead_lag(_arr(X, dtype))
+        Yl = Xl if sym else lead_lag(_arr(Y, dtype))
+        r = gram(Xl, Yl, grad_K, lam1, lam2, flags & ~FLAG_LEAD_LAG, dtype)
+        if grad_K is None:
+            return r
+        return r[0], lead_lag_pullback(r[1]), (None if sym else lead_lag_pullback(r[2]))
     X = _arr(X, dtype)
     Y = X if sym else _arr(Y, dtype)
     N, L1, d = X.shape

@@ -1,0 +1,80 @@
+"""PyTorch autograd over the C ABI (the paper's library is "fully compatible with PyTorch's automatic
+differentiation", Section 1): thin ``torch.autograd.Function`` wrappers whose forward is ``sigkernel_fwd`` /
+``sigkernel_gram`` and whose backward is ``sigkernel_bwd`` / ``sigkernel_gram`` with the upstream gradient
+(Section 3.4: exact gradients of the discrete scheme).  Argument marshalling only; no arithmetic of the
+method happens here.
+
+    k = sig_kernel(x, y, lam1, lam2, flags)          # x[B,L1,d], y[B,L2,d] -> k[B]
+    K = sig_kernel_gram(X, Y, lam1, lam2, flags)     # X[N,L1,d], Y[M,L2,d] -> K[N,M]
+    K = sig_kernel_gram(X, None, lam1, lam2, flags)  # symmetric case K(X, X)
+
+The gradients are first-order only (the backward pass is not itself differentiable).
+"""
+import torch
+
+from . import binding as sk
+
+
+class _PairKernel(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, y, lam1, lam2, flags):
+        x = x.contiguous()
+        y = y.contiguous()
+        ctx.save_for_backward(x, y)
+        ctx.args = (lam1, lam2, flags)
+        return sk.sigkernel_fwd(x, y, lam1, lam2, flags)
+
+    @staticmethod
+    def backward(ctx, grad_k):
+        x, y = ctx.saved_tensors
+        lam1, lam2, flags = ctx.args
+        want_x, want_y = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        if not (want_x or want_y):
+            return None, None, None, None, None
+        _, gx, gy = sk.sigkernel_bwd(x, y, grad_k.contiguous(), lam1, lam2, flags, want_x=want_x, want_y=want_y)
+        return gx, gy, None, None, None
+
+
+class _GramKernel(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, X, Y, lam1, lam2, flags):
+        X = X.contiguous()
+        Y = Y.contiguous()
+        ctx.save_for_backward(X, Y)
+        ctx.args = (lam1, lam2, flags)
+        return sk.sigkernel_gram(X, Y, None, lam1, lam2, flags)
+
+    @staticmethod
+    def backward(ctx, grad_K):
+        X, Y = ctx.saved_tensors
+        lam1, lam2, flags = ctx.args
+        _, gX, gY = sk.sigkernel_gram(X, Y, grad_K.contiguous(), lam1, lam2, flags)
+        return (gX if ctx.needs_input_grad[0] else None), (gY if ctx.needs_input_grad[1] else None), None, None, None
+
+
+class _GramKernelSym(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, X, lam1, lam2, flags):
+        X = X.contiguous()
+        ctx.save_for_backward(X)
+        ctx.args = (lam1, lam2, flags)
+        return sk.sigkernel_gram(X, X, None, lam1, lam2, flags)
+
+    @staticmethod
+    def backward(ctx, grad_K):
+        (X,) = ctx.saved_tensors
+        lam1, lam2, flags = ctx.args
+        _, gX, _ = sk.sigkernel_gram(X, X, grad_K.contiguous(), lam1, lam2, flags)   # total derivative, both slots
+        return gX, None, None, None
+
+
+def sig_kernel(x, y, lam1=0, lam2=0, flags=0):
+    """k[b] = k(x[b], y[b]) for device tensors x[B,L1,d], y[B,L2,d]; differentiable in x and y."""
+    return _PairKernel.apply(x, y, lam1, lam2, flags)
+
+
+def sig_kernel_gram(X, Y=None, lam1=0, lam2=0, flags=0):
+    """K[n,m] = k(X[n], Y[m]); Y = None is the symmetric case K(X, X); differentiable in X and Y."""
+    if Y is None:
+        return _GramKernelSym.apply(X, lam1, lam2, flags)
+    return _GramKernel.apply(X, Y, lam1, lam2, flags)

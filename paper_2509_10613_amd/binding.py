@@ -15,6 +15,7 @@ SK_F32, SK_F64 = 0, 1
 SK_FLAG_TIME_AUG = 1
 SK_FLAG_BWD_REPLAY = 2
 SK_FLAG_SHORT_WAITS = 4
+SK_FLAG_LEAD_LAG = 8
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",

@@ -35,7 +35,7 @@ std::vector<TimedLaunch> g_timed;
 int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
 {
     if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
-    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY | SK_FLAG_SHORT_WAITS)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
+    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY | SK_FLAG_SHORT_WAITS | SK_FLAG_LEAD_LAG)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
     if (lam1 < 0 || lam2 < 0 || lam1 > 20 || lam2 > 20)
         return fail(SK_ERR_DYADIC, "dyadic orders (%d, %d) outside 0..20", lam1, lam2);
     if (nx < 0 || ny < 0) return fail(SK_ERR_SHAPE, "negative batch size");
@@ -45,6 +45,9 @@ int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1
     if (L1 > lim || L2 > lim || ((L1 - 1) << lam1) >= lim || ((L2 - 1) << lam2) >= lim)
         return fail(SK_ERR_SHAPE, "refined grid side (L-1) << lambda must stay below 2^29");
     if (d > 65536) return fail(SK_ERR_SHAPE, "d above 65536");
+    if ((flags & SK_FLAG_LEAD_LAG) && (2 * L1 - 1 > lim || 2 * L2 - 1 > lim || ((2 * L1 - 2) << lam1) >= lim ||
+                                       ((2 * L2 - 2) << lam2) >= lim || 2 * d > 65536))
+        return fail(SK_ERR_SHAPE, "lead-lag transform: refined grid side 2 (L-1) << lambda must stay below 2^29, 2 d below 65536");
     if (nx > ((int64_t)1 << 40) || ny > ((int64_t)1 << 40)) return fail(SK_ERR_SHAPE, "batch too large");
     return SK_OK;
 }
@@ -129,7 +132,11 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     }
     a.err = reinterpret_cast<int*>(base + p.off_err);
     // Lock-step mode on a batch of pairs of double paths works on the caller's arrays directly.
-    const bool fused = p.lock && p.gramM == 0 && kIsDouble;
+    // Lead-lag transform (Section 4): the plan was made for the transformed paths (2L - 1 points, 2d channels);
+    // only the preparation and the finalisation know the caller's shape.
+    const int ll = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
+    const int cL1 = ll ? (p.L1 + 1) / 2 : p.L1, cL2 = ll ? (p.L2 + 1) / 2 : p.L2, cd = ll ? p.d / 2 : p.d;
+    const bool fused = p.lock && p.gramM == 0 && kIsDouble && !ll;
     if (fused) {
         a.fused = 1;
         a.xraw = static_cast<const double*>(x);
@@ -140,10 +147,10 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     }
     // one preparation launch: increments of both sides, cleared gradient accumulators, cleared error flag
     if (!fused)
-    SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, p.L1,
+    SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, cL1,
                                p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
-                               (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, p.L2, p.qpad, p.d,
-                               p.DP, a.err, 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags, st));
+                               (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, cL2, p.qpad, cd,
+                               p.DP, a.err, 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags, ll, st));
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -168,9 +175,9 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     }
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
     if (backward && !fused) {
-        SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.rpad, a.gdy,
-                                    p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, p.L2, p.qpad, p.d, p.DP,
-                                    a.err, st));
+        SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, cL1, p.rpad, a.gdy,
+                                    p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, cL2, p.qpad, cd, p.DP,
+                                    a.err, ll, st));
     }
 #undef SK_CHECK
     return SK_OK;
@@ -228,6 +235,7 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     }
     rc = check_device();
     if (rc != SK_OK) return rc;
+    if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }   // shape of the transformed paths
     sk::Plan p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
                                !(flags & SK_FLAG_BWD_REPLAY));
     if (!p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
@@ -252,6 +260,7 @@ size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, 
     if (op < SK_OP_FWD || op > SK_OP_GRAM_BWD) return 0;
     const int64_t ny = gram ? M : B_or_N;
     if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
+    if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
     // The symmetric Gram case needs no more than the general one, so the query does not distinguish them.
     sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
                                !(flags & SK_FLAG_BWD_REPLAY));
@@ -325,6 +334,7 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     const int64_t ny = gram ? M : B_or_N;
     int rc = validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt);
     if (rc != SK_OK) return rc;
+    if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
     sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
                                !(flags & SK_FLAG_BWD_REPLAY));
     if (!p.valid) {
@@ -361,7 +371,7 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
                       (p.y_lds && p.DT) ? "true" : "false");
         threads = (p.coop ? p.nw : sk::kWavesPerWG) * sk::kWave;
     }
-    const bool fused = p.lock && !gram && dt == SK_F64;
+    const bool fused = p.lock && !gram && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG);
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
                   "workspace_bytes=%zu",

@@ -80,13 +80,13 @@ template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* 
 // dx/dy null = that side is not (re)computed (symmetric Gram); gdx/gdy null = no accumulator to clear.
 template <typename T>
 hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
-                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, hipStream_t st);
+                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, int ll, hipStream_t st);
 // band mode (a.band != 0), defined in sk_band.hip; phase 0: forward sweep, 1: forward sweep of the backward
 // pass (checkpoints), 2: reverse sweep
 hipError_t launch_sweep_band(int phase, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
-                           int L2, int qpad, int d, int DS, const int* err, hipStream_t st);
+                           int L2, int qpad, int d, int DS, const int* err, int ll, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // solo mode (a.solo != 0), defined in sk_solo.hip
 hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);

@@ -261,6 +261,88 @@ def test_band_mode_wait_that_runs_out_gives_nan_and_ends():
     check_grads(host(gy), gyr, torch.float64, "grad_y after a failed call")
 
 
+# ------------------------------------------------------------------ lead-lag transform on the fly (Section 4)
+LL = sk.SK_FLAG_LEAD_LAG
+
+
+@pytest.mark.parametrize("B,L1,L2,d,lam1,lam2,flags,dtype", [
+    (6, 40, 33, 2, 1, 1, LL, torch.float64),            # few pairs: lock-step (not fused: the kernels see increments)
+    (5, 20, 20, 3, 0, 2, LL | 1, torch.float64),        # with time augmentation of the transformed path
+    (1300, 30, 25, 4, 0, 0, LL, torch.float64),         # many pairs, 8 channels after the transform: tile kernels
+    (1300, 24, 31, 2, 1, 1, LL, torch.float32),         # many pairs, float callers: solo kernels
+    (3, 260, 200, 3, 0, 0, LL, torch.float64),          # long paths: band kernels
+])
+def test_lead_lag_pairs(B, L1, L2, d, lam1, lam2, flags, dtype):
+    rng = np.random.default_rng(900 + L1 + d)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L1) ** 0.5, (B, L1, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L2) ** 0.5, (B, L2, d)), axis=1)
+    print(sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, sk.SK_F64), flush=True)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    gk = workloads.upstream_weights(64, (B,))
+    kf = sk.sigkernel_fwd(dev(X, dtype), dev(Y, dtype), lam1, lam2, flags)
+    k, gx, gy = sk.sigkernel_bwd(dev(X, dtype), dev(Y, dtype), dev(gk, dtype), lam1, lam2, flags)
+    torch.cuda.synchronize()
+    kr, gxr, gyr = oracle.bwd(Xr, Yr, rounded(gk, dtype), lam1, lam2, flags)
+    check_values(host(kf), kr, dtype, "k (forward only)")
+    check_values(host(k), kr, dtype, "k")
+    check_grads(host(gx), gxr, dtype, "grad_x")
+    check_grads(host(gy), gyr, dtype, "grad_y")
+
+
+def test_lead_lag_gram():
+    nx, ny, L, d = 21, 17, 36, 3
+    rng = np.random.default_rng(95)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (nx, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (ny, L, d)), axis=1)
+    W = workloads.upstream_weights(65, (nx, ny))
+    K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), 1, 1, LL)
+    x = dev(X)
+    Ws = workloads.upstream_weights(66, (nx, nx))
+    Kxx, gXX, none = sk.sigkernel_gram(x, x, dev(Ws), 1, 1, LL)
+    torch.cuda.synchronize()
+    Kr, gXr, gYr = oracle.gram(X, Y, W, 1, 1, LL)
+    check_values(host(K), Kr, torch.float64, "K")
+    check_grads(host(gX), gXr, torch.float64, "grad_X")
+    check_grads(host(gY), gYr, torch.float64, "grad_Y")
+    Kxr, gXXr, _ = oracle.gram(X, X, Ws, 1, 1, LL)
+    assert none is None
+    check_values(host(Kxx), Kxr, torch.float64, "K(X,X)")
+    check_grads(host(gXX), gXXr, torch.float64, "grad_X total")
+
+
+# ------------------------------------------------------------------ autograd over the C ABI (Section 1)
+def test_autograd_wrappers_give_the_oracle_gradients():
+    from paper_2509_10613_amd import autograd as ska
+    nx, ny, L, d = 9, 7, 24, 3
+    rng = np.random.default_rng(96)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (nx, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (ny, L, d)), axis=1)
+    x = dev(X).requires_grad_(True)
+    y = dev(Y).requires_grad_(True)
+    # a loss of the kind the abstract names: a (biased) squared maximum mean discrepancy between two sets of
+    # paths; the reductions are the test's, the kernels and their gradients the library's
+    loss = ska.sig_kernel_gram(x, None, 1, 1, 1).mean() - 2.0 * ska.sig_kernel_gram(x, y, 1, 1, 1).mean() + \
+        ska.sig_kernel_gram(y, None, 1, 1, 1).mean()
+    loss.backward()
+    torch.cuda.synchronize()
+    Kxx, gxx, _ = oracle.gram(X, X, np.full((nx, nx), 1.0 / (nx * nx)), 1, 1, 1)
+    Kxy, gxy_x, gxy_y = oracle.gram(X, Y, np.full((nx, ny), -2.0 / (nx * ny)), 1, 1, 1)
+    Kyy, gyy, _ = oracle.gram(Y, Y, np.full((ny, ny), 1.0 / (ny * ny)), 1, 1, 1)
+    ref = Kxx.mean() - 2.0 * Kxy.mean() + Kyy.mean()
+    assert abs(float(loss.detach()) - ref) <= 1e-10 * max(1.0, abs(ref))
+    check_grads(host(x.grad), gxx + gxy_x, torch.float64, "d loss / dX")
+    check_grads(host(y.grad), gyy + gxy_y, torch.float64, "d loss / dY")
+    # pairs, one side without gradient
+    xb = dev(X[:7]).requires_grad_(True)
+    gk = workloads.upstream_weights(67, (7,))
+    k = ska.sig_kernel(xb, dev(Y), 0, 1, 0)
+    (k * dev(gk)).sum().backward()
+    torch.cuda.synchronize()
+    kr, gxr, _ = oracle.bwd(X[:7], Y, gk, 0, 1, 0)
+    check_values(host(k), kr, torch.float64, "k")
+    check_grads(host(xb.grad), gxr, torch.float64, "d/dx through autograd")
+
+
 # ------------------------------------------------------------------ full-size runs on sampled outputs
 def test_c3_full_size_sampled_entries():
     w, X, Y = workloads.make("c3")

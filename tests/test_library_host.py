@@ -33,7 +33,7 @@ def test_argument_validation_needs_no_gpu(lib):
     one = C.c_void_p(256)
     # bad dtype, bad flags, bad dyadic order, bad shape: all rejected before any GPU work
     assert f(one, one, one, 4, 8, 8, 2, 0, 0, 0, 7, one, 1 << 20, None) == -4
-    assert f(one, one, one, 4, 8, 8, 2, 0, 0, 8, 1, one, 1 << 20, None) == -4
+    assert f(one, one, one, 4, 8, 8, 2, 0, 0, 16, 1, one, 1 << 20, None) == -4
     assert f(one, one, one, 4, 8, 8, 2, -1, 0, 0, 1, one, 1 << 20, None) == -3
     assert f(one, one, one, 4, 8, 8, 2, 0, 21, 0, 1, one, 1 << 20, None) == -3
     assert f(one, one, one, 4, 0, 8, 2, 0, 0, 0, 1, one, 1 << 20, None) == -2

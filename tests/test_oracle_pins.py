@@ -266,3 +266,72 @@ def test_p6_long_double_arbitration():
 
 def test_oracle_reports_threads():
     assert oracle.num_threads() >= 1
+
+
+# ---------------------------------------------------------------- lead-lag transform (Section 4)
+def test_lead_lag_transform_gives_the_quadratic_variation():
+    # The transform of Section 4, pinned by what it is used for: the lead runs ahead of the lag, so the second
+    # level of the signature of the transformed path picks up every squared increment exactly once,
+    #   S^(lead_c, lag_c) - S^(lag_c, lead_c) = sum_k (x[k+1][c] - x[k][c])^2
+    # (the discrete quadratic variation; its cross terms cancel).  Swapping lead and lag, or dropping the
+    # intermediate points, breaks it.  Signatures by brute force (Proposition 2.1 and Chen's identity).
+    rng = np.random.default_rng(41)
+    x = np.cumsum(rng.normal(0, 0.7, size=(6, 2)), axis=0)
+    xl = oracle.lead_lag(x)
+    assert xl.shape == (11, 4)
+    assert np.array_equal(xl[0], np.concatenate([x[0], x[0]])) and np.array_equal(xl[-1], np.concatenate([x[-1], x[-1]]))
+    S2 = sigbrute.signature(xl, 2)[2]
+    dx = np.diff(x, axis=0)
+    for c in range(2):
+        assert abs((S2[c, 2 + c] - S2[2 + c, c]) - np.sum(dx[:, c] ** 2)) < 1e-12
+    # both halves travel the same total increment
+    S1 = sigbrute.signature(xl, 1)[1]
+    assert np.allclose(S1[:2], x[-1] - x[0]) and np.allclose(S1[2:], x[-1] - x[0])
+
+
+def test_lead_lag_flag_is_the_kernel_of_the_transformed_paths():
+    rng = np.random.default_rng(42)
+    x = np.cumsum(rng.normal(0, 0.4, size=(4, 2)), axis=0)
+    y = np.cumsum(rng.normal(0, 0.4, size=(3, 2)), axis=0)
+    xl, yl = oracle.lead_lag(x), oracle.lead_lag(y)
+    kN = sigbrute.truncated_kernel(xl, yl, 9)
+    assert abs(kN - sigbrute.truncated_kernel(xl, yl, 8)) < 1e-6 * max(1.0, abs(kN))
+    ks = [oracle.fwd(x[None], y[None], lam1=lam, lam2=lam, flags=oracle.FLAG_LEAD_LAG)[0] for lam in (4, 5)]
+    rich = (4.0 * ks[1] - ks[0]) / 3.0
+    assert abs(rich - kN) < 5e-6 * max(1.0, abs(kN))
+    # with time augmentation on top: the time channel of the transformed path, t_i = i / (2L - 2)
+    xa = np.concatenate([xl, (np.arange(7) / 6.0)[:, None]], axis=1)
+    ya = np.concatenate([yl, (np.arange(5) / 4.0)[:, None]], axis=1)
+    both = oracle.FLAG_LEAD_LAG | oracle.FLAG_TIME_AUG
+    assert oracle.fwd(x[None], y[None], 1, 2, both)[0] == oracle.fwd(xa[None], ya[None], 1, 2, 0)[0]
+
+
+def test_lead_lag_gradients_vs_central_differences():
+    rng = np.random.default_rng(43)
+    X = np.cumsum(rng.normal(0, 0.4, size=(2, 5, 2)), axis=1)
+    Y = np.cumsum(rng.normal(0, 0.4, size=(2, 4, 2)), axis=1)
+    gk = rng.normal(size=2)
+    flags = oracle.FLAG_LEAD_LAG | oracle.FLAG_TIME_AUG
+    k, gx, gy = oracle.bwd(X, Y, gk, 1, 0, flags)
+    h = 1e-6
+    for arr, g, which in ((X, gx, 0), (Y, gy, 1)):
+        for idx in [(0, 0, 0), (1, 2, 1), (0, arr.shape[1] - 1, 1), (1, 1, 0)]:
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            fp = np.dot(gk, oracle.fwd(ap, Y, 1, 0, flags) if which == 0 else oracle.fwd(X, ap, 1, 0, flags))
+            fm = np.dot(gk, oracle.fwd(am, Y, 1, 0, flags) if which == 0 else oracle.fwd(X, am, 1, 0, flags))
+            fd = (fp - fm) / (2 * h)
+            assert abs(fd - g[idx]) < 1e-7 * max(1.0, abs(fd)), (which, idx, fd, g[idx])
+    # Gram with a random weight matrix, symmetric case included
+    W = rng.normal(size=(2, 2))
+    K, gX, gY = oracle.gram(X, Y, W, 0, 1, oracle.FLAG_LEAD_LAG)
+    Xp = X.copy(); Xp[1, 3, 0] += h
+    Xm = X.copy(); Xm[1, 3, 0] -= h
+    fd = (np.sum(W * oracle.gram(Xp, Y, None, 0, 1, oracle.FLAG_LEAD_LAG)) -
+          np.sum(W * oracle.gram(Xm, Y, None, 0, 1, oracle.FLAG_LEAD_LAG))) / (2 * h)
+    assert abs(fd - gX[1, 3, 0]) < 1e-7 * max(1.0, abs(fd))
+    Ks, gXs, none = oracle.gram(X, X, W, 0, 0, oracle.FLAG_LEAD_LAG)
+    fd = (np.sum(W * oracle.gram(Xp, Xp, None, 0, 0, oracle.FLAG_LEAD_LAG)) -
+          np.sum(W * oracle.gram(Xm, Xm, None, 0, 0, oracle.FLAG_LEAD_LAG))) / (2 * h)
+    assert none is None and abs(fd - gXs[1, 3, 0]) < 1e-7 * max(1.0, abs(fd))
