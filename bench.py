@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", help="c2 (headline), or c1/c3/c4/c5 for the other configurations")
+    ap.add_argument("--lead-lag", action="store_true",
+                    help="apply the lead-lag transform on the fly (SK_FLAG_LEAD_LAG): a side measurement, not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -65,9 +67,11 @@ def main():
     dev = torch.device("cuda:0")
     w, X, Y = workloads.make(args.workload)
     lam, flags = w.lam, w.flags
+    if args.lead_lag:
+        flags |= sk.SK_FLAG_LEAD_LAG
     x = torch.tensor(X, device=dev)
     y = torch.tensor(Y, device=dev)
-    cells = w.pairs * w.cells_per_pair
+    cells = w.pairs * w.cells_per_pair * (4 if args.lead_lag else 1)   # the transformed paths have 2 (L - 1) steps
     gram = w.kind == "gram"
     f64 = sk.SK_F64
 
@@ -145,7 +149,7 @@ def main():
     # roofline of the dominant kernel (the backward sweep when there is one)
     dom_back = bool(w.backward and nb > 0)
     dom_ms = (bwd_ms / nb) if dom_back else (fwd_ms / max(nf, 1))
-    flops = cells * algorithmic_flops_per_cell(w.d, bool(flags & 1), lam, dom_back)
+    flops = cells * algorithmic_flops_per_cell(w.d * (2 if args.lead_lag else 1), bool(flags & 1), lam, dom_back)
     achieved = flops / (dom_ms * 1e-3) / 1e12
     # the sweep kernel's name as a profiler reports it, from the library's own launch plan
     if gram:
@@ -190,7 +194,7 @@ def main():
                     oracle.bwd(Xs, Ys, np.ones(nx), lam, lam, flags)
             spent += time.perf_counter() - a
             reps += 1
-        cpu = {"value": sample_pairs * w.cells_per_pair * reps / spent, "unit": "cells/s", "cores": oracle.num_threads(),
+        cpu = {"value": sample_pairs * w.cells_per_pair * (4 if args.lead_lag else 1) * reps / spent, "unit": "cells/s", "cores": oracle.num_threads(),
                "kind": "oracle",
                "sample": "%d pairs of %s (fwd%s), %d repetitions, %.1f s" % (sample_pairs, w.name,
                                                                              "+bwd" if w.backward else "", reps, spent)}
@@ -209,7 +213,8 @@ def main():
         "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": "%s: %s, %d pairs, L=%d, d=%d, dyadic order %d%s, fp64, fwd%s" % (
-            w.name, w.kind, w.pairs, w.L, w.d, lam, ", time-augmented" if flags & 1 else "",
+            w.name, w.kind, w.pairs, w.L, w.d, lam,
+            (", time-augmented" if flags & 1 else "") + (", lead-lag transformed" if args.lead_lag else ""),
             "+bwd" if w.backward else ""), "cells_per_step": cells},
         "evals_per_s": w.pairs / sec_per_step,
         "fwd_call_ms": t_fwd * 1e3,

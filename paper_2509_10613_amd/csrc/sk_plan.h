@@ -191,7 +191,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     } else {
         // LDS per wave: y increments (+ their gradient accumulators when going backward) and the replay ring.
         size_t ybytes = (size_t)p.DP * p.qpad * elem * (backward ? 2 : 1);
-        p.y_lds = (p.DT != 0 && ybytes <= 20 * 1024) ? 1 : 0;
+        p.y_lds = (p.DT != 0 && ybytes <= kLdsPerWave) ? 1 : 0;   // up to a whole compute unit for four waves
         size_t used = p.y_lds ? ybytes : 0;
         p.ring_off = used;
         if (backward && p.uncompute) {
