@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--workload", default="c2", help="c2 (headline), or c1/c3/c4/c5 for the other configurations")
     ap.add_argument("--lead-lag", action="store_true",
                     help="apply the lead-lag transform on the fly (SK_FLAG_LEAD_LAG): a side measurement, not the headline")
+    ap.add_argument("--symmetric", action="store_true",
+                    help="Gram workloads: K(X, X) instead of K(X, Y) (a side measurement, not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -71,6 +73,9 @@ def main():
         flags |= sk.SK_FLAG_LEAD_LAG
     x = torch.tensor(X, device=dev)
     y = torch.tensor(Y, device=dev)
+    if args.symmetric:
+        assert w.kind == "gram", "--symmetric is for the Gram workloads"
+        y, Y = x, X   # the same tensor selects the symmetric case
     cells = w.pairs * w.cells_per_pair * (4 if args.lead_lag else 1)   # the transformed paths have 2 (L - 1) steps
     gram = w.kind == "gram"
     f64 = sk.SK_F64
@@ -88,7 +93,7 @@ def main():
             sk.sigkernel_gram(x, y, None, lam, lam, flags, K=K, ws=ws)
 
         def bwd_call():
-            sk.sigkernel_gram(x, y, W, lam, lam, flags, K=K, grad_X=gX, grad_Y=gY, ws=ws)
+            sk.sigkernel_gram(x, y, W, lam, lam, flags, K=K, grad_X=gX, grad_Y=None if args.symmetric else gY, ws=ws)
     else:
         gk = torch.tensor(workloads.upstream_weights(77, (w.n_x,)), device=dev)
         k = torch.empty((w.n_x,), dtype=torch.float64, device=dev)
@@ -214,9 +219,13 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s, %d pairs, L=%d, d=%d, dyadic order %d%s, fp64, fwd%s" % (
             w.name, w.kind, w.pairs, w.L, w.d, lam,
-            (", time-augmented" if flags & 1 else "") + (", lead-lag transformed" if args.lead_lag else ""),
+            (", time-augmented" if flags & 1 else "") + (", lead-lag transformed" if args.lead_lag else "") +
+            (", K(X,X)" if args.symmetric else ""),
             "+bwd" if w.backward else ""), "cells_per_step": cells},
         "evals_per_s": w.pairs / sec_per_step,
+        # K(X, X): the library solves the pairs n <= m only (k(x, y) = k(y, x) bit for bit) and copies the rest
+        "pairs_solved": (w.n_x * (w.n_x + 1) // 2) if args.symmetric else w.pairs,
+        "solved_cells_per_s": (cells * ((w.n_x + 1) / (2.0 * w.n_x)) if args.symmetric else cells) / sec_per_step,
         "fwd_call_ms": t_fwd * 1e3,
         "bwd_call_ms": None if t_bwd is None else t_bwd * 1e3,
         "fwd_cells_per_s": cells / t_fwd,

@@ -84,7 +84,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.k_out = k ? reinterpret_cast<double*>(base + p.off_kio) : nullptr;
         if (backward) {
             double* gk64 = reinterpret_cast<double*>(base + p.off_gkio);
-            SK_CHECK((launch_convert<T, double>(static_cast<const T*>(grad_k), gk64, p.npairs, st)));
+            SK_CHECK((launch_convert<T, double>(static_cast<const T*>(grad_k), gk64, p.kcount, st)));
             a.grad_k = gk64;
         }
     }
@@ -93,6 +93,8 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     a.rowlen = p.rowlen;
     a.npairs = p.npairs;
     a.gramM = p.gramM;
+    a.gramN = p.nx;
+    a.tri = p.tri;
     a.r = p.r; a.q = p.q; a.rs1 = p.rs1; a.rs2 = p.rs2; a.mb = p.mb; a.nb = p.nb; a.ns = p.ns;
     a.S = p.S; a.nseg = p.nseg; a.d = p.d;
     const double sc = 1.0 / (double)((int64_t)1 << (lam1 + lam2));
@@ -173,7 +175,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
-    if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.npairs, st)));
+    if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.kcount, st)));
     if (backward && !fused) {
         SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, cL1, p.rpad, a.gdy,
                                     p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, cL2, p.qpad, cd, p.DP,

@@ -90,6 +90,36 @@ __device__ __forceinline__ void lds_atomic_add(SK_LDS real* p, real v)
 __device__ __forceinline__ void lds_order() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 
+// Pair q of the sequence a launch of the solo / tile kernels works through: the identity for pair batches, y-major
+// for Gram matrices (q = m N + n: consecutive pairs share the y path), and for a symmetric Gram matrix K(X, X)
+// only the pairs n <= m (k(x, y) = k(y, x) holds bit for bit, Section 3.1: the other half is a copy).  There the
+// rows m and N - 1 - m, which hold m + 1 and N - m such pairs, form one virtual row of N + 1 pairs, so that
+// contiguous runs of the sequence are equally long whatever the row.  pid / pid2: where K[n, m] and its mirror
+// image live (equal on the diagonal).
+__device__ __forceinline__ void gram_pair(const SweepArgs& a, long q, long& xi, long& yi, long& pid, long& pid2)
+{
+    if (!a.gramM) {
+        xi = yi = pid = pid2 = q;
+    } else if (!a.tri) {
+        yi = q / a.gramN;
+        xi = q - yi * a.gramN;
+        pid = pid2 = xi * a.gramM + yi;
+    } else {
+        const long N = a.gramN;
+        const long vr = q / (N + 1), t = q - vr * (N + 1);
+        if (t <= vr) { yi = vr; xi = t; }
+        else { yi = N - 1 - vr; xi = t - vr - 1; }
+        pid = xi * N + yi;
+        pid2 = yi * N + xi;
+    }
+}
+// Upstream gradient of the pair: in the symmetric case the pair stands for both (n, m) and (m, n).
+__device__ __forceinline__ real gram_weight(const SweepArgs& a, long pid, long pid2)
+{
+    const real g = a.grad_k[pid];
+    return pid2 != pid ? g + a.grad_k[pid2] : g;
+}
+
 __device__ __forceinline__ void pair_ids(const SweepArgs& a, long pid, long& xi, long& yi)
 {
     xi = a.gramM ? pid / a.gramM : pid;

@@ -27,6 +27,8 @@ struct SweepArgs {
     long ckpt_slot;
     long npairs;
     long gramM;          // > 0: pair id -> (id / gramM, id % gramM)
+    long gramN;          // rows of the Gram matrix
+    int tri;             // symmetric Gram matrix in the solo / tile kernels: npairs = N (N + 1) / 2 pairs n <= m (sk_dev.h)
     int r, q;            // coarse cells per side
     int rs1, rs2;        // residual refinement shifts of block row / column to coarse index
     int mb, nb;          // block rows / columns

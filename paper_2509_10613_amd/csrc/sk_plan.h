@@ -30,7 +30,9 @@ struct Plan {
     int elem = 8;               // bytes per element of every internal buffer (sweeps run in double)
     int io_elem = 8;            // bytes per element of the caller's arrays
     int64_t nx = 0, ny = 0;     // number of x paths and y paths
-    int64_t npairs = 0;
+    int64_t npairs = 0;         // pairs the sweep launch works through
+    int64_t kcount = 0;         // entries of k / K (differs from npairs only for tri)
+    int tri = 0;                // symmetric Gram matrix in solo / tile mode: only the pairs n <= m are solved
     int64_t gramM = 0;          // > 0: pair id -> (id / gramM, id % gramM); 0: pair id -> (id, id)
     int L1 = 0, L2 = 0, d = 0;
     int BL = 0, rs1 = 0, rs2 = 0;
@@ -119,6 +121,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     p.nx = nx;
     p.ny = ny;
     p.npairs = gram ? nx * ny : nx;
+    p.kcount = p.npairs;
     p.gramM = gram ? ny : 0;
     p.L1 = (int)L1; p.L2 = (int)L2; p.d = (int)d;
     p.r = (int)L1 - 1; p.q = (int)L2 - 1;
@@ -317,6 +320,16 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.nseg = NT / kLockS;
     }
 
+    // Symmetric Gram matrix: k(x, y) = k(y, x) bit for bit, so the solo and tile kernels solve the pairs n <= m
+    // only, write both entries of K, and use the sum of the two upstream gradients.
+    if (symmetric && gram && nx == ny && (p.solo || p.tile)) {
+        p.tri = 1;
+        p.npairs = nx * (nx + 1) / 2;
+        const int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
+        if (want < p.grid) p.grid = (int)want;
+        p.nslots = (int64_t)p.grid * kWavesPerWG;
+    }
+
     // Band mode: few pairs of long paths.  The strips of a pair are spread over workgroups (bands of kBandStrips
     // strips) that all run at once; chosen when that fills more of the chip than one workgroup per pair does.
     if (!p.lock && !p.tile && !p.solo && (!backward || p.uncompute) && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips) {
@@ -364,8 +377,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
     }
     if (io_elem != elem) {
-        p.off_kio = take((size_t)p.npairs * elem);
-        if (backward) p.off_gkio = take((size_t)p.npairs * elem);
+        p.off_kio = take((size_t)p.kcount * elem);
+        if (backward) p.off_gkio = take((size_t)p.kcount * elem);
     }
     p.off_err = take(256);
     p.off_flags = take((size_t)p.nflags * sizeof(int) + 4);   // directly behind the error flag: cleared with it

@@ -25,19 +25,6 @@
 
 namespace sk {
 
-// Pair q of the launch's sequence: y-major in Gram mode (q = m N + n), the identity for pair batches.
-__device__ __forceinline__ void solo_pair(const SweepArgs& a, long q, long& xi, long& yi, long& pid)
-{
-    if (a.gramM) {
-        const long N = a.npairs / a.gramM;
-        yi = q / N;
-        xi = q - yi * N;
-        pid = xi * a.gramM + yi;
-    } else {
-        xi = yi = pid = q;
-    }
-}
-
 // ------------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------------
@@ -60,8 +47,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo
     typename LK::Coef cf;
     typename LK::Fwd f;
     for (long q = q0; q < q1; ++q) {
-        long xi, yi, pid;
-        solo_pair(a, q, xi, yi, pid);
+        long xi, yi, pid, pid2;
+        gram_pair(a, q, xi, yi, pid, pid2);
         if (yi != cur_y) {
             const real* dyg = a.dy + yi * a.ystride;
             for (int t = lane; t < a.q * LK::DSc; t += kWave) ylds[t] = dyg[t];
@@ -107,7 +94,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo
             run(std::false_type(), kWave - 1, nb);
             run(std::true_type(), nb, NT);
         }
-        if (lane == kWave - 1) a.k_out[pid] = f.bot[C - 1];
+        if (lane == kWave - 1) {
+            a.k_out[pid] = f.bot[C - 1];
+            if (pid2 != pid) a.k_out[pid2] = f.bot[C - 1];
+        }
     }
 }
 
@@ -156,8 +146,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
     };
 
     for (long q = q0; q < q1; ++q) {
-        long xi, yi, pid;
-        solo_pair(a, q, xi, yi, pid);
+        long xi, yi, pid, pid2;
+        gram_pair(a, q, xi, yi, pid, pid2);
         if (yi != cur_y) {
             flush_gy();
             const real* dyg = a.dy + yi * a.ystride;
@@ -166,7 +156,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
             gdy_cur = a.gdy + yi * a.ystride;
         }
         cf.setup(a, 0, lane, a.dx + xi * a.xstride, ylds);
-        const real gk = a.grad_k[pid];
+        const real gk = gram_weight(a, pid, pid2);
 
         // ---- phase 1: forward, a checkpoint every S macro-steps, the bottom row into LDS ----
         {
@@ -207,7 +197,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
             }
             f.store_ckpt(ckpt + (long)nseg * NVC * kWave);
         }
-        if (a.k_out && lane == 0) a.k_out[pid] = krow[nb * C];
+        if (a.k_out && lane == 0) {
+            a.k_out[pid] = krow[nb * C];
+            if (pid2 != pid) a.k_out[pid2] = krow[nb * C];
+        }
         scratch_fence();   // the checkpoints are read back below
 
         // ---- phase 2: the mirror image ----

@@ -37,19 +37,6 @@ namespace sk {
 
 typedef double real4 __attribute__((ext_vector_type(4)));
 
-// Pair q of the launch's sequence: y-major in Gram mode (q = m N + n), the identity for pair batches.
-__device__ __forceinline__ void tile_pair(const SweepArgs& a, long q, long& xi, long& yi, long& pid)
-{
-    if (a.gramM) {
-        const long N = a.npairs / a.gramM;
-        yi = q / N;
-        xi = q - yi * N;
-        pid = xi * a.gramM + yi;
-    } else {
-        xi = yi = pid = q;
-    }
-}
-
 // Column a lane reads p from: J inside the grid, else the zero column nb (J < 0 is a huge unsigned number).
 __device__ __forceinline__ int read_col(int J, int nb) { return (int)min((unsigned)J, (unsigned)nb); }
 // Column a lane writes dF/dp to: J inside the grid, the zero column nb to its right (the value is zero
@@ -162,8 +149,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_fwd_kernel(SweepAr
 
     typename LK::Fwd f;
     for (long q = q0; q < q1; ++q) {
-        long xi, yi, pid;
-        tile_pair(a, q, xi, yi, pid);
+        long xi, yi, pid, pid2;
+        gram_pair(a, q, xi, yi, pid, pid2);
         if (yi != cur_y) {
             TL::load_b(a.dy + yi * a.ystride, a.DS, 0, lane, yb);
             cur_y = yi;
@@ -197,7 +184,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_fwd_kernel(SweepAr
 #pragma unroll
         for (int i = 0; i < kTilePF; ++i)
             if (T0 + i < NT) step(pq[i]);
-        if (lane == kWave - 1) a.k_out[pid] = f.bot[0];
+        if (lane == kWave - 1) {
+            a.k_out[pid] = f.bot[0];
+            if (pid2 != pid) a.k_out[pid2] = f.bot[0];
+        }
     }
 }
 
@@ -261,14 +251,14 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
     real xb[4][KC];
     real gk = 0.0;
     if (q0 < q1) {
-        long xi, yi, pid;
-        tile_pair(a, q0, xi, yi, pid);
+        long xi, yi, pid, pid2;
+        gram_pair(a, q0, xi, yi, pid, pid2);
         TL::load_b(a.dx + xi * a.xstride, a.DS, padb, lane, xb);
-        gk = a.grad_k[pid];
+        gk = gram_weight(a, pid, pid2);
     }
     for (long q = q0; q < q1; ++q) {
-        long xi, yi, pid;
-        tile_pair(a, q, xi, yi, pid);
+        long xi, yi, pid, pid2;
+        gram_pair(a, q, xi, yi, pid, pid2);
         if (yi != cur_y) {
             flush_gy();
             const real* dyg = a.dy + yi * a.ystride;
@@ -313,7 +303,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
             kR0 = f.left[0];
             kR1 = f.left[1];
         }
-        if (a.k_out && lane == 0) a.k_out[pid] = krow[nb * kTileStride];
+        if (a.k_out && lane == 0) {
+            a.k_out[pid] = krow[nb * kTileStride];
+            if (pid2 != pid) a.k_out[pid2] = krow[nb * kTileStride];
+        }
 
         // ---- phase 2: the mirror image; G = dF/dp replaces p in place ----
         {
@@ -379,10 +372,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
         real xc[16], xbn[4][KC], gkn = 0.0;
         if (a.want_gy) TL::load_c(dxg, a.DS, padb, lane, xc);
         if (q + 1 < q1) {
-            long xin, yin, pidn;
-            tile_pair(a, q + 1, xin, yin, pidn);
+            long xin, yin, pidn, pidn2;
+            gram_pair(a, q + 1, xin, yin, pidn, pidn2);
             TL::load_b(a.dx + xin * a.xstride, a.DS, padb, lane, xbn);
-            gkn = a.grad_k[pidn];
+            gkn = gram_weight(a, pidn, pidn2);
         }
 
         // ---- the linear map of Section 3.4 on the matrix cores ----

@@ -261,6 +261,31 @@ def test_band_mode_wait_that_runs_out_gives_nan_and_ends():
     check_grads(host(gy), gyr, torch.float64, "grad_y after a failed call")
 
 
+@pytest.mark.parametrize("name,N,dtype", [("c3", 41, torch.float64), ("c5", 45, torch.float64), ("c5", 38, torch.float32)])
+def test_symmetric_gram_solves_half_the_pairs(name, N, dtype):
+    # K(X, X) in the solo / tile kernels: only the pairs n <= m are solved (odd and even N), both entries of K are
+    # written, and the gradient is the total derivative for a weight matrix that is not symmetric
+    w, X, _ = workloads.make(name, n_x=N, n_y=N)
+    Xr = rounded(X, dtype)
+    W = workloads.upstream_weights(68, (N, N))
+    x = dev(X, dtype)
+    K, gX, none = sk.sigkernel_gram(x, x, dev(W, dtype), w.lam, w.lam, w.flags)
+    Kf = sk.sigkernel_gram(x, x, None, w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    Kr, gXr, _ = oracle.gram(Xr, Xr, rounded(W, dtype), w.lam, w.lam, w.flags)
+    assert none is None
+    check_values(host(K), Kr, dtype, "K(X,X)")
+    check_values(host(Kf), Kr, dtype, "K(X,X) forward only")
+    check_grads(host(gX), gXr, dtype, "grad_X total")
+    assert torch.equal(K, K.T) and torch.equal(Kf, Kf.T)
+    # the same through the general entry (a copy of X as Y): identical values, the two gradients add up
+    y = dev(X, dtype).clone()
+    K2, gX2, gY2 = sk.sigkernel_gram(x, y, dev(W, dtype), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    assert torch.equal(K2, K)
+    check_grads(host(gX2) + host(gY2), gXr, dtype, "grad_X + grad_Y of the general case")
+
+
 # ------------------------------------------------------------------ lead-lag transform on the fly (Section 4)
 LL = sk.SK_FLAG_LEAD_LAG
 
