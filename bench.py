@@ -48,6 +48,9 @@ def main():
                     help="apply the lead-lag transform on the fly (SK_FLAG_LEAD_LAG): a side measurement, not the headline")
     ap.add_argument("--symmetric", action="store_true",
                     help="Gram workloads: K(X, X) instead of K(X, Y) (a side measurement, not the headline)")
+    ap.add_argument("--mmd", action="store_true",
+                    help="Gram workloads: a step is one sigkernel_mmd2 call (value and both gradients): K(X,X), K(X,Y) "
+                         "and K(Y,Y) with gradients (a side measurement, not the headline; no roofline figure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -115,6 +118,19 @@ def main():
         if w.backward:
             bwd_call()
 
+    if args.mmd:
+        assert gram and not args.symmetric, "--mmd is for the Gram workloads"
+        loss = torch.empty((1,), dtype=torch.float64, device=dev)
+        need = int(sk.load().sigkernel_mmd2_workspace_bytes(w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags, f64, 1))
+        wsm = torch.empty(need, dtype=torch.uint8, device=dev)
+
+        def step():   # noqa: F811
+            sk._check(sk.load().sigkernel_mmd2(sk._ptr(x), sk._ptr(y), sk._ptr(loss), sk._ptr(gX), sk._ptr(gY), w.n_x,
+                                               w.n_y, w.L, w.L, w.d, lam, lam, flags, f64, sk._ptr(wsm), wsm.numel(),
+                                               sk._stream()))
+        # entries of the three Gram matrices; the symmetric ones solve n <= m only
+        cells = (w.n_x * w.n_x + w.n_x * w.n_y + w.n_y * w.n_y) * w.cells_per_pair * (4 if args.lead_lag else 1)
+
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -147,6 +163,16 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - a) / n
 
+    if args.mmd:
+        print(json.dumps({"metric": "PDE cell-updates/s (squared MMD with gradients: K(X,X), K(X,Y), K(Y,Y)), fp64, 1 MI355X",
+                          "value": cells / sec_per_step, "unit": "cells/s", "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True,
+                          "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+                          "config": {"workload": "%s as two path sets of %d and %d paths, L=%d, d=%d, dyadic order %d, "
+                                                 "sigkernel_mmd2" % (w.name, w.n_x, w.n_y, w.L, w.d, lam),
+                                     "cells_per_step": cells},
+                          "sweep_launches_ms": (fwd_ms + bwd_ms) / args.steps, "roofline": None, "cpu_baseline": None}))
+        return
     n_sep = max(3, args.steps // 4)
     t_fwd = time_call(fwd_call, n_sep)
     t_bwd = time_call(bwd_call, n_sep) if w.backward else None

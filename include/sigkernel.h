@@ -114,6 +114,23 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
                    sk_dtype dt, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Squared maximum mean discrepancy between two sets of paths under the signature kernel, the kind of training
+ * loss the paper's abstract and Section 1 name ("training losses for generative models"; the gradients are the
+ * exact ones of Section 3.4):
+ *   loss = mean_{n,n'} k(X[n], X[n']) - 2 mean_{n,m} k(X[n], Y[m]) + mean_{m,m'} k(Y[m], Y[m'])
+ * (the biased estimate, diagonals included), X[N,L1,d], Y[M,L2,d], N, M >= 1.  loss is a device pointer to one
+ * element.  If grad_X / grad_Y are not NULL they receive d loss / dX [N,L1,d] and d loss / dY [M,L2,d].
+ * Three Gram computations (two of them symmetric: half of their pairs are solved) with constant upstream
+ * weights that are generated on the device, then one reduction.  Same conventions as the other entry points;
+ * the workspace size comes from sigkernel_mmd2_workspace_bytes (with_grads != 0 if any gradient is wanted).
+ */
+size_t sigkernel_mmd2_workspace_bytes(int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
+                                      int flags, sk_dtype dt, int with_grads);
+int sigkernel_mmd2(const void* X, const void* Y, void* loss, void* grad_X, void* grad_Y, int64_t N, int64_t M,
+                   int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt, void* ws,
+                   size_t ws_bytes, void* stream);
+
+/*
  * Benchmark support (no passage of the paper): while enabled, every sweep-kernel launch made by the
  * three entry points above is bracketed by a HIP event pair recorded on the caller's stream.
  * sigkernel_event_timing_read waits for the recorded launches to finish, returns the summed elapsed

@@ -184,3 +184,19 @@ def gram(X, Y, grad_K=None, lam1=0, lam2=0, flags=0, dtype=np.float64):
     rc = f(_p(X), _p(Y), _p(K), _p(W), _p(gX), _p(gY), N, M, L1, L2, d, lam1, lam2, flags)
     assert rc == 0
     return K, gX, gY
+
+
+def mmd2(X, Y, lam1=0, lam2=0, flags=0, dtype=np.float64, want_grads=True):
+    """Squared maximum mean discrepancy of two path sets under the signature kernel, written out from its
+    definition (biased estimate): mean K(X,X) - 2 mean K(X,Y) + mean K(Y,Y); the gradients by the chain rule
+    through gram() with the constant weights 1/N^2, -2/(NM), 1/M^2.  Returns loss or (loss, grad_X, grad_Y)."""
+    X = _arr(X, dtype)
+    Y = _arr(Y, dtype)
+    N, M = X.shape[0], Y.shape[0]
+    if not want_grads:
+        return (gram(X, X, None, lam1, lam1, flags, dtype).mean() - 2.0 * gram(X, Y, None, lam1, lam2, flags, dtype).mean()
+                + gram(Y, Y, None, lam2, lam2, flags, dtype).mean())
+    Kxx, gxx, _ = gram(X, X, np.full((N, N), 1.0 / (N * N)), lam1, lam1, flags, dtype)
+    Kxy, gxy_x, gxy_y = gram(X, Y, np.full((N, M), -2.0 / (N * M)), lam1, lam2, flags, dtype)
+    Kyy, gyy, _ = gram(Y, Y, np.full((M, M), 1.0 / (M * M)), lam2, lam2, flags, dtype)
+    return Kxx.mean() - 2.0 * Kxy.mean() + Kyy.mean(), gxx + gxy_x, gyy + gxy_y

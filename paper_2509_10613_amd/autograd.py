@@ -7,6 +7,7 @@ method happens here.
     k = sig_kernel(x, y, lam1, lam2, flags)          # x[B,L1,d], y[B,L2,d] -> k[B]
     K = sig_kernel_gram(X, Y, lam1, lam2, flags)     # X[N,L1,d], Y[M,L2,d] -> K[N,M]
     K = sig_kernel_gram(X, None, lam1, lam2, flags)  # symmetric case K(X, X)
+    loss = sig_mmd2(X, Y, lam1, lam2, flags)         # squared MMD between two sets of paths, one library call
 
 The gradients are first-order only (the backward pass is not itself differentiable).
 """
@@ -66,6 +67,31 @@ class _GramKernelSym(torch.autograd.Function):
         lam1, lam2, flags = ctx.args
         _, gX, _ = sk.sigkernel_gram(X, X, grad_K.contiguous(), lam1, lam2, flags)   # total derivative, both slots
         return gX, None, None, None
+
+
+class _Mmd2(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, X, Y, lam1, lam2, flags):
+        X = X.contiguous()
+        Y = Y.contiguous()
+        want_x, want_y = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        loss, gX, gY = sk.sigkernel_mmd2(X, Y, lam1, lam2, flags, want_x=want_x, want_y=want_y)
+        ctx.save_for_backward(*[g for g in (gX, gY) if g is not None])
+        ctx.have = (gX is not None, gY is not None)
+        return loss[0]
+
+    @staticmethod
+    def backward(ctx, grad_loss):
+        saved = list(ctx.saved_tensors)
+        gX = saved.pop(0) if ctx.have[0] else None
+        gY = saved.pop(0) if ctx.have[1] else None
+        return (None if gX is None else gX * grad_loss), (None if gY is None else gY * grad_loss), None, None, None
+
+
+def sig_mmd2(X, Y, lam1=0, lam2=0, flags=0):
+    """mean K(X,X) - 2 mean K(X,Y) + mean K(Y,Y) for device tensors X[N,L1,d], Y[M,L2,d] (sigkernel_mmd2: value and
+    gradients in one call, the upstream weights never leave the GPU); differentiable in X and Y."""
+    return _Mmd2.apply(X, Y, lam1, lam2, flags)
 
 
 def sig_kernel(x, y, lam1=0, lam2=0, flags=0):

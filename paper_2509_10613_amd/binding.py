@@ -19,6 +19,7 @@ SK_FLAG_LEAD_LAG = 8
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",
+           "sigkernel_mmd2", "sigkernel_mmd2_workspace_bytes",
            "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version"]
 
 _lib = None
@@ -50,6 +51,10 @@ def load():
     lib.sigkernel_gram.restype = ci
     lib.sigkernel_gram.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t,
                                    vp]
+    lib.sigkernel_mmd2_workspace_bytes.restype = C.c_size_t
+    lib.sigkernel_mmd2_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci, ci, ci]
+    lib.sigkernel_mmd2.restype = ci
+    lib.sigkernel_mmd2.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t, vp]
     lib.sigkernel_event_timing.restype = ci
     lib.sigkernel_event_timing.argtypes = [ci]
     lib.sigkernel_event_timing_read.restype = ci
@@ -191,3 +196,22 @@ def sigkernel_gram(X, Y, grad_K=None, lam1=0, lam2=0, flags=0, K=None, grad_X=No
     if backward:
         return K, grad_X, grad_Y
     return K
+
+
+def sigkernel_mmd2(X, Y, lam1=0, lam2=0, flags=0, want_x=True, want_y=True, ws=None):
+    """Squared MMD between the path sets X[N,L1,d] and Y[M,L2,d] under the signature kernel.
+    Returns (loss[1], grad_X or None, grad_Y or None)."""
+    _dev(X, "X"); _dev(Y, "Y")
+    N, L1, d = X.shape
+    M, L2, d2 = Y.shape
+    assert d2 == d and Y.dtype == X.dtype
+    dt = _dt(X)
+    loss = torch.empty((1,), dtype=X.dtype, device=X.device)
+    gX = torch.empty_like(X) if want_x else None
+    gY = torch.empty_like(Y) if want_y else None
+    need = int(load().sigkernel_mmd2_workspace_bytes(N, M, L1, L2, d, lam1, lam2, flags, dt, 1 if (want_x or want_y) else 0))
+    if ws is None:
+        ws = workspace(need, X.device)
+    _check(load().sigkernel_mmd2(_ptr(X), _ptr(Y), _ptr(loss), _ptr(gX), _ptr(gY), N, M, L1, L2, d, lam1, lam2, flags,
+                                 dt, _ptr(ws), ws.numel(), _stream()))
+    return loss, gX, gY

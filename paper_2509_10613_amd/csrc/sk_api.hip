@@ -292,6 +292,120 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
                     dt, ws, ws_bytes, stream);
 }
 
+}  // extern "C"
+
+// Layout of the scratch of sigkernel_mmd2: the three Gram matrices, their constant upstream weights, the second
+// halves of the two gradients (all in the caller's element type), then the scratch of the Gram calls.
+namespace {
+struct MmdLayout {
+    size_t kxx, kxy, kyy, wxx, wxy, wyy, gx2, gy2, sub, sub_bytes, total;
+};
+MmdLayout mmd_layout(int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags,
+                     sk_dtype dt, bool grads)
+{
+    MmdLayout l{};
+    const size_t e = dt == SK_F64 ? 8 : 4;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = sk::align_up(off + bytes, 256); return o; };
+    l.kxx = take((size_t)N * N * e);
+    l.kxy = take((size_t)N * M * e);
+    l.kyy = take((size_t)M * M * e);
+    if (grads) {
+        l.wxx = take((size_t)N * N * e);
+        l.wxy = take((size_t)N * M * e);
+        l.wyy = take((size_t)M * M * e);
+        l.gx2 = take((size_t)N * L1 * d * e);
+        l.gy2 = take((size_t)M * L2 * d * e);
+    }
+    const int op = grads ? SK_OP_GRAM_BWD : SK_OP_GRAM;
+    size_t s = sigkernel_workspace_bytes(op, N, N, L1, L1, d, lam1, lam1, flags, dt);
+    size_t t = sigkernel_workspace_bytes(op, N, M, L1, L2, d, lam1, lam2, flags, dt);
+    if (t > s) s = t;
+    t = sigkernel_workspace_bytes(op, M, M, L2, L2, d, lam2, lam2, flags, dt);
+    if (t > s) s = t;
+    l.sub_bytes = s;
+    l.sub = take(s);
+    l.total = off;
+    return l;
+}
+
+template <typename T>
+int run_mmd2(const MmdLayout& l, const void* X, const void* Y, void* loss, void* grad_X, void* grad_Y, int64_t N,
+             int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt, void* ws,
+             void* stream)
+{
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    T* Kxx = reinterpret_cast<T*>(base + l.kxx);
+    T* Kxy = reinterpret_cast<T*>(base + l.kxy);
+    T* Kyy = reinterpret_cast<T*>(base + l.kyy);
+    void* sub = base + l.sub;
+    const bool grads = grad_X != nullptr || grad_Y != nullptr;
+    T *Wxx = nullptr, *Wxy = nullptr, *Wyy = nullptr, *gx2 = nullptr, *gy2 = nullptr;
+    hipError_t e = hipSuccess;
+    if (grads) {
+        Wxx = reinterpret_cast<T*>(base + l.wxx);
+        Wxy = reinterpret_cast<T*>(base + l.wxy);
+        Wyy = reinterpret_cast<T*>(base + l.wyy);
+        gx2 = grad_X ? reinterpret_cast<T*>(base + l.gx2) : nullptr;
+        gy2 = grad_Y ? reinterpret_cast<T*>(base + l.gy2) : nullptr;
+        // d loss / dK of the three blocks: constants, generated where they are used
+        e = sk::launch_fill<T>(Wxx, N * N, (T)(1.0 / ((double)N * (double)N)), st);
+        if (e == hipSuccess) e = sk::launch_fill<T>(Wxy, N * M, (T)(-2.0 / ((double)N * (double)M)), st);
+        if (e == hipSuccess) e = sk::launch_fill<T>(Wyy, M * M, (T)(1.0 / ((double)M * (double)M)), st);
+        if (e != hipSuccess) return fail(SK_ERR_HIP, "fill: %s", hipGetErrorString(e));
+    }
+    int rc = SK_OK;
+    // K(X, X): symmetric, grad_X receives the total derivative of this block
+    if (grad_X || !grads)
+        rc = dispatch(grad_X != nullptr, true, X, X, Kxx, grad_X ? Wxx : nullptr, grad_X, nullptr, N, N, L1, L1, d, lam1,
+                      lam1, flags, dt, sub, l.sub_bytes, stream);
+    else
+        rc = dispatch(false, true, X, X, Kxx, nullptr, nullptr, nullptr, N, N, L1, L1, d, lam1, lam1, flags, dt, sub,
+                      l.sub_bytes, stream);
+    if (rc != SK_OK) return rc;
+    rc = dispatch(grads, true, X, Y, Kxy, grads ? Wxy : nullptr, gx2, gy2, N, M, L1, L2, d, lam1, lam2, flags, dt, sub,
+                  l.sub_bytes, stream);
+    if (rc != SK_OK) return rc;
+    rc = dispatch(grad_Y != nullptr, true, Y, Y, Kyy, grad_Y ? Wyy : nullptr, grad_Y, nullptr, M, M, L2, L2, d, lam2, lam2,
+                  flags, dt, sub, l.sub_bytes, stream);
+    if (rc != SK_OK) return rc;
+    if (grad_X) e = sk::launch_add_inplace<T>(static_cast<T*>(grad_X), gx2, N * L1 * d, st);
+    if (e == hipSuccess && grad_Y) e = sk::launch_add_inplace<T>(static_cast<T*>(grad_Y), gy2, M * L2 * d, st);
+    if (e == hipSuccess) e = sk::launch_mmd2_reduce<T>(Kxx, Kxy, Kyy, N * N, N * M, M * M, static_cast<T*>(loss), st);
+    if (e != hipSuccess) return fail(SK_ERR_HIP, "mmd2 reduction: %s", hipGetErrorString(e));
+    return SK_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sigkernel_mmd2_workspace_bytes(int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
+                                      int flags, sk_dtype dt, int with_grads)
+{
+    if (N < 1 || M < 1 || validate(N, M, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
+    return mmd_layout(N, M, L1, L2, d, lam1, lam2, flags, dt, with_grads != 0).total;
+}
+
+int sigkernel_mmd2(const void* X, const void* Y, void* loss, void* grad_X, void* grad_Y, int64_t N, int64_t M,
+                   int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt, void* ws,
+                   size_t ws_bytes, void* stream)
+{
+    int rc = validate(N, M, L1, L2, d, lam1, lam2, flags, (int)dt);
+    if (rc != SK_OK) return rc;
+    if (N < 1 || M < 1) return fail(SK_ERR_SHAPE, "mmd2 needs at least one path on either side");
+    if (!X || !Y || !loss) return fail(SK_ERR_NULL, "X / Y / loss is NULL");
+    if (X == Y) return fail(SK_ERR_SHAPE, "mmd2 of a set with itself is zero; pass two arrays");
+    const bool grads = grad_X != nullptr || grad_Y != nullptr;
+    const MmdLayout l = mmd_layout(N, M, L1, L2, d, lam1, lam2, flags, dt, grads);
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0)
+        return fail(SK_ERR_WORKSPACE, "workspace pointer is NULL or not 256-byte aligned");
+    if (ws_bytes < l.total) return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, l.total);
+    if (dt == SK_F64)
+        return run_mmd2<double>(l, X, Y, loss, grad_X, grad_Y, N, M, L1, L2, d, lam1, lam2, flags, dt, ws, stream);
+    return run_mmd2<float>(l, X, Y, loss, grad_X, grad_Y, N, M, L1, L2, d, lam1, lam2, flags, dt, ws, stream);
+}
+
 int sigkernel_event_timing(int enable)
 {
     std::lock_guard<std::mutex> lk(g_timing_mu);

@@ -79,6 +79,10 @@ struct SweepArgs {
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
 template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st);
+template <typename T>
+hipError_t launch_mmd2_reduce(const T* Kxx, const T* Kxy, const T* Kyy, long nxx, long nxy, long nyy, T* out,
+                              hipStream_t st);
+template <typename T> hipError_t launch_add_inplace(T* dst, const T* src, long n, hipStream_t st);
 // dx/dy null = that side is not (re)computed (symmetric Gram); gdx/gdy null = no accumulator to clear.
 template <typename T>
 hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,

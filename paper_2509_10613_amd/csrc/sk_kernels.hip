@@ -46,6 +46,37 @@ __global__ void fill_kernel(T* p, long n, T v)
     for (; i < n; i += st) p[i] = v;
 }
 
+// Squared maximum mean discrepancy from the three Gram matrices (one workgroup, fixed summation order):
+//   out = mean(Kxx) - 2 mean(Kxy) + mean(Kyy).
+template <typename T>
+__global__ __launch_bounds__(1024) void mmd2_reduce_kernel(const T* __restrict__ Kxx, const T* __restrict__ Kxy,
+                                                           const T* __restrict__ Kyy, long nxx, long nxy, long nyy,
+                                                           T* out)
+{
+    __shared__ real part[1024];
+    real acc = 0.0;
+    const real wxx = 1.0 / (real)nxx, wxy = -2.0 / (real)nxy, wyy = 1.0 / (real)nyy;
+    for (long i = threadIdx.x; i < nxx; i += blockDim.x) acc += wxx * (real)Kxx[i];
+    for (long i = threadIdx.x; i < nxy; i += blockDim.x) acc += wxy * (real)Kxy[i];
+    for (long i = threadIdx.x; i < nyy; i += blockDim.x) acc += wyy * (real)Kyy[i];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = blockDim.x / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = (T)part[0];
+}
+
+// dst[i] += src[i]
+template <typename T>
+__global__ void add_inplace_kernel(T* dst, const T* __restrict__ src, long n)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long st = (long)gridDim.x * blockDim.x;
+    for (; i < n; i += st) dst[i] = (T)((real)dst[i] + (real)src[i]);
+}
+
 // One set of paths for the preparation / finalisation kernels.
 template <typename T>
 struct PathSet {
@@ -1784,6 +1815,24 @@ hipError_t launch_fill(T* p, long n, T v, hipStream_t st)
     return hipGetLastError();
 }
 
+template <typename T>
+hipError_t launch_mmd2_reduce(const T* Kxx, const T* Kxy, const T* Kyy, long nxx, long nxy, long nyy, T* out,
+                              hipStream_t st)
+{
+    hipLaunchKernelGGL(mmd2_reduce_kernel<T>, dim3(1), dim3(1024), 0, st, Kxx, Kxy, Kyy, nxx, nxy, nyy, out);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_add_inplace(T* dst, const T* src, long n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    long blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(add_inplace_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, dst, src, n);
+    return hipGetLastError();
+}
+
 template <typename TA, typename TB>
 hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st)
 {
@@ -1940,6 +1989,11 @@ hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int g
     }
 }
 
+template hipError_t launch_mmd2_reduce<float>(const float*, const float*, const float*, long, long, long, float*, hipStream_t);
+template hipError_t launch_mmd2_reduce<double>(const double*, const double*, const double*, long, long, long, double*,
+                                               hipStream_t);
+template hipError_t launch_add_inplace<float>(float*, const float*, long, hipStream_t);
+template hipError_t launch_add_inplace<double>(double*, const double*, long, hipStream_t);
 template hipError_t launch_fill<float>(float*, long, float, hipStream_t);
 template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
 template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);

@@ -368,6 +368,36 @@ def test_autograd_wrappers_give_the_oracle_gradients():
     check_grads(host(xb.grad), gxr, torch.float64, "d/dx through autograd")
 
 
+@pytest.mark.parametrize("N,M,L1,L2,d,lam,flags,dtype", [(9, 7, 24, 30, 3, 1, 1, torch.float64),
+                                                         (40, 44, 64, 64, 16, 0, 0, torch.float64),
+                                                         (33, 20, 40, 40, 3, 1, 0, torch.float32)])
+def test_mmd2_entry_point(N, M, L1, L2, d, lam, flags, dtype):
+    # sigkernel_mmd2: three Gram computations (the two symmetric ones solve half their pairs), constant upstream
+    # weights generated on the device, one reduction; value and gradients against the oracle's definition
+    from paper_2509_10613_amd import autograd as ska
+    rng = np.random.default_rng(97 + N)
+    X = np.cumsum(rng.normal(0.0, (1.0 / (d * L1)) ** 0.5, (N, L1, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.02, (1.5 / (d * L2)) ** 0.5, (M, L2, d)), axis=1)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    loss, gX, gY = sk.sigkernel_mmd2(dev(X, dtype), dev(Y, dtype), lam, lam, flags)
+    loss_only, none_x, none_y = sk.sigkernel_mmd2(dev(X, dtype), dev(Y, dtype), lam, lam, flags, want_x=False, want_y=False)
+    torch.cuda.synchronize()
+    ref, gXr, gYr = oracle.mmd2(Xr, Yr, lam, lam, flags)
+    tol = TOL[dtype]
+    assert none_x is None and none_y is None
+    # the loss is a difference of means of kernel values of order one: its error is measured against those
+    assert abs(float(loss[0]) - ref) <= tol and abs(float(loss_only[0]) - ref) <= tol
+    gscale = max(np.max(np.abs(gXr)), np.max(np.abs(gYr)))
+    assert np.all(np.isfinite(host(gX))) and np.all(np.isfinite(host(gY)))
+    assert np.max(np.abs(host(gX) - gXr)) <= tol * max(1.0, gscale)
+    assert np.max(np.abs(host(gY) - gYr)) <= tol * max(1.0, gscale)
+    # through autograd, one side only
+    x = dev(X, dtype).requires_grad_(True)
+    (3.0 * ska.sig_mmd2(x, dev(Y, dtype), lam, lam, flags)).backward()
+    torch.cuda.synchronize()
+    assert np.max(np.abs(host(x.grad) - 3.0 * gXr)) <= 3.0 * tol * max(1.0, gscale)
+
+
 # ------------------------------------------------------------------ full-size runs on sampled outputs
 def test_c3_full_size_sampled_entries():
     w, X, Y = workloads.make("c3")

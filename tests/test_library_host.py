@@ -21,7 +21,7 @@ def lib():
 
 def test_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "sigkernel.h")).read()
-    declared = set(re.findall(r"\b(sigkernel_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(sigkernel_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None

@@ -335,3 +335,39 @@ def test_lead_lag_gradients_vs_central_differences():
     fd = (np.sum(W * oracle.gram(Xp, Xp, None, 0, 0, oracle.FLAG_LEAD_LAG)) -
           np.sum(W * oracle.gram(Xm, Xm, None, 0, 0, oracle.FLAG_LEAD_LAG))) / (2 * h)
     assert none is None and abs(fd - gXs[1, 3, 0]) < 1e-7 * max(1.0, abs(fd))
+
+
+# ---------------------------------------------------------------- squared MMD (the training loss of Section 1)
+def test_mmd2_properties_and_gradients():
+    rng = np.random.default_rng(51)
+    X = np.cumsum(rng.normal(0, 0.25, size=(5, 6, 2)), axis=1)
+    Y = np.cumsum(rng.normal(0.05, 0.3, size=(4, 7, 2)), axis=1)
+    loss, gX, gY = oracle.mmd2(X, Y, 1, 1, 1)
+    # a squared distance in the kernel's feature space: positive for different sets, zero for a set and its copy,
+    # symmetric in its arguments; and equal to |mean S(x) - mean S(y)|^2 of truncated signatures (brute force)
+    assert loss > 0
+    assert abs(oracle.mmd2(X, X.copy(), 1, 1, 1, want_grads=False)) < 1e-13
+    assert abs(oracle.mmd2(Y, X, 1, 1, 1, want_grads=False) - loss) < 1e-13
+    Xs = np.cumsum(rng.normal(0, 0.2, size=(4, 5, 2)), axis=1)      # small enough for level 9 to have converged
+    Ys = np.cumsum(rng.normal(0.05, 0.25, size=(3, 6, 2)), axis=1)
+    Sx = [sigbrute.signature(p, 9) for p in Xs]
+    Sy = [sigbrute.signature(p, 9) for p in Ys]
+    mx = [sum(S[k] for S in Sx) / len(Sx) for k in range(10)]
+    my = [sum(S[k] for S in Sy) / len(Sy) for k in range(10)]
+    terms = [float(np.sum((a - b) ** 2)) for a, b in zip(mx, my)]
+    feat = sum(terms)
+    assert terms[9] < 1e-7 * feat                            # the truncation has converged
+    fine = [oracle.mmd2(Xs, Ys, lam, lam, 0, want_grads=False) for lam in (4, 5)]
+    rich = (4.0 * fine[1] - fine[0]) / 3.0                   # Richardson on a second-order scheme
+    assert abs(rich - feat) < 1e-5 * feat
+    # gradients against central differences of the loss
+    h = 1e-6
+    for arr, g, which in ((X, gX, 0), (Y, gY, 1)):
+        for idx in [(0, 0, 0), (2, 3, 1), (arr.shape[0] - 1, arr.shape[1] - 1, 0)]:
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            fp = oracle.mmd2(ap, Y, 1, 1, 1, want_grads=False) if which == 0 else oracle.mmd2(X, ap, 1, 1, 1, want_grads=False)
+            fm = oracle.mmd2(am, Y, 1, 1, 1, want_grads=False) if which == 0 else oracle.mmd2(X, am, 1, 1, 1, want_grads=False)
+            fd = (fp - fm) / (2 * h)
+            assert abs(fd - g[idx]) < 1e-7 * max(1.0, abs(fd)), (which, idx, fd, g[idx])
