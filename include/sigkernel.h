@@ -115,8 +115,8 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
 
 /*
  * Squared maximum mean discrepancy between two sets of paths under the signature kernel, the kind of training
- * loss the paper's abstract and Section 1 name ("training losses for generative models"; the gradients are the
- * exact ones of Section 3.4):
+ * loss for generative models that the paper's abstract and Section 1 give as the motivation for differentiable
+ * signature kernels (the gradients are the exact ones of Section 3.4):
  *   loss = mean_{n,n'} k(X[n], X[n']) - 2 mean_{n,m} k(X[n], Y[m]) + mean_{m,m'} k(Y[m], Y[m'])
  * (the biased estimate, diagonals included), X[N,L1,d], Y[M,L2,d], N, M >= 1.  loss is a device pointer to one
  * element.  If grad_X / grad_Y are not NULL they receive d loss / dX [N,L1,d] and d loss / dY [M,L2,d].

@@ -1,5 +1,5 @@
-"""PyTorch autograd over the C ABI (the paper's library is "fully compatible with PyTorch's automatic
-differentiation", Section 1): thin ``torch.autograd.Function`` wrappers whose forward is ``sigkernel_fwd`` /
+"""PyTorch autograd over the C ABI (Section 1 states that the paper's library takes part in PyTorch's automatic
+differentiation): thin ``torch.autograd.Function`` wrappers whose forward is ``sigkernel_fwd`` /
 ``sigkernel_gram`` and whose backward is ``sigkernel_bwd`` / ``sigkernel_gram`` with the upstream gradient
 (Section 3.4: exact gradients of the discrete scheme).  Argument marshalling only; no arithmetic of the
 method happens here.
