@@ -1,0 +1,58 @@
+/*
+ * signature.h - C ABI for batched truncated signatures on MI355X (gfx950); part of libsigkernel.
+ *
+ * What is computed (paper Section 2): for a piecewise-linear path x of L points in R^d the levels 0..N of its
+ * signature (Definition 2.1), S(x) = exp(z_1) (x) exp(z_2) (x) ... (x) exp(z_{L-1}) with z_l = x[l+1] - x[l]
+ * (Proposition 2.1 for a segment, Chen's identity, Proposition 2.2, for the concatenation), evaluated by Horner's
+ * scheme of Section 2.3 (Algorithm "Horner's Algorithm for Truncated Signatures"): per segment and level k,
+ *     A_k <- (B_k + A_{k-1}) (x) z + A_k,   B_k = ((z/k + A_1) (x) z/(k-1) + A_2) (x) ... (x) z/2.
+ *
+ * Layout of a result: levels 0..N one after the other (level 0 is the number 1), level k in row-major order of
+ * its word (i_1, ..., i_k), i_k fastest: signature_length(...) = (D^(N+1) - 1)/(D - 1) entries per path, D the number
+ * of channels after the transformations of `flags` (d, 2d, d + 1 or 2d + 1).
+ *
+ * Conventions are those of sigkernel.h: device pointers to dense row-major arrays owned by the caller, element
+ * type `dt` for every array of the call (the arithmetic is in double for both), caller-owned 256-byte aligned
+ * workspace of at least signature_workspace_bytes(...) bytes, calls only enqueue work on `stream`, return value SK_OK
+ * or a negative SK_ERR_* code with a message in sigkernel_last_error(), nothing enqueued on error.  B = 0 is a
+ * successful no-op; a path of one point has the signature (1, 0, ..., 0).
+ * flags: SK_FLAG_TIME_AUG and SK_FLAG_LEAD_LAG as in sigkernel.h (Section 4, applied on the fly: the transformed
+ * paths are never formed, only their increments), and the diagnostic SK_SIG_DEPTH(m) below; other bits are an error.
+ * Limits: N >= 1; at most 2^40 entries per path and 2^46 per call; a lane carries the entries at up to 8 prefix
+ * letters, which admits every N <= 9 (N <= 14 for two channels); beyond that SK_ERR_SHAPE.
+ */
+#ifndef SIGKERNEL_SIGNATURE_H
+#define SIGKERNEL_SIGNATURE_H
+
+#include "sigkernel.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Diagnostic, for signature_fwd / signature_workspace_bytes / signature_describe only: a lane keeps the entries of a
+ * subtree of words of depth m in registers; SK_SIG_DEPTH(m), m = 0..5, or-ed into `flags` forces that depth instead
+ * of the library's own choice (SK_ERR_SHAPE if no kernel with that depth exists for the shape).  Results do not
+ * depend on it beyond rounding order. */
+#define SK_SIG_DEPTH(m) (((m) + 1) << 8)
+#define SK_SIG_DEPTH_MASK 0xf00
+
+/* Entries per path of the result for paths of d channels, level 0 included; 0 for invalid arguments or when the
+ * count does not fit.  Pure host arithmetic. */
+int64_t signature_length(int64_t d, int N, int flags);
+
+/* Bytes of device scratch for signature_fwd with the same arguments (increments of the transformed paths, and a
+ * double copy of the result for float callers).  Pure host arithmetic; 0 for invalid arguments. */
+size_t signature_workspace_bytes(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt);
+
+/* x[B,L,d] -> out[B, signature_length(d, N, flags)]  (Section 2.3). */
+int signature_fwd(const void* x, void* out, int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, void* ws,
+                  size_t ws_bytes, void* stream);
+
+/* Diagnostics (no passage of the paper): human-readable launch plan for these arguments, as sigkernel_describe. */
+int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, char* out, size_t out_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIGKERNEL_SIGNATURE_H */

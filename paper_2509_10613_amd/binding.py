@@ -18,9 +18,16 @@ SK_FLAG_SHORT_WAITS = 4
 SK_FLAG_LEAD_LAG = 8
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
+
+def SK_SIG_DEPTH(m):
+    """Diagnostic flag of signature_fwd: forces the depth of the register-resident subtree of a lane."""
+    return (m + 1) << 8
+
+
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",
            "sigkernel_mmd2", "sigkernel_mmd2_workspace_bytes",
-           "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version"]
+           "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version",
+           "signature_length", "signature_workspace_bytes", "signature_fwd", "signature_describe"]
 
 _lib = None
 
@@ -60,6 +67,14 @@ def load():
     lib.sigkernel_event_timing_read.restype = ci
     lib.sigkernel_event_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(ci), C.POINTER(C.c_double),
                                                 C.POINTER(ci)]
+    lib.signature_length.restype = i64
+    lib.signature_length.argtypes = [i64, ci, ci]
+    lib.signature_workspace_bytes.restype = C.c_size_t
+    lib.signature_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci]
+    lib.signature_fwd.restype = ci
+    lib.signature_fwd.argtypes = [vp, vp, i64, i64, i64, ci, ci, ci, vp, C.c_size_t, vp]
+    lib.signature_describe.restype = ci
+    lib.signature_describe.argtypes = [i64, i64, i64, ci, ci, ci, C.c_char_p, C.c_size_t]
     lib.sigkernel_last_error.restype = C.c_char_p
     lib.sigkernel_version.restype = C.c_char_p
     _lib = lib
@@ -215,3 +230,33 @@ def sigkernel_mmd2(X, Y, lam1=0, lam2=0, flags=0, want_x=True, want_y=True, ws=N
     _check(load().sigkernel_mmd2(_ptr(X), _ptr(Y), _ptr(loss), _ptr(gX), _ptr(gY), N, M, L1, L2, d, lam1, lam2, flags,
                                  dt, _ptr(ws), ws.numel(), _stream()))
     return loss, gX, gY
+
+
+# ---------------------------------------------------------------- truncated signatures (include/signature.h)
+def signature_length(d, N, flags=0):
+    return int(load().signature_length(d, N, flags))
+
+
+def signature_workspace_bytes(B, L, d, N, flags, dt):
+    return int(load().signature_workspace_bytes(B, L, d, N, flags, dt))
+
+
+def signature_describe(B, L, d, N, flags, dt):
+    buf = C.create_string_buffer(512)
+    _check(load().signature_describe(B, L, d, N, flags, dt, buf, len(buf)))
+    return buf.value.decode()
+
+
+def signature_fwd(x, N, flags=0, ws=None, out=None):
+    """x[B,L,d] (device) -> out[B, signature_length(d, N, flags)]: truncated signatures, levels 0..N flattened."""
+    _dev(x, "x")
+    B, L, d = x.shape
+    dt = _dt(x)
+    n = signature_length(d, N, flags)
+    if out is None:
+        out = torch.empty((B, n), dtype=x.dtype, device=x.device)
+    need = signature_workspace_bytes(B, L, d, N, flags, dt)
+    if ws is None:
+        ws = workspace(need, x.device)
+    _check(load().signature_fwd(_ptr(x), _ptr(out), B, L, d, N, flags, dt, _ptr(ws), ws.numel(), _stream()))
+    return out

@@ -8,8 +8,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsigkernel.so")
-SOURCES = ["sk_api.hip", "sk_kernels.hip", "sk_lockstep.hip", "sk_solo.hip", "sk_tile.hip", "sk_band.hip"]
-HEADERS = ["sk_plan.h", "sk_kernels.h", "sk_dev.h", "sk_lane.h"]
+SOURCES = ["sk_api.hip", "sk_kernels.hip", "sk_lockstep.hip", "sk_solo.hip", "sk_tile.hip", "sk_band.hip", "sg_horner.hip"]
+HEADERS = ["sk_plan.h", "sk_kernels.h", "sk_dev.h", "sk_lane.h", "sg_plan.h", "sg_kernels.h"]
+PUBLIC = ["sigkernel.h", "signature.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -20,13 +21,13 @@ def _stale(target, deps):
 
 
 def build(force: bool = False, verbose: bool = False, extra_flags=()) -> str:
-    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS] + [os.path.join(ROOT, "include", "sigkernel.h")]
+    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS] + [os.path.join(ROOT, "include", h) for h in PUBLIC]
     if not force and not _stale(LIB, deps):
         return LIB
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
 
-    hdrs = [os.path.join(CSRC, f) for f in HEADERS] + [os.path.join(ROOT, "include", "sigkernel.h")]
+    hdrs = [os.path.join(CSRC, f) for f in HEADERS] + [os.path.join(ROOT, "include", h) for h in PUBLIC]
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
@@ -41,7 +42,7 @@ def build(force: bool = False, verbose: bool = False, extra_flags=()) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -1,0 +1,336 @@
+// Batched truncated signatures by Horner's scheme (paper Section 2.3) for gfx950.
+//
+// One step of the scheme for the increment z of a segment, read word by word (v a word, c a letter, |v| its length):
+//     G_k[empty] = 1,   G_k[v c] = G_k[v] z[c] / (k - |v|) + A_{|v|+1}[v c]   for |v| + 1 < k,
+//     A_k[w c] += G_k[w] z[c]                                                  for |w| = k - 1,
+// levels k = N, ..., 1 in that order so that every right-hand side still holds the values before the step
+// (G_k[w] is B_k[w] + A_{k-1}[w] of Section 2.3).  Starting from A = (1, 0, 0, ...), the first step gives the tensor
+// exponential of the first increment (Proposition 2.1), so no separate initialisation is needed.
+//
+// A value at a word depends only on values at its prefixes.  A lane therefore owns a prefix u of Q letters, S
+// consecutive letters after it, and all continuations by up to M more letters, in registers for the whole path, plus
+// its own copies of the Q entries at the prefixes of u.  No lane talks to another one.  All lanes of a wave work on
+// the same path: the D increments of a step are wave-uniform and come in by scalar loads into scalar registers, the
+// few that a lane selects by its own letters come in by ordinary loads; both are fetched one step ahead.
+#include <hip/hip_runtime.h>
+
+#include "sg_kernels.h"
+
+namespace sg {
+
+namespace {
+
+typedef const double __attribute__((address_space(4))) * uniform_ptr;   // constant address space: scalar loads
+
+__host__ __device__ constexpr int ipow(int D, int m)
+{
+    int p = 1;
+    for (int i = 0; i < m; ++i) p *= D;
+    return p;
+}
+
+// The words a lane owns, level by level: node e of level m has the children e * D + c at level m + 1; level m holds
+// S * D^m nodes and starts at off(m).
+template <int D, int M, int S>
+struct Tree {
+    static constexpr int cnt(int m) { return S * ipow(D, m); }
+    static constexpr int off(int m)
+    {
+        int o = 0;
+        for (int i = 0; i < m; ++i) o += cnt(i);
+        return o;
+    }
+    static constexpr int TOT = off(M + 1);
+    static constexpr int GT = M > 0 ? off(M) : 1;
+
+    // levels m .. MT of the update of the owned level MT (the word of node e at level MT has length k - 1 + 1 = k)
+    template <int MT, int m>
+    static __device__ __forceinline__ void descend(double (&A)[TOT], double (&G)[GT], const double (&zz)[D])
+    {
+        constexpr int np = cnt(m - 1);
+#pragma unroll
+        for (int e = 0; e < np; ++e) {
+            // parent word has |v| = Q + m letters and k = Q + 1 + MT, so k - |v| = MT + 1 - m
+            const double gs = (m < MT) ? G[off(m - 1) + e] * (1.0 / (double)(MT + 1 - m)) : G[off(m - 1) + e];
+#pragma unroll
+            for (int c = 0; c < D; ++c) {
+                const int i = off(m) + e * D + c;
+                if (m < MT) G[i] = __builtin_fma(gs, zz[c], A[i]);
+                else A[i] = __builtin_fma(gs, zz[c], A[i]);
+            }
+        }
+        if constexpr (m < MT) descend<MT, m + 1>(A, G, zz);
+    }
+
+    // g = G_k[u] for k = Q + 1 + MT; zc = the increments at the lane's S letters
+    template <int MT>
+    static __device__ __forceinline__ void level(double (&A)[TOT], double g, const double (&zc)[S], const double (&zz)[D])
+    {
+        if constexpr (MT == 0) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) A[s] = __builtin_fma(g, zc[s], A[s]);
+        } else {
+            double G[GT];
+            const double g0 = g * (1.0 / (double)(MT + 1));
+#pragma unroll
+            for (int s = 0; s < S; ++s) G[s] = __builtin_fma(g0, zc[s], A[s]);
+            descend<MT, 1>(A, G, zz);
+        }
+    }
+};
+
+// The carried prefix has Q letters.  QC is Q itself when Q <= kQExact (every loop below then has constant bounds and
+// no test), else kQMax with a test of r against Q in every iteration.
+template <int QC>
+__device__ __forceinline__ bool has(int r, int Q)
+{
+    return QC <= kQExact ? true : r < Q;
+}
+
+// G_k[u] for the level that lies E letters beyond the prefix (k = Q + E): the chain over the prefixes of u.
+// preR[r] / zuR[r] belong to the prefix of length Q - r (reversed so that every index below is a constant).
+template <int E, int QC, int QA>
+__device__ __forceinline__ double prefix_chain(int Q, const double (&preR)[QA], const double (&zuR)[QA])
+{
+    double g = 1.0;
+#pragma unroll
+    for (int r = QC - 1; r >= 0; --r)
+        if (has<QC>(r, Q)) g = __builtin_fma(g, zuR[r] * (1.0 / (double)(r + 1 + E)), preR[r]);   // k - |v| = r + 1 + E
+    return g;
+}
+
+template <int MT, int D, int M, int S, int QC, int TOT, int QA>
+__device__ __forceinline__ void owned_levels(double (&A)[TOT], int Q, const double (&preR)[QA],
+                                             const double (&zuR)[QA], const double (&zc)[S], const double (&zz)[D])
+{
+    Tree<D, M, S>::template level<MT>(A, prefix_chain<MT + 1, QC, QA>(Q, preR, zuR), zc, zz);
+    if constexpr (MT > 0) owned_levels<MT - 1, D, M, S, QC, TOT, QA>(A, Q, preR, zuR, zc, zz);
+}
+
+// the carried entries at the prefixes of u: word length Q - r0, longest first
+template <int QC, int QA>
+__device__ __forceinline__ void prefix_levels(int Q, double (&preR)[QA], const double (&zuR)[QA])
+{
+#pragma unroll
+    for (int r0 = 0; r0 < QC; ++r0) {
+        if (has<QC>(r0, Q)) {
+            double g = 1.0;
+#pragma unroll
+            for (int r = QC - 1; r > r0; --r)
+                if (has<QC>(r, Q)) g = __builtin_fma(g, zuR[r] * (1.0 / (double)(r - r0 + 1)), preR[r]);
+            preR[r0] = __builtin_fma(g, zuR[r0], preR[r0]);
+        }
+    }
+}
+
+// The owned entries of level Q + 1 + m go to the words u (blk S + s) v: `first` is the number of the word u (blk S) in
+// base D, at[m] the start of that level in the flattened signature.
+template <int m, int D, int M, int S, int TOT>
+__device__ __forceinline__ void store_owned(const double (&A)[TOT], double* out, const long (&at)[M + 1], int Dn,
+                                            long first, int c0)
+{
+    constexpr int pm = ipow(D, m);
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        if (c0 + s < Dn) {
+            double* o = out + at[m] + (first + s) * pm;
+#pragma unroll
+            for (int v = 0; v < pm; ++v) o[v] = A[Tree<D, M, S>::off(m) + s * pm + v];
+        }
+    }
+    if constexpr (m < M) store_owned<m + 1, D, M, S, TOT>(A, out, at, Dn, first, c0);
+}
+
+// One wave's share of one path, all steps.  DT > 0: D = DT channels, increments of a step in scalar registers.
+// DT == 0: any number of channels, M = 0, S = 1 (a lane owns one word of the top level).
+template <int DT, int M, int S, int QC>
+__device__ __forceinline__ void run(const Args& a)
+{
+    constexpr int DD = DT > 0 ? DT : 1;
+    constexpr int QA = QC > 0 ? QC : 1;
+    using T = Tree<DD, M, S>;
+    const int D = DT > 0 ? DT : a.D;
+    const int Q = QC <= kQExact ? QC : a.Q;
+    const int lane = threadIdx.x & (kWave - 1);
+    const long wt = (long)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    if (wt >= a.B * a.WP) return;
+    const long b = wt / a.WP;
+    long ti = (wt - b * a.WP) * kWave + lane;
+    const bool valid = ti < a.LP;
+    if (!valid) ti = 0;
+    const int blk = (int)(ti % a.NB);
+    const long rest = ti / a.NB;      // the prefix u as a number in base D, first letter most significant
+    int uR[QA];
+    {
+        long t = rest;
+#pragma unroll
+        for (int r = 0; r < QA; ++r) {
+            uR[r] = (r < QC && has<QC>(r, Q)) ? (int)(t % D) : 0;
+            t /= D;
+        }
+    }
+    int cs[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) cs[s] = min(blk * S + s, D - 1);
+
+    double A[T::TOT];
+#pragma unroll
+    for (int i = 0; i < T::TOT; ++i) A[i] = 0.0;
+    double preR[QA];
+#pragma unroll
+    for (int r = 0; r < QA; ++r) preR[r] = 0.0;
+
+    const double* zrow = a.dz + b * a.n * a.Dpad;
+    double zz[DD], zc[S], zuR[QA];
+    double zzn[DD], zcn[S], zuRn[QA];
+    auto fetch = [&](long step, double (&z_)[DD], double (&zc_)[S], double (&zu_)[QA]) {
+        const double* zp = zrow + step * a.Dpad;
+        if constexpr (DT > 0 && M > 0) {
+            uniform_ptr zs = (uniform_ptr)(zp);
+#pragma unroll
+            for (int c = 0; c < DD; ++c) z_[c] = zs[c];
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) zc_[s] = zp[cs[s]];
+#pragma unroll
+        for (int r = 0; r < QA; ++r) zu_[r] = (r < QC && has<QC>(r, Q)) ? zp[uR[r]] : 0.0;
+    };
+#pragma unroll
+    for (int c = 0; c < DD; ++c) zz[c] = zzn[c] = 0.0;
+    if (a.n > 0) fetch(0, zz, zc, zuR);
+    for (long step = 0; step < a.n; ++step) {
+        fetch(step + 1 < a.n ? step + 1 : step, zzn, zcn, zuRn);
+        owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, zuR, zc, zz);
+        prefix_levels<QC, QA>(Q, preR, zuR);
+#pragma unroll
+        for (int c = 0; c < DD; ++c) zz[c] = zzn[c];
+#pragma unroll
+        for (int s = 0; s < S; ++s) zc[s] = zcn[s];
+#pragma unroll
+        for (int r = 0; r < QA; ++r) zuR[r] = zuRn[r];
+    }
+
+    if (!valid) return;
+    double* out = a.out + b * a.sig_len;
+    // start of level k in the flattened signature: 1 + D + ... + D^(k-1)
+    auto lvl = [&](int k) {
+        long o = 0, p = 1;
+        for (int i = 0; i < k; ++i) {
+            o += p;
+            p *= D;
+        }
+        return o;
+    };
+    if (ti == 0) out[0] = 1.0;
+    // carried prefix entries: written by the lane whose remaining letters are all zero
+    {
+        long pw = 1;
+#pragma unroll
+        for (int r = 0; r < QC; ++r) {
+            if (has<QC>(r, Q) && blk == 0 && rest % pw == 0) out[lvl(Q - r) + rest / pw] = preR[r];
+            pw *= D;
+        }
+    }
+    long at[M + 1];
+#pragma unroll
+    for (int m = 0; m <= M; ++m) at[m] = lvl(Q + 1 + m);
+    store_owned<0, DD, M, S, T::TOT>(A, out, at, D, rest * D + blk * S, blk * S);
+}
+
+template <int DT, int M, int S, int QC>
+__global__ __launch_bounds__(kWave * kWavesPerWG) void horner_kernel(const Args a)
+{
+    run<DT, M, S, QC>(a);
+}
+
+// Increments of the transformed paths (Section 4), one row of Dpad doubles per segment: channels of the path (after
+// the lead-lag transform: lead half, then lag half; a segment of the transformed path moves one half only, the lead
+// first), then the time channel 1/n if asked for, then zero padding.
+template <typename TI>
+__global__ __launch_bounds__(256) void increments_kernel(const TI* __restrict__ x, double* __restrict__ dz, long B, long L,
+                                                         int d, int D, int Dpad, long n, int time_aug, int lead_lag)
+{
+    const long total = B * n * Dpad;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int c = (int)(i % Dpad);
+        const long bs = i / Dpad;
+        const long s = bs % n;
+        const long b = bs / n;
+        double v = 0.0;
+        if (time_aug && c == D - 1) {
+            v = 1.0 / (double)n;
+        } else if (c < D) {
+            long seg = s;
+            int ch = c;
+            bool moves = true;
+            if (lead_lag) {
+                seg = s >> 1;
+                const bool lag_half = c >= d;
+                ch = lag_half ? c - d : c;
+                moves = ((s & 1) != 0) == lag_half;
+            }
+            if (moves) {
+                const TI* xp = x + (b * L + seg) * d + ch;
+                v = (double)xp[d] - (double)xp[0];
+            }
+        }
+        dz[i] = v;
+    }
+}
+
+template <int DT, int M, int S, int QC>
+hipError_t launch_one(const Args& a, long grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((horner_kernel<DT, M, S, QC>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), 0, st, a);
+    return hipGetLastError();
+}
+
+// prefix lengths up to kQExact have kernels of their own; longer ones share the kernel that tests against Q, which
+// exists for the channel counts that can reach them (kLongPrefixMaxD)
+template <int DT, int M, int S>
+hipError_t launch_variant(const Args& a, long grid, hipStream_t st)
+{
+    switch (a.Q) {
+    case 0: return launch_one<DT, M, S, 0>(a, grid, st);
+    case 1: return launch_one<DT, M, S, 1>(a, grid, st);
+    case 2: return launch_one<DT, M, S, 2>(a, grid, st);
+    case 3: return launch_one<DT, M, S, 3>(a, grid, st);
+    case 4: return launch_one<DT, M, S, 4>(a, grid, st);
+    default:
+        if constexpr (DT <= kLongPrefixMaxD) return launch_one<DT, M, S, kQMax>(a, grid, st);
+        else return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStream_t st)
+{
+    if (grid <= 0) return hipSuccess;
+    if (a.Q < 0 || a.Q > kQMax || a.LP <= 0 || a.WP * kWave < a.LP || a.NB * (long)S < (DT ? DT : a.D))
+        return hipErrorInvalidValue;
+    if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, st) : hipErrorInvalidValue;
+#define SG_CASE(D_, M_, S_) \
+    if (DT == D_ && M == M_ && S == S_) return launch_variant<D_, M_, S_>(a, grid, st);
+    SG_VARIANTS(SG_CASE)
+#undef SG_CASE
+    return hipErrorInvalidValue;
+}
+
+template <typename TI>
+hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, int time_aug,
+                             int lead_lag, hipStream_t st)
+{
+    const long total = B * n * Dpad;
+    if (total <= 0) return hipSuccess;
+    long grid = (total + 255) / 256;
+    if (grid > 65536) grid = 65536;
+    hipLaunchKernelGGL((increments_kernel<TI>), dim3((unsigned)grid), dim3(256), 0, st, x, dz, B, L, d, D, Dpad, n,
+                       time_aug, lead_lag);
+    return hipGetLastError();
+}
+
+template hipError_t launch_increments<float>(const float*, double*, long, long, int, int, int, long, int, int, hipStream_t);
+template hipError_t launch_increments<double>(const double*, double*, long, long, int, int, int, long, int, int, hipStream_t);
+
+}  // namespace sg

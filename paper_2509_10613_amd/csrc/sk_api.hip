@@ -10,6 +10,8 @@
 #include <vector>
 
 #include "sigkernel.h"
+#include "signature.h"
+#include "sg_kernels.h"
 #include "sk_kernels.h"
 
 namespace {
@@ -494,6 +496,116 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
                   mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
                   (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
                   fused ? 1 : 0, p.total);
+    return SK_OK;
+}
+
+// ---------------------------------------------------------------- truncated signatures (signature.h)
+}  // extern "C"
+
+namespace {
+
+int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::Plan* plan)
+{
+    if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
+    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG | SK_SIG_DEPTH_MASK)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
+    const int force_M = ((flags & SK_SIG_DEPTH_MASK) >> 8) - 1;
+    if (B < 0) return fail(SK_ERR_SHAPE, "negative batch size");
+    if (L < 1 || d < 1 || N < 1) return fail(SK_ERR_SHAPE, "need L, d, N >= 1 (got %lld, %lld, %d)", (long long)L,
+                                             (long long)d, N);
+    if (L > ((int64_t)1 << 29) || d > 32768 || N > 64 || B > ((int64_t)1 << 40))
+        return fail(SK_ERR_SHAPE, "L above 2^29, d above 32768, N above 64 or B above 2^40");
+    *plan = sg::make_plan(B, L, d, N, (flags & SK_FLAG_TIME_AUG) != 0, (flags & SK_FLAG_LEAD_LAG) != 0, dt == SK_F64,
+                          force_M);
+    if (!plan->valid) return fail(SK_ERR_SHAPE, "signature_fwd: %s", plan->why);
+    return SK_OK;
+}
+
+template <typename T>
+int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* ws, hipStream_t st)
+{
+    constexpr bool kIsDouble = sizeof(T) == 8;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    hipError_t e;
+#define SK_CHECK(call)                                                                         \
+    do {                                                                                       \
+        e = (call);                                                                            \
+        if (e != hipSuccess) return fail(SK_ERR_HIP, "%s: %s", #call, hipGetErrorString(e));   \
+    } while (0)
+    double* dz = reinterpret_cast<double*>(base + p.off_dz);
+    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n,
+                                      (flags & SK_FLAG_TIME_AUG) ? 1 : 0, (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
+    sg::Args a;
+    a.dz = dz;
+    a.out = kIsDouble ? static_cast<double*>(out) : reinterpret_cast<double*>(base + p.off_out);
+    a.B = p.B; a.n = p.n; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
+    a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len;
+    bool timed = false;
+    TimedLaunch tl{};
+    {
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        timed = g_timing_on;
+    }
+    if (timed) {
+        SK_CHECK(hipEventCreate(&tl.start));
+        SK_CHECK(hipEventCreate(&tl.stop));
+        tl.backward = 0;
+        SK_CHECK(hipEventRecord(tl.start, st));
+    }
+    SK_CHECK(sg::launch_horner(p.DT, p.M, p.S, a, p.grid, st));
+    if (timed) {
+        SK_CHECK(hipEventRecord(tl.stop, st));
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        g_timed.push_back(tl);
+    }
+    if (!kIsDouble) SK_CHECK((sk::launch_convert<double, T>(a.out, static_cast<T*>(out), p.B * p.sig_len, st)));
+#undef SK_CHECK
+    return SK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t signature_length(int64_t d, int N, int flags)
+{
+    if (d < 1 || d > 32768 || N < 1 || (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG | SK_SIG_DEPTH_MASK))) return 0;
+    const int64_t D = ((flags & SK_FLAG_LEAD_LAG) ? 2 * d : d) + ((flags & SK_FLAG_TIME_AUG) ? 1 : 0);
+    return sg::sig_length(D, N);
+}
+
+size_t signature_workspace_bytes(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt)
+{
+    sg::Plan p;
+    if (sig_validate(B, L, d, N, flags, (int)dt, &p) != SK_OK || B == 0) return 0;
+    return p.total;
+}
+
+int signature_fwd(const void* x, void* out, int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, void* ws,
+                  size_t ws_bytes, void* stream)
+{
+    sg::Plan p;
+    int rc = sig_validate(B, L, d, N, flags, (int)dt, &p);
+    if (rc != SK_OK) return rc;
+    if (B == 0) return SK_OK;
+    if (!x || !out) return fail(SK_ERR_NULL, "x or out is NULL");
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < p.total)
+        return fail(SK_ERR_WORKSPACE, "workspace is NULL, misaligned or smaller than %zu bytes", p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dt == SK_F64 ? run_signature<double>(p, x, out, flags, ws, st) : run_signature<float>(p, x, out, flags, ws, st);
+}
+
+int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, char* out, size_t out_bytes)
+{
+    if (!out || out_bytes == 0) return fail(SK_ERR_NULL, "out is NULL or empty");
+    out[0] = 0;
+    sg::Plan p;
+    int rc = sig_validate(B, L, d, N, flags, (int)dt, &p);
+    if (rc != SK_OK) return rc;
+    std::snprintf(out, out_bytes,
+                  "kernel=horner_kernel<%d, %d, %d, %d> channels=%d prefix_letters=%d letter_blocks=%d lanes_per_path=%lld "
+                  "waves_per_path=%lld grid=%lld threads=%d entries_per_path=%lld workspace_bytes=%zu",
+                  p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.D, p.Q, p.NB, (long long)p.LP, (long long)p.WP,
+                  (long long)p.grid, sg::kWave * sg::kWavesPerWG, (long long)p.sig_len, B == 0 ? (size_t)0 : p.total);
     return SK_OK;
 }
 

@@ -84,3 +84,20 @@ def make(name: str, n_x: int = None, n_y: int = None, L: int = None):
 def upstream_weights(seed: int, shape) -> np.ndarray:
     """Seeded N(0,1) upstream gradients dF/dk (or dF/dK) for backward tests."""
     return np.random.default_rng(seed).normal(0.0, 1.0, size=shape)
+
+
+# Truncated signatures (paper Table 1 gives shapes (B, L, d, N) only, no dataset): Brownian-like paths with
+# N(0, 1/L) increments per channel, so that the entries of level k are of order 1/sqrt(k!).
+SIGNATURE_WORKLOADS = {
+    "s1": (128, 256, 4, 6, 6001),
+    "s2": (128, 512, 8, 5, 6002),
+    "s3": (128, 1024, 16, 4, 6003),
+}
+
+
+def make_signature(name: str, B: int = None, L: int = None):
+    """Returns ((B, L, d, N), X[B,L,d]) in float64; B / L override the batch size and the length."""
+    B0, L0, d, N, seed = SIGNATURE_WORKLOADS[name]
+    B = B or B0
+    L = L or L0
+    return (B, L, d, N), brownian_paths(seed, B, L, d, 1.0 / L0)

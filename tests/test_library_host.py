@@ -20,8 +20,8 @@ def lib():
 
 
 def test_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "sigkernel.h")).read()
-    declared = set(re.findall(r"\b(sigkernel_[a-z0-9_]+)\s*\(", header))
+    header = open(os.path.join(ROOT, "include", "sigkernel.h")).read() + open(os.path.join(ROOT, "include", "signature.h")).read()
+    declared = set(re.findall(r"\b((?:sigkernel|signature)_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -146,3 +146,68 @@ def test_launch_plan_stays_inside_the_hardware_limits(lib):
     assert len(buf.value) == 7                                  # truncated, still NUL-terminated
     assert lib.sigkernel_describe(99, 4, 0, 8, 8, 2, 0, 0, 0, f64, buf, 8) == -2
     assert lib.sigkernel_describe(binding.SK_OP_FWD, 4, 0, 8, 8, 2, 0, 0, 0, f64, None, 8) == -1
+
+
+# ---------------------------------------------------------------- truncated signatures (include/signature.h)
+def test_signature_host_side(lib):
+    one = C.c_void_p(256)
+    assert lib.signature_length(4, 6, 0) == 5461 and lib.signature_length(16, 4, 0) == 69905
+    assert lib.signature_length(2, 3, binding.SK_FLAG_TIME_AUG | binding.SK_FLAG_LEAD_LAG) == 1 + 5 + 25 + 125
+    assert lib.signature_length(1, 7, 0) == 8
+    assert lib.signature_length(16, 12, 0) == 0 and lib.signature_length(0, 3, 0) == 0 and lib.signature_length(3, 0, 0) == 0
+    f = lib.signature_fwd
+    assert f(one, one, 4, 8, 3, 3, 0, 7, one, 1 << 20, None) == -4       # dtype
+    assert f(one, one, 4, 8, 3, 3, 2, 1, one, 1 << 20, None) == -4       # a flag of the kernel entry points
+    assert f(one, one, 4, 8, 3, 0, 0, 1, one, 1 << 20, None) == -2       # N < 1
+    assert f(one, one, 4, 0, 3, 3, 0, 1, one, 1 << 20, None) == -2       # L < 1
+    assert f(one, one, -1, 8, 3, 3, 0, 1, one, 1 << 20, None) == -2
+    assert f(one, one, 4, 8, 16, 12, 0, 1, one, 1 << 20, None) == -2     # more than 2^40 entries per path
+    assert b"2^40" in lib.sigkernel_last_error()
+    assert f(None, one, 4, 8, 3, 3, 0, 1, one, 1 << 20, None) == -1
+    assert f(one, one, 4, 8, 3, 3, 0, 1, one, 16, None) == -5
+    assert f(one, one, 4, 8, 3, 3, 0, 1, C.c_void_p(264), 1 << 20, None) == -5
+    assert f(None, None, 0, 8, 3, 3, 0, 1, None, 0, None) == 0           # empty batch
+    # workspace: increments of the (transformed) paths in double, rows padded to an even count, plus the double
+    # staging of the result for float callers
+    assert binding.signature_workspace_bytes(128, 1024, 16, 4, 0, binding.SK_F64) >= 128 * 1023 * 16 * 8
+    assert binding.signature_workspace_bytes(128, 1024, 16, 4, 0, binding.SK_F64) < 128 * 1023 * 16 * 8 + 512
+    w32 = binding.signature_workspace_bytes(10, 20, 3, 3, binding.SK_FLAG_LEAD_LAG, binding.SK_F32)
+    assert w32 >= 10 * 38 * 6 * 8 + 10 * (1 + 6 + 36 + 216) * 8
+    assert binding.signature_workspace_bytes(0, 20, 3, 3, 0, binding.SK_F64) == 0
+
+
+def test_signature_launch_plans(lib):
+    def plan(B, L, d, N, flags=0):
+        text = binding.signature_describe(B, L, d, N, flags, binding.SK_F64)
+        kern = re.search(r"kernel=(horner_kernel<[^>]*>)", text).group(1)
+        vals = {k: int(v) for k, v in re.findall(r"(\w+)=(\d+)", text)}
+        return kern, vals
+    # the three shapes of Table 1: deepest subtree that still gives every SIMD a wave
+    kern, v = plan(128, 256, 4, 6)
+    assert kern == "horner_kernel<4, 2, 1, 3>" and v["lanes_per_path"] == 256 and v["grid"] == 128
+    kern, v = plan(128, 512, 8, 5)
+    assert kern == "horner_kernel<8, 2, 1, 2>" and v["lanes_per_path"] == 512 and v["grid"] == 256
+    kern, v = plan(128, 1024, 16, 4)
+    assert kern == "horner_kernel<16, 1, 4, 2>" and v["lanes_per_path"] == 1024 and v["grid"] == 512
+    assert v["entries_per_path"] == 69905
+    # a large batch prefers the deepest subtree; channel counts without a kernel of their own, and one channel, take
+    # the run-time kernel; the transformations change the channel count the plan sees
+    assert plan(100000, 50, 3, 8)[0] == "horner_kernel<3, 3, 1, 4>"
+    assert plan(4, 50, 20, 3)[0] == "horner_kernel<0, 0, 1, 2>"
+    assert plan(4, 50, 1, 5)[0] == "horner_kernel<0, 0, 1, 4>"
+    assert plan(4, 50, 2, 3, binding.SK_FLAG_TIME_AUG | binding.SK_FLAG_LEAD_LAG)[1]["channels"] == 5
+    # lanes of a wave never span two paths, every lane's words fit the level count, the grid covers all waves
+    for (B, L, d, N) in [(3, 9, 5, 4), (7, 5, 11, 3), (2, 4, 17, 4), (1, 3, 2, 14), (9, 9, 9, 9)]:
+        kern, v = plan(B, L, d, N)
+        D, M, S, QC = (int(t) for t in re.search(r"<(\d+), (\d+), (\d+), (\d+)>", kern).groups())
+        Q = v["prefix_letters"]
+        assert Q == N - M - 1 and (QC == Q or (QC == 8 and 4 < Q <= 8))
+        assert v["letter_blocks"] * S >= d and (v["letter_blocks"] - 1) * S < d
+        assert v["lanes_per_path"] == d ** Q * v["letter_blocks"]
+        assert v["waves_per_path"] * 64 >= v["lanes_per_path"] > (v["waves_per_path"] - 1) * 64
+        assert v["grid"] * 4 >= B * v["waves_per_path"] > (v["grid"] - 1) * 4
+    # levels beyond what a lane can carry are refused
+    with pytest.raises(binding.SigKernelError):
+        binding.signature_describe(1, 3, 3, 13, 0, binding.SK_F64)
+    with pytest.raises(binding.SigKernelError):
+        binding.signature_describe(1, 3, 16, 4, binding.SK_SIG_DEPTH(2), binding.SK_F64)
