@@ -38,12 +38,83 @@ def algorithmic_flops_per_cell(d, time_aug, lam, backward):
     return 15.0 + (10.0 + 2.0 * de + 4.0 * d) / per_coarse
 
 
+def bench_signature(args):
+    """Side measurement (not the headline): batched truncated signatures by Horner's scheme (Section 2.3) on the
+    shapes (B, L, d, N) of the paper's Table 1.  A step is one signature_fwd call.  Algorithmic work per path and
+    segment: for every level k, one multiply-add per entry of the nested products of lengths 1..k, that is
+    sum_{k=1..N} sum_{j=1..k} d^j multiply-adds (the divisions by k - j of the scheme are not counted)."""
+    import numpy as np
+    import torch
+    from paper_2509_10613_amd import binding as sk
+    from paper_2509_10613_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    (B, L, d, N), X = workloads.make_signature(args.workload)
+    flags = sk.SK_FLAG_LEAD_LAG if args.lead_lag else 0
+    D, n = (2 * d, 2 * (L - 1)) if args.lead_lag else (d, L - 1)
+    x = torch.tensor(X, device=dev)
+    entries = sk.signature_length(d, N, flags)
+    out = torch.empty((B, entries), dtype=torch.float64, device=dev)
+    ws = torch.empty(max(256, sk.signature_workspace_bytes(B, L, d, N, flags, sk.SK_F64)), dtype=torch.uint8, device=dev)
+
+    def step():
+        sk.signature_fwd(x, N, flags, ws=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sk.sigkernel_event_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sk.sigkernel_event_timing(False)
+    k_ms, nk, _, _ = sk.sigkernel_event_timing_read()
+    sec = (t1 - t0) / args.steps
+    fma = sum(sum(D ** j for j in range(1, k + 1)) for k in range(1, N + 1))
+    flops = 2.0 * fma * B * n
+    kern_ms = k_ms / max(nk, 1)
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+    desc = sk.signature_describe(B, L, d, N, flags, sk.SK_F64)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import signature as osig
+        nb, spent = 0, 0.0
+        while spent < args.cpu_seconds and nb < B:
+            a = time.perf_counter()
+            osig.signature(X[nb:nb + 1], N, flags)
+            spent += time.perf_counter() - a
+            nb += 1
+        cpu = {"value": nb * n * (entries - 1) / spent, "unit": "entry updates/s", "cores": 1, "kind": "oracle",
+               "sample": "%d paths of %s, %.1f s (numpy, full tensor products)" % (nb, args.workload, spent)}
+    print(json.dumps({
+        "metric": "signature entry updates/s (truncated signatures, Horner), fp64, 1 MI355X",
+        "value": B * n * (entries - 1) / sec, "unit": "entry updates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "%s: %d paths, L=%d, d=%d, truncation level %d%s, fp64, forward" % (
+            args.workload, B, L, d, N, ", lead-lag transformed" if args.lead_lag else ""),
+            "entries_per_path": entries},
+        "paths_per_s": B / sec, "horner_kernel_ms": kern_ms,
+        "roofline": {"bound": "alu", "kernel": desc.split("kernel=", 1)[1].split(" channels=", 1)[0],
+                     "launch": dict(kv.split("=", 1) for kv in desc.split(" ") if "=" in kv and not kv.startswith("kernel=")),
+                     "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "avg_launch_ms": kern_ms, "flops_per_launch": flops,
+                     "traffic": None},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", help="c2 (headline), or c1/c3/c4/c5 for the other configurations")
+    ap.add_argument("--workload", default="c2", help="c2 (headline), c1/c3/c4/c5 for the other configurations, or "
+                    "s1/s2/s3 for truncated signatures on the shapes of the paper's Table 1 (a side measurement)")
     ap.add_argument("--lead-lag", action="store_true",
                     help="apply the lead-lag transform on the fly (SK_FLAG_LEAD_LAG): a side measurement, not the headline")
     ap.add_argument("--symmetric", action="store_true",
@@ -61,6 +132,9 @@ def main():
         print("bench.py: this build measures one GPU only (pairs are independent; see DESIGN.md for how the "
               "path would shard); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload in ("s1", "s2", "s3"):
+        return bench_signature(args)
 
     import numpy as np
     import torch

@@ -152,7 +152,11 @@ __device__ __forceinline__ void run(const Args& a)
     const int D = DT > 0 ? DT : a.D;
     const int Q = QC <= kQExact ? QC : a.Q;
     const int lane = threadIdx.x & (kWave - 1);
-    const long wt = (long)blockIdx.x * kWavesPerWG + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    // Workgroups go to the 8 XCDs (each with an L2 of its own) in turn: number them so that the workgroups of one
+    // path, which read the same increments, sit on the same XCD.
+    long wg = blockIdx.x;
+    if (gridDim.x % kXcds == 0) wg = (long)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
+    const long wt = wg * kWavesPerWG + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     if (wt >= a.B * a.WP) return;
     const long b = wt / a.WP;
     long ti = (wt - b * a.WP) * kWave + lane;
@@ -180,7 +184,7 @@ __device__ __forceinline__ void run(const Args& a)
 #pragma unroll
     for (int r = 0; r < QA; ++r) preR[r] = 0.0;
 
-    const double* zrow = a.dz + b * a.n * a.Dpad;
+    const double* zrow = a.dz + b * a.np * a.Dpad;
     double zz[DD], zc[S], zuR[QA];
     double zzn[DD], zcn[S], zuRn[QA];
     auto fetch = [&](long step, double (&z_)[DD], double (&zc_)[S], double (&zu_)[QA]) {
@@ -197,17 +201,23 @@ __device__ __forceinline__ void run(const Args& a)
     };
 #pragma unroll
     for (int c = 0; c < DD; ++c) zz[c] = zzn[c] = 0.0;
-    if (a.n > 0) fetch(0, zz, zc, zuR);
-    for (long step = 0; step < a.n; ++step) {
-        fetch(step + 1 < a.n ? step + 1 : step, zzn, zcn, zuRn);
+    // Two steps per iteration with two sets of registers for the increments, each set requested one step before the
+    // arithmetic that reads it.  Two things keep the compiler from moving a load next to its use: the body has no
+    // branch (loads get moved into the block that uses them), and the set carried round the loop starts as constants,
+    // not as a load (a value that is a load on every path into the loop becomes one load at the top of the body).
+    // So the first step is a zero increment, which changes nothing, the rows follow in pairs, and the stored row count
+    // np is odd with zero rows after the last segment.
+#pragma unroll
+    for (int s = 0; s < S; ++s) zc[s] = 0.0;
+#pragma unroll
+    for (int r = 0; r < QA; ++r) zuR[r] = 0.0;
+    for (long step = 0; step < a.np; step += 2) {
+        fetch(step, zzn, zcn, zuRn);
         owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, zuR, zc, zz);
         prefix_levels<QC, QA>(Q, preR, zuR);
-#pragma unroll
-        for (int c = 0; c < DD; ++c) zz[c] = zzn[c];
-#pragma unroll
-        for (int s = 0; s < S; ++s) zc[s] = zcn[s];
-#pragma unroll
-        for (int r = 0; r < QA; ++r) zuR[r] = zuRn[r];
+        fetch(step + 1 < a.np ? step + 1 : step, zz, zc, zuR);
+        owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, zuRn, zcn, zzn);
+        prefix_levels<QC, QA>(Q, preR, zuRn);
     }
 
     if (!valid) return;
@@ -248,16 +258,19 @@ __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_kernel(const Args 
 // first), then the time channel 1/n if asked for, then zero padding.
 template <typename TI>
 __global__ __launch_bounds__(256) void increments_kernel(const TI* __restrict__ x, double* __restrict__ dz, long B, long L,
-                                                         int d, int D, int Dpad, long n, int time_aug, int lead_lag)
+                                                         int d, int D, int Dpad, long n, long np, int time_aug,
+                                                         int lead_lag)
 {
-    const long total = B * n * Dpad;
+    const long total = B * np * Dpad;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const int c = (int)(i % Dpad);
         const long bs = i / Dpad;
-        const long s = bs % n;
-        const long b = bs / n;
+        const long s = bs % np;
+        const long b = bs / np;
         double v = 0.0;
-        if (time_aug && c == D - 1) {
+        if (s >= n) {
+            // a zero row that makes the count odd
+        } else if (time_aug && c == D - 1) {
             v = 1.0 / (double)n;
         } else if (c < D) {
             long seg = s;
@@ -307,7 +320,7 @@ hipError_t launch_variant(const Args& a, long grid, hipStream_t st)
 hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStream_t st)
 {
     if (grid <= 0) return hipSuccess;
-    if (a.Q < 0 || a.Q > kQMax || a.LP <= 0 || a.WP * kWave < a.LP || a.NB * (long)S < (DT ? DT : a.D))
+    if ((a.np > 0 && !(a.np & 1)) || a.np < a.n || a.Q < 0 || a.Q > kQMax || a.LP <= 0 || a.WP * kWave < a.LP || a.NB * (long)S < (DT ? DT : a.D))
         return hipErrorInvalidValue;
     if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, st) : hipErrorInvalidValue;
 #define SG_CASE(D_, M_, S_) \
@@ -318,19 +331,20 @@ hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStre
 }
 
 template <typename TI>
-hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, int time_aug,
-                             int lead_lag, hipStream_t st)
+hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, long np,
+                             int time_aug, int lead_lag, hipStream_t st)
 {
-    const long total = B * n * Dpad;
+    if (np < n || (np > 0 && !(np & 1))) return hipErrorInvalidValue;
+    const long total = B * np * Dpad;
     if (total <= 0) return hipSuccess;
     long grid = (total + 255) / 256;
     if (grid > 65536) grid = 65536;
-    hipLaunchKernelGGL((increments_kernel<TI>), dim3((unsigned)grid), dim3(256), 0, st, x, dz, B, L, d, D, Dpad, n,
+    hipLaunchKernelGGL((increments_kernel<TI>), dim3((unsigned)grid), dim3(256), 0, st, x, dz, B, L, d, D, Dpad, n, np,
                        time_aug, lead_lag);
     return hipGetLastError();
 }
 
-template hipError_t launch_increments<float>(const float*, double*, long, long, int, int, int, long, int, int, hipStream_t);
-template hipError_t launch_increments<double>(const double*, double*, long, long, int, int, int, long, int, int, hipStream_t);
+template hipError_t launch_increments<float>(const float*, double*, long, long, int, int, int, long, long, int, int, hipStream_t);
+template hipError_t launch_increments<double>(const double*, double*, long, long, int, int, int, long, long, int, int, hipStream_t);
 
 }  // namespace sg

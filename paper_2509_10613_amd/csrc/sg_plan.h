@@ -18,6 +18,7 @@ namespace sg {
 
 constexpr int kWave = 64;
 constexpr int kWavesPerWG = 4;
+constexpr int kXcds = 8;
 constexpr int kQMax = 8;            // longest carried prefix
 constexpr int kQExact = 4;          // prefix lengths with code of their own
 constexpr int kLongPrefixMaxD = 9;   // channel counts whose variants also exist for prefixes longer than kQExact
@@ -46,6 +47,7 @@ struct Plan {
     int D = 0;            // channels after the transformations
     int N = 0;
     int64_t n = 0;        // segments after the transformations
+    int64_t np = 0;       // increment rows stored per path: n rounded up to an odd number (the extra row is zero)
     int DT = 0;           // kernel template channel count (0: run-time channel count, M = 0, S = 1)
     int M = 0, S = 1, Q = 0, NB = 1;
     int64_t LP = 0;       // lanes per path: D^Q * NB
@@ -85,10 +87,11 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     const int64_t D = (lead_lag ? 2 * d : d) + (time_aug ? 1 : 0);
     p.D = (int)D;
     p.n = L < 1 ? 0 : (lead_lag ? 2 * (L - 1) : L - 1);
+    p.np = p.n == 0 ? 0 : (p.n | 1);
     p.sig_len = sig_length(D, N);
     if (p.sig_len == 0) { p.why = "the signature has more than 2^40 entries per path"; return p; }
     if (B > 0 && p.sig_len > ((int64_t)1 << 46) / B) { p.why = "the batch of signatures has more than 2^46 entries"; return p; }
-    if (B > 0 && p.n * (D + 1) > ((int64_t)1 << 44) / B) { p.why = "the batch of increments has more than 2^44 entries"; return p; }
+    if (B > 0 && p.np * (D + 1) > ((int64_t)1 << 44) / B) { p.why = "the batch of increments has more than 2^44 entries"; return p; }
 
     auto lanes = [&](int M, int S, int64_t& LP, int& Q, int& NB) -> bool {
         Q = N - M - 1;
@@ -142,7 +145,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     p.Dpad = (int)align_up((size_t)D, 2);
     size_t off = 0;
     p.off_dz = off;
-    off = align_up(off + (size_t)B * (size_t)p.n * p.Dpad * sizeof(double), 256);
+    off = align_up(off + (size_t)B * (size_t)p.np * p.Dpad * sizeof(double), 256);
     p.off_out = off;
     if (!io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
     p.total = off < 256 ? 256 : off;

@@ -532,12 +532,12 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
         if (e != hipSuccess) return fail(SK_ERR_HIP, "%s: %s", #call, hipGetErrorString(e));   \
     } while (0)
     double* dz = reinterpret_cast<double*>(base + p.off_dz);
-    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n,
+    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, p.np,
                                       (flags & SK_FLAG_TIME_AUG) ? 1 : 0, (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
     sg::Args a;
     a.dz = dz;
     a.out = kIsDouble ? static_cast<double*>(out) : reinterpret_cast<double*>(base + p.off_out);
-    a.B = p.B; a.n = p.n; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
+    a.B = p.B; a.n = p.n; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len;
     bool timed = false;
     TimedLaunch tl{};
