@@ -62,6 +62,13 @@ def bench_signature(args):
     def step():
         sk.signature_fwd(x, N, flags, ws=ws, out=out)
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
