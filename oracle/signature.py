@@ -95,3 +95,77 @@ def signature(x, N, flags=0):
     for b in range(x.shape[0]):
         out[b] = flatten(levels_of_path(xt[b], N))
     return out
+
+
+# ---------------------------------------------------------------- gradients (Section 2.4)
+# The gradient of F = <grad_out, S(x)> with respect to the points of x, by the chain rule through the same products
+# the forward function performs, every intermediate signature kept (no time reversal, no deconstruction: those are
+# ways to save memory that reach the same numbers).
+def unflatten(flat, d, N):
+    out, off = [], 0
+    for k in range(N + 1):
+        out.append(np.asarray(flat[off:off + d ** k], dtype=np.float64).reshape((d,) * k))
+        off += d ** k
+    return out
+
+
+def lead_lag_pullback(g):
+    """Chain rule through lead_lag: a point of the path is copied into the lead half of the transformed points
+    2k - 1, 2k and into the lag half of 2k, 2k + 1.  g[..., 2L - 1, 2d] -> [..., L, d]."""
+    g = np.asarray(g, dtype=np.float64)
+    L, d = (g.shape[-2] + 1) // 2, g.shape[-1] // 2
+    out = np.zeros(g.shape[:-2] + (L, d), dtype=np.float64)
+    for i in range(2 * L - 1):
+        out[..., (i + 1) // 2, :] += g[..., i, :d]
+        out[..., i // 2, :] += g[..., i, d:]
+    return out
+
+
+def path_backward(path, grad_levels, N):
+    """d <grad, S(path)> / d path for one path[L, D] (no transformations); grad_levels[k] has shape (D,)*k."""
+    path = np.asarray(path, dtype=np.float64)
+    L, D = path.shape
+    S = [segment_levels(np.zeros(D), N)]
+    for a in range(L - 1):
+        S.append(tensor_product(S[a], segment_levels(path[a + 1] - path[a], N), N))
+    G = [np.array(g, dtype=np.float64) for g in grad_levels]
+    gz = np.zeros((max(L - 1, 0), D))
+    for a in range(L - 2, -1, -1):
+        z = path[a + 1] - path[a]
+        E = segment_levels(z, N)
+        P = S[a]                                   # signature before this segment: S[a + 1] = P (x) E
+        # level n of the product is sum_i P_i (x) E_{n-i}: the adjoint of E_j collects P_i against G_{i+j} over the
+        # first i indices, the adjoint of P_i collects G_{i+j} against E_j over the last j indices
+        Ebar = [sum(np.tensordot(P[i], G[i + j], axes=i) for i in range(N - j + 1)) for j in range(N + 1)]
+        Gprev = [sum(np.tensordot(G[i + j], E[j], axes=j) for j in range(N - i + 1)) for i in range(N + 1)]
+        # E_j = E_{j-1} (x) z / j
+        zbar = np.zeros(D)
+        for j in range(N, 0, -1):
+            zbar += np.tensordot(E[j - 1], Ebar[j], axes=j - 1) / j
+            Ebar[j - 1] = Ebar[j - 1] + np.tensordot(Ebar[j], z, axes=([j - 1], [0])) / j
+        gz[a] = zbar
+        G = Gprev
+    gp = np.zeros((L, D))
+    for a in range(L - 1):                         # z_a = path[a + 1] - path[a]
+        gp[a + 1] += gz[a]
+        gp[a] -= gz[a]
+    return gp
+
+
+def signature_backward(x, grad_out, N, flags=0):
+    """x[B, L, d], grad_out[B, sig_length(d', N)] -> d <grad_out, signature(x)> / dx  [B, L, d]."""
+    x = np.asarray(x, dtype=np.float64)
+    grad_out = np.asarray(grad_out, dtype=np.float64)
+    B, L, d = x.shape
+    xt = transform(x, flags)
+    D = xt.shape[-1]
+    assert grad_out.shape == (B, sig_length(D, N))
+    out = np.empty_like(x)
+    for b in range(B):
+        g = path_backward(xt[b], unflatten(grad_out[b], D, N), N)
+        if flags & FLAG_TIME_AUG:
+            g = g[:, :-1]                          # the time channel does not depend on the path
+        if flags & FLAG_LEAD_LAG:
+            g = lead_lag_pullback(g)
+        out[b] = g
+    return out

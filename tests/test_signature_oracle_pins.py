@@ -154,3 +154,75 @@ def test_s5_time_augmentation_and_lead_lag_flags():
     assert flat.shape == (1 + 5 + 25,) and abs(level(flat, 5, 1)[4] - 1.0) < 1e-15
     xt = osig.transform(x, osig.FLAG_LEAD_LAG | osig.FLAG_TIME_AUG)
     assert xt.shape == (2 * L - 1, 5) and np.allclose(np.diff(xt[:, 4]), 1.0 / (2 * L - 2))
+
+
+# ---------------------------------------------------------------- gradients (Section 2.4)
+def fd_gradient(x, g, N, flags, h=1e-6):
+    """Central differences of F = <g, signature(x)> (forward function only)."""
+    out = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        out[idx] = (np.sum(g * osig.signature(xp[None], N, flags)[0]) - np.sum(g * osig.signature(xm[None], N, flags)[0])) / (2 * h)
+    return out
+
+
+@pytest.mark.parametrize("L,d,N,flags", [(4, 2, 4, 0), (5, 3, 3, 0), (2, 2, 5, 0), (4, 2, 3, osig.FLAG_TIME_AUG),
+                                         (4, 2, 3, osig.FLAG_LEAD_LAG), (3, 2, 2, osig.FLAG_LEAD_LAG | osig.FLAG_TIME_AUG)])
+def test_s6_gradient_vs_central_differences(L, d, N, flags):
+    rng = np.random.default_rng(60 + L + d + N + flags)
+    x = np.cumsum(rng.normal(0, 0.6, size=(L, d)), axis=0)
+    n = osig.sig_length(osig.transform(x, flags).shape[-1], N)
+    g = rng.normal(0, 1.0, size=n)
+    got = osig.signature_backward(x[None], g[None], N, flags)[0]
+    ref = fd_gradient(x, g, N, flags)
+    assert np.max(np.abs(got - ref)) < 2e-8 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_s6_gradient_closed_forms_and_invariants():
+    rng = np.random.default_rng(66)
+    L, d, N = 6, 2, 3
+    x = np.cumsum(rng.normal(0, 0.7, size=(L, d)), axis=0)
+    n = osig.sig_length(d, N)
+    # level 1 is the total increment: its gradient is -1 at the first point and +1 at the last one
+    for c in range(d):
+        g = np.zeros(n)
+        g[1 + c] = 1.0
+        gx = osig.signature_backward(x[None], g[None], N)[0]
+        want = np.zeros((L, d))
+        want[0, c], want[-1, c] = -1.0, 1.0
+        assert np.allclose(gx, want, atol=1e-14)
+    # the Levy area (S^01 - S^10)/2 = 1/2 sum_i (x_i^0 x_{i+1}^1 - x_{i+1}^0 x_i^1) - 1/2 (x_0^0 x_L^1 - x_L^0 x_0^1)
+    # (shoelace of the polygon closed by the chord), differentiated by hand
+    g = np.zeros(n)
+    g[1 + d + 1], g[1 + d + d] = 0.5, -0.5
+    gx = osig.signature_backward(x[None], g[None], N)[0]
+    want = np.zeros((L, d))
+    for i in range(L):
+        nxt = x[i + 1] if i + 1 < L else None
+        prv = x[i - 1] if i > 0 else None
+        if nxt is not None:
+            want[i, 0] += 0.5 * nxt[1]
+            want[i, 1] -= 0.5 * nxt[0]
+        if prv is not None:
+            want[i, 1] += 0.5 * prv[0]
+            want[i, 0] -= 0.5 * prv[1]
+    want[0, 0] -= 0.5 * x[-1, 1]
+    want[0, 1] += 0.5 * x[-1, 0]
+    want[-1, 1] -= 0.5 * x[0, 0]
+    want[-1, 0] += 0.5 * x[0, 1]
+    assert np.allclose(gx, want, atol=1e-13)
+    # translation invariance: the gradients of the points sum to zero; level 0 has no gradient; linear in grad_out
+    g1, g2 = rng.normal(size=n), rng.normal(size=n)
+    a = osig.signature_backward(x[None], g1[None], N)[0]
+    b = osig.signature_backward(x[None], g2[None], N)[0]
+    assert np.max(np.abs(a.sum(axis=0))) < 1e-12
+    assert np.allclose(osig.signature_backward(x[None], (2.0 * g1 - 3.0 * g2)[None], N)[0], 2.0 * a - 3.0 * b, atol=1e-12)
+    g0 = np.zeros(n)
+    g0[0] = 5.0
+    assert not osig.signature_backward(x[None], g0[None], N)[0].any()
+    # batch entries are independent; one-point paths have zero gradient
+    both = osig.signature_backward(np.stack([x, 2.0 * x]), np.stack([g1, g2]), N)
+    assert np.array_equal(both[0], a)
+    assert not osig.signature_backward(np.zeros((2, 1, 3)), np.ones((2, 40)), 3).any()
