@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-/* Diagnostic, for signature_fwd / signature_workspace_bytes / signature_describe only: a lane keeps the entries of a
+/* Diagnostic, for the entry points of this header only: a lane keeps the entries of a
  * subtree of words of depth m in registers; SK_SIG_DEPTH(m), m = 0..5, or-ed into `flags` forces that depth instead
  * of the library's own choice (SK_ERR_SHAPE if no kernel with that depth exists for the shape).  Results do not
  * depend on it beyond rounding order. */
@@ -49,7 +49,22 @@ size_t signature_workspace_bytes(int64_t B, int64_t L, int64_t d, int N, int fla
 int signature_fwd(const void* x, void* out, int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, void* ws,
                   size_t ws_bytes, void* stream);
 
+/*
+ * Gradient with respect to the path points (Section 2.4): given grad_out[B, signature_length(d, N, flags)] = dF/dS for
+ * the signatures S = signature_fwd(x), writes grad_x[B,L,d] = dF/dx.  sig is the output of signature_fwd for the same
+ * x, N and flags, or NULL to have it computed into the workspace first.  As Section 2.4 describes, the path is walked
+ * backwards, the signature before each segment is recovered from the one after it by multiplying with the tensor
+ * exponential of the negated increment (Horner's step again), and the adjoint is taken through that one step; no
+ * intermediate signature is stored.  Level 0 of grad_out has no effect.  Gradient entries are sums formed by
+ * floating-point atomics: reproducible to rounding, not bit for bit.
+ * have_sig != 0 in the workspace query if sig will not be NULL.
+ */
+size_t signature_bwd_workspace_bytes(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, int have_sig);
+int signature_bwd(const void* x, const void* sig, const void* grad_out, void* grad_x, int64_t B, int64_t L, int64_t d,
+                  int N, int flags, sk_dtype dt, void* ws, size_t ws_bytes, void* stream);
+
 /* Diagnostics (no passage of the paper): human-readable launch plan for these arguments, as sigkernel_describe. */
+int signature_bwd_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, char* out, size_t out_bytes);
 int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, char* out, size_t out_bytes);
 
 #ifdef __cplusplus

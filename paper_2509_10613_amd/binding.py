@@ -27,7 +27,8 @@ def SK_SIG_DEPTH(m):
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",
            "sigkernel_mmd2", "sigkernel_mmd2_workspace_bytes",
            "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version",
-           "signature_length", "signature_workspace_bytes", "signature_fwd", "signature_describe"]
+           "signature_length", "signature_workspace_bytes", "signature_fwd", "signature_describe",
+           "signature_bwd_workspace_bytes", "signature_bwd", "signature_bwd_describe"]
 
 _lib = None
 
@@ -75,6 +76,12 @@ def load():
     lib.signature_fwd.argtypes = [vp, vp, i64, i64, i64, ci, ci, ci, vp, C.c_size_t, vp]
     lib.signature_describe.restype = ci
     lib.signature_describe.argtypes = [i64, i64, i64, ci, ci, ci, C.c_char_p, C.c_size_t]
+    lib.signature_bwd_describe.restype = ci
+    lib.signature_bwd_describe.argtypes = [i64, i64, i64, ci, ci, ci, C.c_char_p, C.c_size_t]
+    lib.signature_bwd_workspace_bytes.restype = C.c_size_t
+    lib.signature_bwd_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci, ci]
+    lib.signature_bwd.restype = ci
+    lib.signature_bwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, ci, ci, vp, C.c_size_t, vp]
     lib.sigkernel_last_error.restype = C.c_char_p
     lib.sigkernel_version.restype = C.c_char_p
     _lib = lib
@@ -260,3 +267,32 @@ def signature_fwd(x, N, flags=0, ws=None, out=None):
         ws = workspace(need, x.device)
     _check(load().signature_fwd(_ptr(x), _ptr(out), B, L, d, N, flags, dt, _ptr(ws), ws.numel(), _stream()))
     return out
+
+
+def signature_bwd_describe(B, L, d, N, flags, dt):
+    buf = C.create_string_buffer(512)
+    _check(load().signature_bwd_describe(B, L, d, N, flags, dt, buf, len(buf)))
+    return buf.value.decode()
+
+
+def signature_bwd(x, grad_out, N, flags=0, sig=None, ws=None, grad_x=None):
+    """dF/dx [B,L,d] for upstream gradients grad_out[B, signature_length(d, N, flags)]; sig = signature_fwd(x, N, flags)
+    if the caller has it, else it is recomputed inside."""
+    _dev(x, "x"); _dev(grad_out, "grad_out")
+    B, L, d = x.shape
+    dt = _dt(x)
+    n = signature_length(d, N, flags)
+    if n == 0:
+        signature_bwd_describe(B, L, d, N, flags, dt)   # raises with the library's message for these arguments
+    assert grad_out.shape == (B, n) and grad_out.dtype == x.dtype
+    if sig is not None:
+        _dev(sig, "sig")
+        assert sig.shape == (B, n) and sig.dtype == x.dtype
+    if grad_x is None:
+        grad_x = torch.empty_like(x)
+    need = int(load().signature_bwd_workspace_bytes(B, L, d, N, flags, dt, 0 if sig is None else 1))
+    if ws is None:
+        ws = workspace(need, x.device)
+    _check(load().signature_bwd(_ptr(x), _ptr(sig), _ptr(grad_out), _ptr(grad_x), B, L, d, N, flags, dt, _ptr(ws),
+                                ws.numel(), _stream()))
+    return grad_x

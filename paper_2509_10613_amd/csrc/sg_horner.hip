@@ -14,114 +14,12 @@
 // few that a lane selects by its own letters come in by ordinary loads; both are fetched one step ahead.
 #include <hip/hip_runtime.h>
 
+#include "sg_dev.h"
 #include "sg_kernels.h"
 
 namespace sg {
 
 namespace {
-
-typedef const double __attribute__((address_space(4))) * uniform_ptr;   // constant address space: scalar loads
-
-__host__ __device__ constexpr int ipow(int D, int m)
-{
-    int p = 1;
-    for (int i = 0; i < m; ++i) p *= D;
-    return p;
-}
-
-// The words a lane owns, level by level: node e of level m has the children e * D + c at level m + 1; level m holds
-// S * D^m nodes and starts at off(m).
-template <int D, int M, int S>
-struct Tree {
-    static constexpr int cnt(int m) { return S * ipow(D, m); }
-    static constexpr int off(int m)
-    {
-        int o = 0;
-        for (int i = 0; i < m; ++i) o += cnt(i);
-        return o;
-    }
-    static constexpr int TOT = off(M + 1);
-    static constexpr int GT = M > 0 ? off(M) : 1;
-
-    // levels m .. MT of the update of the owned level MT (the word of node e at level MT has length k - 1 + 1 = k)
-    template <int MT, int m>
-    static __device__ __forceinline__ void descend(double (&A)[TOT], double (&G)[GT], const double (&zz)[D])
-    {
-        constexpr int np = cnt(m - 1);
-#pragma unroll
-        for (int e = 0; e < np; ++e) {
-            // parent word has |v| = Q + m letters and k = Q + 1 + MT, so k - |v| = MT + 1 - m
-            const double gs = (m < MT) ? G[off(m - 1) + e] * (1.0 / (double)(MT + 1 - m)) : G[off(m - 1) + e];
-#pragma unroll
-            for (int c = 0; c < D; ++c) {
-                const int i = off(m) + e * D + c;
-                if (m < MT) G[i] = __builtin_fma(gs, zz[c], A[i]);
-                else A[i] = __builtin_fma(gs, zz[c], A[i]);
-            }
-        }
-        if constexpr (m < MT) descend<MT, m + 1>(A, G, zz);
-    }
-
-    // g = G_k[u] for k = Q + 1 + MT; zc = the increments at the lane's S letters
-    template <int MT>
-    static __device__ __forceinline__ void level(double (&A)[TOT], double g, const double (&zc)[S], const double (&zz)[D])
-    {
-        if constexpr (MT == 0) {
-#pragma unroll
-            for (int s = 0; s < S; ++s) A[s] = __builtin_fma(g, zc[s], A[s]);
-        } else {
-            double G[GT];
-            const double g0 = g * (1.0 / (double)(MT + 1));
-#pragma unroll
-            for (int s = 0; s < S; ++s) G[s] = __builtin_fma(g0, zc[s], A[s]);
-            descend<MT, 1>(A, G, zz);
-        }
-    }
-};
-
-// The carried prefix has Q letters.  QC is Q itself when Q <= kQExact (every loop below then has constant bounds and
-// no test), else kQMax with a test of r against Q in every iteration.
-template <int QC>
-__device__ __forceinline__ bool has(int r, int Q)
-{
-    return QC <= kQExact ? true : r < Q;
-}
-
-// G_k[u] for the level that lies E letters beyond the prefix (k = Q + E): the chain over the prefixes of u.
-// preR[r] / zuR[r] belong to the prefix of length Q - r (reversed so that every index below is a constant).
-template <int E, int QC, int QA>
-__device__ __forceinline__ double prefix_chain(int Q, const double (&preR)[QA], const double (&zuR)[QA])
-{
-    double g = 1.0;
-#pragma unroll
-    for (int r = QC - 1; r >= 0; --r)
-        if (has<QC>(r, Q)) g = __builtin_fma(g, zuR[r] * (1.0 / (double)(r + 1 + E)), preR[r]);   // k - |v| = r + 1 + E
-    return g;
-}
-
-template <int MT, int D, int M, int S, int QC, int TOT, int QA>
-__device__ __forceinline__ void owned_levels(double (&A)[TOT], int Q, const double (&preR)[QA],
-                                             const double (&zuR)[QA], const double (&zc)[S], const double (&zz)[D])
-{
-    Tree<D, M, S>::template level<MT>(A, prefix_chain<MT + 1, QC, QA>(Q, preR, zuR), zc, zz);
-    if constexpr (MT > 0) owned_levels<MT - 1, D, M, S, QC, TOT, QA>(A, Q, preR, zuR, zc, zz);
-}
-
-// the carried entries at the prefixes of u: word length Q - r0, longest first
-template <int QC, int QA>
-__device__ __forceinline__ void prefix_levels(int Q, double (&preR)[QA], const double (&zuR)[QA])
-{
-#pragma unroll
-    for (int r0 = 0; r0 < QC; ++r0) {
-        if (has<QC>(r0, Q)) {
-            double g = 1.0;
-#pragma unroll
-            for (int r = QC - 1; r > r0; --r)
-                if (has<QC>(r, Q)) g = __builtin_fma(g, zuR[r] * (1.0 / (double)(r - r0 + 1)), preR[r]);
-            preR[r0] = __builtin_fma(g, zuR[r0], preR[r0]);
-        }
-    }
-}
 
 // The owned entries of level Q + 1 + m go to the words u (blk S + s) v: `first` is the number of the word u (blk S) in
 // base D, at[m] the start of that level in the flattened signature.

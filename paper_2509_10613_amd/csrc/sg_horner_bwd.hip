@@ -1,0 +1,294 @@
+// Gradient of batched truncated signatures with respect to the path points (paper Section 2.4) for gfx950.
+//
+// Section 2.4 walks the path backwards: the signature before a segment is recovered from the one after it,
+// S_{l-1} = S_l (x) exp(-z_l), which is Horner's step of Section 2.3 with the increment negated, and the adjoint
+// (dF/dS_l -> dF/dS_{l-1}, dF/dz_l) is taken through that one step.  The lanes are those of the forward kernel: a lane
+// owns the entries under a prefix u and a block of next letters, in registers, now together with their adjoints.
+// The adjoint of the step is linear in the incoming adjoints, so the adjoints of the entries at the prefixes of u,
+// which every lane under the prefix carries a copy of, never have to be summed over lanes: each lane carries a share
+// (the upstream value starts in one lane, zero in the others) and the shares add up to the adjoint at every step.
+// Only dF/dz_l is a sum over all lanes of a path: per step a wave adds its lanes' shares in LDS (a transposed sum
+// for the part that belongs to the wave-uniform increments, LDS atomics for the part a lane picked by its own
+// letters) and issues one global atomic per channel.
+#include <hip/hip_runtime.h>
+
+#include "sg_dev.h"
+#include "sg_kernels.h"
+
+namespace sg {
+
+namespace {
+
+template <int D, int M, int S, int TOT, int m = 0>
+__device__ __forceinline__ void load_owned(double (&A)[TOT], const double* src, const long (&at)[M + 1], int Dn,
+                                           long first, int c0, bool valid)
+{
+    constexpr int pm = ipow(D, m);
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const bool ok = valid && c0 + s < Dn;
+        const double* o = src + at[m] + (first + s) * pm;
+#pragma unroll
+        for (int v = 0; v < pm; ++v) A[Tree<D, M, S>::off(m) + s * pm + v] = ok ? o[v] : 0.0;
+    }
+    if constexpr (m < M) load_owned<D, M, S, TOT, m + 1>(A, src, at, Dn, first, c0, valid);
+}
+
+template <int DT, int M, int S, int QC>
+__device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
+{
+    constexpr int DD = DT > 0 ? DT : 1;
+    constexpr int QA = QC > 0 ? QC : 1;
+    constexpr bool kUniformZ = DT > 0 && M > 0;
+    using T = Tree<DD, M, S>;
+    const int D = DT > 0 ? DT : a.D;
+    const int Q = QC <= kQExact ? QC : a.Q;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    long wg = blockIdx.x;
+    if (gridDim.x % kXcds == 0) wg = (long)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
+    const long wt = wg * kWavesPerWG + wave;
+    if (wt >= a.B * a.WP) return;
+    const long b = wt / a.WP;
+    long ti = (wt - b * a.WP) * kWave + lane;
+    const bool valid = ti < a.LP;
+    if (!valid) ti = 0;
+    const int blk = (int)(ti % a.NB);
+    const long rest = ti / a.NB;
+    int uR[QA];
+    {
+        long t = rest;
+#pragma unroll
+        for (int r = 0; r < QA; ++r) {
+            uR[r] = (r < QC && has<QC>(r, Q)) ? (int)(t % D) : 0;
+            t /= D;
+        }
+    }
+    int cs[S];
+    bool cok[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        cok[s] = valid && blk * S + s < D;
+        cs[s] = min(blk * S + s, D - 1);
+    }
+
+    // this wave's LDS: Dpad sums per channel, then (kernels with wave-uniform increments) 64 rows of DS doubles
+    const int DS = D | 1;
+    double* acc = lds + (size_t)wave * a.lds_wave;
+    double* tr = acc + a.Dpad;
+    for (int c = lane; c < a.Dpad; c += kWave) acc[c] = 0.0;
+
+    auto lvl = [&](int k) {
+        long o = 0, p = 1;
+        for (int i = 0; i < k; ++i) {
+            o += p;
+            p *= D;
+        }
+        return o;
+    };
+    long at[M + 1];
+#pragma unroll
+    for (int m = 0; m <= M; ++m) at[m] = lvl(Q + 1 + m);
+
+    // the signature of the whole path and the upstream gradient, each lane its own entries
+    double A[T::TOT], Ab[T::TOT], preR[QA], prb[QA];
+    const double* sig = a.sig + b * a.sig_len;
+    const double* gout = a.gout + b * a.sig_len;
+    load_owned<DD, M, S, T::TOT>(A, sig, at, D, rest * D + blk * S, blk * S, true);
+    load_owned<DD, M, S, T::TOT>(Ab, gout, at, D, rest * D + blk * S, blk * S, valid);
+    {
+        long pw = 1;
+#pragma unroll
+        for (int r = 0; r < QA; ++r) {
+            preR[r] = 0.0;
+            prb[r] = 0.0;
+            if (r < QC && has<QC>(r, Q)) {
+                const long idx = lvl(Q - r) + rest / pw;
+                preR[r] = sig[idx];
+                if (valid && blk == 0 && rest % pw == 0) prb[r] = gout[idx];   // one lane starts with the upstream value
+            }
+            pw *= D;
+        }
+    }
+
+    const double* zrow = a.dz + b * a.np * a.Dpad;
+    double* grow = a.gz + b * a.np * a.Dpad;
+    double zz[DD], zc[S], zuR[QA];
+    double zzn[DD], zcn[S], zuRn[QA];
+    auto fetch = [&](long row, double (&z_)[DD], double (&zc_)[S], double (&zu_)[QA]) {
+        const double* zp = zrow + row * a.Dpad;
+        if constexpr (kUniformZ) {
+            uniform_ptr zs = (uniform_ptr)(zp);
+#pragma unroll
+            for (int c = 0; c < DD; ++c) z_[c] = zs[c];
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) zc_[s] = zp[cs[s]];
+#pragma unroll
+        for (int r = 0; r < QA; ++r) zu_[r] = (r < QC && has<QC>(r, Q)) ? zp[uR[r]] : 0.0;
+    };
+
+    // one segment backwards; row < 0: the zero increment that starts the loop, nothing to add anywhere
+    auto segment = [&](long row, const double (&z_)[DD], const double (&zc_)[S], const double (&zu_)[QA]) {
+        // the signature before the segment: the forward step with the increment negated
+        double nz[DD], nzc[S], nzu[QA];
+#pragma unroll
+        for (int c = 0; c < DD; ++c) nz[c] = -z_[c];
+#pragma unroll
+        for (int s = 0; s < S; ++s) nzc[s] = -zc_[s];
+#pragma unroll
+        for (int r = 0; r < QA; ++r) nzu[r] = -zu_[r];
+        owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, nzu, nzc, nz);
+        prefix_levels<QC, QA>(Q, preR, nzu);
+        // the adjoint of the forward step from that signature with the increment itself
+        double zzb[DD], zcb[S], zub[QA];
+#pragma unroll
+        for (int c = 0; c < DD; ++c) zzb[c] = 0.0;
+#pragma unroll
+        for (int s = 0; s < S; ++s) zcb[s] = 0.0;
+#pragma unroll
+        for (int r = 0; r < QA; ++r) zub[r] = 0.0;
+        prefix_levels_rev<QC, QA>(Q, preR, zu_, prb, zub);
+        owned_levels_rev<0, DD, M, S, QC, T::TOT, QA>(A, Ab, Q, preR, prb, zu_, zc_, z_, zub, zcb, zzb);
+        if (row < 0) return;
+        // this wave's share of dF/dz[row]
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+            if (cok[s]) atomicAdd(&acc[cs[s]], zcb[s]);
+#pragma unroll
+        for (int r = 0; r < QC; ++r)
+            if (has<QC>(r, Q)) atomicAdd(&acc[uR[r]], zub[r]);
+        if constexpr (kUniformZ) {
+#pragma unroll
+            for (int c = 0; c < DD; ++c) tr[lane * DS + c] = zzb[c];
+            __builtin_amdgcn_wave_barrier();
+            constexpr int P = kWave / DD;                  // lanes per channel
+            constexpr int R = (kWave + P - 1) / P;         // rows per lane
+            if (lane < DD * P) {
+                const int c = lane % DD, q = lane / DD;
+                double sum = 0.0;
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    const int rw = q * R + i;
+                    if (rw < kWave) sum += tr[rw * DS + c];
+                }
+                atomicAdd(&acc[c], sum);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int c = lane; c < D; c += kWave) {
+            const double v = acc[c];
+            acc[c] = 0.0;
+            atomicAdd(&grow[row * a.Dpad + c], v);
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    // Rows np-1 .. 0, two per iteration with two register sets as in the forward kernel; the set carried round the
+    // loop starts as a zero increment (constants, not a load), and np is odd.
+#pragma unroll
+    for (int c = 0; c < DD; ++c) zz[c] = zzn[c] = 0.0;
+#pragma unroll
+    for (int s = 0; s < S; ++s) zc[s] = 0.0;
+#pragma unroll
+    for (int r = 0; r < QA; ++r) zuR[r] = 0.0;
+    long rowA = -1;
+    for (long row = a.np - 1; row >= 0; row -= 2) {
+        fetch(row, zzn, zcn, zuRn);
+        segment(rowA, zz, zc, zuR);
+        fetch(row > 0 ? row - 1 : 0, zz, zc, zuR);
+        segment(row, zzn, zcn, zuRn);
+        rowA = row - 1;
+    }
+}
+
+template <int DT, int M, int S, int QC>
+__global__ __launch_bounds__(kWave * kWavesPerWG) void horner_bwd_kernel(const BwdArgs a)
+{
+    extern __shared__ double lds[];
+    run_bwd<DT, M, S, QC>(a, lds);
+}
+
+// dF/dx from dF/dz (one row per segment of the transformed path): a point gains what the segment before it gives and
+// loses what the segment after it gives.  Lead-lag: segment 2k moves the lead half by x[k+1] - x[k], segment 2k + 1
+// the lag half by the same difference.  The time channel has no gradient.
+template <typename TO>
+__global__ __launch_bounds__(256) void point_gradients_kernel(const double* __restrict__ gz, TO* __restrict__ gx, long B,
+                                                              long L, int d, int Dpad, long np, int lead_lag)
+{
+    const long total = B * L * d;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int ch = (int)(i % d);
+        const long bp = i / d;
+        const long pt = bp % L;
+        const long b = bp / L;
+        const double* g = gz + b * np * Dpad;
+        auto seg = [&](long k) {
+            return lead_lag ? g[(2 * k) * Dpad + ch] + g[(2 * k + 1) * Dpad + d + ch] : g[k * Dpad + ch];
+        };
+        double v = 0.0;
+        if (pt > 0) v += seg(pt - 1);
+        if (pt < L - 1) v -= seg(pt);
+        gx[i] = (TO)v;
+    }
+}
+
+template <int DT, int M, int S, int QC>
+hipError_t launch_one(const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st)
+{
+    hipLaunchKernelGGL((horner_bwd_kernel<DT, M, S, QC>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+template <int DT, int M, int S>
+hipError_t launch_variant(const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st)
+{
+    switch (a.Q) {
+    case 0: return launch_one<DT, M, S, 0>(a, grid, lds_bytes, st);
+    case 1: return launch_one<DT, M, S, 1>(a, grid, lds_bytes, st);
+    case 2: return launch_one<DT, M, S, 2>(a, grid, lds_bytes, st);
+    case 3: return launch_one<DT, M, S, 3>(a, grid, lds_bytes, st);
+    case 4: return launch_one<DT, M, S, 4>(a, grid, lds_bytes, st);
+    default:
+        if constexpr (DT <= kBwdLongPrefixMaxD) return launch_one<DT, M, S, kQMax>(a, grid, lds_bytes, st);
+        else return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_horner_bwd(int DT, int M, int S, const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st)
+{
+    if (grid <= 0) return hipSuccess;
+    const int D = DT ? DT : a.D;
+    const bool uniform = DT > 0 && M > 0;
+    const size_t need = (size_t)kWavesPerWG * a.lds_wave * sizeof(double);
+    if ((a.np > 0 && !(a.np & 1)) || a.np < a.n || a.Q < 0 || a.Q > kQMax || a.LP <= 0 || a.WP * kWave < a.LP ||
+        a.NB * (long)S < D || a.Dpad < D || a.lds_wave < (size_t)a.Dpad + (uniform ? (size_t)kWave * (D | 1) : 0) ||
+        lds_bytes < need || lds_bytes > 160 * 1024)
+        return hipErrorInvalidValue;
+    if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, lds_bytes, st) : hipErrorInvalidValue;
+#define SG_CASE(D_, M_, S_) \
+    if (DT == D_ && M == M_ && S == S_) return launch_variant<D_, M_, S_>(a, grid, lds_bytes, st);
+    SG_BWD_VARIANTS(SG_CASE)
+#undef SG_CASE
+    return hipErrorInvalidValue;
+}
+
+template <typename TO>
+hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int d, int Dpad, long np, int lead_lag,
+                                  hipStream_t st)
+{
+    const long total = B * L * d;
+    if (total <= 0) return hipSuccess;
+    long grid = (total + 255) / 256;
+    if (grid > 65536) grid = 65536;
+    hipLaunchKernelGGL((point_gradients_kernel<TO>), dim3((unsigned)grid), dim3(256), 0, st, gz, gx, B, L, d, Dpad, np,
+                       lead_lag);
+    return hipGetLastError();
+}
+
+template hipError_t launch_point_gradients<float>(const double*, float*, long, long, int, int, long, int, hipStream_t);
+template hipError_t launch_point_gradients<double>(const double*, double*, long, long, int, int, long, int, hipStream_t);
+
+}  // namespace sg

@@ -18,7 +18,25 @@ struct Args {
     long sig_len;
 };
 
+struct BwdArgs {
+    const double* dz;    // [B][np][Dpad] increments of the transformed paths
+    double* gz;          // [B][np][Dpad] dF/dz, zero on entry, accumulated by atomics
+    const double* sig;   // [B][sig_len] signatures of the whole paths
+    const double* gout;  // [B][sig_len] upstream gradient
+    long B;
+    long n, np;
+    int D, Dpad, N, Q, NB;
+    long LP, WP;
+    long sig_len;
+    size_t lds_wave;     // doubles of LDS per wave
+};
+
 hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStream_t st);
+hipError_t launch_horner_bwd(int DT, int M, int S, const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st);
+
+template <typename TO>
+hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int d, int Dpad, long np, int lead_lag,
+                                  hipStream_t st);
 
 template <typename TI>
 hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, long np,

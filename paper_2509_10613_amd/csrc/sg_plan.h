@@ -32,9 +32,20 @@ constexpr int64_t kSimds = 1024;       // 256 compute units of 4 SIMDs
     X(5, 2, 1) X(5, 1, 1) X(6, 2, 1) X(6, 1, 1) X(7, 2, 1) X(7, 1, 1) X(8, 2, 1) X(8, 1, 1) X(9, 2, 1) X(9, 1, 1) \
     X(10, 1, 5) X(11, 1, 4) X(12, 1, 4) X(13, 1, 4) X(14, 1, 4) X(15, 1, 4) X(16, 1, 4) X(17, 1, 4)
 
+// Variants of the backward kernels: a lane also holds the adjoints of its entries, so the subtrees are smaller.
+#define SG_BWD_VARIANTS(X)                                                                                 \
+    X(2, 4, 1) X(2, 3, 1) X(2, 2, 1) X(2, 1, 1)                                                            \
+    X(3, 3, 1) X(3, 2, 1) X(3, 1, 1)                                                                       \
+    X(4, 2, 1) X(4, 1, 1)                                                                                  \
+    X(5, 2, 1) X(5, 1, 1) X(6, 2, 1) X(6, 1, 1) X(7, 1, 1) X(8, 1, 1) X(9, 1, 1)                           \
+    X(10, 1, 2) X(11, 1, 2) X(12, 1, 2) X(13, 1, 2) X(14, 1, 2) X(15, 1, 2) X(16, 1, 2) X(17, 1, 2)
+constexpr int kBwdLongPrefixMaxD = 5;   // as kLongPrefixMaxD, for the backward variants
+constexpr int kBwdMaxRuntimeD = 1024;   // run-time channel count kernel, backward: per-channel sums of a wave live in LDS
+
 struct Variant { int D, M, S; };
 #define SG_ROW(D, M, S) {D, M, S},
 constexpr Variant kVariants[] = {SG_VARIANTS(SG_ROW)};
+constexpr Variant kBwdVariants[] = {SG_BWD_VARIANTS(SG_ROW)};
 #undef SG_ROW
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -58,6 +69,11 @@ struct Plan {
     int64_t sig_len = 0;  // entries per path, level 0 included
     int io_elem = 8;
     size_t off_dz = 0, off_out = 0, total = 0;
+    // backward
+    bool backward = false;
+    size_t lds_wave = 0;      // doubles of LDS per wave
+    size_t lds_bytes = 0;
+    size_t off_gz = 0, off_sig = 0, off_gout = 0;
 };
 
 // entries of levels 0..N over D channels; 0 if that does not fit in 2^40
@@ -78,10 +94,13 @@ inline int64_t sig_length(int64_t D, int N)
 }
 
 // force_M >= 0 picks the variant with that owned depth (diagnostics and tests); -1 = the estimate below decides
+// backward: the plan of signature_bwd (have_sig: the caller passes the signatures, else they are computed into the
+// workspace first, with the forward plan for the same arguments)
 inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, bool lead_lag, bool io_double,
-                      int force_M = -1)
+                      int force_M = -1, bool backward = false, bool have_sig = false)
 {
     Plan p;
+    p.backward = backward;
     p.B = B; p.L = L; p.d = (int)d; p.N = N;
     p.io_elem = io_double ? 8 : 4;
     const int64_t D = (lead_lag ? 2 * d : d) + (time_aug ? 1 : 0);
@@ -96,7 +115,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     auto lanes = [&](int M, int S, int64_t& LP, int& Q, int& NB) -> bool {
         Q = N - M - 1;
         if (Q < 0 || Q > kQMax) return false;
-        if (Q > kQExact && M > 0 && D > kLongPrefixMaxD) return false;
+        if (Q > kQExact && M > 0 && D > (backward ? kBwdLongPrefixMaxD : kLongPrefixMaxD)) return false;
         NB = (int)((D + S - 1) / S);
         LP = NB;
         for (int i = 0; i < Q; ++i) {
@@ -112,7 +131,10 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     // waves of the launch are spread over kSimds SIMDs.
     bool have = false;
     double best = 0.0;
-    for (const Variant& v : kVariants) {
+    const Variant* list = backward ? kBwdVariants : kVariants;
+    const size_t nlist = backward ? sizeof(kBwdVariants) / sizeof(Variant) : sizeof(kVariants) / sizeof(Variant);
+    for (size_t vi = 0; vi < nlist; ++vi) {
+        const Variant& v = list[vi];
         if (v.D != D || (force_M >= 0 && v.M != force_M)) continue;
         int64_t LP; int Q, NB;
         if (!lanes(v.M, v.S, LP, Q, NB)) continue;
@@ -147,7 +169,20 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     p.off_dz = off;
     off = align_up(off + (size_t)B * (size_t)p.np * p.Dpad * sizeof(double), 256);
     p.off_out = off;
-    if (!io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+    if (!backward) {
+        if (!io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+    } else {
+        if (p.DT == 0 && D > kBwdMaxRuntimeD) { p.why = "backward: more than 1024 channels"; return p; }
+        const bool uniform = p.DT > 0 && p.M > 0;
+        p.lds_wave = (size_t)p.Dpad + (uniform ? (size_t)kWave * (size_t)(D | 1) : 0);
+        p.lds_bytes = (size_t)kWavesPerWG * p.lds_wave * sizeof(double);
+        p.off_gz = off;      // dF/dz, one row per stored increment row
+        off = align_up(off + (size_t)B * (size_t)p.np * p.Dpad * sizeof(double), 256);
+        p.off_sig = off;     // signatures in double: computed here, or converted from a float caller's
+        if (!have_sig || !io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+        p.off_gout = off;    // float callers: the upstream gradient in double
+        if (!io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+    }
     p.total = off < 256 ? 256 : off;
     p.valid = true;
     return p;

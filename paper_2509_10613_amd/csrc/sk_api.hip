@@ -504,7 +504,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
 
 namespace {
 
-int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::Plan* plan)
+int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::Plan* plan, bool backward = false,
+                 bool have_sig = false)
 {
     if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
     if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG | SK_SIG_DEPTH_MASK)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
@@ -515,8 +516,8 @@ int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::
     if (L > ((int64_t)1 << 29) || d > 32768 || N > 64 || B > ((int64_t)1 << 40))
         return fail(SK_ERR_SHAPE, "L above 2^29, d above 32768, N above 64 or B above 2^40");
     *plan = sg::make_plan(B, L, d, N, (flags & SK_FLAG_TIME_AUG) != 0, (flags & SK_FLAG_LEAD_LAG) != 0, dt == SK_F64,
-                          force_M);
-    if (!plan->valid) return fail(SK_ERR_SHAPE, "signature_fwd: %s", plan->why);
+                          force_M, backward, have_sig);
+    if (!plan->valid) return fail(SK_ERR_SHAPE, "%s: %s", backward ? "signature_bwd" : "signature_fwd", plan->why);
     return SK_OK;
 }
 
@@ -562,6 +563,78 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
     return SK_OK;
 }
 
+// grad_x from the signatures and the upstream gradient.  The forward plan `pf` is used when the signatures have to be
+// computed first (into the backward workspace).
+template <typename T>
+int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, const void* sig, const void* grad_out,
+                      void* grad_x, int flags, void* ws, hipStream_t st)
+{
+    constexpr bool kIsDouble = sizeof(T) == 8;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    hipError_t e;
+#define SK_CHECK(call)                                                                         \
+    do {                                                                                       \
+        e = (call);                                                                            \
+        if (e != hipSuccess) return fail(SK_ERR_HIP, "%s: %s", #call, hipGetErrorString(e));   \
+    } while (0)
+    double* dz = reinterpret_cast<double*>(base + p.off_dz);
+    double* gz = reinterpret_cast<double*>(base + p.off_gz);
+    const long count = p.B * p.sig_len;
+    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, p.np,
+                                      (flags & SK_FLAG_TIME_AUG) ? 1 : 0, (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
+    SK_CHECK(sk::launch_fill<double>(gz, p.B * p.np * p.Dpad, 0.0, st));
+    const double* sig64;
+    if (!sig) {
+        sg::Args f;
+        f.dz = dz;
+        f.out = reinterpret_cast<double*>(base + p.off_sig);
+        f.B = pf.B; f.n = pf.n; f.np = pf.np; f.D = pf.D; f.Dpad = pf.Dpad; f.N = pf.N; f.Q = pf.Q; f.NB = pf.NB;
+        f.LP = pf.LP; f.WP = pf.WP; f.sig_len = pf.sig_len;
+        SK_CHECK(sg::launch_horner(pf.DT, pf.M, pf.S, f, pf.grid, st));
+        sig64 = f.out;
+    } else if (kIsDouble) {
+        sig64 = static_cast<const double*>(sig);
+    } else {
+        double* s64 = reinterpret_cast<double*>(base + p.off_sig);
+        SK_CHECK((sk::launch_convert<T, double>(static_cast<const T*>(sig), s64, count, st)));
+        sig64 = s64;
+    }
+    const double* gout64;
+    if (kIsDouble) {
+        gout64 = static_cast<const double*>(grad_out);
+    } else {
+        double* g64 = reinterpret_cast<double*>(base + p.off_gout);
+        SK_CHECK((sk::launch_convert<T, double>(static_cast<const T*>(grad_out), g64, count, st)));
+        gout64 = g64;
+    }
+    sg::BwdArgs a;
+    a.dz = dz; a.gz = gz; a.sig = sig64; a.gout = gout64;
+    a.B = p.B; a.n = p.n; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
+    a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.lds_wave = p.lds_wave;
+    bool timed = false;
+    TimedLaunch tl{};
+    {
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        timed = g_timing_on;
+    }
+    if (timed) {
+        SK_CHECK(hipEventCreate(&tl.start));
+        SK_CHECK(hipEventCreate(&tl.stop));
+        tl.backward = 1;
+        SK_CHECK(hipEventRecord(tl.start, st));
+    }
+    SK_CHECK(sg::launch_horner_bwd(p.DT, p.M, p.S, a, p.grid, p.lds_bytes, st));
+    if (timed) {
+        SK_CHECK(hipEventRecord(tl.stop, st));
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        g_timed.push_back(tl);
+    }
+    SK_CHECK(sg::launch_point_gradients<T>(gz, static_cast<T*>(grad_x), p.B, p.L, p.d, p.Dpad, p.np,
+                                           (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
+#undef SK_CHECK
+    return SK_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -592,6 +665,51 @@ int signature_fwd(const void* x, void* out, int64_t B, int64_t L, int64_t d, int
         return fail(SK_ERR_WORKSPACE, "workspace is NULL, misaligned or smaller than %zu bytes", p.total);
     hipStream_t st = static_cast<hipStream_t>(stream);
     return dt == SK_F64 ? run_signature<double>(p, x, out, flags, ws, st) : run_signature<float>(p, x, out, flags, ws, st);
+}
+
+size_t signature_bwd_workspace_bytes(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, int have_sig)
+{
+    sg::Plan p;
+    if (sig_validate(B, L, d, N, flags, (int)dt, &p, true, have_sig != 0) != SK_OK || B == 0) return 0;
+    return p.total;
+}
+
+int signature_bwd(const void* x, const void* sig, const void* grad_out, void* grad_x, int64_t B, int64_t L, int64_t d,
+                  int N, int flags, sk_dtype dt, void* ws, size_t ws_bytes, void* stream)
+{
+    sg::Plan p, pf;
+    int rc = sig_validate(B, L, d, N, flags, (int)dt, &p, true, sig != nullptr);
+    if (rc != SK_OK) return rc;
+    if (B == 0) return SK_OK;
+    if (!x || !grad_out || !grad_x) return fail(SK_ERR_NULL, "x, grad_out or grad_x is NULL");
+    if (!sig) {
+        // the forward launch for the same paths, its output in double whatever the caller's type; a forced subtree
+        // depth applies to the backward kernel only
+        rc = sig_validate(B, L, d, N, flags & ~SK_SIG_DEPTH_MASK, SK_F64, &pf);
+        if (rc != SK_OK) return rc;
+    }
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < p.total)
+        return fail(SK_ERR_WORKSPACE, "workspace is NULL, misaligned or smaller than %zu bytes", p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dt == SK_F64 ? run_signature_bwd<double>(p, pf, x, sig, grad_out, grad_x, flags, ws, st)
+                        : run_signature_bwd<float>(p, pf, x, sig, grad_out, grad_x, flags, ws, st);
+}
+
+int signature_bwd_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, char* out, size_t out_bytes)
+{
+    if (!out || out_bytes == 0) return fail(SK_ERR_NULL, "out is NULL or empty");
+    out[0] = 0;
+    sg::Plan p;
+    int rc = sig_validate(B, L, d, N, flags, (int)dt, &p, true, true);
+    if (rc != SK_OK) return rc;
+    std::snprintf(out, out_bytes,
+                  "kernel=horner_bwd_kernel<%d, %d, %d, %d> channels=%d prefix_letters=%d letter_blocks=%d "
+                  "lanes_per_path=%lld waves_per_path=%lld grid=%lld threads=%d lds_bytes=%zu entries_per_path=%lld "
+                  "workspace_bytes=%zu",
+                  p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.D, p.Q, p.NB, (long long)p.LP, (long long)p.WP,
+                  (long long)p.grid, sg::kWave * sg::kWavesPerWG, p.lds_bytes, (long long)p.sig_len,
+                  B == 0 ? (size_t)0 : p.total);
+    return SK_OK;
 }
 
 int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dtype dt, char* out, size_t out_bytes)

@@ -1,0 +1,147 @@
+"""GPU parity of the gradient of truncated signatures (signature_bwd through the C ABI) against the CPU oracle
+(oracle/signature.py: chain rule with every intermediate signature kept), on the same seeded inputs.
+
+Tolerance: fp64 1e-10, fp32 1e-4, in the sense max|gpu - ref| <= tol * max(1, max|ref|) per gradient tensor (entries
+cross zero, so they are compared against the tensor's scale).  fp32 runs compute in double from the fp32-rounded
+inputs and are compared with the oracle on those inputs.
+"""
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import signature as osig
+from paper_2509_10613_amd import binding as sk
+from paper_2509_10613_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float64: 1e-10, torch.float32: 1e-4}
+
+
+def dev(a, dtype=torch.float64):
+    return torch.tensor(np.asarray(a), dtype=dtype, device="cuda")
+
+
+def host(t):
+    return t.detach().cpu().numpy().astype(np.float64)
+
+
+def paths(seed, B, L, d, scale=0.4):
+    rng = np.random.default_rng(seed)
+    return np.cumsum(rng.normal(0, scale, size=(B, L, d)), axis=1)
+
+
+def check(X, N, flags=0, dtype=torch.float64, give_sig=False, seed=3):
+    B, L, d = X.shape
+    tflags = flags & (sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG)
+    n = sk.signature_length(d, N, tflags)
+    G = np.random.default_rng(seed).normal(0, 1.0, size=(B, n))
+    x, g = dev(X, dtype), dev(G, dtype)
+    print("signature_bwd B=%d L=%d d=%d N=%d flags=%d %s sig=%s: %s" % (
+        B, L, d, N, flags, dtype, give_sig,
+        sk.signature_bwd_describe(B, L, d, N, flags, sk.SK_F64 if dtype == torch.float64 else sk.SK_F32)), flush=True)
+    sig = sk.signature_fwd(x, N, tflags) if give_sig else None
+    got = host(sk.signature_bwd(x, g, N, flags, sig=sig))
+    torch.cuda.synchronize()
+    ref = osig.signature_backward(host(x), host(g), N, tflags)
+    assert got.shape == ref.shape and np.all(np.isfinite(got))
+    scale = max(1.0, np.max(np.abs(ref))) if ref.size else 1.0
+    err = (np.max(np.abs(got - ref)) if ref.size else 0.0) / scale
+    print("  max err / scale %.3e (scale %.3g, tol %.0e)" % (err, scale, TOL[dtype]), flush=True)
+    assert err <= TOL[dtype]
+    return got
+
+
+def bwd_variants():
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2509_10613_amd", "csrc", "sg_plan.h")
+    text = open(hdr).read()
+    body = text[text.index("#define SG_BWD_VARIANTS(X)"):text.index("constexpr int kBwdLongPrefixMaxD")]
+    return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+), (\d+), (\d+)\)", body)]
+
+
+@pytest.mark.parametrize("D,M,S", bwd_variants())
+def test_every_backward_kernel_variant(D, M, S):
+    for Q in (0, 1, 2, 3, 4, 6):
+        N = M + 1 + Q
+        if D ** N > 40000 or (Q > 4 and D > 5):
+            continue
+        L = 5 if D ** N < 5000 else 3
+        desc = sk.signature_bwd_describe(2, L, D, N, sk.SK_SIG_DEPTH(M), sk.SK_F64)
+        assert "horner_bwd_kernel<%d, %d, %d, %d>" % (D, M, S, Q if Q <= 4 else 8) in desc, desc
+        check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=sk.SK_SIG_DEPTH(M))
+
+
+def test_backward_run_time_channel_kernel():
+    for d, N in ((1, 4), (2, 4), (3, 3), (7, 3), (18, 2), (40, 2), (70, 1)):
+        desc = sk.signature_bwd_describe(2, 6, d, N, sk.SK_SIG_DEPTH(0), sk.SK_F64)
+        assert "horner_bwd_kernel<0, 0, 1," in desc, desc
+        check(paths(88 + d, 2, 6, d), N, flags=sk.SK_SIG_DEPTH(0))
+
+
+@pytest.mark.parametrize("B,L,d,N", [(3, 12, 2, 5), (2, 9, 3, 4), (2, 10, 4, 4), (2, 8, 5, 3), (2, 7, 8, 3), (1, 6, 16, 3),
+                                     (3, 4, 2, 1), (2, 16, 6, 3), (130, 7, 3, 5)])
+def test_backward_library_choice_and_given_signatures(B, L, d, N):
+    a = check(paths(300 + d + N, B, L, d), N)
+    b = check(paths(300 + d + N, B, L, d), N, give_sig=True)
+    assert np.max(np.abs(a - b)) <= 1e-12 * max(1.0, np.max(np.abs(a)))
+
+
+@pytest.mark.parametrize("flags", [sk.SK_FLAG_TIME_AUG, sk.SK_FLAG_LEAD_LAG, sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG])
+def test_backward_with_path_transformations(flags):
+    check(paths(21, 3, 9, 2), 4, flags)
+    check(paths(22, 2, 6, 4), 3, flags, give_sig=True)
+    check(paths(23, 2, 5, 8), 2, flags)
+
+
+def test_backward_float32():
+    check(paths(31, 3, 12, 3), 4, dtype=torch.float32)
+    check(paths(32, 2, 8, 16), 3, dtype=torch.float32, give_sig=True)
+    check(paths(33, 2, 8, 2), 3, flags=sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG, dtype=torch.float32)
+
+
+def test_backward_degenerate_shapes_and_errors():
+    got = check(paths(41, 3, 1, 3), 4)           # one point: no gradient
+    assert not got.any()
+    check(paths(42, 2, 2, 3), 5)                 # one segment
+    out = sk.signature_bwd(torch.empty((0, 5, 3), dtype=torch.float64, device="cuda"),
+                           torch.empty((0, 40), dtype=torch.float64, device="cuda"), 3)
+    assert out.shape == (0, 5, 3)
+    got = check(np.ones((2, 6, 4)), 3)           # a constant path still has a gradient (level 1: -g, 0, ..., +g)
+    x = dev(paths(51, 2, 5, 3))
+    g = dev(np.ones((2, 40)))
+    with pytest.raises(sk.SigKernelError):
+        sk.signature_bwd(x, g, 3, flags=2)
+    with pytest.raises(sk.SigKernelError):
+        sk.signature_bwd(x, g, 3, ws=torch.empty((256,), dtype=torch.uint8, device="cuda")[:16])
+    check(paths(53, 2, 5, 3), 3)
+
+
+@pytest.mark.parametrize("name", ["s1", "s2", "s3"])
+def test_backward_benchmark_shapes_sampled(name):
+    # full size of the Table 1 shapes: the oracle computes two paths; every path is checked for translation
+    # invariance (the gradients of its points sum to zero) and against the closed form for the first level
+    (B, L, d, N), X = workloads.make_signature(name)
+    n = sk.signature_length(d, N, 0)
+    rng = np.random.default_rng(9)
+    G = rng.normal(0, 1.0, size=(B, n))
+    x, g = dev(X), dev(G)
+    print(name, sk.signature_bwd_describe(B, L, d, N, 0, sk.SK_F64), flush=True)
+    got = host(sk.signature_bwd(x, g, N))
+    torch.cuda.synchronize()
+    assert got.shape == X.shape and np.all(np.isfinite(got))
+    for b in (0, B - 1):
+        ref = osig.signature_backward(X[b:b + 1], G[b:b + 1], N)[0]
+        scale = max(1.0, np.max(np.abs(ref)))
+        err = np.max(np.abs(got[b] - ref)) / scale
+        print("  path %d: max err / scale %.3e (scale %.3g)" % (b, err, scale), flush=True)
+        assert err <= 1e-10
+    assert np.max(np.abs(got.sum(axis=1))) <= 1e-9 * max(1.0, np.max(np.abs(got)))
+    # only level 1 upstream: gradient is -g at the first point, +g at the last, zero in between
+    G1 = np.zeros((B, n))
+    G1[:, 1:1 + d] = rng.normal(size=(B, d))
+    got1 = host(sk.signature_bwd(x, dev(G1), N))
+    assert np.max(np.abs(got1[:, 0] + G1[:, 1:1 + d])) <= 1e-10 and np.max(np.abs(got1[:, -1] - G1[:, 1:1 + d])) <= 1e-10
+    assert np.max(np.abs(got1[:, 1:-1])) <= 1e-10
