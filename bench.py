@@ -39,10 +39,13 @@ def algorithmic_flops_per_cell(d, time_aug, lam, backward):
 
 
 def bench_signature(args):
-    """Side measurement (not the headline): batched truncated signatures by Horner's scheme (Section 2.3) on the
-    shapes (B, L, d, N) of the paper's Table 1.  A step is one signature_fwd call.  Algorithmic work per path and
-    segment: for every level k, one multiply-add per entry of the nested products of lengths 1..k, that is
-    sum_{k=1..N} sum_{j=1..k} d^j multiply-adds (the divisions by k - j of the scheme are not counted)."""
+    """Side measurement (not the headline): batched truncated signatures by Horner's scheme (Section 2.3) and their
+    gradients (Section 2.4) on the shapes (B, L, d, N) of the paper's Table 1.  A step is one signature_fwd call
+    followed by one signature_bwd call that is handed the signatures.  Algorithmic work per path and segment,
+    forward: for every level k one multiply-add per entry of the nested products of lengths 1..k, that is
+    F = sum_{k=1..N} sum_{j=1..k} d^j multiply-adds (the divisions by k - j of the scheme are not counted);
+    backward: the same step once more with the negated increment, and two multiply-adds of the adjoint for each
+    multiply-add of the step: 3 F."""
     import numpy as np
     import torch
     from paper_2509_10613_amd import binding as sk
@@ -57,10 +60,21 @@ def bench_signature(args):
     x = torch.tensor(X, device=dev)
     entries = sk.signature_length(d, N, flags)
     out = torch.empty((B, entries), dtype=torch.float64, device=dev)
-    ws = torch.empty(max(256, sk.signature_workspace_bytes(B, L, d, N, flags, sk.SK_F64)), dtype=torch.uint8, device=dev)
+    G = torch.tensor(workloads.upstream_weights(78, (B, entries)), device=dev)
+    gx = torch.empty_like(x)
+    ws = torch.empty(max(256, sk.signature_workspace_bytes(B, L, d, N, flags, sk.SK_F64),
+                         int(sk.load().signature_bwd_workspace_bytes(B, L, d, N, flags, sk.SK_F64, 1))),
+                     dtype=torch.uint8, device=dev)
+
+    def fwd_call():
+        sk.signature_fwd(x, N, flags, ws=ws, out=out)
+
+    def bwd_call():
+        sk.signature_bwd(x, G, N, flags, sig=out, ws=ws, grad_x=gx)
 
     def step():
-        sk.signature_fwd(x, N, flags, ws=ws, out=out)
+        fwd_call()
+        bwd_call()
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -80,37 +94,42 @@ def bench_signature(args):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sk.sigkernel_event_timing(False)
-    k_ms, nk, _, _ = sk.sigkernel_event_timing_read()
+    f_ms, nf, b_ms, nb = sk.sigkernel_event_timing_read()
     sec = (t1 - t0) / args.steps
     fma = sum(sum(D ** j for j in range(1, k + 1)) for k in range(1, N + 1))
-    flops = 2.0 * fma * B * n
-    kern_ms = k_ms / max(nk, 1)
-    achieved = flops / (kern_ms * 1e-3) / 1e12
-    desc = sk.signature_describe(B, L, d, N, flags, sk.SK_F64)
+    fwd_ms, bwd_ms = f_ms / max(nf, 1), b_ms / max(nb, 1)
+    flops = 2.0 * 3.0 * fma * B * n            # the backward kernel, the dominant one
+    achieved = flops / (bwd_ms * 1e-3) / 1e12
+    fwd_frac = 2.0 * fma * B * n / (fwd_ms * 1e-3) / 1e12 / FP64_VECTOR_PEAK_TFLOPS
+    desc = sk.signature_bwd_describe(B, L, d, N, flags, sk.SK_F64)
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import signature as osig
-        nb, spent = 0, 0.0
-        while spent < args.cpu_seconds and nb < B:
+        Gh = G.cpu().numpy()
+        npaths, spent = 0, 0.0
+        while spent < args.cpu_seconds and npaths < B:
             a = time.perf_counter()
-            osig.signature(X[nb:nb + 1], N, flags)
+            osig.signature(X[npaths:npaths + 1], N, flags)
+            osig.signature_backward(X[npaths:npaths + 1], Gh[npaths:npaths + 1], N, flags)
             spent += time.perf_counter() - a
-            nb += 1
-        cpu = {"value": nb * n * (entries - 1) / spent, "unit": "entry updates/s", "cores": 1, "kind": "oracle",
-               "sample": "%d paths of %s, %.1f s (numpy, full tensor products)" % (nb, args.workload, spent)}
+            npaths += 1
+        cpu = {"value": npaths * n * (entries - 1) / spent, "unit": "entry updates/s", "cores": 1, "kind": "oracle",
+               "sample": "%d paths of %s, fwd+bwd, %.1f s (numpy, full tensor products)" % (npaths, args.workload, spent)}
     print(json.dumps({
-        "metric": "signature entry updates/s (truncated signatures, Horner), fp64, 1 MI355X",
+        "metric": "signature entry updates/s (truncated signatures by Horner's scheme, fwd+bwd), fp64, 1 MI355X",
         "value": B * n * (entries - 1) / sec, "unit": "entry updates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": "%s: %d paths, L=%d, d=%d, truncation level %d%s, fp64, forward" % (
+        "config": {"workload": "%s: %d paths, L=%d, d=%d, truncation level %d%s, fp64, fwd+bwd" % (
             args.workload, B, L, d, N, ", lead-lag transformed" if args.lead_lag else ""),
             "entries_per_path": entries},
-        "paths_per_s": B / sec, "horner_kernel_ms": kern_ms,
+        "paths_per_s": B / sec, "horner_kernel_ms": fwd_ms, "horner_bwd_kernel_ms": bwd_ms,
+        "fwd_kernel": sk.signature_describe(B, L, d, N, flags, sk.SK_F64).split("kernel=", 1)[1].split(" channels=", 1)[0],
+        "fwd_frac_of_peak": fwd_frac,
         "roofline": {"bound": "alu", "kernel": desc.split("kernel=", 1)[1].split(" channels=", 1)[0],
                      "launch": dict(kv.split("=", 1) for kv in desc.split(" ") if "=" in kv and not kv.startswith("kernel=")),
                      "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "avg_launch_ms": kern_ms, "flops_per_launch": flops,
+                     "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "avg_launch_ms": bwd_ms, "flops_per_launch": flops,
                      "traffic": None},
         "cpu_baseline": cpu}))
 

@@ -17,7 +17,7 @@
  * or a negative SK_ERR_* code with a message in sigkernel_last_error(), nothing enqueued on error.  B = 0 is a
  * successful no-op; a path of one point has the signature (1, 0, ..., 0).
  * flags: SK_FLAG_TIME_AUG and SK_FLAG_LEAD_LAG as in sigkernel.h (Section 4, applied on the fly: the transformed
- * paths are never formed, only their increments), and the diagnostic SK_SIG_DEPTH(m) below; other bits are an error.
+ * paths are never formed, only their increments), and the diagnostics SK_SIG_DEPTH(m), SK_SIG_BLOCK(s) below; other bits are an error.
  * Limits: N >= 1; at most 2^40 entries per path and 2^46 per call; a lane carries the entries at up to 8 prefix
  * letters, which admits every N <= 9 (N <= 14 for two channels); beyond that SK_ERR_SHAPE.
  */
@@ -30,12 +30,13 @@
 extern "C" {
 #endif
 
-/* Diagnostic, for the entry points of this header only: a lane keeps the entries of a
- * subtree of words of depth m in registers; SK_SIG_DEPTH(m), m = 0..5, or-ed into `flags` forces that depth instead
- * of the library's own choice (SK_ERR_SHAPE if no kernel with that depth exists for the shape).  Results do not
- * depend on it beyond rounding order. */
+/* Diagnostics, for the entry points of this header only: a lane keeps the entries of a subtree of words in registers,
+ * a block of s consecutive letters after its prefix and every continuation by up to m more letters.  SK_SIG_DEPTH(m),
+ * m = 0..5, and SK_SIG_BLOCK(s), s = 1..15, or-ed into `flags` force m and s instead of the library's own choice
+ * (SK_ERR_SHAPE if no such kernel exists for the shape).  Results do not depend on them beyond rounding order. */
 #define SK_SIG_DEPTH(m) (((m) + 1) << 8)
-#define SK_SIG_DEPTH_MASK 0xf00
+#define SK_SIG_BLOCK(s) ((s) << 12)
+#define SK_SIG_DEPTH_MASK 0xff00
 
 /* Entries per path of the result for paths of d channels, level 0 included; 0 for invalid arguments or when the
  * count does not fit.  Pure host arithmetic. */

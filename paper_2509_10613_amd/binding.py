@@ -19,6 +19,11 @@ SK_FLAG_LEAD_LAG = 8
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
 
+def SK_SIG_BLOCK(s):
+    """Diagnostic flag of the signature entry points: forces the letter block of a lane."""
+    return s << 12
+
+
 def SK_SIG_DEPTH(m):
     """Diagnostic flag of signature_fwd: forces the depth of the register-resident subtree of a lane."""
     return (m + 1) << 8

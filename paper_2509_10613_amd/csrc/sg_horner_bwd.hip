@@ -7,9 +7,8 @@
 // The adjoint of the step is linear in the incoming adjoints, so the adjoints of the entries at the prefixes of u,
 // which every lane under the prefix carries a copy of, never have to be summed over lanes: each lane carries a share
 // (the upstream value starts in one lane, zero in the others) and the shares add up to the adjoint at every step.
-// Only dF/dz_l is a sum over all lanes of a path: per step a wave adds its lanes' shares in LDS (a transposed sum
-// for the part that belongs to the wave-uniform increments, LDS atomics for the part a lane picked by its own
-// letters) and issues one global atomic per channel.
+// Only dF/dz_l is a sum over all lanes of a path: per step a wave adds its lanes' shares in LDS (each lane a row,
+// summed column by column) and issues one global atomic per channel.
 #include <hip/hip_runtime.h>
 
 #include "sg_dev.h"
@@ -128,6 +127,47 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         for (int r = 0; r < QA; ++r) zu_[r] = (r < QC && has<QC>(r, Q)) ? zp[uR[r]] : 0.0;
     };
 
+    // The sum of dF/dz[row] over the lanes of the wave takes three hops through LDS, and they are spread over three
+    // segments so that no hop waits for the one before it: after segment i the lanes publish their shares of row i
+    // (a row of DS doubles per lane: the shares that belong to the wave-uniform increments are written, the shares a
+    // lane formed with increments it picked by its own letters are added into the same row by LDS atomics, which never
+    // meet another lane's); the rows published after the previous segment are summed column by column by a few lanes
+    // per channel into acc; and the sums that reached acc one segment earlier go out as one global atomic per channel.
+    // LDS executes a wave's instructions in order, which is all the synchronisation this needs.
+    long r1 = -1, r2 = -1;   // row whose shares sit in the lanes' LDS rows / row whose sums sit in acc
+    auto reduce_step = [&](long row_new, const double (&zzb)[DD], const double (&zcb)[S], const double (&zub)[QA]) {
+        constexpr int P = kWave / DD;                  // lanes per channel
+        constexpr int R = (kWave + P - 1) / P;         // LDS rows per lane
+        const bool flush = r2 >= 0, coll = r1 >= 0;
+        const int c = lane % DD, q = lane / DD;
+        double v = 0.0, sum = 0.0;
+        if (flush && lane < DD) v = acc[lane];
+        if (coll && lane < DD * P) {
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const int rw = q * R + i;
+                if (rw < kWave) sum += tr[rw * DS + c];
+            }
+        }
+        if (flush && lane < DD) {
+            acc[lane] = 0.0;
+            atomicAdd(&grow[r2 * a.Dpad + lane], v);
+        }
+        if (coll && lane < DD * P) atomicAdd(&acc[c], sum);
+        if (row_new >= 0) {
+#pragma unroll
+            for (int cc = 0; cc < DD; ++cc) tr[lane * DS + cc] = zzb[cc];
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                if (cok[s]) atomicAdd(&tr[lane * DS + cs[s]], zcb[s]);
+#pragma unroll
+            for (int r = 0; r < QC; ++r)
+                if (has<QC>(r, Q)) atomicAdd(&tr[lane * DS + uR[r]], zub[r]);
+        }
+        r2 = r1;
+        r1 = row_new;
+    };
+
     // one segment backwards; row < 0: the zero increment that starts the loop, nothing to add anywhere
     auto segment = [&](long row, const double (&z_)[DD], const double (&zc_)[S], const double (&zu_)[QA]) {
         // the signature before the segment: the forward step with the increment negated
@@ -150,38 +190,25 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         for (int r = 0; r < QA; ++r) zub[r] = 0.0;
         prefix_levels_rev<QC, QA>(Q, preR, zu_, prb, zub);
         owned_levels_rev<0, DD, M, S, QC, T::TOT, QA>(A, Ab, Q, preR, prb, zu_, zc_, z_, zub, zcb, zzb);
-        if (row < 0) return;
-        // this wave's share of dF/dz[row]
-#pragma unroll
-        for (int s = 0; s < S; ++s)
-            if (cok[s]) atomicAdd(&acc[cs[s]], zcb[s]);
-#pragma unroll
-        for (int r = 0; r < QC; ++r)
-            if (has<QC>(r, Q)) atomicAdd(&acc[uR[r]], zub[r]);
         if constexpr (kUniformZ) {
+            reduce_step(row, zzb, zcb, zub);
+        } else {
+            // run-time channel count: the shares go straight to acc by LDS atomics (lanes with equal letters meet)
+            if (row < 0) return;
 #pragma unroll
-            for (int c = 0; c < DD; ++c) tr[lane * DS + c] = zzb[c];
+            for (int s = 0; s < S; ++s)
+                if (cok[s]) atomicAdd(&acc[cs[s]], zcb[s]);
+#pragma unroll
+            for (int r = 0; r < QC; ++r)
+                if (has<QC>(r, Q)) atomicAdd(&acc[uR[r]], zub[r]);
             __builtin_amdgcn_wave_barrier();
-            constexpr int P = kWave / DD;                  // lanes per channel
-            constexpr int R = (kWave + P - 1) / P;         // rows per lane
-            if (lane < DD * P) {
-                const int c = lane % DD, q = lane / DD;
-                double sum = 0.0;
-#pragma unroll
-                for (int i = 0; i < R; ++i) {
-                    const int rw = q * R + i;
-                    if (rw < kWave) sum += tr[rw * DS + c];
-                }
-                atomicAdd(&acc[c], sum);
+            for (int c = lane; c < D; c += kWave) {
+                const double v = acc[c];
+                acc[c] = 0.0;
+                atomicAdd(&grow[row * a.Dpad + c], v);
             }
+            __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_wave_barrier();
-        for (int c = lane; c < D; c += kWave) {
-            const double v = acc[c];
-            acc[c] = 0.0;
-            atomicAdd(&grow[row * a.Dpad + c], v);
-        }
-        __builtin_amdgcn_wave_barrier();
     };
 
     // Rows np-1 .. 0, two per iteration with two register sets as in the forward kernel; the set carried round the
@@ -199,6 +226,17 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         fetch(row > 0 ? row - 1 : 0, zz, zc, zuR);
         segment(row, zzn, zcn, zuRn);
         rowA = row - 1;
+    }
+    if constexpr (kUniformZ) {
+        double zb0[DD], zb1[S], zb2[QA];
+#pragma unroll
+        for (int c = 0; c < DD; ++c) zb0[c] = 0.0;
+#pragma unroll
+        for (int s = 0; s < S; ++s) zb1[s] = 0.0;
+#pragma unroll
+        for (int r = 0; r < QA; ++r) zb2[r] = 0.0;
+        reduce_step(-1, zb0, zb1, zb2);
+        reduce_step(-1, zb0, zb1, zb2);
     }
 }
 

@@ -36,8 +36,9 @@ constexpr int64_t kSimds = 1024;       // 256 compute units of 4 SIMDs
 #define SG_BWD_VARIANTS(X)                                                                                 \
     X(2, 4, 1) X(2, 3, 1) X(2, 2, 1) X(2, 1, 1)                                                            \
     X(3, 3, 1) X(3, 2, 1) X(3, 1, 1)                                                                       \
-    X(4, 2, 1) X(4, 1, 1)                                                                                  \
-    X(5, 2, 1) X(5, 1, 1) X(6, 2, 1) X(6, 1, 1) X(7, 1, 1) X(8, 1, 1) X(9, 1, 1)                           \
+    X(4, 2, 2) X(4, 2, 1) X(4, 1, 1)                                                                       \
+    X(5, 2, 1) X(5, 1, 1) X(6, 2, 1) X(6, 1, 3) X(6, 1, 1) X(7, 1, 4) X(7, 1, 1) X(8, 1, 4) X(8, 1, 1)     \
+    X(9, 1, 3) X(9, 1, 1)                                                                                  \
     X(10, 1, 2) X(11, 1, 2) X(12, 1, 2) X(13, 1, 2) X(14, 1, 2) X(15, 1, 2) X(16, 1, 2) X(17, 1, 2)
 constexpr int kBwdLongPrefixMaxD = 5;   // as kLongPrefixMaxD, for the backward variants
 constexpr int kBwdMaxRuntimeD = 1024;   // run-time channel count kernel, backward: per-channel sums of a wave live in LDS
@@ -93,11 +94,12 @@ inline int64_t sig_length(int64_t D, int N)
     return tot;
 }
 
-// force_M >= 0 picks the variant with that owned depth (diagnostics and tests); -1 = the estimate below decides
+// force_M >= 0 / force_S > 0 pick the variant with that owned depth / letter block (diagnostics and tests);
+// -1 / 0 = the estimate below decides
 // backward: the plan of signature_bwd (have_sig: the caller passes the signatures, else they are computed into the
 // workspace first, with the forward plan for the same arguments)
 inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, bool lead_lag, bool io_double,
-                      int force_M = -1, bool backward = false, bool have_sig = false)
+                      int force_M = -1, bool backward = false, bool have_sig = false, int force_S = 0)
 {
     Plan p;
     p.backward = backward;
@@ -135,7 +137,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     const size_t nlist = backward ? sizeof(kBwdVariants) / sizeof(Variant) : sizeof(kVariants) / sizeof(Variant);
     for (size_t vi = 0; vi < nlist; ++vi) {
         const Variant& v = list[vi];
-        if (v.D != D || (force_M >= 0 && v.M != force_M)) continue;
+        if (v.D != D || (force_M >= 0 && v.M != force_M) || (force_S > 0 && v.S != force_S)) continue;
         int64_t LP; int Q, NB;
         if (!lanes(v.M, v.S, LP, Q, NB)) continue;
         const int64_t waves = B * ((LP + kWave - 1) / kWave);

@@ -509,14 +509,15 @@ int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::
 {
     if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
     if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG | SK_SIG_DEPTH_MASK)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
-    const int force_M = ((flags & SK_SIG_DEPTH_MASK) >> 8) - 1;
+    const int force_M = ((flags & 0xf00) >> 8) - 1;
+    const int force_S = (flags & 0xf000) >> 12;
     if (B < 0) return fail(SK_ERR_SHAPE, "negative batch size");
     if (L < 1 || d < 1 || N < 1) return fail(SK_ERR_SHAPE, "need L, d, N >= 1 (got %lld, %lld, %d)", (long long)L,
                                              (long long)d, N);
     if (L > ((int64_t)1 << 29) || d > 32768 || N > 64 || B > ((int64_t)1 << 40))
         return fail(SK_ERR_SHAPE, "L above 2^29, d above 32768, N above 64 or B above 2^40");
     *plan = sg::make_plan(B, L, d, N, (flags & SK_FLAG_TIME_AUG) != 0, (flags & SK_FLAG_LEAD_LAG) != 0, dt == SK_F64,
-                          force_M, backward, have_sig);
+                          force_M, backward, have_sig, force_S);
     if (!plan->valid) return fail(SK_ERR_SHAPE, "%s: %s", backward ? "signature_bwd" : "signature_fwd", plan->why);
     return SK_OK;
 }

@@ -69,9 +69,10 @@ def test_every_backward_kernel_variant(D, M, S):
         if D ** N > 40000 or (Q > 4 and D > 5):
             continue
         L = 5 if D ** N < 5000 else 3
-        desc = sk.signature_bwd_describe(2, L, D, N, sk.SK_SIG_DEPTH(M), sk.SK_F64)
+        force = sk.SK_SIG_DEPTH(M) | sk.SK_SIG_BLOCK(S)
+        desc = sk.signature_bwd_describe(2, L, D, N, force, sk.SK_F64)
         assert "horner_bwd_kernel<%d, %d, %d, %d>" % (D, M, S, Q if Q <= 4 else 8) in desc, desc
-        check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=sk.SK_SIG_DEPTH(M))
+        check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=force)
 
 
 def test_backward_run_time_channel_kernel():
