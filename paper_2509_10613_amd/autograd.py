@@ -8,6 +8,7 @@ method happens here.
     K = sig_kernel_gram(X, Y, lam1, lam2, flags)     # X[N,L1,d], Y[M,L2,d] -> K[N,M]
     K = sig_kernel_gram(X, None, lam1, lam2, flags)  # symmetric case K(X, X)
     loss = sig_mmd2(X, Y, lam1, lam2, flags)         # squared MMD between two sets of paths, one library call
+    S = signature(x, N, flags)                       # x[B,L,d] -> truncated signatures [B, entries] (Section 2)
 
 The gradients are first-order only (the backward pass is not itself differentiable).
 """
@@ -86,6 +87,28 @@ class _Mmd2(torch.autograd.Function):
         gX = saved.pop(0) if ctx.have[0] else None
         gY = saved.pop(0) if ctx.have[1] else None
         return (None if gX is None else gX * grad_loss), (None if gY is None else gY * grad_loss), None, None, None
+
+
+class _Signature(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, N, flags):
+        x = x.contiguous()
+        out = sk.signature_fwd(x, N, flags)
+        ctx.save_for_backward(x, out)
+        ctx.args = (N, flags)
+        return out
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        x, out = ctx.saved_tensors
+        N, flags = ctx.args
+        return sk.signature_bwd(x, grad_out.contiguous(), N, flags, sig=out), None, None
+
+
+def signature(x, N, flags=0):
+    """Truncated signatures of device paths x[B,L,d] up to level N, levels 0..N flattened (signature_fwd);
+    differentiable in x (signature_bwd, handed the signatures of the forward call)."""
+    return _Signature.apply(x, N, flags)
 
 
 def sig_mmd2(X, Y, lam1=0, lam2=0, flags=0):

@@ -69,7 +69,7 @@ def kernel_variants():
     import re
     hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2509_10613_amd", "csrc", "sg_plan.h")
     text = open(hdr).read()
-    body = text[text.index("#define SG_VARIANTS(X)"):text.index("struct Variant")]
+    body = text[text.index("#define SG_VARIANTS(X)"):text.index("#define SG_BWD_VARIANTS(X)")]
     return [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+), (\d+), (\d+)\)", body)]
 
 

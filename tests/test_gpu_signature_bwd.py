@@ -146,3 +146,20 @@ def test_backward_benchmark_shapes_sampled(name):
     got1 = host(sk.signature_bwd(x, dev(G1), N))
     assert np.max(np.abs(got1[:, 0] + G1[:, 1:1 + d])) <= 1e-10 and np.max(np.abs(got1[:, -1] - G1[:, 1:1 + d])) <= 1e-10
     assert np.max(np.abs(got1[:, 1:-1])) <= 1e-10
+
+
+def test_autograd_wrapper_gives_the_oracle_gradient():
+    from paper_2509_10613_amd import autograd as ag
+    X = paths(71, 3, 7, 3)
+    N = 4
+    x = dev(X).requires_grad_(True)
+    S = ag.signature(x, N)
+    w = dev(np.random.default_rng(72).normal(size=S.shape))
+    loss = (S * w).sum() + (S[:, 1:4] ** 2).sum()
+    loss.backward()
+    Sh = osig.signature(X, N)
+    assert np.max(np.abs(host(S) - Sh)) <= 1e-10 * max(1.0, np.max(np.abs(Sh)))
+    gout = host(w).copy()
+    gout[:, 1:4] += 2.0 * Sh[:, 1:4]
+    ref = osig.signature_backward(X, gout, N)
+    assert np.max(np.abs(host(x.grad) - ref)) <= 1e-10 * max(1.0, np.max(np.abs(ref)))

@@ -211,3 +211,30 @@ def test_signature_launch_plans(lib):
         binding.signature_describe(1, 3, 3, 13, 0, binding.SK_F64)
     with pytest.raises(binding.SigKernelError):
         binding.signature_describe(1, 3, 16, 4, binding.SK_SIG_DEPTH(2), binding.SK_F64)
+
+
+def test_signature_backward_host_side(lib):
+    one = C.c_void_p(256)
+    f = lib.signature_bwd
+    assert f(one, None, one, one, 4, 8, 3, 3, 0, 7, one, 1 << 20, None) == -4
+    assert f(one, None, one, one, 4, 8, 3, 0, 0, 1, one, 1 << 20, None) == -2
+    assert f(one, None, None, one, 4, 8, 3, 3, 0, 1, one, 1 << 20, None) == -1
+    assert f(one, None, one, one, 4, 8, 3, 3, 0, 1, one, 16, None) == -5
+    assert f(None, None, None, None, 0, 8, 3, 3, 0, 1, None, 0, None) == 0
+    # workspace: increments and their gradients (rows rounded up to an odd count), the signatures when the caller
+    # does not pass them, double copies for float callers
+    n = 1 + 3 + 9 + 27
+    base = 2 * 4 * 7 * 4 * 8
+    w0 = lib.signature_bwd_workspace_bytes(4, 8, 3, 3, 0, 1, 1)
+    w1 = lib.signature_bwd_workspace_bytes(4, 8, 3, 3, 0, 1, 0)
+    w2 = lib.signature_bwd_workspace_bytes(4, 8, 3, 3, 0, 0, 1)
+    assert base <= w0 < base + 1024 and w1 >= w0 + 4 * n * 8 and w2 >= w0 + 2 * 4 * n * 8
+    # launch plans: the backward variants hold entries and adjoints, so the subtrees are smaller than the forward's
+    text = binding.signature_bwd_describe(128, 1024, 16, 4, 0, binding.SK_F64)
+    assert "horner_bwd_kernel<16, 1, 2, 2>" in text and "lanes_per_path=2048" in text and "grid=1024" in text
+    assert "horner_bwd_kernel<8, 1, 4, 3>" in binding.signature_bwd_describe(128, 512, 8, 5, 0, binding.SK_F64)
+    assert "horner_bwd_kernel<0, 0, 1, 2>" in binding.signature_bwd_describe(4, 9, 20, 3, 0, binding.SK_F64)
+    lds = int(re.search(r"lds_bytes=(\d+)", text).group(1))
+    assert lds == 4 * (16 + 64 * 17) * 8
+    with pytest.raises(binding.SigKernelError):
+        binding.signature_bwd_describe(4, 9, 2000, 2, 0, binding.SK_F64)    # beyond the run-time kernel's channel limit
