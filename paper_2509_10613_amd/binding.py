@@ -24,6 +24,11 @@ def SK_SIG_BLOCK(s):
     return s << 12
 
 
+def SK_SIG_PIECES(q):
+    """Diagnostic flag of signature_fwd: cut every path into 2^q pieces (q = 0: never)."""
+    return (q + 1) << 16
+
+
 def SK_SIG_DEPTH(m):
     """Diagnostic flag of signature_fwd: forces the depth of the register-resident subtree of a lane."""
     return (m + 1) << 8

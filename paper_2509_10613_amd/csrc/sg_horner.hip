@@ -153,21 +153,25 @@ __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_kernel(const Args 
 
 // Increments of the transformed paths (Section 4), one row of Dpad doubles per segment: channels of the path (after
 // the lead-lag transform: lead half, then lag half; a segment of the transformed path moves one half only, the lead
-// first), then the time channel 1/n if asked for, then zero padding.
+// first), then the time channel 1/n if asked for, then zero padding.  A path is stored as P pieces of np rows: piece p
+// holds the segments p Lc .. p Lc + Lc - 1 (those below n), then zero rows.
 template <typename TI>
 __global__ __launch_bounds__(256) void increments_kernel(const TI* __restrict__ x, double* __restrict__ dz, long B, long L,
-                                                         int d, int D, int Dpad, long n, long np, int time_aug,
-                                                         int lead_lag)
+                                                         int d, int D, int Dpad, long n, int P, long Lc, long np,
+                                                         int time_aug, int lead_lag)
 {
-    const long total = B * np * Dpad;
+    const long total = B * P * np * Dpad;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const int c = (int)(i % Dpad);
         const long bs = i / Dpad;
-        const long s = bs % np;
-        const long b = bs / np;
+        const long j = bs % np;
+        const long bp = bs / np;
+        const long piece = bp % P;
+        const long b = bp / P;
+        const long s = piece * Lc + j;
         double v = 0.0;
-        if (s >= n) {
-            // a zero row that makes the count odd
+        if (j >= Lc || s >= n) {
+            // a zero row: past the piece or past the path
         } else if (time_aug && c == D - 1) {
             v = 1.0 / (double)n;
         } else if (c < D) {
@@ -186,6 +190,46 @@ __global__ __launch_bounds__(256) void increments_kernel(const TI* __restrict__ 
             }
         }
         dz[i] = v;
+    }
+}
+
+// Chen's identity (Proposition 2.2) for pairs of neighbouring pieces: out[i] = in[2 i] (x) in[2 i + 1], truncated at
+// level N; entry w of level k is sum_{j=0..k} A[first j letters of w] B[last k - j letters of w].  One thread per entry.
+__global__ __launch_bounds__(256) void chen_pairs_kernel(const double* __restrict__ in, double* __restrict__ out, long pairs,
+                                                         int D, int N, long sig_len)
+{
+    const unsigned Du = (unsigned)D;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < sig_len; e += (long)gridDim.x * blockDim.x) {
+        // level k and word number of entry e (32-bit arithmetic: a signature here has fewer than 2^31 entries)
+        int k = 0;
+        unsigned at = 0, pw = 1;            // start of level k, D^k
+        while ((unsigned)e >= at + pw) {
+            at += pw;
+            pw *= Du;
+            ++k;
+        }
+        for (long pr = blockIdx.y; pr < pairs; pr += gridDim.y) {
+            const double* A = in + 2 * pr * sig_len;
+            const double* Bm = A + sig_len;
+            // t = 0 .. k letters go to the second factor: the prefix of k - t letters has the number w / D^t, the
+            // suffix the number w % D^t; one letter moves over per term
+            unsigned pre = (unsigned)e - at, suf = 0, div = 1;
+            unsigned at_pre = at;      // start of level k - t
+            unsigned pw_pre = pw;      // D^(k - t)
+            unsigned at_suf = 0;       // start of level t
+            double acc = 0.0;
+            for (int t = 0; t <= k; ++t) {
+                acc = __builtin_fma(A[at_pre + pre], Bm[at_suf + suf], acc);
+                const unsigned q = pre / Du;
+                suf += (pre - q * Du) * div;
+                pre = q;
+                at_suf += div;
+                div *= Du;
+                pw_pre /= Du;
+                at_pre -= pw_pre;
+            }
+            out[pr * sig_len + e] = acc;
+        }
     }
 }
 
@@ -228,21 +272,32 @@ hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStre
     return hipErrorInvalidValue;
 }
 
-template <typename TI>
-hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, long np,
-                             int time_aug, int lead_lag, hipStream_t st)
+hipError_t launch_chen_pairs(const double* in, double* out, long pairs, int D, int N, long sig_len, hipStream_t st)
 {
-    if (np < n || (np > 0 && !(np & 1))) return hipErrorInvalidValue;
-    const long total = B * np * Dpad;
-    if (total <= 0) return hipSuccess;
-    long grid = (total + 255) / 256;
-    if (grid > 65536) grid = 65536;
-    hipLaunchKernelGGL((increments_kernel<TI>), dim3((unsigned)grid), dim3(256), 0, st, x, dz, B, L, d, D, Dpad, n, np,
-                       time_aug, lead_lag);
+    if (pairs <= 0 || sig_len <= 0) return hipSuccess;
+    if (sig_len >= (1L << 31) || D < 1) return hipErrorInvalidValue;
+    long gx = (sig_len + 255) / 256;
+    if (gx > 65536) gx = 65536;
+    const long gy = pairs < 65535 ? pairs : 65535;
+    hipLaunchKernelGGL(chen_pairs_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st, in, out, pairs, D, N, sig_len);
     return hipGetLastError();
 }
 
-template hipError_t launch_increments<float>(const float*, double*, long, long, int, int, int, long, long, int, int, hipStream_t);
-template hipError_t launch_increments<double>(const double*, double*, long, long, int, int, int, long, long, int, int, hipStream_t);
+template <typename TI>
+hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, int P, long Lc,
+                             long np, int time_aug, int lead_lag, hipStream_t st)
+{
+    if (P < 1 || np < Lc || P * Lc < n || (np > 0 && !(np & 1))) return hipErrorInvalidValue;
+    const long total = B * P * np * Dpad;
+    if (total <= 0) return hipSuccess;
+    long grid = (total + 255) / 256;
+    if (grid > 65536) grid = 65536;
+    hipLaunchKernelGGL((increments_kernel<TI>), dim3((unsigned)grid), dim3(256), 0, st, x, dz, B, L, d, D, Dpad, n, P, Lc,
+                       np, time_aug, lead_lag);
+    return hipGetLastError();
+}
+
+template hipError_t launch_increments<float>(const float*, double*, long, long, int, int, int, long, int, long, long, int, int, hipStream_t);
+template hipError_t launch_increments<double>(const double*, double*, long, long, int, int, int, long, int, long, long, int, int, hipStream_t);
 
 }  // namespace sg

@@ -39,7 +39,10 @@ hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int 
                                   hipStream_t st);
 
 template <typename TI>
-hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, long np,
-                             int time_aug, int lead_lag, hipStream_t st);
+hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, int P, long Lc,
+                             long np, int time_aug, int lead_lag, hipStream_t st);
+
+// out[i] = in[2 i] (x) in[2 i + 1] for i < pairs, signatures of sig_len entries (levels 0..N over D channels)
+hipError_t launch_chen_pairs(const double* in, double* out, long pairs, int D, int N, long sig_len, hipStream_t st);
 
 }  // namespace sg

@@ -23,6 +23,8 @@ constexpr int kQMax = 8;            // longest carried prefix
 constexpr int kQExact = 4;          // prefix lengths with code of their own
 constexpr int kLongPrefixMaxD = 9;   // channel counts whose variants also exist for prefixes longer than kQExact
 constexpr int64_t kSimds = 1024;       // 256 compute units of 4 SIMDs
+constexpr int kMinPiece = 32;          // fewest segments a piece of a path is cut down to
+constexpr int kMaxPieces = 1024;
 
 // (channels, owned depth M, letter block S), per channel count in order of falling register use.
 #define SG_VARIANTS(X)                                                                                     \
@@ -59,7 +61,10 @@ struct Plan {
     int D = 0;            // channels after the transformations
     int N = 0;
     int64_t n = 0;        // segments after the transformations
-    int64_t np = 0;       // increment rows stored per path: n rounded up to an odd number (the extra row is zero)
+    int64_t np = 0;       // increment rows stored per piece: its segments, then zero rows up to an odd count
+    int P = 1;            // pieces per path (forward only): the signatures of the pieces are multiplied afterwards
+    int64_t Lc = 0;       // segments per piece
+    int64_t VB = 0;       // pieces in the batch: B * P, each one a path of its own to the Horner kernel
     int DT = 0;           // kernel template channel count (0: run-time channel count, M = 0, S = 1)
     int M = 0, S = 1, Q = 0, NB = 1;
     int64_t LP = 0;       // lanes per path: D^Q * NB
@@ -70,6 +75,7 @@ struct Plan {
     int64_t sig_len = 0;  // entries per path, level 0 included
     int io_elem = 8;
     size_t off_dz = 0, off_out = 0, total = 0;
+    size_t off_t0 = 0, off_t1 = 0;   // signatures of the pieces and of their pairwise products (P > 1)
     // backward
     bool backward = false;
     size_t lds_wave = 0;      // doubles of LDS per wave
@@ -99,7 +105,8 @@ inline int64_t sig_length(int64_t D, int N)
 // backward: the plan of signature_bwd (have_sig: the caller passes the signatures, else they are computed into the
 // workspace first, with the forward plan for the same arguments)
 inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, bool lead_lag, bool io_double,
-                      int force_M = -1, bool backward = false, bool have_sig = false, int force_S = 0)
+                      int force_M = -1, bool backward = false, bool have_sig = false, int force_S = 0,
+                      int force_P = 0)   // force_P: 0 = the plan decides, else the number of pieces (a power of two)
 {
     Plan p;
     p.backward = backward;
@@ -108,7 +115,9 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     const int64_t D = (lead_lag ? 2 * d : d) + (time_aug ? 1 : 0);
     p.D = (int)D;
     p.n = L < 1 ? 0 : (lead_lag ? 2 * (L - 1) : L - 1);
+    p.Lc = p.n;
     p.np = p.n == 0 ? 0 : (p.n | 1);
+    p.VB = B;
     p.sig_len = sig_length(D, N);
     if (p.sig_len == 0) { p.why = "the signature has more than 2^40 entries per path"; return p; }
     if (B > 0 && p.sig_len > ((int64_t)1 << 46) / B) { p.why = "the batch of signatures has more than 2^46 entries"; return p; }
@@ -126,53 +135,84 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
         }
         return true;
     };
-    // The variant with the least estimated time.  A lane executes about `instr` vector instructions per step: the
-    // multiply-adds of its owned levels and their chains, the chains over the carried prefix for each owned level,
-    // the updates of the carried entries, and a fixed part for loads and loop control.  A SIMD issues one such
-    // instruction per 4 clocks when it has several waves and per about 5 clocks when it has a single one, and the
-    // waves of the launch are spread over kSimds SIMDs.
-    bool have = false;
-    double best = 0.0;
-    const Variant* list = backward ? kBwdVariants : kVariants;
-    const size_t nlist = backward ? sizeof(kBwdVariants) / sizeof(Variant) : sizeof(kVariants) / sizeof(Variant);
-    for (size_t vi = 0; vi < nlist; ++vi) {
-        const Variant& v = list[vi];
-        if (v.D != D || (force_M >= 0 && v.M != force_M) || (force_S > 0 && v.S != force_S)) continue;
-        int64_t LP; int Q, NB;
-        if (!lanes(v.M, v.S, LP, Q, NB)) continue;
-        const int64_t waves = B * ((LP + kWave - 1) / kWave);
-        double owned = 0.0, lvl = v.S, sum = 0.0;
-        for (int m = 0; m <= v.M; ++m) {
-            sum += lvl;        // nodes of levels 0..m
-            owned += sum;      // the update of owned level m touches all of them once
-            lvl *= (double)D;
+    auto choose = [&](int64_t Bsel) -> bool {
+        // The variant with the least estimated time.  A lane executes about `instr` vector instructions per step: the
+        // multiply-adds of its owned levels and their chains, the chains over the carried prefix for each owned level,
+        // the updates of the carried entries, and a fixed part for loads and loop control.  A SIMD issues one such
+        // instruction per 4 clocks when it has several waves and per about 5 clocks when it has a single one, and the
+        // waves of the launch are spread over kSimds SIMDs.
+        bool have = false;
+        double best = 0.0;
+        const Variant* list = backward ? kBwdVariants : kVariants;
+        const size_t nlist = backward ? sizeof(kBwdVariants) / sizeof(Variant) : sizeof(kVariants) / sizeof(Variant);
+        for (size_t vi = 0; vi < nlist; ++vi) {
+            const Variant& v = list[vi];
+            if (v.D != D || (force_M >= 0 && v.M != force_M) || (force_S > 0 && v.S != force_S)) continue;
+            int64_t LP; int Q, NB;
+            if (!lanes(v.M, v.S, LP, Q, NB)) continue;
+            const int64_t waves = Bsel * ((LP + kWave - 1) / kWave);
+            double owned = 0.0, lvl = v.S, sum = 0.0;
+            for (int m = 0; m <= v.M; ++m) {
+                sum += lvl;        // nodes of levels 0..m
+                owned += sum;      // the update of owned level m touches all of them once
+                lvl *= (double)D;
+            }
+            const double instr = owned + (v.M + 1) * (2.0 * Q + 1.0) + (double)Q * Q + 12.0;
+            const double rounds = (double)((waves + kSimds - 1) / kSimds);
+            const double cost = rounds * instr * (waves <= kSimds ? 5.0 : 4.0);
+            if (!have || cost < best) {
+                best = cost;
+                p.DT = v.D; p.M = v.M; p.S = v.S; p.Q = Q; p.NB = NB; p.LP = LP;
+                have = true;
+            }
         }
-        const double instr = owned + (v.M + 1) * (2.0 * Q + 1.0) + (double)Q * Q + 12.0;
-        const double rounds = (double)((waves + kSimds - 1) / kSimds);
-        const double cost = rounds * instr * (waves <= kSimds ? 5.0 : 4.0);
-        if (!have || cost < best) {
-            best = cost;
-            p.DT = v.D; p.M = v.M; p.S = v.S; p.Q = Q; p.NB = NB; p.LP = LP;
-            have = true;
+        if (!have && force_M > 0) { p.why = "no kernel with the requested subtree depth for this number of channels and level"; return false; }
+        if (!have) {
+            int64_t LP; int Q, NB;
+            if (!lanes(0, 1, LP, Q, NB)) { p.why = "truncation level too high for this number of channels (a lane carries at most 8 prefix letters)"; return false; }
+            p.DT = 0; p.M = 0; p.S = 1; p.Q = Q; p.NB = NB; p.LP = LP;
+        }
+        p.WP = (p.LP + kWave - 1) / kWave;
+        return true;
+    };
+    if (!choose(B)) return p;
+    // Few long paths leave most SIMDs without a wave: cut every path into P pieces of Lc segments, let the Horner
+    // kernel treat the pieces as paths, and multiply the signatures of the pieces pairwise afterwards (Chen's identity,
+    // Proposition 2.2).  Forward only.
+    if (!backward && p.n > 0) {
+        int P = 1;
+        if (force_P > 0) {
+            P = force_P;
+        } else if (B > 0 && B * p.WP < kSimds && p.n >= 2 * kMinPiece && p.sig_len < ((int64_t)1 << 31)) {
+            while (P < kMaxPieces && B * p.WP * P < 2 * kSimds && p.n / (2 * P) >= kMinPiece) P *= 2;
+        }
+        if (P > 1) {
+            if ((P & (P - 1)) != 0 || P > kMaxPieces) { p.why = "the number of pieces must be a power of two up to 1024"; return p; }
+            if (p.sig_len >= ((int64_t)1 << 31)) { p.why = "paths are cut into pieces only for signatures of fewer than 2^31 entries"; return p; }
+            if (B > 0 && (p.sig_len > ((int64_t)1 << 44) / (B * P))) { p.why = "too many pieces for this signature size"; return p; }
+            p.P = P;
+            p.Lc = (p.n + P - 1) / P;
+            p.np = p.Lc | 1;
+            p.VB = B * P;
+            if (!choose(p.VB)) return p;
         }
     }
-    if (!have && force_M > 0) { p.why = "no kernel with the requested subtree depth for this number of channels and level"; return p; }
-    if (!have) {
-        int64_t LP; int Q, NB;
-        if (!lanes(0, 1, LP, Q, NB)) { p.why = "truncation level too high for this number of channels (a lane carries at most 8 prefix letters)"; return p; }
-        p.DT = 0; p.M = 0; p.S = 1; p.Q = Q; p.NB = NB; p.LP = LP;
-    }
-    p.WP = (p.LP + kWave - 1) / kWave;
-    p.waves = B * p.WP;
+    p.waves = p.VB * p.WP;
     p.grid = (p.waves + kWavesPerWG - 1) / kWavesPerWG;
     if (p.grid > 0x7fffffffLL) { p.why = "too many workgroups"; return p; }
     p.Dpad = (int)align_up((size_t)D, 2);
     size_t off = 0;
     p.off_dz = off;
-    off = align_up(off + (size_t)B * (size_t)p.np * p.Dpad * sizeof(double), 256);
+    off = align_up(off + (size_t)p.VB * (size_t)p.np * p.Dpad * sizeof(double), 256);
     p.off_out = off;
     if (!backward) {
         if (!io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+        if (p.P > 1) {
+            p.off_t0 = off;
+            off = align_up(off + (size_t)p.VB * (size_t)p.sig_len * sizeof(double), 256);
+            p.off_t1 = off;
+            off = align_up(off + (size_t)(p.VB / 2) * (size_t)p.sig_len * sizeof(double), 256);
+        }
     } else {
         if (p.DT == 0 && D > kBwdMaxRuntimeD) { p.why = "backward: more than 1024 channels"; return p; }
         const bool uniform = p.DT > 0 && p.M > 0;

@@ -511,13 +511,17 @@ int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::
     if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG | SK_SIG_DEPTH_MASK)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
     const int force_M = ((flags & 0xf00) >> 8) - 1;
     const int force_S = (flags & 0xf000) >> 12;
+    const int split = (flags & 0x1f0000) >> 16;          // SK_SIG_PIECES(log2 P) = (log2 P + 1) << 16
+    const int force_P = split ? (1 << (split - 1)) : 0;
+    if (split > 11) return fail(SK_ERR_SHAPE, "at most 2^10 pieces per path");
+    if (backward && force_P > 1) return fail(SK_ERR_SHAPE, "signature_bwd does not cut paths into pieces");
     if (B < 0) return fail(SK_ERR_SHAPE, "negative batch size");
     if (L < 1 || d < 1 || N < 1) return fail(SK_ERR_SHAPE, "need L, d, N >= 1 (got %lld, %lld, %d)", (long long)L,
                                              (long long)d, N);
     if (L > ((int64_t)1 << 29) || d > 32768 || N > 64 || B > ((int64_t)1 << 40))
         return fail(SK_ERR_SHAPE, "L above 2^29, d above 32768, N above 64 or B above 2^40");
     *plan = sg::make_plan(B, L, d, N, (flags & SK_FLAG_TIME_AUG) != 0, (flags & SK_FLAG_LEAD_LAG) != 0, dt == SK_F64,
-                          force_M, backward, have_sig, force_S);
+                          force_M, backward, have_sig, force_S, backward ? 1 : force_P);
     if (!plan->valid) return fail(SK_ERR_SHAPE, "%s: %s", backward ? "signature_bwd" : "signature_fwd", plan->why);
     return SK_OK;
 }
@@ -534,12 +538,13 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
         if (e != hipSuccess) return fail(SK_ERR_HIP, "%s: %s", #call, hipGetErrorString(e));   \
     } while (0)
     double* dz = reinterpret_cast<double*>(base + p.off_dz);
-    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, p.np,
+    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, p.P, p.Lc, p.np,
                                       (flags & SK_FLAG_TIME_AUG) ? 1 : 0, (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
+    double* result = kIsDouble ? static_cast<double*>(out) : reinterpret_cast<double*>(base + p.off_out);
     sg::Args a;
     a.dz = dz;
-    a.out = kIsDouble ? static_cast<double*>(out) : reinterpret_cast<double*>(base + p.off_out);
-    a.B = p.B; a.n = p.n; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
+    a.out = p.P > 1 ? reinterpret_cast<double*>(base + p.off_t0) : result;
+    a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len;
     bool timed = false;
     TimedLaunch tl{};
@@ -554,12 +559,23 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
         SK_CHECK(hipEventRecord(tl.start, st));
     }
     SK_CHECK(sg::launch_horner(p.DT, p.M, p.S, a, p.grid, st));
+    if (p.P > 1) {
+        // the signatures of the pieces, multiplied pairwise until one per path is left (Chen's identity)
+        double* t0 = reinterpret_cast<double*>(base + p.off_t0);
+        double* t1 = reinterpret_cast<double*>(base + p.off_t1);
+        const double* src = t0;
+        for (int cur = p.P; cur > 1; cur /= 2) {
+            double* dst = cur == 2 ? result : (src == t0 ? t1 : t0);
+            SK_CHECK(sg::launch_chen_pairs(src, dst, p.B * (cur / 2), p.D, p.N, p.sig_len, st));
+            src = dst;
+        }
+    }
     if (timed) {
         SK_CHECK(hipEventRecord(tl.stop, st));
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
-    if (!kIsDouble) SK_CHECK((sk::launch_convert<double, T>(a.out, static_cast<T*>(out), p.B * p.sig_len, st)));
+    if (!kIsDouble) SK_CHECK((sk::launch_convert<double, T>(result, static_cast<T*>(out), p.B * p.sig_len, st)));
 #undef SK_CHECK
     return SK_OK;
 }
@@ -581,7 +597,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
     double* dz = reinterpret_cast<double*>(base + p.off_dz);
     double* gz = reinterpret_cast<double*>(base + p.off_gz);
     const long count = p.B * p.sig_len;
-    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, p.np,
+    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, 1, p.n, p.np,
                                       (flags & SK_FLAG_TIME_AUG) ? 1 : 0, (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
     SK_CHECK(sk::launch_fill<double>(gz, p.B * p.np * p.Dpad, 0.0, st));
     const double* sig64;
@@ -686,7 +702,7 @@ int signature_bwd(const void* x, const void* sig, const void* grad_out, void* gr
     if (!sig) {
         // the forward launch for the same paths, its output in double whatever the caller's type; a forced subtree
         // depth applies to the backward kernel only
-        rc = sig_validate(B, L, d, N, flags & ~SK_SIG_DEPTH_MASK, SK_F64, &pf);
+        rc = sig_validate(B, L, d, N, (flags & ~SK_SIG_DEPTH_MASK) | SK_SIG_PIECES(0), SK_F64, &pf);
         if (rc != SK_OK) return rc;
     }
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < p.total)
@@ -722,9 +738,11 @@ int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dty
     if (rc != SK_OK) return rc;
     std::snprintf(out, out_bytes,
                   "kernel=horner_kernel<%d, %d, %d, %d> channels=%d prefix_letters=%d letter_blocks=%d lanes_per_path=%lld "
-                  "waves_per_path=%lld grid=%lld threads=%d entries_per_path=%lld workspace_bytes=%zu",
+                  "waves_per_path=%lld pieces_per_path=%d segments_per_piece=%lld grid=%lld threads=%d "
+                  "entries_per_path=%lld workspace_bytes=%zu",
                   p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.D, p.Q, p.NB, (long long)p.LP, (long long)p.WP,
-                  (long long)p.grid, sg::kWave * sg::kWavesPerWG, (long long)p.sig_len, B == 0 ? (size_t)0 : p.total);
+                  p.P, (long long)p.Lc, (long long)p.grid, sg::kWave * sg::kWavesPerWG, (long long)p.sig_len,
+                  B == 0 ? (size_t)0 : p.total);
     return SK_OK;
 }
 

@@ -94,6 +94,23 @@ def test_run_time_channel_kernel_for_any_channel_count():
         check(paths(77 + d, 2, 6, d), N, flags=sk.SK_SIG_DEPTH(0))
 
 
+def test_paths_cut_into_pieces():
+    # forced: 2, 4 and 8 pieces per path, piece lengths that do not divide the path, pieces left empty, with flags and
+    # in float32; the library's own choice for a few long paths
+    for q, (B, L, d, N) in ((1, (3, 12, 2, 4)), (2, (2, 11, 3, 3)), (3, (2, 9, 3, 3)), (3, (2, 5, 4, 3)), (2, (2, 30, 5, 4)),
+                            (1, (2, 10, 16, 3)), (4, (1, 70, 2, 6)), (2, (2, 2, 3, 3))):
+        desc = sk.signature_describe(B, L, d, N, sk.SK_SIG_PIECES(q), sk.SK_F64)
+        assert "pieces_per_path=%d " % (1 << q) in desc, desc
+        check(paths(500 + 10 * q + d, B, L, d), N, flags=sk.SK_SIG_PIECES(q))
+    check(paths(521, 2, 13, 2), 4, flags=sk.SK_SIG_PIECES(2) | sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG)
+    check(paths(522, 2, 13, 3), 3, flags=sk.SK_SIG_PIECES(2) | sk.SK_FLAG_LEAD_LAG, dtype=torch.float32)
+    assert "pieces_per_path=1 " in sk.signature_describe(2, 400, 3, 3, sk.SK_SIG_PIECES(0), sk.SK_F64)
+    for (B, L, d, N) in ((2, 400, 3, 3), (1, 1500, 2, 5), (3, 257, 5, 3)):
+        desc = sk.signature_describe(B, L, d, N, 0, sk.SK_F64)
+        assert int(desc.split("pieces_per_path=")[1].split(" ")[0]) > 1, desc
+        check(paths(530 + d, B, L, d, 0.1), N)
+
+
 def test_signature_batches_beyond_one_wave_per_simd():
     # many paths: the launch has more waves than the chip has SIMDs, and picks the deepest register-resident subtree
     check(paths(7, 2100, 6, 3, 0.5), 4)
@@ -151,6 +168,8 @@ def test_signature_benchmark_shapes_sampled(name):
     got = host(sk.signature_fwd(x, N))
     torch.cuda.synchronize()
     assert got.shape == (B, osig.sig_length(d, N)) and np.all(np.isfinite(got))
+    whole = host(sk.signature_fwd(x, N, sk.SK_SIG_PIECES(0)))     # uncut paths: the same numbers up to rounding order
+    assert np.max(np.abs(got - whole) / np.maximum(1.0, np.abs(whole))) <= 1e-12
     for b in (0, B // 2 + 1, B - 1):
         ref = osig.signature(X[b:b + 1], N)[0]
         err = np.abs(got[b] - ref) / np.maximum(1.0, np.abs(ref))

@@ -183,13 +183,20 @@ def test_signature_launch_plans(lib):
         vals = {k: int(v) for k, v in re.findall(r"(\w+)=(\d+)", text)}
         return kern, vals
     # the three shapes of Table 1: deepest subtree that still gives every SIMD a wave
-    kern, v = plan(128, 256, 4, 6)
-    assert kern == "horner_kernel<4, 2, 1, 3>" and v["lanes_per_path"] == 256 and v["grid"] == 128
+    kern, v = plan(128, 256, 4, 6)     # too few waves for the chip as whole paths: cut into 4 pieces of 64 segments
+    assert kern == "horner_kernel<4, 2, 1, 3>" and v["lanes_per_path"] == 256 and v["grid"] == 512
+    assert v["pieces_per_path"] == 4 and v["segments_per_piece"] == 64
+    kern, v = plan(128, 256, 4, 6, binding.SK_SIG_PIECES(0))
+    assert kern == "horner_kernel<4, 2, 1, 3>" and v["grid"] == 128 and v["pieces_per_path"] == 1
     kern, v = plan(128, 512, 8, 5)
     assert kern == "horner_kernel<8, 2, 1, 2>" and v["lanes_per_path"] == 512 and v["grid"] == 256
+    assert v["pieces_per_path"] == 1
     kern, v = plan(128, 1024, 16, 4)
     assert kern == "horner_kernel<16, 1, 4, 2>" and v["lanes_per_path"] == 1024 and v["grid"] == 512
-    assert v["entries_per_path"] == 69905
+    assert v["entries_per_path"] == 69905 and v["pieces_per_path"] == 1
+    # the shape of the paper's figure (32 long paths): pieces of at least 32 segments
+    kern, v = plan(32, 1024, 5, 4)
+    assert v["pieces_per_path"] == 16 and v["segments_per_piece"] == 64
     # a large batch prefers the deepest subtree; channel counts without a kernel of their own, and one channel, take
     # the run-time kernel; the transformations change the channel count the plan sees
     assert plan(100000, 50, 3, 8)[0] == "horner_kernel<3, 3, 1, 4>"
