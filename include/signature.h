@@ -17,7 +17,7 @@
  * or a negative SK_ERR_* code with a message in sigkernel_last_error(), nothing enqueued on error.  B = 0 is a
  * successful no-op; a path of one point has the signature (1, 0, ..., 0).
  * flags: SK_FLAG_TIME_AUG and SK_FLAG_LEAD_LAG as in sigkernel.h (Section 4, applied on the fly: the transformed
- * paths are never formed, only their increments), and the diagnostics SK_SIG_DEPTH(m), SK_SIG_BLOCK(s), SK_SIG_PIECES(q) below; other bits are an error.
+ * paths are never formed, only their increments), and the diagnostics SK_SIG_DEPTH(m), SK_SIG_BLOCK(s), SK_SIG_PIECES(q), SK_SIG_ONE_PATH_PER_WAVE below; other bits are an error.
  * Limits: N >= 1; at most 2^40 entries per path and 2^46 per call; a lane carries the entries at up to 8 prefix
  * letters, which admits every N <= 9 (N <= 14 for two channels); beyond that SK_ERR_SHAPE.
  */
@@ -40,7 +40,10 @@ extern "C" {
  * and multiplies their signatures afterwards (Chen's identity, Proposition 2.2).  SK_SIG_PIECES(q), q = 0..10, forces
  * 2^q pieces (q = 0: never cut) instead of the library's own choice. */
 #define SK_SIG_PIECES(q) (((q) + 1) << 16)
-#define SK_SIG_DEPTH_MASK 0x1fff00
+/* signature_fwd lets a wave work on several short paths side by side when a path needs at most half a wave's lanes;
+ * this flag keeps every wave to one path. */
+#define SK_SIG_ONE_PATH_PER_WAVE 0x200000
+#define SK_SIG_DEPTH_MASK 0x3fff00
 
 /* Entries per path of the result for paths of d channels, level 0 included; 0 for invalid arguments or when the
  * count does not fit.  Pure host arithmetic. */

@@ -24,6 +24,9 @@ def SK_SIG_BLOCK(s):
     return s << 12
 
 
+SK_SIG_ONE_PATH_PER_WAVE = 0x200000   # diagnostic flag of signature_fwd: a wave never holds more than one path
+
+
 def SK_SIG_PIECES(q):
     """Diagnostic flag of signature_fwd: cut every path into 2^q pieces (q = 0: never)."""
     return (q + 1) << 16

@@ -41,7 +41,9 @@ __device__ __forceinline__ void store_owned(const double (&A)[TOT], double* out,
 
 // One wave's share of one path, all steps.  DT > 0: D = DT channels, increments of a step in scalar registers.
 // DT == 0: any number of channels, M = 0, S = 1 (a lane owns one word of the top level).
-template <int DT, int M, int S, int QC>
+// SHARED: a wave holds several short paths (lanes per path at most 32): lane groups of LP lanes, each group a path
+// of its own; the increments are then per-lane values and come in by ordinary loads.
+template <int DT, int M, int S, int QC, bool SHARED>
 __device__ __forceinline__ void run(const Args& a)
 {
     constexpr int DD = DT > 0 ? DT : 1;
@@ -55,11 +57,24 @@ __device__ __forceinline__ void run(const Args& a)
     long wg = blockIdx.x;
     if (gridDim.x % kXcds == 0) wg = (long)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
     const long wt = wg * kWavesPerWG + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
-    if (wt >= a.B * a.WP) return;
-    const long b = wt / a.WP;
-    long ti = (wt - b * a.WP) * kWave + lane;
-    const bool valid = ti < a.LP;
-    if (!valid) ti = 0;
+    if (wt >= a.NW) return;
+    long b, ti;
+    bool valid;
+    if constexpr (SHARED) {
+        const int g = lane / (int)a.LP;
+        b = wt * a.PW + g;
+        ti = lane - g * (int)a.LP;
+        valid = g < a.PW && b < a.B;
+        if (!valid) {       // idle lanes follow the wave's first path and write nothing
+            b = wt * a.PW;
+            ti = 0;
+        }
+    } else {
+        b = wt / a.WP;
+        ti = (wt - b * a.WP) * kWave + lane;
+        valid = ti < a.LP;
+        if (!valid) ti = 0;
+    }
     const int blk = (int)(ti % a.NB);
     const long rest = ti / a.NB;      // the prefix u as a number in base D, first letter most significant
     int uR[QA];
@@ -87,10 +102,13 @@ __device__ __forceinline__ void run(const Args& a)
     double zzn[DD], zcn[S], zuRn[QA];
     auto fetch = [&](long step, double (&z_)[DD], double (&zc_)[S], double (&zu_)[QA]) {
         const double* zp = zrow + step * a.Dpad;
-        if constexpr (DT > 0 && M > 0) {
+        if constexpr (DT > 0 && M > 0 && !SHARED) {
             uniform_ptr zs = (uniform_ptr)(zp);
 #pragma unroll
             for (int c = 0; c < DD; ++c) z_[c] = zs[c];
+        } else if constexpr (DT > 0 && M > 0) {
+#pragma unroll
+            for (int c = 0; c < DD; ++c) z_[c] = zp[c];
         }
 #pragma unroll
         for (int s = 0; s < S; ++s) zc_[s] = zp[cs[s]];
@@ -145,10 +163,10 @@ __device__ __forceinline__ void run(const Args& a)
     store_owned<0, DD, M, S, T::TOT>(A, out, at, D, rest * D + blk * S, blk * S);
 }
 
-template <int DT, int M, int S, int QC>
+template <int DT, int M, int S, int QC, bool SHARED>
 __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_kernel(const Args a)
 {
-    run<DT, M, S, QC>(a);
+    run<DT, M, S, QC, SHARED>(a);
 }
 
 // Increments of the transformed paths (Section 4), one row of Dpad doubles per segment: channels of the path (after
@@ -233,26 +251,39 @@ __global__ __launch_bounds__(256) void chen_pairs_kernel(const double* __restric
     }
 }
 
-template <int DT, int M, int S, int QC>
+template <int DT, int M, int S, int QC, bool SHARED>
 hipError_t launch_one(const Args& a, long grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((horner_kernel<DT, M, S, QC>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), 0, st, a);
+    hipLaunchKernelGGL((horner_kernel<DT, M, S, QC, SHARED>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), 0, st, a);
     return hipGetLastError();
 }
 
 // prefix lengths up to kQExact have kernels of their own; longer ones share the kernel that tests against Q, which
-// exists for the channel counts that can reach them (kLongPrefixMaxD)
+// exists for the channel counts that can reach them (kLongPrefixMaxD).  Kernels whose waves hold several paths exist
+// for prefixes up to kSharedMaxQ letters and up to kSharedMaxD channels (beyond that a path fills a wave anyway).
 template <int DT, int M, int S>
 hipError_t launch_variant(const Args& a, long grid, hipStream_t st)
 {
+    if (a.PW > 1) {
+        if constexpr (DT <= kSharedMaxD) {
+            switch (a.Q) {
+            case 0: return launch_one<DT, M, S, 0, true>(a, grid, st);
+            case 1: return launch_one<DT, M, S, 1, true>(a, grid, st);
+            case 2: return launch_one<DT, M, S, 2, true>(a, grid, st);
+            default: return hipErrorInvalidValue;
+            }
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     switch (a.Q) {
-    case 0: return launch_one<DT, M, S, 0>(a, grid, st);
-    case 1: return launch_one<DT, M, S, 1>(a, grid, st);
-    case 2: return launch_one<DT, M, S, 2>(a, grid, st);
-    case 3: return launch_one<DT, M, S, 3>(a, grid, st);
-    case 4: return launch_one<DT, M, S, 4>(a, grid, st);
+    case 0: return launch_one<DT, M, S, 0, false>(a, grid, st);
+    case 1: return launch_one<DT, M, S, 1, false>(a, grid, st);
+    case 2: return launch_one<DT, M, S, 2, false>(a, grid, st);
+    case 3: return launch_one<DT, M, S, 3, false>(a, grid, st);
+    case 4: return launch_one<DT, M, S, 4, false>(a, grid, st);
     default:
-        if constexpr (DT <= kLongPrefixMaxD) return launch_one<DT, M, S, kQMax>(a, grid, st);
+        if constexpr (DT <= kLongPrefixMaxD) return launch_one<DT, M, S, kQMax, false>(a, grid, st);
         else return hipErrorInvalidValue;
     }
 }
@@ -263,6 +294,9 @@ hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStre
 {
     if (grid <= 0) return hipSuccess;
     if ((a.np > 0 && !(a.np & 1)) || a.np < a.n || a.Q < 0 || a.Q > kQMax || a.LP <= 0 || a.WP * kWave < a.LP || a.NB * (long)S < (DT ? DT : a.D))
+        return hipErrorInvalidValue;
+    if (a.PW < 1 || (a.PW > 1 && (a.WP != 1 || a.PW * a.LP > kWave || a.NW * a.PW < a.B)) || (a.PW == 1 && a.NW != a.B * a.WP) ||
+        grid * kWavesPerWG < a.NW)
         return hipErrorInvalidValue;
     if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, st) : hipErrorInvalidValue;
 #define SG_CASE(D_, M_, S_) \

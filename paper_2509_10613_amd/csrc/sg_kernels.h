@@ -16,6 +16,8 @@ struct Args {
     int D, Dpad, N, Q, NB;
     long LP, WP;        // lanes and waves per path
     long sig_len;
+    int PW;             // paths per wave (1, or several short paths side by side in a wave: then WP = 1)
+    long NW;            // waves of the launch
 };
 
 struct BwdArgs {

@@ -25,6 +25,8 @@ constexpr int kLongPrefixMaxD = 9;   // channel counts whose variants also exist
 constexpr int64_t kSimds = 1024;       // 256 compute units of 4 SIMDs
 constexpr int kMinPiece = 32;          // fewest segments a piece of a path is cut down to
 constexpr int kMaxPieces = 1024;
+constexpr int kSharedMaxQ = 2;         // waves that hold several paths: longest prefix and most channels with such kernels
+constexpr int kSharedMaxD = 9;
 
 // (channels, owned depth M, letter block S), per channel count in order of falling register use.
 #define SG_VARIANTS(X)                                                                                     \
@@ -69,6 +71,7 @@ struct Plan {
     int M = 0, S = 1, Q = 0, NB = 1;
     int64_t LP = 0;       // lanes per path: D^Q * NB
     int64_t WP = 0;       // waves per path
+    int PW = 1;           // paths per wave (forward): short paths side by side in one wave
     int64_t waves = 0;
     int64_t grid = 0;
     int Dpad = 0;         // doubles per stored increment row
@@ -106,7 +109,8 @@ inline int64_t sig_length(int64_t D, int N)
 // workspace first, with the forward plan for the same arguments)
 inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, bool lead_lag, bool io_double,
                       int force_M = -1, bool backward = false, bool have_sig = false, int force_S = 0,
-                      int force_P = 0)   // force_P: 0 = the plan decides, else the number of pieces (a power of two)
+                      int force_P = 0,   // force_P: 0 = the plan decides, else the number of pieces (a power of two)
+                      int force_W = 0)   // force_W: 1 = a wave never holds more than one path
 {
     Plan p;
     p.backward = backward;
@@ -150,19 +154,21 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
             if (v.D != D || (force_M >= 0 && v.M != force_M) || (force_S > 0 && v.S != force_S)) continue;
             int64_t LP; int Q, NB;
             if (!lanes(v.M, v.S, LP, Q, NB)) continue;
-            const int64_t waves = Bsel * ((LP + kWave - 1) / kWave);
+            // lane groups of at most half a wave can share a wave (forward kernels for few channels and letters)
+            const int pw = (!backward && LP <= kWave / 2 && Q <= kSharedMaxQ && D <= kSharedMaxD && force_W != 1) ? (int)(kWave / LP) : 1;
+            const int64_t waves = pw > 1 ? (Bsel + pw - 1) / pw : Bsel * ((LP + kWave - 1) / kWave);
             double owned = 0.0, lvl = v.S, sum = 0.0;
             for (int m = 0; m <= v.M; ++m) {
                 sum += lvl;        // nodes of levels 0..m
                 owned += sum;      // the update of owned level m touches all of them once
                 lvl *= (double)D;
             }
-            const double instr = owned + (v.M + 1) * (2.0 * Q + 1.0) + (double)Q * Q + 12.0;
+            const double instr = owned + (v.M + 1) * (2.0 * Q + 1.0) + (double)Q * Q + 12.0 + (pw > 1 ? (double)D : 0.0);
             const double rounds = (double)((waves + kSimds - 1) / kSimds);
             const double cost = rounds * instr * (waves <= kSimds ? 5.0 : 4.0);
             if (!have || cost < best) {
                 best = cost;
-                p.DT = v.D; p.M = v.M; p.S = v.S; p.Q = Q; p.NB = NB; p.LP = LP;
+                p.DT = v.D; p.M = v.M; p.S = v.S; p.Q = Q; p.NB = NB; p.LP = LP; p.PW = pw;
                 have = true;
             }
         }
@@ -171,6 +177,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
             int64_t LP; int Q, NB;
             if (!lanes(0, 1, LP, Q, NB)) { p.why = "truncation level too high for this number of channels (a lane carries at most 8 prefix letters)"; return false; }
             p.DT = 0; p.M = 0; p.S = 1; p.Q = Q; p.NB = NB; p.LP = LP;
+            p.PW = (!backward && LP <= kWave / 2 && Q <= kSharedMaxQ && force_W != 1) ? (int)(kWave / LP) : 1;
         }
         p.WP = (p.LP + kWave - 1) / kWave;
         return true;
@@ -183,8 +190,9 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
         int P = 1;
         if (force_P > 0) {
             P = force_P;
-        } else if (B > 0 && B * p.WP < kSimds && p.n >= 2 * kMinPiece && p.sig_len < ((int64_t)1 << 31)) {
-            while (P < kMaxPieces && B * p.WP * P < 2 * kSimds && p.n / (2 * P) >= kMinPiece) P *= 2;
+        } else if (B > 0 && (p.PW > 1 ? (B + p.PW - 1) / p.PW : B * p.WP) < kSimds && p.n >= 2 * kMinPiece && p.sig_len < ((int64_t)1 << 31)) {
+            const int64_t w1 = p.PW > 1 ? (B + p.PW - 1) / p.PW : B * p.WP;
+            while (P < kMaxPieces && w1 * P < 2 * kSimds && p.n / (2 * P) >= kMinPiece) P *= 2;
         }
         if (P > 1) {
             if ((P & (P - 1)) != 0 || P > kMaxPieces) { p.why = "the number of pieces must be a power of two up to 1024"; return p; }
@@ -197,7 +205,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
             if (!choose(p.VB)) return p;
         }
     }
-    p.waves = p.VB * p.WP;
+    p.waves = p.PW > 1 ? (p.VB + p.PW - 1) / p.PW : p.VB * p.WP;
     p.grid = (p.waves + kWavesPerWG - 1) / kWavesPerWG;
     if (p.grid > 0x7fffffffLL) { p.why = "too many workgroups"; return p; }
     p.Dpad = (int)align_up((size_t)D, 2);

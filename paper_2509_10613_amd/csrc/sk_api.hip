@@ -521,7 +521,8 @@ int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::
     if (L > ((int64_t)1 << 29) || d > 32768 || N > 64 || B > ((int64_t)1 << 40))
         return fail(SK_ERR_SHAPE, "L above 2^29, d above 32768, N above 64 or B above 2^40");
     *plan = sg::make_plan(B, L, d, N, (flags & SK_FLAG_TIME_AUG) != 0, (flags & SK_FLAG_LEAD_LAG) != 0, dt == SK_F64,
-                          force_M, backward, have_sig, force_S, backward ? 1 : force_P);
+                          force_M, backward, have_sig, force_S, backward ? 1 : force_P,
+                          (flags & SK_SIG_ONE_PATH_PER_WAVE) ? 1 : 0);
     if (!plan->valid) return fail(SK_ERR_SHAPE, "%s: %s", backward ? "signature_bwd" : "signature_fwd", plan->why);
     return SK_OK;
 }
@@ -545,7 +546,7 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
     a.dz = dz;
     a.out = p.P > 1 ? reinterpret_cast<double*>(base + p.off_t0) : result;
     a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
-    a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len;
+    a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.PW = p.PW; a.NW = p.waves;
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -606,7 +607,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
         f.dz = dz;
         f.out = reinterpret_cast<double*>(base + p.off_sig);
         f.B = pf.B; f.n = pf.n; f.np = pf.np; f.D = pf.D; f.Dpad = pf.Dpad; f.N = pf.N; f.Q = pf.Q; f.NB = pf.NB;
-        f.LP = pf.LP; f.WP = pf.WP; f.sig_len = pf.sig_len;
+        f.LP = pf.LP; f.WP = pf.WP; f.sig_len = pf.sig_len; f.PW = pf.PW; f.NW = pf.waves;
         SK_CHECK(sg::launch_horner(pf.DT, pf.M, pf.S, f, pf.grid, st));
         sig64 = f.out;
     } else if (kIsDouble) {
@@ -738,10 +739,10 @@ int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dty
     if (rc != SK_OK) return rc;
     std::snprintf(out, out_bytes,
                   "kernel=horner_kernel<%d, %d, %d, %d> channels=%d prefix_letters=%d letter_blocks=%d lanes_per_path=%lld "
-                  "waves_per_path=%lld pieces_per_path=%d segments_per_piece=%lld grid=%lld threads=%d "
+                  "waves_per_path=%lld paths_per_wave=%d pieces_per_path=%d segments_per_piece=%lld grid=%lld threads=%d "
                   "entries_per_path=%lld workspace_bytes=%zu",
                   p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.D, p.Q, p.NB, (long long)p.LP, (long long)p.WP,
-                  p.P, (long long)p.Lc, (long long)p.grid, sg::kWave * sg::kWavesPerWG, (long long)p.sig_len,
+                  p.PW, p.P, (long long)p.Lc, (long long)p.grid, sg::kWave * sg::kWavesPerWG, (long long)p.sig_len,
                   B == 0 ? (size_t)0 : p.total);
     return SK_OK;
 }

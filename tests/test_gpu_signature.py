@@ -85,6 +85,8 @@ def test_every_kernel_variant(D, M, S):
         desc = sk.signature_describe(2, L, D, N, sk.SK_SIG_DEPTH(M), sk.SK_F64)
         assert "horner_kernel<%d, %d, %d, %d>" % (D, M, S, Q if Q <= 4 else 8) in desc, desc
         check(paths(1000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=sk.SK_SIG_DEPTH(M))
+        if "paths_per_wave=1 " not in desc:     # the kernel whose waves hold one path each, too
+            check(paths(1000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=sk.SK_SIG_DEPTH(M) | sk.SK_SIG_ONE_PATH_PER_WAVE)
 
 
 def test_run_time_channel_kernel_for_any_channel_count():
@@ -92,6 +94,25 @@ def test_run_time_channel_kernel_for_any_channel_count():
         desc = sk.signature_describe(2, 6, d, N, sk.SK_SIG_DEPTH(0), sk.SK_F64)
         assert "horner_kernel<0, 0, 1," in desc, desc
         check(paths(77 + d, 2, 6, d), N, flags=sk.SK_SIG_DEPTH(0))
+
+
+def test_several_short_paths_share_a_wave():
+    # lane groups of at most half a wave sit side by side in one wave: batch sizes that do and do not fill the last
+    # wave, every prefix length with such kernels, the run-time channel count kernel, with pieces, flags, float32
+    for (B, L, d, N) in ((50, 9, 2, 3), (7, 8, 2, 2), (64, 6, 3, 3), (13, 7, 3, 2), (33, 6, 4, 3), (9, 5, 5, 2), (21, 5, 8, 2),
+                         (10, 6, 9, 1), (5, 6, 20, 1), (40, 5, 1, 3), (300, 6, 2, 4)):
+        desc = sk.signature_describe(B, L, d, N, 0, sk.SK_F64)
+        pw = int(desc.split("paths_per_wave=")[1].split(" ")[0])
+        assert pw > 1, desc
+        got = check(paths(600 + B + d, B, L, d), N)
+        one = host(sk.signature_fwd(dev(paths(600 + B + d, B, L, d)), N, sk.SK_SIG_ONE_PATH_PER_WAVE))
+        assert np.max(np.abs(got - one) / np.maximum(1.0, np.abs(one))) <= 1e-13
+    assert "paths_per_wave=1 " in sk.signature_describe(50, 9, 2, 3, sk.SK_SIG_ONE_PATH_PER_WAVE, sk.SK_F64)
+    check(paths(621, 5, 40, 2), 3, flags=sk.SK_SIG_PIECES(2))
+    check(paths(622, 11, 9, 2), 3, flags=sk.SK_FLAG_TIME_AUG)
+    check(paths(623, 11, 9, 1), 3, flags=sk.SK_FLAG_LEAD_LAG | sk.SK_FLAG_TIME_AUG, dtype=torch.float32)
+    # many short paths, the case this is for
+    check(paths(624, 5000, 12, 3, 0.3), 4)
 
 
 def test_paths_cut_into_pieces():
