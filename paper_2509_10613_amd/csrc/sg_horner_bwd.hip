@@ -33,12 +33,16 @@ __device__ __forceinline__ void load_owned(double (&A)[TOT], const double* src, 
     if constexpr (m < M) load_owned<D, M, S, TOT, m + 1>(A, src, at, Dn, first, c0, valid);
 }
 
-template <int DT, int M, int S, int QC>
+// SHARED: a wave holds several short paths (lane groups of LP <= 32 lanes, as in the forward kernel); a path then
+// lives in one wave, and the sums of dF/dz over its lanes are stored, not added.
+template <int DT, int M, int S, int QC, bool SHARED>
 __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
 {
     constexpr int DD = DT > 0 ? DT : 1;
     constexpr int QA = QC > 0 ? QC : 1;
-    constexpr bool kUniformZ = DT > 0 && M > 0;
+    constexpr bool kRows = DT > 0 && M > 0;            // the lanes' shares of dF/dz go through rows in LDS
+    constexpr bool kUniformZ = kRows && !SHARED;       // increments of a step in scalar registers
+    static_assert(!SHARED || kRows, "waves that hold several paths exist for the kernels with rows only");
     using T = Tree<DD, M, S>;
     const int D = DT > 0 ? DT : a.D;
     const int Q = QC <= kQExact ? QC : a.Q;
@@ -47,11 +51,24 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
     long wg = blockIdx.x;
     if (gridDim.x % kXcds == 0) wg = (long)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
     const long wt = wg * kWavesPerWG + wave;
-    if (wt >= a.B * a.WP) return;
-    const long b = wt / a.WP;
-    long ti = (wt - b * a.WP) * kWave + lane;
-    const bool valid = ti < a.LP;
-    if (!valid) ti = 0;
+    if (wt >= a.NW) return;
+    long b, ti;
+    bool valid;
+    if constexpr (SHARED) {
+        const int g = lane / (int)a.LP;
+        b = wt * a.PW + g;
+        ti = lane - g * (int)a.LP;
+        valid = g < a.PW && b < a.B;
+        if (!valid) {       // idle lanes follow the wave's first path with zero adjoints
+            b = wt * a.PW;
+            ti = 0;
+        }
+    } else {
+        b = wt / a.WP;
+        ti = (wt - b * a.WP) * kWave + lane;
+        valid = ti < a.LP;
+        if (!valid) ti = 0;
+    }
     const int blk = (int)(ti % a.NB);
     const long rest = ti / a.NB;
     int uR[QA];
@@ -120,6 +137,9 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
             uniform_ptr zs = (uniform_ptr)(zp);
 #pragma unroll
             for (int c = 0; c < DD; ++c) z_[c] = zs[c];
+        } else if constexpr (kRows) {
+#pragma unroll
+            for (int c = 0; c < DD; ++c) z_[c] = zp[c];
         }
 #pragma unroll
         for (int s = 0; s < S; ++s) zc_[s] = zp[cs[s]];
@@ -135,6 +155,34 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
     // per channel into acc; and the sums that reached acc one segment earlier go out as one global atomic per channel.
     // LDS executes a wave's instructions in order, which is all the synchronisation this needs.
     long r1 = -1, r2 = -1;   // row whose shares sit in the lanes' LDS rows / row whose sums sit in acc
+    auto publish = [&](const double (&zzb)[DD], const double (&zcb)[S], const double (&zub)[QA]) {
+#pragma unroll
+        for (int cc = 0; cc < DD; ++cc) tr[lane * DS + cc] = zzb[cc];
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+            if (cok[s]) atomicAdd(&tr[lane * DS + cs[s]], zcb[s]);
+#pragma unroll
+        for (int r = 0; r < QC; ++r)
+            if (has<QC>(r, Q)) atomicAdd(&tr[lane * DS + uR[r]], zub[r]);
+    };
+    // waves that hold several paths: two hops (rows, then one lane per path and channel sums the rows of its path and
+    // stores the result: no other wave has a share of it)
+    auto reduce_step_shared = [&](long row_new, const double (&zzb)[DD], const double (&zcb)[S], const double (&zub)[QA]) {
+        if (r1 >= 0) {
+            const int LPi = (int)a.LP;
+            for (int idx = lane; idx < a.PW * DD; idx += kWave) {
+                const int g = idx / DD, c = idx - g * DD;
+                const long bg = wt * a.PW + g;
+                if (bg < a.B) {
+                    double sum = 0.0;
+                    for (int i = 0; i < LPi; ++i) sum += tr[(g * LPi + i) * DS + c];
+                    a.gz[(bg * a.np + r1) * a.Dpad + c] = sum;
+                }
+            }
+        }
+        if (row_new >= 0) publish(zzb, zcb, zub);
+        r1 = row_new;
+    };
     auto reduce_step = [&](long row_new, const double (&zzb)[DD], const double (&zcb)[S], const double (&zub)[QA]) {
         constexpr int P = kWave / DD;                  // lanes per channel
         constexpr int R = (kWave + P - 1) / P;         // LDS rows per lane
@@ -154,16 +202,7 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
             atomicAdd(&grow[r2 * a.Dpad + lane], v);
         }
         if (coll && lane < DD * P) atomicAdd(&acc[c], sum);
-        if (row_new >= 0) {
-#pragma unroll
-            for (int cc = 0; cc < DD; ++cc) tr[lane * DS + cc] = zzb[cc];
-#pragma unroll
-            for (int s = 0; s < S; ++s)
-                if (cok[s]) atomicAdd(&tr[lane * DS + cs[s]], zcb[s]);
-#pragma unroll
-            for (int r = 0; r < QC; ++r)
-                if (has<QC>(r, Q)) atomicAdd(&tr[lane * DS + uR[r]], zub[r]);
-        }
+        if (row_new >= 0) publish(zzb, zcb, zub);
         r2 = r1;
         r1 = row_new;
     };
@@ -190,7 +229,9 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         for (int r = 0; r < QA; ++r) zub[r] = 0.0;
         prefix_levels_rev<QC, QA>(Q, preR, zu_, prb, zub);
         owned_levels_rev<0, DD, M, S, QC, T::TOT, QA>(A, Ab, Q, preR, prb, zu_, zc_, z_, zub, zcb, zzb);
-        if constexpr (kUniformZ) {
+        if constexpr (SHARED) {
+            reduce_step_shared(row, zzb, zcb, zub);
+        } else if constexpr (kRows) {
             reduce_step(row, zzb, zcb, zub);
         } else {
             // run-time channel count: the shares go straight to acc by LDS atomics (lanes with equal letters meet)
@@ -227,7 +268,7 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         segment(row, zzn, zcn, zuRn);
         rowA = row - 1;
     }
-    if constexpr (kUniformZ) {
+    if constexpr (kRows) {
         double zb0[DD], zb1[S], zb2[QA];
 #pragma unroll
         for (int c = 0; c < DD; ++c) zb0[c] = 0.0;
@@ -235,16 +276,20 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         for (int s = 0; s < S; ++s) zb1[s] = 0.0;
 #pragma unroll
         for (int r = 0; r < QA; ++r) zb2[r] = 0.0;
-        reduce_step(-1, zb0, zb1, zb2);
-        reduce_step(-1, zb0, zb1, zb2);
+        if constexpr (SHARED) {
+            reduce_step_shared(-1, zb0, zb1, zb2);
+        } else {
+            reduce_step(-1, zb0, zb1, zb2);
+            reduce_step(-1, zb0, zb1, zb2);
+        }
     }
 }
 
-template <int DT, int M, int S, int QC>
+template <int DT, int M, int S, int QC, bool SHARED>
 __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_bwd_kernel(const BwdArgs a)
 {
     extern __shared__ double lds[];
-    run_bwd<DT, M, S, QC>(a, lds);
+    run_bwd<DT, M, S, QC, SHARED>(a, lds);
 }
 
 // dF/dx from dF/dz (one row per segment of the transformed path): a point gains what the segment before it gives and
@@ -271,24 +316,36 @@ __global__ __launch_bounds__(256) void point_gradients_kernel(const double* __re
     }
 }
 
-template <int DT, int M, int S, int QC>
+template <int DT, int M, int S, int QC, bool SHARED>
 hipError_t launch_one(const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st)
 {
-    hipLaunchKernelGGL((horner_bwd_kernel<DT, M, S, QC>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), lds_bytes, st, a);
+    hipLaunchKernelGGL((horner_bwd_kernel<DT, M, S, QC, SHARED>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), lds_bytes, st, a);
     return hipGetLastError();
 }
 
 template <int DT, int M, int S>
 hipError_t launch_variant(const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st)
 {
+    if (a.PW > 1) {
+        if constexpr (DT > 0 && M > 0 && DT <= kSharedMaxD) {
+            switch (a.Q) {
+            case 0: return launch_one<DT, M, S, 0, true>(a, grid, lds_bytes, st);
+            case 1: return launch_one<DT, M, S, 1, true>(a, grid, lds_bytes, st);
+            case 2: return launch_one<DT, M, S, 2, true>(a, grid, lds_bytes, st);
+            default: return hipErrorInvalidValue;
+            }
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     switch (a.Q) {
-    case 0: return launch_one<DT, M, S, 0>(a, grid, lds_bytes, st);
-    case 1: return launch_one<DT, M, S, 1>(a, grid, lds_bytes, st);
-    case 2: return launch_one<DT, M, S, 2>(a, grid, lds_bytes, st);
-    case 3: return launch_one<DT, M, S, 3>(a, grid, lds_bytes, st);
-    case 4: return launch_one<DT, M, S, 4>(a, grid, lds_bytes, st);
+    case 0: return launch_one<DT, M, S, 0, false>(a, grid, lds_bytes, st);
+    case 1: return launch_one<DT, M, S, 1, false>(a, grid, lds_bytes, st);
+    case 2: return launch_one<DT, M, S, 2, false>(a, grid, lds_bytes, st);
+    case 3: return launch_one<DT, M, S, 3, false>(a, grid, lds_bytes, st);
+    case 4: return launch_one<DT, M, S, 4, false>(a, grid, lds_bytes, st);
     default:
-        if constexpr (DT <= kBwdLongPrefixMaxD) return launch_one<DT, M, S, kQMax>(a, grid, lds_bytes, st);
+        if constexpr (DT <= kBwdLongPrefixMaxD) return launch_one<DT, M, S, kQMax, false>(a, grid, lds_bytes, st);
         else return hipErrorInvalidValue;
     }
 }
@@ -303,7 +360,10 @@ hipError_t launch_horner_bwd(int DT, int M, int S, const BwdArgs& a, long grid, 
     const size_t need = (size_t)kWavesPerWG * a.lds_wave * sizeof(double);
     if ((a.np > 0 && !(a.np & 1)) || a.np < a.n || a.Q < 0 || a.Q > kQMax || a.LP <= 0 || a.WP * kWave < a.LP ||
         a.NB * (long)S < D || a.Dpad < D || a.lds_wave < (size_t)a.Dpad + (uniform ? (size_t)kWave * (D | 1) : 0) ||
-        lds_bytes < need || lds_bytes > 160 * 1024)
+        lds_bytes < need || lds_bytes > 64 * 1024)
+        return hipErrorInvalidValue;
+    if (a.PW < 1 || (a.PW > 1 && (a.WP != 1 || a.PW * a.LP > kWave || a.NW * a.PW < a.B)) || (a.PW == 1 && a.NW != a.B * a.WP) ||
+        grid * kWavesPerWG < a.NW)
         return hipErrorInvalidValue;
     if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, lds_bytes, st) : hipErrorInvalidValue;
 #define SG_CASE(D_, M_, S_) \

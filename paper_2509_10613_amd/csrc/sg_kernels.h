@@ -31,6 +31,8 @@ struct BwdArgs {
     long LP, WP;
     long sig_len;
     size_t lds_wave;     // doubles of LDS per wave
+    int PW;              // paths per wave (several short paths side by side: then WP = 1)
+    long NW;             // waves of the launch
 };
 
 hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStream_t st);

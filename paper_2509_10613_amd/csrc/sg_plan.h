@@ -155,7 +155,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
             int64_t LP; int Q, NB;
             if (!lanes(v.M, v.S, LP, Q, NB)) continue;
             // lane groups of at most half a wave can share a wave (forward kernels for few channels and letters)
-            const int pw = (!backward && LP <= kWave / 2 && Q <= kSharedMaxQ && D <= kSharedMaxD && force_W != 1) ? (int)(kWave / LP) : 1;
+            const int pw = (LP <= kWave / 2 && Q <= kSharedMaxQ && D <= kSharedMaxD && force_W != 1) ? (int)(kWave / LP) : 1;
             const int64_t waves = pw > 1 ? (Bsel + pw - 1) / pw : Bsel * ((LP + kWave - 1) / kWave);
             double owned = 0.0, lvl = v.S, sum = 0.0;
             for (int m = 0; m <= v.M; ++m) {

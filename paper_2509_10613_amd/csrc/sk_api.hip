@@ -628,7 +628,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
     sg::BwdArgs a;
     a.dz = dz; a.gz = gz; a.sig = sig64; a.gout = gout64;
     a.B = p.B; a.n = p.n; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
-    a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.lds_wave = p.lds_wave;
+    a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.lds_wave = p.lds_wave; a.PW = p.PW; a.NW = p.waves;
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -722,10 +722,10 @@ int signature_bwd_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk
     if (rc != SK_OK) return rc;
     std::snprintf(out, out_bytes,
                   "kernel=horner_bwd_kernel<%d, %d, %d, %d> channels=%d prefix_letters=%d letter_blocks=%d "
-                  "lanes_per_path=%lld waves_per_path=%lld grid=%lld threads=%d lds_bytes=%zu entries_per_path=%lld "
-                  "workspace_bytes=%zu",
+                  "lanes_per_path=%lld waves_per_path=%lld paths_per_wave=%d grid=%lld threads=%d lds_bytes=%zu "
+                  "entries_per_path=%lld workspace_bytes=%zu",
                   p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.D, p.Q, p.NB, (long long)p.LP, (long long)p.WP,
-                  (long long)p.grid, sg::kWave * sg::kWavesPerWG, p.lds_bytes, (long long)p.sig_len,
+                  p.PW, (long long)p.grid, sg::kWave * sg::kWavesPerWG, p.lds_bytes, (long long)p.sig_len,
                   B == 0 ? (size_t)0 : p.total);
     return SK_OK;
 }

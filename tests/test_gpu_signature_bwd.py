@@ -73,6 +73,8 @@ def test_every_backward_kernel_variant(D, M, S):
         desc = sk.signature_bwd_describe(2, L, D, N, force, sk.SK_F64)
         assert "horner_bwd_kernel<%d, %d, %d, %d>" % (D, M, S, Q if Q <= 4 else 8) in desc, desc
         check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=force)
+        if "paths_per_wave=1 " not in desc:     # the kernel whose waves hold one path each, too
+            check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=force | sk.SK_SIG_ONE_PATH_PER_WAVE)
 
 
 def test_backward_run_time_channel_kernel():
@@ -88,6 +90,19 @@ def test_backward_library_choice_and_given_signatures(B, L, d, N):
     a = check(paths(300 + d + N, B, L, d), N)
     b = check(paths(300 + d + N, B, L, d), N, give_sig=True)
     assert np.max(np.abs(a - b)) <= 1e-12 * max(1.0, np.max(np.abs(a)))
+
+
+def test_backward_several_short_paths_share_a_wave():
+    for (B, L, d, N) in ((50, 9, 2, 3), (7, 8, 2, 2), (64, 6, 3, 3), (13, 7, 3, 2), (33, 6, 4, 3), (9, 5, 5, 2), (21, 5, 8, 2),
+                         (300, 6, 2, 4), (40, 6, 9, 2)):
+        desc = sk.signature_bwd_describe(B, L, d, N, 0, sk.SK_F64)
+        assert int(desc.split("paths_per_wave=")[1].split(" ")[0]) > 1, desc
+        a = check(paths(700 + B + d, B, L, d), N)
+        b = check(paths(700 + B + d, B, L, d), N, flags=sk.SK_SIG_ONE_PATH_PER_WAVE, give_sig=True)
+        assert np.max(np.abs(a - b)) <= 1e-12 * max(1.0, np.max(np.abs(a)))
+    check(paths(722, 11, 9, 2), 3, flags=sk.SK_FLAG_TIME_AUG)
+    check(paths(723, 11, 9, 1), 3, flags=sk.SK_FLAG_LEAD_LAG | sk.SK_FLAG_TIME_AUG, dtype=torch.float32)
+    check(paths(724, 3000, 10, 3, 0.3), 4)
 
 
 @pytest.mark.parametrize("flags", [sk.SK_FLAG_TIME_AUG, sk.SK_FLAG_LEAD_LAG, sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG])
