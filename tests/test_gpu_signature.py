@@ -83,7 +83,7 @@ def test_every_kernel_variant(D, M, S):
             continue
         L = 5 if D ** N < 20000 else 3
         desc = sk.signature_describe(2, L, D, N, sk.SK_SIG_DEPTH(M), sk.SK_F64)
-        assert "horner_kernel<%d, %d, %d, %d>" % (D, M, S, Q if Q <= 4 else 8) in desc, desc
+        assert "horner_kernel<%d, %d, %d, %d, " % (D, M, S, Q if Q <= 4 else 8) in desc, desc
         check(paths(1000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=sk.SK_SIG_DEPTH(M))
         if "paths_per_wave=1 " not in desc:     # the kernel whose waves hold one path each, too
             check(paths(1000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=sk.SK_SIG_DEPTH(M) | sk.SK_SIG_ONE_PATH_PER_WAVE)

@@ -71,7 +71,7 @@ def test_every_backward_kernel_variant(D, M, S):
         L = 5 if D ** N < 5000 else 3
         force = sk.SK_SIG_DEPTH(M) | sk.SK_SIG_BLOCK(S)
         desc = sk.signature_bwd_describe(2, L, D, N, force, sk.SK_F64)
-        assert "horner_bwd_kernel<%d, %d, %d, %d>" % (D, M, S, Q if Q <= 4 else 8) in desc, desc
+        assert "horner_bwd_kernel<%d, %d, %d, %d, " % (D, M, S, Q if Q <= 4 else 8) in desc, desc
         check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=force)
         if "paths_per_wave=1 " not in desc:     # the kernel whose waves hold one path each, too
             check(paths(2000 * D + 10 * M + Q, 2, L, D, 0.5), N, flags=force | sk.SK_SIG_ONE_PATH_PER_WAVE)
