@@ -11,6 +11,8 @@
 // summed column by column) and issues one global atomic per channel.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "sg_dev.h"
 #include "sg_kernels.h"
 
@@ -174,9 +176,23 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
                 const int g = idx / DD, c = idx - g * DD;
                 const long bg = wt * a.PW + g;
                 if (bg < a.B) {
-                    double sum = 0.0;
-                    for (int i = 0; i < LPi; ++i) sum += tr[(g * LPi + i) * DS + c];
-                    a.gz[(bg * a.np + r1) * a.Dpad + c] = sum;
+                    // all reads issued back to back (rows past the group are read again and not counted)
+                    const double* col = tr + g * LPi * DS + c;
+                    double s0 = 0.0, s1 = 0.0;
+                    auto rows = [&](auto count) {
+#pragma unroll
+                        for (int i = 0; i < decltype(count)::value; i += 2) {
+                            const double v0 = col[min(i, LPi - 1) * DS], v1 = col[min(i + 1, LPi - 1) * DS];
+                            s0 += i < LPi ? v0 : 0.0;
+                            s1 += i + 1 < LPi ? v1 : 0.0;
+                        }
+                    };
+                    if (LPi <= 2) rows(std::integral_constant<int, 2>());
+                    else if (LPi <= 4) rows(std::integral_constant<int, 4>());
+                    else if (LPi <= 8) rows(std::integral_constant<int, 8>());
+                    else if (LPi <= 16) rows(std::integral_constant<int, 16>());
+                    else rows(std::integral_constant<int, 32>());
+                    a.gz[(bg * a.np + r1) * a.Dpad + c] = s0 + s1;
                 }
             }
         }

@@ -163,7 +163,10 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
                 owned += sum;      // the update of owned level m touches all of them once
                 lvl *= (double)D;
             }
-            const double instr = owned + (v.M + 1) * (2.0 * Q + 1.0) + (double)Q * Q + 12.0 + (pw > 1 ? (double)D : 0.0);
+            // several paths per wave: the increments are loaded per lane; backward, a lane per path and channel reads the
+            // LDS rows of its path
+            const double instr = owned + (v.M + 1) * (2.0 * Q + 1.0) + (double)Q * Q + 12.0 + (pw > 1 ? (double)D : 0.0) +
+                                 (pw > 1 && backward ? (double)LP : 0.0);
             const double rounds = (double)((waves + kSimds - 1) / kSimds);
             const double cost = rounds * instr * (waves <= kSimds ? 5.0 : 4.0);
             if (!have || cost < best) {
