@@ -313,7 +313,8 @@ __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_bwd_kernel(const B
 // the lag half by the same difference.  The time channel has no gradient.
 template <typename TO>
 __global__ __launch_bounds__(256) void point_gradients_kernel(const double* __restrict__ gz, TO* __restrict__ gx, long B,
-                                                              long L, int d, int Dpad, long np, int lead_lag)
+                                                              long L, int d, int Dpad, int P, long Lc, long np,
+                                                              int lead_lag)
 {
     const long total = B * L * d;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
@@ -321,14 +322,65 @@ __global__ __launch_bounds__(256) void point_gradients_kernel(const double* __re
         const long bp = i / d;
         const long pt = bp % L;
         const long b = bp / L;
-        const double* g = gz + b * np * Dpad;
-        auto seg = [&](long k) {
-            return lead_lag ? g[(2 * k) * Dpad + ch] + g[(2 * k + 1) * Dpad + d + ch] : g[k * Dpad + ch];
-        };
+        const double* g = gz + b * P * np * Dpad;
+        // row of segment s of the transformed path: piece s / Lc, row s % Lc of that piece
+        auto row = [&](long s, int c) { return g[((s / Lc) * np + s % Lc) * Dpad + c]; };
+        auto seg = [&](long k) { return lead_lag ? row(2 * k, ch) + row(2 * k + 1, d + ch) : row(k, ch); };
         double v = 0.0;
         if (pt > 0) v += seg(pt - 1);
         if (pt < L - 1) v -= seg(pt);
         gx[i] = (TO)v;
+    }
+}
+
+// Adjoint of chen_pairs_kernel (the product X = Xl (x) Xr of two neighbouring pieces, truncated at level N): from the
+// adjoint Gp of X, the adjoint of Xl is Gl[w] = sum_c Gp[w c] Xr[c] and that of Xr is Gr[w] = sum_a Xl[a] Gp[a w], over
+// all words c, a with |w| + |c| <= N.  X holds 2 * pairs signatures (Xl, Xr interleaved), Gc receives their adjoints
+// in the same order.  The entries of levels k_lo..k_hi are computed by one lane each (lanes == 1) or by one wave each,
+// its lanes striding over the terms (lanes == 64): short words have sums of up to the whole signature.
+struct LevelTable {
+    unsigned lv[24];    // start of level k in a flattened signature
+    unsigned pw[24];    // D^k
+};
+
+__global__ __launch_bounds__(256) void chen_pairs_adjoint_kernel(const double* __restrict__ X, const double* __restrict__ Gp,
+                                                                 double* __restrict__ Gc, long pairs, const LevelTable T,
+                                                                 int N, long sig_len, int k_lo, int k_hi, int lanes)
+{
+    // blockIdx.y walks over the child signatures (2 * pair + child), blockIdx.x and the threads over the entries
+    const unsigned e_lo = T.lv[k_lo], e_hi = T.lv[k_hi + 1];      // entries [e_lo, e_hi)
+    const unsigned lane = lanes == 1 ? 0u : (threadIdx.x & 63u);
+    const unsigned slot = blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned e = e_lo + (lanes == 1 ? slot : slot / 64u);
+    if (e >= e_hi) return;                             // whole waves leave together in the wave-per-entry form
+    int k = k_lo;
+    while (e >= T.lv[k + 1]) ++k;
+    const unsigned w = e - T.lv[k];
+    for (long sg = blockIdx.y; sg < 2 * pairs; sg += gridDim.y) {
+        const long pr = sg >> 1;
+        const int child = (int)(sg & 1);
+        const double* Gpar = Gp + pr * sig_len;
+        const double* Xo = X + (2 * pr + (child ^ 1)) * sig_len;      // the sibling
+        double acc = 0.0;
+        if (k > 0) {
+            for (int j = 0; j <= N - k; ++j) {                         // the other word o has j letters
+                const unsigned cnt = T.pw[j];
+                const double* xo = Xo + T.lv[j];
+                if (child == 0) {                                      // left factor: the word w o
+                    const double* g = Gpar + T.lv[k + j] + w * cnt;
+                    for (unsigned o = lane; o < cnt; o += (unsigned)lanes) acc = __builtin_fma(g[o], xo[o], acc);
+                } else {                                               // right factor: the word o w
+                    const double* g = Gpar + T.lv[k + j] + w;
+                    const unsigned st = T.pw[k];
+                    for (unsigned o = lane; o < cnt; o += (unsigned)lanes) acc = __builtin_fma(g[o * st], xo[o], acc);
+                }
+            }
+        }
+        if (lanes != 1) {
+#pragma unroll
+            for (int sh = 32; sh >= 1; sh >>= 1) acc += __shfl_xor(acc, sh, 64);
+        }
+        if (lane == 0) Gc[sg * sig_len + e] = acc;
     }
 }
 
@@ -390,19 +442,68 @@ hipError_t launch_horner_bwd(int DT, int M, int S, const BwdArgs& a, long grid, 
 }
 
 template <typename TO>
-hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int d, int Dpad, long np, int lead_lag,
-                                  hipStream_t st)
+hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int d, int Dpad, int P, long Lc, long np,
+                                  int lead_lag, hipStream_t st)
 {
     const long total = B * L * d;
     if (total <= 0) return hipSuccess;
+    if (P < 1 || (Lc < 1 && L > 1) || np < Lc) return hipErrorInvalidValue;
     long grid = (total + 255) / 256;
     if (grid > 65536) grid = 65536;
-    hipLaunchKernelGGL((point_gradients_kernel<TO>), dim3((unsigned)grid), dim3(256), 0, st, gz, gx, B, L, d, Dpad, np,
-                       lead_lag);
+    hipLaunchKernelGGL((point_gradients_kernel<TO>), dim3((unsigned)grid), dim3(256), 0, st, gz, gx, B, L, d, Dpad, P, Lc,
+                       np, lead_lag);
     return hipGetLastError();
 }
 
-template hipError_t launch_point_gradients<float>(const double*, float*, long, long, int, int, long, int, hipStream_t);
-template hipError_t launch_point_gradients<double>(const double*, double*, long, long, int, int, long, int, hipStream_t);
+template hipError_t launch_point_gradients<float>(const double*, float*, long, long, int, int, int, long, long, int, hipStream_t);
+template hipError_t launch_point_gradients<double>(const double*, double*, long, long, int, int, int, long, long, int, hipStream_t);
+
+hipError_t launch_chen_pairs_adjoint(const double* X, const double* Gp, double* Gc, long pairs, int D, int N, long sig_len,
+                                     hipStream_t st)
+{
+    if (pairs <= 0 || sig_len <= 0) return hipSuccess;
+    if (sig_len >= (1L << 31) || D < 1 || N < 1 || N > 21) return hipErrorInvalidValue;
+    // levels whose sums have more than 64 terms get a wave per entry: words of length k with 1 + D + ... + D^(N-k) > 64
+    int k_split = 0;         // first level computed by single lanes
+    {
+        long terms = 0, pw = 1;
+        int j = 0;
+        while (j <= N && terms + pw <= 64) {
+            terms += pw;
+            pw *= D;
+            ++j;
+        }
+        k_split = N - j + 1;           // levels k >= k_split have at most 64 terms
+        if (k_split < 0) k_split = 0;
+    }
+    LevelTable T;
+    {
+        unsigned o = 0, q = 1;
+        for (int k = 0; k < 24; ++k) {
+            T.lv[k] = o;
+            T.pw[k] = q;
+            if (k <= N) {
+                o += q;
+                q *= (unsigned)D;
+            }
+        }
+    }
+    const unsigned gy = (unsigned)(2 * pairs < 65535 ? 2 * pairs : 65535);
+    if (k_split <= N) {
+        const long entries = (long)T.lv[N + 1] - (long)T.lv[k_split];
+        hipLaunchKernelGGL(chen_pairs_adjoint_kernel, dim3((unsigned)((entries + 255) / 256), gy), dim3(256), 0, st, X, Gp, Gc,
+                           pairs, T, N, sig_len, k_split, N, 1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (k_split > 0) {
+        const long entries = (long)T.lv[k_split];
+        hipLaunchKernelGGL(chen_pairs_adjoint_kernel, dim3((unsigned)((entries + 3) / 4), gy), dim3(256), 0, st, X, Gp, Gc,
+                           pairs, T, N, sig_len, 0, k_split - 1, 64);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 
 }  // namespace sg

@@ -39,8 +39,13 @@ hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStre
 hipError_t launch_horner_bwd(int DT, int M, int S, const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st);
 
 template <typename TO>
-hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int d, int Dpad, long np, int lead_lag,
-                                  hipStream_t st);
+hipError_t launch_point_gradients(const double* gz, TO* gx, long B, long L, int d, int Dpad, int P, long Lc, long np,
+                                  int lead_lag, hipStream_t st);
+
+// adjoints of the two factors of each pair product: Gc[2 i] = adjoint of X[2 i], Gc[2 i + 1] = adjoint of X[2 i + 1],
+// given the adjoint Gp[i] of X[2 i] (x) X[2 i + 1]
+hipError_t launch_chen_pairs_adjoint(const double* X, const double* Gp, double* Gc, long pairs, int D, int N, long sig_len,
+                                     hipStream_t st);
 
 template <typename TI>
 hipError_t launch_increments(const TI* x, double* dz, long B, long L, int d, int D, int Dpad, long n, int P, long Lc,

@@ -188,14 +188,18 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
     if (!choose(B)) return p;
     // Few long paths leave most SIMDs without a wave: cut every path into P pieces of Lc segments, let the Horner
     // kernel treat the pieces as paths, and multiply the signatures of the pieces pairwise afterwards (Chen's identity,
-    // Proposition 2.2).  Forward only.
-    if (!backward && p.n > 0) {
+    // Proposition 2.2).  Backward: the same products, then their adjoints pair by pair back down to the pieces, then
+    // the backward kernel on the pieces.
+    if (p.n > 0) {
         int P = 1;
         if (force_P > 0) {
             P = force_P;
-        } else if (B > 0 && (p.PW > 1 ? (B + p.PW - 1) / p.PW : B * p.WP) < kSimds && p.n >= 2 * kMinPiece && p.sig_len < ((int64_t)1 << 31)) {
+        } else if (B > 0 && p.n >= 2 * kMinPiece && p.sig_len < ((int64_t)1 << 31)) {
+            // backward, the products and their adjoints cost several launches: only when the chip is mostly empty
             const int64_t w1 = p.PW > 1 ? (B + p.PW - 1) / p.PW : B * p.WP;
-            while (P < kMaxPieces && w1 * P < 2 * kSimds && p.n / (2 * P) >= kMinPiece) P *= 2;
+            const int64_t few = backward ? kSimds / 2 : kSimds, want = backward ? kSimds : 2 * kSimds;
+            if (w1 < few)
+                while (P < kMaxPieces && w1 * P < want && p.n / (2 * P) >= kMinPiece) P *= 2;
         }
         if (P > 1) {
             if ((P & (P - 1)) != 0 || P > kMaxPieces) { p.why = "the number of pieces must be a power of two up to 1024"; return p; }
@@ -230,11 +234,20 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
         p.lds_wave = (size_t)p.Dpad + (uniform ? (size_t)kWave * (size_t)(D | 1) : 0);
         p.lds_bytes = (size_t)kWavesPerWG * p.lds_wave * sizeof(double);
         p.off_gz = off;      // dF/dz, one row per stored increment row
-        off = align_up(off + (size_t)B * (size_t)p.np * p.Dpad * sizeof(double), 256);
+        off = align_up(off + (size_t)p.VB * (size_t)p.np * p.Dpad * sizeof(double), 256);
         p.off_sig = off;     // signatures in double: computed here, or converted from a float caller's
-        if (!have_sig || !io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+        if (p.P == 1 && (!have_sig || !io_double)) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
         p.off_gout = off;    // float callers: the upstream gradient in double
         if (!io_double) off = align_up(off + (size_t)B * (size_t)p.sig_len * sizeof(double), 256);
+        if (p.P > 1) {
+            // signatures of the pieces and of the products of 2, 4, ... neighbouring pieces (levels 0 .. log2 P - 1 of
+            // the product tree, P + P/2 + ... + 2 signatures per path), and the adjoints of the same
+            const size_t tree = (size_t)(2 * p.VB - 2 * B) * (size_t)p.sig_len * sizeof(double);
+            p.off_t0 = off;
+            off = align_up(off + tree, 256);
+            p.off_t1 = off;
+            off = align_up(off + tree, 256);
+        }
     }
     p.total = off < 256 ? 256 : off;
     p.valid = true;

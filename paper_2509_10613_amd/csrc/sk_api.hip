@@ -514,14 +514,13 @@ int sig_validate(int64_t B, int64_t L, int64_t d, int N, int flags, int dt, sg::
     const int split = (flags & 0x1f0000) >> 16;          // SK_SIG_PIECES(log2 P) = (log2 P + 1) << 16
     const int force_P = split ? (1 << (split - 1)) : 0;
     if (split > 11) return fail(SK_ERR_SHAPE, "at most 2^10 pieces per path");
-    if (backward && force_P > 1) return fail(SK_ERR_SHAPE, "signature_bwd does not cut paths into pieces");
     if (B < 0) return fail(SK_ERR_SHAPE, "negative batch size");
     if (L < 1 || d < 1 || N < 1) return fail(SK_ERR_SHAPE, "need L, d, N >= 1 (got %lld, %lld, %d)", (long long)L,
                                              (long long)d, N);
     if (L > ((int64_t)1 << 29) || d > 32768 || N > 64 || B > ((int64_t)1 << 40))
         return fail(SK_ERR_SHAPE, "L above 2^29, d above 32768, N above 64 or B above 2^40");
     *plan = sg::make_plan(B, L, d, N, (flags & SK_FLAG_TIME_AUG) != 0, (flags & SK_FLAG_LEAD_LAG) != 0, dt == SK_F64,
-                          force_M, backward, have_sig, force_S, backward ? 1 : force_P,
+                          force_M, backward, have_sig, force_S, force_P,
                           (flags & SK_SIG_ONE_PATH_PER_WAVE) ? 1 : 0);
     if (!plan->valid) return fail(SK_ERR_SHAPE, "%s: %s", backward ? "signature_bwd" : "signature_fwd", plan->why);
     return SK_OK;
@@ -598,16 +597,68 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
     double* dz = reinterpret_cast<double*>(base + p.off_dz);
     double* gz = reinterpret_cast<double*>(base + p.off_gz);
     const long count = p.B * p.sig_len;
-    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, 1, p.n, p.np,
+    SK_CHECK(sg::launch_increments<T>(static_cast<const T*>(x), dz, p.B, p.L, p.d, p.D, p.Dpad, p.n, p.P, p.Lc, p.np,
                                       (flags & SK_FLAG_TIME_AUG) ? 1 : 0, (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
-    SK_CHECK(sk::launch_fill<double>(gz, p.B * p.np * p.Dpad, 0.0, st));
-    const double* sig64;
-    if (!sig) {
+    SK_CHECK(sk::launch_fill<double>(gz, p.VB * p.np * p.Dpad, 0.0, st));
+    const double* gout64;
+    if (kIsDouble) {
+        gout64 = static_cast<const double*>(grad_out);
+    } else {
+        double* g64 = reinterpret_cast<double*>(base + p.off_gout);
+        SK_CHECK((sk::launch_convert<T, double>(static_cast<const T*>(grad_out), g64, count, st)));
+        gout64 = g64;
+    }
+    bool timed = false;
+    TimedLaunch tl{};
+    {
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        timed = g_timing_on;
+    }
+    auto forward_args = [&](double* out) {
         sg::Args f;
         f.dz = dz;
-        f.out = reinterpret_cast<double*>(base + p.off_sig);
-        f.B = pf.B; f.n = pf.n; f.np = pf.np; f.D = pf.D; f.Dpad = pf.Dpad; f.N = pf.N; f.Q = pf.Q; f.NB = pf.NB;
+        f.out = out;
+        f.B = pf.VB; f.n = pf.Lc; f.np = pf.np; f.D = pf.D; f.Dpad = pf.Dpad; f.N = pf.N; f.Q = pf.Q; f.NB = pf.NB;
         f.LP = pf.LP; f.WP = pf.WP; f.sig_len = pf.sig_len; f.PW = pf.PW; f.NW = pf.waves;
+        return f;
+    };
+    const double* sig64;
+    if (p.P > 1) {
+        // Paths cut into pieces: signatures of the pieces (level 0 of a tree), products of neighbouring pairs level by
+        // level up to the whole paths, then the adjoints back down; the backward kernel then sees the pieces as paths
+        // with their own signatures and upstream gradients.  Signatures the caller passed are not used.
+        if (timed) {
+            SK_CHECK(hipEventCreate(&tl.start));
+            SK_CHECK(hipEventCreate(&tl.stop));
+            tl.backward = 1;
+            SK_CHECK(hipEventRecord(tl.start, st));
+        }
+        double* tv = reinterpret_cast<double*>(base + p.off_t0);
+        double* ta = reinterpret_cast<double*>(base + p.off_t1);
+        sg::Args f = forward_args(tv);
+        SK_CHECK(sg::launch_horner(pf.DT, pf.M, pf.S, f, pf.grid, st));
+        // level j holds P >> j signatures per path, starting at lev[j] signatures into the tree buffers
+        long lev[16];
+        int nlev = 0;
+        {
+            long o = 0;
+            for (int cur = p.P; cur > 1; cur /= 2) {
+                lev[nlev++] = o;
+                o += p.B * cur;
+            }
+        }
+        for (int j = 0; j + 1 < nlev; ++j)      // the product of all pieces is not needed: its adjoint is grad_out
+            SK_CHECK(sg::launch_chen_pairs(tv + lev[j] * p.sig_len, tv + lev[j + 1] * p.sig_len, p.B * (p.P >> (j + 1)), p.D,
+                                           p.N, p.sig_len, st));
+        for (int j = nlev - 1; j >= 0; --j) {
+            const double* parent = j == nlev - 1 ? gout64 : ta + lev[j + 1] * p.sig_len;
+            SK_CHECK(sg::launch_chen_pairs_adjoint(tv + lev[j] * p.sig_len, parent, ta + lev[j] * p.sig_len,
+                                                   p.B * (p.P >> (j + 1)), p.D, p.N, p.sig_len, st));
+        }
+        sig64 = tv;
+        gout64 = ta;
+    } else if (!sig) {
+        sg::Args f = forward_args(reinterpret_cast<double*>(base + p.off_sig));
         SK_CHECK(sg::launch_horner(pf.DT, pf.M, pf.S, f, pf.grid, st));
         sig64 = f.out;
     } else if (kIsDouble) {
@@ -617,25 +668,11 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
         SK_CHECK((sk::launch_convert<T, double>(static_cast<const T*>(sig), s64, count, st)));
         sig64 = s64;
     }
-    const double* gout64;
-    if (kIsDouble) {
-        gout64 = static_cast<const double*>(grad_out);
-    } else {
-        double* g64 = reinterpret_cast<double*>(base + p.off_gout);
-        SK_CHECK((sk::launch_convert<T, double>(static_cast<const T*>(grad_out), g64, count, st)));
-        gout64 = g64;
-    }
     sg::BwdArgs a;
     a.dz = dz; a.gz = gz; a.sig = sig64; a.gout = gout64;
-    a.B = p.B; a.n = p.n; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
+    a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.lds_wave = p.lds_wave; a.PW = p.PW; a.NW = p.waves;
-    bool timed = false;
-    TimedLaunch tl{};
-    {
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        timed = g_timing_on;
-    }
-    if (timed) {
+    if (timed && p.P == 1) {
         SK_CHECK(hipEventCreate(&tl.start));
         SK_CHECK(hipEventCreate(&tl.stop));
         tl.backward = 1;
@@ -647,7 +684,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
-    SK_CHECK(sg::launch_point_gradients<T>(gz, static_cast<T*>(grad_x), p.B, p.L, p.d, p.Dpad, p.np,
+    SK_CHECK(sg::launch_point_gradients<T>(gz, static_cast<T*>(grad_x), p.B, p.L, p.d, p.Dpad, p.P, p.Lc, p.np,
                                            (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
 #undef SK_CHECK
     return SK_OK;
@@ -700,11 +737,16 @@ int signature_bwd(const void* x, const void* sig, const void* grad_out, void* gr
     if (rc != SK_OK) return rc;
     if (B == 0) return SK_OK;
     if (!x || !grad_out || !grad_x) return fail(SK_ERR_NULL, "x, grad_out or grad_x is NULL");
-    if (!sig) {
-        // the forward launch for the same paths, its output in double whatever the caller's type; a forced subtree
-        // depth applies to the backward kernel only
-        rc = sig_validate(B, L, d, N, (flags & ~SK_SIG_DEPTH_MASK) | SK_SIG_PIECES(0), SK_F64, &pf);
+    if (!sig || p.P > 1) {
+        // the forward launch for the same paths, cut into the same pieces, its output in double whatever the caller's
+        // type; a forced subtree depth applies to the backward kernel only
+        int q = 0;
+        while ((1 << q) < p.P) ++q;
+        rc = sig_validate(B, L, d, N, (flags & (SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG | SK_SIG_ONE_PATH_PER_WAVE)) | SK_SIG_PIECES(q),
+                          SK_F64, &pf);
         if (rc != SK_OK) return rc;
+        if (pf.P != p.P || pf.Lc != p.Lc || pf.np != p.np || pf.Dpad != p.Dpad)
+            return fail(SK_ERR_SHAPE, "signature_bwd: forward and backward plans disagree on the pieces");
     }
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < p.total)
         return fail(SK_ERR_WORKSPACE, "workspace is NULL, misaligned or smaller than %zu bytes", p.total);
@@ -722,10 +764,10 @@ int signature_bwd_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk
     if (rc != SK_OK) return rc;
     std::snprintf(out, out_bytes,
                   "kernel=horner_bwd_kernel<%d, %d, %d, %d, %s> channels=%d prefix_letters=%d letter_blocks=%d "
-                  "lanes_per_path=%lld waves_per_path=%lld paths_per_wave=%d grid=%lld threads=%d lds_bytes=%zu "
-                  "entries_per_path=%lld workspace_bytes=%zu",
+                  "lanes_per_path=%lld waves_per_path=%lld paths_per_wave=%d pieces_per_path=%d segments_per_piece=%lld "
+                  "grid=%lld threads=%d lds_bytes=%zu entries_per_path=%lld workspace_bytes=%zu",
                   p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.PW > 1 ? "true" : "false", p.D, p.Q, p.NB,
-                  (long long)p.LP, (long long)p.WP, p.PW, (long long)p.grid, sg::kWave * sg::kWavesPerWG, p.lds_bytes, (long long)p.sig_len,
+                  (long long)p.LP, (long long)p.WP, p.PW, p.P, (long long)p.Lc, (long long)p.grid, sg::kWave * sg::kWavesPerWG, p.lds_bytes, (long long)p.sig_len,
                   B == 0 ? (size_t)0 : p.total);
     return SK_OK;
 }

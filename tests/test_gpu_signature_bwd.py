@@ -112,6 +112,26 @@ def test_backward_with_path_transformations(flags):
     check(paths(23, 2, 5, 8), 2, flags)
 
 
+def test_backward_paths_cut_into_pieces():
+    # forced: 2 .. 16 pieces per path, lengths that do not divide, pieces left empty, short and long sums in the
+    # adjoints of the pair products (few and many channels, low and high levels); then the library's own choice
+    for q, (B, L, d, N) in ((1, (3, 12, 2, 4)), (2, (2, 11, 3, 3)), (3, (2, 9, 3, 3)), (3, (2, 5, 4, 3)), (2, (2, 30, 5, 4)),
+                            (1, (2, 10, 16, 3)), (4, (1, 70, 2, 6)), (2, (2, 2, 3, 3)), (2, (2, 14, 2, 9)), (1, (2, 9, 6, 5)),
+                            (3, (2, 20, 1, 5)), (2, (3, 9, 20, 2))):
+        desc = sk.signature_bwd_describe(B, L, d, N, sk.SK_SIG_PIECES(q), sk.SK_F64)
+        assert "pieces_per_path=%d " % (1 << q) in desc, desc
+        a = check(paths(800 + 10 * q + d, B, L, d), N, flags=sk.SK_SIG_PIECES(q))
+        b = check(paths(800 + 10 * q + d, B, L, d), N, flags=sk.SK_SIG_PIECES(0))
+        assert np.max(np.abs(a - b)) <= 1e-11 * max(1.0, np.max(np.abs(a)))
+    check(paths(821, 2, 13, 2), 4, flags=sk.SK_SIG_PIECES(2) | sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG)
+    check(paths(822, 2, 13, 3), 3, flags=sk.SK_SIG_PIECES(2) | sk.SK_FLAG_LEAD_LAG, dtype=torch.float32)
+    check(paths(823, 2, 13, 3), 3, flags=sk.SK_SIG_PIECES(1), give_sig=True)      # the given signatures are not needed
+    for (B, L, d, N) in ((2, 400, 3, 3), (1, 1500, 2, 5), (3, 257, 5, 3)):
+        desc = sk.signature_bwd_describe(B, L, d, N, 0, sk.SK_F64)
+        assert int(desc.split("pieces_per_path=")[1].split(" ")[0]) > 1, desc
+        check(paths(830 + d, B, L, d, 0.1), N)
+
+
 def test_backward_float32():
     check(paths(31, 3, 12, 3), 4, dtype=torch.float32)
     check(paths(32, 2, 8, 16), 3, dtype=torch.float32, give_sig=True)
