@@ -10,6 +10,10 @@ method happens here.
     loss = sig_mmd2(X, Y, lam1, lam2, flags)         # squared MMD between two sets of paths, one library call
     S = signature(x, N, flags)                       # x[B,L,d] -> truncated signatures [B, entries] (Section 2)
 
+A time grid of the caller's own (Section 4 defines the time-augmented path as (x_{t_i}, t_i) and fixes no grid; the
+library's flag takes t_i = i/(L-1)) is an ordinary channel: ``with_times(x, t)`` appends it, and the wrappers below take
+``times=`` / ``times_x=, times_y=`` and do that for the caller.
+
 The gradients are first-order only (the backward pass is not itself differentiable).
 """
 import torch
@@ -105,10 +109,20 @@ class _Signature(torch.autograd.Function):
         return sk.signature_bwd(x, grad_out.contiguous(), N, flags, sig=out), None, None
 
 
-def signature(x, N, flags=0):
+def signature(x, N, flags=0, times=None):
     """Truncated signatures of device paths x[B,L,d] up to level N, levels 0..N flattened (signature_fwd);
-    differentiable in x (signature_bwd, handed the signatures of the forward call)."""
+    differentiable in x (signature_bwd, handed the signatures of the forward call).  times: a time grid of the
+    caller's own, appended as the last channel."""
+    if times is not None:
+        x = with_times(x, times)
     return _Signature.apply(x, N, flags)
+
+
+def with_times(x, t):
+    """x[..., L, d] with the channel t appended: t[L] (one grid for every path) or t[..., L]."""
+    t = torch.as_tensor(t, dtype=x.dtype, device=x.device)
+    t = t.expand(x.shape[:-1]) if t.dim() == 1 else t
+    return torch.cat([x, t.unsqueeze(-1)], dim=-1)
 
 
 def sig_mmd2(X, Y, lam1=0, lam2=0, flags=0):
@@ -117,13 +131,27 @@ def sig_mmd2(X, Y, lam1=0, lam2=0, flags=0):
     return _Mmd2.apply(X, Y, lam1, lam2, flags)
 
 
-def sig_kernel(x, y, lam1=0, lam2=0, flags=0):
-    """k[b] = k(x[b], y[b]) for device tensors x[B,L1,d], y[B,L2,d]; differentiable in x and y."""
+def sig_kernel(x, y, lam1=0, lam2=0, flags=0, times_x=None, times_y=None):
+    """k[b] = k(x[b], y[b]) for device tensors x[B,L1,d], y[B,L2,d]; differentiable in x and y.  times_x, times_y: time
+    grids of the caller's own (both or neither), appended as the last channel of each side."""
+    if (times_x is None) != (times_y is None):
+        raise ValueError("give time grids for both sides or for neither")
+    if times_x is not None:
+        x, y = with_times(x, times_x), with_times(y, times_y)
     return _PairKernel.apply(x, y, lam1, lam2, flags)
 
 
-def sig_kernel_gram(X, Y=None, lam1=0, lam2=0, flags=0):
-    """K[n,m] = k(X[n], Y[m]); Y = None is the symmetric case K(X, X); differentiable in X and Y."""
+def sig_kernel_gram(X, Y=None, lam1=0, lam2=0, flags=0, times_x=None, times_y=None):
+    """K[n,m] = k(X[n], Y[m]); Y = None is the symmetric case K(X, X); differentiable in X and Y.  times_x (and times_y
+    when Y is given): time grids of the caller's own, appended as the last channel."""
+    if times_x is not None:
+        X = with_times(X, times_x)
+        if Y is not None:
+            if times_y is None:
+                raise ValueError("give time grids for both sides or for neither")
+            Y = with_times(Y, times_y)
+    elif times_y is not None:
+        raise ValueError("give time grids for both sides or for neither")
     if Y is None:
         return _GramKernelSym.apply(X, lam1, lam2, flags)
     return _GramKernel.apply(X, Y, lam1, lam2, flags)

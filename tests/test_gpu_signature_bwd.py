@@ -223,3 +223,37 @@ def test_large_shapes_sampled_forward_and_backward(B, L, d, N):
         assert np.max(np.abs(gx[b] - gref)) <= 1e-10 * max(1.0, np.max(np.abs(gref)))
     assert np.max(np.abs(S[:, 1:1 + d] - (X[:, -1] - X[:, 0]))) <= 1e-11
     assert np.max(np.abs(gx.sum(axis=1))) <= 1e-9 * max(1.0, np.max(np.abs(gx)))
+
+
+def test_time_grids_of_the_callers_own():
+    # a general time grid is an ordinary channel: the wrappers append it; values and gradients against the oracle on
+    # the paths with that channel, and the uniform grid reproduces the library's flag
+    import oracle
+    from paper_2509_10613_amd import autograd as ag
+    rng = np.random.default_rng(91)
+    B, L, d, N = 3, 9, 2, 3
+    X, Y = paths(92, B, L, d), paths(93, B, L + 2, d)
+    tx = np.sort(rng.uniform(0, 1, size=L))
+    ty = np.sort(rng.uniform(0, 2, size=(B, L + 2)), axis=1)
+    Xt = np.concatenate([X, np.broadcast_to(tx, (B, L))[..., None]], axis=-1)
+    Yt = np.concatenate([Y, ty[..., None]], axis=-1)
+    x, y = dev(X).requires_grad_(True), dev(Y).requires_grad_(True)
+    k = ag.sig_kernel(x, y, 1, 1, times_x=dev(tx), times_y=dev(ty))
+    w = rng.normal(size=B)
+    (k * dev(w)).sum().backward()
+    kr, gxr, gyr = oracle.bwd(Xt, Yt, w, 1, 1, 0)
+    assert np.max(np.abs(host(k) - kr) / np.maximum(1.0, np.abs(kr))) <= 1e-10
+    assert np.max(np.abs(host(x.grad) - gxr[..., :d])) <= 1e-10 * max(1.0, np.max(np.abs(gxr)))
+    assert np.max(np.abs(host(y.grad) - gyr[..., :d])) <= 1e-10 * max(1.0, np.max(np.abs(gyr)))
+    xs = dev(X).requires_grad_(True)
+    S = ag.signature(xs, N, times=dev(tx))
+    ws = rng.normal(size=tuple(S.shape))
+    (S * dev(ws)).sum().backward()
+    Sr = osig.signature(Xt, N)
+    assert np.max(np.abs(host(S) - Sr) / np.maximum(1.0, np.abs(Sr))) <= 1e-10
+    gr = osig.signature_backward(Xt, ws, N)[..., :d]
+    assert np.max(np.abs(host(xs.grad) - gr)) <= 1e-10 * max(1.0, np.max(np.abs(gr)))
+    uni = np.arange(L) / (L - 1)
+    a = host(ag.signature(dev(X), N, times=dev(uni)))
+    b = host(ag.signature(dev(X), N, flags=sk.SK_FLAG_TIME_AUG))
+    assert np.max(np.abs(a - b)) <= 1e-13
