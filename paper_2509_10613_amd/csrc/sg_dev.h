@@ -31,8 +31,17 @@ struct Tree {
     static constexpr int TOT = off(M + 1);
     static constexpr int GT = M > 0 ? off(M) : 1;
 
+    // Lead-lag paths (Section 4) move one half of their channels per segment: H = 1, the lead half [0, D/2), H = 2, the
+    // lag half [D/2, 2 (D/2)); an odd D has the time channel last, which always moves.  The increments of the other
+    // channels are zero, so their multiply-adds are left out (a chain value is then the entry itself).  H = 0: all.
+    template <int H>
+    static constexpr bool moves(int c)
+    {
+        return H == 0 || ((D & 1) && c == D - 1) || (H == 1 ? c < D / 2 : (c >= D / 2 && c < 2 * (D / 2)));
+    }
+
     // levels m .. MT of the update of the owned level MT (the word of node e at level MT has length k - 1 + 1 = k)
-    template <int MT, int m>
+    template <int MT, int m, int H>
     static __device__ __forceinline__ void descend(double (&A)[TOT], double (&G)[GT], const double (&zz)[D])
     {
         constexpr int np = cnt(m - 1);
@@ -43,15 +52,19 @@ struct Tree {
 #pragma unroll
             for (int c = 0; c < D; ++c) {
                 const int i = off(m) + e * D + c;
-                if (m < MT) G[i] = __builtin_fma(gs, zz[c], A[i]);
-                else A[i] = __builtin_fma(gs, zz[c], A[i]);
+                if (moves<H>(c)) {
+                    if (m < MT) G[i] = __builtin_fma(gs, zz[c], A[i]);
+                    else A[i] = __builtin_fma(gs, zz[c], A[i]);
+                } else if (m < MT) {
+                    G[i] = A[i];
+                }
             }
         }
-        if constexpr (m < MT) descend<MT, m + 1>(A, G, zz);
+        if constexpr (m < MT) descend<MT, m + 1, H>(A, G, zz);
     }
 
     // g = G_k[u] for k = Q + 1 + MT; zc = the increments at the lane's S letters
-    template <int MT>
+    template <int MT, int H = 0>
     static __device__ __forceinline__ void level(double (&A)[TOT], double g, const double (&zc)[S], const double (&zz)[D])
     {
         if constexpr (MT == 0) {
@@ -62,7 +75,7 @@ struct Tree {
             const double g0 = g * (1.0 / (double)(MT + 1));
 #pragma unroll
             for (int s = 0; s < S; ++s) G[s] = __builtin_fma(g0, zc[s], A[s]);
-            descend<MT, 1>(A, G, zz);
+            descend<MT, 1, H>(A, G, zz);
         }
     }
 
@@ -177,12 +190,12 @@ __device__ __forceinline__ double prefix_chain(int Q, const double (&preR)[QA], 
     return g;
 }
 
-template <int MT, int D, int M, int S, int QC, int TOT, int QA>
+template <int MT, int D, int M, int S, int QC, int TOT, int QA, int H = 0>
 __device__ __forceinline__ void owned_levels(double (&A)[TOT], int Q, const double (&preR)[QA],
                                              const double (&zuR)[QA], const double (&zc)[S], const double (&zz)[D])
 {
-    Tree<D, M, S>::template level<MT>(A, prefix_chain<MT + 1, QC, QA>(Q, preR, zuR), zc, zz);
-    if constexpr (MT > 0) owned_levels<MT - 1, D, M, S, QC, TOT, QA>(A, Q, preR, zuR, zc, zz);
+    Tree<D, M, S>::template level<MT, H>(A, prefix_chain<MT + 1, QC, QA>(Q, preR, zuR), zc, zz);
+    if constexpr (MT > 0) owned_levels<MT - 1, D, M, S, QC, TOT, QA, H>(A, Q, preR, zuR, zc, zz);
 }
 
 // the carried entries at the prefixes of u: word length Q - r0, longest first

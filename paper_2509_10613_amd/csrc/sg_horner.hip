@@ -43,7 +43,9 @@ __device__ __forceinline__ void store_owned(const double (&A)[TOT], double* out,
 // DT == 0: any number of channels, M = 0, S = 1 (a lane owns one word of the top level).
 // SHARED: a wave holds several short paths (lanes per path at most 32): lane groups of LP lanes, each group a path
 // of its own; the increments are then per-lane values and come in by ordinary loads.
-template <int DT, int M, int S, int QC, bool SHARED>
+// LEADLAG: the rows alternate between a move of the lead half (even rows) and of the lag half (odd rows) of the
+// channels; the multiply-adds with the half that stands still are left out.
+template <int DT, int M, int S, int QC, bool SHARED, bool LEADLAG>
 __device__ __forceinline__ void run(const Args& a)
 {
     constexpr int DD = DT > 0 ? DT : 1;
@@ -128,11 +130,13 @@ __device__ __forceinline__ void run(const Args& a)
 #pragma unroll
     for (int r = 0; r < QA; ++r) zuR[r] = 0.0;
     for (long step = 0; step < a.np; step += 2) {
+        // the set carried round the loop holds the odd rows (lag half; the zero increment at the start fits any
+        // half), the other set the even rows (lead half)
         fetch(step, zzn, zcn, zuRn);
-        owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, zuR, zc, zz);
+        owned_levels<M, DD, M, S, QC, T::TOT, QA, LEADLAG ? 2 : 0>(A, Q, preR, zuR, zc, zz);
         prefix_levels<QC, QA>(Q, preR, zuR);
         fetch(step + 1 < a.np ? step + 1 : step, zz, zc, zuR);
-        owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, zuRn, zcn, zzn);
+        owned_levels<M, DD, M, S, QC, T::TOT, QA, LEADLAG ? 1 : 0>(A, Q, preR, zuRn, zcn, zzn);
         prefix_levels<QC, QA>(Q, preR, zuRn);
     }
 
@@ -163,10 +167,10 @@ __device__ __forceinline__ void run(const Args& a)
     store_owned<0, DD, M, S, T::TOT>(A, out, at, D, rest * D + blk * S, blk * S);
 }
 
-template <int DT, int M, int S, int QC, bool SHARED>
+template <int DT, int M, int S, int QC, bool SHARED, bool LEADLAG>
 __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_kernel(const Args a)
 {
-    run<DT, M, S, QC, SHARED>(a);
+    run<DT, M, S, QC, SHARED, LEADLAG>(a);
 }
 
 // Increments of the transformed paths (Section 4), one row of Dpad doubles per segment: channels of the path (after
@@ -254,7 +258,15 @@ __global__ __launch_bounds__(256) void chen_pairs_kernel(const double* __restric
 template <int DT, int M, int S, int QC, bool SHARED>
 hipError_t launch_one(const Args& a, long grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((horner_kernel<DT, M, S, QC, SHARED>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), 0, st, a);
+    // kernels that skip the half of the channels a lead-lag segment does not move: where a lane has registers over
+    // those channels at all (M >= 1) and at least four channels
+    if constexpr (DT >= 4 && M >= 1) {
+        if (a.leadlag) {
+            hipLaunchKernelGGL((horner_kernel<DT, M, S, QC, SHARED, true>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), 0, st, a);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((horner_kernel<DT, M, S, QC, SHARED, false>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), 0, st, a);
     return hipGetLastError();
 }
 
@@ -298,6 +310,7 @@ hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStre
     if (a.PW < 1 || (a.PW > 1 && (a.WP != 1 || a.PW * a.LP > kWave || a.NW * a.PW < a.B)) || (a.PW == 1 && a.NW != a.B * a.WP) ||
         grid * kWavesPerWG < a.NW)
         return hipErrorInvalidValue;
+    if (a.leadlag && (a.n & 1)) return hipErrorInvalidValue;      // pieces of a lead-lag path start with a lead move
     if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, st) : hipErrorInvalidValue;
 #define SG_CASE(D_, M_, S_) \
     if (DT == D_ && M == M_ && S == S_) return launch_variant<D_, M_, S_>(a, grid, st);

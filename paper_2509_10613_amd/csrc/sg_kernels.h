@@ -18,6 +18,7 @@ struct Args {
     long sig_len;
     int PW;             // paths per wave (1, or several short paths side by side in a wave: then WP = 1)
     long NW;            // waves of the launch
+    int leadlag;        // rows alternate between moves of the lead and of the lag half of the channels (n is even)
 };
 
 struct BwdArgs {

@@ -207,6 +207,7 @@ inline Plan make_plan(int64_t B, int64_t L, int64_t d, int N, bool time_aug, boo
             if (B > 0 && (p.sig_len > ((int64_t)1 << 44) / (B * P))) { p.why = "too many pieces for this signature size"; return p; }
             p.P = P;
             p.Lc = (p.n + P - 1) / P;
+            if (lead_lag) p.Lc += p.Lc & 1;      // a piece starts with a move of the lead half
             p.np = p.Lc | 1;
             p.VB = B * P;
             if (!choose(p.VB)) return p;

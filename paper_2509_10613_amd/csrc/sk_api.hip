@@ -546,6 +546,7 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
     a.out = p.P > 1 ? reinterpret_cast<double*>(base + p.off_t0) : result;
     a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.PW = p.PW; a.NW = p.waves;
+    a.leadlag = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -620,6 +621,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
         f.out = out;
         f.B = pf.VB; f.n = pf.Lc; f.np = pf.np; f.D = pf.D; f.Dpad = pf.Dpad; f.N = pf.N; f.Q = pf.Q; f.NB = pf.NB;
         f.LP = pf.LP; f.WP = pf.WP; f.sig_len = pf.sig_len; f.PW = pf.PW; f.NW = pf.waves;
+        f.leadlag = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
         return f;
     };
     const double* sig64;
