@@ -81,7 +81,7 @@ struct Tree {
 
     // ---- the adjoint of the step (used by the backward kernels) ----
     // The chain values of owned level MT >= 1 as the forward step forms them: G[off(m) + i], m = 0 .. MT - 1.
-    template <int MT, int m>
+    template <int MT, int m, int H>
     static __device__ __forceinline__ void chain_descend(const double (&A)[TOT], double (&G)[GT], const double (&zz)[D])
     {
         if constexpr (m < MT) {
@@ -90,14 +90,19 @@ struct Tree {
             for (int e = 0; e < np; ++e) {
                 const double gs = G[off(m - 1) + e] * (1.0 / (double)(MT + 1 - m));
 #pragma unroll
-                for (int c = 0; c < D; ++c) G[off(m) + e * D + c] = __builtin_fma(gs, zz[c], A[off(m) + e * D + c]);
+                for (int c = 0; c < D; ++c) {
+                    const int i = off(m) + e * D + c;
+                    G[i] = moves<H>(c) ? __builtin_fma(gs, zz[c], A[i]) : A[i];
+                }
             }
-            chain_descend<MT, m + 1>(A, G, zz);
+            chain_descend<MT, m + 1, H>(A, G, zz);
         }
     }
 
     // adjoints from level m up to the roots; Gb[off(m) ..] is complete when this is entered
-    template <int MT, int m>
+    // (channels that stand still in a lead-lag segment: their increments are zero and are no variables, so neither
+    // their products nor their adjoints are formed)
+    template <int MT, int m, int H>
     static __device__ __forceinline__ void ascend_rev(double (&Ab)[TOT], const double (&G)[GT], double (&Gb)[GT],
                                                       const double (&zz)[D], double (&zzb)[D])
     {
@@ -112,19 +117,21 @@ struct Tree {
                 for (int c = 0; c < D; ++c) {
                     const int i = off(m) + e * D + c;
                     Ab[i] += Gb[i];                               // the chain value holds the old entry itself
-                    acc = __builtin_fma(Gb[i], zz[c], acc);
-                    zzb[c] = __builtin_fma(Gb[i], gs, zzb[c]);
+                    if (moves<H>(c)) {
+                        acc = __builtin_fma(Gb[i], zz[c], acc);
+                        zzb[c] = __builtin_fma(Gb[i], gs, zzb[c]);
+                    }
                 }
                 Gb[off(m - 1) + e] = acc * f;
             }
-            ascend_rev<MT, m - 1>(Ab, G, Gb, zz, zzb);
+            ascend_rev<MT, m - 1, H>(Ab, G, Gb, zz, zzb);
         }
     }
 
     // Adjoint of the update of owned level MT: A holds the entries before the step, Ab the adjoints (those of level MT
     // are read, those of the lower owned levels receive their share), gP = G_k[u]; returns the adjoint of gP and adds
     // to the adjoints of the increments.
-    template <int MT>
+    template <int MT, int H = 0>
     static __device__ __forceinline__ double level_rev(const double (&A)[TOT], double (&Ab)[TOT], double gP,
                                                        const double (&zc)[S], const double (&zz)[D], double (&zcb)[S],
                                                        double (&zzb)[D])
@@ -142,7 +149,7 @@ struct Tree {
             const double g0 = gP * i0;
 #pragma unroll
             for (int s = 0; s < S; ++s) G[s] = __builtin_fma(g0, zc[s], A[s]);
-            chain_descend<MT, 1>(A, G, zz);
+            chain_descend<MT, 1, H>(A, G, zz);
             // the entries of level MT themselves: A_new = A + G[parent] z[c]
             constexpr int np = cnt(MT - 1);
 #pragma unroll
@@ -152,12 +159,14 @@ struct Tree {
 #pragma unroll
                 for (int c = 0; c < D; ++c) {
                     const int i = off(MT) + e * D + c;
-                    acc = __builtin_fma(Ab[i], zz[c], acc);
-                    zzb[c] = __builtin_fma(Ab[i], gs, zzb[c]);
+                    if (moves<H>(c)) {
+                        acc = __builtin_fma(Ab[i], zz[c], acc);
+                        zzb[c] = __builtin_fma(Ab[i], gs, zzb[c]);
+                    }
                 }
                 Gb[off(MT - 1) + e] = acc;
             }
-            ascend_rev<MT, MT - 1>(Ab, G, Gb, zz, zzb);
+            ascend_rev<MT, MT - 1, H>(Ab, G, Gb, zz, zzb);
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 Ab[s] += Gb[s];
@@ -280,7 +289,7 @@ __device__ __forceinline__ void prefix_levels_rev(int Q, const double (&preR)[QA
     }
 }
 
-template <int MT, int D, int M, int S, int QC, int TOT, int QA>
+template <int MT, int D, int M, int S, int QC, int TOT, int QA, int H = 0>
 __device__ __forceinline__ void owned_levels_rev(const double (&A)[TOT], double (&Ab)[TOT], int Q,
                                                  const double (&preR)[QA], double (&prb)[QA], const double (&zuR)[QA],
                                                  const double (&zc)[S], const double (&zz)[D], double (&zub)[QA],
@@ -288,9 +297,9 @@ __device__ __forceinline__ void owned_levels_rev(const double (&A)[TOT], double 
 {
     double h[QA + 1];
     const double gP = prefix_chain_keep<MT + 1, QC, QA>(Q, preR, zuR, h);
-    const double gPb = Tree<D, M, S>::template level_rev<MT>(A, Ab, gP, zc, zz, zcb, zzb);
+    const double gPb = Tree<D, M, S>::template level_rev<MT, H>(A, Ab, gP, zc, zz, zcb, zzb);
     prefix_chain_rev<MT + 1, QC, QA>(Q, zuR, h, gPb, prb, zub);
-    if constexpr (MT < M) owned_levels_rev<MT + 1, D, M, S, QC, TOT, QA>(A, Ab, Q, preR, prb, zuR, zc, zz, zub, zcb, zzb);
+    if constexpr (MT < M) owned_levels_rev<MT + 1, D, M, S, QC, TOT, QA, H>(A, Ab, Q, preR, prb, zuR, zc, zz, zub, zcb, zzb);
 }
 
 }  // namespace sg

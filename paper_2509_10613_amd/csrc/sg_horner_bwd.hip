@@ -37,7 +37,9 @@ __device__ __forceinline__ void load_owned(double (&A)[TOT], const double* src, 
 
 // SHARED: a wave holds several short paths (lane groups of LP <= 32 lanes, as in the forward kernel); a path then
 // lives in one wave, and the sums of dF/dz over its lanes are stored, not added.
-template <int DT, int M, int S, int QC, bool SHARED>
+// LEADLAG: even rows move the lead half of the channels, odd rows the lag half; the multiply-adds and adjoints of the
+// half that stands still are left out, as in the forward kernel.
+template <int DT, int M, int S, int QC, bool SHARED, bool LEADLAG>
 __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
 {
     constexpr int DD = DT > 0 ? DT : 1;
@@ -224,7 +226,8 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
     };
 
     // one segment backwards; row < 0: the zero increment that starts the loop, nothing to add anywhere
-    auto segment = [&](long row, const double (&z_)[DD], const double (&zc_)[S], const double (&zu_)[QA]) {
+    auto segment = [&](auto half, long row, const double (&z_)[DD], const double (&zc_)[S], const double (&zu_)[QA]) {
+        constexpr int H = decltype(half)::value;
         // the signature before the segment: the forward step with the increment negated
         double nz[DD], nzc[S], nzu[QA];
 #pragma unroll
@@ -233,7 +236,7 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
         for (int s = 0; s < S; ++s) nzc[s] = -zc_[s];
 #pragma unroll
         for (int r = 0; r < QA; ++r) nzu[r] = -zu_[r];
-        owned_levels<M, DD, M, S, QC, T::TOT, QA>(A, Q, preR, nzu, nzc, nz);
+        owned_levels<M, DD, M, S, QC, T::TOT, QA, H>(A, Q, preR, nzu, nzc, nz);
         prefix_levels<QC, QA>(Q, preR, nzu);
         // the adjoint of the forward step from that signature with the increment itself
         double zzb[DD], zcb[S], zub[QA];
@@ -244,7 +247,7 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
 #pragma unroll
         for (int r = 0; r < QA; ++r) zub[r] = 0.0;
         prefix_levels_rev<QC, QA>(Q, preR, zu_, prb, zub);
-        owned_levels_rev<0, DD, M, S, QC, T::TOT, QA>(A, Ab, Q, preR, prb, zu_, zc_, z_, zub, zcb, zzb);
+        owned_levels_rev<0, DD, M, S, QC, T::TOT, QA, H>(A, Ab, Q, preR, prb, zu_, zc_, z_, zub, zcb, zzb);
         if constexpr (SHARED) {
             reduce_step_shared(row, zzb, zcb, zub);
         } else if constexpr (kRows) {
@@ -278,10 +281,11 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
     for (int r = 0; r < QA; ++r) zuR[r] = 0.0;
     long rowA = -1;
     for (long row = a.np - 1; row >= 0; row -= 2) {
+        // `row` is even (np is odd): the lead half moves; the set carried round the loop holds odd rows
         fetch(row, zzn, zcn, zuRn);
-        segment(rowA, zz, zc, zuR);
+        segment(std::integral_constant<int, LEADLAG ? 2 : 0>(), rowA, zz, zc, zuR);
         fetch(row > 0 ? row - 1 : 0, zz, zc, zuR);
-        segment(row, zzn, zcn, zuRn);
+        segment(std::integral_constant<int, LEADLAG ? 1 : 0>(), row, zzn, zcn, zuRn);
         rowA = row - 1;
     }
     if constexpr (kRows) {
@@ -301,11 +305,11 @@ __device__ __forceinline__ void run_bwd(const BwdArgs& a, double* lds)
     }
 }
 
-template <int DT, int M, int S, int QC, bool SHARED>
+template <int DT, int M, int S, int QC, bool SHARED, bool LEADLAG>
 __global__ __launch_bounds__(kWave * kWavesPerWG) void horner_bwd_kernel(const BwdArgs a)
 {
     extern __shared__ double lds[];
-    run_bwd<DT, M, S, QC, SHARED>(a, lds);
+    run_bwd<DT, M, S, QC, SHARED, LEADLAG>(a, lds);
 }
 
 // dF/dx from dF/dz (one row per segment of the transformed path): a point gains what the segment before it gives and
@@ -387,7 +391,15 @@ __global__ __launch_bounds__(256) void chen_pairs_adjoint_kernel(const double* _
 template <int DT, int M, int S, int QC, bool SHARED>
 hipError_t launch_one(const BwdArgs& a, long grid, size_t lds_bytes, hipStream_t st)
 {
-    hipLaunchKernelGGL((horner_bwd_kernel<DT, M, S, QC, SHARED>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG), lds_bytes, st, a);
+    if constexpr (DT >= 4 && M >= 1) {
+        if (a.leadlag) {
+            hipLaunchKernelGGL((horner_bwd_kernel<DT, M, S, QC, SHARED, true>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG),
+                               lds_bytes, st, a);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((horner_bwd_kernel<DT, M, S, QC, SHARED, false>), dim3((unsigned)grid), dim3(kWave * kWavesPerWG),
+                       lds_bytes, st, a);
     return hipGetLastError();
 }
 
@@ -433,6 +445,7 @@ hipError_t launch_horner_bwd(int DT, int M, int S, const BwdArgs& a, long grid, 
     if (a.PW < 1 || (a.PW > 1 && (a.WP != 1 || a.PW * a.LP > kWave || a.NW * a.PW < a.B)) || (a.PW == 1 && a.NW != a.B * a.WP) ||
         grid * kWavesPerWG < a.NW)
         return hipErrorInvalidValue;
+    if (a.leadlag && (a.n & 1)) return hipErrorInvalidValue;      // pieces of a lead-lag path start with a lead move
     if (DT == 0) return (M == 0 && S == 1) ? launch_variant<0, 0, 1>(a, grid, lds_bytes, st) : hipErrorInvalidValue;
 #define SG_CASE(D_, M_, S_) \
     if (DT == D_ && M == M_ && S == S_) return launch_variant<D_, M_, S_>(a, grid, lds_bytes, st);

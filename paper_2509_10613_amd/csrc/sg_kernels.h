@@ -34,6 +34,7 @@ struct BwdArgs {
     size_t lds_wave;     // doubles of LDS per wave
     int PW;              // paths per wave (several short paths side by side: then WP = 1)
     long NW;             // waves of the launch
+    int leadlag;         // rows alternate between moves of the lead and of the lag half of the channels (n is even)
 };
 
 hipError_t launch_horner(int DT, int M, int S, const Args& a, long grid, hipStream_t st);

@@ -674,6 +674,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
     a.dz = dz; a.gz = gz; a.sig = sig64; a.gout = gout64;
     a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.lds_wave = p.lds_wave; a.PW = p.PW; a.NW = p.waves;
+    a.leadlag = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
     if (timed && p.P == 1) {
         SK_CHECK(hipEventCreate(&tl.start));
         SK_CHECK(hipEventCreate(&tl.stop));
@@ -765,10 +766,11 @@ int signature_bwd_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk
     int rc = sig_validate(B, L, d, N, flags, (int)dt, &p, true, true);
     if (rc != SK_OK) return rc;
     std::snprintf(out, out_bytes,
-                  "kernel=horner_bwd_kernel<%d, %d, %d, %d, %s> channels=%d prefix_letters=%d letter_blocks=%d "
+                  "kernel=horner_bwd_kernel<%d, %d, %d, %d, %s, %s> channels=%d prefix_letters=%d letter_blocks=%d "
                   "lanes_per_path=%lld waves_per_path=%lld paths_per_wave=%d pieces_per_path=%d segments_per_piece=%lld "
                   "grid=%lld threads=%d lds_bytes=%zu entries_per_path=%lld workspace_bytes=%zu",
-                  p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.PW > 1 ? "true" : "false", p.D, p.Q, p.NB,
+                  p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.PW > 1 ? "true" : "false",
+                  ((flags & SK_FLAG_LEAD_LAG) && p.DT >= 4 && p.M >= 1) ? "true" : "false", p.D, p.Q, p.NB,
                   (long long)p.LP, (long long)p.WP, p.PW, p.P, (long long)p.Lc, (long long)p.grid, sg::kWave * sg::kWavesPerWG, p.lds_bytes, (long long)p.sig_len,
                   B == 0 ? (size_t)0 : p.total);
     return SK_OK;
@@ -782,10 +784,11 @@ int signature_describe(int64_t B, int64_t L, int64_t d, int N, int flags, sk_dty
     int rc = sig_validate(B, L, d, N, flags, (int)dt, &p);
     if (rc != SK_OK) return rc;
     std::snprintf(out, out_bytes,
-                  "kernel=horner_kernel<%d, %d, %d, %d, %s> channels=%d prefix_letters=%d letter_blocks=%d lanes_per_path=%lld "
+                  "kernel=horner_kernel<%d, %d, %d, %d, %s, %s> channels=%d prefix_letters=%d letter_blocks=%d lanes_per_path=%lld "
                   "waves_per_path=%lld paths_per_wave=%d pieces_per_path=%d segments_per_piece=%lld grid=%lld threads=%d "
                   "entries_per_path=%lld workspace_bytes=%zu",
-                  p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.PW > 1 ? "true" : "false", p.D, p.Q, p.NB,
+                  p.DT, p.M, p.S, p.Q <= sg::kQExact ? p.Q : sg::kQMax, p.PW > 1 ? "true" : "false",
+                  ((flags & SK_FLAG_LEAD_LAG) && p.DT >= 4 && p.M >= 1) ? "true" : "false", p.D, p.Q, p.NB,
                   (long long)p.LP, (long long)p.WP, p.PW, p.P, (long long)p.Lc, (long long)p.grid, sg::kWave * sg::kWavesPerWG, (long long)p.sig_len,
                   B == 0 ? (size_t)0 : p.total);
     return SK_OK;

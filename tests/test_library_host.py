@@ -184,29 +184,29 @@ def test_signature_launch_plans(lib):
         return kern, vals
     # the three shapes of Table 1: deepest subtree that still gives every SIMD a wave
     kern, v = plan(128, 256, 4, 6)     # too few waves for the chip as whole paths: cut into 4 pieces of 64 segments
-    assert kern == "horner_kernel<4, 2, 1, 3, false>" and v["lanes_per_path"] == 256 and v["grid"] == 512
+    assert kern == "horner_kernel<4, 2, 1, 3, false, false>" and v["lanes_per_path"] == 256 and v["grid"] == 512
     assert v["pieces_per_path"] == 4 and v["segments_per_piece"] == 64
     kern, v = plan(128, 256, 4, 6, binding.SK_SIG_PIECES(0))
-    assert kern == "horner_kernel<4, 2, 1, 3, false>" and v["grid"] == 128 and v["pieces_per_path"] == 1
+    assert kern == "horner_kernel<4, 2, 1, 3, false, false>" and v["grid"] == 128 and v["pieces_per_path"] == 1
     kern, v = plan(128, 512, 8, 5)
-    assert kern == "horner_kernel<8, 2, 1, 2, false>" and v["lanes_per_path"] == 512 and v["grid"] == 256
+    assert kern == "horner_kernel<8, 2, 1, 2, false, false>" and v["lanes_per_path"] == 512 and v["grid"] == 256
     assert v["pieces_per_path"] == 1
     kern, v = plan(128, 1024, 16, 4)
-    assert kern == "horner_kernel<16, 1, 4, 2, false>" and v["lanes_per_path"] == 1024 and v["grid"] == 512
+    assert kern == "horner_kernel<16, 1, 4, 2, false, false>" and v["lanes_per_path"] == 1024 and v["grid"] == 512
     assert v["entries_per_path"] == 69905 and v["pieces_per_path"] == 1
     # the shape of the paper's figure (32 long paths): pieces of at least 32 segments
     kern, v = plan(32, 1024, 5, 4)
     assert v["pieces_per_path"] == 16 and v["segments_per_piece"] == 64
     # a large batch prefers the deepest subtree; channel counts without a kernel of their own, and one channel, take
     # the run-time kernel; the transformations change the channel count the plan sees
-    assert plan(100000, 50, 3, 8)[0] == "horner_kernel<3, 3, 1, 4, false>"
-    assert plan(4, 50, 20, 3)[0] == "horner_kernel<0, 0, 1, 2, false>"
-    assert plan(4, 50, 1, 5)[0] == "horner_kernel<0, 0, 1, 4, false>"
+    assert plan(100000, 50, 3, 8)[0] == "horner_kernel<3, 3, 1, 4, false, false>"
+    assert plan(4, 50, 20, 3)[0] == "horner_kernel<0, 0, 1, 2, false, false>"
+    assert plan(4, 50, 1, 5)[0] == "horner_kernel<0, 0, 1, 4, false, false>"
     assert plan(4, 50, 2, 3, binding.SK_FLAG_TIME_AUG | binding.SK_FLAG_LEAD_LAG)[1]["channels"] == 5
     # lanes of a wave never span two paths, every lane's words fit the level count, the grid covers all waves
     for (B, L, d, N) in [(3, 9, 5, 4), (7, 5, 11, 3), (2, 4, 17, 4), (1, 3, 2, 14), (9, 9, 9, 9)]:
         kern, v = plan(B, L, d, N)
-        D, M, S, QC = (int(t) for t in re.search(r"<(\d+), (\d+), (\d+), (\d+), \w+>", kern).groups())
+        D, M, S, QC = (int(t) for t in re.search(r"<(\d+), (\d+), (\d+), (\d+), \w+, \w+>", kern).groups())
         Q = v["prefix_letters"]
         assert Q == N - M - 1 and (QC == Q or (QC == 8 and 4 < Q <= 8))
         assert v["letter_blocks"] * S >= d and (v["letter_blocks"] - 1) * S < d
@@ -238,10 +238,17 @@ def test_signature_backward_host_side(lib):
     assert base <= w0 < base + 1024 and w1 >= w0 + 4 * n * 8 and w2 >= w0 + 2 * 4 * n * 8
     # launch plans: the backward variants hold entries and adjoints, so the subtrees are smaller than the forward's
     text = binding.signature_bwd_describe(128, 1024, 16, 4, 0, binding.SK_F64)
-    assert "horner_bwd_kernel<16, 1, 2, 2, false>" in text and "lanes_per_path=2048" in text and "grid=1024" in text
-    assert "horner_bwd_kernel<8, 1, 4, 3, false>" in binding.signature_bwd_describe(128, 512, 8, 5, 0, binding.SK_F64)
-    assert "horner_bwd_kernel<0, 0, 1, 2, false>" in binding.signature_bwd_describe(4, 9, 20, 3, 0, binding.SK_F64)
+    assert "horner_bwd_kernel<16, 1, 2, 2, false, false>" in text and "lanes_per_path=2048" in text and "grid=1024" in text
+    assert "horner_bwd_kernel<8, 1, 4, 3, false, false>" in binding.signature_bwd_describe(128, 512, 8, 5, 0, binding.SK_F64)
+    assert "horner_bwd_kernel<0, 0, 1, 2, false, false>" in binding.signature_bwd_describe(4, 9, 20, 3, 0, binding.SK_F64)
     lds = int(re.search(r"lds_bytes=(\d+)", text).group(1))
     assert lds == 4 * (16 + 64 * 17) * 8
+    # lead-lag paths take the kernels that leave out the half of the channels a segment does not move
+    assert "horner_bwd_kernel<16, 1, 2, 2, false, true>" in binding.signature_bwd_describe(
+        128, 512, 8, 4, binding.SK_FLAG_LEAD_LAG, binding.SK_F64)
+    assert "horner_kernel<16, 1, 4, 2, false, true>" in binding.signature_describe(
+        128, 512, 8, 4, binding.SK_FLAG_LEAD_LAG, binding.SK_F64)
+    assert "horner_kernel<2, 3, 1, 2, true, false>" in binding.signature_describe(    # two channels: no such form
+        128, 512, 1, 6, binding.SK_FLAG_LEAD_LAG, binding.SK_F64)
     with pytest.raises(binding.SigKernelError):
         binding.signature_bwd_describe(4, 9, 2000, 2, 0, binding.SK_F64)    # beyond the run-time kernel's channel limit
