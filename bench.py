@@ -148,6 +148,9 @@ def main():
     ap.add_argument("--mmd", action="store_true",
                     help="Gram workloads: a step is one sigkernel_mmd2 call (value and both gradients): K(X,X), K(X,Y) "
                          "and K(Y,Y) with gradients (a side measurement, not the headline; no roofline figure)")
+    ap.add_argument("--no-keep-forward", action="store_true",
+                    help="pair workloads: the backward call sweeps forward again instead of taking over the sweep of the "
+                         "forward call before it (SK_FLAG_KEEP_FORWARD / SK_FLAG_HAVE_FORWARD)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -203,15 +206,19 @@ def main():
         k2 = torch.empty_like(k)
         gx = torch.empty_like(x)
         gy = torch.empty_like(y)
-        need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags, f64),
+        # A step is a forward call followed by a backward call on the same paths and workspace, so the forward call
+        # keeps its sweep for the backward call (launch modes without that form ignore the two flags).
+        keep = sk.SK_FLAG_KEEP_FORWARD if (w.backward and not args.no_keep_forward) else 0
+        have = sk.SK_FLAG_HAVE_FORWARD if keep else 0
+        need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags | keep, f64),
                    sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags, f64))
         ws = torch.empty(need, dtype=torch.uint8, device=dev)
 
         def fwd_call():
-            sk.sigkernel_fwd(x, y, lam, lam, flags, k=k, ws=ws)
+            sk.sigkernel_fwd(x, y, lam, lam, flags | keep, k=k, ws=ws)
 
         def bwd_call():
-            sk.sigkernel_bwd(x, y, gk, lam, lam, flags, grad_x=gx, grad_y=gy, k_out=k2, ws=ws)
+            sk.sigkernel_bwd(x, y, gk, lam, lam, flags | have, grad_x=gx, grad_y=gy, k_out=k2, ws=ws)
 
     def step():
         fwd_call()
@@ -287,8 +294,8 @@ def main():
         desc = sk.sigkernel_describe(sk.SK_OP_GRAM_BWD if dom_back else sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, lam,
                                      lam, flags, f64)
     else:
-        desc = sk.sigkernel_describe(sk.SK_OP_BWD if dom_back else sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam, flags,
-                                     f64)
+        desc = sk.sigkernel_describe(sk.SK_OP_BWD if dom_back else sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam,
+                                     flags | (have if dom_back else keep), f64)
     plan = dict(kv.split("=", 1) for kv in desc.split(" ") if "=" in kv and not kv.startswith("kernel="))
     kname = desc.split("kernel=", 1)[1].split(" grid=", 1)[0] if "kernel=" in desc else "?"
     roofline = {"bound": "alu", "kernel": kname, "launch": plan,
@@ -347,7 +354,8 @@ def main():
             w.name, w.kind, w.pairs, w.L, w.d, lam,
             (", time-augmented" if flags & 1 else "") + (", lead-lag transformed" if args.lead_lag else "") +
             (", K(X,X)" if args.symmetric else ""),
-            "+bwd" if w.backward else ""), "cells_per_step": cells},
+            "+bwd" if w.backward else ""), "cells_per_step": cells,
+            "forward_sweep_kept_for_backward": bool((not gram) and w.backward and not args.no_keep_forward)},
         "evals_per_s": w.pairs / sec_per_step,
         # K(X, X): the library solves the pairs n <= m only (k(x, y) = k(y, x) bit for bit) and copies the rest
         "pairs_solved": (w.n_x * (w.n_x + 1) // 2) if args.symmetric else w.pairs,

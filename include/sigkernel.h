@@ -51,6 +51,9 @@ enum {
     SK_FLAG_TIME_AUG = 1,   /* append the channel t_i = i/(L-1) to both paths on the fly (Section 4) */
     SK_FLAG_BWD_REPLAY = 2, /* backward: replay forward segments instead of inverting Eq. (1); see sigkernel_bwd */
     SK_FLAG_LEAD_LAG = 8,   /* lead-lag transform of both paths on the fly (Section 4) */
+    SK_FLAG_KEEP_FORWARD = 16, /* sigkernel_fwd: leave the forward sweep in the workspace for the backward call
+                                  (Section 3.4: the backward pass works on the forward pass's grid); see sigkernel_bwd */
+    SK_FLAG_HAVE_FORWARD = 32, /* sigkernel_bwd: the workspace holds the forward sweep a sigkernel_fwd call kept */
     SK_FLAG_SHORT_WAITS = 4 /* diagnostic: a workgroup that waits for another one's progress gives up after a single
                                poll.  Exercises the path a wait that runs out takes: every kernel still ends normally
                                and the results of the call are NaN.  Only launches whose workgroups wait for each
@@ -96,6 +99,16 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  * order one make the inverse recurrence ill-conditioned), the gradients of that pair - or, depending on the
  * launch mode, every gradient of the call - are returned as NaN, never as inaccurate numbers.
  * SK_FLAG_BWD_REPLAY selects the slower variant that replays forward segments and has no such limit.
+ *
+ * A forward sweep that was kept.  A training step calls sigkernel_fwd and then sigkernel_bwd on the same paths; the
+ * backward call then need not sweep forward again.  sigkernel_fwd with SK_FLAG_KEEP_FORWARD takes the workspace of
+ * the backward call (sigkernel_workspace_bytes reports that size for SK_OP_FWD with the flag) and leaves the
+ * checkpoints of its sweep there; sigkernel_bwd with SK_FLAG_HAVE_FORWARD, the same workspace, x, y, shapes, lam and
+ * other flags, and no other call on that workspace in between, runs the reverse sweep from them (and leaves them as
+ * they are: the backward call may be repeated, say with another grad_k).  The caller vouches
+ * for all of that: the library cannot check it, and a workspace that holds something else gives wrong gradients (or
+ * NaN through the drift check).  Launch modes without this form ignore both flags (the forward call runs as usual,
+ * the backward call sweeps forward itself), so results never depend on the flags; sigkernel_describe names the kernels.
  */
 int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
                   int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,

@@ -28,6 +28,17 @@ class _PairKernel(torch.autograd.Function):
         y = y.contiguous()
         ctx.save_for_backward(x, y)
         ctx.args = (lam1, lam2, flags)
+        ctx.ws = None
+        # Where the launch mode can hand its forward sweep to the backward call, this call keeps it in a workspace of
+        # its own, which lives until the graph is freed (the grid the paper's backward pass takes over from its
+        # forward pass, here as checkpoints).
+        B, L1, d = x.shape
+        if (ctx.needs_input_grad[0] or ctx.needs_input_grad[1]) and sk.keeps_forward(B, L1, y.shape[1], d, lam1, lam2,
+                                                                                     flags, sk._dt(x)):
+            need = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L1, y.shape[1], d, lam1, lam2,
+                                                flags | sk.SK_FLAG_KEEP_FORWARD, sk._dt(x))
+            ctx.ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=x.device)
+            return sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ctx.ws)
         return sk.sigkernel_fwd(x, y, lam1, lam2, flags)
 
     @staticmethod
@@ -37,7 +48,11 @@ class _PairKernel(torch.autograd.Function):
         want_x, want_y = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
         if not (want_x or want_y):
             return None, None, None, None, None
-        _, gx, gy = sk.sigkernel_bwd(x, y, grad_k.contiguous(), lam1, lam2, flags, want_x=want_x, want_y=want_y)
+        if ctx.ws is not None:
+            _, gx, gy = sk.sigkernel_bwd(x, y, grad_k.contiguous(), lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD,
+                                         want_x=want_x, want_y=want_y, ws=ctx.ws)
+        else:
+            _, gx, gy = sk.sigkernel_bwd(x, y, grad_k.contiguous(), lam1, lam2, flags, want_x=want_x, want_y=want_y)
         return gx, gy, None, None, None
 
 

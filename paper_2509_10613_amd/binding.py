@@ -16,6 +16,8 @@ SK_FLAG_TIME_AUG = 1
 SK_FLAG_BWD_REPLAY = 2
 SK_FLAG_SHORT_WAITS = 4
 SK_FLAG_LEAD_LAG = 8
+SK_FLAG_KEEP_FORWARD = 16
+SK_FLAG_HAVE_FORWARD = 32
 SK_OP_FWD, SK_OP_BWD, SK_OP_GRAM, SK_OP_GRAM_BWD = 0, 1, 2, 3
 
 
@@ -162,6 +164,15 @@ def workspace(nbytes, device):
         t = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
         _ws_cache[key] = t
     return t
+
+
+def keeps_forward(B, L1, L2, d, lam1, lam2, flags, dt):
+    """Whether sigkernel_fwd with SK_FLAG_KEEP_FORWARD leaves a sweep that sigkernel_bwd with SK_FLAG_HAVE_FORWARD takes
+    over for this shape (the launch plan names the first half of the backward kernel), or ignores the flag."""
+    if B < 1 or L1 < 2 or L2 < 2:
+        return False
+    desc = sigkernel_describe(SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
+    return "lock_bwd_kernel<" in desc and ", 1>" in desc.split("kernel=", 1)[1].split(" grid=", 1)[0]
 
 
 def sigkernel_fwd(x, y, lam1=0, lam2=0, flags=0, k=None, ws=None):

@@ -37,7 +37,9 @@ std::vector<TimedLaunch> g_timed;
 int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
 {
     if (dt != SK_F32 && dt != SK_F64) return fail(SK_ERR_DTYPE, "dtype %d is neither SK_F32 nor SK_F64", dt);
-    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY | SK_FLAG_SHORT_WAITS | SK_FLAG_LEAD_LAG)) return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
+    if (flags & ~(SK_FLAG_TIME_AUG | SK_FLAG_BWD_REPLAY | SK_FLAG_SHORT_WAITS | SK_FLAG_LEAD_LAG | SK_FLAG_KEEP_FORWARD |
+                  SK_FLAG_HAVE_FORWARD))
+        return fail(SK_ERR_DTYPE, "unknown flag bits 0x%x", flags);
     if (lam1 < 0 || lam2 < 0 || lam1 > 20 || lam2 > 20)
         return fail(SK_ERR_DYADIC, "dyadic orders (%d, %d) outside 0..20", lam1, lam2);
     if (nx < 0 || ny < 0) return fail(SK_ERR_SHAPE, "negative batch size");
@@ -60,7 +62,7 @@ int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1
 // that grows linearly with the number of cells.  Float callers get float storage at the edges only.
 template <typename T>
 int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
-        void* grad_y, int lam1, int lam2, int flags, void* ws, hipStream_t st)
+        void* grad_y, int lam1, int lam2, int flags, void* ws, hipStream_t st, int phase = 0)
 {
     using namespace sk;
     constexpr bool kIsDouble = sizeof(T) == 8;
@@ -148,6 +150,10 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.gxraw = static_cast<double*>(grad_x);
         a.gyraw = static_cast<double*>(grad_y);
         a.L1 = p.L1; a.L2 = p.L2;
+        a.lk_phase = phase;
+        a.lk_keep = backward ? reinterpret_cast<double*>(base + p.off_keep) : nullptr;
+    } else if (phase != 0) {
+        return fail(SK_ERR_SHAPE, "internal: no split form of this launch");
     }
     // one preparation launch: increments of both sides, cleared gradient accumulators, cleared error flag
     if (!fused)
@@ -164,7 +170,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     if (timed) {
         SK_CHECK(hipEventCreate(&tl.start));
         SK_CHECK(hipEventCreate(&tl.stop));
-        tl.backward = backward ? 1 : 0;
+        tl.backward = (backward && phase != 1) ? 1 : 0;   // a kept forward sweep counts as a forward launch
         SK_CHECK(hipEventRecord(tl.start, st));
     }
     if (p.band) SK_CHECK(launch_sweep_band(backward ? 1 : 0, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
@@ -216,6 +222,13 @@ int check_device()
     return SK_OK;
 }
 
+// Whether the backward plan pb has its forward and reverse sweeps as launches of their own: the lock-step kernels that
+// work on the caller's arrays (pairs of double paths, no lead-lag transform).
+bool split_forward(const sk::Plan& pb, sk_dtype dt, int flags)
+{
+    return pb.lock && pb.gramM == 0 && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG);
+}
+
 int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
              void* grad_y, int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags,
              sk_dtype dt, void* ws, size_t ws_bytes, void* stream)
@@ -245,8 +258,25 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     if (!p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0)
         return fail(SK_ERR_WORKSPACE, "workspace pointer is NULL or not 256-byte aligned");
+    // A forward sweep kept for the backward call: the launch modes that have the two halves of the backward call as
+    // launches of their own run the first half here and the second half there; the others ignore both flags.
+    int phase = 0;
+    if (!gram && (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD))) {
+        const sk::Plan pb = backward ? p : sk::make_plan(true, false, false, nx, ny, L1, L2, d, lam1, lam2, elem,
+                                                         !(flags & SK_FLAG_BWD_REPLAY));
+        if (!pb.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
+        if (!backward && ws_bytes < pb.total)
+            return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed (SK_FLAG_KEEP_FORWARD: that of sigkernel_bwd)",
+                        ws_bytes, pb.total);
+        if (split_forward(pb, dt, flags)) {
+            phase = backward ? 2 : 1;
+            if (!backward) p = pb;
+        }
+    }
     if (ws_bytes < p.total)
         return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, p.total);
+    if (phase == 1) return run<double>(p, true, x, y, k, nullptr, nullptr, nullptr, lam1, lam2, flags, ws, st, 1);
+    if (phase == 2) return run<double>(p, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, 2);
     if (dt == SK_F64)
         return run<double>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
     return run<float>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
@@ -260,7 +290,8 @@ size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, 
                                  int lam2, int flags, sk_dtype dt)
 {
     const bool gram = op == SK_OP_GRAM || op == SK_OP_GRAM_BWD;
-    const bool backward = op == SK_OP_BWD || op == SK_OP_GRAM_BWD;
+    // a forward call that keeps its sweep works in the backward call's workspace
+    const bool backward = op == SK_OP_BWD || op == SK_OP_GRAM_BWD || (op == SK_OP_FWD && (flags & SK_FLAG_KEEP_FORWARD));
     if (op < SK_OP_FWD || op > SK_OP_GRAM_BWD) return 0;
     const int64_t ny = gram ? M : B_or_N;
     if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
@@ -459,6 +490,18 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         std::snprintf(out, out_bytes, "mode=trivial (no cells to sweep)");
         return SK_OK;
     }
+    // a kept forward sweep: the two halves of the backward call, where the launch mode has them
+    int phase = 0;
+    if (!gram && (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD))) {
+        const sk::Plan pb = backward ? p : sk::make_plan(true, false, false, B_or_N, ny, L1, L2, d, lam1, lam2,
+                                                         dt == SK_F64 ? 8 : 4, !(flags & SK_FLAG_BWD_REPLAY));
+        if (pb.valid && split_forward(pb, dt, flags)) {
+            phase = backward ? 2 : 1;
+            p = pb;
+        } else if (pb.valid && !backward) {
+            p.total = pb.total > p.total ? pb.total : p.total;   // the caller still brings the backward call's workspace
+        }
+    }
     char kern[96];
     int threads;
     const char* mode;
@@ -480,7 +523,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.lock) {
         mode = "lock-step";
-        std::snprintf(kern, sizeof(kern), "lock_%s_kernel<%d, %d, %d>", backward ? "bwd" : "fwd", p.BL, p.DT, p.lk_M);
+        if (backward || phase) std::snprintf(kern, sizeof(kern), "lock_bwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase);
+        else std::snprintf(kern, sizeof(kern), "lock_fwd_kernel<%d, %d, %d>", p.BL, p.DT, p.lk_M);
         threads = (p.lk_ns == 1 ? 3 : (p.lk_ns == 2 ? 8 : 12)) * sk::kWave;
     } else {
         const char* base = !backward ? "sweep_fwd" : (p.uncompute ? "sweep_bwdu" : "sweep_bwd");

@@ -74,6 +74,10 @@ struct SweepArgs {
     real* gxraw;         // [npairs][L1][d] or null
     real* gyraw;         // [npairs][L2][d] or null
     int L1, L2;
+    // the two halves of the fused backward call as launches of their own: 1 = the forward sweep only, leaving the
+    // checkpoints and the strips' bottom rows in global memory; 2 = the reverse sweep only, from what 1 left; 0 = both
+    int lk_phase;
+    real* lk_keep;       // [npairs][lk_ns + 1][lk_rowlen]: the hand-over rows between the two launches
     int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted
 };
 

@@ -173,7 +173,10 @@ __global__ __launch_bounds__(12 * kWave) void lock_fwd_kernel(SweepArgs a)
 // ------------------------------------------------------------------------------------------------
 // backward
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D, int M>
+// PHASE 0: the whole backward call.  PHASE 1 / 2: its two halves as launches of their own (a forward call whose
+// sweep is kept, and the backward call that follows it): what crosses from phase 1 to phase 2 is the checkpoints,
+// which are in global memory anyway, and the hand-over rows, which phase 1 then copies out and phase 2 copies in.
+template <int BL, int D, int M, int PHASE>
 __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -197,10 +200,14 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     real* ckpt = a.ckpt + pid * a.ckpt_slot + (long)strip * (nckS + 1) * NVC * kWave + lane;
 
     stage_y<LK::DSc, true>(a, yi, l.y, l.gy);
-    for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) { l.krows[t] = 1.0; l.arows[t] = 0.0; }
+    real* keep = PHASE == 0 ? nullptr : a.lk_keep + pid * (long)(ns + 1) * rowlen;
+    for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) {
+        l.krows[t] = PHASE == 2 ? keep[t] : 1.0;
+        l.arows[t] = 0.0;
+    }
     __syncthreads();
     // dF/dk[m, n] enters through the adjoint row under the last strip
-    if (threadIdx.x == 0) l.arows[ns * rowlen + LK::PADF + (a.nb - 1) * C + (C - 1)] = a.grad_k[pid];
+    if (PHASE != 1 && threadIdx.x == 0) l.arows[ns * rowlen + LK::PADF + (a.nb - 1) * C + (C - 1)] = a.grad_k[pid];
 
     const SK_LDS real* rowprev = l.krows + strip * rowlen + LK::PADF;
     SK_LDS real* rowcur = l.krows + (strip + 1) * rowlen + LK::PADF;
@@ -212,7 +219,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     if (role == kRoleCoef || role == kRoleAux) cf.setup(a, strip, lane, dxp, l.y);
 
     // ---- phase 1: forward with checkpoints ----
-    {
+    if constexpr (PHASE != 2) {
         typename LK::Fwd f;
         f.init();
         const int nck = a.lk_NT / CH1;
@@ -236,6 +243,10 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     }
     if (threadIdx.x == 0 && a.k_out) a.k_out[pid] = l.krows[ns * rowlen + LK::PADF + a.nb * C];
     __syncthreads();   // also completes the checkpoint stores before they are read back
+    if constexpr (PHASE == 1) {
+        for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) keep[t] = l.krows[t];
+        return;
+    }
 
     // ---- phase 2: the mirror image ----
     {
@@ -416,18 +427,29 @@ hipError_t launch_lock_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t
     return hipGetLastError();
 }
 
-template <int BL, int D, int M>
-hipError_t launch_lock_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+template <int BL, int D, int M, int PHASE>
+hipError_t launch_lock_bwd_phase(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M, PHASE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
+    hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M, PHASE>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
     return hipGetLastError();
+}
+
+template <int BL, int D, int M>
+hipError_t launch_lock_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.lk_phase == 0) return launch_lock_bwd_phase<BL, D, M, 0>(a, grid, lds, st);
+    // the halves exist for the calls that work on the caller's arrays, and need the rows' place in global memory
+    if (!a.fused || !a.lk_keep) return hipErrorInvalidValue;
+    if (a.lk_phase == 1) return launch_lock_bwd_phase<BL, D, M, 1>(a, grid, lds, st);
+    if (a.lk_phase == 2) return launch_lock_bwd_phase<BL, D, M, 2>(a, grid, lds, st);
+    return hipErrorInvalidValue;
 }
 
 // Two block rows per lane are only built where the registers allow it (lock_max_rows in sk_plan.h).

@@ -366,6 +366,23 @@ def test_autograd_wrappers_give_the_oracle_gradients():
     kr, gxr, _ = oracle.bwd(X[:7], Y, gk, 0, 1, 0)
     check_values(host(k), kr, torch.float64, "k")
     check_grads(host(xb.grad), gxr, torch.float64, "d/dx through autograd")
+    # two graphs alive at once (a forward call that keeps its sweep keeps it in a workspace of its own), and a graph
+    # that is walked twice
+    from paper_2509_10613_amd import binding
+    assert binding.keeps_forward(7, L, L, d, 1, 1, 1, binding.SK_F64)
+    xa = dev(X[:7]).requires_grad_(True)
+    xc = dev(X[2:9]).requires_grad_(True)
+    k1 = ska.sig_kernel(xa, dev(Y), 1, 1, 1)
+    k2 = ska.sig_kernel(xc, dev(Y), 1, 1, 1)
+    (k1 * dev(gk)).sum().backward(retain_graph=True)
+    first = xa.grad.clone()
+    (k2 * dev(gk)).sum().backward()
+    xa.grad = None
+    (k1 * dev(gk)).sum().backward()
+    torch.cuda.synchronize()
+    assert torch.equal(xa.grad, first)
+    check_grads(host(xa.grad), oracle.bwd(X[:7], Y, gk, 1, 1, 1)[1], torch.float64, "d/dx, first graph")
+    check_grads(host(xc.grad), oracle.bwd(X[2:9], Y, gk, 1, 1, 1)[1], torch.float64, "d/dx, second graph")
 
 
 @pytest.mark.parametrize("N,M,L1,L2,d,lam,flags,dtype", [(9, 7, 24, 30, 3, 1, 1, torch.float64),
@@ -457,6 +474,46 @@ def test_shapes_fp32(L1, L2, d, lam):
     X = rand_paths(3000 + L1, B, L1, d, 0.2)
     Y = rand_paths(4000 + L2, B, L2, d, 0.2)
     run_pairs(X, Y, lam, lam, 0, torch.float32, backward=True)
+
+
+@pytest.mark.parametrize("B,L1,L2,d,lam1,lam2,flags,dtype", [
+    (5, 66, 70, 4, 0, 0, 1, torch.float64),      # two strips, ragged second strip
+    (5, 20, 35, 5, 1, 1, 0, torch.float64),      # one strip
+    (3, 100, 300, 4, 1, 1, 1, torch.float64),    # two block rows per lane, many more columns than rows
+    (4, 12, 50, 8, 2, 2, 0, torch.float64),
+    (2, 40, 9, 7, 2, 2, 1, torch.float64),
+    (5, 9, 12, 20, 1, 1, 1, torch.float64),      # run-time channel loop: no split form, the flags change nothing
+    (6, 40, 33, 3, 0, 0, 0, torch.float32),      # float paths: likewise
+    (5000, 6, 5, 2, 1, 1, 0, torch.float64),     # many pairs: likewise
+    (5, 20, 18, 3, 1, 1, sk.SK_FLAG_LEAD_LAG, torch.float64),
+])
+def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flags, dtype):
+    """sigkernel_fwd with SK_FLAG_KEEP_FORWARD followed by sigkernel_bwd with SK_FLAG_HAVE_FORWARD on the same
+    workspace: the same arithmetic as the backward call alone, so the same bits; and both against the oracle."""
+    X = rand_paths(8100 + L1, B, L1, d, 0.25)
+    Y = rand_paths(8200 + L2, B, L2, d, 0.25)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    x, y = dev(X, dtype), dev(Y, dtype)
+    gk = dev(np.random.default_rng(83).normal(size=B), dtype)
+    k0, gx0, gy0 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags)
+    need = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD,
+                                        sk.SK_F64 if dtype == torch.float64 else sk.SK_F32)
+    assert need >= sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags,
+                                                sk.SK_F64 if dtype == torch.float64 else sk.SK_F32)
+    ws = sk.workspace(need, x.device)
+    for rep in range(2):                         # the second round finds the workspace as the first one left it
+        k1 = sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+        k2, gx1, gy1 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(k1, k0) and torch.equal(k2, k0)
+        assert torch.equal(gx1, gx0) and torch.equal(gy1, gy0)
+    kref, gxr, gyr = oracle.bwd(Xr, Yr, host(gk), lam1, lam2, flags)
+    check_values(host(k1), kref, dtype, "k of the kept sweep")
+    check_grads(host(gx1), gxr, dtype, "grad_x after a kept sweep")
+    check_grads(host(gy1), gyr, dtype, "grad_y after a kept sweep")
+    # only one gradient wanted
+    _, gx2, _ = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws, want_y=False)
+    assert torch.equal(gx2, gx0)
 
 
 def test_more_pairs_than_wave_slots():

@@ -33,7 +33,7 @@ def test_argument_validation_needs_no_gpu(lib):
     one = C.c_void_p(256)
     # bad dtype, bad flags, bad dyadic order, bad shape: all rejected before any GPU work
     assert f(one, one, one, 4, 8, 8, 2, 0, 0, 0, 7, one, 1 << 20, None) == -4
-    assert f(one, one, one, 4, 8, 8, 2, 0, 0, 16, 1, one, 1 << 20, None) == -4
+    assert f(one, one, one, 4, 8, 8, 2, 0, 0, 64, 1, one, 1 << 20, None) == -4
     assert f(one, one, one, 4, 8, 8, 2, -1, 0, 0, 1, one, 1 << 20, None) == -3
     assert f(one, one, one, 4, 8, 8, 2, 0, 21, 0, 1, one, 1 << 20, None) == -3
     assert f(one, one, one, 4, 0, 8, 2, 0, 0, 0, 1, one, 1 << 20, None) == -2
@@ -78,12 +78,24 @@ def test_launch_plan_of_the_five_configurations(lib):
     # c2 (128 pairs, L = 256, order 1): the chip is under-filled -> one workgroup per pair in lock step,
     # two strips of 128 block rows, eight waves, everything resident at once, caller's arrays used directly
     p = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
-    assert p["mode"] == "lock-step" and p["kernel"] == "lock_bwd_kernel<1, 5, 2>"
+    assert p["mode"] == "lock-step" and p["kernel"] == "lock_bwd_kernel<1, 5, 2, 0>"
     assert (p["grid"], p["threads"], p["strips"], p["rows_per_lane"], p["fused"]) == ("128", "512", "2", "2", "1")
     assert int(p["lds_bytes"]) <= 160 * 1024
     p = _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
     assert p["kernel"] == "lock_fwd_kernel<1, 5, 2>" and p["fused"] == "1"
     assert _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f32)["fused"] == "0"   # float callers are converted
+    # a forward sweep kept for the backward call: the two halves of the backward kernel as launches of their own, in
+    # the backward call's workspace; launch modes without that form ignore the flags
+    KEEP, HAVE = binding.SK_FLAG_KEEP_FORWARD, binding.SK_FLAG_HAVE_FORWARD
+    p1 = _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1 | KEEP, f64)
+    p2 = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f64)
+    assert p1["kernel"] == "lock_bwd_kernel<1, 5, 2, 1>" and p2["kernel"] == "lock_bwd_kernel<1, 5, 2, 2>"
+    q = lib.sigkernel_workspace_bytes
+    assert q(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1 | KEEP, f64) == q(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
+    assert int(p1["workspace_bytes"]) == q(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
+    assert q(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f64) < q(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1 | KEEP, f64)
+    assert _plan(binding.SK_OP_FWD, 5000, 0, 6, 5, 2, 1, 1, KEEP, f64)["kernel"] == _plan(binding.SK_OP_FWD, 5000, 0, 6, 5, 2, 1, 1, 0, f64)["kernel"]
+    assert _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f32)["kernel"] == "lock_bwd_kernel<1, 5, 2, 0>"
     # c1: tiny, one strip: stencil, coefficient and auxiliary wave
     p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
     assert p["mode"] == "lock-step" and p["threads"] == "192" and p["strips"] == "1"
