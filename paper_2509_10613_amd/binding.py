@@ -172,7 +172,9 @@ def keeps_forward(B, L1, L2, d, lam1, lam2, flags, dt):
     if B < 1 or L1 < 2 or L2 < 2:
         return False
     desc = sigkernel_describe(SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
-    return "lock_bwd_kernel<" in desc and ", 1>" in desc.split("kernel=", 1)[1].split(" grid=", 1)[0]
+    kern = desc.split("kernel=", 1)[1].split(" grid=", 1)[0]
+    return (kern.startswith("lock_bwd_kernel<") and kern.endswith(", 1>")) or \
+        (kern.startswith("band_fwd_kernel<") and kern.endswith(", true>"))
 
 
 def sigkernel_fwd(x, y, lam1=0, lam2=0, flags=0, k=None, ws=None):

@@ -86,7 +86,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.grad_k = static_cast<const double*>(grad_k);
     } else {
         a.k_out = k ? reinterpret_cast<double*>(base + p.off_kio) : nullptr;
-        if (backward) {
+        if (backward && phase != 1) {
             double* gk64 = reinterpret_cast<double*>(base + p.off_gkio);
             SK_CHECK((launch_convert<T, double>(static_cast<const T*>(grad_k), gk64, p.kcount, st)));
             a.grad_k = gk64;
@@ -152,15 +152,22 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.L1 = p.L1; a.L2 = p.L2;
         a.lk_phase = phase;
         a.lk_keep = backward ? reinterpret_cast<double*>(base + p.off_keep) : nullptr;
-    } else if (phase != 0) {
+    } else if (phase != 0 && !p.band) {
         return fail(SK_ERR_SHAPE, "internal: no split form of this launch");
     }
+    // Band mode is two launches anyway (forward sweep with checkpoints and bottom rows in global memory, reverse
+    // sweep); a kept forward sweep is the first of them, and its kernel values wait in the workspace.
+    double* keep_k = (p.band && phase != 0) ? reinterpret_cast<double*>(base + p.off_keep) : nullptr;
     // one preparation launch: increments of both sides, cleared gradient accumulators, cleared error flag
+    // (the reverse sweep of a kept forward sweep: the same increments once more, cleared accumulators, and only the
+    // reverse sweep's progress counters cleared - the error flag still says how the forward sweep went)
     if (!fused)
     SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, cL1,
                                p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
                                (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, cL2, p.qpad, cd,
-                               p.DP, a.err, 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags, ll, st));
+                               p.DP, phase == 2 ? a.bd_flags + p.nflags / 2 : a.err,
+                               phase == 2 ? p.nflags / 2 : 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags,
+                               ll, st));
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -173,7 +180,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         tl.backward = (backward && phase != 1) ? 1 : 0;   // a kept forward sweep counts as a forward launch
         SK_CHECK(hipEventRecord(tl.start, st));
     }
-    if (p.band) SK_CHECK(launch_sweep_band(backward ? 1 : 0, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    if (p.band) SK_CHECK(launch_sweep_band(phase ? phase + 1 : (backward ? 1 : 0), p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
@@ -183,8 +190,12 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
+    if (keep_k && phase == 1)
+        SK_CHECK(hipMemcpyAsync(keep_k, a.k_out, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
+    if (keep_k && phase == 2 && a.k_out)
+        SK_CHECK(hipMemcpyAsync(a.k_out, keep_k, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.kcount, st)));
-    if (backward && !fused) {
+    if (backward && !fused && phase != 1) {
         SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, cL1, p.rpad, a.gdy,
                                     p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, cL2, p.qpad, cd, p.DP,
                                     a.err, ll, st));
@@ -223,10 +234,11 @@ int check_device()
 }
 
 // Whether the backward plan pb has its forward and reverse sweeps as launches of their own: the lock-step kernels that
-// work on the caller's arrays (pairs of double paths, no lead-lag transform).
+// work on the caller's arrays (pairs of double paths, no lead-lag transform), and the band kernels.
 bool split_forward(const sk::Plan& pb, sk_dtype dt, int flags)
 {
-    return pb.lock && pb.gramM == 0 && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG);
+    if (pb.gramM != 0) return false;
+    return pb.band || (pb.lock && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG));
 }
 
 int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
@@ -275,8 +287,11 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     }
     if (ws_bytes < p.total)
         return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, p.total);
-    if (phase == 1) return run<double>(p, true, x, y, k, nullptr, nullptr, nullptr, lam1, lam2, flags, ws, st, 1);
-    if (phase == 2) return run<double>(p, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, 2);
+    if (phase != 0) {
+        if (phase == 1) { grad_k = nullptr; grad_x = nullptr; grad_y = nullptr; }
+        if (dt == SK_F64) return run<double>(p, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, phase);
+        return run<float>(p, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, phase);
+    }
     if (dt == SK_F64)
         return run<double>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
     return run<float>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
@@ -508,7 +523,9 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     if (p.band) {
         mode = "band";
         // backward: two launches, the forward sweep with checkpoints and then the reverse sweep (the larger one)
-        if (backward)
+        if (phase == 1) std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true>", p.BL, p.DT);
+        else if (phase == 2) std::snprintf(kern, sizeof(kern), "band_rev_kernel<%d, %d>", p.BL, p.DT);
+        else if (backward)
             std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true>+band_rev_kernel<%d, %d>", p.BL, p.DT, p.BL, p.DT);
         else
             std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, false>", p.BL, p.DT);

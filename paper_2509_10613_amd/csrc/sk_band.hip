@@ -656,14 +656,17 @@ hipError_t launch_band_t(int phase, const SweepArgs& a, int grid, size_t lds, hi
         hipLaunchKernelGGL((band_fwd_kernel<BL, D, false>), dim3(grid), block, lds, st, a);
     } else {
         // backward: the forward sweep with checkpoints, then the reverse sweep with the bands in reverse order
+        // (phase 2 / 3: one of the two only, for a forward sweep that is kept for the backward call)
         e = prep(reinterpret_cast<const void*>(&band_fwd_kernel<BL, D, true>));
         if (e != hipSuccess) return e;
         e = prep(reinterpret_cast<const void*>(&band_rev_kernel<BL, D>));
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((band_fwd_kernel<BL, D, true>), dim3(grid), block, lds, st, a);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((band_rev_kernel<BL, D>), dim3(grid), block, lds, st, a);
+        if (phase != 3) {
+            hipLaunchKernelGGL((band_fwd_kernel<BL, D, true>), dim3(grid), block, lds, st, a);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        if (phase != 2) hipLaunchKernelGGL((band_rev_kernel<BL, D>), dim3(grid), block, lds, st, a);
     }
     return hipGetLastError();
 }
@@ -682,11 +685,12 @@ hipError_t launch_band_bl(int phase, int DT, const SweepArgs& a, int grid, size_
     }
 }
 
-// phase 0: forward sweep; phase 1: backward pass (forward sweep with checkpoints, then the reverse sweep)
+// phase 0: forward sweep; phase 1: backward pass (forward sweep with checkpoints, then the reverse sweep);
+// phase 2 / 3: the first / second launch of phase 1 alone
 hipError_t launch_sweep_band(int phase, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     // what the kernels assume about the launch
-    if (a.lk_M != 1 || a.lk_ns < 1 || a.bd_nbands != (a.lk_ns + kBandStrips - 1) / kBandStrips ||
+    if (phase < 0 || phase > 3 || a.lk_M != 1 || a.lk_ns < 1 || a.bd_nbands != (a.lk_ns + kBandStrips - 1) / kBandStrips ||
         (long)grid != a.npairs * a.bd_nbands || (a.lk_NT % 8) != 0 || a.lk_NT < a.nb + kWave - 1 ||
         a.lk_padb != a.lk_ns * kWave - a.mb || a.bd_flags == nullptr || a.lk_NT >= a.nb + kWave - 1 + 8 ||
         a.rowlen < (a.lk_NT - (kWave - 1)) * (1 << BL) + 1 ||
