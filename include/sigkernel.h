@@ -106,8 +106,10 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  * checkpoints of its sweep there; sigkernel_bwd with SK_FLAG_HAVE_FORWARD, the same workspace, x, y, shapes, lam and
  * other flags, and no other call on that workspace in between, runs the reverse sweep from them (and leaves them as
  * they are: the backward call may be repeated, say with another grad_k).  The caller vouches
- * for all of that: the library cannot check it, and a workspace that holds something else gives wrong gradients (or
- * NaN through the drift check).  Launch modes without this form ignore both flags (the forward call runs as usual,
+ * for all of that.  What the library checks: a kept sweep is signed with a hash of the call's pointers x and y,
+ * shapes, lam, transformation flags and dtype, a backward call that sweeps forward itself in that workspace erases
+ * the signature, and a backward call whose own hash differs from the signature it finds returns NaN gradients.  Paths
+ * changed in place between the two calls, or another forward call on that workspace, are not noticed.  Launch modes without this form ignore both flags (the forward call runs as usual,
  * the backward call sweeps forward itself), so results never depend on the flags; sigkernel_describe names the kernels.
  */
 int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,

@@ -158,6 +158,19 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     // Band mode is two launches anyway (forward sweep with checkpoints and bottom rows in global memory, reverse
     // sweep); a kept forward sweep is the first of them, and its kernel values wait in the workspace.
     double* keep_k = (p.band && phase != 0) ? reinterpret_cast<double*>(base + p.off_keep) : nullptr;
+    if (backward && p.gramM == 0 && (fused || p.band) && p.off_keep_tag != 0) {
+        a.keep_tag = reinterpret_cast<unsigned long long*>(base + p.off_keep_tag);
+        // FNV-1a over what the kept sweep depends on
+        unsigned long long h = 1469598103934665603ull;
+        auto mix = [&](unsigned long long v) {
+            for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xffull; h *= 1099511628211ull; }
+        };
+        mix(reinterpret_cast<uintptr_t>(x)); mix(reinterpret_cast<uintptr_t>(y));
+        mix((unsigned long long)p.npairs); mix((unsigned long long)p.L1); mix((unsigned long long)p.L2);
+        mix((unsigned long long)p.d); mix((unsigned long long)lam1); mix((unsigned long long)lam2);
+        mix((unsigned long long)(flags & (SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG))); mix(sizeof(T));
+        a.keep_tag_val = h | 1ull;
+    }
     // one preparation launch: increments of both sides, cleared gradient accumulators, cleared error flag
     // (the reverse sweep of a kept forward sweep: the same increments once more, cleared accumulators, and only the
     // reverse sweep's progress counters cleared - the error flag still says how the forward sweep went)
@@ -180,6 +193,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         tl.backward = (backward && phase != 1) ? 1 : 0;   // a kept forward sweep counts as a forward launch
         SK_CHECK(hipEventRecord(tl.start, st));
     }
+    if (p.band && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
     if (p.band) SK_CHECK(launch_sweep_band(phase ? phase + 1 : (backward ? 1 : 0), p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
@@ -190,6 +204,8 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
+    // band mode signs, erases and checks in launches of their own (the lock-step kernels do it themselves)
+    if (p.band && a.keep_tag && phase != 2) SK_CHECK(launch_keep_tag(a.keep_tag, phase == 1 ? a.keep_tag_val : 0ull, 0, a.err, st));
     if (keep_k && phase == 1)
         SK_CHECK(hipMemcpyAsync(keep_k, a.k_out, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
     if (keep_k && phase == 2 && a.k_out)

@@ -78,10 +78,16 @@ struct SweepArgs {
     // checkpoints and the strips' bottom rows in global memory; 2 = the reverse sweep only, from what 1 left; 0 = both
     int lk_phase;
     real* lk_keep;       // [npairs][lk_ns + 1][lk_rowlen]: the hand-over rows between the two launches
+    // A kept forward sweep is signed with a hash of the call's arguments; the reverse sweep that takes it over compares
+    // (a mismatch gives NaN gradients), and a backward call that sweeps forward itself erases the signature.
+    unsigned long long* keep_tag;
+    unsigned long long keep_tag_val;
     int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted
 };
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
+// tag[0] = val (check == 0), or: *err = 3 if tag[0] != val, and an earlier 3 taken back if it is equal (check != 0)
+hipError_t launch_keep_tag(unsigned long long* tag, unsigned long long val, int check, int* err, hipStream_t st);
 template <typename TA, typename TB> hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st);
 template <typename T>
 hipError_t launch_mmd2_reduce(const T* Kxx, const T* Kxy, const T* Kyy, long nxx, long nxy, long nyy, T* out,

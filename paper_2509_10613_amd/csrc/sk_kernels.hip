@@ -38,6 +38,13 @@ __global__ void convert_kernel(const TA* __restrict__ in, TB* __restrict__ out, 
     for (; i < n; i += st) out[i] = (TB)in[i];
 }
 
+__global__ void keep_tag_kernel(unsigned long long* tag, unsigned long long val, int check, int* err)
+{
+    if (!check) *tag = val;
+    else if (*tag != val) *err = 3;
+    else if (*err == 3) *err = 0;   // an earlier call with other arguments was turned away; this one is not
+}
+
 template <typename T>
 __global__ void fill_kernel(T* p, long n, T v)
 {
@@ -1812,6 +1819,12 @@ hipError_t launch_fill(T* p, long n, T v, hipStream_t st)
     long blocks = (n + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(fill_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_keep_tag(unsigned long long* tag, unsigned long long val, int check, int* err, hipStream_t st)
+{
+    hipLaunchKernelGGL(keep_tag_kernel, dim3(1), dim3(1), 0, st, tag, val, check, err);
     return hipGetLastError();
 }
 

@@ -245,8 +245,14 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     __syncthreads();   // also completes the checkpoint stores before they are read back
     if constexpr (PHASE == 1) {
         for (int t = threadIdx.x; t < (ns + 1) * rowlen; t += blockDim.x) keep[t] = l.krows[t];
+        if (pid == 0 && threadIdx.x == 0) *a.keep_tag = a.keep_tag_val;
         return;
     }
+    // both sweeps in one call: whatever sweep the workspace held is gone
+    if (PHASE == 0 && a.keep_tag && pid == 0 && threadIdx.x == 0) *a.keep_tag = 0;
+    // the reverse sweep alone: is the sweep in the workspace the one of this call's arguments?
+    bool stale = false;
+    if (PHASE == 2 && threadIdx.x == 0) stale = *a.keep_tag != a.keep_tag_val;
 
     // ---- phase 2: the mirror image ----
     {
@@ -356,7 +362,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
             SK_LDS real* gxl = (SK_LDS real*)(smem + a.lk_off_cring);
             SK_LDS int* bad = (SK_LDS int*)l.dump;
             for (int t = threadIdx.x; t < a.r * LK::DSc; t += blockDim.x) gxl[t] = 0.0;
-            if (threadIdx.x == 0) *bad = 0;
+            if (threadIdx.x == 0) *bad = stale ? 1 : 0;
             __syncthreads();
             if (stencil) {
                 if (drift) *bad = 1;
@@ -446,7 +452,7 @@ hipError_t launch_lock_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t
 {
     if (a.lk_phase == 0) return launch_lock_bwd_phase<BL, D, M, 0>(a, grid, lds, st);
     // the halves exist for the calls that work on the caller's arrays, and need the rows' place in global memory
-    if (!a.fused || !a.lk_keep) return hipErrorInvalidValue;
+    if (!a.fused || !a.lk_keep || !a.keep_tag) return hipErrorInvalidValue;
     if (a.lk_phase == 1) return launch_lock_bwd_phase<BL, D, M, 1>(a, grid, lds, st);
     if (a.lk_phase == 2) return launch_lock_bwd_phase<BL, D, M, 2>(a, grid, lds, st);
     return hipErrorInvalidValue;

@@ -51,6 +51,7 @@ struct Plan {
     int64_t xstride = 0, ystride = 0, rows_slot = 0, ckpt_slot = 0, adj_slot = 0;
     size_t off_dxT = 0, off_dyT = 0, off_gdxT = 0, off_gdyT = 0, off_rows = 0, off_adj = 0, off_ckpt = 0;
     size_t off_kio = 0, off_gkio = 0;   // float callers: double staging of k and grad_k
+    size_t off_keep_tag = 0;
     size_t off_keep = 0;                // backward: what a kept forward sweep leaves besides rows and checkpoints
                                         // (lock-step: the hand-over rows; band: the kernel values)
     size_t off_err = 0;                 // one int: a bounded wait between cooperating waves ran out
@@ -379,6 +380,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
         if (p.lock) p.off_keep = take((size_t)p.npairs * (p.lk_ns + 1) * p.lk_rowlen * elem);
         else if (p.band) p.off_keep = take((size_t)p.kcount * elem);   // band mode: the kernel values of the kept sweep
+        if (p.lock || p.band) p.off_keep_tag = take(256);   // which call's forward sweep the workspace holds
     }
     if (io_elem != elem) {
         p.off_kio = take((size_t)p.kcount * elem);

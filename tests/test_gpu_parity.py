@@ -535,6 +535,29 @@ def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flag
     # only one gradient wanted
     _, gx2, _ = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws, want_y=False)
     assert same(gx2, gx0)
+    # a workspace that holds another call's sweep, or none: NaN gradients, never numbers (where the flags do anything)
+    if sk.keeps_forward(B, L1, L2, d, lam1, lam2, flags, sdt):
+        x2 = x.clone()
+        _, gx3, gy3 = sk.sigkernel_bwd(x2, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+        assert torch.all(torch.isnan(gx3)) and torch.all(torch.isnan(gy3))
+        _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)   # still there
+        assert same(gx3, gx0) and same(gy3, gy0)
+        blank = torch.zeros(need, dtype=torch.uint8, device="cuda")
+        _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=blank)
+        assert torch.all(torch.isnan(gx3)) and torch.all(torch.isnan(gy3))
+        # a backward call that sweeps forward itself uses the same memory: the kept sweep is gone afterwards
+        sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+        sk.sigkernel_bwd(x2, y, gk, lam1, lam2, flags, ws=ws)
+        _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+        assert torch.all(torch.isnan(gx3)) and torch.all(torch.isnan(gy3))
+        _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags, ws=ws)
+        assert same(gx3, gx0) and same(gy3, gy0)
+    # the kept sweep needs the backward call's workspace: the forward call's own is refused where it is smaller
+    small = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags, sdt)
+    if small < need:
+        with pytest.raises(sk.SigKernelError):
+            sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD,
+                             ws=torch.empty(small, dtype=torch.uint8, device="cuda"))
 
 
 def test_more_pairs_than_wave_slots():
