@@ -381,13 +381,12 @@ struct Lock {
 #pragma unroll
             for (int cc = 0; cc < C; ++cc) gn[RR][cc + 1] += recv[cc];
             gn[0][C] = corner;
-#pragma unroll
-            for (int m = 0; m < M; ++m) accP[m] = 0.0;
+            // dF/dp of a block: sum over its cells of g (s A'(p) - k B'(p)); p is the block's, so the two sums over the
+            // cells are formed first and the derivatives of the coefficients applied once
+            real gs[M], gk[M];
 #pragma unroll
             for (int rr = RR - 1; rr >= 0; --rr) {
                 const int m = rr >> BL;
-                const real dA = p6[m] + 0.5;   // A'(p)
-                const real dB = p6[m];         // -B'(p)
 #pragma unroll
                 for (int cc = C - 1; cc >= 0; --cc) {
                     const real s = e[rr + 1][cc] + e[rr][cc + 1];
@@ -396,10 +395,13 @@ struct Lock {
                     gn[rr + 1][cc] = fma(go, Ac[m], gn[rr + 1][cc]);
                     gn[rr][cc + 1] = fma(go, Ac[m], gn[rr][cc + 1]);
                     gn[rr][cc] = fma(-go, Bc[m], gn[rr][cc]);
-                    const real loc = fma(s, dA, e[rr][cc] * dB);
-                    accP[m] = fma(go, loc, accP[m]);
+                    const bool first = (rr & (C - 1)) == C - 1 && cc == C - 1;   // the block's first cell in this order
+                    gs[m] = first ? go * s : fma(go, s, gs[m]);
+                    gk[m] = first ? go * e[rr][cc] : fma(go, e[rr][cc], gk[m]);
                 }
             }
+#pragma unroll
+            for (int m = 0; m < M; ++m) accP[m] = fma(gs[m], p6[m] + 0.5, gk[m] * p6[m]);   // A'(p) = p/6 + 1/2, -B'(p) = p/6
 #pragma unroll
             for (int cc = 0; cc < C; ++cc) { up[cc] = gn[0][cc + 1]; ktop[cc] = e[0][cc]; }
             corner = gn[0][0];
