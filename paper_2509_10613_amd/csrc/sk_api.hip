@@ -181,6 +181,8 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
                                p.DP, phase == 2 ? a.bd_flags + p.nflags / 2 : a.err,
                                phase == 2 ? p.nflags / 2 : 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags,
                                ll, st));
+    // band mode signs, erases and checks a kept sweep in launches of their own (the lock-step kernels do it themselves)
+    if (p.band && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -193,7 +195,6 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         tl.backward = (backward && phase != 1) ? 1 : 0;   // a kept forward sweep counts as a forward launch
         SK_CHECK(hipEventRecord(tl.start, st));
     }
-    if (p.band && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
     if (p.band) SK_CHECK(launch_sweep_band(phase ? phase + 1 : (backward ? 1 : 0), p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
@@ -204,7 +205,6 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
-    // band mode signs, erases and checks in launches of their own (the lock-step kernels do it themselves)
     if (p.band && a.keep_tag && phase != 2) SK_CHECK(launch_keep_tag(a.keep_tag, phase == 1 ? a.keep_tag_val : 0ull, 0, a.err, st));
     if (keep_k && phase == 1)
         SK_CHECK(hipMemcpyAsync(keep_k, a.k_out, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));

@@ -560,6 +560,34 @@ def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flag
                              ws=torch.empty(small, dtype=torch.uint8, device="cuda"))
 
 
+def test_kept_forward_sweep_degenerate_shapes():
+    # no increments on one side, an empty batch: the flags change nothing
+    KEEP, HAVE = sk.SK_FLAG_KEEP_FORWARD, sk.SK_FLAG_HAVE_FORWARD
+    x = dev(rand_paths(1, 3, 1, 2))
+    y = dev(rand_paths(2, 3, 6, 2))
+    assert torch.all(sk.sigkernel_fwd(x, y, 0, 0, KEEP) == 1.0)
+    k, gx, gy = sk.sigkernel_bwd(x, y, torch.ones(3, dtype=torch.float64, device="cuda"), 0, 0, HAVE)
+    assert torch.all(k == 1.0) and torch.all(gx == 0.0) and torch.all(gy == 0.0)
+    e = torch.empty((0, 4, 2), dtype=torch.float64, device="cuda")
+    assert sk.sigkernel_fwd(e, e, 1, 1, KEEP).shape == (0,)
+    k, gx, gy = sk.sigkernel_bwd(e, e, torch.empty(0, dtype=torch.float64, device="cuda"), 1, 1, HAVE)
+    assert k.shape == (0,) and gx.shape == (0, 4, 2)
+    # a single cell
+    X, Y = rand_paths(3, 2, 2, 1, 0.5), rand_paths(4, 2, 2, 1, 0.5)
+    ws = torch.empty(sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, 2, 0, 2, 2, 1, 0, 0, KEEP, sk.SK_F64), dtype=torch.uint8,
+                     device="cuda")
+    gk = dev(np.array([0.5, -2.0]))
+    xd, yd = dev(X), dev(Y)
+    k1 = sk.sigkernel_fwd(xd, yd, 0, 0, KEEP, ws=ws)
+    k2, gx, gy = sk.sigkernel_bwd(xd, yd, gk, 0, 0, HAVE, ws=ws)
+    torch.cuda.synchronize()
+    kr, gxr, gyr = oracle.bwd(X, Y, host(gk), 0, 0, 0)
+    check_values(host(k1), kr, torch.float64, "k")
+    check_values(host(k2), kr, torch.float64, "k_out")
+    check_grads(host(gx), gxr, torch.float64, "grad_x")
+    check_grads(host(gy), gyr, torch.float64, "grad_y")
+
+
 def test_more_pairs_than_wave_slots():
     # every wave slot handles several pairs in turn, so its scratch rows and checkpoints are reused
     X = rand_paths(71, 5000, 6, 2, 0.3)
