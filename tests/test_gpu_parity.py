@@ -52,7 +52,7 @@ def check_grads(got, ref, dtype, what):
     assert err <= tol, what
 
 
-def run_pairs(X, Y, lam1, lam2, flags, dtype, backward, seed=5):
+def run_pairs(X, Y, lam1, lam2, flags, dtype, backward, seed=5, keep=False):
     Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
     x, y = dev(X, dtype), dev(Y, dtype)
     k = sk.sigkernel_fwd(x, y, lam1, lam2, flags)
@@ -68,6 +68,19 @@ def run_pairs(X, Y, lam1, lam2, flags, dtype, backward, seed=5):
         check_values(host(k2), kr, dtype, "k (from bwd)")
         check_grads(host(gx), gxr, dtype, "grad_x")
         check_grads(host(gy), gyr, dtype, "grad_y")
+        if keep:   # the step bench.py times: the forward call keeps its sweep for the backward call
+            B, L1, d = X.shape
+            sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+            need = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L1, Y.shape[1], d, lam1, lam2,
+                                                flags | sk.SK_FLAG_KEEP_FORWARD, sdt)
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            k3 = sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+            k4, gx, gy = sk.sigkernel_bwd(x, y, dev(gk, dtype), lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+            torch.cuda.synchronize()
+            check_values(host(k3), kr, dtype, "k (kept sweep)")
+            check_values(host(k4), kr, dtype, "k (from bwd after a kept sweep)")
+            check_grads(host(gx), gxr, dtype, "grad_x (kept sweep)")
+            check_grads(host(gy), gyr, dtype, "grad_y (kept sweep)")
 
 
 def rand_paths(seed, B, L, d, scale=0.3):
@@ -83,7 +96,8 @@ def test_c1_forward_fp64():
 
 def test_c2_forward_backward_fp64_full_size():
     w, X, Y = workloads.make("c2")
-    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=True)
+    assert sk.keeps_forward(w.n_x, w.L, w.L, w.d, w.lam, w.lam, w.flags, sk.SK_F64)
+    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=True, keep=True)
 
 
 @pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
@@ -104,7 +118,7 @@ def test_c3_gram_reduced(dtype):
 
 def test_c4_long_sequences_two_pairs_full_length():
     w, X, Y = workloads.make("c4", n_x=2, n_y=2)
-    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=True)
+    run_pairs(X, Y, w.lam, w.lam, w.flags, torch.float64, backward=True, keep=True)
 
 
 def test_c5_gram_reduced_and_symmetric():
