@@ -38,6 +38,19 @@ def algorithmic_flops_per_cell(d, time_aug, lam, backward):
     return 15.0 + (10.0 + 2.0 * de + 4.0 * d) / per_coarse
 
 
+def timed_step(sk, step, i, every):
+    """Step i of the timed region.  The library brackets its sweep launches with HIP events on the launch stream while
+    event timing is on; a pair of events costs a few microseconds of idle GPU around the launch (measured on c2: 0.195
+    ms per step with every launch bracketed, 0.180 ms with none), so only one step in `every` is bracketed.  The
+    kernel durations are averages over those steps, taken inside the timed region."""
+    on = every > 0 and i % every == 0
+    if on:
+        sk.sigkernel_event_timing(True)
+    step()
+    if on:
+        sk.sigkernel_event_timing(False)
+
+
 def bench_signature(args):
     """Side measurement (not the headline): batched truncated signatures by Horner's scheme (Section 2.3) and their
     gradients (Section 2.4) on the shapes (B, L, d, N) of the paper's Table 1.  A step is one signature_fwd call
@@ -86,14 +99,12 @@ def bench_signature(args):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    sk.sigkernel_event_timing(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        timed_step(sk, step, i, args.time_every)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    sk.sigkernel_event_timing(False)
     f_ms, nf, b_ms, nb = sk.sigkernel_event_timing_read()
     sec = (t1 - t0) / args.steps
     fma = sum(sum(D ** j for j in range(1, k + 1)) for k in range(1, N + 1))
@@ -148,6 +159,8 @@ def main():
     ap.add_argument("--mmd", action="store_true",
                     help="Gram workloads: a step is one sigkernel_mmd2 call (value and both gradients): K(X,X), K(X,Y) "
                          "and K(Y,Y) with gradients (a side measurement, not the headline; no roofline figure)")
+    ap.add_argument("--time-every", type=int, default=8,
+                    help="bracket the sweep launches of one step in this many with HIP events (1: every step)")
     ap.add_argument("--no-keep-forward", action="store_true",
                     help="pair workloads: the backward call sweeps forward again instead of taking over the sweep of the "
                          "forward call before it (SK_FLAG_KEEP_FORWARD / SK_FLAG_HAVE_FORWARD)")
@@ -249,15 +262,14 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # timed region: exactly --steps steps, sweep kernels bracketed by HIP events on the launch stream
-    sk.sigkernel_event_timing(True)
+    # timed region: exactly --steps steps; in one step out of --time-every the sweep kernels are bracketed by HIP events
+    # on the launch stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        timed_step(sk, step, i, args.time_every)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    sk.sigkernel_event_timing(False)
     fwd_ms, nf, bwd_ms, nb = sk.sigkernel_event_timing_read()
     sec_per_step = (t1 - t0) / args.steps
 
