@@ -350,7 +350,7 @@ def main():
                                                                              "+bwd" if w.backward else "", reps, spent)}
 
     out = {
-        "metric": "PDE cell-updates/s (fwd+bwd), fp64, 1 MI355X",
+        "metric": "PDE cell-updates/s (%s), fp64, 1 MI355X" % ("fwd+bwd" if w.backward else "fwd"),
         "value": cells / sec_per_step,
         "unit": "cells/s",
         "n_gpus": 1,
