@@ -23,6 +23,10 @@
  *  - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue work: no host
  *    synchronisation, results are complete when the stream reaches the end of the call's work.
  *    Two calls that share a workspace must be ordered (same stream).
+ *    The work of a call is kernel launches and, in one launch mode, device-to-device copies: no allocation, no
+ *    memset.  A call can therefore be recorded into a HIP graph (stream capture) and replayed, provided the same
+ *    call has been made once before outside a capture (the first launch of a kernel sets its attributes) and event
+ *    timing is off.
  *  - Return value: SK_OK (0) or a negative error code; nothing is enqueued on error.  Errors never
  *    throw or exit.  sigkernel_last_error() gives a thread-local message for the last non-zero return.
  *  - Empty batches (B = 0, N*M = 0) are a successful no-op.  A path with a single point (L = 1) has no

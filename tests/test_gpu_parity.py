@@ -602,6 +602,58 @@ def test_kept_forward_sweep_degenerate_shapes():
     check_grads(host(gy), gyr, torch.float64, "grad_y")
 
 
+@pytest.mark.parametrize("B,L,d,lam,flags", [(6, 70, 5, 1, 1),        # lock-step, kept forward sweep
+                                             (3000, 12, 3, 1, 0)])     # many pairs: preparation, sweep, finalisation
+def test_calls_can_be_captured_in_a_hip_graph(B, L, d, lam, flags):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no synchronisation, no memset), so a
+    training step can be captured once and replayed: every replay, with eager work in between, gives the eager bits
+    (many pairs: the gradient sums meet in global atomics, so those are compared to the tolerance)."""
+    X, Y = rand_paths(8300 + B, B, L, d, 0.25), rand_paths(8400 + B, B, L, d, 0.25)
+    x, y = dev(X), dev(Y)
+    gk = dev(np.random.default_rng(85).normal(size=B))
+    keeps = sk.keeps_forward(B, L, L, d, lam, lam, flags, sk.SK_F64)
+    assert keeps == (B == 6)
+    KEEP, HAVE = (sk.SK_FLAG_KEEP_FORWARD, sk.SK_FLAG_HAVE_FORWARD) if keeps else (0, 0)
+    need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L, L, d, lam, lam, flags | KEEP, sk.SK_F64),
+               sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, B, 0, L, L, d, lam, lam, flags, sk.SK_F64))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    k = torch.empty(B, dtype=torch.float64, device="cuda")
+    k2 = torch.empty_like(k)
+    gx, gy = torch.empty_like(x), torch.empty_like(y)
+
+    def step():
+        sk.sigkernel_fwd(x, y, lam, lam, flags | KEEP, k=k, ws=ws)
+        sk.sigkernel_bwd(x, y, gk, lam, lam, flags | HAVE, grad_x=gx, grad_y=gy, k_out=k2, ws=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            step()            # first launches set kernel attributes: not inside a capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    ref = (k.clone(), k2.clone(), gx.clone(), gy.clone())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (k, k2, gx, gy):
+            t.fill_(float(rep))                                     # eager work between the replays
+        other = sk.sigkernel_fwd(y, x, lam, lam, flags)             # ... and an eager call of the library
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(k, ref[0]) and torch.equal(k2, ref[1]) and torch.equal(other, ref[0])
+        if keeps:
+            assert torch.equal(gx, ref[2]) and torch.equal(gy, ref[3])
+        else:
+            check_grads(host(gx), host(ref[2]), torch.float64, "grad_x of replay %d" % rep)
+            check_grads(host(gy), host(ref[3]), torch.float64, "grad_y of replay %d" % rep)
+    kr, gxr, gyr = oracle.bwd(X, Y, host(gk), lam, lam, flags)
+    check_values(host(k), kr, torch.float64, "k from the graph")
+    check_grads(host(gx), gxr, torch.float64, "grad_x from the graph")
+
+
 def test_more_pairs_than_wave_slots():
     # every wave slot handles several pairs in turn, so its scratch rows and checkpoints are reused
     X = rand_paths(71, 5000, 6, 2, 0.3)
