@@ -204,15 +204,19 @@ def main():
         K = torch.empty((w.n_x, w.n_y), dtype=torch.float64, device=dev)
         gX = torch.empty_like(x)
         gY = torch.empty_like(y)
-        need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags, f64),
-                   sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM_BWD, w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags, f64))
+        # (as for the pair workloads below: the forward call keeps its sweep for the backward call where the launch
+        # mode can; the tile kernels of c5 cannot and ignore the flags)
+        keep = sk.SK_FLAG_KEEP_FORWARD if (w.backward and not args.no_keep_forward and not args.mmd) else 0
+        have = sk.SK_FLAG_HAVE_FORWARD if keep else 0
+        need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags | keep, f64),
+                   sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM_BWD, w.n_x, w.n_y, w.L, w.L, w.d, lam, lam, flags | have, f64))
         ws = torch.empty(need, dtype=torch.uint8, device=dev)
 
         def fwd_call():
-            sk.sigkernel_gram(x, y, None, lam, lam, flags, K=K, ws=ws)
+            sk.sigkernel_gram(x, y, None, lam, lam, flags | keep, K=K, ws=ws)
 
         def bwd_call():
-            sk.sigkernel_gram(x, y, W, lam, lam, flags, K=K, grad_X=gX, grad_Y=None if args.symmetric else gY, ws=ws)
+            sk.sigkernel_gram(x, y, W, lam, lam, flags | have, K=K, grad_X=gX, grad_Y=None if args.symmetric else gY, ws=ws)
     else:
         gk = torch.tensor(workloads.upstream_weights(77, (w.n_x,)), device=dev)
         k = torch.empty((w.n_x,), dtype=torch.float64, device=dev)
@@ -304,7 +308,7 @@ def main():
     # the sweep kernel's name as a profiler reports it, from the library's own launch plan
     if gram:
         desc = sk.sigkernel_describe(sk.SK_OP_GRAM_BWD if dom_back else sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, lam,
-                                     lam, flags, f64)
+                                     lam, flags | (have if dom_back else keep), f64)
     else:
         desc = sk.sigkernel_describe(sk.SK_OP_BWD if dom_back else sk.SK_OP_FWD, w.n_x, 0, w.L, w.L, w.d, lam, lam,
                                      flags | (have if dom_back else keep), f64)
@@ -367,7 +371,8 @@ def main():
             (", time-augmented" if flags & 1 else "") + (", lead-lag transformed" if args.lead_lag else "") +
             (", K(X,X)" if args.symmetric else ""),
             "+bwd" if w.backward else ""), "cells_per_step": cells,
-            "forward_sweep_kept_for_backward": bool((not gram) and w.backward and not args.no_keep_forward)},
+            "forward_sweep_kept_for_backward": bool(keep) and (
+                sk.keeps_forward(w.n_x, w.L, w.L, w.d, lam, lam, flags, f64, gram_M=w.n_y if gram else None))},
         "evals_per_s": w.pairs / sec_per_step,
         # K(X, X): the library solves the pairs n <= m only (k(x, y) = k(y, x) bit for bit) and copies the rest
         "pairs_solved": (w.n_x * (w.n_x + 1) // 2) if args.symmetric else w.pairs,

@@ -104,15 +104,19 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  * launch mode, every gradient of the call - are returned as NaN, never as inaccurate numbers.
  * SK_FLAG_BWD_REPLAY selects the slower variant that replays forward segments and has no such limit.
  *
- * A forward sweep that was kept.  A training step calls sigkernel_fwd and then sigkernel_bwd on the same paths; the
+ * A forward sweep that was kept (sigkernel_fwd / sigkernel_bwd, and sigkernel_gram without / with grad_K).  A training
+ * step calls sigkernel_fwd and then sigkernel_bwd on the same paths; the
  * backward call then need not sweep forward again.  sigkernel_fwd with SK_FLAG_KEEP_FORWARD takes the workspace of
- * the backward call (sigkernel_workspace_bytes reports that size for SK_OP_FWD with the flag) and leaves the
+ * the backward call, asked for with the flags (sigkernel_workspace_bytes for SK_OP_FWD / SK_OP_GRAM with
+ * SK_FLAG_KEEP_FORWARD, or for the backward operation with SK_FLAG_HAVE_FORWARD: it can be much larger than without,
+ * where checkpoints are then kept per pair instead of per wavefront) and leaves the
  * checkpoints of its sweep there; sigkernel_bwd with SK_FLAG_HAVE_FORWARD, the same workspace, x, y, shapes, lam and
  * other flags, and no other call on that workspace in between, runs the reverse sweep from them (and leaves them as
  * they are: the backward call may be repeated, say with another grad_k).  The caller vouches
  * for all of that.  What the library checks: a kept sweep is signed with a hash of the call's pointers x and y,
  * shapes, lam, transformation flags and dtype, a backward call that sweeps forward itself in that workspace erases
- * the signature, and a backward call whose own hash differs from the signature it finds returns NaN gradients.  Paths
+ * the signature (where it lays the workspace out in the same way), and a backward call whose own hash differs from
+ * the signature it finds returns NaN gradients.  Paths
  * changed in place between the two calls, or another forward call on that workspace, are not noticed.  Launch modes without this form ignore both flags (the forward call runs as usual,
  * the backward call sweeps forward itself), so results never depend on the flags; sigkernel_describe names the kernels.
  */

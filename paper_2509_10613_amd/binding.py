@@ -166,14 +166,18 @@ def workspace(nbytes, device):
     return t
 
 
-def keeps_forward(B, L1, L2, d, lam1, lam2, flags, dt):
-    """Whether sigkernel_fwd with SK_FLAG_KEEP_FORWARD leaves a sweep that sigkernel_bwd with SK_FLAG_HAVE_FORWARD takes
-    over for this shape (the launch plan names the first half of the backward kernel), or ignores the flag."""
-    if B < 1 or L1 < 2 or L2 < 2:
+def keeps_forward(B, L1, L2, d, lam1, lam2, flags, dt, gram_M=None):
+    """Whether sigkernel_fwd (gram_M = M: sigkernel_gram on B x M paths) with SK_FLAG_KEEP_FORWARD leaves a sweep that
+    the backward call with SK_FLAG_HAVE_FORWARD takes over for this shape (the launch plan names the first half of the
+    backward pass), or ignores the flag."""
+    if B < 1 or L1 < 2 or L2 < 2 or (gram_M is not None and gram_M < 1):
         return False
-    desc = sigkernel_describe(SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
+    if gram_M is None:
+        desc = sigkernel_describe(SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
+    else:
+        desc = sigkernel_describe(SK_OP_GRAM, B, gram_M, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
     kern = desc.split("kernel=", 1)[1].split(" grid=", 1)[0]
-    return (kern.startswith("lock_bwd_kernel<") and kern.endswith(", 1>")) or \
+    return ((kern.startswith("lock_bwd_kernel<") or kern.startswith("solo_bwd_kernel<")) and kern.endswith(", 1>")) or \
         (kern.startswith("band_fwd_kernel<") and kern.endswith(", true>"))
 
 

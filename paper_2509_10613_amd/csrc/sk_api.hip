@@ -152,13 +152,18 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.L1 = p.L1; a.L2 = p.L2;
         a.lk_phase = phase;
         a.lk_keep = backward ? reinterpret_cast<double*>(base + p.off_keep) : nullptr;
+    } else if (phase != 0 && p.keep_solo) {
+        a.lk_phase = phase;
+        a.lk_keep = reinterpret_cast<double*>(base + p.off_keep);
+        a.keep_len = p.keep_len;
     } else if (phase != 0 && !p.band) {
         return fail(SK_ERR_SHAPE, "internal: no split form of this launch");
     }
     // Band mode is two launches anyway (forward sweep with checkpoints and bottom rows in global memory, reverse
     // sweep); a kept forward sweep is the first of them, and its kernel values wait in the workspace.
     double* keep_k = (p.band && phase != 0) ? reinterpret_cast<double*>(base + p.off_keep) : nullptr;
-    if (backward && p.gramM == 0 && (fused || p.band) && p.off_keep_tag != 0) {
+    const bool own_tag_launch = p.band || p.keep_solo;   // these sign, erase and check in launches of their own
+    if (backward && ((p.gramM == 0 && (fused || p.band)) || p.keep_solo) && p.off_keep_tag != 0) {
         a.keep_tag = reinterpret_cast<unsigned long long*>(base + p.off_keep_tag);
         // FNV-1a over what the kept sweep depends on
         unsigned long long h = 1469598103934665603ull;
@@ -166,7 +171,8 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
             for (int i = 0; i < 8; ++i) { h ^= (v >> (8 * i)) & 0xffull; h *= 1099511628211ull; }
         };
         mix(reinterpret_cast<uintptr_t>(x)); mix(reinterpret_cast<uintptr_t>(y));
-        mix((unsigned long long)p.npairs); mix((unsigned long long)p.L1); mix((unsigned long long)p.L2);
+        mix((unsigned long long)p.npairs); mix((unsigned long long)p.nx); mix((unsigned long long)p.ny);
+        mix((unsigned long long)p.L1); mix((unsigned long long)p.L2);
         mix((unsigned long long)p.d); mix((unsigned long long)lam1); mix((unsigned long long)lam2);
         mix((unsigned long long)(flags & (SK_FLAG_TIME_AUG | SK_FLAG_LEAD_LAG))); mix(sizeof(T));
         a.keep_tag_val = h | 1ull;
@@ -182,7 +188,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
                                phase == 2 ? p.nflags / 2 : 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags,
                                ll, st));
     // band mode signs, erases and checks a kept sweep in launches of their own (the lock-step kernels do it themselves)
-    if (p.band && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
+    if (own_tag_launch && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
     bool timed = false;
     TimedLaunch tl{};
     {
@@ -205,7 +211,7 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         std::lock_guard<std::mutex> lk(g_timing_mu);
         g_timed.push_back(tl);
     }
-    if (p.band && a.keep_tag && phase != 2) SK_CHECK(launch_keep_tag(a.keep_tag, phase == 1 ? a.keep_tag_val : 0ull, 0, a.err, st));
+    if (own_tag_launch && a.keep_tag && phase != 2) SK_CHECK(launch_keep_tag(a.keep_tag, phase == 1 ? a.keep_tag_val : 0ull, 0, a.err, st));
     if (keep_k && phase == 1)
         SK_CHECK(hipMemcpyAsync(keep_k, a.k_out, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
     if (keep_k && phase == 2 && a.k_out)
@@ -250,9 +256,11 @@ int check_device()
 }
 
 // Whether the backward plan pb has its forward and reverse sweeps as launches of their own: the lock-step kernels that
-// work on the caller's arrays (pairs of double paths, no lead-lag transform), and the band kernels.
+// work on the caller's arrays (pairs of double paths, no lead-lag transform), the band kernels, and the solo kernels
+// (pb made with keep = true: checkpoints and bottom rows per pair).
 bool split_forward(const sk::Plan& pb, sk_dtype dt, int flags)
 {
+    if (pb.keep_solo) return true;                     // pair batches and Gram matrices
     if (pb.gramM != 0) return false;
     return pb.band || (pb.lock && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG));
 }
@@ -289,16 +297,16 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     // A forward sweep kept for the backward call: the launch modes that have the two halves of the backward call as
     // launches of their own run the first half here and the second half there; the others ignore both flags.
     int phase = 0;
-    if (!gram && (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD))) {
-        const sk::Plan pb = backward ? p : sk::make_plan(true, false, false, nx, ny, L1, L2, d, lam1, lam2, elem,
-                                                         !(flags & SK_FLAG_BWD_REPLAY));
+    if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
+        const sk::Plan pb = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
+                                          !(flags & SK_FLAG_BWD_REPLAY), true);
         if (!pb.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
-        if (!backward && ws_bytes < pb.total)
-            return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed (SK_FLAG_KEEP_FORWARD: that of sigkernel_bwd)",
-                        ws_bytes, pb.total);
+        if (ws_bytes < pb.total)
+            return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed (a kept forward sweep: the backward call's, "
+                        "asked for with the flag)", ws_bytes, pb.total);
         if (split_forward(pb, dt, flags)) {
             phase = backward ? 2 : 1;
-            if (!backward) p = pb;
+            p = pb;
         }
     }
     if (ws_bytes < p.total)
@@ -322,14 +330,16 @@ size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, 
 {
     const bool gram = op == SK_OP_GRAM || op == SK_OP_GRAM_BWD;
     // a forward call that keeps its sweep works in the backward call's workspace
-    const bool backward = op == SK_OP_BWD || op == SK_OP_GRAM_BWD || (op == SK_OP_FWD && (flags & SK_FLAG_KEEP_FORWARD));
+    const bool fwd_op = op == SK_OP_FWD || op == SK_OP_GRAM;
+    const bool kept = (flags & (fwd_op ? SK_FLAG_KEEP_FORWARD : SK_FLAG_HAVE_FORWARD)) != 0;
+    const bool backward = !fwd_op || kept;
     if (op < SK_OP_FWD || op > SK_OP_GRAM_BWD) return 0;
     const int64_t ny = gram ? M : B_or_N;
     if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
     if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
     // The symmetric Gram case needs no more than the general one, so the query does not distinguish them.
     sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
-                               !(flags & SK_FLAG_BWD_REPLAY));
+                               !(flags & SK_FLAG_BWD_REPLAY), kept);
     return p.valid ? p.total : 0;
 }
 
@@ -523,13 +533,13 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     }
     // a kept forward sweep: the two halves of the backward call, where the launch mode has them
     int phase = 0;
-    if (!gram && (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD))) {
-        const sk::Plan pb = backward ? p : sk::make_plan(true, false, false, B_or_N, ny, L1, L2, d, lam1, lam2,
-                                                         dt == SK_F64 ? 8 : 4, !(flags & SK_FLAG_BWD_REPLAY));
+    if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
+        const sk::Plan pb = sk::make_plan(true, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+                                          !(flags & SK_FLAG_BWD_REPLAY), true);
         if (pb.valid && split_forward(pb, dt, flags)) {
             phase = backward ? 2 : 1;
             p = pb;
-        } else if (pb.valid && !backward) {
+        } else if (pb.valid) {
             p.total = pb.total > p.total ? pb.total : p.total;   // the caller still brings the backward call's workspace
         }
     }
@@ -552,7 +562,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.solo) {
         mode = "solo";
-        std::snprintf(kern, sizeof(kern), "solo_%s_kernel<%d, %d, %d>", backward ? "bwd" : "fwd", p.BL, p.DT, p.lk_M);
+        if (backward || phase) std::snprintf(kern, sizeof(kern), "solo_bwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase);
+        else std::snprintf(kern, sizeof(kern), "solo_fwd_kernel<%d, %d, %d>", p.BL, p.DT, p.lk_M);
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.lock) {
         mode = "lock-step";

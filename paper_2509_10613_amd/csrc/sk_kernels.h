@@ -78,6 +78,8 @@ struct SweepArgs {
     // checkpoints and the strips' bottom rows in global memory; 2 = the reverse sweep only, from what 1 left; 0 = both
     int lk_phase;
     real* lk_keep;       // [npairs][lk_ns + 1][lk_rowlen]: the hand-over rows between the two launches
+                         // (solo kernels: [npairs][keep_len], the pair's bottom row)
+    long keep_len;
     // A kept forward sweep is signed with a hash of the call's arguments; the reverse sweep that takes it over compares
     // (a mismatch gives NaN gradients), and a backward call that sweeps forward itself erases the signature.
     unsigned long long* keep_tag;

@@ -52,6 +52,8 @@ struct Plan {
     size_t off_dxT = 0, off_dyT = 0, off_gdxT = 0, off_gdyT = 0, off_rows = 0, off_adj = 0, off_ckpt = 0;
     size_t off_kio = 0, off_gkio = 0;   // float callers: double staging of k and grad_k
     size_t off_keep_tag = 0;
+    int keep_solo = 0;                  // solo backward plan with per-pair checkpoints and bottom rows
+    int64_t keep_len = 0;               // doubles per kept bottom row (solo)
     size_t off_keep = 0;                // backward: what a kept forward sweep leaves besides rows and checkpoints
                                         // (lock-step: the hand-over rows; band: the kernel values)
     size_t off_err = 0;                 // one int: a bounded wait between cooperating waves ran out
@@ -112,8 +114,11 @@ constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair alrea
 constexpr int kUncomputeS = 8;   // macro-steps between checkpoints when the reverse sweep inverts Eq. (1)
 
 inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
-                      int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true)
+                      int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true, bool keep = false)
 {
+    // keep: a backward plan whose forward sweep may be a launch of its own (a forward call that keeps its sweep for
+    // the backward call).  Lock-step and band plans are laid out for that anyway; solo plans then get checkpoints and
+    // a bottom row per pair instead of per wave.
     Plan p;
     p.uncompute = backward && uncompute;
     const int elem = 8;
@@ -377,7 +382,13 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const bool lean = p.lock || p.solo || p.tile || p.band;
         const int NVC = lean ? p.lk_M * R + C + 2 : R + C + 2;
         p.ckpt_slot = p.tile ? 0 : (int64_t)(lean ? p.lk_ns : p.ns) * (p.nseg + 1) * NVC * kWave;
-        p.off_ckpt = take((size_t)p.nslots * p.ckpt_slot * elem);
+        p.keep_solo = (keep && p.solo) ? 1 : 0;
+        p.off_ckpt = take((size_t)(p.keep_solo ? p.npairs : p.nslots) * p.ckpt_slot * elem);
+        if (p.keep_solo) {
+            p.keep_len = (int64_t)kWave * C + (int64_t)p.lk_NT * C + 2;   // the bottom row as the kernel holds it in LDS
+            p.off_keep = take((size_t)p.npairs * p.keep_len * elem);
+            p.off_keep_tag = take(256);
+        }
         if (p.lock) p.off_keep = take((size_t)p.npairs * (p.lk_ns + 1) * p.lk_rowlen * elem);
         else if (p.band) p.off_keep = take((size_t)p.kcount * elem);   // band mode: the kernel values of the kept sweep
         if (p.lock || p.band) p.off_keep_tag = take(256);   // which call's forward sweep the workspace holds

@@ -105,7 +105,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo
 // backward
 // ------------------------------------------------------------------------------------------------
 // (second launch bound: wavefronts per SIMD the register allocation has to leave room for)
-template <int BL, int D, int M>
+// PHASE 0: the whole backward pass.  PHASE 1 / 2: its two halves as launches of their own, for a forward call that
+// keeps its sweep and the backward call that takes it over: checkpoints and bottom row then have a place per pair in
+// global memory (phase 1 copies the row out of LDS, phase 2 copies it in) instead of one per wave.
+template <int BL, int D, int M, int PHASE>
 __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -124,7 +127,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
     SK_LDS real* gyl = (SK_LDS real*)(mylds + a.lk_off_gy);
     SK_LDS real* krow = (SK_LDS real*)(mylds + a.lk_off_krows) + LK::PADF;   // bottom row, by node column
     SK_LDS real* dump = (SK_LDS real*)(mylds + a.lk_off_dump);
-    real* ckpt = a.ckpt + slot * a.ckpt_slot + lane;
+    real* ckpt = a.ckpt + slot * a.ckpt_slot + lane;   // PHASE != 0: set per pair below
+    const int klen = kWave * C + a.lk_NT * C + 2;      // the bottom row's place in LDS, from krow - PADF
     const long q0 = slot * a.npairs / nslots, q1 = (slot + 1) * a.npairs / nslots;
     const int nb = a.nb;
     const int NT = a.lk_NT;           // macro-steps, a multiple of S
@@ -156,10 +160,18 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
             gdy_cur = a.gdy + yi * a.ystride;
         }
         cf.setup(a, 0, lane, a.dx + xi * a.xstride, ylds);
-        const real gk = gram_weight(a, pid, pid2);
+        const real gk = PHASE == 1 ? 0.0 : gram_weight(a, pid, pid2);
+        real* keepq = nullptr;
+        if constexpr (PHASE != 0) {
+            ckpt = a.ckpt + q * a.ckpt_slot + lane;
+            keepq = a.lk_keep + q * a.keep_len;
+        }
+        if constexpr (PHASE == 2) {
+            for (int t = lane; t < klen; t += kWave) krow[t - LK::PADF] = keepq[t];
+        }
 
         // ---- phase 1: forward, a checkpoint every S macro-steps, the bottom row into LDS ----
-        {
+        if constexpr (PHASE != 2) {
             typename LK::Fwd f;
             f.init();
             for (int t = lane; t < LK::PADF + 1; t += kWave) krow[t - LK::PADF] = 1.0;   // columns left of the grid
@@ -200,6 +212,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
         if (a.k_out && lane == 0) {
             a.k_out[pid] = krow[nb * C];
             if (pid2 != pid) a.k_out[pid2] = krow[nb * C];
+        }
+        if constexpr (PHASE == 1) {
+            for (int t = lane; t < klen; t += kWave) keepq[t] = krow[t - LK::PADF];
+            continue;
         }
         scratch_fence();   // the checkpoints are read back below
 
@@ -338,18 +354,29 @@ hipError_t launch_solo_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t
     return hipGetLastError();
 }
 
-template <int BL, int D, int M>
-hipError_t launch_solo_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+template <int BL, int D, int M, int PHASE>
+hipError_t launch_solo_bwd_phase(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M, PHASE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((solo_bwd_kernel<BL, D, M>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+    hipLaunchKernelGGL((solo_bwd_kernel<BL, D, M, PHASE>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     return hipGetLastError();
+}
+
+template <int BL, int D, int M>
+hipError_t launch_solo_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.lk_phase == 0) return launch_solo_bwd_phase<BL, D, M, 0>(a, grid, lds, st);
+    // the halves need the per-pair places of checkpoints and bottom rows
+    if (!a.lk_keep || a.keep_len != (long)kWave * (1 << BL) + (long)a.lk_NT * (1 << BL) + 2) return hipErrorInvalidValue;
+    if (a.lk_phase == 1) return launch_solo_bwd_phase<BL, D, M, 1>(a, grid, lds, st);
+    if (a.lk_phase == 2) return launch_solo_bwd_phase<BL, D, M, 2>(a, grid, lds, st);
+    return hipErrorInvalidValue;
 }
 
 template <int BL, int D>

@@ -218,7 +218,7 @@ def test_short_paths_with_many_channels_stay_solo():
     rng = np.random.default_rng(78)
     X = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (nx, L, d)), axis=1)
     Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (ny, L, d)), axis=1)
-    assert "solo_bwd_kernel<0, 16, 1>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
+    assert "solo_bwd_kernel<0, 16, 1, 0>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
     W = workloads.upstream_weights(61, (nx, ny))
     K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), 0, 0, 0)
     torch.cuda.synchronize()
@@ -506,7 +506,8 @@ def test_shapes_fp32(L1, L2, d, lam):
     (2, 40, 9, 7, 2, 2, 1, torch.float64),
     (5, 9, 12, 20, 1, 1, 1, torch.float64),      # run-time channel loop: no split form, the flags change nothing
     (6, 40, 33, 3, 0, 0, 0, torch.float32),      # float paths: likewise
-    (5000, 6, 5, 2, 1, 1, 0, torch.float64),     # many pairs: likewise
+    (5000, 6, 5, 2, 1, 1, 0, torch.float64),     # many pairs: solo kernels, checkpoints and bottom row per pair
+    (3000, 40, 33, 3, 0, 0, 1, torch.float32),
     (5, 20, 18, 3, 1, 1, sk.SK_FLAG_LEAD_LAG, torch.float64),
     (5, 400, 330, 3, 0, 0, 0, torch.float64),    # band kernels: the two launches of the backward call, one per call
     (8, 700, 500, 5, 1, 1, 1, torch.float64),
@@ -518,8 +519,9 @@ def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flag
     workspace: the same arithmetic as the backward call alone, so the same bits (band kernels: their gradient sums
     meet in global atomics, in any order); and both against the oracle."""
     sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
-    band = "mode=band" in sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, sdt)
-    assert band == (min(L1, L2) >= 200)
+    desc = sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, sdt)
+    band = "mode=band" in desc or "mode=solo" in desc      # modes whose gradient sums meet in atomics
+    assert ("mode=band" in desc) == (min(L1, L2) >= 200) and ("mode=solo" in desc) == (B >= 700)
 
     def same(a, b):
         if not band:
@@ -559,11 +561,13 @@ def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flag
         blank = torch.zeros(need, dtype=torch.uint8, device="cuda")
         _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=blank)
         assert torch.all(torch.isnan(gx3)) and torch.all(torch.isnan(gy3))
-        # a backward call that sweeps forward itself uses the same memory: the kept sweep is gone afterwards
-        sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
-        sk.sigkernel_bwd(x2, y, gk, lam1, lam2, flags, ws=ws)
-        _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
-        assert torch.all(torch.isnan(gx3)) and torch.all(torch.isnan(gy3))
+        # a backward call that sweeps forward itself uses the same memory: the kept sweep is gone afterwards (where
+        # that call lays the workspace out in the same way: not the solo kernels)
+        if "mode=solo" not in desc:
+            sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+            sk.sigkernel_bwd(x2, y, gk, lam1, lam2, flags, ws=ws)
+            _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+            assert torch.all(torch.isnan(gx3)) and torch.all(torch.isnan(gy3))
         _, gx3, gy3 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags, ws=ws)
         assert same(gx3, gx0) and same(gy3, gy0)
     # the kept sweep needs the backward call's workspace: the forward call's own is refused where it is smaller
@@ -572,6 +576,49 @@ def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flag
         with pytest.raises(sk.SigKernelError):
             sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD,
                              ws=torch.empty(small, dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("N,M,L,d,lam,flags,dtype,sym", [(40, 30, 128, 3, 1, 0, torch.float64, False),   # c3's shape
+                                                          (36, 36, 40, 5, 1, 1, torch.float64, True),
+                                                          (60, 50, 30, 2, 0, 0, torch.float32, False)])
+def test_forward_sweep_of_a_gram_matrix_kept_for_its_backward_call(N, M, L, d, lam, flags, dtype, sym):
+    """sigkernel_gram with SK_FLAG_KEEP_FORWARD, then sigkernel_gram with grad_K and SK_FLAG_HAVE_FORWARD on the same
+    workspace (solo kernels: checkpoints and bottom row per pair), against the call that sweeps forward itself and
+    against the oracle."""
+    sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+    X = rand_paths(8500 + N, N, L, d, 0.2)
+    Y = X if sym else rand_paths(8600 + M, M, L, d, 0.2)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    x = dev(X, dtype)
+    y = x if sym else dev(Y, dtype)
+    assert sk.keeps_forward(N, L, L, d, lam, lam, flags, sdt, gram_M=M)
+    W = workloads.upstream_weights(86, (N, M))
+    w = dev(W, dtype)
+    K0, gX0, gY0 = sk.sigkernel_gram(x, y, w, lam, lam, flags)
+    need = sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, N, M, L, L, d, lam, lam, flags | sk.SK_FLAG_KEEP_FORWARD, sdt)
+    assert need == sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM_BWD, N, M, L, L, d, lam, lam,
+                                                flags | sk.SK_FLAG_HAVE_FORWARD, sdt)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    tol = TOL[dtype]
+    for rep in range(2):
+        K1 = sk.sigkernel_gram(x, y, None, lam, lam, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+        K2, gX, gY = sk.sigkernel_gram(x, y, w, lam, lam, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(K1, K0) and torch.equal(K2, K0)
+        assert float((gX - gX0).abs().max()) <= tol * max(1.0, float(gX0.abs().max()))
+        if not sym:
+            assert float((gY - gY0).abs().max()) <= tol * max(1.0, float(gY0.abs().max()))
+    Kr, gXr, gYr = oracle.gram(Xr, Yr, rounded(W, dtype), lam, lam, flags)
+    check_values(host(K1), Kr, dtype, "K of the kept sweep")
+    check_grads(host(gX), gXr + (gYr if sym else 0.0), dtype, "grad_X after a kept sweep")
+    if not sym:
+        check_grads(host(gY), gYr, dtype, "grad_Y after a kept sweep")
+    # another call's sweep in the workspace: NaN, not numbers
+    x2 = x.clone()
+    _, gX3, _ = sk.sigkernel_gram(x2, x2 if sym else y, w, lam, lam, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+    assert torch.all(torch.isnan(gX3))
+    _, gX3, _ = sk.sigkernel_gram(x, y, w, lam, lam, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+    assert float((gX3 - gX0).abs().max()) <= tol * max(1.0, float(gX0.abs().max()))
 
 
 def test_kept_forward_sweep_degenerate_shapes():
@@ -603,7 +650,7 @@ def test_kept_forward_sweep_degenerate_shapes():
 
 
 @pytest.mark.parametrize("B,L,d,lam,flags", [(6, 70, 5, 1, 1),        # lock-step, kept forward sweep
-                                             (3000, 12, 3, 1, 0)])     # many pairs: preparation, sweep, finalisation
+                                             (3000, 12, 3, 1, 0)])     # solo: preparation, sweep, finalisation
 def test_calls_can_be_captured_in_a_hip_graph(B, L, d, lam, flags):
     """The entry points only enqueue kernels on the caller's stream (no allocation, no synchronisation, no memset), so a
     training step can be captured once and replayed: every replay, with eager work in between, gives the eager bits
@@ -611,9 +658,9 @@ def test_calls_can_be_captured_in_a_hip_graph(B, L, d, lam, flags):
     X, Y = rand_paths(8300 + B, B, L, d, 0.25), rand_paths(8400 + B, B, L, d, 0.25)
     x, y = dev(X), dev(Y)
     gk = dev(np.random.default_rng(85).normal(size=B))
-    keeps = sk.keeps_forward(B, L, L, d, lam, lam, flags, sk.SK_F64)
-    assert keeps == (B == 6)
-    KEEP, HAVE = (sk.SK_FLAG_KEEP_FORWARD, sk.SK_FLAG_HAVE_FORWARD) if keeps else (0, 0)
+    assert sk.keeps_forward(B, L, L, d, lam, lam, flags, sk.SK_F64)
+    keeps = B == 6            # the lock-step kernels: every sum in a fixed order
+    KEEP, HAVE = sk.SK_FLAG_KEEP_FORWARD, sk.SK_FLAG_HAVE_FORWARD
     need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L, L, d, lam, lam, flags | KEEP, sk.SK_F64),
                sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, B, 0, L, L, d, lam, lam, flags, sk.SK_F64))
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
