@@ -21,6 +21,9 @@ import torch
 from . import binding as sk
 
 
+_KEEP_LIMIT = 1 << 30   # bytes of workspace a forward call may hold on to for its backward call
+
+
 class _PairKernel(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, y, lam1, lam2, flags):
@@ -37,8 +40,9 @@ class _PairKernel(torch.autograd.Function):
                                                                                      flags, sk._dt(x)):
             need = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, L1, y.shape[1], d, lam1, lam2,
                                                 flags | sk.SK_FLAG_KEEP_FORWARD, sk._dt(x))
-            ctx.ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=x.device)
-            return sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ctx.ws)
+            if need <= _KEEP_LIMIT:    # large batches of pairs would pin gigabytes per live graph: they sweep twice
+                ctx.ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=x.device)
+                return sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ctx.ws)
         return sk.sigkernel_fwd(x, y, lam1, lam2, flags)
 
     @staticmethod
