@@ -146,6 +146,7 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
  * Three Gram computations (two of them symmetric: half of their pairs are solved) with constant upstream
  * weights that are generated on the device, then one reduction.  Same conventions as the other entry points;
  * the workspace size comes from sigkernel_mmd2_workspace_bytes (with_grads != 0 if any gradient is wanted).
+ * SK_FLAG_KEEP_FORWARD and SK_FLAG_HAVE_FORWARD do not apply here (one call computes everything) and are refused.
  */
 size_t sigkernel_mmd2_workspace_bytes(int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
                                       int flags, sk_dtype dt, int with_grads);

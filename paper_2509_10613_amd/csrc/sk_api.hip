@@ -457,7 +457,9 @@ extern "C" {
 size_t sigkernel_mmd2_workspace_bytes(int64_t N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
                                       int flags, sk_dtype dt, int with_grads)
 {
-    if (N < 1 || M < 1 || validate(N, M, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
+    if (N < 1 || M < 1 || (flags & (SK_FLAG_KEEP_FORWARD | SK_FLAG_HAVE_FORWARD)) ||
+        validate(N, M, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK)
+        return 0;
     return mmd_layout(N, M, L1, L2, d, lam1, lam2, flags, dt, with_grads != 0).total;
 }
 
@@ -465,6 +467,9 @@ int sigkernel_mmd2(const void* X, const void* Y, void* loss, void* grad_X, void*
                    int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt, void* ws,
                    size_t ws_bytes, void* stream)
 {
+    // one call computes everything: there is no forward sweep to keep or to take over
+    if (flags & (SK_FLAG_KEEP_FORWARD | SK_FLAG_HAVE_FORWARD))
+        return fail(SK_ERR_DTYPE, "SK_FLAG_KEEP_FORWARD / SK_FLAG_HAVE_FORWARD do not apply to sigkernel_mmd2");
     int rc = validate(N, M, L1, L2, d, lam1, lam2, flags, (int)dt);
     if (rc != SK_OK) return rc;
     if (N < 1 || M < 1) return fail(SK_ERR_SHAPE, "mmd2 needs at least one path on either side");

@@ -28,6 +28,15 @@ def test_exports_every_declared_symbol(lib):
     assert b"gfx950" in lib.sigkernel_version()
 
 
+def test_mmd2_takes_no_kept_sweep(lib):
+    q = lib.sigkernel_mmd2_workspace_bytes
+    assert q(8, 8, 16, 16, 3, 0, 0, 0, binding.SK_F64, 1) > 0
+    assert q(8, 8, 16, 16, 3, 0, 0, binding.SK_FLAG_KEEP_FORWARD, binding.SK_F64, 1) == 0
+    one = C.c_void_p(256)
+    assert lib.sigkernel_mmd2(one, one, one, one, one, 8, 8, 16, 16, 3, 0, 0, binding.SK_FLAG_HAVE_FORWARD, binding.SK_F64,
+                              one, 1 << 30, None) == -4
+
+
 def test_argument_validation_needs_no_gpu(lib):
     f = lib.sigkernel_fwd
     one = C.c_void_p(256)
