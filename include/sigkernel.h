@@ -55,9 +55,9 @@ enum {
     SK_FLAG_TIME_AUG = 1,   /* append the channel t_i = i/(L-1) to both paths on the fly (Section 4) */
     SK_FLAG_BWD_REPLAY = 2, /* backward: replay forward segments instead of inverting Eq. (1); see sigkernel_bwd */
     SK_FLAG_LEAD_LAG = 8,   /* lead-lag transform of both paths on the fly (Section 4) */
-    SK_FLAG_KEEP_FORWARD = 16, /* sigkernel_fwd: leave the forward sweep in the workspace for the backward call
+    SK_FLAG_KEEP_FORWARD = 16, /* forward calls: leave the forward sweep in the workspace for the backward call
                                   (Section 3.4: the backward pass works on the forward pass's grid); see sigkernel_bwd */
-    SK_FLAG_HAVE_FORWARD = 32, /* sigkernel_bwd: the workspace holds the forward sweep a sigkernel_fwd call kept */
+    SK_FLAG_HAVE_FORWARD = 32, /* backward calls: the workspace holds the forward sweep a forward call kept */
     SK_FLAG_SHORT_WAITS = 4 /* diagnostic: a workgroup that waits for another one's progress gives up after a single
                                poll.  Exercises the path a wait that runs out takes: every kernel still ends normally
                                and the results of the call are NaN.  Only launches whose workgroups wait for each
@@ -104,21 +104,24 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  * launch mode, every gradient of the call - are returned as NaN, never as inaccurate numbers.
  * SK_FLAG_BWD_REPLAY selects the slower variant that replays forward segments and has no such limit.
  *
- * A forward sweep that was kept (sigkernel_fwd / sigkernel_bwd, and sigkernel_gram without / with grad_K).  A training
- * step calls sigkernel_fwd and then sigkernel_bwd on the same paths; the
- * backward call then need not sweep forward again.  sigkernel_fwd with SK_FLAG_KEEP_FORWARD takes the workspace of
- * the backward call, asked for with the flags (sigkernel_workspace_bytes for SK_OP_FWD / SK_OP_GRAM with
- * SK_FLAG_KEEP_FORWARD, or for the backward operation with SK_FLAG_HAVE_FORWARD: it can be much larger than without,
- * where checkpoints are then kept per pair instead of per wavefront) and leaves the
- * checkpoints of its sweep there; sigkernel_bwd with SK_FLAG_HAVE_FORWARD, the same workspace, x, y, shapes, lam and
- * other flags, and no other call on that workspace in between, runs the reverse sweep from them (and leaves them as
- * they are: the backward call may be repeated, say with another grad_k).  The caller vouches
- * for all of that.  What the library checks: a kept sweep is signed with a hash of the call's pointers x and y,
- * shapes, lam, transformation flags and dtype, a backward call that sweeps forward itself in that workspace erases
- * the signature (where it lays the workspace out in the same way), and a backward call whose own hash differs from
- * the signature it finds returns NaN gradients.  Paths
- * changed in place between the two calls, or another forward call on that workspace, are not noticed.  Launch modes without this form ignore both flags (the forward call runs as usual,
- * the backward call sweeps forward itself), so results never depend on the flags; sigkernel_describe names the kernels.
+ * A forward sweep that was kept (sigkernel_fwd then sigkernel_bwd; sigkernel_gram without, then with grad_K).
+ * A training step makes the forward call and then the backward call on the same paths; the backward call then need
+ * not sweep forward again.
+ *  - The forward call with SK_FLAG_KEEP_FORWARD takes the workspace of the backward call and leaves the checkpoints
+ *    of its sweep there.  That workspace is asked for with the flags: sigkernel_workspace_bytes for SK_OP_FWD /
+ *    SK_OP_GRAM with SK_FLAG_KEEP_FORWARD, or for SK_OP_BWD / SK_OP_GRAM_BWD with SK_FLAG_HAVE_FORWARD (the same
+ *    number).  It can be much larger than without the flags: launch modes that keep checkpoints per wavefront then
+ *    keep them per pair.
+ *  - The backward call with SK_FLAG_HAVE_FORWARD, the same workspace, the same arrays x and y, shapes, lam and other
+ *    flags, and no other call on that workspace in between, runs the reverse sweep from them.  It leaves them as they
+ *    are: it may be repeated, say with another grad_k.
+ *  - The caller vouches for all of that.  What the library checks: a kept sweep is signed with a hash of the call's
+ *    pointers x and y, shapes, lam, transformation flags and dtype; a backward call that sweeps forward itself in
+ *    that workspace erases the signature (where it lays the workspace out in the same way); and a backward call
+ *    whose own hash differs from the signature it finds returns NaN gradients.  Paths changed in place between the
+ *    two calls, or another forward call on that workspace, are not noticed.
+ *  - Launch modes without this form ignore both flags (the forward call runs as usual, the backward call sweeps
+ *    forward itself), so results never depend on the flags; sigkernel_describe names the kernels either way.
  */
 int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
                   int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,
