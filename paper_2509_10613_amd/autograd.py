@@ -60,6 +60,22 @@ class _PairKernel(torch.autograd.Function):
         return gx, gy, None, None, None
 
 
+def _gram_keep_workspace(ctx, X, Y, lam1, lam2, flags):
+    """A workspace of this call's own if it wants gradients, the launch mode can keep the forward sweep of a Gram matrix
+    for its backward call, and that costs no more than _KEEP_LIMIT bytes; else None."""
+    if not any(ctx.needs_input_grad[:2]):
+        return None
+    N, L1, d = X.shape
+    M, L2 = Y.shape[0], Y.shape[1]
+    if not sk.keeps_forward(N, L1, L2, d, lam1, lam2, flags, sk._dt(X), gram_M=M):
+        return None
+    need = sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, N, M, L1, L2, d, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD,
+                                        sk._dt(X))
+    if need > _KEEP_LIMIT:
+        return None
+    return torch.empty(max(int(need), 256), dtype=torch.uint8, device=X.device)
+
+
 class _GramKernel(torch.autograd.Function):
     @staticmethod
     def forward(ctx, X, Y, lam1, lam2, flags):
@@ -67,13 +83,19 @@ class _GramKernel(torch.autograd.Function):
         Y = Y.contiguous()
         ctx.save_for_backward(X, Y)
         ctx.args = (lam1, lam2, flags)
+        ctx.ws = _gram_keep_workspace(ctx, X, Y, lam1, lam2, flags)
+        if ctx.ws is not None:
+            return sk.sigkernel_gram(X, Y, None, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ctx.ws)
         return sk.sigkernel_gram(X, Y, None, lam1, lam2, flags)
 
     @staticmethod
     def backward(ctx, grad_K):
         X, Y = ctx.saved_tensors
         lam1, lam2, flags = ctx.args
-        _, gX, gY = sk.sigkernel_gram(X, Y, grad_K.contiguous(), lam1, lam2, flags)
+        if ctx.ws is not None:
+            _, gX, gY = sk.sigkernel_gram(X, Y, grad_K.contiguous(), lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ctx.ws)
+        else:
+            _, gX, gY = sk.sigkernel_gram(X, Y, grad_K.contiguous(), lam1, lam2, flags)
         return (gX if ctx.needs_input_grad[0] else None), (gY if ctx.needs_input_grad[1] else None), None, None, None
 
 
@@ -83,13 +105,17 @@ class _GramKernelSym(torch.autograd.Function):
         X = X.contiguous()
         ctx.save_for_backward(X)
         ctx.args = (lam1, lam2, flags)
+        ctx.ws = _gram_keep_workspace(ctx, X, X, lam1, lam2, flags)
+        if ctx.ws is not None:
+            return sk.sigkernel_gram(X, X, None, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ctx.ws)
         return sk.sigkernel_gram(X, X, None, lam1, lam2, flags)
 
     @staticmethod
     def backward(ctx, grad_K):
         (X,) = ctx.saved_tensors
         lam1, lam2, flags = ctx.args
-        _, gX, _ = sk.sigkernel_gram(X, X, grad_K.contiguous(), lam1, lam2, flags)   # total derivative, both slots
+        keep = sk.SK_FLAG_HAVE_FORWARD if ctx.ws is not None else 0
+        _, gX, _ = sk.sigkernel_gram(X, X, grad_K.contiguous(), lam1, lam2, flags | keep, ws=ctx.ws)   # total derivative
         return gX, None, None, None
 
 

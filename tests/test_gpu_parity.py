@@ -405,6 +405,24 @@ def test_autograd_wrappers_give_the_oracle_gradients():
     assert torch.equal(xa.grad, first)
     check_grads(host(xa.grad), oracle.bwd(X[:7], Y, gk, 1, 1, 1)[1], torch.float64, "d/dx, first graph")
     check_grads(host(xc.grad), oracle.bwd(X[2:9], Y, gk, 1, 1, 1)[1], torch.float64, "d/dx, second graph")
+    # Gram matrices large enough for the solo kernels: the wrappers keep the forward sweep there too
+    nx, ny = 40, 36
+    X = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (nx, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (ny, L, d)), axis=1)
+    assert binding.keeps_forward(nx, L, L, d, 1, 1, 1, binding.SK_F64, gram_M=ny)
+    x = dev(X).requires_grad_(True)
+    y = dev(Y).requires_grad_(True)
+    Wxy = workloads.upstream_weights(68, (nx, ny))
+    Wxx = workloads.upstream_weights(69, (nx, nx))
+    loss = (ska.sig_kernel_gram(x, y, 1, 1, 1) * dev(Wxy)).sum() + (ska.sig_kernel_gram(x, None, 1, 1, 1) * dev(Wxx)).sum()
+    loss.backward()
+    torch.cuda.synchronize()
+    Kxy, gx1, gy1 = oracle.gram(X, Y, Wxy, 1, 1, 1)
+    Kxx, gx2, _ = oracle.gram(X, X, Wxx, 1, 1, 1)     # the total derivative of K(X, X)
+    ref = (Kxy * Wxy).sum() + (Kxx * Wxx).sum()
+    assert abs(float(loss.detach()) - ref) <= 1e-10 * max(1.0, abs(ref))
+    check_grads(host(x.grad), gx1 + gx2, torch.float64, "d loss / dX, kept sweeps")
+    check_grads(host(y.grad), gy1, torch.float64, "d loss / dY, kept sweeps")
 
 
 @pytest.mark.parametrize("N,M,L1,L2,d,lam,flags,dtype", [(9, 7, 24, 30, 3, 1, 1, torch.float64),
