@@ -161,7 +161,8 @@ struct Lock {
         template <bool EDGE>
         __device__ __forceinline__ void produce_rev_t(int T0, SK_LDS real* half) const
         {
-            SK_LDS real* wp = half + lane * 4;
+            // two planes of 16 bytes per lane, (A, B) and (1/B, p/6): consecutive lanes at consecutive 16 bytes
+            SK_LDS real* wp = half + lane * 2;
             int J[2], b[2];
             real y[2][D];
             fetch<EDGE>(T0, J[0], b[0], y[0]);
@@ -176,9 +177,9 @@ struct Lock {
                     const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
                     real invB = __builtin_amdgcn_rcp(Bc);
                     invB = fma(fma(-Bc, invB, 1.0), invB, invB);
-                    SK_LDS real* ep = wp + (i * M + m) * (kWave * 4);
+                    SK_LDS real* ep = wp + (i * M + m) * (kWave * 2);
                     *(SK_LDS real2*)(ep) = real2{Ac, Bc};
-                    *(SK_LDS real2*)(ep + 2) = real2{invB, p * (1.0 / 6.0)};
+                    *(SK_LDS real2*)(ep + CR2 / 2) = real2{invB, p * (1.0 / 6.0)};
                 }
             }
         }
@@ -415,7 +416,7 @@ struct Lock {
                                               const SK_LDS real* krow, SK_LDS real* arow_out, SK_LDS real* dump,
                                               SK_LDS real* gphalf)
         {
-            const SK_LDS real* cp = half + lane * 4;
+            const SK_LDS real* cp = half + lane * 2;                    // see produce_rev_t for the layout
             const SK_LDS real* ap = arow_in + (T0 - (kWave - 1)) * C;   // feeds of the strip's last lane
             const SK_LDS real* kp = krow + (T0 - (kWave - 1)) * C;
             SK_LDS real* op = lane == 0 ? arow_out + T0 * C : dump + lane * C;
@@ -425,9 +426,9 @@ struct Lock {
             auto load = [&](int i) {
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    const SK_LDS real* ep = cp + (i * M + m) * (kWave * 4);
+                    const SK_LDS real* ep = cp + (i * M + m) * (kWave * 2);
                     ab[i][m] = *(const SK_LDS real2*)(ep);
-                    ip6[i][m] = *(const SK_LDS real2*)(ep + 2);
+                    ip6[i][m] = *(const SK_LDS real2*)(ep + CR2 / 2);
                 }
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) { ea[i][cc] = ap[i * C + cc]; ek[i][cc] = kp[i * C + cc]; }
