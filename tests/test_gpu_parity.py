@@ -556,7 +556,7 @@ def test_forward_sweep_kept_for_the_backward_call(B, L1, L2, d, lam1, lam2, flag
     assert need >= sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags,
                                                 sk.SK_F64 if dtype == torch.float64 else sk.SK_F32)
     ws = sk.workspace(need, x.device)
-    for rep in range(2):                         # the second round finds the workspace as the first one left it
+    for rep in range(2):                         # the second pass finds the workspace as the first one left it
         k1 = sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
         k2, gx1, gy1 = sk.sigkernel_bwd(x, y, gk, lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
         torch.cuda.synchronize()
