@@ -175,8 +175,11 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
             typename LK::Fwd f;
             f.init();
             for (int t = lane; t < LK::PADF + 1; t += kWave) krow[t - LK::PADF] = 1.0;   // columns left of the grid
-            SK_LDS real* const op0 = lane == kWave - 1 ? krow + (0 - (kWave - 1)) * C + 1 : dump + lane * C;
+            // every lane stores its bottom edge, the last lane into the row, the others into a dump that nobody reads:
+            // [c][lane], so that the 64 stores of an instruction are 8 bytes apart (16 apart they collide in pairs)
+            SK_LDS real* const op0 = lane == kWave - 1 ? krow + (0 - (kWave - 1)) * C + 1 : dump + lane;
             const int ostep = lane == kWave - 1 ? C : 0;
+            const int cstep = lane == kWave - 1 ? 1 : kWave;
             auto seg = [&](auto edge_c, int T0) {
                 constexpr bool EDGE = decltype(edge_c)::value;
                 SK_LDS real* op = op0 + T0 * ostep;
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
                     for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(f.bot[cc], 1.0);
                     f.step(recv, Ac, Bc);
 #pragma unroll
-                    for (int cc = 0; cc < C; ++cc) op[i * ostep + cc] = f.bot[cc];
+                    for (int cc = 0; cc < C; ++cc) op[i * ostep + cc * cstep] = f.bot[cc];
                 }
             };
             for (int g = 0; g < nseg; ++g) {
