@@ -27,7 +27,9 @@
  *    memset.  A call can therefore be recorded into a HIP graph (stream capture) and replayed, provided the same
  *    call has been made once before outside a capture (the first launch of a kernel sets its attributes) and event
  *    timing is off.
- *  - Return value: SK_OK (0) or a negative error code; nothing is enqueued on error.  Errors never
+ *  - Return value: SK_OK (0) or a negative error code.  Arguments are checked before anything is enqueued, so
+ *    nothing is enqueued for SK_ERR_NULL .. SK_ERR_WORKSPACE; after SK_ERR_HIP (a launch was refused by the
+ *    runtime) the launches made before the failing one stay enqueued and the outputs are undefined.  Errors never
  *    throw or exit.  sigkernel_last_error() gives a thread-local message for the last non-zero return.
  *  - Empty batches (B = 0, N*M = 0) are a successful no-op.  A path with a single point (L = 1) has no
  *    increments: k = 1 and all gradients are 0.
@@ -159,12 +161,17 @@ int sigkernel_mmd2(const void* X, const void* Y, void* loss, void* grad_X, void*
 
 /*
  * Benchmark support (no passage of the paper): while enabled, every sweep-kernel launch made by the
- * three entry points above is bracketed by a HIP event pair recorded on the caller's stream.
+ * entry points above is bracketed by a HIP event pair recorded on the caller's stream.
+ * sigkernel_event_timing(enable): 0 switches it off, any other value switches it on and is kept as a tag
+ * with every launch recorded from then on (a benchmark that times several kinds of call tags them apart).
  * sigkernel_event_timing_read waits for the recorded launches to finish, returns the summed elapsed
  * milliseconds and the launch counts of the forward and the backward sweep kernels since the last
- * read (any pointer may be NULL), and releases the events.  Not for use under stream capture.
+ * read (any pointer may be NULL), and releases the events; sigkernel_event_timing_read_tag does the same
+ * for the launches recorded under one tag and leaves the others (tag 0: all of them).
+ * Not for use under stream capture.
  */
 int sigkernel_event_timing(int enable);
+int sigkernel_event_timing_read_tag(int tag, double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches);
 int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches);
 
 /*

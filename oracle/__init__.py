@@ -168,6 +168,8 @@ def gram(X, Y, grad_K=None, lam1=0, lam2=0, flags=0, dtype=np.float64):
         return r[0], lead_lag_pullback(r[1]), (None if sym else lead_lag_pullback(r[2]))
     X = _arr(X, dtype)
     Y = X if sym else _arr(Y, dtype)
+    if not sym and Y.ctypes.data == X.ctypes.data:
+        Y = Y.copy()   # a slice that starts where X starts: the C entry point takes equal pointers for the symmetric case
     N, L1, d = X.shape
     M, L2, d2 = Y.shape
     assert d == d2

@@ -41,7 +41,7 @@ def SK_SIG_DEPTH(m):
 
 EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",
            "sigkernel_mmd2", "sigkernel_mmd2_workspace_bytes",
-           "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_last_error", "sigkernel_version",
+           "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_event_timing_read_tag", "sigkernel_last_error", "sigkernel_version",
            "signature_length", "signature_workspace_bytes", "signature_fwd", "signature_describe",
            "signature_bwd_workspace_bytes", "signature_bwd", "signature_bwd_describe"]
 
@@ -83,6 +83,9 @@ def load():
     lib.sigkernel_event_timing_read.restype = ci
     lib.sigkernel_event_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(ci), C.POINTER(C.c_double),
                                                 C.POINTER(ci)]
+    lib.sigkernel_event_timing_read_tag.restype = ci
+    lib.sigkernel_event_timing_read_tag.argtypes = [ci, C.POINTER(C.c_double), C.POINTER(ci), C.POINTER(C.c_double),
+                                                    C.POINTER(ci)]
     lib.signature_length.restype = i64
     lib.signature_length.argtypes = [i64, ci, ci]
     lib.signature_workspace_bytes.restype = C.c_size_t
@@ -142,14 +145,16 @@ def sigkernel_describe(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dt):
 
 
 def sigkernel_event_timing(enable):
-    _check(load().sigkernel_event_timing(1 if enable else 0))
+    """False / 0: off; True or a positive tag: on, launches are recorded under that tag."""
+    _check(load().sigkernel_event_timing(int(enable)))
 
 
-def sigkernel_event_timing_read():
-    """Returns (fwd_ms, fwd_launches, bwd_ms, bwd_launches) summed since the last read."""
+def sigkernel_event_timing_read(tag=0):
+    """Returns (fwd_ms, fwd_launches, bwd_ms, bwd_launches) summed since the last read (tag > 0: of the launches
+    recorded under that tag only)."""
     f, b = C.c_double(0), C.c_double(0)
     nf, nb = C.c_int(0), C.c_int(0)
-    _check(load().sigkernel_event_timing_read(C.byref(f), C.byref(nf), C.byref(b), C.byref(nb)))
+    _check(load().sigkernel_event_timing_read_tag(int(tag), C.byref(f), C.byref(nf), C.byref(b), C.byref(nb)))
     return f.value, nf.value, b.value, nb.value
 
 
@@ -157,8 +162,9 @@ _ws_cache = {}
 
 
 def workspace(nbytes, device):
-    """A cached, 256-byte aligned scratch tensor of at least nbytes on `device` (grown on demand)."""
-    key = str(device)
+    """A cached, 256-byte aligned scratch tensor of at least nbytes on `device` for calls on the current stream
+    (grown on demand; one per device and stream: calls that share a workspace must be ordered)."""
+    key = (str(device), torch.cuda.current_stream(device).cuda_stream)
     t = _ws_cache.get(key)
     if t is None or t.numel() < nbytes:
         t = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

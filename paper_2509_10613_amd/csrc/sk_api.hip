@@ -3,6 +3,7 @@
 // method lives in the kernels.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -29,10 +30,49 @@ int fail(int code, const char* fmt, ...)
 
 // Optional HIP-event timing of the sweep kernels (for benchmarks): one event pair per sweep launch,
 // recorded on the caller's stream while enabled.
-struct TimedLaunch { hipEvent_t start, stop; int backward; };
+struct TimedLaunch { hipEvent_t start, stop; int backward; int tag; };
 std::mutex g_timing_mu;
-bool g_timing_on = false;
+int g_timing_tag = 0;   // 0: off; otherwise the tag new launches are recorded under
 std::vector<TimedLaunch> g_timed;
+
+// The event pair of a launch that is being timed; an error return between the two records destroys the events.
+struct EventPair {
+    TimedLaunch tl{};
+    bool live = false;
+    ~EventPair()
+    {
+        if (live) {
+            (void)hipEventDestroy(tl.start);
+            (void)hipEventDestroy(tl.stop);
+        }
+    }
+    hipError_t begin(int backward, int tag, hipStream_t st)
+    {
+        hipError_t e = hipEventCreate(&tl.start);
+        if (e != hipSuccess) return e;
+        e = hipEventCreate(&tl.stop);
+        if (e != hipSuccess) { (void)hipEventDestroy(tl.start); return e; }
+        live = true;
+        tl.backward = backward;
+        tl.tag = tag;
+        return hipEventRecord(tl.start, st);
+    }
+    hipError_t end(hipStream_t st)
+    {
+        hipError_t e = hipEventRecord(tl.stop, st);
+        if (e != hipSuccess) return e;
+        std::lock_guard<std::mutex> lk(g_timing_mu);
+        g_timed.push_back(tl);
+        live = false;   // the reader releases them
+        return hipSuccess;
+    }
+};
+
+int timing_tag()
+{
+    std::lock_guard<std::mutex> lk(g_timing_mu);
+    return g_timing_tag;
+}
 
 int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, int dt)
 {
@@ -189,28 +229,15 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
                                ll, st));
     // band mode signs, erases and checks a kept sweep in launches of their own (the lock-step kernels do it themselves)
     if (own_tag_launch && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
-    bool timed = false;
-    TimedLaunch tl{};
-    {
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        timed = g_timing_on;
-    }
-    if (timed) {
-        SK_CHECK(hipEventCreate(&tl.start));
-        SK_CHECK(hipEventCreate(&tl.stop));
-        tl.backward = (backward && phase != 1) ? 1 : 0;   // a kept forward sweep counts as a forward launch
-        SK_CHECK(hipEventRecord(tl.start, st));
-    }
+    const int ttag = timing_tag();
+    EventPair ev;
+    if (ttag) SK_CHECK(ev.begin((backward && phase != 1) ? 1 : 0, ttag, st));   // a kept forward sweep counts as a forward launch
     if (p.band) SK_CHECK(launch_sweep_band(phase ? phase + 1 : (backward ? 1 : 0), p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
-    if (timed) {
-        SK_CHECK(hipEventRecord(tl.stop, st));
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        g_timed.push_back(tl);
-    }
+    if (ttag) SK_CHECK(ev.end(st));
     if (own_tag_launch && a.keep_tag && phase != 2) SK_CHECK(launch_keep_tag(a.keep_tag, phase == 1 ? a.keep_tag_val : 0ull, 0, a.err, st));
     if (keep_k && phase == 1)
         SK_CHECK(hipMemcpyAsync(keep_k, a.k_out, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
@@ -241,8 +268,8 @@ int run_trivial(int64_t npairs, int64_t nx, int64_t ny, int64_t L1, int64_t L2, 
 
 int check_device()
 {
-    static int state = 0;   // 0 unknown, 1 ok, -1 bad
-    if (state == 1) return SK_OK;
+    static std::atomic<int> state{0};   // 0 unknown, 1 ok (a failed check is repeated, and reported, by the next call)
+    if (state.load(std::memory_order_acquire) == 1) return SK_OK;
     int dev = 0, lds = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail(SK_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
@@ -251,7 +278,7 @@ int check_device()
     if ((size_t)lds < sk::kLdsPerCU)
         return fail(SK_ERR_HIP, "device offers %d bytes of LDS per workgroup, this library is built for %zu (gfx950)",
                     lds, sk::kLdsPerCU);
-    state = 1;
+    state.store(1, std::memory_order_release);
     return SK_OK;
 }
 
@@ -488,16 +515,22 @@ int sigkernel_mmd2(const void* X, const void* Y, void* loss, void* grad_X, void*
 int sigkernel_event_timing(int enable)
 {
     std::lock_guard<std::mutex> lk(g_timing_mu);
-    g_timing_on = enable != 0;
+    g_timing_tag = enable;
     return SK_OK;
 }
 
-int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches)
+int sigkernel_event_timing_read_tag(int tag, double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches)
 {
     std::vector<TimedLaunch> v;
     {
         std::lock_guard<std::mutex> lk(g_timing_mu);
-        v.swap(g_timed);
+        if (tag == 0) {
+            v.swap(g_timed);
+        } else {
+            std::vector<TimedLaunch> rest;
+            for (auto& t : g_timed) (t.tag == tag ? v : rest).push_back(t);
+            g_timed.swap(rest);
+        }
     }
     double ms[2] = {0.0, 0.0};
     int cnt[2] = {0, 0};
@@ -516,6 +549,11 @@ int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_m
     if (bwd_ms) *bwd_ms = ms[1];
     if (bwd_launches) *bwd_launches = cnt[1];
     return rc;
+}
+
+int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_ms, int* bwd_launches)
+{
+    return sigkernel_event_timing_read_tag(0, fwd_ms, fwd_launches, bwd_ms, bwd_launches);
 }
 
 int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
@@ -640,18 +678,9 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
     a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.PW = p.PW; a.NW = p.waves;
     a.leadlag = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
-    bool timed = false;
-    TimedLaunch tl{};
-    {
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        timed = g_timing_on;
-    }
-    if (timed) {
-        SK_CHECK(hipEventCreate(&tl.start));
-        SK_CHECK(hipEventCreate(&tl.stop));
-        tl.backward = 0;
-        SK_CHECK(hipEventRecord(tl.start, st));
-    }
+    const int ttag = timing_tag();
+    EventPair ev;
+    if (ttag) SK_CHECK(ev.begin(0, ttag, st));
     SK_CHECK(sg::launch_horner(p.DT, p.M, p.S, a, p.grid, st));
     if (p.P > 1) {
         // the signatures of the pieces, multiplied pairwise until one per path is left (Chen's identity)
@@ -664,11 +693,7 @@ int run_signature(const sg::Plan& p, const void* x, void* out, int flags, void* 
             src = dst;
         }
     }
-    if (timed) {
-        SK_CHECK(hipEventRecord(tl.stop, st));
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        g_timed.push_back(tl);
-    }
+    if (ttag) SK_CHECK(ev.end(st));
     if (!kIsDouble) SK_CHECK((sk::launch_convert<double, T>(result, static_cast<T*>(out), p.B * p.sig_len, st)));
 #undef SK_CHECK
     return SK_OK;
@@ -702,12 +727,9 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
         SK_CHECK((sk::launch_convert<T, double>(static_cast<const T*>(grad_out), g64, count, st)));
         gout64 = g64;
     }
-    bool timed = false;
-    TimedLaunch tl{};
-    {
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        timed = g_timing_on;
-    }
+    const int ttag = timing_tag();
+    const bool timed = ttag != 0;
+    EventPair ev;
     auto forward_args = [&](double* out) {
         sg::Args f;
         f.dz = dz;
@@ -722,12 +744,7 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
         // Paths cut into pieces: signatures of the pieces (level 0 of a tree), products of neighbouring pairs level by
         // level up to the whole paths, then the adjoints back down; the backward kernel then sees the pieces as paths
         // with their own signatures and upstream gradients.  Signatures the caller passed are not used.
-        if (timed) {
-            SK_CHECK(hipEventCreate(&tl.start));
-            SK_CHECK(hipEventCreate(&tl.stop));
-            tl.backward = 1;
-            SK_CHECK(hipEventRecord(tl.start, st));
-        }
+        if (timed) SK_CHECK(ev.begin(1, ttag, st));
         double* tv = reinterpret_cast<double*>(base + p.off_t0);
         double* ta = reinterpret_cast<double*>(base + p.off_t1);
         sg::Args f = forward_args(tv);
@@ -768,18 +785,9 @@ int run_signature_bwd(const sg::Plan& p, const sg::Plan& pf, const void* x, cons
     a.B = p.VB; a.n = p.Lc; a.np = p.np; a.D = p.D; a.Dpad = p.Dpad; a.N = p.N; a.Q = p.Q; a.NB = p.NB;
     a.LP = p.LP; a.WP = p.WP; a.sig_len = p.sig_len; a.lds_wave = p.lds_wave; a.PW = p.PW; a.NW = p.waves;
     a.leadlag = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
-    if (timed && p.P == 1) {
-        SK_CHECK(hipEventCreate(&tl.start));
-        SK_CHECK(hipEventCreate(&tl.stop));
-        tl.backward = 1;
-        SK_CHECK(hipEventRecord(tl.start, st));
-    }
+    if (timed && p.P == 1) SK_CHECK(ev.begin(1, ttag, st));
     SK_CHECK(sg::launch_horner_bwd(p.DT, p.M, p.S, a, p.grid, p.lds_bytes, st));
-    if (timed) {
-        SK_CHECK(hipEventRecord(tl.stop, st));
-        std::lock_guard<std::mutex> lk(g_timing_mu);
-        g_timed.push_back(tl);
-    }
+    if (timed) SK_CHECK(ev.end(st));
     SK_CHECK(sg::launch_point_gradients<T>(gz, static_cast<T*>(grad_x), p.B, p.L, p.d, p.Dpad, p.P, p.Lc, p.np,
                                            (flags & SK_FLAG_LEAD_LAG) ? 1 : 0, st));
 #undef SK_CHECK

@@ -329,8 +329,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     }
 
     // Symmetric Gram matrix: k(x, y) = k(y, x) bit for bit, so the solo and tile kernels solve the pairs n <= m
-    // only, write both entries of K, and use the sum of the two upstream gradients.
-    if (symmetric && gram && nx == ny && (p.solo || p.tile)) {
+    // only, write both entries of K, and use the sum of the two upstream gradients.  Eq. (1) is symmetric under
+    // a swap of the paths together with their dyadic orders, so this holds for equal orders only; with unequal
+    // orders K(X, X) is not a symmetric matrix and all N^2 pairs are solved over the shared increment buffer.
+    if (symmetric && gram && nx == ny && lam1 == lam2 && (p.solo || p.tile)) {
         p.tri = 1;
         p.npairs = nx * (nx + 1) / 2;
         const int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;

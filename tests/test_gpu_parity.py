@@ -455,27 +455,147 @@ def test_mmd2_entry_point(N, M, L1, L2, d, lam, flags, dtype):
     assert np.max(np.abs(host(x.grad) - 3.0 * gXr)) <= 3.0 * tol * max(1.0, gscale)
 
 
-# ------------------------------------------------------------------ full-size runs on sampled outputs
-def test_c3_full_size_sampled_entries():
+# ------------------------------------------------------------------ full-size runs: the launches bench.py times
+def check_rows(got, ref, dtype, what):
+    """Gradients of several paths, each path against its own scale (stricter than one scale per tensor)."""
+    for i in range(ref.shape[0]):
+        check_grads(got[i], ref[i], dtype, "%s [%d]" % (what, i))
+
+
+def translation_residual(g):
+    """A kernel does not change when a path is translated, so the gradients of a path's points sum to zero per
+    channel; returns the largest such sum relative to the largest gradient entry."""
+    return float(np.max(np.abs(g.sum(axis=1))) / max(1.0, np.max(np.abs(g))))
+
+
+def test_c4_full_size_all_pairs():
+    # all 32 pairs: 256 band workgroups, one per compute unit, the strips of a pair handed from workgroup to workgroup
+    # through global rows and progress counters - the launch bench.py times.  Values of every pair against the oracle;
+    # gradients of the first, a middle and the last pair (workgroups 0.., and the last of the grid) against the oracle,
+    # of every pair against translation invariance; the one-call backward and the kept-sweep pair of calls.
+    w, X, Y = workloads.make("c4")
+    B = w.n_x
+    desc = sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, w.L, w.L, w.d, w.lam, w.lam, w.flags, sk.SK_F64)
+    assert "mode=band" in desc and "grid=256" in desc
+    x, y = dev(X), dev(Y)
+    gk = workloads.upstream_weights(41, (B,))
+    kf = sk.sigkernel_fwd(x, y, w.lam, w.lam, w.flags)
+    k1, gx1, gy1 = sk.sigkernel_bwd(x, y, dev(gk), w.lam, w.lam, w.flags)
+    need = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, B, 0, w.L, w.L, w.d, w.lam, w.lam,
+                                        w.flags | sk.SK_FLAG_KEEP_FORWARD, sk.SK_F64)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    k2 = sk.sigkernel_fwd(x, y, w.lam, w.lam, w.flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+    k3, gx2, gy2 = sk.sigkernel_bwd(x, y, dev(gk), w.lam, w.lam, w.flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+    torch.cuda.synchronize()
+    print("c4: GPU calls done", flush=True)
+    kref = oracle.fwd(X, Y, w.lam, w.lam, w.flags)
+    for name, k in (("forward call", kf), ("one-call backward", k1), ("kept sweep", k2), ("backward after kept sweep", k3)):
+        check_values(host(k), kref, torch.float64, "k, all pairs, " + name)
+    sample = [0, B // 2 - 1, B - 1]
+    kr, gxr, gyr = oracle.bwd(X[sample], Y[sample], gk[sample], w.lam, w.lam, w.flags)
+    for name, gx, gy in (("one call", gx1, gy1), ("kept sweep", gx2, gy2)):
+        gx, gy = host(gx), host(gy)
+        check_rows(gx[sample], gxr, torch.float64, "grad_x, " + name)
+        check_rows(gy[sample], gyr, torch.float64, "grad_y, " + name)
+        assert np.all(np.isfinite(gx)) and np.all(np.isfinite(gy))
+        assert translation_residual(gx) <= 1e-10 and translation_residual(gy) <= 1e-10
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_c3_full_size_gram_forward_and_backward(dtype):
+    # the whole 256 x 256 Gram matrix and both gradients against the oracle (4.2e9 cells: seconds on the host), for
+    # the forward call, the one-call backward, and the pair of calls of a training step that keeps the forward sweep
     w, X, Y = workloads.make("c3")
-    K = host(sk.sigkernel_gram(dev(X), dev(Y), None, w.lam, w.lam, w.flags))
-    rng = np.random.default_rng(9)
-    ns = rng.integers(0, w.n_x, 24)
-    ms = rng.integers(0, w.n_y, 24)
-    ref = oracle.fwd(X[ns], Y[ms], w.lam, w.lam, w.flags)
-    check_values(K[ns, ms], ref, torch.float64, "K sampled")
-    assert np.all(np.isfinite(K))
+    sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    W = workloads.upstream_weights(35, (w.n_x, w.n_y))
+    Wr = rounded(W, dtype)
+    x, y, wd = dev(X, dtype), dev(Y, dtype), dev(W, dtype)
+    Kf = sk.sigkernel_gram(x, y, None, w.lam, w.lam, w.flags)
+    K1, gX1, gY1 = sk.sigkernel_gram(x, y, wd, w.lam, w.lam, w.flags)
+    KEEP, HAVE = sk.SK_FLAG_KEEP_FORWARD, sk.SK_FLAG_HAVE_FORWARD
+    need = max(sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, w.n_x, w.n_y, w.L, w.L, w.d, w.lam, w.lam, w.flags | KEEP, sdt),
+               sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM_BWD, w.n_x, w.n_y, w.L, w.L, w.d, w.lam, w.lam, w.flags | HAVE, sdt))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    K2 = sk.sigkernel_gram(x, y, None, w.lam, w.lam, w.flags | KEEP, ws=ws)
+    K3, gX2, gY2 = sk.sigkernel_gram(x, y, wd, w.lam, w.lam, w.flags | HAVE, ws=ws)
+    torch.cuda.synchronize()
+    print("c3: GPU calls done", flush=True)
+    Kref, gXr, gYr = oracle.gram(Xr, Yr, Wr, w.lam, w.lam, w.flags)
+    for name, K in (("forward call", Kf), ("one-call backward", K1), ("kept sweep", K2), ("backward after kept sweep", K3)):
+        check_values(host(K), Kref, dtype, "K, " + name)
+    for name, gX, gY in (("one call", gX1, gY1), ("kept sweep", gX2, gY2)):
+        check_rows(host(gX), gXr, dtype, "grad_X, " + name)
+        check_rows(host(gY), gYr, dtype, "grad_Y, " + name)
 
 
-def test_c5_full_size_sampled_entries():
+def test_c5_full_size_gram_sampled_rows_and_columns():
+    # 1024 x 1024 pairs, K(X, Y) and K(X, X), forward and backward as bench.py times them.  Against the oracle: sampled
+    # rows of K and grad_X (one oracle row of 1024 pairs each), sampled columns of K and grad_Y, sampled entries and
+    # rows of the total derivative of the symmetric case; on everything: finite, translation invariance, symmetry.
     w, X, Y = workloads.make("c5")
-    K = host(sk.sigkernel_gram(dev(X), dev(Y), None, w.lam, w.lam, w.flags))
-    rng = np.random.default_rng(10)
-    ns = rng.integers(0, w.n_x, 64)
-    ms = rng.integers(0, w.n_y, 64)
-    ref = oracle.fwd(X[ns], Y[ms], w.lam, w.lam, w.flags)
-    check_values(K[ns, ms], ref, torch.float64, "K sampled")
-    assert np.all(np.isfinite(K))
+    N, M = w.n_x, w.n_y
+    W = workloads.upstream_weights(51, (N, M))
+    Ws = workloads.upstream_weights(52, (N, N))
+    x, y = dev(X), dev(Y)
+    Kf = sk.sigkernel_gram(x, y, None, w.lam, w.lam, w.flags)
+    K, gX, gY = sk.sigkernel_gram(x, y, dev(W), w.lam, w.lam, w.flags)
+    Kxxf = sk.sigkernel_gram(x, x, None, w.lam, w.lam, w.flags)
+    Kxx, gXX, _ = sk.sigkernel_gram(x, x, dev(Ws), w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    print("c5: GPU calls done", flush=True)
+    assert torch.equal(Kf, K) and torch.equal(Kxxf, Kxx) and torch.equal(Kxx, Kxx.T)
+    K, gX, gY, Kxx, gXX = host(K), host(gX), host(gY), host(Kxx), host(gXX)
+    for t in (K, gX, gY, Kxx, gXX):
+        assert np.all(np.isfinite(t))
+    for g in (gX, gY, gXX):
+        assert translation_residual(g) <= 1e-10
+    rng = np.random.default_rng(12)
+    rows = [0, N - 1] + [int(v) for v in rng.integers(1, N - 1, 3)]
+    cols = [0, M - 1] + [int(v) for v in rng.integers(1, M - 1, 3)]
+    for n in rows:
+        Kr, gXr, _ = oracle.gram(X[n:n + 1], Y, W[n:n + 1], w.lam, w.lam, w.flags)
+        check_values(K[n], Kr[0], torch.float64, "K row %d" % n)
+        check_grads(gX[n], gXr[0], torch.float64, "grad_X row %d" % n)
+    for m in cols:
+        Kr, _, gYr = oracle.gram(X, Y[m:m + 1], W[:, m:m + 1], w.lam, w.lam, w.flags)
+        check_values(K[:, m], Kr[:, 0], torch.float64, "K column %d" % m)
+        check_grads(gY[m], gYr[0], torch.float64, "grad_Y row %d" % m)
+    # K(X, X): rows of K and of the total derivative (path n appears as the first argument in row n of K and as the
+    # second argument in column n)
+    for n in rows[:4]:
+        Kr, g1, _ = oracle.gram(X[n:n + 1], X, Ws[n:n + 1], w.lam, w.lam, w.flags)
+        _, _, g2 = oracle.gram(X, X[n:n + 1], Ws[:, n:n + 1], w.lam, w.lam, w.flags)
+        check_values(Kxx[n], Kr[0], torch.float64, "K(X,X) row %d" % n)
+        check_grads(gXX[n], g1[0] + g2[0], torch.float64, "total derivative of K(X,X), row %d" % n)
+    assert np.all(np.diag(Kxx) > 0.0)
+
+
+def test_symmetric_gram_with_unequal_dyadic_orders():
+    # k with orders (l1, l2) of (y, x) equals k with orders (l2, l1) of (x, y), not k with (l1, l2): for unequal orders
+    # K(X, X) is not a symmetric matrix and every pair has to be solved (solo kernels, shared increment buffer)
+    N, L, d, lam1, lam2 = 300, 20, 3, 0, 1
+    assert "mode=solo" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, N, N, L, L, d, lam1, lam2, 0, sk.SK_F64)
+    X = rand_paths(8700, N, L, d, 0.25)
+    W = workloads.upstream_weights(87, (N, N))
+    x = dev(X)
+    Kf = sk.sigkernel_gram(x, x, None, lam1, lam2, 0)
+    K, gX, none = sk.sigkernel_gram(x, x, dev(W), lam1, lam2, 0)
+    torch.cuda.synchronize()
+    Kr, gXr, _ = oracle.gram(X, X, W, lam1, lam2, 0)
+    assert none is None
+    assert np.max(np.abs(Kr - Kr.T)) > 1e-6        # what the test is about
+    check_values(host(Kf), Kr, torch.float64, "K(X,X), orders (0,1), forward only")
+    check_values(host(K), Kr, torch.float64, "K(X,X), orders (0,1)")
+    check_grads(host(gX), gXr, torch.float64, "total derivative, orders (0,1)")
+    # and through the squared MMD, whose symmetric blocks use one order each: (l1, l1) and (l2, l2)
+    Y = rand_paths(8701, 40, L, d, 0.25)
+    loss, gX2, gY2 = sk.sigkernel_mmd2(dev(X[:50]), dev(Y), lam1, lam2, 0)
+    torch.cuda.synchronize()
+    ref, gXr2, gYr2 = oracle.mmd2(X[:50], Y, lam1, lam2, 0)
+    assert abs(float(loss[0]) - ref) <= 1e-10
+    check_grads(host(gX2), gXr2, torch.float64, "mmd2 grad_X, orders (0,1)")
+    check_grads(host(gY2), gYr2, torch.float64, "mmd2 grad_Y, orders (0,1)")
 
 
 # ------------------------------------------------------------------ shapes, orders, channels, edges
