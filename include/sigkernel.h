@@ -130,6 +130,24 @@ int sigkernel_bwd(const void* x, const void* y, const void* grad_k, void* grad_x
                   void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * sigkernel_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc) and have no workspace to hand in: the same operation, arguments and results as
+ * sigkernel_bwd, with the scratch taken from an array of SK_STATIC_SCRATCH_BYTES bytes that is part of the library
+ * (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ *  - Shapes whose sigkernel_workspace_bytes(SK_OP_BWD, ...) exceeds SK_STATIC_SCRATCH_BYTES are refused with
+ *    SK_ERR_WORKSPACE (configuration-2-sized batches fit: 128 pairs of 256 points at dyadic order 1).
+ *  - SK_FLAG_KEEP_FORWARD / SK_FLAG_HAVE_FORWARD are refused (SK_ERR_DTYPE): the scratch belongs to no caller.
+ *  - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race.
+ *    Calls on one stream are ordered and safe; each call clears what it needs cleared.
+ *  - The first call on a device looks the array's address up (hipGetSymbolAddress); make that call, like the first
+ *    call of any kernel, outside a stream capture.
+ */
+#define SK_STATIC_SCRATCH_BYTES (64u << 20)
+int sigkernel_bwd_static(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y, void* k_out,
+                         int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2, int flags, sk_dtype dt,
+                         void* stream);
+
+/*
  * Gram matrix (the N x M product set of Eq. (1) solves): X[N,L1,d], Y[M,L2,d] -> K[N,M] = k(X[n], Y[m]).
  * If grad_K[N,M] = dF/dK is not NULL, also
  *   grad_X[n] = sum_m grad_K[n,m] dk(X[n],Y[m])/dX[n],   grad_Y[m] = sum_n grad_K[n,m] dk(X[n],Y[m])/dY[m]

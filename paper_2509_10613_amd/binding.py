@@ -39,7 +39,8 @@ def SK_SIG_DEPTH(m):
     return (m + 1) << 8
 
 
-EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_gram", "sigkernel_describe",
+EXPORTS = ["sigkernel_workspace_bytes", "sigkernel_fwd", "sigkernel_bwd", "sigkernel_bwd_static", "sigkernel_gram",
+           "sigkernel_describe",
            "sigkernel_mmd2", "sigkernel_mmd2_workspace_bytes",
            "sigkernel_event_timing", "sigkernel_event_timing_read", "sigkernel_event_timing_read_tag", "sigkernel_last_error", "sigkernel_version",
            "signature_length", "signature_workspace_bytes", "signature_fwd", "signature_describe",
@@ -71,6 +72,8 @@ def load():
     lib.sigkernel_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t, vp]
     lib.sigkernel_bwd.restype = ci
     lib.sigkernel_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t, vp]
+    lib.sigkernel_bwd_static.restype = ci
+    lib.sigkernel_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, vp]
     lib.sigkernel_gram.restype = ci
     lib.sigkernel_gram.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, C.c_size_t,
                                    vp]
@@ -223,6 +226,20 @@ def sigkernel_bwd(x, y, grad_k, lam1=0, lam2=0, flags=0, grad_x=None, grad_y=Non
         ws = workspace(need, x.device)
     _check(load().sigkernel_bwd(_ptr(x), _ptr(y), _ptr(grad_k), _ptr(grad_x), _ptr(grad_y), _ptr(k_out), B, L1, L2,
                                 d, lam1, lam2, flags, dt, _ptr(ws), ws.numel(), _stream()))
+    return k_out, grad_x, grad_y
+
+
+SK_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def sigkernel_bwd_static(x, y, grad_k, grad_x, grad_y, k_out, lam1=0, lam2=0, flags=0):
+    """sigkernel_bwd with the library's own per-device scratch: the caller passes every output, nothing is allocated."""
+    _dev(x, "x"); _dev(y, "y"); _dev(grad_k, "grad_k")
+    B, L1, d = x.shape
+    L2 = y.shape[1]
+    assert y.shape[0] == B and y.shape[2] == d and y.dtype == x.dtype and grad_k.dtype == x.dtype
+    _check(load().sigkernel_bwd_static(_ptr(x), _ptr(y), _ptr(grad_k), _ptr(grad_x), _ptr(grad_y), _ptr(k_out), B, L1,
+                                       L2, d, lam1, lam2, flags, _dt(x), _stream()))
     return k_out, grad_x, grad_y
 
 

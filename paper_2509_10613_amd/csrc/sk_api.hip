@@ -395,6 +395,61 @@ int sigkernel_gram(const void* X, const void* Y, void* K, const void* grad_K, vo
 
 }  // extern "C"
 
+// ---------------------------------------------------------------- sigkernel_bwd without a caller's workspace
+// Scratch of sigkernel_bwd_static: one array per GPU, part of the library's code object, alive until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels are given the address that
+// call returns for the device in use.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)SK_STATIC_SCRATCH_BYTES;
+}
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};   // per device: the address of that device's copy of the array
+
+int static_scratch(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SK_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SK_ERR_HIP, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));   // with device `dev` current: that device's copy
+        if (e != hipSuccess || !ptr)
+            return fail(SK_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SK_OK;
+}
+}  // namespace
+
+extern "C" int sigkernel_bwd_static(const void* x, const void* y, const void* grad_k, void* grad_x, void* grad_y,
+                                    void* k_out, int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,
+                                    int flags, sk_dtype dt, void* stream)
+{
+    if (flags & (SK_FLAG_KEEP_FORWARD | SK_FLAG_HAVE_FORWARD))
+        return fail(SK_ERR_DTYPE, "SK_FLAG_KEEP_FORWARD / SK_FLAG_HAVE_FORWARD do not apply to sigkernel_bwd_static "
+                    "(its scratch is shared by every call on the device)");
+    int rc = validate(B, B, L1, L2, d, lam1, lam2, flags, (int)dt);
+    if (rc != SK_OK) return rc;
+    const size_t need = B > 0 ? sigkernel_workspace_bytes(SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, dt) : 0;
+    if (need > kStaticScratchBytes)
+        return fail(SK_ERR_WORKSPACE, "this shape needs %zu bytes of scratch, sigkernel_bwd_static holds %zu per device; "
+                    "use sigkernel_bwd with a workspace of the caller's", need, kStaticScratchBytes);
+    void* ptr = nullptr;
+    rc = static_scratch(&ptr);
+    if (rc != SK_OK) return rc;
+    // The preparation launch of every call clears the accumulators, the error flag and the counters it uses, and a
+    // call that sweeps forward itself erases the signature of a kept sweep: nothing of the previous call's contents
+    // is read before it is written.
+    return dispatch(true, false, x, y, k_out, grad_k, grad_x, grad_y, B, B, L1, L2, d, lam1, lam2, flags, dt, ptr,
+                    kStaticScratchBytes, stream);
+}
+
 // Layout of the scratch of sigkernel_mmd2: the three Gram matrices, their constant upstream weights, the second
 // halves of the two gradients (all in the caller's element type), then the scratch of the Gram calls.
 namespace {

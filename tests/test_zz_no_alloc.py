@@ -1,0 +1,109 @@
+"""sigkernel_bwd_static: the backward entry point that takes its scratch from the library's own per-device array
+(for callers that cannot allocate).  Same results as sigkernel_bwd, which is checked against the oracle here too;
+two calls in a row, the second with a smaller input (the array keeps the first call's contents)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_10613_amd import binding as sk
+from paper_2509_10613_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-10
+
+
+def dev(a, dtype=torch.float64):
+    return torch.tensor(np.asarray(a), dtype=dtype, device="cuda")
+
+
+def host(t):
+    return t.detach().cpu().numpy().astype(np.float64)
+
+
+def paths(seed, B, L, d):
+    """Brownian-like paths of unit quadratic variation."""
+    return np.cumsum(np.random.default_rng(seed).normal(0, (1.0 / (d * L)) ** 0.5, size=(B, L, d)), axis=1)
+
+
+def close(a, b, tol=TOL):
+    a, b = host(a), host(b) if torch.is_tensor(b) else b
+    return np.all(np.isfinite(a)) and np.max(np.abs(a - b)) <= tol * max(1.0, np.max(np.abs(b)))
+
+
+def one_call(B, L1, L2, d, lam, flags, seed, dtype=torch.float64):
+    X, Y = paths(seed, B, L1, d), paths(seed + 1, B, L2, d)
+    gk = workloads.upstream_weights(seed + 2, (B,))
+    x, y, g = dev(X, dtype), dev(Y, dtype), dev(gk, dtype)
+    k0, gx0, gy0 = sk.sigkernel_bwd(x, y, g, lam, lam, flags)              # the existing entry point
+    k1, gx1, gy1 = torch.empty_like(k0), torch.empty_like(gx0), torch.empty_like(gy0)
+    for t in (k1, gx1, gy1):
+        t.fill_(float("nan"))
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    sk.sigkernel_bwd_static(x, y, g, gx1, gy1, k1, lam, lam, flags)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    tol = TOL if dtype == torch.float64 else 1e-4
+    assert close(k1, k0, tol) and close(gx1, gx0, tol) and close(gy1, gy0, tol)
+    kr, gxr, gyr = oracle.bwd(host(x), host(y), host(g), lam, lam, flags)
+    assert close(k1, kr, tol) and close(gx1, gxr, tol) and close(gy1, gyr, tol)
+    return k1, gx1, gy1
+
+
+def test_static_scratch_matches_the_workspace_entry_point_twice_in_a_row():
+    # c2's shape cut down (lock-step kernels), then a smaller batch of shorter paths on the same device array
+    one_call(24, 128, 128, 5, 1, sk.SK_FLAG_TIME_AUG, 9100)
+    one_call(6, 40, 33, 5, 1, sk.SK_FLAG_TIME_AUG, 9200)
+    # other launch modes on the same array: many short pairs (solo and tile kernels, gradient sums in atomics), float arrays,
+    # long paths (band kernels: progress counters in the scratch), and the first shape once more
+    one_call(2500, 6, 7, 2, 0, 0, 9300)
+    one_call(1300, 40, 40, 16, 0, 0, 9350)      # tile kernels
+    one_call(300, 30, 20, 2, 0, 0, 9400, torch.float32)
+    one_call(3, 400, 330, 3, 0, 0, 9500)
+    one_call(24, 128, 128, 5, 1, sk.SK_FLAG_TIME_AUG, 9100)
+
+
+def test_static_scratch_full_c2():
+    w, X, Y = workloads.make("c2")
+    assert sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, w.n_x, 0, w.L, w.L, w.d, w.lam, w.lam, w.flags,
+                                        sk.SK_F64) <= sk.SK_STATIC_SCRATCH_BYTES
+    x, y = dev(X), dev(Y)
+    gk = workloads.upstream_weights(9, (w.n_x,))
+    k0, gx0, gy0 = sk.sigkernel_bwd(x, y, dev(gk), w.lam, w.lam, w.flags)
+    k1, gx1, gy1 = torch.empty_like(k0), torch.empty_like(gx0), torch.empty_like(gy0)
+    sk.sigkernel_bwd_static(x, y, dev(gk), gx1, gy1, k1, w.lam, w.lam, w.flags)
+    torch.cuda.synchronize()
+    assert torch.equal(k1, k0) and torch.equal(gx1, gx0) and torch.equal(gy1, gy0)   # lock-step: sums in a fixed order
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, w.lam, w.lam, w.flags)
+    assert close(k1, kr) and close(gx1, gxr) and close(gy1, gyr)
+
+
+def test_static_scratch_limits_and_degenerate_shapes():
+    w, X, Y = workloads.make("c4", n_x=2, n_y=2)
+    x, y = dev(X), dev(Y)
+    g = torch.ones(2, dtype=torch.float64, device="cuda")
+    k, gx, gy = torch.empty_like(g), torch.empty_like(x), torch.empty_like(y)
+    assert sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, 2, 0, w.L, w.L, w.d, w.lam, w.lam, 0, sk.SK_F64) > sk.SK_STATIC_SCRATCH_BYTES
+    with pytest.raises(sk.SigKernelError, match="sigkernel_bwd_static holds"):
+        sk.sigkernel_bwd_static(x, y, g, gx, gy, k, w.lam, w.lam, 0)
+    xs, ys = dev(paths(1, 2, 9, 2)), dev(paths(2, 2, 7, 2))
+    ks, gxs, gys = torch.empty_like(g), torch.empty_like(xs), torch.empty_like(ys)
+    for flag in (sk.SK_FLAG_KEEP_FORWARD, sk.SK_FLAG_HAVE_FORWARD):
+        with pytest.raises(sk.SigKernelError):
+            sk.sigkernel_bwd_static(xs, ys, g, gxs, gys, ks, 1, 1, flag)
+    # only one gradient wanted, no k_out
+    k0, gx0, gy0 = sk.sigkernel_bwd(xs, ys, g, 1, 1, 0)
+    sk.sigkernel_bwd_static(xs, ys, g, gxs, None, None, 1, 1, 0)
+    torch.cuda.synchronize()
+    assert close(gxs, gx0)
+    # a path of one point: k = 1, zero gradients; an empty batch: a no-op
+    x1 = dev(paths(3, 2, 1, 2))
+    gx1 = torch.empty_like(x1)
+    sk.sigkernel_bwd_static(x1, ys, g, gx1, gys, ks, 0, 0, 0)
+    torch.cuda.synchronize()
+    assert torch.all(ks == 1.0) and torch.all(gx1 == 0.0) and torch.all(gys == 0.0)
+    e = torch.empty((0, 4, 2), dtype=torch.float64, device="cuda")
+    sk.sigkernel_bwd_static(e, e, torch.empty(0, dtype=torch.float64, device="cuda"), torch.empty_like(e),
+                            torch.empty_like(e), torch.empty(0, dtype=torch.float64, device="cuda"), 1, 1, 0)
