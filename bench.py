@@ -146,10 +146,21 @@ def copy_calibration(args, torch, dev):
 class Part:
     """One forward call + one backward call on the same paths: a pair batch, or one Gram matrix of a step."""
 
-    def __init__(self, tag, label, fwd, bwd, pairs, pairs_solved, desc_fwd, desc_bwd):
+    def __init__(self, tag, label, fwd, bwd, pairs, pairs_solved, desc_fwd, desc_bwd, ws):
         self.tag, self.label, self.fwd, self.bwd = tag, label, fwd, bwd
         self.pairs, self.pairs_solved = pairs, pairs_solved
         self.desc_fwd, self.desc_bwd = desc_fwd, desc_bwd
+        self.ws = ws
+
+    def pairs_solved_twice(self):
+        """Pairs the last backward call handed to the replay kernel because the inverse recurrence drifted (the
+        launch description says where in the workspace the call counts them): 0 means the timed path was the fast one."""
+        import torch
+        if not self.bwd or "drifted_pairs_counter_at=" not in self.desc_bwd:
+            return None
+        at = int(self.desc_bwd.split("drifted_pairs_counter_at=", 1)[1].split()[0])
+        torch.cuda.synchronize()
+        return int(self.ws[at:at + 4].view(torch.int32)[0])
 
 
 def make_case(name, io, args, sk, workloads, torch, dev):
@@ -212,7 +223,7 @@ def make_case(name, io, args, sk, workloads, torch, dev):
             solved = N * (N + 1) // 2 if sym else N * M
             parts.append(Part(tag, label, fwd, bwd, N * M, solved,
                               sk.sigkernel_describe(sk.SK_OP_GRAM, N, M, w.L, w.L, w.d, lam, lam, flags | keep, sdt),
-                              sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, N, M, w.L, w.L, w.d, lam, lam, flags | have, sdt)))
+                              sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, N, M, w.L, w.L, w.d, lam, lam, flags | have, sdt), ws))
 
             def check(label=label, Xa=Xa, Ya=Ya, Wr=Wr, K=K, K2=K2, gX=gX, gY=gY, sym=sym, N=N, M=M):
                 # sampled rows (and columns) of the Gram matrix and of its gradients: one oracle row of M pairs each
@@ -258,7 +269,7 @@ def make_case(name, io, args, sk, workloads, torch, dev):
 
         parts.append(Part(1, "pairs", fwd, bwd if w.backward else None, B, B,
                           sk.sigkernel_describe(sk.SK_OP_FWD, B, 0, w.L, w.L, w.d, lam, lam, flags | keep, sdt),
-                          sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, w.L, w.L, w.d, lam, lam, flags | have, sdt)))
+                          sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, w.L, w.L, w.d, lam, lam, flags | have, sdt), ws))
 
         def check():
             import oracle
@@ -334,7 +345,8 @@ def run_case(case, args, sk, torch):
                "fwd_kernel": kernel_name(p.desc_fwd), "fwd_kernel_ms": f_ms / max(nf, 1),
                "fwd_flops": cells_launch * algorithmic_flops_per_cell(d_eff, ta, w.lam, False)}
         if p.bwd:
-            rec.update({"bwd_kernel": kernel_name(p.desc_bwd), "bwd_kernel_ms": b_ms / max(nb, 1),
+            rec.update({"pairs_solved_twice": p.pairs_solved_twice(),
+                        "bwd_kernel": kernel_name(p.desc_bwd), "bwd_kernel_ms": b_ms / max(nb, 1),
                         "bwd_flops": cells_launch * algorithmic_flops_per_cell(d_eff, ta, w.lam, True)})
         launches.append(rec)
     # roofline of the dominant kernel (the backward sweep when there is one), over all its launches of a step:

@@ -100,11 +100,16 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  *   grad_x[B,L1,d] = dF/dx,  grad_y[B,L2,d] = dF/dy   (either may be NULL = not wanted)
  * and, if k_out != NULL, k_out[B] = k(x[b], y[b]) (the forward values are recomputed inside).
  * By default the reverse sweep recovers the forward values it needs by inverting Eq. (1) between exact
- * checkpoints eight block steps apart, and checks the recovered state against every checkpoint: if they
- * differ by more than 1e-9 of the largest forward value met along the row (increment inner products of
- * order one make the inverse recurrence ill-conditioned), the gradients of that pair - or, depending on the
- * launch mode, every gradient of the call - are returned as NaN, never as inaccurate numbers.
- * SK_FLAG_BWD_REPLAY selects the slower variant that replays forward segments and has no such limit.
+ * checkpoints eight block steps apart (24 in one launch mode), and checks the recovered state against every
+ * checkpoint and, at the left end of the grid, against the boundary value 1.  Increment inner products of order one
+ * make the inverse recurrence ill-conditioned (it divides by B(p)): where the recovered state differs from the exact
+ * one by more than 1e-11 of the largest forward value met along the row, the pair is left out of the gradient sums
+ * and solved once more, in the same call, by the variant that replays forward segments, which has no such limit.
+ * The gradients are therefore the exact ones of the scheme for any input (Section 3.4); such pairs only cost more
+ * time (a few launch modes cannot tell which pair drifted and then solve every pair of the call again).
+ * SK_FLAG_BWD_REPLAY selects the replaying variant for the whole call from the start: the choice for data sets
+ * whose increments are large throughout.  sigkernel_describe says where in the workspace the call counts the
+ * pairs it solved twice.
  *
  * A forward sweep that was kept (sigkernel_fwd then sigkernel_bwd; sigkernel_gram without, then with grad_K).
  * A training step makes the forward call and then the backward call on the same paths; the backward call then need

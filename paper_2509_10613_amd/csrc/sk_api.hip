@@ -96,15 +96,41 @@ int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1
     return SK_OK;
 }
 
+// The scratch of a call: the launch plan's, then (backward calls whose reverse sweep inverts Eq. (1)) that of the
+// launch that solves drifted pairs once more with the replay kernel.
+struct Layout {
+    sk::Plan p;
+    sk::Plan sc;          // the second launch (valid only if has_sc)
+    bool has_sc = false;
+    size_t off_sc = 0;
+    size_t total = 0;
+};
+
+Layout make_layout(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d,
+                   int lam1, int lam2, int io_elem, bool uncompute, bool keep = false)
+{
+    Layout l;
+    l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, uncompute, keep);
+    l.total = l.p.total;
+    if (l.p.valid && backward && l.p.uncompute) {
+        l.sc = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, false, false, true);
+        l.has_sc = l.sc.valid;
+        l.off_sc = l.p.total;
+        l.total = l.p.total + l.sc.total;
+    }
+    return l;
+}
+
 // T is the element type of the caller's arrays.  The sweeps run in double whatever T is: non-packed
 // single-precision vector instructions issue at the same rate as double ones on this chip, and the
 // recurrence of Eq. (1) in single precision loses the low bits of p when forming 1 + p/2 + ..., an error
 // that grows linearly with the number of cells.  Float callers get float storage at the edges only.
 template <typename T>
-int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
+int run(const Layout& lay, bool backward, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
         void* grad_y, int lam1, int lam2, int flags, void* ws, hipStream_t st, int phase = 0)
 {
     using namespace sk;
+    const Plan& p = lay.p;
     constexpr bool kIsDouble = sizeof(T) == 8;
     unsigned char* base = static_cast<unsigned char*>(ws);
     double* dxT = reinterpret_cast<double*>(base + p.off_dxT);
@@ -177,6 +203,11 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
         a.ckpt_slot = p.ckpt_slot;
     }
     a.err = reinterpret_cast<int*>(base + p.off_err);
+    a.lk_off_gyp = (unsigned)p.lk_off_gyp;
+    if (p.off_badlist != 0) {
+        a.bad_count = reinterpret_cast<int*>(base + p.off_badcnt);
+        a.bad_list = reinterpret_cast<long long*>(base + p.off_badlist);
+    }
     // Lock-step mode on a batch of pairs of double paths works on the caller's arrays directly.
     // Lead-lag transform (Section 4): the plan was made for the transformed paths (2L - 1 points, 2d channels);
     // only the preparation and the finalisation know the caller's shape.
@@ -225,8 +256,10 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
                                p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
                                (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, cL2, p.qpad, cd,
                                p.DP, phase == 2 ? a.bd_flags + p.nflags / 2 : a.err,
-                               phase == 2 ? p.nflags / 2 : 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags,
-                               ll, st));
+                               phase == 2 ? p.nflags / 2 + 1 : 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags,
+                               ll, st));   // (both ranges end with the counter of drifted pairs, the int behind the flags)
+    // the calls that work on the caller's arrays have no preparation launch: their counter of drifted pairs
+    if (fused && backward && phase != 1 && a.bad_count) SK_CHECK(launch_fill<int>(a.bad_count, 1, 0, st));
     // band mode signs, erases and checks a kept sweep in launches of their own (the lock-step kernels do it themselves)
     if (own_tag_launch && phase == 2) SK_CHECK(launch_keep_tag(a.keep_tag, a.keep_tag_val, 1, a.err, st));
     const int ttag = timing_tag();
@@ -238,6 +271,35 @@ int run(const sk::Plan& p, bool backward, const void* x, const void* y, void* k,
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     if (ttag) SK_CHECK(ev.end(st));
+    // Pairs whose inverse recurrence drifted were left out of the gradient sums and listed: the replay kernel solves
+    // them once more (an empty list ends that launch at once).  Launch modes that cannot tell which pairs drifted
+    // raise the flag instead; then the sums are cleared and every pair is solved again.
+    if (backward && phase != 1 && lay.has_sc && a.bad_count) {
+        const Plan& q = lay.sc;
+        unsigned char* sbase = base + lay.off_sc;
+        SweepArgs b = a;
+        b.second_chance = fused ? 2 : 1;
+        b.npairs = p.kcount;
+        b.tri = 0;
+        b.rows = reinterpret_cast<double*>(sbase + q.off_rows);
+        b.rows_slot = q.rows_slot;
+        b.rowlen = q.rowlen;
+        b.adj = reinterpret_cast<double*>(sbase + q.off_adj);
+        b.adj_slot = q.adj_slot;
+        b.ckpt = reinterpret_cast<double*>(sbase + q.off_ckpt);
+        b.ckpt_slot = q.ckpt_slot;
+        b.ns = q.ns; b.S = q.S; b.nseg = q.nseg;
+        b.y_lds = q.y_lds;
+        b.lds_wave = (unsigned)q.lds_wave;
+        b.ring_off = (unsigned)q.ring_off;
+        b.coop = 0; b.uncompute = 0; b.lock = 0; b.solo = 0; b.tile = 0; b.band = 0;
+        b.lk_phase = 0; b.keep_tag = nullptr;
+        if (!(p.lock || p.solo || p.tile))
+            SK_CHECK(launch_second_chance_reset(a.want_gx ? a.gdx : nullptr, (long)(p.nx * p.xstride),
+                                                (a.want_gy && !p.symmetric) ? a.gdy : nullptr,
+                                                (long)(p.ny * p.ystride), a.err, st));
+        SK_CHECK(launch_sweep(true, q.BL, q.DT, b, q.grid, q.lds_bytes, st));
+    }
     if (own_tag_launch && a.keep_tag && phase != 2) SK_CHECK(launch_keep_tag(a.keep_tag, phase == 1 ? a.keep_tag_val : 0ull, 0, a.err, st));
     if (keep_k && phase == 1)
         SK_CHECK(hipMemcpyAsync(keep_k, a.k_out, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
@@ -316,36 +378,36 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     rc = check_device();
     if (rc != SK_OK) return rc;
     if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }   // shape of the transformed paths
-    sk::Plan p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
-                               !(flags & SK_FLAG_BWD_REPLAY));
-    if (!p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
+    Layout lay = make_layout(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
+                             !(flags & SK_FLAG_BWD_REPLAY));
+    if (!lay.p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0)
         return fail(SK_ERR_WORKSPACE, "workspace pointer is NULL or not 256-byte aligned");
     // A forward sweep kept for the backward call: the launch modes that have the two halves of the backward call as
     // launches of their own run the first half here and the second half there; the others ignore both flags.
     int phase = 0;
     if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
-        const sk::Plan pb = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
-                                          !(flags & SK_FLAG_BWD_REPLAY), true);
-        if (!pb.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
-        if (ws_bytes < pb.total)
+        const Layout lb = make_layout(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
+                                      !(flags & SK_FLAG_BWD_REPLAY), true);
+        if (!lb.p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
+        if (ws_bytes < lb.total)
             return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed (a kept forward sweep: the backward call's, "
-                        "asked for with the flag)", ws_bytes, pb.total);
-        if (split_forward(pb, dt, flags)) {
+                        "asked for with the flag)", ws_bytes, lb.total);
+        if (split_forward(lb.p, dt, flags)) {
             phase = backward ? 2 : 1;
-            p = pb;
+            lay = lb;
         }
     }
-    if (ws_bytes < p.total)
-        return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, p.total);
+    if (ws_bytes < lay.total)
+        return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, lay.total);
     if (phase != 0) {
         if (phase == 1) { grad_k = nullptr; grad_x = nullptr; grad_y = nullptr; }
-        if (dt == SK_F64) return run<double>(p, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, phase);
-        return run<float>(p, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, phase);
+        if (dt == SK_F64) return run<double>(lay, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, phase);
+        return run<float>(lay, true, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st, phase);
     }
     if (dt == SK_F64)
-        return run<double>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
-    return run<float>(p, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
+        return run<double>(lay, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
+    return run<float>(lay, backward, x, y, k, grad_k, grad_x, grad_y, lam1, lam2, flags, ws, st);
 }
 
 }  // namespace
@@ -365,9 +427,9 @@ size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, 
     if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
     if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
     // The symmetric Gram case needs no more than the general one, so the query does not distinguish them.
-    sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
-                               !(flags & SK_FLAG_BWD_REPLAY), kept);
-    return p.valid ? p.total : 0;
+    const Layout l = make_layout(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+                                 !(flags & SK_FLAG_BWD_REPLAY), kept);
+    return l.p.valid ? l.total : 0;
 }
 
 int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, int64_t L2, int64_t d, int lam1,
@@ -623,24 +685,25 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     int rc = validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt);
     if (rc != SK_OK) return rc;
     if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
-    sk::Plan p = sk::make_plan(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
-                               !(flags & SK_FLAG_BWD_REPLAY));
-    if (!p.valid) {
+    Layout lay = make_layout(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+                             !(flags & SK_FLAG_BWD_REPLAY));
+    if (!lay.p.valid) {
         std::snprintf(out, out_bytes, "mode=trivial (no cells to sweep)");
         return SK_OK;
     }
     // a kept forward sweep: the two halves of the backward call, where the launch mode has them
     int phase = 0;
     if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
-        const sk::Plan pb = sk::make_plan(true, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
-                                          !(flags & SK_FLAG_BWD_REPLAY), true);
-        if (pb.valid && split_forward(pb, dt, flags)) {
+        const Layout lb = make_layout(true, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+                                      !(flags & SK_FLAG_BWD_REPLAY), true);
+        if (lb.p.valid && split_forward(lb.p, dt, flags)) {
             phase = backward ? 2 : 1;
-            p = pb;
-        } else if (pb.valid) {
-            p.total = pb.total > p.total ? pb.total : p.total;   // the caller still brings the backward call's workspace
+            lay = lb;
+        } else if (lb.p.valid) {
+            lay.total = lb.total > lay.total ? lb.total : lay.total;   // the caller still brings the backward call's workspace
         }
     }
+    const sk::Plan& p = lay.p;
     char kern[96];
     int threads;
     const char* mode;
@@ -678,10 +741,10 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     const bool fused = p.lock && !gram && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG);
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
-                  "workspace_bytes=%zu",
+                  "workspace_bytes=%zu drifted_pairs_counter_at=%zu",
                   mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
                   (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
-                  fused ? 1 : 0, p.total);
+                  fused ? 1 : 0, lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
     return SK_OK;
 }
 

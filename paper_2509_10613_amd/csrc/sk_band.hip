@@ -451,7 +451,7 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(
                     if (rc > 0) {
 #pragma unroll
                         for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
-                            if (!(fabs(rv.kR[i] - cv[i]) <= 1e-9 * kscale)) drift = true;
+                            if (!(fabs(rv.kR[i] - cv[i]) <= kDriftTol * kscale)) drift = true;
                     }
 #pragma unroll
                     for (int i = 0; i <= RR; ++i) rv.kR[i] = cv[i];
@@ -464,7 +464,13 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(
             band_barrier();
         }
         if (active) {
-            if (drift) atomicExch(a.err, 2);
+            // the left end: every strip started from the boundary value 1 in every lane
+#pragma unroll
+            for (int i = 0; i <= RR; ++i)
+                if (!(fabs(rv.kR[i] - 1.0) <= kDriftTol * kscale)) drift = true;
+            // the sums of a pair are spread over workgroups and already on their way: every pair of the call is then
+            // solved once more by the replay kernel
+            if (drift) atomicCAS(a.err, 0, 2);   // (an error already raised stays)
             if (a.want_gx) {
                 const int I = sg * kWave + lane - a.lk_padb;
                 if (I >= 0) {

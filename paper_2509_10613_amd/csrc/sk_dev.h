@@ -120,6 +120,15 @@ __device__ __forceinline__ real gram_weight(const SweepArgs& a, long pid, long p
     return pid2 != pid ? g + a.grad_k[pid2] : g;
 }
 
+// Called by one lane: the pair's inverse recurrence drifted, list it for the replay kernel.
+__device__ __forceinline__ void list_drifted(const SweepArgs& a, long pid, long pid2)
+{
+    const int n = pid2 != pid ? 2 : 1;
+    const int at = atomicAdd(a.bad_count, n);
+    a.bad_list[at] = pid;
+    if (n == 2) a.bad_list[at + 1] = pid2;
+}
+
 __device__ __forceinline__ void pair_ids(const SweepArgs& a, long pid, long& xi, long& yi)
 {
     xi = a.gramM ? pid / a.gramM : pid;

@@ -57,6 +57,7 @@ struct SweepArgs {
     unsigned lk_off_y, lk_off_gy, lk_off_cring, lk_off_gp, lk_off_krows, lk_off_arows, lk_off_dump;   // LDS bytes
     unsigned lk_cring_stride, lk_gp_stride;   // LDS bytes per strip
     unsigned lk_off_ck, lk_ck_stride;         // checkpoint staging (backward)
+    unsigned lk_off_gyp;                      // solo kernels, backward: y-side gradient sums of the pair in work
     int solo;            // 1: solo kernels (one wave per pair, a single strip of 64 * lk_M block rows; uses lk_M,
                          // lk_NT, lk_padb and, as offsets inside a wave's LDS, lk_off_gy / lk_off_krows / lk_off_dump)
     int band;            // 1: band kernels (a pair's strips spread over bd_nbands workgroups; uses lk_ns, lk_NT, lk_padb)
@@ -84,7 +85,17 @@ struct SweepArgs {
     // (a mismatch gives NaN gradients), and a backward call that sweeps forward itself erases the signature.
     unsigned long long* keep_tag;
     unsigned long long keep_tag_val;
-    int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted
+    int* err;            // device int: 1 = a bounded wait between waves ran out, 2 = the un-compute drifted in a
+                         // launch mode that cannot tell which pair (every pair is then solved once more), 3 = the
+                         // workspace does not hold the forward sweep the call was told to take over
+    // Pairs whose inverse recurrence drifted (solo, tile and lock-step kernels): the reverse sweep adds nothing to
+    // the gradients for them and lists them here; the replay kernel then solves the listed pairs (sk_api.hip).
+    long long* bad_list; // [kcount] pair ids (a pair of a symmetric Gram matrix is listed as (n, m) and (m, n))
+    int* bad_count;      // entries of bad_list, zero at launch
+    // the replay kernel as that second launch: 0 = an ordinary backward call over all pairs; 1 = the listed pairs
+    // (all pairs if *err == 2); 2 = the listed pairs of a call that works on the caller's arrays: the wave forms the
+    // pair's increments, clears its accumulators and differences them into the caller's gradients itself
+    int second_chance;
 };
 
 template <typename T> hipError_t launch_fill(T* p, long n, T v, hipStream_t st);
@@ -106,6 +117,8 @@ template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
                            int L2, int qpad, int d, int DS, const int* err, int ll, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
+// clears the n doubles at g1 and at g2 (either may be null) if *err == 2: every pair is about to be solved once more
+hipError_t launch_second_chance_reset(real* g1, long n1, real* g2, long n2, const int* err, hipStream_t st);
 // solo mode (a.solo != 0), defined in sk_solo.hip
 hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // tile mode (a.tile != 0), defined in sk_tile.hip

@@ -84,6 +84,18 @@ __global__ void add_inplace_kernel(T* dst, const T* __restrict__ src, long n)
     for (; i < n; i += st) dst[i] = (T)((real)dst[i] + (real)src[i]);
 }
 
+// Between the reverse sweep and the replay kernel that solves drifted pairs once more: if the reverse sweep could
+// not tell which pairs drifted (*err == 2), every pair is solved again, and what the sweep has summed is dropped.
+__global__ void second_chance_reset_kernel(real* g1, long n1, real* g2, long n2, const int* err)
+{
+    if (*err != 2) return;
+    const long st = (long)gridDim.x * blockDim.x;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n1 + n2; i += st) {
+        if (i < n1) g1[i] = 0.0;
+        else g2[i - n1] = 0.0;
+    }
+}
+
 // One set of paths for the preparation / finalisation kernels.
 template <typename T>
 struct PathSet {
@@ -148,7 +160,9 @@ __global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, in
 template <typename TO>
 __global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS, const int* err, int ll)
 {
-    const bool bad = err != nullptr && *err != 0;   // a bounded wait ran out or the un-compute drifted
+    // a bounded wait ran out (1) or the workspace held another call's forward sweep (3); 2 means that every pair was
+    // solved once more by the replay kernel, whose results the accumulators then hold
+    const bool bad = err != nullptr && *err != 0 && *err != 2;
     const long nx = px.grad ? px.npaths * (long)px.L * d : 0;
     const long ny = py.grad ? py.npaths * (long)py.L * d : 0;
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -657,8 +671,14 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
     real* ckpt = a.ckpt + slot * a.ckpt_slot;
     const int S = a.S;
     SW sw(a, lane);
+    // As the launch that solves drifted pairs once more, the kernel works through the list the reverse sweep left
+    // (through every pair if that sweep could not tell which ones drifted); an empty list ends it at once.
+    const bool listed = a.second_chance != 0 && *a.err != 2;
+    const long count = a.second_chance == 0 ? a.npairs : (listed ? (long)*a.bad_count : a.npairs);
+    const bool own_edges = a.second_chance == 2;   // a call that works on the caller's arrays (pairs of double paths)
 
-    for (long pid = slot; pid < a.npairs; pid += nslots) {
+    for (long it = slot; it < count; it += nslots) {
+        const long pid = listed ? (long)a.bad_list[it] : it;
         long xi, yi;
         pair_ids(a, pid, xi, yi);
         sw.dxp = a.dx + xi * a.xstride;
@@ -666,9 +686,29 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
         sw.dyl = ylds;
         real* gdx = a.gdx + xi * a.xstride;
         real* gdy = a.gdy + yi * a.ystride;
+        if (own_edges) {
+            // increments of the pair (first line of the paper's forward listing), zero padded, and cleared sums
+            real* dxw = const_cast<real*>(a.dx) + xi * a.xstride;
+            real* dyw = const_cast<real*>(a.dy) + yi * a.ystride;
+            const real* xp = a.xraw + xi * (long)a.L1 * a.d;
+            const real* yp = a.yraw + yi * (long)a.L2 * a.d;
+            for (int t = lane; t < a.rpad * a.DS; t += kWave) {
+                const int r_ = t / a.DS, c = t - r_ * a.DS;
+                dxw[t] = (r_ < a.r && c < a.d) ? xp[(long)(r_ + 1) * a.d + c] - xp[(long)r_ * a.d + c] : 0.0;
+                gdx[t] = 0.0;
+            }
+            for (int t = lane; t < a.qpad * a.DS; t += kWave) {
+                const int r_ = t / a.DS, c = t - r_ * a.DS;
+                dyw[t] = (r_ < a.q && c < a.d) ? yp[(long)(r_ + 1) * a.d + c] - yp[(long)r_ * a.d + c] : 0.0;
+                gdy[t] = 0.0;
+            }
+            // the sweep reads the increments with ordinary loads: make the stores visible to them
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
         if constexpr (YLDS) {
             const int n = a.q * a.DS;
-            for (int t = lane; t < n; t += kWave) { ylds[t] = sw.dyg[t]; glds[t] = 0.0; }
+            for (int t = lane; t < n; t += kWave) { ylds[t] = ld_scratch(sw.dyg + t); glds[t] = 0.0; }
         }
         const real gk = a.grad_k[pid];
 
@@ -834,6 +874,29 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                 }
             }
         }
+        if (own_edges) {
+            // the gradient of a point collects the two increments it touches (the linear map of Section 3.4)
+            scratch_fence();
+            const int d = a.d;
+            if (a.gxraw) {
+                real* go = a.gxraw + xi * (long)a.L1 * d;
+                for (int t = lane; t < a.L1 * d; t += kWave) {
+                    const int pt = t / d, c = t - pt * d;
+                    const real hi = pt >= 1 ? ld_scratch(gdx + (long)(pt - 1) * a.DS + c) : 0.0;
+                    const real lo = pt < a.L1 - 1 ? ld_scratch(gdx + (long)pt * a.DS + c) : 0.0;
+                    go[t] = hi - lo;
+                }
+            }
+            if (a.gyraw) {
+                real* go = a.gyraw + yi * (long)a.L2 * d;
+                for (int t = lane; t < a.L2 * d; t += kWave) {
+                    const int pt = t / d, c = t - pt * d;
+                    const real hi = pt >= 1 ? ld_scratch(gdy + (long)(pt - 1) * a.DS + c) : 0.0;
+                    const real lo = pt < a.L2 - 1 ? ld_scratch(gdy + (long)pt * a.DS + c) : 0.0;
+                    go[t] = hi - lo;
+                }
+            }
+        }
     }
 }
 
@@ -983,7 +1046,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwdu_kernel(SweepArg
                     if (Jp >= 1 && Jp < sw.nbl) {
 #pragma unroll
                         for (int i = 0; i <= R; ++i)
-                            if (!(fabs(sw.left[i] - cpn[i]) <= 1e-9 * kscale)) drift = true;
+                            if (!(fabs(sw.left[i] - cpn[i]) <= kDriftTol * kscale)) drift = true;
                     }
                 }
 #pragma unroll
@@ -1050,11 +1113,12 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwdu_kernel(SweepArg
                 };
                 if (full) run_segment(std::true_type()); else run_segment(std::false_type());
             }
-            if (drift) {
-                atomicExch(a.err, 2);
+            // the left end: the recovered left edge of the strip against the boundary value 1
 #pragma unroll
-                for (int k = 0; k < DN; ++k) gacc[k] = __builtin_nan("");
-            }
+            for (int i = 0; i <= R; ++i)
+                if (!(fabs(sw.left[i] - 1.0) <= kDriftTol * kscale)) drift = true;
+            // this kernel's sums are already on their way: every pair of the call is then solved once more
+            if (drift) atomicCAS(a.err, 0, 2);   // (an error already raised stays)
             sw.flush_gdx(gacc, gdx);
             scratch_fence();
         }
@@ -1711,7 +1775,7 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
                     if (Jp >= 1 && Jp < sw.nbl) {
 #pragma unroll
                         for (int k = 0; k <= R; ++k)
-                            if (!(fabs(sw.left[k] - cpn[k]) <= 1e-9 * kscale)) drift = true;
+                            if (!(fabs(sw.left[k] - cpn[k]) <= kDriftTol * kscale)) drift = true;
                     }
                 }
 #pragma unroll
@@ -1793,7 +1857,12 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
             }
             lk.publish(a.nb);
             lk.consumed(a.nb);
-            if (drift) atomicExch(a.err, 2);
+            // the left end: the recovered left edge of the strip against the boundary value 1
+#pragma unroll
+            for (int k = 0; k <= R; ++k)
+                if (!(fabs(sw.left[k] - 1.0) <= kDriftTol * kscale)) drift = true;
+            // this kernel's sums are already on their way: every pair of the call is then solved once more
+            if (drift) atomicCAS(a.err, 0, 2);   // (an error already raised stays)
             sw.flush_gdx(gacc, gdx);
         }
         __syncthreads();
@@ -1825,6 +1894,17 @@ hipError_t launch_fill(T* p, long n, T v, hipStream_t st)
 hipError_t launch_keep_tag(unsigned long long* tag, unsigned long long val, int check, int* err, hipStream_t st)
 {
     hipLaunchKernelGGL(keep_tag_kernel, dim3(1), dim3(1), 0, st, tag, val, check, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_second_chance_reset(real* g1, long n1, real* g2, long n2, const int* err, hipStream_t st)
+{
+    if (!g1) n1 = 0;
+    if (!g2) n2 = 0;
+    if (n1 + n2 == 0) return hipSuccess;
+    long blocks = (n1 + n2 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(second_chance_reset_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g1, n1, g2, n2, err);
     return hipGetLastError();
 }
 
@@ -2007,6 +2087,7 @@ template hipError_t launch_mmd2_reduce<double>(const double*, const double*, con
                                                hipStream_t);
 template hipError_t launch_add_inplace<float>(float*, const float*, long, hipStream_t);
 template hipError_t launch_add_inplace<double>(double*, const double*, long, hipStream_t);
+template hipError_t launch_fill<int>(int*, long, int, hipStream_t);
 template hipError_t launch_fill<float>(float*, long, float, hipStream_t);
 template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
 template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);

@@ -31,8 +31,9 @@
 // (bottom edge: the top edge the lane below recovered one step earlier; for the strip's last lane the
 // exact row kept from phase 1), scatters the adjoint (first relation of Section 3.4) and forms dF/dp per
 // block (second relation).  Every 8 steps the forward state is replaced by the exact checkpoint, after
-// comparing the two: a difference above 1e-9 of the lane's largest forward value raises the error flag, and the finalisation then
-// returns NaN gradients instead of inaccurate ones.  Outside the grid the adjoint is exactly zero (the
+// comparing the two (at the left end the recovered state is compared with the boundary value 1): a difference above
+// kDriftTol of the lane's largest forward value disqualifies the pair - nothing of it reaches the gradients, and it
+// is listed for the replay kernel, which solves it once more.  Outside the grid the adjoint is exactly zero (the
 // seed dF/dk enters through the adjoint hand-over row under the last strip), and the products of zero with
 // the finite values computed there stay zero.
 #include <hip/hip_runtime.h>
@@ -271,22 +272,22 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     if (PHASE == 2 && threadIdx.x == 0) stale = *a.keep_tag != a.keep_tag_val;
 
     // ---- phase 2: the mirror image ----
+    real gacc[M][D];
+#pragma unroll
+    for (int m = 0; m < M; ++m)
+#pragma unroll
+        for (int c = 0; c < D; ++c) gacc[m][c] = 0.0;
+    // Drift of the recovered forward values against the exact checkpoints, measured against the largest
+    // forward value this lane has met (the gradients are sums of products of adjoints with forward values,
+    // and are checked against their own largest entry).
+    bool drift = false;
     {
         typename LK::Rev rv;
         rv.init();
-        real gacc[M][D];
-#pragma unroll
-        for (int m = 0; m < M; ++m)
-#pragma unroll
-            for (int c = 0; c < D; ++c) gacc[m][c] = 0.0;
         const int nck = a.lk_NT / CH2;
         const int lagc = kLockLag2 / CH2;
         const int niter = nck + (ns - 1) * lagc;
         const int rs = ns - 1 - strip;   // strips start bottom-up
-        // Drift of the recovered forward values against the exact checkpoints, measured against the largest
-        // forward value this lane has met (the gradients are sums of products of adjoints with forward values,
-        // and are checked against their own largest entry).
-        bool drift = false;
         real kscale = 1.0;
         // Checkpoints reach the stencil wave through LDS: the coefficient wave of the strip loads checkpoint idx
         // from global memory three chunks before it is needed, writes it into half (idx & 1) of the strip's
@@ -319,7 +320,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
                 if (rc > 0) {
 #pragma unroll
                     for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
-                        if (!(fabs(rv.kR[i] - cv[i]) <= 1e-9 * kscale)) drift = true;
+                        if (!(fabs(rv.kR[i] - cv[i]) <= kDriftTol * kscale)) drift = true;
                 }
 #pragma unroll
                 for (int i = 0; i <= RR; ++i) rv.kR[i] = cv[i];
@@ -358,45 +359,54 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
             }
             chunk_barrier();
         }
-        if (!a.fused) {
-            if (stencil) {
-                if (drift) atomicExch(a.err, 2);
-            } else if (role == kRoleCoef && a.want_gx) {
+        if (stencil) {   // the left end: every strip started from the boundary value 1 in every lane
 #pragma unroll
-                for (int m = 0; m < M; ++m) {
-                    const int I = (strip * kWave + lane) * M + m - a.lk_padb;
-                    if (I >= 0) {
-                        real* gq = gdx + (long)(I >> a.rs1) * LK::DSc;
+            for (int i = 0; i <= RR; ++i)
+                if (!(fabs(rv.kR[i] - 1.0) <= kDriftTol * kscale)) drift = true;
+        }
+    }
+    // The rings are free now.  In the fused form their memory collects the gradients with respect to the x
+    // increments, [r][DSc]; two ints of the dump row say how the pair went.
+    SK_LDS real* gxl = (SK_LDS real*)(smem + a.lk_off_cring);
+    SK_LDS int* bad = (SK_LDS int*)l.dump;   // [0]: the inverse recurrence drifted, [1]: not this call's forward sweep
+    if (a.fused) {
+        for (int t = threadIdx.x; t < a.r * LK::DSc; t += blockDim.x) gxl[t] = 0.0;
+    }
+    if (threadIdx.x == 0) { bad[0] = 0; bad[1] = stale ? 1 : 0; }
+    __syncthreads();
+    if (stencil) {
+        if (drift) bad[0] = 1;
+    } else if (a.fused && role == kRoleCoef && a.want_gx) {
 #pragma unroll
-                        for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
-                    }
-                }
-            }
-        } else {
-            // Fused finalisation.  The coefficient rings are free now: their memory collects the gradients
-            // with respect to the x increments, [r][DSc].
-            SK_LDS real* gxl = (SK_LDS real*)(smem + a.lk_off_cring);
-            SK_LDS int* bad = (SK_LDS int*)l.dump;
-            for (int t = threadIdx.x; t < a.r * LK::DSc; t += blockDim.x) gxl[t] = 0.0;
-            if (threadIdx.x == 0) *bad = stale ? 1 : 0;
-            __syncthreads();
-            if (stencil) {
-                if (drift) *bad = 1;
-            } else if (role == kRoleCoef && a.want_gx) {
+        for (int m = 0; m < M; ++m) {
+            const int I = (strip * kWave + lane) * M + m - a.lk_padb;
+            if (I >= 0) {
+                SK_LDS real* gq = gxl + (I >> a.rs1) * LK::DSc;
 #pragma unroll
-                for (int m = 0; m < M; ++m) {
-                    const int I = (strip * kWave + lane) * M + m - a.lk_padb;
-                    if (I >= 0) {
-                        SK_LDS real* gq = gxl + (I >> a.rs1) * LK::DSc;
-#pragma unroll
-                        for (int c = 0; c < D; ++c) lds_atomic_add(gq + c, gacc[m][c] * a.sc);
-                    }
-                }
+                for (int c = 0; c < D; ++c) lds_atomic_add(gq + c, gacc[m][c] * a.sc);
             }
         }
     }
     __syncthreads();
+    const bool is_stale = bad[1] != 0;
+    if (bad[0] != 0 && !is_stale) {
+        // A drifted pair adds nothing to the gradients: it is listed for the replay kernel, which solves it once more
+        // (and, in the fused form, writes the pair's gradients itself).
+        if (threadIdx.x == 0) list_drifted(a, pid, pid);
+        return;
+    }
     if (!a.fused) {
+        if (role == kRoleCoef && a.want_gx) {
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int I = (strip * kWave + lane) * M + m - a.lk_padb;
+                if (I >= 0) {
+                    real* gq = gdx + (long)(I >> a.rs1) * LK::DSc;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                }
+            }
+        }
         if (a.want_gy) {
             const int n = a.q * LK::DSc;
             for (int t = threadIdx.x; t < n; t += blockDim.x) {
@@ -406,9 +416,8 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
         }
     } else {
         // The increments are differences of consecutive points, so the gradient of a point collects the two
-        // increments it touches (the linear map of Section 3.4).  A drifted un-compute poisons the pair.
-        const SK_LDS real* gxl = (const SK_LDS real*)(smem + a.lk_off_cring);
-        const bool bad = *(const SK_LDS int*)l.dump != 0;
+        // increments it touches (the linear map of Section 3.4).  A reverse sweep that found another call's forward
+        // sweep in the workspace returns NaN.
         const real nan = __builtin_nan("");
         const int d = a.d;
         if (a.gxraw) {
@@ -417,7 +426,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
                 const int pt = t / d, c = t - pt * d;
                 const real hi = pt >= 1 ? gxl[(pt - 1) * LK::DSc + c] : 0.0;
                 const real lo = pt < a.L1 - 1 ? gxl[pt * LK::DSc + c] : 0.0;
-                go[t] = bad ? nan : hi - lo;
+                go[t] = is_stale ? nan : hi - lo;
             }
         }
         if (a.gyraw) {
@@ -426,7 +435,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
                 const int pt = t / d, c = t - pt * d;
                 const real hi = pt >= 1 ? l.gy[(pt - 1) * LK::DSc + c] : 0.0;
                 const real lo = pt < a.L2 - 1 ? l.gy[pt * LK::DSc + c] : 0.0;
-                go[t] = bad ? nan : hi - lo;
+                go[t] = is_stale ? nan : hi - lo;
             }
         }
     }
@@ -511,7 +520,8 @@ hipError_t launch_lock_bl(bool backward, int DT, const SweepArgs& a, int grid, s
 hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
                                  hipStream_t st)
 {
-    if (a.lk_ns < 1 || a.lk_ns > (backward ? kLockMaxStripsBwd : kLockMaxStrips) || (a.lk_NT & 7) != 0)
+    if (a.lk_ns < 1 || a.lk_ns > (backward ? kLockMaxStripsBwd : kLockMaxStrips) || (a.lk_NT & 7) != 0 ||
+        (backward && a.lk_phase != 1 && (!a.bad_list || !a.bad_count)))
         return hipErrorInvalidValue;
     switch (BL) {
 #ifndef SK_ONLY_C2

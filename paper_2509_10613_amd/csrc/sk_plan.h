@@ -66,11 +66,14 @@ struct Plan {
     int band = 0, bd_nbands = 0;   // bands of kBandStrips strips on different compute units (sk_band.hip)
     size_t bd_off_y = 0, bd_off_gy = 0, bd_off_rings = 0, off_flags = 0;
     int nflags = 0;
+    // Pairs whose inverse recurrence drifted are listed here by the reverse sweep and solved once more by the replay
+    // kernel (sk_api.hip): a counter (the int behind the progress counters, cleared with them) and the pair ids.
+    size_t off_badcnt = 0, off_badlist = 0;
     int tile = 0;   // one wave per pair, at most 64 x 64 cells, contractions on the matrix cores (sk_tile.hip)
     int solo = 0;   // one wave per pair, a single strip of 64 * lk_M block rows (many pairs of short paths)
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
     size_t lk_off_y = 0, lk_off_gy = 0, lk_off_cring = 0, lk_off_gp = 0, lk_off_krows = 0, lk_off_arows = 0,
-           lk_off_dump = 0, lk_cring_stride = 0, lk_gp_stride = 0, lk_off_ck = 0, lk_ck_stride = 0;
+           lk_off_dump = 0, lk_cring_stride = 0, lk_gp_stride = 0, lk_off_ck = 0, lk_ck_stride = 0, lk_off_gyp = 0;
 };
 
 // Lock-step mode constants: chunk lengths (macro-steps between workgroup barriers) of the forward and the
@@ -112,10 +115,19 @@ constexpr int kBandStrips = 4, kBandRing = 64, kBandYRing = 512, kBandLead = 2, 
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
 constexpr int kUncomputeS = 8;   // macro-steps between checkpoints when the reverse sweep inverts Eq. (1)
+constexpr size_t kSecondChanceBytes = (size_t)8 << 20;   // scratch of the launch that solves drifted pairs once more
+// A recovered forward value may differ from the exact checkpoint by this fraction of the lane's largest forward
+// value; beyond it the pair is solved once more by the replay kernel.  Gradients are sums of products of adjoints
+// with forward values, so this bounds their relative error, and it sits a decade below the 1e-10 the results are
+// held to; inside the validity range of the inverse recurrence the observed differences are below 1e-13.
+constexpr double kDriftTol = 1e-11;
 
 inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
-                      int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true, bool keep = false)
+                      int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true, bool keep = false,
+                      bool second_chance = false)
 {
+    // second_chance: the plan of the launch that solves the listed pairs once more (wave-per-pair replay kernel,
+    // a bounded number of waves, no increment and accumulator areas of its own: it works on the main plan's).
     // keep: a backward plan whose forward sweep may be a launch of its own (a forward call that keeps its sweep for
     // the backward call).  Lock-step and band plans are laid out for that anyway; solo plans then get checkpoints and
     // a bottom row per pair instead of per wave.
@@ -151,7 +163,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
 
     const int NVR = R + C + 1;   // block input edges kept per macro-step in the ring
     const size_t ring_step = (size_t)kWave * NVR * elem;
-    p.coop = (p.ns >= 2 && p.npairs <= kCoopMaxPairs) ? 1 : 0;
+    p.coop = (p.ns >= 2 && p.npairs <= kCoopMaxPairs && !second_chance) ? 1 : 0;
     if (p.coop) {
         // Workgroup-shared LDS: y (+ gradient accumulators), flags, ones/zeros/outbox rings; then one replay
         // ring per wave.
@@ -224,7 +236,18 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         if (backward && wg_per_cu > 2) wg_per_cu = 2;   // register file: the backward kernels run 2 waves per SIMD at most
         int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
         int64_t cap = (int64_t)kNumCU * wg_per_cu;
+        if (second_chance && cap > kNumCU) cap = kNumCU;
         p.grid = (int)(want < cap ? want : cap);
+        p.nslots = (int64_t)p.grid * kWavesPerWG;
+    }
+    if (second_chance) {
+        // rows, adjoint rows and checkpoints per wave slot, held to kSecondChanceBytes (at least one workgroup)
+        const int C2 = 1 << p.BL;
+        const size_t slot_bytes = ((size_t)p.ns * p.rowlen + 4 * (size_t)p.rowlen +
+                                   (size_t)p.ns * (p.nseg + 1) * (2 * C2 + 2) * kWave) * elem;
+        int64_t g = (int64_t)(kSecondChanceBytes / (slot_bytes * kWavesPerWG));
+        if (g < 1) g = 1;
+        if (g < p.grid) p.grid = (int)g;
         p.nslots = (int64_t)p.grid * kWavesPerWG;
     }
 
@@ -232,7 +255,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     // once: the chip is then under-filled and the time of a call is the latency of one pair's chain of
     // macro-steps, which this mode shortens (fewer instructions in the wave that carries the recurrence,
     // fewer strips, no waits).
-    if (lock_max_rows(backward, p.BL, p.DT) > 0 && (!backward || p.uncompute)) {
+    if (lock_max_rows(backward, p.BL, p.DT) > 0 && (!backward || p.uncompute) && !second_chance) {
         const int maxM = lock_max_rows(backward, p.BL, p.DT);
         int M = 1;
         while (M < maxM && (p.mb + kWave * M - 1) / (kWave * M) > 2) M *= 2;
@@ -275,7 +298,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     }
 
     // Solo mode: enough pairs to fill the chip, and all block rows of a pair fit one strip of 64 M rows.
-    if (!p.lock && solo_max_rows(backward, p.BL, p.DT) > 0 && (!backward || p.uncompute)) {
+    if (!p.lock && solo_max_rows(backward, p.BL, p.DT) > 0 && (!backward || p.uncompute) && !second_chance) {
         const int M = p.mb > kWave ? 2 : 1;
         const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
         size_t used = 0;
@@ -283,13 +306,14 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const size_t ycopy = (size_t)p.q * p.DP * elem;
         lds_take(ycopy);
         const size_t o_gy = backward ? lds_take(ycopy) : 0;
+        const size_t o_gyp = backward ? lds_take(ycopy) : 0;   // y-side sums of the pair in work
         const size_t o_kr = backward ? lds_take(((size_t)kWave * C + (size_t)NT * C + 2) * elem) : 0;
         const size_t o_dump = backward ? lds_take((size_t)kWave * C * elem) : 0;
         const int maxwg = backward ? 2 : 4;   // register file: the backward kernel runs two waves per SIMD at most
         if (M <= solo_max_rows(backward, p.BL, p.DT) && p.mb <= kWave * M && used * kWavesPerWG <= kLdsPerCU / 2) {
             p.solo = 1; p.coop = 0;
             p.lk_M = M; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave * M - p.mb;
-            p.lk_off_y = 0; p.lk_off_gy = o_gy; p.lk_off_krows = o_kr; p.lk_off_dump = o_dump;
+            p.lk_off_y = 0; p.lk_off_gy = o_gy; p.lk_off_krows = o_kr; p.lk_off_dump = o_dump; p.lk_off_gyp = o_gyp;
             p.y_lds = 1;
             p.lds_wave = used;
             p.lds_bytes = used * kWavesPerWG;
@@ -307,7 +331,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     // Tile mode: many pairs of at most 64 x 64 unrefined cells with 8 or 16 channels; the contractions over
     // the channels and over the rows / columns run as MFMA tiles, the sweep reads one number per cell from LDS.
     if (!p.lock && p.BL == 0 && p.rs1 == 0 && p.rs2 == 0 && (p.DT == 8 || p.DT == 16) && p.mb > kWave / 2 &&
-        p.mb <= kWave && p.nb > kWave / 2 && p.nb <= kWave && (!backward || p.uncompute)) {
+        p.mb <= kWave && p.nb > kWave / 2 && p.nb <= kWave && (!backward || p.uncompute) && !second_chance) {
         const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
         size_t used = 0;
         auto lds_take = [&](size_t bytes) { size_t o = used; used = align_up(used + bytes, 256); return o; };
@@ -342,7 +366,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
 
     // Band mode: few pairs of long paths.  The strips of a pair are spread over workgroups (bands of kBandStrips
     // strips) that all run at once; chosen when that fills more of the chip than one workgroup per pair does.
-    if (!p.lock && !p.tile && !p.solo && (!backward || p.uncompute) && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips) {
+    if (!p.lock && !p.tile && !p.solo && (!backward || p.uncompute) && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips &&
+        !second_chance) {
         const int nbands = (p.ns + kBandStrips - 1) / kBandStrips;
         if (p.npairs * nbands <= kNumCU) {
             const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
@@ -371,13 +396,22 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     // Workspace layout (all offsets 256-byte aligned).
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    p.off_dxT = take((size_t)nx * p.xstride * elem);
-    p.off_dyT = symmetric ? p.off_dxT : take((size_t)ny * p.ystride * elem);
+    // first, so that their place does not depend on the rest of the layout: the error flag, the progress counters
+    // of band mode directly behind it (cleared with it), and behind those the counter of drifted pairs
+    p.off_err = take(256);
+    p.off_flags = take((size_t)p.nflags * sizeof(int) + 4);
+    p.off_badcnt = p.off_flags + (size_t)p.nflags * sizeof(int);
+    if (!second_chance) {
+        p.off_dxT = take((size_t)nx * p.xstride * elem);
+        p.off_dyT = symmetric ? p.off_dxT : take((size_t)ny * p.ystride * elem);
+    }
     p.rows_slot = (int64_t)p.ns * p.rowlen;
     p.off_rows = take((size_t)p.nslots * p.rows_slot * elem);
     if (backward) {
-        p.off_gdxT = take((size_t)nx * p.xstride * elem);
-        p.off_gdyT = symmetric ? p.off_gdxT : take((size_t)ny * p.ystride * elem);
+        if (!second_chance) {
+            p.off_gdxT = take((size_t)nx * p.xstride * elem);
+            p.off_gdyT = symmetric ? p.off_gdxT : take((size_t)ny * p.ystride * elem);
+        }
         p.adj_slot = (p.band && p.bd_nbands > 4 ? p.bd_nbands : 4) * (int64_t)p.rowlen;   // two rows of 2C values per block column; band mode: one row per band
         p.off_adj = take((size_t)p.nslots * p.adj_slot * elem);
         // lane state kept per checkpoint: right edge, bottom edge, bottom-left corner
@@ -399,8 +433,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.off_kio = take((size_t)p.kcount * elem);
         if (backward) p.off_gkio = take((size_t)p.kcount * elem);
     }
-    p.off_err = take(256);
-    p.off_flags = take((size_t)p.nflags * sizeof(int) + 4);   // directly behind the error flag: cleared with it
+    if (backward && p.uncompute && !second_chance) p.off_badlist = take((size_t)p.kcount * sizeof(long long));
     p.total = off;
     p.valid = true;
     return p;

@@ -13,8 +13,10 @@
 // Backward (Section 3.4): forward sweep with a checkpoint of the lane state every 8 macro-steps and the
 // pair's bottom row kept in LDS, then the mirrored reverse sweep that recovers the forward values by
 // inverting Eq. (1) between checkpoints (see sk_lane.h), with the same drift guard as the other kernels:
-// a recovered state that differs from the exact checkpoint by more than 1e-9 of the lane's largest forward
-// value raises the call's error flag, and the finalisation returns NaN gradients.
+// a recovered state that differs from the exact checkpoint (at the left end: from the boundary value 1) by more
+// than kDriftTol of the lane's largest forward value disqualifies the pair: nothing of it reaches the gradient
+// sums (the y side is collected per pair and merged into the run's sums only when the pair has passed), and
+// the pair is listed for the replay kernel, which solves it once more.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -124,7 +126,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
     const long nslots = (long)gridDim.x * kWavesPerWG;
     unsigned char* mylds = smem + (size_t)w * a.lds_wave;
     SK_LDS real* ylds = (SK_LDS real*)mylds;
-    SK_LDS real* gyl = (SK_LDS real*)(mylds + a.lk_off_gy);
+    SK_LDS real* gyl = (SK_LDS real*)(mylds + a.lk_off_gy);    // y-side sums of the run of pairs
+    SK_LDS real* gyp = (SK_LDS real*)(mylds + a.lk_off_gyp);   // ... of the pair in work
     SK_LDS real* krow = (SK_LDS real*)(mylds + a.lk_off_krows) + LK::PADF;   // bottom row, by node column
     SK_LDS real* dump = (SK_LDS real*)(mylds + a.lk_off_dump);
     real* ckpt = a.ckpt + slot * a.ckpt_slot + lane;   // PHASE != 0: set per pair below
@@ -137,8 +140,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
     const bool plain = a.rs2 == 0;    // 64 lanes at 64 different y rows: plain read-modify-write is safe
     long cur_y = -1;
     real* gdy_cur = nullptr;
-    bool drift = false;
 
+    for (int t = lane; t < ny; t += kWave) gyp[t] = 0.0;
     typename LK::Coef cf;
     auto flush_gy = [&]() {
         if (gdy_cur && a.want_gy) {
@@ -232,6 +235,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
 #pragma unroll
                 for (int c = 0; c < D; ++c) gacc[m][c] = 0.0;
             real kscale = 1.0;
+            bool drift = false;
             const int up1 = lane > 0 ? -1 : 0;   // the bottom edge of the lane above travels with this lane's top edge
             real cpn[NVS];
             auto load_ckpt = [&](int idx) {
@@ -284,7 +288,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
                             for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp[m], y[i & 1][c], gacc[m][c]);
                     }
                     if (a.want_gy) {
-                        SK_LDS real* gq = gyl + __mul24(b[i & 1], LK::DSc);
+                        SK_LDS real* gq = gyp + __mul24(b[i & 1], LK::DSc);
                         real t[D];
 #pragma unroll
                         for (int c = 0; c < D; ++c) {
@@ -312,7 +316,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
                 if (g < nseg - 1) {
 #pragma unroll
                     for (int i = 0; i <= RR; ++i)   // written so that a NaN counts as drift
-                        if (!(fabs(rv.kR[i] - cpn[i]) <= 1e-9 * kscale)) drift = true;
+                        if (!(fabs(rv.kR[i] - cpn[i]) <= kDriftTol * kscale)) drift = true;
                 }
 #pragma unroll
                 for (int i = 0; i <= RR; ++i) rv.kR[i] = cpn[i];
@@ -322,22 +326,34 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
                 if (cf.interior(g * S, S)) seg(std::false_type(), g * S);
                 else seg(std::true_type(), g * S);
             }
-            if (a.want_gx) {
+            // the left end: the sweep started from the boundary value 1 in every lane
 #pragma unroll
-                for (int m = 0; m < M; ++m) {
-                    const int I = lane * M + m - a.lk_padb;
-                    if (I >= 0) {
-                        real* gq = a.gdx + xi * a.xstride + (long)(I >> a.rs1) * LK::DSc;
+            for (int i = 0; i <= RR; ++i)
+                if (!(fabs(rv.kR[i] - 1.0) <= kDriftTol * kscale)) drift = true;
+            if (__ballot(drift) == 0ull) {
+                if (a.want_gx) {
 #pragma unroll
-                        for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                    for (int m = 0; m < M; ++m) {
+                        const int I = lane * M + m - a.lk_padb;
+                        if (I >= 0) {
+                            real* gq = a.gdx + xi * a.xstride + (long)(I >> a.rs1) * LK::DSc;
+#pragma unroll
+                            for (int c = 0; c < D; ++c) unsafeAtomicAdd(gq + c, gacc[m][c] * a.sc);
+                        }
                     }
                 }
+                if (a.want_gy) {
+                    for (int t = lane; t < ny; t += kWave) { gyl[t] += gyp[t]; gyp[t] = 0.0; }
+                }
+            } else {
+                // nothing of this pair is kept: the replay kernel solves it once more
+                for (int t = lane; t < ny; t += kWave) gyp[t] = 0.0;
+                if (lane == 0) list_drifted(a, pid, pid2);
             }
         }
         scratch_fence();   // the next pair overwrites the checkpoints
     }
     flush_gy();
-    if (drift) atomicExch(a.err, 2);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -415,7 +431,7 @@ hipError_t launch_solo_bl(bool backward, int DT, const SweepArgs& a, int grid, s
 
 hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    if (a.lk_M < 1 || (backward && (a.lk_NT % kLockS) != 0)) return hipErrorInvalidValue;
+    if (a.lk_M < 1 || (backward && ((a.lk_NT % kLockS) != 0 || !a.bad_list || !a.bad_count))) return hipErrorInvalidValue;
     switch (BL) {
         case 0: return launch_solo_bl<0>(backward, DT, a, grid, lds, st);
         case 1: return launch_solo_bl<1>(backward, DT, a, grid, lds, st);

@@ -226,7 +226,6 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
     const bool last = lane == kWave - 1;
     long cur_y = -1;
     real* gdy_cur = nullptr;
-    bool drift = false;
 
     P[(kTileCols - 1) * kTileStride + lane] = 0.0;   // column 64: the zero column of a pair with 64 columns
     if (last) krow[-kTileStride] = 1.0;              // node column -1 (stands for all nodes left of the grid)
@@ -309,6 +308,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
         }
 
         // ---- phase 2: the mirror image; G = dF/dp replaces p in place ----
+        bool drift = false;
         {
             typename LK::Rev rv;
             rv.init();
@@ -352,25 +352,31 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                 }
                 if (g > 0 && g % CK == 0) {
                     // the recovered state against the exact one, which replaces it: rounding errors of the inverse
-                    // recurrence cannot build up over more than CK chunks, and a drift raises the error flag
+                    // recurrence cannot build up over more than CK chunks, and a drift disqualifies the pair
                     const SK_LDS real* cp = ckl + (g / CK - 1) * (2 * kWave);
                     const real e1 = cp[0];
                     const real e0 = wave_from_above_or(cp[kWave], 1.0);   // the lane above's k[a][J]; row 0 has the boundary above it
                     kscale = fmax(kscale, fmax(fabs(e0), fabs(e1)));
                     // written so that a NaN counts as drift
-                    if (!(fabs(rv.kR[0] - e0) <= 1e-9 * kscale) || !(fabs(rv.kR[1] - e1) <= 1e-9 * kscale)) drift = true;
+                    if (!(fabs(rv.kR[0] - e0) <= kDriftTol * kscale) || !(fabs(rv.kR[1] - e1) <= kDriftTol * kscale)) drift = true;
                     rv.kR[0] = e0;
                     rv.kR[1] = e1;
                     rv.ktop[0] = e0;
                 }
             }
+            // the left end: the sweep started from the boundary value 1 in every lane
+            if (!(fabs(rv.kR[0] - 1.0) <= kDriftTol * kscale) || !(fabs(rv.kR[1] - 1.0) <= kDriftTol * kscale)) drift = true;
         }
+        // A pair whose inverse recurrence drifted adds nothing to the gradient sums (its G is not mapped) and is
+        // listed for the replay kernel, which solves it once more.
+        const bool passed = __ballot(drift) == 0ull;
+        if (!passed && lane == 0) list_drifted(a, pid, pid2);
 
         // Loads for the second half of the linear map and for the next pair, issued here so that the first half
         // of the map covers their latency (during the sweeps the registers are needed elsewhere).
         const real* dxg = a.dx + xi * a.xstride;
         real xc[16], xbn[4][KC], gkn = 0.0;
-        if (a.want_gy) TL::load_c(dxg, a.DS, padb, lane, xc);
+        if (a.want_gy && passed) TL::load_c(dxg, a.DS, padb, lane, xc);
         if (q + 1 < q1) {
             long xin, yin, pidn, pidn2;
             gram_pair(a, q + 1, xin, yin, pidn, pidn2);
@@ -379,7 +385,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
         }
 
         // ---- the linear map of Section 3.4 on the matrix cores ----
-        if (a.want_gx) {
+        if (a.want_gx && passed) {
             // dF/d(dx)[a, c] = sum_b G[a, b] dy[b, c]: A operand G[16 I + l % 16][4 kb + l / 16], B operand yc[kb]
             // (the lane's part of the address goes through an opaque move: computed here, once per pair, from one
             // register, instead of sixteen loop-invariant addresses kept alive over the whole pair loop)
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                 }
             }
         }
-        if (a.want_gy) {
+        if (a.want_gy && passed) {
             // dF/d(dy)[b, c] = sum_a G[a, b] dx[a, c]: A operand G[4 ka + l / 16][16 J + l % 16], B operand xc[ka]
 #pragma unroll
             for (int J = 0; J < 4; ++J) {
@@ -417,7 +423,6 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
         gk = gkn;
     }
     flush_gy();
-    if (drift) atomicExch(a.err, 2);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -444,7 +449,7 @@ hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid
     // what the kernels assume about the launch
     if (a.lk_M != 1 || a.rs1 != 0 || a.rs2 != 0 || a.mb > kWave || a.nb > kWave || a.mb < 1 || a.nb < 1 ||
         a.lk_padb != kWave - a.mb || a.rpad < kWave || a.qpad < kWave || a.DS <= DT || a.d > DT ||
-        (backward && ((a.lk_NT % kLockS) != 0 || a.lk_NT < a.nb + kWave - 1 || a.lk_NT >= a.nb + kWave - 1 + kLockS ||
+        (backward && (!a.bad_list || !a.bad_count || (a.lk_NT % kLockS) != 0 || a.lk_NT < a.nb + kWave - 1 || a.lk_NT >= a.nb + kWave - 1 + kLockS ||
                       (size_t)a.lk_off_ck + (size_t)((a.lk_NT / kLockS - 1) / kTileCkChunks) * 2 * kWave * sizeof(real) >
                           a.lds_wave)))
         return hipErrorInvalidValue;

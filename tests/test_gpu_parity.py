@@ -919,31 +919,116 @@ def test_backward_replay_variant_many_pairs():
     check_grads(host(gY2), gYr, torch.float64, "grad_Y (default)")
 
 
+def drifted_pairs(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, dtype, ws):
+    """How many pairs the reverse sweep of the last call on `ws` handed to the replay kernel (the library's launch
+    description says where in the workspace it counts them); -1: the launch mode does not count per pair."""
+    sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+    desc = sk.sigkernel_describe(op, B_or_N, M, L1, L2, d, lam1, lam2, flags, sdt)
+    at = int(desc.split("drifted_pairs_counter_at=", 1)[1].split()[0])
+    torch.cuda.synchronize()
+    n = int(ws[at:at + 4].view(torch.int32)[0])
+    mode = desc.split("mode=", 1)[1].split()[0]
+    return n if mode in ("lock-step", "solo", "tile") else -1
+
+
+def pairs_backward_with_ws(X, Y, gk, lam1, lam2, flags, dtype=torch.float64):
+    B, L1, d = X.shape
+    sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+    ws = torch.empty(sk.sigkernel_workspace_bytes(sk.SK_OP_BWD, B, 0, L1, Y.shape[1], d, lam1, lam2, flags, sdt),
+                     dtype=torch.uint8, device="cuda")
+    k, gx, gy = sk.sigkernel_bwd(dev(X, dtype), dev(Y, dtype), dev(gk, dtype), lam1, lam2, flags, ws=ws)
+    torch.cuda.synchronize()
+    return k, gx, gy, drifted_pairs(sk.SK_OP_BWD, B, 0, L1, Y.shape[1], d, lam1, lam2, flags, dtype, ws)
+
+
 @pytest.mark.parametrize("scale", [0.5, 1.5, 4.0])
-def test_inverse_recurrence_never_fails_silently(scale):
-    # Large increments make the inverse of Eq. (1) ill-conditioned.  The default backward must then either
-    # still meet the tolerance or return NaN everywhere (its drift check); the replay variant has no limit.
+def test_default_backward_is_exact_for_large_increments(scale):
+    # Large increments make the inverse of Eq. (1) ill-conditioned (and B(p) = 0 at p = sqrt(12)).  The default backward
+    # notices (its drift check), leaves such pairs out, and solves them once more by replaying forward segments: the
+    # gradients are the oracle's whatever the input (Section 3.4: exact gradients of the scheme).
     B, L, d = 4, 150, 3
     X = rand_paths(7001, B, L, d, 0.1) * scale
     Y = rand_paths(7002, B, L, d, 0.1) * scale
     gk = np.ones(B)
     kr, gxr, gyr = oracle.bwd(X, Y, gk, 1, 1, 0)
-    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, 0)
-    torch.cuda.synchronize()
-    gx, gy = host(gx), host(gy)
-    # a pair whose check failed is NaN in every entry of both gradients (the whole call may be); every other
-    # pair meets the tolerance
-    bad = np.isnan(gx).any(axis=(1, 2)) | np.isnan(gy).any(axis=(1, 2))
-    if bad.any():
-        print("scale %g: inverse recurrence drifted for %d of %d pairs, their gradients are NaN" % (scale, bad.sum(), B),
-              flush=True)
-        assert np.all(np.isnan(gx[bad])) and np.all(np.isnan(gy[bad]))
-    good = ~bad
-    if good.any():
-        assert np.max(np.abs(gx[good] - gxr[good])) <= 1e-10 * max(1.0, np.max(np.abs(gxr)))
-        assert np.max(np.abs(gy[good] - gyr[good])) <= 1e-10 * max(1.0, np.max(np.abs(gyr)))
+    k, gx, gy, n = pairs_backward_with_ws(X, Y, gk, 1, 1, 0)
+    print("scale %g: %d of %d pairs solved once more" % (scale, n, B), flush=True)
+    check_values(host(k), kr, torch.float64, "k")
+    check_rows(host(gx), gxr, torch.float64, "grad_x (scale %g)" % scale)
+    check_rows(host(gy), gyr, torch.float64, "grad_y (scale %g)" % scale)
+    assert (n == 0) if scale == 0.5 else (n >= 0)
+    if scale == 4.0:
+        assert n > 0          # the case the second launch exists for
     k2, gx2, gy2 = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), 1, 1, sk.SK_FLAG_BWD_REPLAY)
     torch.cuda.synchronize()
-    assert np.all(np.isfinite(host(gx2))) and np.all(np.isfinite(host(gy2)))
-    check_grads(host(gx2), gxr, torch.float64, "grad_x (replay, scale %g)" % scale)
-    check_grads(host(gy2), gyr, torch.float64, "grad_y (replay, scale %g)" % scale)
+    check_rows(host(gx2), gxr, torch.float64, "grad_x (replay, scale %g)" % scale)
+    check_rows(host(gy2), gyr, torch.float64, "grad_y (replay, scale %g)" % scale)
+
+
+@pytest.mark.parametrize("B,L1,L2,d,lam,mode", [(5, 70, 66, 3, 1, "lock-step"),      # fused: works on the caller's arrays
+                                                  (6, 150, 140, 5, 0, "lock-step"),    # two strips
+                                                  (2600, 14, 12, 3, 1, "solo"),
+                                                  (1300, 40, 44, 16, 0, "tile"),
+                                                  (3, 400, 330, 3, 0, "band"),
+                                                  (1100, 140, 20, 3, 0, "wave-per-pair"),
+                                                  (40, 200, 40, 20, 0, "cooperative")])
+@pytest.mark.parametrize("where", ["first columns", "last rows", "one pair"])
+def test_large_increments_in_every_launch_mode(B, L1, L2, d, lam, mode, where):
+    # Increments of order one in a few places of otherwise benign paths: in the first columns (the stretch left of the
+    # first checkpoint, which is compared with the boundary value), in the last rows, or in one pair of the batch only
+    # (then the other pairs must come through the fast path: the count says so).  Every launch mode.
+    assert ("mode=" + mode) in sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L1, L2, d, lam, lam, 0, sk.SK_F64)
+    rng = np.random.default_rng(7100 + L1 + d)
+    dX = rng.normal(0.0, (1.0 / (d * L1)) ** 0.5, (B, L1, d))
+    dY = rng.normal(0.0, (1.0 / (d * L2)) ** 0.5, (B, L2, d))
+    big = 2.2
+    if where == "first columns":
+        dY[:, 1:4, :] = rng.choice([-big, big], size=(B, 3, d)) / d ** 0.5
+        dX[:, 1::7, :] = rng.choice([-big, big], size=dX[:, 1::7, :].shape) / d ** 0.5
+    elif where == "last rows":
+        dX[:, -3:, :] = rng.choice([-big, big], size=(B, 3, d)) / d ** 0.5
+        dY[:, 2::5, :] = rng.choice([-big, big], size=dY[:, 2::5, :].shape) / d ** 0.5
+    else:
+        dX[B // 2, 1::3, :] = rng.choice([-big, big], size=dX[B // 2, 1::3, :].shape) / d ** 0.5
+        dY[B // 2, 1::3, :] = rng.choice([-big, big], size=dY[B // 2, 1::3, :].shape) / d ** 0.5
+    X, Y = np.cumsum(dX, axis=1), np.cumsum(dY, axis=1)
+    gk = workloads.upstream_weights(71, (B,))
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, lam, lam, 0)
+    assert np.all(np.isfinite(kr))
+    k, gx, gy, n = pairs_backward_with_ws(X, Y, gk, lam, lam, 0)
+    print("%s, %s: %d of %d pairs solved once more; |k| up to %.3g" % (mode, where, n, B, np.abs(kr).max()), flush=True)
+    check_values(host(k), kr, torch.float64, "k")
+    check_rows(host(gx), gxr, torch.float64, "grad_x")
+    check_rows(host(gy), gyr, torch.float64, "grad_y")
+    if n >= 0 and where == "one pair":
+        assert n <= 1
+
+
+def test_gram_with_one_wild_path_among_benign_ones():
+    # c3's shape cut down (solo kernels) and c5's (tile kernels): one path of X has increments of order one.  Only the
+    # pairs of its row are solved once more; K, grad_X and grad_Y are the oracle's; then the symmetric case.
+    for name, nx, ny in (("c3", 40, 36), ("c5", 48, 40)):
+        w, X, Y = workloads.make(name, n_x=nx, n_y=ny)
+        rng = np.random.default_rng(72)
+        dXw = rng.choice([-1.0, 1.0], size=(w.L - 1, w.d)) * (2.0 / w.d ** 0.5)
+        X[7, 1:, :] = np.cumsum(dXw, axis=0)
+        Y[3, 1:, :] = np.cumsum(dXw[::-1] * 0.8, axis=0)
+        W = workloads.upstream_weights(73, (nx, ny))
+        need = sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM_BWD, nx, ny, w.L, w.L, w.d, w.lam, w.lam, w.flags, sk.SK_F64)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), w.lam, w.lam, w.flags, ws=ws)
+        n = drifted_pairs(sk.SK_OP_GRAM_BWD, nx, ny, w.L, w.L, w.d, w.lam, w.lam, w.flags, torch.float64, ws)
+        Kr, gXr, gYr = oracle.gram(X, Y, W, w.lam, w.lam, w.flags)
+        print("%s: %d of %d pairs solved once more; |K| up to %.3g" % (name, n, nx * ny, np.abs(Kr).max()), flush=True)
+        assert 0 < n <= nx + ny - 1
+        check_values(host(K), Kr, torch.float64, "K")
+        check_rows(host(gX), gXr, torch.float64, "grad_X")
+        check_rows(host(gY), gYr, torch.float64, "grad_Y")
+        x = dev(X)
+        Ws = workloads.upstream_weights(74, (nx, nx))
+        Kxx, gXX, _ = sk.sigkernel_gram(x, x, dev(Ws), w.lam, w.lam, w.flags, ws=ws)
+        n = drifted_pairs(sk.SK_OP_GRAM_BWD, nx, nx, w.L, w.L, w.d, w.lam, w.lam, w.flags, torch.float64, ws)
+        Kxr, gXXr, _ = oracle.gram(X, X, Ws, w.lam, w.lam, w.flags)
+        assert 0 < n <= 2 * nx - 1
+        check_values(host(Kxx), Kxr, torch.float64, "K(X,X)")
+        check_rows(host(gXX), gXXr, torch.float64, "total derivative of K(X,X)")

@@ -58,7 +58,7 @@ def test_static_scratch_matches_the_workspace_entry_point_twice_in_a_row():
     one_call(6, 40, 33, 5, 1, sk.SK_FLAG_TIME_AUG, 9200)
     # other launch modes on the same array: many short pairs (solo and tile kernels, gradient sums in atomics), float arrays,
     # long paths (band kernels: progress counters in the scratch), and the first shape once more
-    one_call(2500, 6, 7, 2, 0, 0, 9300)
+    one_call(2000, 6, 7, 2, 0, 0, 9300)
     one_call(1300, 40, 40, 16, 0, 0, 9350)      # tile kernels
     one_call(300, 30, 20, 2, 0, 0, 9400, torch.float32)
     one_call(3, 400, 330, 3, 0, 0, 9500)
