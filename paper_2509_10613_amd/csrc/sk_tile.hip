@@ -287,6 +287,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                     cp[0] = f.left[1];
                     cp[kWave] = f.blc;
                 }
+                real kb[S];   // the lane's bottom values of the chunk; the last lane's are the pair's bottom row
 #pragma unroll
                 for (int i = 0; i < S; ++i) {
                     const real p = pq[i];
@@ -295,8 +296,17 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
                     TL::coef_fwd(p, Ac[0], Bc[0]);
                     recv[0] = wave_from_above_or(f.bot[0], 1.0);
                     f.step(recv, Ac, Bc);
-                    const int c = cl + i > -1 ? cl + i : -1;   // wave-uniform
-                    if (last) krow[c * kTileStride] = f.bot[0];
+                    kb[i] = f.bot[0];
+                }
+                if (last) {   // node columns left of the grid all go to the one slot that stands for them
+                    if (cl >= -1) {
+                        SK_LDS real* kp = krow + cl * kTileStride;
+#pragma unroll
+                        for (int i = 0; i < S; ++i) kp[i * kTileStride] = kb[i];
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < S; ++i) krow[(cl + i > -1 ? cl + i : -1) * kTileStride] = kb[i];
+                    }
                 }
             }
             kR0 = f.left[0];
@@ -326,10 +336,14 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
             for (int i = 0; i < S; ++i) pq[i] = readp(Jb + i);
             int cl = (nch - 1) * S - tpad - (kWave - 1);   // node column under the last lane's block, first macro-step
             for (int g = nch - 1; g >= 0; --g, Jb -= S, cl -= S) {
+                // the last lane's bottom edge, before any store of this chunk
+                if (cl >= -1) {
+                    const SK_LDS real* kp = krow + cl * kTileStride;
 #pragma unroll
-                for (int i = 0; i < S; ++i) {   // the last lane's bottom edge, before any store of this chunk
-                    const int c = cl + i > -1 ? cl + i : -1;
-                    kq[i] = krow[c * kTileStride];
+                    for (int i = 0; i < S; ++i) kq[i] = kp[i * kTileStride];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < S; ++i) kq[i] = krow[(cl + i > -1 ? cl + i : -1) * kTileStride];
                 }
 #pragma unroll
                 for (int i = S - 1; i >= 0; --i) {
