@@ -910,9 +910,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
 // of its previous block; the bottom edge of that block is the top edge the lane below recovered one
 // step earlier (one more DPP hand-over, next to the adjoint messages).  Rounding errors of the inverse
 // recurrence grow with the number of steps, so S is short, and at every checkpoint the recovered state
-// is compared with the exact one: a drift above 1e-9 of the row's largest value raises the error flag
-// (outputs become NaN) rather than returning inaccurate gradients; such inputs (increment inner products
-// of order one) need the replay variant (SK_FLAG_BWD_REPLAY).
+// is compared with the exact one (at the left end: with the boundary value 1): a drift above kDriftTol of the
+// row's largest value raises the flag that makes the call solve every pair once more with the replay kernel
+// above (this kernel's gradient sums are on their way by then, so it cannot leave out the one pair); such
+// inputs have increment inner products of order one.
 template <int BL, int D, bool YLDS>
 __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwdu_kernel(SweepArgs a)
 {
