@@ -839,6 +839,26 @@ def test_calls_can_be_captured_in_a_hip_graph(B, L, d, lam, flags):
     check_grads(host(gx), gxr, torch.float64, "grad_x from the graph")
 
 
+def test_event_timing_tags():
+    # the benchmark's timing hook: launches are recorded under the tag that was current, and read per tag
+    X, Y = rand_paths(8800, 6, 40, 3, 0.2), rand_paths(8801, 6, 40, 3, 0.2)
+    x, y = dev(X), dev(Y)
+    gk = dev(np.ones(6))
+    sk.sigkernel_event_timing_read()           # drop whatever earlier tests left
+    sk.sigkernel_event_timing(1)
+    sk.sigkernel_fwd(x, y, 1, 1)
+    sk.sigkernel_event_timing(2)
+    sk.sigkernel_fwd(x, y, 1, 1)
+    sk.sigkernel_bwd(x, y, gk, 1, 1)
+    sk.sigkernel_event_timing(0)
+    sk.sigkernel_fwd(x, y, 1, 1)               # not recorded
+    f_ms, nf, b_ms, nb = sk.sigkernel_event_timing_read(2)
+    assert (nf, nb) == (1, 1) and f_ms > 0.0 and b_ms > 0.0
+    f_ms, nf, b_ms, nb = sk.sigkernel_event_timing_read()      # the rest: tag 1
+    assert (nf, nb) == (1, 0) and f_ms > 0.0
+    assert sk.sigkernel_event_timing_read() == (0.0, 0, 0.0, 0)
+
+
 def test_more_pairs_than_wave_slots():
     # every wave slot handles several pairs in turn, so its scratch rows and checkpoints are reused
     X = rand_paths(71, 5000, 6, 2, 0.3)
