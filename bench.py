@@ -312,9 +312,7 @@ def kernel_name(desc):
 
 def keeps_forward(desc_fwd):
     """Whether the forward call's launch plan is the first half of the backward pass (its sweep is kept)."""
-    k = kernel_name(desc_fwd)
-    return ((k.startswith("lock_bwd_kernel<") or k.startswith("solo_bwd_kernel<")) and k.endswith(", 1>")) or \
-        (k.startswith("band_fwd_kernel<") and k.endswith(", true>"))
+    return " kept_sweep_half=1 " in desc_fwd
 
 
 def run_case(case, args, sk, torch):

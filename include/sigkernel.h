@@ -201,7 +201,11 @@ int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_m
  * Diagnostics (no passage of the paper): writes a NUL-terminated, human-readable description of the launch
  * the library would make for this operation and shape into out (host memory, out_bytes >= 1; truncated if
  * too small): the launch mode, the name of the sweep kernel as a profiler reports it, grid and workgroup
- * size, LDS bytes per workgroup and the workspace size.  Same arguments as sigkernel_workspace_bytes.
+ * size, LDS bytes per workgroup and the workspace size; kept_sweep_half (1: the launch is the forward half of
+ * the backward pass, kept for the backward call; 2: its reverse half; 0: neither); lead_lag_form (none,
+ * checkerboard: the grid of the caller's increments swept with one more level of refinement whose off-diagonal
+ * quadrants carry no increment product, or transformed_increments: the increments of the transformed paths
+ * written out and swept as they are).  Same arguments as sigkernel_workspace_bytes.
  * Pure host arithmetic: no GPU call.  Returns SK_OK or a negative error code.
  */
 int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,

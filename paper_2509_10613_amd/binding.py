@@ -185,9 +185,7 @@ def keeps_forward(B, L1, L2, d, lam1, lam2, flags, dt, gram_M=None):
         desc = sigkernel_describe(SK_OP_FWD, B, 0, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
     else:
         desc = sigkernel_describe(SK_OP_GRAM, B, gram_M, L1, L2, d, lam1, lam2, flags | SK_FLAG_KEEP_FORWARD, dt)
-    kern = desc.split("kernel=", 1)[1].split(" grid=", 1)[0]
-    return ((kern.startswith("lock_bwd_kernel<") or kern.startswith("solo_bwd_kernel<")) and kern.endswith(", 1>")) or \
-        (kern.startswith("band_fwd_kernel<") and kern.endswith(", true>"))
+    return " kept_sweep_half=1 " in desc
 
 
 def sigkernel_fwd(x, y, lam1=0, lam2=0, flags=0, k=None, ws=None):

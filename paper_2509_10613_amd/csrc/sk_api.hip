@@ -104,16 +104,34 @@ struct Layout {
     bool has_sc = false;
     size_t off_sc = 0;
     size_t total = 0;
+    // Lead-lag transform (Section 4): 0 not asked for; 1 the plan is that of the transformed paths (2L - 1 points,
+    // 2d channels), whose increments the preparation kernel writes out; 2 the plan is that of the caller's paths with
+    // one more dyadic level, swept in its lead-lag form (the kernels of the lock-step, solo and band families have
+    // one, for equal dyadic orders).
+    int ll = 0;
 };
 
+// L1, L2, d, lam1, lam2 are the caller's.
 Layout make_layout(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d,
-                   int lam1, int lam2, int io_elem, bool uncompute, bool keep = false)
+                   int lam1, int lam2, int flags, int io_elem, bool uncompute, bool keep = false)
 {
     Layout l;
-    l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, uncompute, keep);
+    bool native = false;
+    if ((flags & SK_FLAG_LEAD_LAG) && lam1 == lam2) {
+        l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1 + 1, lam2 + 1, io_elem, uncompute, keep,
+                            false, true);
+        native = l.p.valid && l.p.solo;
+    }
+    if (native) {
+        l.ll = 2;
+        lam1 += 1; lam2 += 1;
+    } else {
+        if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; l.ll = 1; }
+        l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, uncompute, keep);
+    }
     l.total = l.p.total;
     if (l.p.valid && backward && l.p.uncompute) {
-        l.sc = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, false, false, true);
+        l.sc = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, false, false, true, native);
         l.has_sc = l.sc.valid;
         l.off_sc = l.p.total;
         l.total = l.p.total + l.sc.total;
@@ -169,7 +187,10 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
     a.S = p.S; a.nseg = p.nseg; a.d = p.d;
     const double sc = 1.0 / (double)((int64_t)1 << (lam1 + lam2));
     a.sc = sc;
-    a.tc = (flags & SK_FLAG_TIME_AUG) ? sc * (1.0 / (double)(p.L1 - 1)) * (1.0 / (double)(p.L2 - 1)) : 0.0;
+    // the time channel t_i = i / (points - 1) of the paths the sweep stands for (lead-lag paths have 2L - 1 points)
+    const int tsteps1 = lay.ll == 2 ? 2 * (p.L1 - 1) : p.L1 - 1, tsteps2 = lay.ll == 2 ? 2 * (p.L2 - 1) : p.L2 - 1;
+    a.tc = (flags & SK_FLAG_TIME_AUG) ? sc * (1.0 / (double)tsteps1) * (1.0 / (double)tsteps2) : 0.0;
+    a.ll = lay.ll == 2 ? p.ll : 0;
     a.y_lds = p.y_lds;
     a.lds_wave = (unsigned)p.lds_wave;
     a.ring_off = (unsigned)p.ring_off;
@@ -209,9 +230,9 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
         a.bad_list = reinterpret_cast<long long*>(base + p.off_badlist);
     }
     // Lock-step mode on a batch of pairs of double paths works on the caller's arrays directly.
-    // Lead-lag transform (Section 4): the plan was made for the transformed paths (2L - 1 points, 2d channels);
+    // Lead-lag transform (Section 4) with a plan made for the transformed paths (2L - 1 points, 2d channels):
     // only the preparation and the finalisation know the caller's shape.
-    const int ll = (flags & SK_FLAG_LEAD_LAG) ? 1 : 0;
+    const int ll = lay.ll == 1 ? 1 : 0;
     const int cL1 = ll ? (p.L1 + 1) / 2 : p.L1, cL2 = ll ? (p.L2 + 1) / 2 : p.L2, cd = ll ? p.d / 2 : p.d;
     const bool fused = p.lock && p.gramM == 0 && kIsDouble && !ll;
     if (fused) {
@@ -377,8 +398,7 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     }
     rc = check_device();
     if (rc != SK_OK) return rc;
-    if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }   // shape of the transformed paths
-    Layout lay = make_layout(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
+    Layout lay = make_layout(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, flags, elem,
                              !(flags & SK_FLAG_BWD_REPLAY));
     if (!lay.p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0)
@@ -387,7 +407,7 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
     // launches of their own run the first half here and the second half there; the others ignore both flags.
     int phase = 0;
     if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
-        const Layout lb = make_layout(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, elem,
+        const Layout lb = make_layout(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, flags, elem,
                                       !(flags & SK_FLAG_BWD_REPLAY), true);
         if (!lb.p.valid) return fail(SK_ERR_SHAPE, "internal: plan invalid");
         if (ws_bytes < lb.total)
@@ -425,9 +445,8 @@ size_t sigkernel_workspace_bytes(int op, int64_t B_or_N, int64_t M, int64_t L1, 
     if (op < SK_OP_FWD || op > SK_OP_GRAM_BWD) return 0;
     const int64_t ny = gram ? M : B_or_N;
     if (validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt) != SK_OK) return 0;
-    if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
     // The symmetric Gram case needs no more than the general one, so the query does not distinguish them.
-    const Layout l = make_layout(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+    const Layout l = make_layout(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, flags, dt == SK_F64 ? 8 : 4,
                                  !(flags & SK_FLAG_BWD_REPLAY), kept);
     return l.p.valid ? l.total : 0;
 }
@@ -684,8 +703,7 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     const int64_t ny = gram ? M : B_or_N;
     int rc = validate(B_or_N, ny, L1, L2, d, lam1, lam2, flags, (int)dt);
     if (rc != SK_OK) return rc;
-    if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; }
-    Layout lay = make_layout(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+    Layout lay = make_layout(backward, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, flags, dt == SK_F64 ? 8 : 4,
                              !(flags & SK_FLAG_BWD_REPLAY));
     if (!lay.p.valid) {
         std::snprintf(out, out_bytes, "mode=trivial (no cells to sweep)");
@@ -694,7 +712,7 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     // a kept forward sweep: the two halves of the backward call, where the launch mode has them
     int phase = 0;
     if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
-        const Layout lb = make_layout(true, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, dt == SK_F64 ? 8 : 4,
+        const Layout lb = make_layout(true, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, flags, dt == SK_F64 ? 8 : 4,
                                       !(flags & SK_FLAG_BWD_REPLAY), true);
         if (lb.p.valid && split_forward(lb.p, dt, flags)) {
             phase = backward ? 2 : 1;
@@ -723,8 +741,9 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.solo) {
         mode = "solo";
-        if (backward || phase) std::snprintf(kern, sizeof(kern), "solo_bwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase);
-        else std::snprintf(kern, sizeof(kern), "solo_fwd_kernel<%d, %d, %d>", p.BL, p.DT, p.lk_M);
+        if (backward || phase)
+            std::snprintf(kern, sizeof(kern), "solo_bwd_kernel<%d, %d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase, p.ll);
+        else std::snprintf(kern, sizeof(kern), "solo_fwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, p.ll);
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.lock) {
         mode = "lock-step";
@@ -738,13 +757,14 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
                       (p.y_lds && p.DT) ? "true" : "false");
         threads = (p.coop ? p.nw : sk::kWavesPerWG) * sk::kWave;
     }
-    const bool fused = p.lock && !gram && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG);
+    const bool fused = p.lock && !gram && dt == SK_F64 && lay.ll != 1;
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
-                  "workspace_bytes=%zu drifted_pairs_counter_at=%zu",
+                  "kept_sweep_half=%d lead_lag_form=%s workspace_bytes=%zu drifted_pairs_counter_at=%zu",
                   mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
                   (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
-                  fused ? 1 : 0, lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
+                  fused ? 1 : 0, phase, lay.ll == 0 ? "none" : (lay.ll == 1 ? "transformed_increments" : "checkerboard"),
+                  lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
     return SK_OK;
 }
 

@@ -37,6 +37,10 @@ struct SweepArgs {
     int d;               // channels (runtime loop when the kernel has no compile-time count)
     real tc;             // scaled product of the two time-channel increments (0 without time augmentation)
     real sc;             // 2^-(lam1+lam2)
+    // Lead-lag paths (Section 4) swept on the grid of the original increments with one more level of refinement:
+    // of the 2 x 2 quadrants of that level the diagonal ones carry p, the others the time constant alone.
+    // 0: no transform; 1: the level lies inside a block (rs1 = rs2 = 0); 2: above the blocks (rs1, rs2 >= 1)
+    int ll;
     int y_lds;
     unsigned lds_wave;   // LDS bytes per wave
     unsigned ring_off;   // byte offset of the replay ring inside a wave's LDS

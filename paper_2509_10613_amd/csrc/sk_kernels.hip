@@ -209,6 +209,7 @@ struct Sweep {
     int s = 0, lb = 0, arow = 0;
     int nbl = 0;                        // a.nb for lanes that own a block row, 0 otherwise
     int nbm1 = 0;                       // a.nb - 1
+    int rowpar = 0;                     // a.ll == 2: parity of the lead-lag step the lane's block row belongs to
     int lbw = -1;                       // lane that writes the strip's bottom row to global (-1: nobody)
     int lbany = -1;                     // lb if the bottom row goes anywhere (global row or outbox)
     real dxr[DN];
@@ -237,6 +238,7 @@ struct Sweep {
         lbo = -1;
         int ar = I >> a.rs1;
         arow = ar < a.r ? ar : a.r - 1;
+        rowpar = a.ll == 2 ? (I >> (a.rs1 - 1)) & 1 : 0;
         if constexpr (D > 0) {
             const real* xp = dxp + (long)arow * DSc;
 #pragma unroll
@@ -285,6 +287,42 @@ struct Sweep {
             for (int c = 0; c < a.d; ++c) p = fma(a.sc * xp[c], yp[c], p);
         }
         return p;
+    }
+
+    // Lead-lag paths (Section 4; SweepArgs::ll) are swept on the grid of the original increments with one more level
+    // of refinement: the diagonal quadrants of that level carry p, the other two the time constant alone.
+    // a.ll == 2: the level lies above the blocks; whether block column J of this lane's row is off the diagonal
+    __device__ __forceinline__ bool ll_off_block(int J) const
+    {
+        return a.ll == 2 && (((J >> (a.rs2 - 1)) ^ rowpar) & 1) != 0;
+    }
+    // p of the lane's block in column J
+    __device__ __forceinline__ real p_block(int J, const real (&yv)[DN]) const
+    {
+        const real p = inner(J >> a.rs2, yv);
+        return ll_off_block(J) ? a.tc : p;
+    }
+    // a.ll == 1: the level lies inside the block; whether cell (rr, cc) is off the diagonal quadrants
+    static __device__ __forceinline__ constexpr bool cell_off(int rr, int cc)
+    {
+        return BL >= 1 && (((rr >> (BL > 0 ? BL - 1 : 0)) ^ (cc >> (BL > 0 ? BL - 1 : 0))) & 1) != 0;
+    }
+    static __device__ __forceinline__ void block_forward_ll(real (&e)[R + 1][C + 1], real p, real p0)
+    {
+        const real q2 = p * p, q0 = p0 * p0;
+        const real Bc = fma(q2, -1.0 / 12.0, 1.0), B0 = fma(q0, -1.0 / 12.0, 1.0);
+        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0)), A0 = fma(p0, 0.5, fma(q0, 1.0 / 12.0, 1.0));
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc)
+                e[rr + 1][cc + 1] = fma(e[rr + 1][cc] + e[rr][cc + 1], cell_off(rr, cc) ? A0 : Ac,
+                                        -(e[rr][cc] * (cell_off(rr, cc) ? B0 : Bc)));
+    }
+    __device__ __forceinline__ void block_forward_any(real (&e)[R + 1][C + 1], real p) const
+    {
+        if (a.ll == 1) block_forward_ll(e, p, a.tc);
+        else block_forward(e, p);
     }
 
     // Eq. (1) on the R x C cells of one block; e[0][*] and e[*][0] are given.
@@ -338,8 +376,8 @@ struct Sweep {
             for (int cc = 0; cc < C; ++cc) e[0][cc + 1] = recv[cc];
 #pragma unroll
             for (int rr = 1; rr <= R; ++rr) e[rr][0] = left[rr];
-            const real p = inner(J >> a.rs2, ycur);
-            block_forward(e, p);
+            const real p = p_block(J, ycur);
+            block_forward_any(e, p);
             blc = e[R][0];
 #pragma unroll
             for (int rr = 0; rr <= R; ++rr) left[rr] = e[rr][C];
@@ -507,15 +545,26 @@ struct Sweep {
     __device__ __forceinline__ real reverse_block(const real (&ein)[NVR], real p, const real (&recv)[C], bool seed,
                                                   real gk, real (&accL)[R + 1], real& corner, real (&up)[C]) const
     {
+        if (a.ll == 1) return reverse_block_t<true>(ein, p, a.tc, recv, seed, gk, accL, corner, up);
+        return reverse_block_t<false>(ein, p, p, recv, seed, gk, accL, corner, up);
+    }
+    // CHK: lead-lag level inside the block; the cells off its diagonal quadrants have the constant p0, take part in
+    // both recurrences and add nothing to dF/dp
+    template <bool CHK>
+    __device__ __forceinline__ real reverse_block_t(const real (&ein)[NVR], real p, real p0, const real (&recv)[C],
+                                                    bool seed, real gk, real (&accL)[R + 1], real& corner,
+                                                    real (&up)[C]) const
+    {
         real e[R + 1][C + 1];
 #pragma unroll
         for (int cc = 0; cc <= C; ++cc) e[0][cc] = ein[cc];
 #pragma unroll
         for (int rr = 1; rr <= R; ++rr) e[rr][0] = ein[C + rr];
-        block_forward(e, p);
-        const real q2 = p * p;
-        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
-        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+        if constexpr (CHK) block_forward_ll(e, p, p0);
+        else block_forward(e, p);
+        const real q2 = p * p, q0 = p0 * p0;
+        const real Bc = fma(q2, -1.0 / 12.0, 1.0), B0 = fma(q0, -1.0 / 12.0, 1.0);
+        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0)), A0 = fma(p0, 0.5, fma(q0, 1.0 / 12.0, 1.0));
         const real dA = fma(p, 1.0 / 6.0, 0.5);   // A'(p)
         const real dB = p * (1.0 / 6.0);          // -B'(p)
         real gn[R + 1][C + 1];
@@ -534,10 +583,13 @@ struct Sweep {
         for (int rr = R - 1; rr >= 0; --rr)
 #pragma unroll
             for (int cc = C - 1; cc >= 0; --cc) {
+                const bool off = CHK && cell_off(rr, cc);
+                const real Aq = off ? A0 : Ac, Bq = off ? B0 : Bc;
                 const real go = gn[rr + 1][cc + 1];
-                gn[rr + 1][cc] = fma(go, Ac, gn[rr + 1][cc]);
-                gn[rr][cc + 1] = fma(go, Ac, gn[rr][cc + 1]);
-                gn[rr][cc] = fma(-go, Bc, gn[rr][cc]);
+                gn[rr + 1][cc] = fma(go, Aq, gn[rr + 1][cc]);
+                gn[rr][cc + 1] = fma(go, Aq, gn[rr][cc + 1]);
+                gn[rr][cc] = fma(-go, Bq, gn[rr][cc]);
+                if (off) continue;
                 const real loc = fma(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
                 accP = fma(go, loc, accP);
             }
@@ -832,9 +884,10 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwd_kernel(SweepArgs
                     const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
                         const int b = J >> a.rs2;
-                        const real p = sw.inner(b, yv);
+                        const real p = sw.p_block(J, yv);
                         const bool seed = s == a.ns - 1 && lane == lb && J == a.nb - 1;
-                        const real accP = sw.reverse_block(ein, p, recv, seed, gk, accL, corner, up);
+                        real accP = sw.reverse_block(ein, p, recv, seed, gk, accL, corner, up);
+                        if (sw.ll_off_block(J)) accP = 0.0;   // the block's p is a constant
                         if (lane == 0 && s > 0) {
                             real* wp = adjw + (J * C + 1);
 #pragma unroll
@@ -1548,9 +1601,10 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
                     const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
                         const int b = J >> a.rs2;
-                        const real p = sw.inner(b, yv);
+                        const real p = sw.p_block(J, yv);
                         const bool seed = s == a.ns - 1 && lane == lb && J == a.nb - 1;
-                        const real accP = sw.reverse_block(ein, p, recv, seed, gk, accL, corner, up);
+                        real accP = sw.reverse_block(ein, p, recv, seed, gk, accL, corner, up);
+                        if (sw.ll_off_block(J)) accP = 0.0;   // the block's p is a constant
                         if (lane == lane_out) {
                             SK_LDS real* op = obox + ((a.nb - 1 - J) & sw.rbmask) * C;
 #pragma unroll
@@ -2073,6 +2127,12 @@ hipError_t launch_sweep_bl(bool backward, int DT, bool ylds, const SweepArgs& a,
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     const bool ylds = a.y_lds != 0;
+    // the lead-lag form of the sweep: the forward kernel and the replay kernel have it, with the level inside the blocks
+    // (which then hold every refined cell of a pair of increments) or above them
+    if (a.ll != 0 && (a.coop || (backward && a.uncompute))) return hipErrorInvalidValue;
+    if (a.ll == 1 && (BL < 1 || a.rs1 != 0 || a.rs2 != 0)) return hipErrorInvalidValue;
+    if (a.ll == 2 && (a.rs1 < 1 || a.rs2 < 1)) return hipErrorInvalidValue;
+    if (a.ll < 0 || a.ll > 2) return hipErrorInvalidValue;
     switch (BL) {
 #ifndef SK_ONLY_C2
         case 0: return launch_sweep_bl<0>(backward, DT, ylds, a, grid, lds, st);

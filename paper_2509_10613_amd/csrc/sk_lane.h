@@ -21,9 +21,25 @@ __device__ __forceinline__ int clamp_col(int J, int hi)
     return r;
 }
 
-template <int BL, int D, int M>
+//
+// LL (lead-lag paths, Section 4): the two transformed paths move their lead and their lag halves in turn, so
+// their increment Gram matrix is a checkerboard: the 2 x 2 steps that come from one pair of original increments
+// (a, b) hold <dx[a], dy[b]> on the diagonal (lead with lead, lag with lag) and nothing off it.  The transformed
+// paths are never formed: the grid of the original increments is swept with one more level of refinement, whose
+// cells take the coefficients of p on the diagonal quadrants of that level and those of p0 (the time channel's
+// constant product alone, 0 without time augmentation) on the others.
+//   LL = 0: no transform;  LL = 1: that level lies inside a block (block = all refined cells of one (a, b));
+//   LL = 2: it lies above the blocks (a block is uniform: diagonal or not by the parity of its row and column).
+template <int BL, int D, int M, int LL = 0>
 struct Lock {
+    static_assert(LL == 0 || BL >= 1, "the lead-lag level needs blocks of at least 2 x 2 cells");
     static constexpr int C = 1 << BL;
+    static constexpr int HB = BL > 0 ? BL - 1 : 0;   // LL = 1: log2 of a quadrant's side
+    // LL = 1: whether cell (rr, cc) of a lane's block column lies off the diagonal quadrants of its block
+    static __device__ __forceinline__ constexpr bool cell_off(int rr, int cc)
+    {
+        return LL == 1 && ((((rr & (C - 1)) >> HB) ^ (cc >> HB)) & 1) != 0;
+    }
     static constexpr int RR = M << BL;        // refined rows per lane
     static constexpr int DSc = D | 1;         // row stride of the increment arrays (doubles)
     static constexpr int NVC = RR + C + 2;    // checkpoint: right edge (RR+1), bottom edge (C), bottom-left corner
@@ -32,6 +48,20 @@ struct Lock {
     static constexpr int CR1 = CH1 * M * kWave * 2;   // doubles per half of the coefficient ring, forward
     static constexpr int CR2 = CH2 * M * kWave * 4;   // ... reverse sweep
     static constexpr int GPH = CH2 * M * kWave;       // doubles per half of the dF/dp ring
+
+    // A(p), B(p) of Eq. (1), and 1 / B(p) for the reverse sweep (one Newton step on the hardware estimate)
+    static __device__ __forceinline__ void coef_fwd(real p, real& Ac, real& Bc)
+    {
+        const real q2 = p * p;
+        Bc = fma(q2, -1.0 / 12.0, 1.0);
+        Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+    }
+    static __device__ __forceinline__ void coef_rev(real p, real& Ac, real& Bc, real& iB)
+    {
+        coef_fwd(p, Ac, Bc);
+        const real r = __builtin_amdgcn_rcp(Bc);
+        iB = fma(fma(-Bc, r, 1.0), r, r);
+    }
 
     // dF/dp ring: [macro-step][lane][M], so that a lane's M values move in one LDS instruction
     static __device__ __forceinline__ void gp_store(SK_LDS real* half, int i, int lane, const real (&v)[M])
@@ -62,17 +92,21 @@ struct Lock {
         int nbl[M];
         int lane, nb, nbm1, rs2;
         real tcm[M];   // the time channel's constant product; 0 for block rows above the grid
+        int rowpar[M]; // LL = 2: parity of the lead-lag step the block row belongs to
+        int rs2h;      // LL = 2: block columns per lead-lag step, log2
         const SK_LDS real* ylds;
 
         __device__ __forceinline__ void setup(const SweepArgs& a, int strip, int lane_, const real* dxp,
                                               const SK_LDS real* y)
         {
             lane = lane_; nb = a.nb; nbm1 = a.nb - 1; rs2 = a.rs2; ylds = y;
+            rs2h = a.rs2 - 1;
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 const int I = (strip * kWave + lane) * M + m - a.lk_padb;   // block row; < 0: above the grid
                 nbl[m] = I >= 0 ? a.nb : 0;
                 tcm[m] = I >= 0 ? a.tc : 0.0;
+                rowpar[m] = LL == 2 ? ((I >= 0 ? I : 0) >> (a.rs1 - 1)) & 1 : 0;
                 const int arow = (I >= 0 ? I : 0) >> a.rs1;
                 if (a.fused) {   // dxp: the pair's points [L1][d]; increments are formed here
                     const real* xp = dxp + (long)arow * a.d;
@@ -106,8 +140,23 @@ struct Lock {
             real p = tcm[m];
 #pragma unroll
             for (int c = 0; c < D; ++c) p = fma(dxr[m][c], y[c], p);
+            if constexpr (LL == 2) p = off_block(m, J) ? tcm[m] : p;
             if constexpr (EDGE) return (unsigned)J < (unsigned)nbl[m] ? p : 0.0;
             else return p;
+        }
+        // LL = 2: whether block (m, J) lies off the diagonal of its lead-lag level (then p is the constant alone
+        // and the block's dF/dp belongs to no increment)
+        __device__ __forceinline__ bool off_block(int m, int J) const
+        {
+            if constexpr (LL == 2) return (((J >> rs2h) ^ rowpar[m]) & 1) != 0;
+            else return false;
+        }
+        // LL = 1: p0 of the off-diagonal quadrants of block m in column J
+        template <bool EDGE>
+        __device__ __forceinline__ real inner_off(int m, int J) const
+        {
+            if constexpr (EDGE) return (unsigned)J < (unsigned)nbl[m] ? tcm[m] : 0.0;
+            else return tcm[m];
         }
         // forward: (A, B) of the chunk of CH1 macro-steps starting at T0
         // part 0: every macro-step of the chunk; part 1 / 2: the even / odd ones (two coefficient waves share a
@@ -286,6 +335,13 @@ struct Lock {
         // one macro-step: Eq. (1) on the RR x C cells of this lane's block column
         __device__ __forceinline__ void step(const real (&recv)[C], const real (&Ac)[M], const real (&Bc)[M])
         {
+            static_assert(LL != 1, "lead-lag blocks take the coefficients of their off-diagonal quadrants too");
+            step(recv, Ac, Bc, Ac, Bc);
+        }
+        // A0, B0: coefficients of the off-diagonal quadrants (LL = 1; unused otherwise)
+        __device__ __forceinline__ void step(const real (&recv)[C], const real (&Ac)[M], const real (&Bc)[M],
+                                             const real (&A0)[M], const real (&B0)[M])
+        {
             real top[C + 1];
             top[0] = left[0];
 #pragma unroll
@@ -296,7 +352,10 @@ struct Lock {
                 real cur[C + 1];
                 cur[0] = left[rr + 1];
 #pragma unroll
-                for (int cc = 0; cc < C; ++cc) cur[cc + 1] = fma(cur[cc] + top[cc + 1], Ac[m], -(top[cc] * Bc[m]));
+                for (int cc = 0; cc < C; ++cc) {
+                    const real Aq = cell_off(rr, cc) ? A0[m] : Ac[m], Bq = cell_off(rr, cc) ? B0[m] : Bc[m];
+                    cur[cc + 1] = fma(cur[cc] + top[cc + 1], Aq, -(top[cc] * Bq));
+                }
                 left[rr + 1] = cur[C];
 #pragma unroll
                 for (int cc = 0; cc <= C; ++cc) top[cc] = cur[cc];
@@ -368,6 +427,16 @@ struct Lock {
                                              const real (&Bc)[M], const real (&iB)[M], const real (&p6)[M],
                                              real (&accP)[M])
         {
+            static_assert(LL != 1, "lead-lag blocks take the coefficients of their off-diagonal quadrants too");
+            step(recv, recvk, Ac, Bc, iB, p6, Ac, Bc, iB, accP);
+        }
+        // A0, B0, iB0: coefficients of the off-diagonal quadrants (LL = 1; unused otherwise), whose cells take part in
+        // the recurrences but not in dF/dp: their p is a constant
+        __device__ __forceinline__ void step(const real (&recv)[C], const real (&recvk)[C], const real (&Ac)[M],
+                                             const real (&Bc)[M], const real (&iB)[M], const real (&p6)[M],
+                                             const real (&A0)[M], const real (&B0)[M], const real (&iB0)[M],
+                                             real (&accP)[M])
+        {
             real e[RR + 1][C + 1], gn[RR + 1][C + 1];
 #pragma unroll
             for (int rr = 0; rr <= RR; ++rr) e[rr][C] = kR[rr];
@@ -390,12 +459,15 @@ struct Lock {
                 const int m = rr >> BL;
 #pragma unroll
                 for (int cc = C - 1; cc >= 0; --cc) {
+                    const bool off = cell_off(rr, cc);
+                    const real Aq = off ? A0[m] : Ac[m], Bq = off ? B0[m] : Bc[m], iBq = off ? iB0[m] : iB[m];
                     const real s = e[rr + 1][cc] + e[rr][cc + 1];
-                    e[rr][cc] = fma(s, Ac[m], -e[rr + 1][cc + 1]) * iB[m];   // Eq. (1) solved for its oldest term
+                    e[rr][cc] = fma(s, Aq, -e[rr + 1][cc + 1]) * iBq;   // Eq. (1) solved for its oldest term
                     const real go = gn[rr + 1][cc + 1];
-                    gn[rr + 1][cc] = fma(go, Ac[m], gn[rr + 1][cc]);
-                    gn[rr][cc + 1] = fma(go, Ac[m], gn[rr][cc + 1]);
-                    gn[rr][cc] = fma(-go, Bc[m], gn[rr][cc]);
+                    gn[rr + 1][cc] = fma(go, Aq, gn[rr + 1][cc]);
+                    gn[rr][cc + 1] = fma(go, Aq, gn[rr][cc + 1]);
+                    gn[rr][cc] = fma(-go, Bq, gn[rr][cc]);
+                    if (off) continue;
                     const bool first = (rr & (C - 1)) == C - 1 && cc == C - 1;   // the block's first cell in this order
                     gs[m] = first ? go * s : fma(go, s, gs[m]);
                     gk[m] = first ? go * e[rr][cc] : fma(go, e[rr][cc], gk[m]);

@@ -69,6 +69,7 @@ struct Plan {
     // Pairs whose inverse recurrence drifted are listed here by the reverse sweep and solved once more by the replay
     // kernel (sk_api.hip): a counter (the int behind the progress counters, cleared with them) and the pair ids.
     size_t off_badcnt = 0, off_badlist = 0;
+    int ll = 0;     // lead-lag form of the sweep: 0 none, 1 the level lies inside a block, 2 above the blocks
     int tile = 0;   // one wave per pair, at most 64 x 64 cells, contractions on the matrix cores (sk_tile.hip)
     int solo = 0;   // one wave per pair, a single strip of 64 * lk_M block rows (many pairs of short paths)
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
@@ -98,9 +99,13 @@ constexpr int lock_max_rows(bool backward, int BL, int DT)
 constexpr int solo_max_rows(bool backward, int BL, int DT)
 {
     if (DT == 0) return 0;
-    if (backward) return (BL <= 1 && DT <= 8) ? 2 : 1;
+    if (backward) return ((BL <= 1 && DT <= 8) || DT <= 4) ? 2 : 1;
     return (BL >= 2 && DT >= 16) ? 1 : 2;
 }
+
+// Wavefronts per SIMD the solo backward kernel is built for: two, or one where the lane state of two block rows of
+// 4 x 4 cells needs the whole register file (accumulation registers included).
+constexpr int solo_bwd_waves_per_simd(int BL, int M) { return (BL >= 2 && M >= 2) ? 1 : 2; }
 
 // Tile mode: the increment Gram matrix of a pair as a 64 x 64 array of doubles in LDS, column stride
 // kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most
@@ -124,8 +129,12 @@ constexpr double kDriftTol = 1e-11;
 
 inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int64_t ny, int64_t L1, int64_t L2,
                       int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true, bool keep = false,
-                      bool second_chance = false)
+                      bool second_chance = false, bool lead_lag = false)
 {
+    // lead_lag: the sweep of two lead-lag paths (Section 4) on the grid of the original increments; lam1 == lam2 then
+    // count the lead-lag level as one more dyadic level (the caller's orders plus one), L1, L2 and d are the caller's.
+    // The level lies inside the blocks when these hold every refined cell of a pair of increments, above them
+    // otherwise (Plan::ll); the tile kernels have no such form.
     // second_chance: the plan of the launch that solves the listed pairs once more (wave-per-pair replay kernel,
     // a bounded number of waves, no increment and accumulator areas of its own: it works on the main plan's).
     // keep: a backward plan whose forward sweep may be a launch of its own (a forward call that keeps its sweep for
@@ -150,6 +159,10 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     p.BL = mn < kMaxBL ? mn : kMaxBL;
     p.rs1 = lam1 - p.BL; p.rs2 = lam2 - p.BL;
     p.mb = p.r << p.rs1; p.nb = p.q << p.rs2;
+    if (lead_lag) {
+        if (lam1 != lam2 || lam1 < 1) return p;   // not valid
+        p.ll = p.rs1 == 0 ? 1 : 2;
+    }
     p.ns = (p.mb + kWave - 1) / kWave;
     const int C = 1 << p.BL, R = C;
     p.rowlen = (int)align_up((size_t)(p.nb + 8) * C + 1, 64);   // a few block columns beyond the grid (band mode)
@@ -309,8 +322,8 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const size_t o_gyp = backward ? lds_take(ycopy) : 0;   // y-side sums of the pair in work
         const size_t o_kr = backward ? lds_take(((size_t)kWave * C + (size_t)NT * C + 2) * elem) : 0;
         const size_t o_dump = backward ? lds_take((size_t)kWave * C * elem) : 0;
-        const int maxwg = backward ? 2 : 4;   // register file: the backward kernel runs two waves per SIMD at most
-        if (M <= solo_max_rows(backward, p.BL, p.DT) && p.mb <= kWave * M && used * kWavesPerWG <= kLdsPerCU / 2) {
+        const int maxwg = backward ? solo_bwd_waves_per_simd(p.BL, M) : 4;   // register file of the backward kernel
+        if (M <= solo_max_rows(backward, p.BL, p.DT) && p.mb <= kWave * M && used * kWavesPerWG <= kLdsPerCU) {
             p.solo = 1; p.coop = 0;
             p.lk_M = M; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave * M - p.mb;
             p.lk_off_y = 0; p.lk_off_gy = o_gy; p.lk_off_krows = o_kr; p.lk_off_dump = o_dump; p.lk_off_gyp = o_gyp;
@@ -330,7 +343,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
 
     // Tile mode: many pairs of at most 64 x 64 unrefined cells with 8 or 16 channels; the contractions over
     // the channels and over the rows / columns run as MFMA tiles, the sweep reads one number per cell from LDS.
-    if (!p.lock && p.BL == 0 && p.rs1 == 0 && p.rs2 == 0 && (p.DT == 8 || p.DT == 16) && p.mb > kWave / 2 &&
+    if (!p.lock && !lead_lag && p.BL == 0 && p.rs1 == 0 && p.rs2 == 0 && (p.DT == 8 || p.DT == 16) && p.mb > kWave / 2 &&
         p.mb <= kWave && p.nb > kWave / 2 && p.nb <= kWave && (!backward || p.uncompute) && !second_chance) {
         const int NT = (int)align_up((size_t)p.nb + kWave - 1, 8);
         size_t used = 0;

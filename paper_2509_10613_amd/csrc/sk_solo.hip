@@ -30,11 +30,11 @@ namespace sk {
 // ------------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D, int M>
+template <int BL, int D, int M, int LL>
 __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo_fwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using LK = Lock<BL, D, M>;
+    using LK = Lock<BL, D, M, LL>;
     constexpr int C = LK::C;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -61,18 +61,17 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo
 
         auto step = [&](auto edge_c, int J, const real (&y)[D]) {
             constexpr bool EDGE = decltype(edge_c)::value;
-            real Ac[M], Bc[M];
+            real Ac[M], Bc[M], A0[M], B0[M];
 #pragma unroll
             for (int m = 0; m < M; ++m) {
-                const real p = cf.template inner<EDGE>(m, J, y);
-                const real q2 = p * p;
-                Bc[m] = fma(q2, -1.0 / 12.0, 1.0);
-                Ac[m] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                LK::coef_fwd(cf.template inner<EDGE>(m, J, y), Ac[m], Bc[m]);
+                if constexpr (LL == 1) LK::coef_fwd(cf.template inner_off<EDGE>(m, J), A0[m], B0[m]);
+                else { A0[m] = Ac[m]; B0[m] = Bc[m]; }
             }
             real recv[C];
 #pragma unroll
             for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(f.bot[cc], 1.0);
-            f.step(recv, Ac, Bc);
+            f.step(recv, Ac, Bc, A0, B0);
         };
         // macro-steps [T0, T1), the y increments fetched one step ahead
         auto run = [&](auto edge_c, int T0, int T1) {
@@ -110,11 +109,11 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo
 // PHASE 0: the whole backward pass.  PHASE 1 / 2: its two halves as launches of their own, for a forward call that
 // keeps its sweep and the backward call that takes it over: checkpoints and bottom row then have a place per pair in
 // global memory (phase 1 copies the row out of LDS, phase 2 copies it in) instead of one per wave.
-template <int BL, int D, int M, int PHASE>
-__global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepArgs a)
+template <int BL, int D, int M, int PHASE, int LL>
+__global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M)) void solo_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using LK = Lock<BL, D, M>;
+    using LK = Lock<BL, D, M, LL>;
     constexpr int C = LK::C, RR = LK::RR, NVC = LK::NVC, S = kLockS;
     constexpr int NVS = RR + 1 + C;
     // the macro-steps of a segment are unrolled in pairs (the y buffers alternate) when a lane holds many channels:
@@ -192,18 +191,17 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
 #pragma unroll kUnroll
                 for (int i = 0; i < S; ++i) {
                     if (i + 1 < S) cf.template fetch<EDGE>(T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);
-                    real Ac[M], Bc[M];
+                    real Ac[M], Bc[M], A0[M], B0[M];
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
-                        const real p = cf.template inner<EDGE>(m, J[i & 1], y[i & 1]);
-                        const real q2 = p * p;
-                        Bc[m] = fma(q2, -1.0 / 12.0, 1.0);
-                        Ac[m] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                        LK::coef_fwd(cf.template inner<EDGE>(m, J[i & 1], y[i & 1]), Ac[m], Bc[m]);
+                        if constexpr (LL == 1) LK::coef_fwd(cf.template inner_off<EDGE>(m, J[i & 1]), A0[m], B0[m]);
+                        else { A0[m] = Ac[m]; B0[m] = Bc[m]; }
                     }
                     real recv[C];
 #pragma unroll
                     for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(f.bot[cc], 1.0);
-                    f.step(recv, Ac, Bc);
+                    f.step(recv, Ac, Bc, A0, B0);
 #pragma unroll
                     for (int cc = 0; cc < C; ++cc) op[i * ostep + cc * cstep] = f.bot[cc];
                 }
@@ -256,16 +254,14 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
 #pragma unroll kUnroll
                 for (int i = S - 1; i >= 0; --i) {
                     if (i >= 1) cf.template fetch<EDGE>(T0 + i - 1, J[(i - 1) & 1], b[(i - 1) & 1], y[(i - 1) & 1]);
-                    real Ac[M], Bc[M], iB[M], p6[M], accP[M];
+                    real Ac[M], Bc[M], iB[M], p6[M], A0[M], B0[M], iB0[M], accP[M];
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
                         const real p = cf.template inner<EDGE>(m, J[i & 1], y[i & 1]);
-                        const real q2 = p * p;
-                        Bc[m] = fma(q2, -1.0 / 12.0, 1.0);
-                        Ac[m] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                        real r = __builtin_amdgcn_rcp(Bc[m]);
-                        iB[m] = fma(fma(-Bc[m], r, 1.0), r, r);
+                        LK::coef_rev(p, Ac[m], Bc[m], iB[m]);
                         p6[m] = p * (1.0 / 6.0);
+                        if constexpr (LL == 1) LK::coef_rev(cf.template inner_off<EDGE>(m, J[i & 1]), A0[m], B0[m], iB0[m]);
+                        else { A0[m] = Ac[m]; B0[m] = Bc[m]; iB0[m] = iB[m]; }
                     }
                     // dF/dk[m, n] enters under the last lane at the last column
                     const real seed = (T0 + i == Tseed) ? gk : 0.0;
@@ -275,12 +271,12 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
                         recv[cc] = wave_from_below_or(rv.up[cc], cc == C - 1 ? seed : 0.0);
                         recvk[cc] = wave_from_below_or(rv.ktop[cc], kp[i * C + cc]);
                     }
-                    rv.step(recv, recvk, Ac, Bc, iB, p6, accP);
-                    // the linear map of Section 3.4
+                    rv.step(recv, recvk, Ac, Bc, iB, p6, A0, B0, iB0, accP);
+                    // the linear map of Section 3.4 (lead-lag: blocks off the diagonal of that level have no increment)
                     real gp[M];
 #pragma unroll
                     for (int m = 0; m < M; ++m)
-                        gp[m] = (!EDGE || (unsigned)J[i & 1] < (unsigned)cf.nbl[m]) ? accP[m] : 0.0;
+                        gp[m] = ((!EDGE || (unsigned)J[i & 1] < (unsigned)cf.nbl[m]) && !cf.off_block(m, J[i & 1])) ? accP[m] : 0.0;
                     if (a.want_gx) {
 #pragma unroll
                         for (int m = 0; m < M; ++m)
@@ -359,55 +355,70 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void solo_bwd_kernel(SweepAr
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D, int M>
+template <int BL, int D, int M, int LL>
 hipError_t launch_solo_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_fwd_kernel<BL, D, M>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_fwd_kernel<BL, D, M, LL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((solo_fwd_kernel<BL, D, M>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+    hipLaunchKernelGGL((solo_fwd_kernel<BL, D, M, LL>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     return hipGetLastError();
 }
 
-template <int BL, int D, int M, int PHASE>
+template <int BL, int D, int M, int PHASE, int LL>
 hipError_t launch_solo_bwd_phase(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M, PHASE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M, PHASE, LL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((solo_bwd_kernel<BL, D, M, PHASE>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+    hipLaunchKernelGGL((solo_bwd_kernel<BL, D, M, PHASE, LL>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     return hipGetLastError();
 }
 
-template <int BL, int D, int M>
+template <int BL, int D, int M, int LL>
 hipError_t launch_solo_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    if (a.lk_phase == 0) return launch_solo_bwd_phase<BL, D, M, 0>(a, grid, lds, st);
+    if (a.lk_phase == 0) return launch_solo_bwd_phase<BL, D, M, 0, LL>(a, grid, lds, st);
     // the halves need the per-pair places of checkpoints and bottom rows
     if (!a.lk_keep || a.keep_len != (long)kWave * (1 << BL) + (long)a.lk_NT * (1 << BL) + 2) return hipErrorInvalidValue;
-    if (a.lk_phase == 1) return launch_solo_bwd_phase<BL, D, M, 1>(a, grid, lds, st);
-    if (a.lk_phase == 2) return launch_solo_bwd_phase<BL, D, M, 2>(a, grid, lds, st);
+    if (a.lk_phase == 1) return launch_solo_bwd_phase<BL, D, M, 1, LL>(a, grid, lds, st);
+    if (a.lk_phase == 2) return launch_solo_bwd_phase<BL, D, M, 2, LL>(a, grid, lds, st);
     return hipErrorInvalidValue;
 }
 
-template <int BL, int D>
+template <int BL, int D, int LL>
 hipError_t launch_solo_m(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     if (a.lk_M > solo_max_rows(backward, BL, D)) return hipErrorInvalidValue;
     if (backward) {
-        if (a.lk_M == 1) return launch_solo_bwd<BL, D, 1>(a, grid, lds, st);
-        if constexpr (solo_max_rows(true, BL, D) >= 2) return launch_solo_bwd<BL, D, 2>(a, grid, lds, st);
+        if (a.lk_M == 1) return launch_solo_bwd<BL, D, 1, LL>(a, grid, lds, st);
+        if constexpr (solo_max_rows(true, BL, D) >= 2) return launch_solo_bwd<BL, D, 2, LL>(a, grid, lds, st);
     } else {
-        if (a.lk_M == 1) return launch_solo_fwd<BL, D, 1>(a, grid, lds, st);
-        if constexpr (solo_max_rows(false, BL, D) >= 2) return launch_solo_fwd<BL, D, 2>(a, grid, lds, st);
+        if (a.lk_M == 1) return launch_solo_fwd<BL, D, 1, LL>(a, grid, lds, st);
+        if constexpr (solo_max_rows(false, BL, D) >= 2) return launch_solo_fwd<BL, D, 2, LL>(a, grid, lds, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// lead-lag form of the sweep (SweepArgs::ll): inside the blocks (1) for blocks that hold every refined cell of a pair
+// of increments, above them (2) otherwise
+template <int BL, int D>
+hipError_t launch_solo_ll(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.ll == 0) return launch_solo_m<BL, D, 0>(backward, a, grid, lds, st);
+    if constexpr (BL >= 1) {
+        if (a.ll == 1 && a.rs1 == 0 && a.rs2 == 0) return launch_solo_m<BL, D, 1>(backward, a, grid, lds, st);
+    }
+    if constexpr (BL == kMaxBL) {
+        if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_solo_m<BL, D, 2>(backward, a, grid, lds, st);
     }
     return hipErrorInvalidValue;
 }
@@ -417,14 +428,14 @@ hipError_t launch_solo_bl(bool backward, int DT, const SweepArgs& a, int grid, s
 {
     switch (DT) {
 #ifndef SK_ONLY_C2   /* development builds instantiate a single shape */
-        case 2: return launch_solo_m<BL, 2>(backward, a, grid, lds, st);
-        case 4: return launch_solo_m<BL, 4>(backward, a, grid, lds, st);
-        case 5: return launch_solo_m<BL, 5>(backward, a, grid, lds, st);
-        case 6: return launch_solo_m<BL, 6>(backward, a, grid, lds, st);
-        case 8: return launch_solo_m<BL, 8>(backward, a, grid, lds, st);
+        case 2: return launch_solo_ll<BL, 2>(backward, a, grid, lds, st);
+        case 4: return launch_solo_ll<BL, 4>(backward, a, grid, lds, st);
+        case 5: return launch_solo_ll<BL, 5>(backward, a, grid, lds, st);
+        case 6: return launch_solo_ll<BL, 6>(backward, a, grid, lds, st);
+        case 8: return launch_solo_ll<BL, 8>(backward, a, grid, lds, st);
 #endif
-        case 3: return launch_solo_m<BL, 3>(backward, a, grid, lds, st);
-        case 16: return launch_solo_m<BL, 16>(backward, a, grid, lds, st);
+        case 3: return launch_solo_ll<BL, 3>(backward, a, grid, lds, st);
+        case 16: return launch_solo_ll<BL, 16>(backward, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }

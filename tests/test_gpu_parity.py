@@ -218,7 +218,7 @@ def test_short_paths_with_many_channels_stay_solo():
     rng = np.random.default_rng(78)
     X = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (nx, L, d)), axis=1)
     Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (ny, L, d)), axis=1)
-    assert "solo_bwd_kernel<0, 16, 1, 0>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
+    assert "solo_bwd_kernel<0, 16, 1, 0, 0>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
     W = workloads.upstream_weights(61, (nx, ny))
     K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), 0, 0, 0)
     torch.cuda.synchronize()
@@ -355,6 +355,98 @@ def test_lead_lag_gram():
     assert none is None
     check_values(host(Kxx), Kxr, torch.float64, "K(X,X)")
     check_grads(host(gXX), gXXr, torch.float64, "grad_X total")
+
+
+def lead_lag_form(op, B, M, L1, L2, d, lam1, lam2, flags):
+    desc = sk.sigkernel_describe(op, B, M, L1, L2, d, lam1, lam2, flags, sk.SK_F64)
+    return desc.split("lead_lag_form=", 1)[1].split(" ", 1)[0], desc
+
+
+# The lead-lag form of the sweep: the grid of the original increments with one more level of refinement, whose diagonal
+# quadrants carry p and whose other two carry the time constant alone.  The level lies inside the blocks for dyadic
+# orders 0 and 1 (blocks of 2 x 2 and 4 x 4 cells) and above them from order 2 on; one or two block rows per lane;
+# with and without the time channel (whose constant the off-diagonal quadrants keep); float callers.
+@pytest.mark.parametrize("B,L1,L2,d,lam,flags,dtype", [
+    (1300, 30, 25, 4, 0, LL, torch.float64),
+    (1300, 100, 90, 3, 0, LL | 1, torch.float64),       # two block rows per lane
+    (1300, 24, 31, 2, 1, LL, torch.float32),
+    (1300, 40, 50, 5, 1, LL | 1, torch.float64),
+    (1300, 20, 22, 3, 2, LL | 1, torch.float64),        # the level above the blocks
+    (1100, 9, 12, 16, 3, LL, torch.float64),
+    (1300, 2, 2, 3, 0, LL, torch.float64),              # one increment each: a single block
+    (1300, 60, 3, 6, 1, LL | 1, torch.float64),
+])
+def test_lead_lag_checkerboard_form_pairs(B, L1, L2, d, lam, flags, dtype):
+    form, desc = lead_lag_form(sk.SK_OP_BWD, B, 0, L1, L2, d, lam, lam, flags)
+    print(desc, flush=True)
+    assert form == "checkerboard"
+    rng = np.random.default_rng(910 + L1 + d)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L1) ** 0.5, (B, L1, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L2) ** 0.5, (B, L2, d)), axis=1)
+    Xr, Yr = rounded(X, dtype), rounded(Y, dtype)
+    gk = workloads.upstream_weights(67, (B,))
+    kf = sk.sigkernel_fwd(dev(X, dtype), dev(Y, dtype), lam, lam, flags)
+    k, gx, gy = sk.sigkernel_bwd(dev(X, dtype), dev(Y, dtype), dev(gk, dtype), lam, lam, flags)
+    torch.cuda.synchronize()
+    kr, gxr, gyr = oracle.bwd(Xr, Yr, rounded(gk, dtype), lam, lam, flags)
+    check_values(host(kf), kr, dtype, "k (forward only)")
+    check_values(host(k), kr, dtype, "k")
+    check_grads(host(gx), gxr, dtype, "grad_x")
+    check_grads(host(gy), gyr, dtype, "grad_y")
+
+
+@pytest.mark.parametrize("lam,flags", [(0, LL), (1, LL | 1), (2, LL)])
+def test_lead_lag_checkerboard_form_gram(lam, flags):
+    nx, ny, L, d = 40, 36, 28, 3
+    assert lead_lag_form(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, lam, lam, flags)[0] == "checkerboard"
+    rng = np.random.default_rng(96 + lam)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (nx, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L) ** 0.5, (ny, L, d)), axis=1)
+    W = workloads.upstream_weights(68, (nx, ny))
+    Kf = sk.sigkernel_gram(dev(X), dev(Y), None, lam, lam, flags)
+    K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), lam, lam, flags)
+    x = dev(X)
+    Ws = workloads.upstream_weights(69, (nx, nx))
+    Kxx, gXX, none = sk.sigkernel_gram(x, x, dev(Ws), lam, lam, flags)   # the pairs n <= m only
+    torch.cuda.synchronize()
+    Kr, gXr, gYr = oracle.gram(X, Y, W, lam, lam, flags)
+    check_values(host(Kf), Kr, torch.float64, "K (forward only)")
+    check_values(host(K), Kr, torch.float64, "K")
+    check_grads(host(gX), gXr, torch.float64, "grad_X")
+    check_grads(host(gY), gYr, torch.float64, "grad_Y")
+    Kxr, gXXr, _ = oracle.gram(X, X, Ws, lam, lam, flags)
+    assert none is None
+    check_values(host(Kxx), Kxr, torch.float64, "K(X,X)")
+    check_grads(host(gXX), gXXr, torch.float64, "grad_X total")
+
+
+def test_lead_lag_with_unequal_dyadic_orders_takes_the_transformed_increments():
+    assert lead_lag_form(sk.SK_OP_BWD, 1300, 0, 20, 20, 3, 0, 2, LL)[0] == "transformed_increments"
+    assert lead_lag_form(sk.SK_OP_BWD, 1300, 0, 20, 20, 3, 1, 1, 0)[0] == "none"
+
+
+@pytest.mark.parametrize("lam,flags", [(0, LL), (1, LL | 1), (2, LL | 1)])
+def test_lead_lag_checkerboard_form_with_large_increments(lam, flags):
+    # pairs whose inverse recurrence drifts are solved once more by the replay kernel, in its lead-lag form
+    B, L1, L2, d = 1300, 14, 12, 3
+    assert lead_lag_form(sk.SK_OP_BWD, B, 0, L1, L2, d, lam, lam, flags)[0] == "checkerboard"
+    rng = np.random.default_rng(7300 + lam)
+    dX = rng.normal(0.0, (1.0 / (d * L1)) ** 0.5, (B, L1, d))
+    dY = rng.normal(0.0, (1.0 / (d * L2)) ** 0.5, (B, L2, d))
+    big = 2.2 * 2 ** lam
+    wild = np.arange(0, B, 13)
+    dX[wild, 1::3, :] = rng.choice([-big, big], size=dX[wild, 1::3, :].shape) / d ** 0.5
+    dY[wild, 1::3, :] = rng.choice([-big, big], size=dY[wild, 1::3, :].shape) / d ** 0.5
+    X, Y = np.cumsum(dX, axis=1), np.cumsum(dY, axis=1)
+    gk = workloads.upstream_weights(74, (B,))
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, lam, lam, flags)
+    assert np.all(np.isfinite(kr))
+    k, gx, gy, n = pairs_backward_with_ws(X, Y, gk, lam, lam, flags)
+    print("lead-lag, order %d: %d of %d pairs solved once more; |k| up to %.3g" % (lam, n, B, np.abs(kr).max()), flush=True)
+    assert 0 < n <= len(wild)
+    check_values(host(k), kr, torch.float64, "k")
+    check_rows(host(gx), gxr, torch.float64, "grad_x")
+    check_rows(host(gy), gyr, torch.float64, "grad_y")
 
 
 # ------------------------------------------------------------------ autograd over the C ABI (Section 1)
