@@ -205,7 +205,8 @@ int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_m
  * the backward pass, kept for the backward call; 2: its reverse half; 0: neither); lead_lag_form (none,
  * checkerboard: the grid of the caller's increments swept with one more level of refinement whose off-diagonal
  * quadrants carry no increment product, or transformed_increments: the increments of the transformed paths
- * written out and swept as they are).  Same arguments as sigkernel_workspace_bytes.
+ * written out and swept as they are); second_launch_lds_bytes (backward calls: LDS per workgroup of the launch
+ * that solves drifted pairs once more).  Same arguments as sigkernel_workspace_bytes.
  * Pure host arithmetic: no GPU call.  Returns SK_OK or a negative error code.
  */
 int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2, int64_t d, int lam1, int lam2,

@@ -120,7 +120,7 @@ Layout make_layout(bool backward, bool gram, bool symmetric, int64_t nx, int64_t
     if ((flags & SK_FLAG_LEAD_LAG) && lam1 == lam2) {
         l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1 + 1, lam2 + 1, io_elem, uncompute, keep,
                             false, true);
-        native = l.p.valid && l.p.solo;
+        native = l.p.valid && (l.p.solo || l.p.lock || l.p.band);
     }
     if (native) {
         l.ll = 2;
@@ -722,18 +722,19 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         }
     }
     const sk::Plan& p = lay.p;
-    char kern[96];
+    char kern[128];
     int threads;
     const char* mode;
     if (p.band) {
         mode = "band";
         // backward: two launches, the forward sweep with checkpoints and then the reverse sweep (the larger one)
-        if (phase == 1) std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true>", p.BL, p.DT);
-        else if (phase == 2) std::snprintf(kern, sizeof(kern), "band_rev_kernel<%d, %d>", p.BL, p.DT);
+        if (phase == 1) std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true, %d>", p.BL, p.DT, p.ll);
+        else if (phase == 2) std::snprintf(kern, sizeof(kern), "band_rev_kernel<%d, %d, %d>", p.BL, p.DT, p.ll);
         else if (backward)
-            std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true>+band_rev_kernel<%d, %d>", p.BL, p.DT, p.BL, p.DT);
+            std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, true, %d>+band_rev_kernel<%d, %d, %d>", p.BL, p.DT,
+                          p.ll, p.BL, p.DT, p.ll);
         else
-            std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, false>", p.BL, p.DT);
+            std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, false, %d>", p.BL, p.DT, p.ll);
         threads = (sk::kBandStrips + 1) * sk::kWave;
     } else if (p.tile) {
         mode = "tile";
@@ -747,8 +748,9 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.lock) {
         mode = "lock-step";
-        if (backward || phase) std::snprintf(kern, sizeof(kern), "lock_bwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase);
-        else std::snprintf(kern, sizeof(kern), "lock_fwd_kernel<%d, %d, %d>", p.BL, p.DT, p.lk_M);
+        if (backward || phase)
+            std::snprintf(kern, sizeof(kern), "lock_bwd_kernel<%d, %d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase, p.ll);
+        else std::snprintf(kern, sizeof(kern), "lock_fwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, p.ll);
         threads = (p.lk_ns == 1 ? 3 : (p.lk_ns == 2 ? 8 : 12)) * sk::kWave;
     } else {
         const char* base = !backward ? "sweep_fwd" : (p.uncompute ? "sweep_bwdu" : "sweep_bwd");
@@ -760,11 +762,12 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     const bool fused = p.lock && !gram && dt == SK_F64 && lay.ll != 1;
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
-                  "kept_sweep_half=%d lead_lag_form=%s workspace_bytes=%zu drifted_pairs_counter_at=%zu",
+                  "kept_sweep_half=%d lead_lag_form=%s second_launch_lds_bytes=%zu workspace_bytes=%zu "
+                  "drifted_pairs_counter_at=%zu",
                   mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
                   (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
                   fused ? 1 : 0, phase, lay.ll == 0 ? "none" : (lay.ll == 1 ? "transformed_increments" : "checkerboard"),
-                  lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
+                  (lay.has_sc && backward && phase != 1) ? lay.sc.lds_bytes : (size_t)0, lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
     return SK_OK;
 }
 

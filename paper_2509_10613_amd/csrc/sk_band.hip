@@ -69,9 +69,9 @@ __device__ __forceinline__ int wait_progress(const int* ctr, int want, int limit
     return v;
 }
 
-template <int BL, int D>
+template <int BL, int D, int LL>
 struct Band {
-    using LK = Lock<BL, D, 1>;
+    using LK = Lock<BL, D, 1, LL>;
     static constexpr int C = LK::C, DSc = LK::DSc;
     static constexpr int RM = kBandRing - 1, YM = kBandYRing - 1;
 
@@ -91,12 +91,12 @@ struct Band {
 // ------------------------------------------------------------------------------------------------
 // forward (CKPT: phase 1 of the backward pass: checkpoints and every strip's bottom row go to global memory)
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D, bool CKPT>
+template <int BL, int D, bool CKPT, int LL>
 __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using BD = Band<BL, D>;
-    using LK = Lock<BL, D, 1>;
+    using BD = Band<BL, D, LL>;
+    using LK = Lock<BL, D, 1, LL>;
     constexpr int C = LK::C, DSc = LK::DSc, CH = kLockCH1, NVC = LK::NVC, SPB = kBandStrips;
     constexpr int RM = BD::RM, YM = BD::YM;
     const int lane = threadIdx.x & 63;
@@ -158,15 +158,14 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 if (i + 1 < CH) BD::template fetch<EDGE>(cf, yring, T0 + i + 1, J[(i + 1) & 1], b[(i + 1) & 1], y[(i + 1) & 1]);
-                real Ac[1], Bc[1];
-                const real p = cf.template inner<EDGE>(0, J[i & 1], y[i & 1]);
-                const real q2 = p * p;
-                Bc[0] = fma(q2, -1.0 / 12.0, 1.0);
-                Ac[0] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+                real Ac[1], Bc[1], A0[1], B0[1];
+                LK::coef_fwd(cf.template inner<EDGE>(0, J[i & 1], y[i & 1]), Ac[0], Bc[0]);
+                if constexpr (LL == 1) LK::coef_fwd(cf.template inner_off<EDGE>(0, J[i & 1]), A0[0], B0[0]);
+                else { A0[0] = Ac[0]; B0[0] = Bc[0]; }
                 real recv[C];
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(f.bot[cc], edge[i][cc]);
-                f.step(recv, Ac, Bc);
+                f.step(recv, Ac, Bc, A0, B0);
                 if (lane == kWave - 1) {
                     const int Jw = T0 + i - (kWave - 1);
                     if (!EDGE || Jw >= 0) {
@@ -293,12 +292,12 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_fwd_kernel(
 // top edges to the strip above.  dF/dp of every block is mapped to the increments at once: the x side in the
 // lane's registers, the y side in a ring of accumulators in LDS that the data-moving wave flushes to global
 // memory once all strips of the band have passed a column.
-template <int BL, int D>
+template <int BL, int D, int LL>
 __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using BD = Band<BL, D>;
-    using LK = Lock<BL, D, 1>;
+    using BD = Band<BL, D, LL>;
+    using LK = Lock<BL, D, 1, LL>;
     constexpr int C = LK::C, RR = LK::RR, DSc = LK::DSc, CH = kLockCH2, S = kLockS, NVC = LK::NVC, SPB = kBandStrips;
     constexpr int NVS = RR + 1 + C;
     constexpr int RM = BD::RM, YM = BD::YM;
@@ -385,21 +384,19 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(
 #pragma unroll
             for (int i = CH - 1; i >= 0; --i) {
                 if (i >= 1) BD::template fetch<EDGE>(cf, yring, T0 + i - 1, J[(i - 1) & 1], b[(i - 1) & 1], y[(i - 1) & 1]);
-                real Ac[1], Bc[1], iB[1], p6[1], accP[1];
+                real Ac[1], Bc[1], iB[1], p6[1], A0[1], B0[1], iB0[1], accP[1];
                 const real p = cf.template inner<EDGE>(0, J[i & 1], y[i & 1]);
-                const real q2 = p * p;
-                Bc[0] = fma(q2, -1.0 / 12.0, 1.0);
-                Ac[0] = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                const real r = __builtin_amdgcn_rcp(Bc[0]);
-                iB[0] = fma(fma(-Bc[0], r, 1.0), r, r);
+                LK::coef_rev(p, Ac[0], Bc[0], iB[0]);
                 p6[0] = p * (1.0 / 6.0);
+                if constexpr (LL == 1) LK::coef_rev(cf.template inner_off<EDGE>(0, J[i & 1]), A0[0], B0[0], iB0[0]);
+                else { A0[0] = Ac[0]; B0[0] = Bc[0]; iB0[0] = iB[0]; }
                 real recv[C], recvk[C];
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) {
                     recv[cc] = wave_from_below_or(rv.up[cc], ea[i][cc]);
                     recvk[cc] = wave_from_below_or(rv.ktop[cc], ek[i][cc]);
                 }
-                rv.step(recv, recvk, Ac, Bc, iB, p6, accP);
+                rv.step(recv, recvk, Ac, Bc, iB, p6, A0, B0, iB0, accP);
                 if (lane == 0) {
                     const int J0 = T0 + i;
                     if (!EDGE || J0 < nb) {
@@ -409,7 +406,8 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(
                 }
                 // the linear map of Section 3.4 (outside the grid dF/dp is not zero on the left: the adjoint has left
                 // the grid there; rows above the grid have zero increments and are never flushed)
-                const real gp = (!EDGE || (unsigned)J[i & 1] < (unsigned)cf.nbl[0]) ? accP[0] : 0.0;
+                // (lead-lag: blocks off the diagonal of that level have no increment)
+                const real gp = ((!EDGE || (unsigned)J[i & 1] < (unsigned)cf.nbl[0]) && !cf.off_block(0, J[i & 1])) ? accP[0] : 0.0;
                 if (a.want_gx) {
 #pragma unroll
                     for (int c = 0; c < D; ++c) gacc[c] = fma(gp, y[i & 1][c], gacc[c]);
@@ -648,7 +646,7 @@ __global__ __launch_bounds__((kBandStrips + 1) * kWave, 1) void band_rev_kernel(
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D>
+template <int BL, int D, int LL>
 hipError_t launch_band_t(int phase, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     const dim3 block((kBandStrips + 1) * kWave);
@@ -657,36 +655,51 @@ hipError_t launch_band_t(int phase, const SweepArgs& a, int grid, size_t lds, hi
     };
     hipError_t e;
     if (phase == 0) {
-        e = prep(reinterpret_cast<const void*>(&band_fwd_kernel<BL, D, false>));
+        e = prep(reinterpret_cast<const void*>(&band_fwd_kernel<BL, D, false, LL>));
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((band_fwd_kernel<BL, D, false>), dim3(grid), block, lds, st, a);
+        hipLaunchKernelGGL((band_fwd_kernel<BL, D, false, LL>), dim3(grid), block, lds, st, a);
     } else {
         // backward: the forward sweep with checkpoints, then the reverse sweep with the bands in reverse order
         // (phase 2 / 3: one of the two only, for a forward sweep that is kept for the backward call)
-        e = prep(reinterpret_cast<const void*>(&band_fwd_kernel<BL, D, true>));
+        e = prep(reinterpret_cast<const void*>(&band_fwd_kernel<BL, D, true, LL>));
         if (e != hipSuccess) return e;
-        e = prep(reinterpret_cast<const void*>(&band_rev_kernel<BL, D>));
+        e = prep(reinterpret_cast<const void*>(&band_rev_kernel<BL, D, LL>));
         if (e != hipSuccess) return e;
         if (phase != 3) {
-            hipLaunchKernelGGL((band_fwd_kernel<BL, D, true>), dim3(grid), block, lds, st, a);
+            hipLaunchKernelGGL((band_fwd_kernel<BL, D, true, LL>), dim3(grid), block, lds, st, a);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
-        if (phase != 2) hipLaunchKernelGGL((band_rev_kernel<BL, D>), dim3(grid), block, lds, st, a);
+        if (phase != 2) hipLaunchKernelGGL((band_rev_kernel<BL, D, LL>), dim3(grid), block, lds, st, a);
     }
     return hipGetLastError();
+}
+
+// lead-lag form of the sweep (SweepArgs::ll): inside the blocks (1) for blocks that hold every refined cell of a pair
+// of increments, above them (2) otherwise
+template <int BL, int D>
+hipError_t launch_band_ll(int phase, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.ll == 0) return launch_band_t<BL, D, 0>(phase, a, grid, lds, st);
+    if constexpr (BL >= 1) {
+        if (a.ll == 1 && a.rs1 == 0 && a.rs2 == 0) return launch_band_t<BL, D, 1>(phase, a, grid, lds, st);
+    }
+    if constexpr (BL == kMaxBL) {
+        if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_band_t<BL, D, 2>(phase, a, grid, lds, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 template <int BL>
 hipError_t launch_band_bl(int phase, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     switch (DT) {
-        case 2: return launch_band_t<BL, 2>(phase, a, grid, lds, st);
-        case 3: return launch_band_t<BL, 3>(phase, a, grid, lds, st);
-        case 4: return launch_band_t<BL, 4>(phase, a, grid, lds, st);
-        case 5: return launch_band_t<BL, 5>(phase, a, grid, lds, st);
-        case 6: return launch_band_t<BL, 6>(phase, a, grid, lds, st);
-        case 8: return launch_band_t<BL, 8>(phase, a, grid, lds, st);
+        case 2: return launch_band_ll<BL, 2>(phase, a, grid, lds, st);
+        case 3: return launch_band_ll<BL, 3>(phase, a, grid, lds, st);
+        case 4: return launch_band_ll<BL, 4>(phase, a, grid, lds, st);
+        case 5: return launch_band_ll<BL, 5>(phase, a, grid, lds, st);
+        case 6: return launch_band_ll<BL, 6>(phase, a, grid, lds, st);
+        case 8: return launch_band_ll<BL, 8>(phase, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -258,7 +258,7 @@ struct Lock {
                     for (int m = 0; m < M; ++m) {
                         // outside the grid dF/dp is not zero on the left (the adjoint has left the grid there);
                         // rows above the grid are never flushed
-                        const real gp = (!EDGE || (unsigned)J[u] < (unsigned)nbl[m]) ? gv[u][m] : 0.0;
+                        const real gp = ((!EDGE || (unsigned)J[u] < (unsigned)nbl[m]) && !off_block(m, J[u])) ? gv[u][m] : 0.0;
 #pragma unroll
                         for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp, y[u][c], gacc[m][c]);
                     }
@@ -295,7 +295,7 @@ struct Lock {
                     real v = 0.0;
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
-                        const real gp = (!EDGE || (unsigned)J < (unsigned)nbl[m]) ? gv[i][m] : 0.0;
+                        const real gp = ((!EDGE || (unsigned)J < (unsigned)nbl[m]) && !off_block(m, J)) ? gv[i][m] : 0.0;
                         v = m == 0 ? gp * dxr[0][c] : fma(gp, dxr[m][c], v);
                     }
                     t[c] = v;
@@ -315,6 +315,40 @@ struct Lock {
                     for (int c = 0; c < D; ++c) lds_atomic_add(gq + c, t[c]);
                 }
             }
+        }
+    };
+
+    // ---------------- LL = 1: coefficients of the off-diagonal quadrants, kept by the stencil wave ----------------
+    // Their p is the time channel's constant inside the grid and 0 outside it, where A = B = 1 keep the boundary
+    // value: above the grid (block rows that pad the first strip) and left of it (a lane that has not started).
+    // Right of the grid nothing depends on them (both sweeps use the same ones there).
+    struct Off {
+        real A0c, B0c, iB0c;
+        int tmin[M];   // first macro-step of the strip in which the lane's block m is inside the grid
+
+        __device__ __forceinline__ void setup(const SweepArgs& a, int strip, int lane)
+        {
+            coef_rev(a.tc, A0c, B0c, iB0c);
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int I = (strip * kWave + lane) * M + m - a.lk_padb;
+                tmin[m] = I >= 0 ? lane : 0x7fffffff;
+            }
+        }
+        __device__ __forceinline__ void at(int T, real (&A0)[M], real (&B0)[M]) const
+        {
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const bool in = T >= tmin[m];
+                A0[m] = in ? A0c : 1.0;
+                B0[m] = in ? B0c : 1.0;
+            }
+        }
+        __device__ __forceinline__ void at(int T, real (&A0)[M], real (&B0)[M], real (&iB0)[M]) const
+        {
+            at(T, A0, B0);
+#pragma unroll
+            for (int m = 0; m < M; ++m) iB0[m] = T >= tmin[m] ? iB0c : 1.0;
         }
     };
 
@@ -367,7 +401,7 @@ struct Lock {
         }
         // chunk of CH1 macro-steps starting at T0
         __device__ __forceinline__ void chunk(int T0, int lane, const SK_LDS real* half, const SK_LDS real* rowprev,
-                                              SK_LDS real* rowcur, SK_LDS real* dump)
+                                              SK_LDS real* rowcur, SK_LDS real* dump, const Off& off)
         {
             const SK_LDS real* cp = half + lane * 2;
             const SK_LDS real* ip = rowprev + T0 * C + 1;                          // lane 0's top edge
@@ -392,7 +426,13 @@ struct Lock {
                 real recv[C];
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) recv[cc] = wave_from_above_or(bot[cc], edge[i][cc]);
-                step(recv, Ac, Bc);
+                if constexpr (LL == 1) {
+                    real A0[M], B0[M];
+                    off.at(T0 + i, A0, B0);
+                    step(recv, Ac, Bc, A0, B0);
+                } else {
+                    step(recv, Ac, Bc);
+                }
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) op[i * C + cc] = bot[cc];
             }
@@ -486,7 +526,7 @@ struct Lock {
         // chunk of CH2 mirrored macro-steps T0 + CH2 - 1 down to T0
         __device__ __forceinline__ void chunk(int T0, int lane, const SK_LDS real* half, const SK_LDS real* arow_in,
                                               const SK_LDS real* krow, SK_LDS real* arow_out, SK_LDS real* dump,
-                                              SK_LDS real* gphalf)
+                                              SK_LDS real* gphalf, const Off& off)
         {
             const SK_LDS real* cp = half + lane * 2;                    // see produce_rev_t for the layout
             const SK_LDS real* ap = arow_in + (T0 - (kWave - 1)) * C;   // feeds of the strip's last lane
@@ -519,7 +559,13 @@ struct Lock {
                     recv[cc] = wave_from_below_or(up[cc], ea[i][cc]);
                     recvk[cc] = wave_from_below_or(ktop[cc], ek[i][cc]);
                 }
-                step(recv, recvk, Ac, Bc, iB, p6, accP);
+                if constexpr (LL == 1) {
+                    real A0[M], B0[M], iB0[M];
+                    off.at(T0 + i, A0, B0, iB0);
+                    step(recv, recvk, Ac, Bc, iB, p6, A0, B0, iB0, accP);
+                } else {
+                    step(recv, recvk, Ac, Bc, iB, p6, accP);
+                }
 #pragma unroll
                 for (int cc = 0; cc < C; ++cc) op[i * C + cc] = up[cc];
                 gp_store(gphalf, i, lane, accP);

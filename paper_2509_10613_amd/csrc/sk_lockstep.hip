@@ -122,11 +122,11 @@ __device__ __forceinline__ void stage_y(const SweepArgs& a, long yi, SK_LDS real
 // ------------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D, int M>
+template <int BL, int D, int M, int LL>
 __global__ __launch_bounds__(12 * kWave) void lock_fwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using LK = Lock<BL, D, M>;
+    using LK = Lock<BL, D, M, LL>;
     constexpr int C = LK::C, CH = LK::CH1;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -152,14 +152,16 @@ __global__ __launch_bounds__(12 * kWave) void lock_fwd_kernel(SweepArgs a)
 
     typename LK::Fwd f;
     typename LK::Coef cf;
+    typename LK::Off off;   // lead-lag blocks: the stencil wave's own coefficients of the off-diagonal quadrants
     constexpr int kSplit = 1;   // two coefficient waves per strip
     if (role == kRoleCoef || role == kRoleAux) cf.setup(a, strip, lane, dxp, l.y);
     else f.init();
+    off.setup(a, strip, lane);
 
     for (int g = -1; g < niter; ++g) {
         const int lc = g - strip * lagc;
         if (role == kRoleStencil) {
-            if (lc >= 0 && lc < nck) f.chunk(lc * CH, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump);
+            if (lc >= 0 && lc < nck) f.chunk(lc * CH, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump, off);
         } else if (role == kRoleCoef || (kSplit && role == kRoleAux)) {
             const int hc = lc + 1;
             if (hc >= 0 && hc < nck)
@@ -177,11 +179,11 @@ __global__ __launch_bounds__(12 * kWave) void lock_fwd_kernel(SweepArgs a)
 // PHASE 0: the whole backward call.  PHASE 1 / 2: its two halves as launches of their own (a forward call whose
 // sweep is kept, and the backward call that follows it): what crosses from phase 1 to phase 2 is the checkpoints,
 // which are in global memory anyway, and the hand-over rows, which phase 1 then copies out and phase 2 copies in.
-template <int BL, int D, int M, int PHASE>
+template <int BL, int D, int M, int PHASE, int LL>
 __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    using LK = Lock<BL, D, M>;
+    using LK = Lock<BL, D, M, LL>;
     constexpr int C = LK::C, RR = LK::RR, NVC = LK::NVC, CH1 = LK::CH1, CH2 = LK::CH2;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -232,8 +234,10 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
     SK_LDS real* arow_out = l.arows + strip * rowlen + LK::PADF;               // read by the strip above
 
     typename LK::Coef cf;
+    typename LK::Off off;   // lead-lag blocks: the stencil wave's own coefficients of the off-diagonal quadrants
     constexpr int kSplit = 1;   // two coefficient waves per strip in the forward phase
     if (role == kRoleCoef || role == kRoleAux) cf.setup(a, strip, lane, dxp, l.y);
+    off.setup(a, strip, lane);
 
     // ---- phase 1: forward with checkpoints ----
     if constexpr (PHASE != 2) {
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
             if (stencil) {
                 if (lc >= 0 && lc < nck) {
                     f.store_ckpt(ckpt + (long)lc * NVC * kWave);   // kLockS == CH1: one checkpoint per chunk
-                    f.chunk(lc * CH1, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump);
+                    f.chunk(lc * CH1, lane, l.cring + (lc & 1) * LK::CR1, rowprev, rowcur, l.dump, off);
                     if (lc == nck - 1) f.store_ckpt(ckpt + (long)nck * NVC * kWave);
                 }
             } else if (role == kRoleCoef || (kSplit && role == kRoleAux)) {
@@ -328,7 +332,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
                 for (int i = 0; i < C; ++i) rv.ktop[i] = cv[RR + 1 + i];
             }
             rv.chunk(fc * CH2, lane, l.cring + (rc & 1) * LK::CR2, arow_in, rowcur, arow_out, l.dump,
-                     l.gp + (rc & 1) * LK::GPH);
+                     l.gp + (rc & 1) * LK::GPH, off);
         };
         for (int g = -1; g <= niter; ++g) {
             const int rc = g - rs * lagc;
@@ -444,58 +448,73 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-template <int BL, int D, int M>
+template <int BL, int D, int M, int LL>
 hipError_t launch_lock_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M, LL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((lock_fwd_kernel<BL, D, M>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
+    hipLaunchKernelGGL((lock_fwd_kernel<BL, D, M, LL>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
     return hipGetLastError();
 }
 
-template <int BL, int D, int M, int PHASE>
+template <int BL, int D, int M, int PHASE, int LL>
 hipError_t launch_lock_bwd_phase(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M, PHASE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M, PHASE, LL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M, PHASE>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
+    hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M, PHASE, LL>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
     return hipGetLastError();
 }
 
-template <int BL, int D, int M>
+template <int BL, int D, int M, int LL>
 hipError_t launch_lock_bwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    if (a.lk_phase == 0) return launch_lock_bwd_phase<BL, D, M, 0>(a, grid, lds, st);
+    if (a.lk_phase == 0) return launch_lock_bwd_phase<BL, D, M, 0, LL>(a, grid, lds, st);
     // the halves exist for the calls that work on the caller's arrays, and need the rows' place in global memory
     if (!a.fused || !a.lk_keep || !a.keep_tag) return hipErrorInvalidValue;
-    if (a.lk_phase == 1) return launch_lock_bwd_phase<BL, D, M, 1>(a, grid, lds, st);
-    if (a.lk_phase == 2) return launch_lock_bwd_phase<BL, D, M, 2>(a, grid, lds, st);
+    if (a.lk_phase == 1) return launch_lock_bwd_phase<BL, D, M, 1, LL>(a, grid, lds, st);
+    if (a.lk_phase == 2) return launch_lock_bwd_phase<BL, D, M, 2, LL>(a, grid, lds, st);
     return hipErrorInvalidValue;
 }
 
 // Two block rows per lane are only built where the registers allow it (lock_max_rows in sk_plan.h).
-template <int BL, int D>
+template <int BL, int D, int LL>
 hipError_t launch_lock_m(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     if (a.lk_M > lock_max_rows(backward, BL, D)) return hipErrorInvalidValue;
     if (backward) {
         if constexpr (lock_max_rows(true, BL, D) >= 1) {
-            if (a.lk_M == 1) return launch_lock_bwd<BL, D, 1>(a, grid, lds, st);
+            if (a.lk_M == 1) return launch_lock_bwd<BL, D, 1, LL>(a, grid, lds, st);
         }
-        if constexpr (lock_max_rows(true, BL, D) >= 2) return launch_lock_bwd<BL, D, 2>(a, grid, lds, st);
+        if constexpr (lock_max_rows(true, BL, D) >= 2) return launch_lock_bwd<BL, D, 2, LL>(a, grid, lds, st);
     } else {
-        if (a.lk_M == 1) return launch_lock_fwd<BL, D, 1>(a, grid, lds, st);
-        if constexpr (lock_max_rows(false, BL, D) >= 2) return launch_lock_fwd<BL, D, 2>(a, grid, lds, st);
+        if (a.lk_M == 1) return launch_lock_fwd<BL, D, 1, LL>(a, grid, lds, st);
+        if constexpr (lock_max_rows(false, BL, D) >= 2) return launch_lock_fwd<BL, D, 2, LL>(a, grid, lds, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// lead-lag form of the sweep (SweepArgs::ll): inside the blocks (1) for blocks that hold every refined cell of a pair
+// of increments, above them (2) otherwise
+template <int BL, int D>
+hipError_t launch_lock_ll(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (a.ll == 0) return launch_lock_m<BL, D, 0>(backward, a, grid, lds, st);
+    if constexpr (BL >= 1) {
+        if (a.ll == 1 && a.rs1 == 0 && a.rs2 == 0) return launch_lock_m<BL, D, 1>(backward, a, grid, lds, st);
+    }
+    if constexpr (BL == kMaxBL) {
+        if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_lock_m<BL, D, 2>(backward, a, grid, lds, st);
     }
     return hipErrorInvalidValue;
 }
@@ -505,14 +524,14 @@ hipError_t launch_lock_bl(bool backward, int DT, const SweepArgs& a, int grid, s
 {
     switch (DT) {
 #ifndef SK_ONLY_C2   /* development builds instantiate a single shape */
-        case 2: return launch_lock_m<BL, 2>(backward, a, grid, lds, st);
-        case 3: return launch_lock_m<BL, 3>(backward, a, grid, lds, st);
-        case 4: return launch_lock_m<BL, 4>(backward, a, grid, lds, st);
-        case 6: return launch_lock_m<BL, 6>(backward, a, grid, lds, st);
-        case 8: return launch_lock_m<BL, 8>(backward, a, grid, lds, st);
-        case 16: return launch_lock_m<BL, 16>(backward, a, grid, lds, st);
+        case 2: return launch_lock_ll<BL, 2>(backward, a, grid, lds, st);
+        case 3: return launch_lock_ll<BL, 3>(backward, a, grid, lds, st);
+        case 4: return launch_lock_ll<BL, 4>(backward, a, grid, lds, st);
+        case 6: return launch_lock_ll<BL, 6>(backward, a, grid, lds, st);
+        case 8: return launch_lock_ll<BL, 8>(backward, a, grid, lds, st);
+        case 16: return launch_lock_ll<BL, 16>(backward, a, grid, lds, st);
 #endif
-        case 5: return launch_lock_m<BL, 5>(backward, a, grid, lds, st);
+        case 5: return launch_lock_ll<BL, 5>(backward, a, grid, lds, st);
         default: return hipErrorInvalidValue;
     }
 }

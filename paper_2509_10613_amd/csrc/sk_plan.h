@@ -117,6 +117,9 @@ constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between 
 // two), chunks the data-moving wave works ahead, and the bound on its polls of another workgroup's counter.
 constexpr int kBandStrips = 4, kBandRing = 64, kBandYRing = 512, kBandLead = 2, kBandSpin = 1 << 22, kBandSlack = 8, kBandLeadRev = 3;
 
+// Band mode takes over from three strips on (a single band then: measured a little ahead of the cooperative kernels,
+// and it has the lead-lag form of the sweep, which those have not).
+constexpr int kBandMinStrips = 2;
 constexpr int64_t kCoopMaxPairs = 1024;   // above this, one wave per pair already fills the chip
 
 constexpr int kUncomputeS = 8;   // macro-steps between checkpoints when the reverse sweep inverts Eq. (1)
@@ -234,8 +237,19 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
             p.S = kUncomputeS;
             p.nseg = (p.nb + kWave - 1 + p.S - 1) / p.S;
         } else if (backward) {
-            int S = 64;
-            while (S > 4 && used + (size_t)S * ring_step > kLdsPerWave) S >>= 1;
+            auto fit = [&](size_t before) {
+                int S = 64;
+                while (S > 4 && before + (size_t)S * ring_step > kLdsPerWave) S >>= 1;
+                return S;
+            };
+            int S = fit(used);
+            if (used + (size_t)S * ring_step > kLdsPerWave) {
+                // not even the shortest ring fits next to the y increments: these stay in global memory
+                p.y_lds = 0;
+                used = 0;
+                p.ring_off = 0;
+                S = fit(0);
+            }
             p.S = S;
             p.nseg = (p.nb + kWave - 1 + S - 1) / S;   // strips run nb + (lanes-1) macro-steps at most
             used += (size_t)S * ring_step;
@@ -379,7 +393,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
 
     // Band mode: few pairs of long paths.  The strips of a pair are spread over workgroups (bands of kBandStrips
     // strips) that all run at once; chosen when that fills more of the chip than one workgroup per pair does.
-    if (!p.lock && !p.tile && !p.solo && (!backward || p.uncompute) && p.DT >= 2 && p.DT <= 8 && p.ns > kBandStrips &&
+    if (!p.lock && !p.tile && !p.solo && (!backward || p.uncompute) && p.DT >= 2 && p.DT <= 8 && p.ns > kBandMinStrips &&
         !second_chance) {
         const int nbands = (p.ns + kBandStrips - 1) / kBandStrips;
         if (p.npairs * nbands <= kNumCU) {

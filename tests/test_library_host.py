@@ -87,18 +87,18 @@ def test_launch_plan_of_the_five_configurations(lib):
     # c2 (128 pairs, L = 256, order 1): the chip is under-filled -> one workgroup per pair in lock step,
     # two strips of 128 block rows, eight waves, everything resident at once, caller's arrays used directly
     p = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
-    assert p["mode"] == "lock-step" and p["kernel"] == "lock_bwd_kernel<1, 5, 2, 0>"
+    assert p["mode"] == "lock-step" and p["kernel"] == "lock_bwd_kernel<1, 5, 2, 0, 0>"
     assert (p["grid"], p["threads"], p["strips"], p["rows_per_lane"], p["fused"]) == ("128", "512", "2", "2", "1")
     assert int(p["lds_bytes"]) <= 160 * 1024
     p = _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
-    assert p["kernel"] == "lock_fwd_kernel<1, 5, 2>" and p["fused"] == "1"
+    assert p["kernel"] == "lock_fwd_kernel<1, 5, 2, 0>" and p["fused"] == "1"
     assert _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f32)["fused"] == "0"   # float callers are converted
     # a forward sweep kept for the backward call: the two halves of the backward kernel as launches of their own, in
     # the backward call's workspace; launch modes without that form ignore the flags
     KEEP, HAVE = binding.SK_FLAG_KEEP_FORWARD, binding.SK_FLAG_HAVE_FORWARD
     p1 = _plan(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1 | KEEP, f64)
     p2 = _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f64)
-    assert p1["kernel"] == "lock_bwd_kernel<1, 5, 2, 1>" and p2["kernel"] == "lock_bwd_kernel<1, 5, 2, 2>"
+    assert p1["kernel"] == "lock_bwd_kernel<1, 5, 2, 1, 0>" and p2["kernel"] == "lock_bwd_kernel<1, 5, 2, 2, 0>"
     q = lib.sigkernel_workspace_bytes
     assert q(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1 | KEEP, f64) == q(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
     assert int(p1["workspace_bytes"]) == q(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
@@ -115,7 +115,7 @@ def test_launch_plan_of_the_five_configurations(lib):
     assert q(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64) < 1 << 30
     # tile mode keeps its checkpoints in LDS: no such form
     assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, KEEP, f64)["kernel"] == "tile_fwd_kernel<4>"
-    assert _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f32)["kernel"] == "lock_bwd_kernel<1, 5, 2, 0>"
+    assert _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f32)["kernel"] == "lock_bwd_kernel<1, 5, 2, 0, 0>"
     # c1: tiny, one strip: stencil, coefficient and auxiliary wave
     p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
     assert p["mode"] == "lock-step" and p["threads"] == "192" and p["strips"] == "1"
@@ -143,10 +143,10 @@ def test_launch_plan_of_the_five_configurations(lib):
     # c4 (32 pairs, 2047 block rows = 32 strips each): bands of four strips on different compute units, eight
     # bands per pair, all 256 workgroups resident at once; four strip waves and a data-moving wave each
     p = _plan(binding.SK_OP_BWD, 32, 0, 2048, 2048, 8, 2, 2, 0, f64)
-    assert p["mode"] == "band" and p["kernel"] == "band_fwd_kernel<2, 8, true>+band_rev_kernel<2, 8>" and p["grid"] == "256"
+    assert p["mode"] == "band" and p["kernel"] == "band_fwd_kernel<2, 8, true, 0>+band_rev_kernel<2, 8, 0>" and p["grid"] == "256"
     assert p["threads"] == "320" and p["strips"] == "32" and int(p["lds_bytes"]) <= 160 * 1024
     p = _plan(binding.SK_OP_FWD, 32, 0, 2048, 2048, 8, 2, 2, 0, f64)
-    assert p["mode"] == "band" and p["kernel"] == "band_fwd_kernel<2, 8, false>" and p["grid"] == "256"
+    assert p["mode"] == "band" and p["kernel"] == "band_fwd_kernel<2, 8, false, 0>" and p["grid"] == "256"
     # more long pairs than the chip has room for bands: one workgroup per pair, its strips in rounds
     p = _plan(binding.SK_OP_BWD, 64, 0, 2048, 2048, 8, 2, 2, 0, f64)
     assert p["mode"] == "cooperative" and p["grid"] == "64"
@@ -166,8 +166,14 @@ def test_launch_plan_stays_inside_the_hardware_limits(lib):
                     for lam in (0, 1, 2, 3):
                         if ((L - 1) << lam) >= (1 << 14):
                             continue
+                        for flags in (0, binding.SK_FLAG_LEAD_LAG | 1, binding.SK_FLAG_BWD_REPLAY):
+                            if flags & binding.SK_FLAG_LEAD_LAG and ((2 * L - 2) << lam) >= (1 << 14):
+                                continue
+                            p = _plan(op, B, 0, L, max(2, L // 2), d, lam, lam, flags, f64)
+                            assert int(p["lds_bytes"]) <= 160 * 1024, p
+                            # the launch that solves drifted pairs once more (the replay kernel)
+                            assert int(p["second_launch_lds_bytes"]) <= 160 * 1024, p
                         p = _plan(op, B, 0, L, max(2, L // 2), d, lam, lam, 0, f64)
-                        assert int(p["lds_bytes"]) <= 160 * 1024, p
                         assert 64 <= int(p["threads"]) <= 1024 and int(p["threads"]) % 64 == 0, p
                         assert 1 <= int(p["grid"]), p
                         if p["mode"] == "lock-step":
