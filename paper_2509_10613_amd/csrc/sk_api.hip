@@ -106,8 +106,8 @@ struct Layout {
     size_t total = 0;
     // Lead-lag transform (Section 4): 0 not asked for; 1 the plan is that of the transformed paths (2L - 1 points,
     // 2d channels), whose increments the preparation kernel writes out; 2 the plan is that of the caller's paths with
-    // one more dyadic level, swept in its lead-lag form (the kernels of the lock-step, solo and band families have
-    // one, for equal dyadic orders).
+    // one more dyadic level, swept in its lead-lag form (equal dyadic orders; every kernel but the tile kernels has
+    // that form, and such plans never choose those).
     int ll = 0;
 };
 
@@ -120,7 +120,7 @@ Layout make_layout(bool backward, bool gram, bool symmetric, int64_t nx, int64_t
     if ((flags & SK_FLAG_LEAD_LAG) && lam1 == lam2) {
         l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1 + 1, lam2 + 1, io_elem, uncompute, keep,
                             false, true);
-        native = l.p.valid && (l.p.solo || l.p.lock || l.p.band);
+        native = l.p.valid;
     }
     if (native) {
         l.ll = 2;

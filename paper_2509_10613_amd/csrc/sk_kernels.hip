@@ -462,6 +462,70 @@ struct Sweep {
         return accP;
     }
 
+    // One reverse step of the un-compute kernels on one block: e holds the right edge e[*][C] and the bottom edge
+    // e[R][*] on entry and every node on exit; returns the block's dF/dp.
+    __device__ __forceinline__ real uncompute_adjoint(real (&e)[R + 1][C + 1], real p, const real (&recv)[C],
+                                                      real (&accL)[R + 1], real& corner, real (&up)[C]) const
+    {
+        if (a.ll == 1) return uncompute_adjoint_t<true>(e, p, a.tc, recv, accL, corner, up);
+        return uncompute_adjoint_t<false>(e, p, p, recv, accL, corner, up);
+    }
+    // CHK: lead-lag level inside the block (see block_forward_ll and reverse_block_t)
+    template <bool CHK>
+    __device__ __forceinline__ real uncompute_adjoint_t(real (&e)[R + 1][C + 1], real p, real p0, const real (&recv)[C],
+                                                        real (&accL)[R + 1], real& corner, real (&up)[C]) const
+    {
+        const real q2 = p * p;
+        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
+        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
+        real invB = __builtin_amdgcn_rcp(Bc);
+        invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+        if constexpr (!CHK) {
+            block_uncompute(e, Ac, invB);
+            return adjoint_block(e, p, Ac, Bc, recv, accL, corner, up);
+        } else {
+            const real q0 = p0 * p0;
+            const real B0 = fma(q0, -1.0 / 12.0, 1.0);
+            const real A0 = fma(p0, 0.5, fma(q0, 1.0 / 12.0, 1.0));
+            real invB0 = __builtin_amdgcn_rcp(B0);
+            invB0 = fma(fma(-B0, invB0, 1.0), invB0, invB0);
+            const real dA = fma(p, 1.0 / 6.0, 0.5);   // A'(p)
+            const real dB = p * (1.0 / 6.0);          // -B'(p)
+            real gn[R + 1][C + 1];
+#pragma unroll
+            for (int rr = 0; rr <= R; ++rr)
+#pragma unroll
+                for (int cc = 0; cc <= C; ++cc) gn[rr][cc] = 0.0;
+#pragma unroll
+            for (int rr = 1; rr <= R; ++rr) gn[rr][C] = accL[rr];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) gn[R][cc + 1] += recv[cc];
+            gn[0][C] = corner;
+            real accP = 0.0;
+#pragma unroll
+            for (int rr = R - 1; rr >= 0; --rr)
+#pragma unroll
+                for (int cc = C - 1; cc >= 0; --cc) {
+                    const bool off = cell_off(rr, cc);
+                    const real Aq = off ? A0 : Ac, Bq = off ? B0 : Bc, iBq = off ? invB0 : invB;
+                    e[rr][cc] = fma(e[rr + 1][cc] + e[rr][cc + 1], Aq, -e[rr + 1][cc + 1]) * iBq;
+                    const real go = gn[rr + 1][cc + 1];
+                    gn[rr + 1][cc] = fma(go, Aq, gn[rr + 1][cc]);
+                    gn[rr][cc + 1] = fma(go, Aq, gn[rr][cc + 1]);
+                    gn[rr][cc] = fma(-go, Bq, gn[rr][cc]);
+                    if (off) continue;
+                    const real loc = fma(e[rr + 1][cc] + e[rr][cc + 1], dA, e[rr][cc] * dB);
+                    accP = fma(go, loc, accP);
+                }
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) up[cc] = gn[0][cc + 1];
+            corner = gn[0][0];
+#pragma unroll
+            for (int rr = 1; rr <= R; ++rr) accL[rr] = gn[rr][0];
+            return accP;
+        }
+    }
+
     // Steps [T0, T1) of the forward sweep of the current strip, T1 - T0 <= 64 and topc loaded for T0.
     // f(Tstep, active, e) is called after every step.
     template <class F>
@@ -1130,19 +1194,14 @@ __global__ __launch_bounds__(kWavesPerWG* kWave) void sweep_bwdu_kernel(SweepArg
                     const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
                         const int b = J >> a.rs2;
-                        const real p = sw.inner(b, yv);
-                        const real q2 = p * p;
-                        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
-                        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                        real invB = __builtin_amdgcn_rcp(Bc);
-                        invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+                        const real p = sw.p_block(J, yv);
                         real e[R + 1][C + 1];
 #pragma unroll
                         for (int rr = 0; rr <= R; ++rr) e[rr][C] = sw.left[rr];
 #pragma unroll
                         for (int cc = 0; cc < C; ++cc) e[R][cc] = recvk[cc];
-                        SW::block_uncompute(e, Ac, invB);
-                        const real accP = sw.adjoint_block(e, p, Ac, Bc, recv, accL, corner, up);
+                        real accP = sw.uncompute_adjoint(e, p, recv, accL, corner, up);
+                        if (sw.ll_off_block(J)) accP = 0.0;   // the block's p is a constant
 #pragma unroll
                         for (int rr = 0; rr <= R; ++rr) sw.left[rr] = e[rr][0];
 #pragma unroll
@@ -1865,19 +1924,14 @@ __global__ __launch_bounds__((CoopCfg<BL, true>::kMaxWaves) * 64) void sweep_bwd
                     const bool active = (unsigned)J < (unsigned)sw.nbl;
                     if (active) {
                         const int b = J >> a.rs2;
-                        const real p = sw.inner(b, yv);
-                        const real q2 = p * p;
-                        const real Bc = fma(q2, -1.0 / 12.0, 1.0);
-                        const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                        real invB = __builtin_amdgcn_rcp(Bc);
-                        invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+                        const real p = sw.p_block(J, yv);
                         real e[R + 1][C + 1];
 #pragma unroll
                         for (int rr = 0; rr <= R; ++rr) e[rr][C] = sw.left[rr];
 #pragma unroll
                         for (int cc = 0; cc < C; ++cc) e[R][cc] = recvk[cc];
-                        SW::block_uncompute(e, Ac, invB);
-                        const real accP = sw.adjoint_block(e, p, Ac, Bc, recv, accL, corner, up);
+                        real accP = sw.uncompute_adjoint(e, p, recv, accL, corner, up);
+                        if (sw.ll_off_block(J)) accP = 0.0;   // the block's p is a constant
 #pragma unroll
                         for (int rr = 0; rr <= R; ++rr) sw.left[rr] = e[rr][0];
 #pragma unroll
@@ -2127,9 +2181,8 @@ hipError_t launch_sweep_bl(bool backward, int DT, bool ylds, const SweepArgs& a,
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     const bool ylds = a.y_lds != 0;
-    // the lead-lag form of the sweep: the forward kernel and the replay kernel have it, with the level inside the blocks
-    // (which then hold every refined cell of a pair of increments) or above them
-    if (a.ll != 0 && (a.coop || (backward && a.uncompute))) return hipErrorInvalidValue;
+    // the lead-lag form of the sweep: the level lies inside the blocks (which then hold every refined cell of a pair of
+    // increments) or above them
     if (a.ll == 1 && (BL < 1 || a.rs1 != 0 || a.rs2 != 0)) return hipErrorInvalidValue;
     if (a.ll == 2 && (a.rs1 < 1 || a.rs2 < 1)) return hipErrorInvalidValue;
     if (a.ll < 0 || a.ll > 2) return hipErrorInvalidValue;

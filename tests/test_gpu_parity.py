@@ -375,6 +375,9 @@ def lead_lag_form(op, B, M, L1, L2, d, lam1, lam2, flags):
     (1100, 9, 12, 16, 3, LL, torch.float64),
     (1300, 2, 2, 3, 0, LL, torch.float64),              # one increment each: a single block
     (1300, 60, 3, 6, 1, LL | 1, torch.float64),
+    (1300, 30, 25, 4, 0, LL | 1 | sk.SK_FLAG_BWD_REPLAY, torch.float64),   # the replaying backward, wave per pair
+    (6, 90, 80, 2, 1, LL | sk.SK_FLAG_BWD_REPLAY, torch.float64),          # ... and cooperative
+    (6, 50, 40, 3, 2, LL | 1 | sk.SK_FLAG_BWD_REPLAY, torch.float64),
 ])
 def test_lead_lag_checkerboard_form_pairs(B, L1, L2, d, lam, flags, dtype):
     form, desc = lead_lag_form(sk.SK_OP_BWD, B, 0, L1, L2, d, lam, lam, flags)
@@ -457,6 +460,12 @@ def test_lead_lag_checkerboard_form_with_large_increments(lam, flags):
     (3, 260, 200, 3, 0, LL | 1, torch.float64, "band"),
     (2, 300, 280, 4, 1, LL | 1, torch.float64, "band"),
     (2, 200, 180, 2, 2, LL, torch.float64, "band"),
+    (1100, 140, 20, 3, 0, LL | 1, torch.float64, "wave-per-pair"),
+    (1100, 70, 20, 5, 1, LL, torch.float64, "wave-per-pair"),
+    (1100, 40, 12, 5, 2, LL | 1, torch.float32, "wave-per-pair"),
+    (40, 200, 40, 20, 0, LL | 1, torch.float64, "cooperative"),     # more than 16 channels: the run-time channel loop
+    (40, 100, 40, 16, 1, LL, torch.float64, "cooperative"),
+    (40, 100, 40, 16, 2, LL | 1, torch.float64, "cooperative"),
 ])
 @pytest.mark.parametrize("big", [0.0, 2.2])
 def test_lead_lag_checkerboard_form_few_pairs(B, L1, L2, d, lam, flags, dtype, mode, big):
