@@ -17,7 +17,7 @@ from paper_2509_10613_amd import workloads
 
 pytestmark = pytest.mark.gpu
 
-TOL = {torch.float64: 1e-10, torch.float32: 1e-4}
+TOL = {torch.float64: 1e-10, torch.float32: 1e-4, "wild": 1e-9}
 
 
 def dev(a, dtype=torch.float64):
@@ -496,6 +496,137 @@ def test_lead_lag_checkerboard_form_few_pairs(B, L1, L2, d, lam, flags, dtype, m
     check_values(host(k), kr, dtype, "k")
     check_rows(host(gx), gxr, dtype, "grad_x")
     check_rows(host(gy), gyr, dtype, "grad_y")
+
+
+# ------------------------------------------------------------------ seeded random shapes, every flag combination
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        gram = int(rng.integers(0, 3))                    # 0: pairs, 1: K(X, Y), 2: K(X, X)
+        L1 = int(rng.choice([2, 3, 5, 9, 17, 33, 40, 64, 65, 70, 100, 129, 150, 200, 260, 300]))
+        L2 = L1 if gram == 2 else int(rng.choice([2, 3, 6, 12, 31, 33, 50, 64, 66, 90, 128, 140, 257]))
+        d = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16, 17, 20]))
+        lam1 = int(rng.integers(0, 4))
+        lam2 = lam1 if rng.random() < 0.7 else int(rng.integers(0, 4))
+        flags = int(rng.choice([0, 1, LL, LL | 1])) | (sk.SK_FLAG_BWD_REPLAY if rng.random() < 0.15 else 0)
+        tile_like = rng.random() < 0.1                    # many pairs of at most 64 x 64 cells with 8 or 16 channels
+        if tile_like:
+            L1, L2, d = int(rng.integers(34, 66)), int(rng.integers(34, 66)), int(rng.choice([7, 8, 13, 16]))
+            if gram == 2:
+                L2 = L1
+            lam1 = lam2 = 0
+            flags &= 1
+        ll = 2 if flags & LL else 1
+        cells = ((L1 - 1) * ll << lam1) * ((L2 - 1) * ll << lam2)
+        if cells > 3_000_000:
+            continue
+        if gram:
+            nx = int(rng.choice([1, 2, 5, 12, 33, 40, 70]))
+            ny = nx if gram == 2 else int(rng.choice([1, 3, 8, 20, 36, 64]))
+            npairs = nx * ny
+        else:
+            nx = ny = npairs = int(rng.choice([1, 2, 3, 7, 40, 130, 300, 1100, 2600]))
+        if tile_like and gram:
+            nx = 40
+            ny = nx if gram == 2 else 36
+            npairs = nx * ny
+        if npairs * cells > 60_000_000:
+            continue
+        dtype = torch.float32 if rng.random() < 0.2 else torch.float64
+        keep = bool(rng.random() < 0.3)
+        # a few paths with increments of order one: their pairs are solved once more by the replay kernel
+        wild = bool(rng.random() < 0.25) and dtype == torch.float64 and min(L1, L2) >= 5
+        cases.append((gram, nx, ny, L1, L2, d, lam1, lam2, flags, dtype, keep, wild, int(rng.integers(1, 1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(8))
+def test_random_shapes_against_the_oracle(chunk):
+    # Shapes, dyadic orders, channel counts, flags, element types and call forms (pairs, K(X,Y), K(X,X); with and
+    # without a kept forward sweep) drawn from a seeded generator: whatever launch plan they land in, the numbers are
+    # the oracle's.
+    check_random_cases(15, 4200 + chunk)
+
+
+def ill_conditioned(k64, k80):
+    """Whether the oracle's own rounding (double against x87 extended arithmetic) already takes a tenth of the
+    tolerance: such inputs say nothing about the kernels."""
+    k80 = np.asarray(k80, dtype=np.float64)
+    return float(np.max(np.abs(k64 - k80) / np.maximum(1.0, np.abs(k80)))) > 1e-11
+
+
+def check_random_cases(n, seed):
+    for case in _random_cases(n, seed):
+        gram, nx, ny, L1, L2, d, lam1, lam2, flags, dtype, keep, wild, seed = case
+        sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+        # Gradients of paths with increments of order one are held to 1e-9: the default backward accepts a recovered
+        # forward state within 1e-11 of the lane's largest value, and where the kernel values of such a pair cancel
+        # along a row that has been seen to cost a decade (the replaying backward stays at 1e-12 there).
+        gdt = "wild" if wild and not (flags & sk.SK_FLAG_BWD_REPLAY) else dtype
+        op = sk.SK_OP_GRAM_BWD if gram else sk.SK_OP_BWD
+        print(case, sk.sigkernel_describe(op, nx, ny if gram else 0, L1, L2, d, lam1, lam2, flags, sdt).split(" grid=")[0],
+              flush=True)
+        rng = np.random.default_rng(seed)
+        dX = rng.normal(0.0, (1.0 / (d * L1)) ** 0.5, (nx, L1, d))
+        dY = rng.normal(0.0, (1.0 / (d * L2)) ** 0.5, (ny, L2, d))
+        if wild:
+            big = 2.2 * 2 ** (0.25 * (lam1 + lam2)) / d ** 0.5
+            wx, wy = rng.integers(0, nx, size=1 + nx // 16), rng.integers(0, ny, size=1 + ny // 16)
+            dX[wx, 1:8:3, :] = rng.choice([-big, big], size=dX[wx, 1:8:3, :].shape)
+            dY[wy, 1:8:3, :] = rng.choice([-big, big], size=dY[wy, 1:8:3, :].shape)
+        X = np.cumsum(dX, axis=1)
+        Y = X if gram == 2 else np.cumsum(dY, axis=1)
+        Xr = rounded(X, dtype)
+        Yr = Xr if gram == 2 else rounded(Y, dtype)
+        x = dev(X, dtype)
+        y = x if gram == 2 else dev(Y, dtype)
+        of = flags & ~sk.SK_FLAG_BWD_REPLAY
+        if gram:
+            W = workloads.upstream_weights(seed % 1000, (nx, ny))
+            Kr, gXr, gYr = oracle.gram(Xr, Yr, rounded(W, dtype), lam1, lam2, of)
+            if not np.all(np.abs(Kr) < 1e30):
+                continue                                  # beyond what the test's tolerances are meant for
+            if wild and ill_conditioned(Kr, oracle.gram(Xr, Yr, None, lam1, lam2, of, dtype=np.longdouble)):
+                continue
+            if keep:
+                need = sk.sigkernel_workspace_bytes(sk.SK_OP_GRAM, nx, ny, L1, L2, d, lam1, lam2,
+                                                    flags | sk.SK_FLAG_KEEP_FORWARD, sdt)
+                ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+                Kf = sk.sigkernel_gram(x, y, None, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+                K, gX, gY = sk.sigkernel_gram(x, y, dev(W, dtype), lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+            else:
+                Kf = sk.sigkernel_gram(x, y, None, lam1, lam2, flags)
+                K, gX, gY = sk.sigkernel_gram(x, y, dev(W, dtype), lam1, lam2, flags)
+            torch.cuda.synchronize()
+            check_values(host(Kf), Kr, dtype, "K (forward call)")
+            check_values(host(K), Kr, dtype, "K")
+            check_rows(host(gX), gXr, gdt, "grad_X")
+            if gram == 1:
+                check_rows(host(gY), gYr, gdt, "grad_Y")
+            else:
+                assert gY is None
+        else:
+            gk = workloads.upstream_weights(seed % 1000, (nx,))
+            kr, gxr, gyr = oracle.bwd(Xr, Yr, rounded(gk, dtype), lam1, lam2, of)
+            if not np.all(np.abs(kr) < 1e30):
+                continue
+            if wild and ill_conditioned(kr, oracle.fwd(Xr, Yr, lam1, lam2, of, dtype=np.longdouble)):
+                continue
+            if keep:
+                need = sk.sigkernel_workspace_bytes(sk.SK_OP_FWD, nx, 0, L1, L2, d, lam1, lam2,
+                                                    flags | sk.SK_FLAG_KEEP_FORWARD, sdt)
+                ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+                kf = sk.sigkernel_fwd(x, y, lam1, lam2, flags | sk.SK_FLAG_KEEP_FORWARD, ws=ws)
+                k, gx, gy = sk.sigkernel_bwd(x, y, dev(gk, dtype), lam1, lam2, flags | sk.SK_FLAG_HAVE_FORWARD, ws=ws)
+            else:
+                kf = sk.sigkernel_fwd(x, y, lam1, lam2, flags)
+                k, gx, gy = sk.sigkernel_bwd(x, y, dev(gk, dtype), lam1, lam2, flags)
+            torch.cuda.synchronize()
+            check_values(host(kf), kr, dtype, "k (forward call)")
+            check_values(host(k), kr, dtype, "k")
+            check_rows(host(gx), gxr, gdt, "grad_x")
+            check_rows(host(gy), gyr, gdt, "grad_y")
 
 
 # ------------------------------------------------------------------ autograd over the C ABI (Section 1)
