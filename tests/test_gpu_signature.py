@@ -201,3 +201,31 @@ def test_signature_benchmark_shapes_sampled(name):
     assert np.abs(S1 - (X[:, -1] - X[:, 0])).max() <= 1e-12
     assert np.abs(S2 + S2.transpose(0, 2, 1) - S1[:, :, None] * S1[:, None, :]).max() <= 1e-12
     assert np.array_equal(got[:, 0], np.ones(B))
+
+
+def _random_signature_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        d = int(rng.integers(1, 21))
+        N = int(rng.integers(1, 8))
+        flags = int(rng.choice([0, sk.SK_FLAG_TIME_AUG, sk.SK_FLAG_LEAD_LAG, sk.SK_FLAG_TIME_AUG | sk.SK_FLAG_LEAD_LAG]))
+        D = (2 * d if flags & sk.SK_FLAG_LEAD_LAG else d) + (1 if flags & sk.SK_FLAG_TIME_AUG else 0)
+        if D ** N > 60000:
+            continue
+        B = int(rng.choice([1, 2, 3, 5, 17, 64, 200]))
+        L = int(rng.choice([1, 2, 3, 4, 7, 16, 33, 70, 130]))
+        if B * L * D ** N > 1500000:
+            continue
+        dtype = torch.float32 if rng.random() < 0.2 else torch.float64
+        cases.append((B, L, d, N, flags, dtype, bool(rng.random() < 0.5), int(rng.integers(1, 1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_random_signature_shapes(chunk):
+    # batch sizes, lengths, channel counts, depths, transformations and element types from a seeded generator: whichever
+    # kernel variant, prefix length, piece count and lane grouping the plan picks, the numbers are the oracle's
+    for B, L, d, N, flags, dtype, give, seed in _random_signature_cases(12, 5200 + chunk):
+        X = paths(seed, B, L, d, 0.6 / max(1.0, L) ** 0.5)
+        check(X, N, flags, dtype)
