@@ -37,8 +37,9 @@
  *    gradients are returned for the original d channels only.  SK_FLAG_LEAD_LAG applies the lead-lag transform
  *    of Section 4 to both paths on the fly: a path of L points in R^d is treated as the path of 2L - 1 points in
  *    R^2d with lead_i = x[k] for i in {2k - 1, 2k} and lag_i = x[k] for i in {2k, 2k + 1} (lead channels first);
- *    the transformed paths are never formed, their increments are written by the preparation kernel, and the
- *    gradients come back with respect to the original points.  With both flags the time channel is that of
+ *    neither the transformed paths nor their increments are formed (the sweep runs on the grid of the original
+ *    increments with one more level of refinement, whose off-diagonal quadrants carry no increment product), and
+ *    the gradients come back with respect to the original points.  With both flags the time channel is that of
  *    the transformed path, t_i = i/(2L - 2).  Dyadic orders then refine the 2 (L - 1) steps of the transformed path.
  */
 #ifndef SIGKERNEL_H
@@ -202,10 +203,9 @@ int sigkernel_event_timing_read(double* fwd_ms, int* fwd_launches, double* bwd_m
  * the library would make for this operation and shape into out (host memory, out_bytes >= 1; truncated if
  * too small): the launch mode, the name of the sweep kernel as a profiler reports it, grid and workgroup
  * size, LDS bytes per workgroup and the workspace size; kept_sweep_half (1: the launch is the forward half of
- * the backward pass, kept for the backward call; 2: its reverse half; 0: neither); lead_lag_form (none,
+ * the backward pass, kept for the backward call; 2: its reverse half; 0: neither); lead_lag_form (none, or
  * checkerboard: the grid of the caller's increments swept with one more level of refinement whose off-diagonal
- * quadrants carry no increment product, or transformed_increments: the increments of the transformed paths
- * written out and swept as they are); second_launch_lds_bytes (backward calls: LDS per workgroup of the launch
+ * quadrants carry no increment product); second_launch_lds_bytes (backward calls: LDS per workgroup of the launch
  * that solves drifted pairs once more).  Same arguments as sigkernel_workspace_bytes.
  * Pure host arithmetic: no GPU call.  Returns SK_OK or a negative error code.
  */

@@ -90,8 +90,8 @@ int validate(int64_t nx, int64_t ny, int64_t L1, int64_t L2, int64_t d, int lam1
         return fail(SK_ERR_SHAPE, "refined grid side (L-1) << lambda must stay below 2^29");
     if (d > 65536) return fail(SK_ERR_SHAPE, "d above 65536");
     if ((flags & SK_FLAG_LEAD_LAG) && (2 * L1 - 1 > lim || 2 * L2 - 1 > lim || ((2 * L1 - 2) << lam1) >= lim ||
-                                       ((2 * L2 - 2) << lam2) >= lim || 2 * d > 65536))
-        return fail(SK_ERR_SHAPE, "lead-lag transform: refined grid side 2 (L-1) << lambda must stay below 2^29, 2 d below 65536");
+                                       ((2 * L2 - 2) << lam2) >= lim))
+        return fail(SK_ERR_SHAPE, "lead-lag transform: refined grid side 2 (L-1) << lambda must stay below 2^29");
     if (nx > ((int64_t)1 << 40) || ny > ((int64_t)1 << 40)) return fail(SK_ERR_SHAPE, "batch too large");
     return SK_OK;
 }
@@ -104,11 +104,9 @@ struct Layout {
     bool has_sc = false;
     size_t off_sc = 0;
     size_t total = 0;
-    // Lead-lag transform (Section 4): 0 not asked for; 1 the plan is that of the transformed paths (2L - 1 points,
-    // 2d channels), whose increments the preparation kernel writes out; 2 the plan is that of the caller's paths with
-    // one more dyadic level, swept in its lead-lag form (equal dyadic orders; every kernel but the tile kernels has
-    // that form, and such plans never choose those).
-    int ll = 0;
+    // Lead-lag transform (Section 4): the plan is that of the caller's paths with one more dyadic level on either
+    // side, swept in its lead-lag form (every kernel but the tile kernels has one, and such plans never choose those).
+    bool ll = false;
 };
 
 // L1, L2, d, lam1, lam2 are the caller's.
@@ -116,22 +114,12 @@ Layout make_layout(bool backward, bool gram, bool symmetric, int64_t nx, int64_t
                    int lam1, int lam2, int flags, int io_elem, bool uncompute, bool keep = false)
 {
     Layout l;
-    bool native = false;
-    if ((flags & SK_FLAG_LEAD_LAG) && lam1 == lam2) {
-        l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1 + 1, lam2 + 1, io_elem, uncompute, keep,
-                            false, true);
-        native = l.p.valid;
-    }
-    if (native) {
-        l.ll = 2;
-        lam1 += 1; lam2 += 1;
-    } else {
-        if (flags & SK_FLAG_LEAD_LAG) { L1 = 2 * L1 - 1; L2 = 2 * L2 - 1; d = 2 * d; l.ll = 1; }
-        l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, uncompute, keep);
-    }
+    l.ll = (flags & SK_FLAG_LEAD_LAG) != 0;
+    if (l.ll) { lam1 += 1; lam2 += 1; }
+    l.p = sk::make_plan(backward, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, uncompute, keep, false, l.ll);
     l.total = l.p.total;
     if (l.p.valid && backward && l.p.uncompute) {
-        l.sc = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, false, false, true, native);
+        l.sc = sk::make_plan(true, gram, symmetric, nx, ny, L1, L2, d, lam1, lam2, io_elem, false, false, true, l.ll);
         l.has_sc = l.sc.valid;
         l.off_sc = l.p.total;
         l.total = l.p.total + l.sc.total;
@@ -188,9 +176,9 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
     const double sc = 1.0 / (double)((int64_t)1 << (lam1 + lam2));
     a.sc = sc;
     // the time channel t_i = i / (points - 1) of the paths the sweep stands for (lead-lag paths have 2L - 1 points)
-    const int tsteps1 = lay.ll == 2 ? 2 * (p.L1 - 1) : p.L1 - 1, tsteps2 = lay.ll == 2 ? 2 * (p.L2 - 1) : p.L2 - 1;
+    const int tsteps1 = lay.ll ? 2 * (p.L1 - 1) : p.L1 - 1, tsteps2 = lay.ll ? 2 * (p.L2 - 1) : p.L2 - 1;
     a.tc = (flags & SK_FLAG_TIME_AUG) ? sc * (1.0 / (double)tsteps1) * (1.0 / (double)tsteps2) : 0.0;
-    a.ll = lay.ll == 2 ? p.ll : 0;
+    a.ll = p.ll;
     a.y_lds = p.y_lds;
     a.lds_wave = (unsigned)p.lds_wave;
     a.ring_off = (unsigned)p.ring_off;
@@ -230,11 +218,7 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
         a.bad_list = reinterpret_cast<long long*>(base + p.off_badlist);
     }
     // Lock-step mode on a batch of pairs of double paths works on the caller's arrays directly.
-    // Lead-lag transform (Section 4) with a plan made for the transformed paths (2L - 1 points, 2d channels):
-    // only the preparation and the finalisation know the caller's shape.
-    const int ll = lay.ll == 1 ? 1 : 0;
-    const int cL1 = ll ? (p.L1 + 1) / 2 : p.L1, cL2 = ll ? (p.L2 + 1) / 2 : p.L2, cd = ll ? p.d / 2 : p.d;
-    const bool fused = p.lock && p.gramM == 0 && kIsDouble && !ll;
+    const bool fused = p.lock && p.gramM == 0 && kIsDouble;
     if (fused) {
         a.fused = 1;
         a.xraw = static_cast<const double*>(x);
@@ -273,12 +257,12 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
     // (the reverse sweep of a kept forward sweep: the same increments once more, cleared accumulators, and only the
     // reverse sweep's progress counters cleared - the error flag still says how the forward sweep went)
     if (!fused)
-    SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, cL1,
+    SK_CHECK(launch_prepare<T>(static_cast<const T*>(x), dxT, (backward && a.want_gx) ? a.gdx : nullptr, p.nx, p.L1,
                                p.rpad, static_cast<const T*>(y), p.symmetric ? nullptr : dyT,
-                               (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, cL2, p.qpad, cd,
+                               (backward && a.want_gy && !p.symmetric) ? a.gdy : nullptr, p.ny, p.L2, p.qpad, p.d,
                                p.DP, phase == 2 ? a.bd_flags + p.nflags / 2 : a.err,
                                phase == 2 ? p.nflags / 2 + 1 : 1 + (int)((p.off_flags - p.off_err) / sizeof(int)) + p.nflags,
-                               ll, st));   // (both ranges end with the counter of drifted pairs, the int behind the flags)
+                               st));   // (both ranges end with the counter of drifted pairs, the int behind the flags)
     // the calls that work on the caller's arrays have no preparation launch: their counter of drifted pairs
     if (fused && backward && phase != 1 && a.bad_count) SK_CHECK(launch_fill<int>(a.bad_count, 1, 0, st));
     // band mode signs, erases and checks a kept sweep in launches of their own (the lock-step kernels do it themselves)
@@ -328,9 +312,9 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
         SK_CHECK(hipMemcpyAsync(a.k_out, keep_k, (size_t)p.kcount * sizeof(double), hipMemcpyDeviceToDevice, st));
     if (!kIsDouble && k) SK_CHECK((launch_convert<double, T>(a.k_out, static_cast<T*>(k), p.kcount, st)));
     if (backward && !fused && phase != 1) {
-        SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, cL1, p.rpad, a.gdy,
-                                    p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, cL2, p.qpad, cd, p.DP,
-                                    a.err, ll, st));
+        SK_CHECK(launch_finalize<T>(a.gdx, static_cast<T*>(grad_x), p.nx, p.L1, p.rpad, a.gdy,
+                                    p.symmetric ? nullptr : static_cast<T*>(grad_y), p.ny, p.L2, p.qpad, p.d, p.DP,
+                                    a.err, st));
     }
 #undef SK_CHECK
     return SK_OK;
@@ -366,13 +350,13 @@ int check_device()
 }
 
 // Whether the backward plan pb has its forward and reverse sweeps as launches of their own: the lock-step kernels that
-// work on the caller's arrays (pairs of double paths, no lead-lag transform), the band kernels, and the solo kernels
+// work on the caller's arrays (pairs of double paths), the band kernels, and the solo kernels
 // (pb made with keep = true: checkpoints and bottom rows per pair).
-bool split_forward(const sk::Plan& pb, sk_dtype dt, int flags)
+bool split_forward(const sk::Plan& pb, sk_dtype dt)
 {
     if (pb.keep_solo) return true;                     // pair batches and Gram matrices
     if (pb.gramM != 0) return false;
-    return pb.band || (pb.lock && dt == SK_F64 && !(flags & SK_FLAG_LEAD_LAG));
+    return pb.band || (pb.lock && dt == SK_F64);
 }
 
 int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, const void* grad_k, void* grad_x,
@@ -413,7 +397,7 @@ int dispatch(bool backward, bool gram, const void* x, const void* y, void* k, co
         if (ws_bytes < lb.total)
             return fail(SK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed (a kept forward sweep: the backward call's, "
                         "asked for with the flag)", ws_bytes, lb.total);
-        if (split_forward(lb.p, dt, flags)) {
+        if (split_forward(lb.p, dt)) {
             phase = backward ? 2 : 1;
             lay = lb;
         }
@@ -714,7 +698,7 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     if (flags & (backward ? SK_FLAG_HAVE_FORWARD : SK_FLAG_KEEP_FORWARD)) {
         const Layout lb = make_layout(true, gram, false, B_or_N, ny, L1, L2, d, lam1, lam2, flags, dt == SK_F64 ? 8 : 4,
                                       !(flags & SK_FLAG_BWD_REPLAY), true);
-        if (lb.p.valid && split_forward(lb.p, dt, flags)) {
+        if (lb.p.valid && split_forward(lb.p, dt)) {
             phase = backward ? 2 : 1;
             lay = lb;
         } else if (lb.p.valid) {
@@ -759,14 +743,14 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
                       (p.y_lds && p.DT) ? "true" : "false");
         threads = (p.coop ? p.nw : sk::kWavesPerWG) * sk::kWave;
     }
-    const bool fused = p.lock && !gram && dt == SK_F64 && lay.ll != 1;
+    const bool fused = p.lock && !gram && dt == SK_F64;
     std::snprintf(out, out_bytes,
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
                   "kept_sweep_half=%d lead_lag_form=%s second_launch_lds_bytes=%zu workspace_bytes=%zu "
                   "drifted_pairs_counter_at=%zu",
                   mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
                   (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
-                  fused ? 1 : 0, phase, lay.ll == 0 ? "none" : (lay.ll == 1 ? "transformed_increments" : "checkerboard"),
+                  fused ? 1 : 0, phase, lay.ll ? "checkerboard" : "none",
                   (lay.has_sc && backward && phase != 1) ? lay.sc.lds_bytes : (size_t)0, lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
     return SK_OK;
 }

@@ -684,9 +684,7 @@ hipError_t launch_band_ll(int phase, const SweepArgs& a, int grid, size_t lds, h
     if constexpr (BL >= 1) {
         if (a.ll == 1 && a.rs1 == 0 && a.rs2 == 0) return launch_band_t<BL, D, 1>(phase, a, grid, lds, st);
     }
-    if constexpr (BL == kMaxBL) {
-        if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_band_t<BL, D, 2>(phase, a, grid, lds, st);
-    }
+    if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_band_t<BL, D, 2>(phase, a, grid, lds, st);
     return hipErrorInvalidValue;
 }
 

@@ -113,13 +113,13 @@ template <typename T> hipError_t launch_add_inplace(T* dst, const T* src, long n
 // dx/dy null = that side is not (re)computed (symmetric Gram); gdx/gdy null = no accumulator to clear.
 template <typename T>
 hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
-                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, int ll, hipStream_t st);
+                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, hipStream_t st);
 // band mode (a.band != 0), defined in sk_band.hip; phase 0: forward sweep, 1: forward sweep of the backward
 // pass (checkpoints), 2: reverse sweep
 hipError_t launch_sweep_band(int phase, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
-                           int L2, int qpad, int d, int DS, const int* err, int ll, hipStream_t st);
+                           int L2, int qpad, int d, int DS, const int* err, hipStream_t st);
 hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // clears the n doubles at g1 and at g2 (either may be null) if *err == 2: every pair is about to be solved once more
 hipError_t launch_second_chance_reset(real* g1, long n1, real* g2, long n2, const int* err, hipStream_t st);

@@ -110,13 +110,9 @@ struct PathSet {
 // Preparation, one launch per call: increments of both path sets, padded with zeros
 // (inc[path][a][c] = x[path][a+1][c] - x[path][a][c] for a < L-1, c < d: first line of the paper's
 // forward listing), the gradient accumulators cleared, and the error flag cleared.
-// With ll != 0 the increments are those of the lead-lag transform of the path (Section 4), formed on the fly:
-// the transformed path has 2L - 1 points in R^2d, lead channels first; its step 2k moves the lead half from
-// x[k] to x[k+1] and its step 2k + 1 moves the lag half likewise, so
-// inc[2k][c] = x[k+1][c] - x[k][c], inc[2k+1][d + c] = x[k+1][c] - x[k][c], and every other entry is zero.
-// L and d are the caller's; the rows of inc then count 2 (L - 1) increments of 2d channels.
+// (Lead-lag paths, Section 4, need nothing here: the sweeps work on the increments of the original paths.)
 template <typename TI>
-__global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, int* err, int nclear, int ll)
+__global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, int* err, int nclear)
 {
     const long nx = px.inc ? px.npaths * (long)px.rows * DS : 0;
     const long ny = py.inc ? py.npaths * (long)py.rows * DS : 0;
@@ -134,18 +130,9 @@ __global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, in
         const int a = (int)(t % p.rows);
         const long pth = t / p.rows;
         real v = 0.0;
-        if (!ll) {
-            if (a < p.L - 1 && c < d) {
-                const TI* xp = p.x + (pth * p.L + a) * (long)d + c;
-                v = (real)xp[d] - (real)xp[0];
-            }
-        } else {
-            const int k = a >> 1;
-            const int cc = (a & 1) ? c - d : c;   // odd steps move the lag half (channels d .. 2d-1)
-            if (k < p.L - 1 && cc >= 0 && cc < d) {
-                const TI* xp = p.x + (pth * p.L + k) * (long)d + cc;
-                v = (real)xp[d] - (real)xp[0];
-            }
+        if (a < p.L - 1 && c < d) {
+            const TI* xp = p.x + (pth * p.L + a) * (long)d + c;
+            v = (real)xp[d] - (real)xp[0];
         }
         p.inc[j] = v;
         if (p.ginc) p.ginc[j] = 0.0;
@@ -155,10 +142,8 @@ __global__ void prepare_kernel(PathSet<TI> px, PathSet<TI> py, int d, int DS, in
 // Finalisation, one launch per backward call: grad[path][i][c] = g[path][i-1][c] - g[path][i][c]
 // (out-of-range terms zero).  The increments are differences of consecutive points, so the gradient of
 // a point collects the two increments it touches.
-// With ll != 0 the accumulators belong to the lead-lag increments (see prepare_kernel): the increment x[k+1] - x[k]
-// collects row 2k (lead channels) and row 2k + 1 (lag channels).
 template <typename TO>
-__global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS, const int* err, int ll)
+__global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS, const int* err)
 {
     // a bounded wait ran out (1) or the workspace held another call's forward sweep (3); 2 means that every pair was
     // solved once more by the replay kernel, whose results the accumulators then hold
@@ -176,11 +161,8 @@ __global__ void finalize_kernel(PathSet<TO> px, PathSet<TO> py, int d, int DS, c
         const int pt = (int)(t % p.L);
         const long pth = t / p.L;
         const real* gp = p.ginc + (pth * p.rows) * (long)DS + c;
-        auto ginc_of = [&](int k) {   // dF/d(x[k+1] - x[k])
-            return ll ? gp[(long)(2 * k) * DS] + gp[(long)(2 * k + 1) * DS + d] : gp[(long)k * DS];
-        };
-        const real hi = pt >= 1 ? ginc_of(pt - 1) : 0.0;
-        const real lo = pt < p.L - 1 ? ginc_of(pt) : 0.0;
+        const real hi = pt >= 1 ? gp[(long)(pt - 1) * DS] : 0.0;
+        const real lo = pt < p.L - 1 ? gp[(long)pt * DS] : 0.0;
         p.grad[j] = bad ? (TO)__builtin_nan("") : (TO)(hi - lo);
     }
 }
@@ -2047,7 +2029,7 @@ hipError_t launch_convert(const TA* in, TB* out, long n, hipStream_t st)
 
 template <typename T>
 hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int rpad, const T* y, real* dy, real* gdy,
-                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, int ll, hipStream_t st)
+                          long ny, int L2, int qpad, int d, int DS, int* err, int nclear, hipStream_t st)
 {
     PathSet<T> px{x, nullptr, dx, gdx, nx, L1, rpad};
     PathSet<T> py{y, nullptr, dy, gdy, ny, L2, qpad};
@@ -2055,13 +2037,13 @@ hipError_t launch_prepare(const T* x, real* dx, real* gdx, long nx, int L1, int 
     if (total <= 0) total = 1;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(prepare_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err, nclear, ll);
+    hipLaunchKernelGGL(prepare_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err, nclear);
     return hipGetLastError();
 }
 
 template <typename T>
 hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad, const real* gdy, T* grad_y, long ny,
-                           int L2, int qpad, int d, int DS, const int* err, int ll, hipStream_t st)
+                           int L2, int qpad, int d, int DS, const int* err, hipStream_t st)
 {
     PathSet<T> px{nullptr, grad_x, nullptr, const_cast<real*>(gdx), nx, L1, rpad};
     PathSet<T> py{nullptr, grad_y, nullptr, const_cast<real*>(gdy), ny, L2, qpad};
@@ -2069,7 +2051,7 @@ hipError_t launch_finalize(const real* gdx, T* grad_x, long nx, int L1, int rpad
     if (total <= 0) return hipSuccess;
     long blocks = (total + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(finalize_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err, ll);
+    hipLaunchKernelGGL(finalize_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, st, px, py, d, DS, err);
     return hipGetLastError();
 }
 
@@ -2207,12 +2189,12 @@ template hipError_t launch_fill<double>(double*, long, double, hipStream_t);
 template hipError_t launch_convert<float, double>(const float*, double*, long, hipStream_t);
 template hipError_t launch_convert<double, float>(const double*, float*, long, hipStream_t);
 template hipError_t launch_prepare<float>(const float*, real*, real*, long, int, int, const float*, real*, real*, long,
-                                          int, int, int, int, int*, int, int, hipStream_t);
+                                          int, int, int, int, int*, int, hipStream_t);
 template hipError_t launch_prepare<double>(const double*, real*, real*, long, int, int, const double*, real*, real*,
-                                           long, int, int, int, int, int*, int, int, hipStream_t);
+                                           long, int, int, int, int, int*, int, hipStream_t);
 template hipError_t launch_finalize<float>(const real*, float*, long, int, int, const real*, float*, long, int, int, int,
-                                           int, const int*, int, hipStream_t);
+                                           int, const int*, hipStream_t);
 template hipError_t launch_finalize<double>(const real*, double*, long, int, int, const real*, double*, long, int, int,
-                                            int, int, const int*, int, hipStream_t);
+                                            int, int, const int*, hipStream_t);
 
 }  // namespace sk

@@ -32,7 +32,7 @@ __device__ __forceinline__ int clamp_col(int J, int hi)
 //   LL = 2: it lies above the blocks (a block is uniform: diagonal or not by the parity of its row and column).
 template <int BL, int D, int M, int LL = 0>
 struct Lock {
-    static_assert(LL == 0 || BL >= 1, "the lead-lag level needs blocks of at least 2 x 2 cells");
+    static_assert(LL != 1 || BL >= 1, "a lead-lag level inside the blocks needs blocks of at least 2 x 2 cells");
     static constexpr int C = 1 << BL;
     static constexpr int HB = BL > 0 ? BL - 1 : 0;   // LL = 1: log2 of a quadrant's side
     // LL = 1: whether cell (rr, cc) of a lane's block column lies off the diagonal quadrants of its block

@@ -513,9 +513,7 @@ hipError_t launch_lock_ll(bool backward, const SweepArgs& a, int grid, size_t ld
     if constexpr (BL >= 1) {
         if (a.ll == 1 && a.rs1 == 0 && a.rs2 == 0) return launch_lock_m<BL, D, 1>(backward, a, grid, lds, st);
     }
-    if constexpr (BL == kMaxBL) {
-        if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_lock_m<BL, D, 2>(backward, a, grid, lds, st);
-    }
+    if (a.ll == 2 && a.rs1 >= 1 && a.rs2 >= 1) return launch_lock_m<BL, D, 2>(backward, a, grid, lds, st);
     return hipErrorInvalidValue;
 }
 

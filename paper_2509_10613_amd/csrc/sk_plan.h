@@ -135,7 +135,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
                       int64_t d, int lam1, int lam2, int io_elem, bool uncompute = true, bool keep = false,
                       bool second_chance = false, bool lead_lag = false)
 {
-    // lead_lag: the sweep of two lead-lag paths (Section 4) on the grid of the original increments; lam1 == lam2 then
+    // lead_lag: the sweep of two lead-lag paths (Section 4) on the grid of the original increments; lam1 and lam2 then
     // count the lead-lag level as one more dyadic level (the caller's orders plus one), L1, L2 and d are the caller's.
     // The level lies inside the blocks when these hold every refined cell of a pair of increments, above them
     // otherwise (Plan::ll); the tile kernels have no such form.
@@ -160,13 +160,16 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
     p.r = (int)L1 - 1; p.q = (int)L2 - 1;
     if (p.npairs <= 0 || p.r <= 0 || p.q <= 0) return p;   // nothing to sweep
     int mn = lam1 < lam2 ? lam1 : lam2;
+    if (lead_lag) {
+        if (mn < 1) return p;   // not valid: the lead-lag level counts as one dyadic level on either side
+        // With unequal orders the blocks stay below the lead-lag level on both sides (a block then lies inside one
+        // quadrant of that level, whichever side is refined more).
+        if (lam1 != lam2) mn -= 1;
+    }
     p.BL = mn < kMaxBL ? mn : kMaxBL;
     p.rs1 = lam1 - p.BL; p.rs2 = lam2 - p.BL;
     p.mb = p.r << p.rs1; p.nb = p.q << p.rs2;
-    if (lead_lag) {
-        if (lam1 != lam2 || lam1 < 1) return p;   // not valid
-        p.ll = p.rs1 == 0 ? 1 : 2;
-    }
+    if (lead_lag) p.ll = (p.rs1 == 0 && p.rs2 == 0) ? 1 : 2;
     p.ns = (p.mb + kWave - 1) / kWave;
     const int C = 1 << p.BL, R = C;
     p.rowlen = (int)align_up((size_t)(p.nb + 8) * C + 1, 64);   // a few block columns beyond the grid (band mode)

@@ -313,10 +313,10 @@ LL = sk.SK_FLAG_LEAD_LAG
 
 
 @pytest.mark.parametrize("B,L1,L2,d,lam1,lam2,flags,dtype", [
-    (6, 40, 33, 2, 1, 1, LL, torch.float64),            # few pairs: lock-step (not fused: the kernels see increments)
+    (6, 40, 33, 2, 1, 1, LL, torch.float64),            # few pairs: lock-step
     (5, 20, 20, 3, 0, 2, LL | 1, torch.float64),        # with time augmentation of the transformed path
-    (1300, 30, 25, 4, 0, 0, LL, torch.float64),         # many pairs, 8 channels after the transform: tile kernels
-    (1300, 24, 31, 2, 1, 1, LL, torch.float32),         # many pairs, float callers: solo kernels
+    (1300, 30, 25, 4, 0, 0, LL, torch.float64),         # many pairs: solo kernels
+    (1300, 24, 31, 2, 1, 1, LL, torch.float32),         # ... and float callers
     (3, 260, 200, 3, 0, 0, LL, torch.float64),          # long paths: band kernels
 ])
 def test_lead_lag_pairs(B, L1, L2, d, lam1, lam2, flags, dtype):
@@ -423,9 +423,30 @@ def test_lead_lag_checkerboard_form_gram(lam, flags):
     check_grads(host(gXX), gXXr, torch.float64, "grad_X total")
 
 
-def test_lead_lag_with_unequal_dyadic_orders_takes_the_transformed_increments():
-    assert lead_lag_form(sk.SK_OP_BWD, 1300, 0, 20, 20, 3, 0, 2, LL)[0] == "transformed_increments"
-    assert lead_lag_form(sk.SK_OP_BWD, 1300, 0, 20, 20, 3, 1, 1, 0)[0] == "none"
+@pytest.mark.parametrize("B,L1,L2,d,lam1,lam2,flags", [
+    (1300, 20, 22, 3, 0, 2, LL | 1),      # solo; blocks of one cell below the lead-lag level
+    (1300, 20, 22, 3, 2, 1, LL),
+    (5, 40, 30, 2, 1, 3, LL | 1),         # lock-step
+    (3, 150, 90, 4, 0, 1, LL),            # band
+    (1100, 80, 20, 5, 3, 2, LL | 1),      # wave per pair
+    (40, 60, 40, 20, 1, 0, LL),           # cooperative
+])
+def test_lead_lag_checkerboard_form_with_unequal_dyadic_orders(B, L1, L2, d, lam1, lam2, flags):
+    desc = sk.sigkernel_describe(sk.SK_OP_BWD, B, 0, L1, L2, d, lam1, lam2, flags, sk.SK_F64)
+    print(desc, flush=True)
+    assert "lead_lag_form=checkerboard" in desc
+    rng = np.random.default_rng(930 + L1 + d)
+    X = np.cumsum(rng.normal(0.0, (1.0 / L1) ** 0.5, (B, L1, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / L2) ** 0.5, (B, L2, d)), axis=1)
+    gk = workloads.upstream_weights(76, (B,))
+    kf = sk.sigkernel_fwd(dev(X), dev(Y), lam1, lam2, flags)
+    k, gx, gy = sk.sigkernel_bwd(dev(X), dev(Y), dev(gk), lam1, lam2, flags)
+    torch.cuda.synchronize()
+    kr, gxr, gyr = oracle.bwd(X, Y, gk, lam1, lam2, flags)
+    check_values(host(kf), kr, torch.float64, "k (forward only)")
+    check_values(host(k), kr, torch.float64, "k")
+    check_grads(host(gx), gxr, torch.float64, "grad_x")
+    check_grads(host(gy), gyr, torch.float64, "grad_y")
 
 
 @pytest.mark.parametrize("lam,flags", [(0, LL), (1, LL | 1), (2, LL | 1)])
