@@ -335,17 +335,20 @@ int run_trivial(int64_t npairs, int64_t nx, int64_t ny, int64_t L1, int64_t L2, 
 
 int check_device()
 {
-    static std::atomic<int> state{0};   // 0 unknown, 1 ok (a failed check is repeated, and reported, by the next call)
-    if (state.load(std::memory_order_acquire) == 1) return SK_OK;
+    // per device: 0 unknown, 1 ok (a failed check is repeated, and reported, by the next call)
+    constexpr int kKnown = 64;
+    static std::atomic<int> state[kKnown];
     int dev = 0, lds = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return fail(SK_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    const bool tracked = dev >= 0 && dev < kKnown;
+    if (tracked && state[dev].load(std::memory_order_acquire) == 1) return SK_OK;
     e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
     if (e != hipSuccess) return fail(SK_ERR_HIP, "hipDeviceGetAttribute: %s", hipGetErrorString(e));
     if ((size_t)lds < sk::kLdsPerCU)
         return fail(SK_ERR_HIP, "device offers %d bytes of LDS per workgroup, this library is built for %zu (gfx950)",
                     lds, sk::kLdsPerCU);
-    state.store(1, std::memory_order_release);
+    if (tracked) state[dev].store(1, std::memory_order_release);
     return SK_OK;
 }
 

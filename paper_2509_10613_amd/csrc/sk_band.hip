@@ -650,9 +650,7 @@ template <int BL, int D, int LL>
 hipError_t launch_band_t(int phase, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
     const dim3 block((kBandStrips + 1) * kWave);
-    auto prep = [&](const void* fn) {
-        return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-    };
+    auto prep = [&](const void* fn) { return allow_full_lds(fn); };
     hipError_t e;
     if (phase == 0) {
         e = prep(reinterpret_cast<const void*>(&band_fwd_kernel<BL, D, false, LL>));

@@ -2,9 +2,29 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "sk_plan.h"
 
 namespace sk {
+
+// Lets a kernel use the whole LDS of a compute unit as dynamic shared memory.  The attribute belongs to the kernel
+// on one device, so it is set once per (device, kernel); safe to call from several host threads.
+inline hipError_t allow_full_lds(const void* kernel)
+{
+    static std::mutex mu;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({dev, kernel})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
+    if (e == hipSuccess) done.insert({dev, kernel});
+    return e;
+}
 
 using real = double;   // arithmetic type of every sweep
 

@@ -2062,33 +2062,18 @@ hipError_t launch_sweep_coop(bool backward, const SweepArgs& a, int grid, size_t
     const int maxw = backward ? CoopCfg<BL, true>::kMaxWaves : CoopCfg<BL, false>::kMaxWaves;
     if (a.nw < 1 || a.nw > maxw) return hipErrorInvalidValue;
     if (backward) {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwd_coop_kernel<BL, D, YLDS>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        e = allow_full_lds(reinterpret_cast<const void*>(&sweep_bwd_coop_kernel<BL, D, YLDS>));
+        if (e != hipSuccess) return e;
         if (a.uncompute) {
-            static bool attr_done_u = false;
-            if (!attr_done_u) {
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwdu_coop_kernel<BL, D, YLDS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-                if (e != hipSuccess) return e;
-                attr_done_u = true;
-            }
+            e = allow_full_lds(reinterpret_cast<const void*>(&sweep_bwdu_coop_kernel<BL, D, YLDS>));
+            if (e != hipSuccess) return e;
             hipLaunchKernelGGL((sweep_bwdu_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
         } else {
             hipLaunchKernelGGL((sweep_bwd_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
         }
     } else {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_fwd_coop_kernel<BL, D, YLDS>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        e = allow_full_lds(reinterpret_cast<const void*>(&sweep_fwd_coop_kernel<BL, D, YLDS>));
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((sweep_fwd_coop_kernel<BL, D, YLDS>), dim3(grid), dim3(a.nw * kWave), lds, st, a);
     }
     return hipGetLastError();
@@ -2100,33 +2085,18 @@ hipError_t launch_sweep_one(bool backward, const SweepArgs& a, int grid, size_t 
     hipError_t e;
     if (a.coop) return launch_sweep_coop<BL, D, YLDS>(backward, a, grid, lds, st);
     if (backward) {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwd_kernel<BL, D, YLDS>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        e = allow_full_lds(reinterpret_cast<const void*>(&sweep_bwd_kernel<BL, D, YLDS>));
+        if (e != hipSuccess) return e;
         if (a.uncompute) {
-            static bool attr_done_u = false;
-            if (!attr_done_u) {
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_bwdu_kernel<BL, D, YLDS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-                if (e != hipSuccess) return e;
-                attr_done_u = true;
-            }
+            e = allow_full_lds(reinterpret_cast<const void*>(&sweep_bwdu_kernel<BL, D, YLDS>));
+            if (e != hipSuccess) return e;
             hipLaunchKernelGGL((sweep_bwdu_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
         } else {
             hipLaunchKernelGGL((sweep_bwd_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
         }
     } else {
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_fwd_kernel<BL, D, YLDS>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        e = allow_full_lds(reinterpret_cast<const void*>(&sweep_fwd_kernel<BL, D, YLDS>));
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((sweep_fwd_kernel<BL, D, YLDS>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     }
     return hipGetLastError();

@@ -451,13 +451,7 @@ __global__ __launch_bounds__(8 * kWave) void lock_bwd_kernel(SweepArgs a)
 template <int BL, int D, int M, int LL>
 hipError_t launch_lock_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M, LL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&lock_fwd_kernel<BL, D, M, LL>)); e != hipSuccess) return e;
     hipLaunchKernelGGL((lock_fwd_kernel<BL, D, M, LL>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
     return hipGetLastError();
 }
@@ -465,13 +459,7 @@ hipError_t launch_lock_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t
 template <int BL, int D, int M, int PHASE, int LL>
 hipError_t launch_lock_bwd_phase(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M, PHASE, LL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&lock_bwd_kernel<BL, D, M, PHASE, LL>)); e != hipSuccess) return e;
     hipLaunchKernelGGL((lock_bwd_kernel<BL, D, M, PHASE, LL>), dim3(grid), dim3(lock_waves(a.lk_ns) * kWave), lds, st, a);
     return hipGetLastError();
 }

@@ -358,13 +358,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M))
 template <int BL, int D, int M, int LL>
 hipError_t launch_solo_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_fwd_kernel<BL, D, M, LL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&solo_fwd_kernel<BL, D, M, LL>)); e != hipSuccess) return e;
     hipLaunchKernelGGL((solo_fwd_kernel<BL, D, M, LL>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     return hipGetLastError();
 }
@@ -372,13 +366,7 @@ hipError_t launch_solo_fwd(const SweepArgs& a, int grid, size_t lds, hipStream_t
 template <int BL, int D, int M, int PHASE, int LL>
 hipError_t launch_solo_bwd_phase(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M, PHASE, LL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&solo_bwd_kernel<BL, D, M, PHASE, LL>)); e != hipSuccess) return e;
     hipLaunchKernelGGL((solo_bwd_kernel<BL, D, M, PHASE, LL>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     return hipGetLastError();
 }

@@ -445,14 +445,9 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_bwd_kernel(SweepAr
 template <int KC>
 hipError_t launch_tile_k(bool backward, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
 {
-    static bool attr_done[2] = {false, false};
     const void* fn = backward ? reinterpret_cast<const void*>(&tile_bwd_kernel<KC>)
                               : reinterpret_cast<const void*>(&tile_fwd_kernel<KC>);
-    if (!attr_done[backward]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCU);
-        if (e != hipSuccess) return e;
-        attr_done[backward] = true;
-    }
+    if (hipError_t e = allow_full_lds(fn); e != hipSuccess) return e;
     if (backward) hipLaunchKernelGGL((tile_bwd_kernel<KC>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     else hipLaunchKernelGGL((tile_fwd_kernel<KC>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
     return hipGetLastError();
