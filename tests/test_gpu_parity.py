@@ -1189,6 +1189,30 @@ def test_symmetry_and_batch_independence():
         assert K[n, m] == sk.sigkernel_fwd(x[n:n + 1].contiguous(), y[m:m + 1].contiguous(), 1, 1)[0]
 
 
+def test_repeated_calls_kernel_values_bitwise_gradients_to_rounding():
+    # Kernel values are computed by one wave in a fixed order: the same bits every time.  Gradient sums are collected
+    # with floating-point atomics whose order of arrival varies from launch to launch: equal up to rounding (1e-13 of
+    # the tensor's scale), which is what the library states about them.
+    for name, nx, ny in (("c3", 40, 36), ("c5", 48, 40)):
+        w, X, Y = workloads.make(name, n_x=nx, n_y=ny)
+        W = dev(workloads.upstream_weights(77, (nx, ny)))
+        x, y = dev(X), dev(Y)
+        runs = [sk.sigkernel_gram(x, y, W, w.lam, w.lam, w.flags) for _ in range(3)]
+        torch.cuda.synchronize()
+        for K, gX, gY in runs[1:]:
+            assert torch.equal(K, runs[0][0])
+            for g, g0 in ((gX, runs[0][1]), (gY, runs[0][2])):
+                assert float((g - g0).abs().max() / g0.abs().max().clamp(min=1.0)) <= 1e-13
+    w, X, Y = workloads.make("c2", n_x=16, n_y=16)
+    gk = dev(workloads.upstream_weights(78, (16,)))
+    runs = [sk.sigkernel_bwd(dev(X), dev(Y), gk, w.lam, w.lam, w.flags) for _ in range(3)]
+    torch.cuda.synchronize()
+    for k, gx, gy in runs[1:]:
+        assert torch.equal(k, runs[0][0])
+        for g, g0 in ((gx, runs[0][1]), (gy, runs[0][2])):
+            assert float((g - g0).abs().max() / g0.abs().max().clamp(min=1.0)) <= 1e-13
+
+
 def test_only_one_gradient_requested():
     X = rand_paths(91, 4, 20, 3)
     Y = rand_paths(92, 4, 25, 3)
