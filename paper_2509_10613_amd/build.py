@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsigkernel.so")
-SOURCES = ["sk_api.hip", "sk_kernels.hip", "sk_lockstep.hip", "sk_solo.hip", "sk_tile.hip", "sk_band.hip", "sg_horner.hip", "sg_horner_bwd.hip"]
-HEADERS = ["sk_plan.h", "sk_kernels.h", "sk_dev.h", "sk_lane.h", "sg_plan.h", "sg_kernels.h", "sg_dev.h"]
+SOURCES = ["sk_api.hip", "sk_kernels.hip", "sk_lockstep.hip", "sk_solo.hip", "sk_tile.hip", "sk_tile_bwd.hip", "sk_band.hip", "sg_horner.hip", "sg_horner_bwd.hip"]
+HEADERS = ["sk_plan.h", "sk_kernels.h", "sk_dev.h", "sk_lane.h", "sk_tile.h", "sg_plan.h", "sg_kernels.h", "sg_dev.h"]
 PUBLIC = ["sigkernel.h", "signature.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -42,7 +42,7 @@ def build(force: bool = False, verbose: bool = False, extra_flags=()) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
