@@ -277,13 +277,13 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M))
 #pragma unroll
                     for (int m = 0; m < M; ++m)
                         gp[m] = ((!EDGE || (unsigned)J[i & 1] < (unsigned)cf.nbl[m]) && !cf.off_block(m, J[i & 1])) ? accP[m] : 0.0;
-                    if (a.want_gx) {
+                    // (both sides are always formed: a call that wants one gradient only is rare, and two uniform
+                    // branches per macro-step cost every call; the flushes below look at what is wanted)
 #pragma unroll
-                        for (int m = 0; m < M; ++m)
+                    for (int m = 0; m < M; ++m)
 #pragma unroll
-                            for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp[m], y[i & 1][c], gacc[m][c]);
-                    }
-                    if (a.want_gy) {
+                        for (int c = 0; c < D; ++c) gacc[m][c] = fma(gp[m], y[i & 1][c], gacc[m][c]);
+                    {
                         SK_LDS real* gq = gyp + __mul24(b[i & 1], LK::DSc);
                         real t[D];
 #pragma unroll
@@ -295,8 +295,11 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M))
                         }
                         if (plain) {
                             if (!EDGE || (unsigned)J[i & 1] < (unsigned)nb) {
+                                real o[D];   // every read before the first write: one wait instead of one per channel
 #pragma unroll
-                                for (int c = 0; c < D; ++c) gq[c] += t[c];
+                                for (int c = 0; c < D; ++c) o[c] = gq[c];
+#pragma unroll
+                                for (int c = 0; c < D; ++c) gq[c] = o[c] + t[c];
                             }
                         } else {
 #pragma unroll
@@ -338,9 +341,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M))
                         }
                     }
                 }
-                if (a.want_gy) {
-                    for (int t = lane; t < ny; t += kWave) { gyl[t] += gyp[t]; gyp[t] = 0.0; }
-                }
+                for (int t = lane; t < ny; t += kWave) { gyl[t] += gyp[t]; gyp[t] = 0.0; }
             } else {
                 // nothing of this pair is kept: the replay kernel solves it once more
                 for (int t = lane; t < ny; t += kWave) gyp[t] = 0.0;
