@@ -189,6 +189,7 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
     a.coop_ring_stride = (unsigned)p.coop_ring_stride;
     a.solo = p.solo;
     a.tile = p.tile;
+    a.quad = p.quad; a.qd_nquads = p.nquads;
     a.band = p.band; a.bd_nbands = p.bd_nbands;
     a.bd_off_y = (unsigned)p.bd_off_y; a.bd_off_gy = (unsigned)p.bd_off_gy; a.bd_off_rings = (unsigned)p.bd_off_rings;
     a.bd_flags = reinterpret_cast<int*>(base + p.off_flags);
@@ -272,6 +273,7 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
     if (ttag) SK_CHECK(ev.begin((backward && phase != 1) ? 1 : 0, ttag, st));   // a kept forward sweep counts as a forward launch
     if (p.band) SK_CHECK(launch_sweep_band(phase ? phase + 1 : (backward ? 1 : 0), p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
+    else if (p.quad) SK_CHECK(launch_sweep_quad(p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
@@ -723,6 +725,10 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         else
             std::snprintf(kern, sizeof(kern), "band_fwd_kernel<%d, %d, false, %d>", p.BL, p.DT, p.ll);
         threads = (sk::kBandStrips + 1) * sk::kWave;
+    } else if (p.quad) {
+        mode = "quad";
+        std::snprintf(kern, sizeof(kern), "quad_fwd_kernel<%d>", p.DT);
+        threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.tile) {
         mode = "tile";
         std::snprintf(kern, sizeof(kern), "tile_%s_kernel<%d>", backward ? "bwd" : "fwd", p.DT / 4);
@@ -751,8 +757,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
                   "mode=%s kernel=%s grid=%d threads=%d lds_bytes=%zu strips=%d rows_per_lane=%d fused=%d "
                   "kept_sweep_half=%d lead_lag_form=%s second_launch_lds_bytes=%zu workspace_bytes=%zu "
                   "drifted_pairs_counter_at=%zu",
-                  mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.band) ? p.lk_ns : p.ns,
-                  (p.lock || p.solo || p.tile || p.band) ? p.lk_M : 1,
+                  mode, kern, p.grid, threads, p.lds_bytes, (p.lock || p.solo || p.tile || p.quad || p.band) ? p.lk_ns : p.ns,
+                  (p.lock || p.solo || p.tile || p.quad || p.band) ? p.lk_M : 1,
                   fused ? 1 : 0, phase, lay.ll ? "checkerboard" : "none",
                   (lay.has_sc && backward && phase != 1) ? lay.sc.lds_bytes : (size_t)0, lay.total, p.off_badlist != 0 ? p.off_badcnt : (size_t)0);
     return SK_OK;

@@ -71,6 +71,8 @@ struct Plan {
     size_t off_badcnt = 0, off_badlist = 0;
     int ll = 0;     // lead-lag form of the sweep: 0 none, 1 the level lies inside a block, 2 above the blocks
     int tile = 0;   // one wave per pair, at most 64 x 64 cells, contractions on the matrix cores (sk_tile.hip)
+    int quad = 0;   // four pairs per wave, forward Gram calls on the tile kernels' shapes (sk_quad.hip)
+    int64_t nquads = 0;   // groups of four pairs of one Gram row the quad launch works through
     int solo = 0;   // one wave per pair, a single strip of 64 * lk_M block rows (many pairs of short paths)
     int lock = 0, lk_M = 0, lk_ns = 0, lk_NT = 0, lk_padb = 0, lk_rowlen = 0;
     size_t lk_off_y = 0, lk_off_gy = 0, lk_off_cring = 0, lk_off_gp = 0, lk_off_krows = 0, lk_off_arows = 0,
@@ -111,6 +113,8 @@ constexpr int solo_bwd_waves_per_simd(int BL, int M) { return (BL >= 2 && M >= 2
 // kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most
 // two-way bank conflicted), kTileCols columns (-1 .. 64: a zero guard column on either side).
 constexpr int kTileStride = 66, kTileCols = 66;
+// Quad mode: a wavefront works on four pairs that share the y path, 16 lanes and four grid rows per lane each.
+constexpr int kQuadPairs = 4, kQuadRows = 4;
 constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
 
 // Band mode: strips per workgroup, block columns per hand-over ring, coarse y columns per y ring (powers of
@@ -392,6 +396,25 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.npairs = nx * (nx + 1) / 2;
         const int64_t want = (p.npairs + kWavesPerWG - 1) / kWavesPerWG;
         if (want < p.grid) p.grid = (int)want;
+        p.nslots = (int64_t)p.grid * kWavesPerWG;
+    }
+
+    // Quad mode: forward calls on the tile kernels' shapes, for Gram matrices (the four pairs of a wavefront share
+    // the y path).  The sequence is the Gram matrix row by row (y-major) in groups of four x paths; a symmetric
+    // Gram matrix has the pairs n <= m of row m only.  Two workgroups of four waves per compute unit.
+    if (p.tile && !backward && gram) {
+        p.tile = 0; p.quad = 1;
+        if (p.tri) {
+            const int64_t J = nx / kQuadPairs, e = nx % kQuadPairs;
+            p.nquads = 2 * J * (J + 1) + e * (J + 1);
+        } else {
+            p.nquads = ny * ((nx + kQuadPairs - 1) / kQuadPairs);
+        }
+        p.lk_M = kQuadRows;
+        p.lds_wave = align_up((size_t)p.nb * (p.DT + 2) * elem, 256);
+        p.lds_bytes = p.lds_wave * kWavesPerWG;
+        const int64_t want = (p.nquads + kWavesPerWG - 1) / kWavesPerWG;
+        p.grid = (int)(want < 2 * kNumCU ? want : 2 * kNumCU);
         p.nslots = (int64_t)p.grid * kWavesPerWG;
     }
 

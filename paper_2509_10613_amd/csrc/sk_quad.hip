@@ -1,0 +1,216 @@
+// Quad sweep (gfx950), forward: four path pairs per wavefront, for Gram matrices of many short paths with many
+// channels and no dyadic refinement (at most 64 x 64 cells per pair, 8 or 16 channels: forward calls on the shapes
+// the tile kernels take).
+//
+// A wavefront that gives one lane to every grid row of one pair walks 64 lanes over 63 columns: the skew of the
+// anti-diagonal sweep (Section 3.3) leaves half of its lane-steps outside the grid.  Here a pair has 16 lanes, each
+// with four consecutive grid rows, and the wavefront's four groups of 16 lanes work on four pairs at once, in
+// lock-step, so that a sweep takes nb + 15 macro-steps of four cells per lane instead of nb + 63 of one:
+//
+//  * the four pairs of a wavefront share the y path (pairs are taken in y-major order, four x paths at a time):
+//    its increments sit in the wavefront's LDS once, and the four groups read the same addresses (broadcast);
+//  * p = <dx[a], dy[b]> (Eq. (1), third line) is formed in registers: the lane keeps the increments of its four
+//    rows (4 x D doubles) and reads the D increments of its column once per macro-step, 16 bytes at a time (the
+//    row stride of the y copy, D + 2 doubles, keeps those reads free of bank conflicts);
+//  * the bottom edge of a lane goes to the lane below by a DPP shift inside its row of 16 lanes; the first lane of
+//    a group holds the top of the grid (boundary value 1);
+//  * nothing is masked: a lane whose column lies outside the grid works with p = 0, i.e. A = B = 1, and the
+//    macro-steps whose 16 columns all lie inside the grid run without clamping or selects.
+//
+// The rows of a pair are aligned to the bottom of its 64 lane-rows (rows above the grid have zero increments), so the
+// result leaves through the last lane of the group.  The registers of a wavefront leave room for two per SIMD.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "sk_dev.h"
+#include "sk_kernels.h"
+#include "sk_lane.h"
+
+namespace sk {
+
+// lane i of a row of 16 lanes receives v of lane i - 1; the row's first lane receives edge (its own lane's value)
+__device__ __forceinline__ real row_from_above_or(real v, real edge)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    int elo = __double2loint(edge), ehi = __double2hiint(edge);
+    lo = __builtin_amdgcn_update_dpp(elo, lo, 0x111, 0xf, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(ehi, hi, 0x111, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Quad q of the sequence a launch works through: row yi of the Gram matrix in groups of four x paths, rows in
+// ascending order.  A row has N pairs, or, for a symmetric Gram matrix K(X, X), the yi + 1 pairs n <= yi.
+struct QuadCursor {
+    long yi, xi0, npr;
+    __device__ __forceinline__ void locate(const SweepArgs& a, long u)
+    {
+        if (!a.tri) {
+            const long per_row = (a.gramN + kQuadPairs - 1) / kQuadPairs;
+            yi = u / per_row;
+            xi0 = (u - yi * per_row) * kQuadPairs;
+            npr = a.gramN;
+        } else {
+            // rows 4 j .. 4 j + 3 hold j + 1 quads each: 2 j (j + 1) quads lie before row 4 j
+            long j = (long)((sqrt(2.0 * (double)u + 1.0) - 1.0) * 0.5);
+            while (2 * (j + 1) * (j + 2) <= u) ++j;
+            while (2 * j * (j + 1) > u) --j;
+            const long rest = u - 2 * j * (j + 1);
+            yi = 4 * j + rest / (j + 1);
+            xi0 = (rest % (j + 1)) * kQuadPairs;
+            npr = yi + 1;
+        }
+    }
+    __device__ __forceinline__ void next(const SweepArgs& a)
+    {
+        xi0 += kQuadPairs;
+        if (xi0 >= npr) {
+            xi0 = 0;
+            ++yi;
+            if (a.tri) npr = yi + 1;
+        }
+    }
+};
+
+template <int D>
+__global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int M = kQuadRows, LP = kWave / kQuadPairs, YS = D + 2;
+    using LK = Lock<0, D, M>;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, r = lane & (LP - 1);
+    const long slot = (long)blockIdx.x * kWavesPerWG + w;
+    const long nslots = (long)gridDim.x * kWavesPerWG;
+    SK_LDS real* ylds = (SK_LDS real*)(smem + (size_t)w * a.lds_wave);
+    const long u0 = slot * a.qd_nquads / nslots, u1 = (slot + 1) * a.qd_nquads / nslots;
+    const int nb = a.nb, nbm1 = a.nb - 1;
+    const int NT = nb + LP - 1;
+    long cur_y = -1;
+    if (u0 >= u1) return;
+
+    QuadCursor cur;
+    cur.locate(a, u0);
+    typename LK::Fwd f;
+    for (long u = u0; u < u1; ++u, cur.next(a)) {
+        const long yi = cur.yi;
+        if (yi != cur_y) {
+            // the y increments, row stride YS: a lane's 16-byte reads of its column meet no other lane's banks
+            const real* dyg = a.dy + yi * a.ystride;
+            for (int t = lane; t < a.q * D; t += kWave) {
+                const int b = t / D, c = t - b * D;
+                ylds[b * YS + c] = dyg[(long)b * a.DS + c];
+            }
+            cur_y = yi;
+        }
+        const bool valid = cur.xi0 + g < cur.npr;
+        const long xi = valid ? cur.xi0 + g : cur.npr - 1;   // a group beyond the row's end repeats its last pair
+        // increments of the lane's rows (zero above the grid) and the time channel's constant product
+        real dxr[M][D], tcm[M];
+        {
+            const real* dxp = a.dx + xi * a.xstride;
+            // (every load is issued before the first value is used, from a row inside the array: a load under a
+            // condition would be waited for on the spot)
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int I = r * M + m - a.lk_padb;
+                const real* xp = dxp + (long)(I >= 0 ? I : 0) * a.DS;
+#pragma unroll
+                for (int c = 0; c < D; ++c) dxr[m][c] = xp[c];
+            }
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int I = r * M + m - a.lk_padb;
+                const real s = I >= 0 ? a.sc : 0.0;
+                tcm[m] = I >= 0 ? a.tc : 0.0;
+#pragma unroll
+                for (int c = 0; c < D; ++c) dxr[m][c] *= s;
+            }
+        }
+        f.init();
+
+        auto fetch = [&](auto edge_c, int T, int& J, real (&y)[D]) {
+            constexpr bool EDGE = decltype(edge_c)::value;
+            J = T - r;
+            const int b = EDGE ? clamp_col(J, nbm1) : J;
+            const SK_LDS real2* yp = (const SK_LDS real2*)(ylds + __mul24(b, YS));
+#pragma unroll
+            for (int c = 0; c < D / 2; ++c) {
+                const real2 v = yp[c];
+                y[2 * c] = v.x;
+                y[2 * c + 1] = v.y;
+            }
+        };
+        auto step = [&](auto edge_c, int J, const real (&y)[D]) {
+            constexpr bool EDGE = decltype(edge_c)::value;
+            real Ac[M], Bc[M];
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                real p = dxr[m][0] * y[0];
+#pragma unroll
+                for (int c = 1; c < D; ++c) p = fma(dxr[m][c], y[c], p);
+                p += tcm[m];
+                if constexpr (EDGE) p = (unsigned)J < (unsigned)nb ? p : 0.0;
+                LK::coef_fwd(p, Ac[m], Bc[m]);
+            }
+            real recv[1];
+            recv[0] = row_from_above_or(f.bot[0], 1.0);
+            f.step(recv, Ac, Bc);
+        };
+        // macro-steps [T0, T1), the y increments fetched one step ahead
+        auto run = [&](auto edge_c, int T0, int T1) {
+            if (T0 >= T1) return;
+            int Ja, Jb;
+            real ya[D], yb[D];
+            fetch(edge_c, T0, Ja, ya);
+            int T = T0;
+            for (; T + 2 <= T1; T += 2) {
+                fetch(edge_c, T + 1, Jb, yb);
+                step(edge_c, Ja, ya);
+                fetch(edge_c, T + 2 < T1 ? T + 2 : T + 1, Ja, ya);
+                step(edge_c, Jb, yb);
+            }
+            if (T < T1) step(edge_c, Ja, ya);
+        };
+        const int Ti = nb > LP - 1 ? LP - 1 : NT;   // end of the leading edge range
+        run(std::true_type(), 0, Ti);
+        if (nb > LP - 1) {
+            run(std::false_type(), LP - 1, nb);
+            run(std::true_type(), nb, NT);
+        }
+        if (r == LP - 1 && valid) {
+            const long N = a.gramN;
+            const long pid = a.tri ? xi * N + yi : xi * a.gramM + yi;
+            a.k_out[pid] = f.bot[0];
+            if (a.tri && xi != yi) a.k_out[yi * N + xi] = f.bot[0];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// launcher
+// ------------------------------------------------------------------------------------------------
+template <int D>
+static hipError_t launch_quad_fwd_d(const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&quad_fwd_kernel<D>)); e != hipSuccess) return e;
+    hipLaunchKernelGGL((quad_fwd_kernel<D>), dim3(grid), dim3(kWavesPerWG * kWave), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_sweep_quad(int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st)
+{
+    // what the kernel assumes about the launch
+    if (!a.gramM || !a.k_out || a.rs1 != 0 || a.rs2 != 0 || a.ll != 0 || a.mb < 1 || a.mb > kWave || a.nb < 1 || a.q != a.nb ||
+        a.lk_padb != kWave - a.mb || a.DS < DT || a.d > DT || a.qd_nquads < 1 ||
+        (size_t)a.nb * (DT + 2) * sizeof(real) > a.lds_wave || (size_t)a.lds_wave * kWavesPerWG > lds)
+        return hipErrorInvalidValue;
+    switch (DT) {
+        case 8: return launch_quad_fwd_d<8>(a, grid, lds, st);
+        case 16: return launch_quad_fwd_d<16>(a, grid, lds, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sk

@@ -113,8 +113,8 @@ def test_launch_plan_of_the_five_configurations(lib):
         == q(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, HAVE, f64)
     assert 6 << 30 < int(p1["workspace_bytes"]) < 8 << 30          # 65536 pairs x 26 checkpoints of 8 x 64 doubles
     assert q(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64) < 1 << 30
-    # tile mode keeps its checkpoints in LDS: no such form
-    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, KEEP, f64)["kernel"] == "tile_fwd_kernel<4>"
+    # tile mode keeps its checkpoints in LDS: no such form (the forward call takes the quad kernel as without the flag)
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, KEEP, f64)["kernel"] == "quad_fwd_kernel<16>"
     assert _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f32)["kernel"] == "lock_bwd_kernel<1, 5, 2, 0, 0>"
     # c1: tiny, one strip: stencil, coefficient and auxiliary wave
     p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
@@ -123,9 +123,13 @@ def test_launch_plan_of_the_five_configurations(lib):
     # strip (127 block rows at two per lane)
     p = _plan(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64)
     assert p["mode"] == "solo" and p["kernel"] == "solo_bwd_kernel<1, 3, 2, 0, 0>" and p["strips"] == "1"
-    # c5 (1048576 pairs, 63 x 63 unrefined cells, 16 channels): the channel contraction dominates -> tile mode,
+    # c5 (1048576 pairs, 63 x 63 unrefined cells, 16 channels).  Forward: quad mode, four pairs of a Gram row per
+    # wave (16 lanes with four grid rows each per pair), two workgroups per compute unit; a pair batch of that shape
+    # has no shared y path and takes the tile kernel.  Backward: the channel contraction dominates -> tile mode,
     # increment Gram matrix of a pair in LDS, contractions on the matrix cores, one workgroup per compute unit
     p = _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
+    assert p["mode"] == "quad" and p["kernel"] == "quad_fwd_kernel<16>" and p["grid"] == "512" and p["rows_per_lane"] == "4"
+    p = _plan(binding.SK_OP_FWD, 100000, 0, 64, 64, 16, 0, 0, 0, f64)
     assert p["mode"] == "tile" and p["kernel"] == "tile_fwd_kernel<4>" and p["grid"] == "256"
     p = _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
     assert p["mode"] == "tile" and p["kernel"] == "tile_bwd_kernel<4>" and int(p["lds_bytes"]) <= 160 * 1024
