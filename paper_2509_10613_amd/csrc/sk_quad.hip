@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
                 y[2 * c + 1] = v.y;
             }
         };
-        auto step = [&](auto edge_c, int J, const real (&y)[D]) {
+        auto step = [&](auto edge_c, auto tc_c, int J, const real (&y)[D]) {
             constexpr bool EDGE = decltype(edge_c)::value;
             real Ac[M], Bc[M];
 #pragma unroll
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
                 real p = dxr[m][0] * y[0];
 #pragma unroll
                 for (int c = 1; c < D; ++c) p = fma(dxr[m][c], y[c], p);
-                p += tcm[m];
+                if constexpr (decltype(tc_c)::value) p += tcm[m];
                 if constexpr (EDGE) p = (unsigned)J < (unsigned)nb ? p : 0.0;
                 LK::coef_fwd(p, Ac[m], Bc[m]);
             }
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
             f.step(recv, Ac, Bc);
         };
         // macro-steps [T0, T1), the y increments fetched one step ahead
-        auto run = [&](auto edge_c, int T0, int T1) {
+        auto run = [&](auto edge_c, auto tc_c, int T0, int T1) {
             if (T0 >= T1) return;
             int Ja, Jb;
             real ya[D], yb[D];
@@ -167,18 +167,23 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
             int T = T0;
             for (; T + 2 <= T1; T += 2) {
                 fetch(edge_c, T + 1, Jb, yb);
-                step(edge_c, Ja, ya);
+                step(edge_c, tc_c, Ja, ya);
                 fetch(edge_c, T + 2 < T1 ? T + 2 : T + 1, Ja, ya);
-                step(edge_c, Jb, yb);
+                step(edge_c, tc_c, Jb, yb);
             }
-            if (T < T1) step(edge_c, Ja, ya);
+            if (T < T1) step(edge_c, tc_c, Ja, ya);
         };
-        const int Ti = nb > LP - 1 ? LP - 1 : NT;   // end of the leading edge range
-        run(std::true_type(), 0, Ti);
-        if (nb > LP - 1) {
-            run(std::false_type(), LP - 1, nb);
-            run(std::true_type(), nb, NT);
-        }
+        // (tc_c: whether there is a time channel; without one its constant is not added)
+        auto sweep = [&](auto tc_c) {
+            const int Ti = nb > LP - 1 ? LP - 1 : NT;   // end of the leading edge range
+            run(std::true_type(), tc_c, 0, Ti);
+            if (nb > LP - 1) {
+                run(std::false_type(), tc_c, LP - 1, nb);
+                run(std::true_type(), tc_c, nb, NT);
+            }
+        };
+        if (a.tc != 0.0) sweep(std::true_type());
+        else sweep(std::false_type());
         if (r == LP - 1 && valid) {
             const long N = a.gramN;
             const long pid = a.tri ? xi * N + yi : xi * a.gramM + yi;

@@ -62,7 +62,8 @@ struct Tile {
         }
     }
     // Delta tiles into P.  Result register r of lane l of tile (J, I) is Delta[a = 16 I + l % 16][b = 16 J + l / 16 + 4 r].
-    // The time channel adds its constant product inside the grid only.
+    // The time channel adds its constant product inside the grid only (TC = false: there is none, tc is zero).
+    template <bool TC = true>
     static __device__ __forceinline__ void gram_tiles(SK_LDS real* P, const real (&yb)[4][KC], const real (&xb)[4][KC],
                                                       int lane, int padb, int nb, real tc)
     {
@@ -79,7 +80,8 @@ struct Tile {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int b = 16 * J + g16 + 4 * r;
-                    const real v = acc[r] + ((al >= padb && b < nb) ? tc : 0.0);
+                    real v = acc[r];
+                    if constexpr (TC) v += (al >= padb && b < nb) ? tc : 0.0;
                     P[(b + 1) * kTileStride + al] = v;
                 }
             }

@@ -62,7 +62,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 1) void tile_fwd_kernel(SweepAr
         }
         real xb[4][KC];
         TL::load_b(a.dx + xi * a.xstride, a.DS, padb, lane, xb);
-        TL::gram_tiles(P, yb, xb, lane, padb, nb, a.tc);
+        if (a.tc != 0.0) TL::template gram_tiles<true>(P, yb, xb, lane, padb, nb, a.tc);
+        else TL::template gram_tiles<false>(P, yb, xb, lane, padb, nb, 0.0);
 
         f.init();
         auto readp = [&](int J) { return P[__mul24(read_col(J, nb), kTileStride) + pbase]; };

@@ -104,7 +104,8 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             cur_y = yi;
             gdy_cur = a.gdy + yi * a.ystride;
         }
-        TL::gram_tiles(P, yb, xb, lane, padb, nb, a.tc);
+        if (a.tc != 0.0) TL::template gram_tiles<true>(P, yb, xb, lane, padb, nb, a.tc);
+        else TL::template gram_tiles<false>(P, yb, xb, lane, padb, nb, 0.0);
 
         // ---- phase 1: forward; a checkpoint every CK chunks and the bottom row into LDS ----
         real kR0, kR1;   // exact state the reverse sweep starts from: k[a][J], k[a + 1][J]
