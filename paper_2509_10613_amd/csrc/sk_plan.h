@@ -411,7 +411,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
             p.nquads = ny * ((nx + kQuadPairs - 1) / kQuadPairs);
         }
         p.lk_M = kQuadRows;
-        p.lds_wave = align_up((size_t)p.nb * (p.DT + 2) * elem, 256);
+        p.lds_wave = align_up((size_t)(p.nb + 1) * (p.DT + 2) * elem, 256);   // the y copy and a row of zeros
         p.lds_bytes = p.lds_wave * kWavesPerWG;
         const int64_t want = (p.nquads + kWavesPerWG - 1) / kWavesPerWG;
         p.grid = (int)(want < 2 * kNumCU ? want : 2 * kNumCU);

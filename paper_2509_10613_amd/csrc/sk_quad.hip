@@ -14,8 +14,8 @@
 //    row stride of the y copy, D + 2 doubles, keeps those reads free of bank conflicts);
 //  * the bottom edge of a lane goes to the lane below by a DPP shift inside its row of 16 lanes; the first lane of
 //    a group holds the top of the grid (boundary value 1);
-//  * nothing is masked: a lane whose column lies outside the grid works with p = 0, i.e. A = B = 1, and the
-//    macro-steps whose 16 columns all lie inside the grid run without clamping or selects.
+//  * nothing is masked: a lane whose column lies outside the grid reads a row of zeros behind the y copy and works
+//    with p = 0, i.e. A = B = 1, and the macro-steps whose 16 columns all lie inside the grid run without clamping.
 //
 // The rows of a pair are aligned to the bottom of its 64 lane-rows (rows above the grid have zero increments), so the
 // result leaves through the last lane of the group.  The registers of a wavefront leave room for two per SIMD.
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
     const long nslots = (long)gridDim.x * kWavesPerWG;
     SK_LDS real* ylds = (SK_LDS real*)(smem + (size_t)w * a.lds_wave);
     const long u0 = slot * a.qd_nquads / nslots, u1 = (slot + 1) * a.qd_nquads / nslots;
-    const int nb = a.nb, nbm1 = a.nb - 1;
+    const int nb = a.nb;
     const int NT = nb + LP - 1;
     long cur_y = -1;
     if (u0 >= u1) return;
@@ -98,9 +98,9 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
         if (yi != cur_y) {
             // the y increments, row stride YS: a lane's 16-byte reads of its column meet no other lane's banks
             const real* dyg = a.dy + yi * a.ystride;
-            for (int t = lane; t < a.q * D; t += kWave) {
+            for (int t = lane; t < (a.q + 1) * D; t += kWave) {   // and a row of zeros behind the last one
                 const int b = t / D, c = t - b * D;
-                ylds[b * YS + c] = dyg[(long)b * a.DS + c];
+                ylds[b * YS + c] = b < a.q ? dyg[(long)b * a.DS + c] : 0.0;
             }
             cur_y = yi;
         }
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
         auto fetch = [&](auto edge_c, int T, int& J, real (&y)[D]) {
             constexpr bool EDGE = decltype(edge_c)::value;
             J = T - r;
-            const int b = EDGE ? clamp_col(J, nbm1) : J;
+            const int b = EDGE ? (int)min((unsigned)J, (unsigned)nb) : J;   // outside the grid: the row of zeros
             const SK_LDS real2* yp = (const SK_LDS real2*)(ylds + __mul24(b, YS));
 #pragma unroll
             for (int c = 0; c < D / 2; ++c) {
@@ -150,8 +150,8 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, 2) void quad_fwd_kernel(SweepAr
                 real p = dxr[m][0] * y[0];
 #pragma unroll
                 for (int c = 1; c < D; ++c) p = fma(dxr[m][c], y[c], p);
-                if constexpr (decltype(tc_c)::value) p += tcm[m];
-                if constexpr (EDGE) p = (unsigned)J < (unsigned)nb ? p : 0.0;
+                // (outside the grid the column's increments read as zeros, so only the time constant is left to mask)
+                if constexpr (decltype(tc_c)::value) p += (!EDGE || (unsigned)J < (unsigned)nb) ? tcm[m] : 0.0;
                 LK::coef_fwd(p, Ac[m], Bc[m]);
             }
             real recv[1];
@@ -209,7 +209,7 @@ hipError_t launch_sweep_quad(int DT, const SweepArgs& a, int grid, size_t lds, h
     // what the kernel assumes about the launch
     if (!a.gramM || !a.k_out || a.rs1 != 0 || a.rs2 != 0 || a.ll != 0 || a.mb < 1 || a.mb > kWave || a.nb < 1 || a.q != a.nb ||
         a.lk_padb != kWave - a.mb || a.DS < DT || a.d > DT || a.qd_nquads < 1 ||
-        (size_t)a.nb * (DT + 2) * sizeof(real) > a.lds_wave || (size_t)a.lds_wave * kWavesPerWG > lds)
+        (size_t)(a.nb + 1) * (DT + 2) * sizeof(real) > a.lds_wave || (size_t)a.lds_wave * kWavesPerWG > lds)
         return hipErrorInvalidValue;
     switch (DT) {
         case 8: return launch_quad_fwd_d<8>(a, grid, lds, st);
