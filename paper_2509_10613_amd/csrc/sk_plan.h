@@ -115,6 +115,7 @@ constexpr int solo_bwd_waves_per_simd(int BL, int M) { return (BL >= 2 && M >= 2
 constexpr int kTileStride = 66, kTileCols = 66;
 // Quad mode: a wavefront works on four pairs that share the y path, 16 lanes and four grid rows per lane each.
 constexpr int kQuadPairs = 4, kQuadRows = 4;
+constexpr int kTileRowPad = 8;     // backward: node columns kept left of column 0 in the pair's bottom row (all 1)
 constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
 
 // Band mode: strips per workgroup, block columns per hand-over ring, coarse y columns per y ring (powers of
@@ -374,9 +375,11 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         // backward: compact checkpoints (two doubles per lane) every kTileCkChunks chunks of 8 macro-steps
         const int nck = backward ? (NT / kLockS - 1) / kTileCkChunks : 0;
         const size_t o_ck = nck ? lds_take((size_t)nck * 2 * kWave * elem) : 0;
+        // backward: the pair's bottom row, node columns -kTileRowPad .. 64 and slack up to a multiple of eight
+        const size_t o_kr = backward ? lds_take((size_t)(kTileRowPad + kWave + 8) * elem) : 0;
         p.tile = 1; p.solo = 0; p.coop = 0;
         p.lk_M = 1; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave - p.mb;
-        p.lk_off_y = 0; p.lk_off_gy = 0; p.lk_off_krows = 0; p.lk_off_dump = 0; p.lk_off_ck = o_ck;
+        p.lk_off_y = 0; p.lk_off_gy = 0; p.lk_off_krows = o_kr; p.lk_off_dump = 0; p.lk_off_ck = o_ck;
         p.y_lds = 0;
         p.lds_wave = used;
         p.lds_bytes = used * kWavesPerWG;   // one workgroup per compute unit

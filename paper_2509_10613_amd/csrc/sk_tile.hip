@@ -115,7 +115,8 @@ hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid
         a.lk_padb != kWave - a.mb || a.rpad < kWave || a.qpad < kWave || a.DS <= DT || a.d > DT ||
         (backward && (!a.bad_list || !a.bad_count || (a.lk_NT % kLockS) != 0 || a.lk_NT < a.nb + kWave - 1 || a.lk_NT >= a.nb + kWave - 1 + kLockS ||
                       (size_t)a.lk_off_ck + (size_t)((a.lk_NT / kLockS - 1) / kTileCkChunks) * 2 * kWave * sizeof(real) >
-                          a.lds_wave)))
+                          a.lk_off_krows ||
+                      (size_t)a.lk_off_krows + (size_t)(kTileRowPad + kWave + 8) * sizeof(real) > a.lds_wave)))
         return hipErrorInvalidValue;
     if (backward) return launch_tile_bwd(DT, a, grid, st);
     switch (DT) {

@@ -32,13 +32,15 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
     // Checkpoints of the forward sweep, in LDS: per lane the last two values of its row, k[a + 1][J] and
     // k[a + 1][J - 1] (J the column the lane is about to process); the row above is the neighbouring lane's.
     SK_LDS real* ckl = (SK_LDS real*)(mylds + a.lk_off_ck) + lane;
-    // The bottom row of the pair (the last lane's outputs, which no lane recovers in the reverse sweep) sits
-    // in the spare slot 64 of P's columns, by node column c = -1 .. 64 (every node left of the grid is 1).
-    SK_LDS real* const krow = P + kTileStride + kWave;
+    // The bottom row of the pair (the last lane's outputs, which no lane recovers in the reverse sweep) has an array
+    // of its own, by node column: krow[c] for c = -8 .. 64 (every node left of the grid is 1, and a chunk of eight
+    // macro-steps that lies wholly left of column -8 neither writes nor reads).  Contiguous, so that the eight values
+    // of a chunk move two per LDS instruction.
     // Macro-steps run from 0 to NT - 1 with NT a multiple of S; the sweep proper ends at the last one (the last lane at
     // the last column), so that the reverse sweep starts with the seed in place, and begins tpad steps late.
     const int NT = a.lk_NT;
     const int tpad = NT - (a.nb + kWave - 1);   // 0 .. S - 1
+    SK_LDS real* const krow = (SK_LDS real*)(mylds + a.lk_off_krows) + kTileRowPad;
     const long q0 = slot * a.npairs / nslots, q1 = (slot + 1) * a.npairs / nslots;
     const int nb = a.nb, padb = a.lk_padb;
     const int nch = NT / S;
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
     real* gdy_cur = nullptr;
 
     P[(kTileCols - 1) * kTileStride + lane] = 0.0;   // column 64: the zero column of a pair with 64 columns
-    if (last) krow[-kTileStride] = 1.0;              // node column -1 (stands for all nodes left of the grid)
+    if (lane < kTileRowPad) krow[lane - kTileRowPad] = 1.0;   // node columns -8 .. -1
 
     real yb[4][KC], yc[16];
     real4 gy[4];
@@ -135,23 +137,18 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
                     f.step(recv, Ac, Bc);
                     kb[i] = f.bot[0];
                 }
-                if (last) {   // node columns left of the grid all go to the one slot that stands for them
-                    if (cl >= -1) {
-                        SK_LDS real* kp = krow + cl * kTileStride;
+                if (last && cl >= -kTileRowPad) {   // (further left every value is the boundary value 1)
+                    SK_LDS real* kp = krow + cl;
 #pragma unroll
-                        for (int i = 0; i < S; ++i) kp[i * kTileStride] = kb[i];
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < S; ++i) krow[(cl + i > -1 ? cl + i : -1) * kTileStride] = kb[i];
-                    }
+                    for (int i = 0; i < S; ++i) kp[i] = kb[i];
                 }
             }
             kR0 = f.left[0];
             kR1 = f.left[1];
         }
         if (a.k_out && lane == 0) {
-            a.k_out[pid] = krow[nb * kTileStride];
-            if (pid2 != pid) a.k_out[pid2] = krow[nb * kTileStride];
+            a.k_out[pid] = krow[nb];
+            if (pid2 != pid) a.k_out[pid2] = krow[nb];
         }
 
         // ---- phase 2: the mirror image; 6 G = 6 dF/dp replaces p in place ----
@@ -174,14 +171,14 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             for (int i = 0; i < S; ++i) pq[i] = readp(tb + i * kColBytes);
             int cl = (nch - 1) * S - tpad - (kWave - 1);   // node column under the last lane's block, first macro-step
             for (int g = nch - 1; g >= 0; --g, tb -= S * kColBytes, cl -= S) {
-                // the last lane's bottom edge, before any store of this chunk
-                if (cl >= -1) {
-                    const SK_LDS real* kp = krow + cl * kTileStride;
+                // the last lane's bottom edge
+                if (cl >= -kTileRowPad) {
+                    const SK_LDS real* kp = krow + cl;
 #pragma unroll
-                    for (int i = 0; i < S; ++i) kq[i] = kp[i * kTileStride];
+                    for (int i = 0; i < S; ++i) kq[i] = kp[i];
                 } else {
 #pragma unroll
-                    for (int i = 0; i < S; ++i) kq[i] = krow[(cl + i > -1 ? cl + i : -1) * kTileStride];
+                    for (int i = 0; i < S; ++i) kq[i] = 1.0;
                 }
 #pragma unroll
                 for (int i = S - 1; i >= 0; --i) {
