@@ -7,7 +7,9 @@ namespace sk {
 // ------------------------------------------------------------------------------------------------
 // backward
 // ------------------------------------------------------------------------------------------------
-template <int KC>
+// PAIRS: the sweeps move p and dF/dp two columns per LDS instruction (grids of at most 63 columns: the zero column
+// then has another one behind it).
+template <int KC, bool PAIRS>
 __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -50,6 +52,7 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
 
     P[(kTileCols - 1) * kTileStride + lane] = 0.0;   // column 64: the zero column of a pair with 64 columns
     if (lane < kTileRowPad) krow[lane - kTileRowPad] = 1.0;   // node columns -8 .. -1
+    if constexpr (PAIRS) P[lane] = 0.0;                        // column -1 (reads as zero in the sweeps)
 
     real yb[4][KC], yc[16];
     real4 gy[4];
@@ -80,6 +83,25 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
         int o;
         asm("v_med3_i32 %0, %1, %2, %3" : "=v"(o) : "v"(t), "v"(t_unread), "v"((int)t_zero));
         *(SK_LDS real*)((SK_LDS char*)P + kColBytes + o) = v;
+    };
+    // Two columns at once (PAIRS), J and J + 1, with one clamp on the byte offset u = t + kColBytes of (J, lane) from
+    // column -1.  Reads: J from -1 to nb as it is (column -1 reads as zero: it is cleared before every pair, and a lane
+    // writes there only after its last read of it; columns nb and nb + 1 are zero), anything else the zero columns.
+    // Writes: the same, except that a pair wholly left of the grid (u < 0) goes to two spare slots (slot 64 of the
+    // columns lane and lane + 1, which no one reads).
+    const unsigned u_zero = t_zero + kColBytes;
+    const unsigned u_dump = (unsigned)(lane * kColBytes + kWave * (int)sizeof(real));
+    auto readp2 = [&](int t, real& lo, real& hi) {
+        const SK_LDS real* bp = (const SK_LDS real*)((const SK_LDS char*)P + min((unsigned)(t + kColBytes), u_zero));
+        lo = bp[0];
+        hi = bp[kTileStride];
+    };
+    auto writep2 = [&](int t, real lo, real hi) {
+        const int u = t + kColBytes;
+        const unsigned o = u < 0 ? u_dump : min((unsigned)u, u_zero);
+        SK_LDS real* bp = (SK_LDS real*)((SK_LDS char*)P + o);
+        bp[0] = lo;
+        bp[kTileStride] = hi;
     };
 
     // Operands of the pair in work, loaded while the previous pair was in the linear map.
@@ -117,7 +139,10 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             real pq[S];
             int tn = (-tpad - lane) * kColBytes + lane8;   // t of the next macro-step to fetch p for
 #pragma unroll
-            for (int i = 0; i < S; ++i) pq[i] = readp(tn + i * kColBytes);
+            for (int i = 0; i < S; ++i) {
+                if constexpr (!PAIRS) pq[i] = readp(tn + i * kColBytes);
+                else if (i % 2 == 0) readp2(tn + i * kColBytes, pq[i], pq[i + 1]);
+            }
             tn += S * kColBytes;
             int cl = -tpad - (kWave - 1) + 1;   // node column the last lane writes in the chunk's first macro-step
             for (int g = 0; g < nch; ++g, tn += S * kColBytes, cl += S) {
@@ -127,10 +152,14 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
                     cp[kWave] = f.blc;
                 }
                 real kb[S];   // the lane's bottom values of the chunk; the last lane's are the pair's bottom row
+                real pnext = 0.0;
 #pragma unroll
                 for (int i = 0; i < S; ++i) {
                     const real p = pq[i];
-                    pq[i] = readp(tn + i * kColBytes);   // past the last step: the zero column, unused
+                    // the next chunk's p (past the last step: the zero column, unused)
+                    if constexpr (!PAIRS) pq[i] = readp(tn + i * kColBytes);
+                    else if (i % 2 == 0) readp2(tn + i * kColBytes, pq[i], pnext);
+                    else pq[i] = pnext;
                     real Ac[1], Bc[1], recv[1];
                     TL::coef_fwd(p, Ac[0], Bc[0]);
                     recv[0] = wave_from_above_or(f.bot[0], 1.0);
@@ -168,7 +197,10 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             // t of this lane's column in the first macro-step of the chunk
             int tb = ((nch - 1) * S - tpad - lane) * kColBytes + lane8;
 #pragma unroll
-            for (int i = 0; i < S; ++i) pq[i] = readp(tb + i * kColBytes);
+            for (int i = 0; i < S; ++i) {
+                if constexpr (!PAIRS) pq[i] = readp(tb + i * kColBytes);
+                else if (i % 2 == 0) readp2(tb + i * kColBytes, pq[i], pq[i + 1]);
+            }
             int cl = (nch - 1) * S - tpad - (kWave - 1);   // node column under the last lane's block, first macro-step
             for (int g = nch - 1; g >= 0; --g, tb -= S * kColBytes, cl -= S) {
                 // the last lane's bottom edge
@@ -180,10 +212,14 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
 #pragma unroll
                     for (int i = 0; i < S; ++i) kq[i] = 1.0;
                 }
+                real pnext = 0.0, ghold = 0.0;
 #pragma unroll
                 for (int i = S - 1; i >= 0; --i) {
                     const real p = pq[i];
-                    pq[i] = readp(tb + (i - S) * kColBytes);   // left of the grid: the zero column
+                    // the next chunk's p (left of the grid: the zero column)
+                    if constexpr (!PAIRS) pq[i] = readp(tb + (i - S) * kColBytes);
+                    else if (i % 2 == 1) readp2(tb + (i - 1 - S) * kColBytes, pnext, pq[i]);
+                    else pq[i] = pnext;
                     real Ac, Bc, iB;
                     LK::coef_rev(p, Ac, Bc, iB);
                     const real recv = wave_shift_down(rv.up[0]);   // nothing enters under the last lane
@@ -204,7 +240,9 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
                     // right of the grid dF/dp is an exact zero (the adjoint is zero there) and lands in the zero
                     // column; left of the grid it is not zero (the adjoint has left the grid) and lands in the
                     // column nobody reads
-                    writep(tb + i * kColBytes, accP6);
+                    if constexpr (!PAIRS) writep(tb + i * kColBytes, accP6);
+                    else if (i % 2 == 1) ghold = accP6;
+                    else writep2(tb + i * kColBytes, accP6, ghold);
                 }
                 if (g > 0 && g % CK == 0) {
                     // the recovered state against the exact one, which replaces it: rounding errors of the inverse
@@ -223,6 +261,7 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             // the left end: the sweep started from the boundary value 1 in every lane
             if (!(fabs(rv.kR[0] - 1.0) <= kDriftTol * kscale) || !(fabs(rv.kR[1] - 1.0) <= kDriftTol * kscale)) drift = true;
         }
+        if constexpr (PAIRS) P[lane] = 0.0;   // column -1 took the dF/dp of lanes left of the grid
         // A pair whose inverse recurrence drifted adds nothing to the gradient sums (its G is not mapped) and is
         // listed for the replay kernel, which solves it once more.
         const bool passed = __ballot(drift) == 0ull;
@@ -248,19 +287,24 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             int lrow = g16 - padb;
             asm volatile("" : "+v"(lrow));
             real* gq = a.gdx + xi * a.xstride + (long)lrow * a.DS + n16;
+            // (the four row tiles advance together: four independent accumulators keep the matrix core busy while the
+            // operands of the next step are on their way, and two operands 16 rows apart come with one LDS instruction)
+            real4 acc[4];
 #pragma unroll
-            for (int I = 0; I < 4; ++I) {
-                real4 acc = {0.0, 0.0, 0.0, 0.0};
-                const SK_LDS real* gp = P + (g16 + 1) * kTileStride + 16 * I + n16;
+            for (int I = 0; I < 4; ++I) acc[I] = real4{0.0, 0.0, 0.0, 0.0};
+            const SK_LDS real* gp = P + (g16 + 1) * kTileStride + n16;
 #pragma unroll
-                for (int kb = 0; kb < 16; ++kb)
-                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(gp[4 * kb * kTileStride], yc[kb], acc, 0, 0, 0);
+            for (int kb = 0; kb < 16; ++kb)
+#pragma unroll
+                for (int I = 0; I < 4; ++I)
+                    acc[I] = __builtin_amdgcn_mfma_f64_16x16x4f64(gp[4 * kb * kTileStride + 16 * I], yc[kb], acc[I], 0, 0, 0);
+#pragma unroll
+            for (int I = 0; I < 4; ++I)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int up = 16 * I + 4 * r;   // rows above the lane's first one
-                    if (lrow + up >= 0 && n16 < a.d) unsafeAtomicAdd(&gq[(long)up * a.DS], acc[r]);
+                    if (lrow + up >= 0 && n16 < a.d) unsafeAtomicAdd(&gq[(long)up * a.DS], acc[I][r]);
                 }
-            }
         }
         if (a.want_gy && passed) {
             // dF/d(dy)[b, c] = sum_a G[a, b] dx[a, c]: A operand G[4 ka + l / 16][16 J + l % 16], B operand xc[ka]
@@ -288,12 +332,19 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
 // workgroup of its own (its registers leave room for one wave per SIMD, so four of them share a compute unit all the
 // same, and the workgroup's LDS starts at address 0: no base to add); the forward kernel, with fewer registers, would be
 // packed unevenly onto the SIMDs that way (measured: 12.5 ms instead of 7.4) and keeps four waves per workgroup.
+template <int KC, bool PAIRS>
+static hipError_t launch_tile_bwd_p(const SweepArgs& a, int grid, hipStream_t st)
+{
+    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&tile_bwd_kernel<KC, PAIRS>)); e != hipSuccess) return e;
+    hipLaunchKernelGGL((tile_bwd_kernel<KC, PAIRS>), dim3((unsigned)grid * kWavesPerWG), dim3(kWave), a.lds_wave, st, a);
+    return hipGetLastError();
+}
+
 template <int KC>
 static hipError_t launch_tile_bwd_k(const SweepArgs& a, int grid, hipStream_t st)
 {
-    if (hipError_t e = allow_full_lds(reinterpret_cast<const void*>(&tile_bwd_kernel<KC>)); e != hipSuccess) return e;
-    hipLaunchKernelGGL((tile_bwd_kernel<KC>), dim3((unsigned)grid * kWavesPerWG), dim3(kWave), a.lds_wave, st, a);
-    return hipGetLastError();
+    // two columns per LDS instruction need a zero column behind the zero column nb: P has columns up to 64
+    return a.nb + 1 < kTileCols - 1 ? launch_tile_bwd_p<KC, true>(a, grid, st) : launch_tile_bwd_p<KC, false>(a, grid, st);
 }
 
 hipError_t launch_tile_bwd(int DT, const SweepArgs& a, int grid, hipStream_t st)
