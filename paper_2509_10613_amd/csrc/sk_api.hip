@@ -731,7 +731,9 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.tile) {
         mode = "tile";
-        std::snprintf(kern, sizeof(kern), "tile_%s_kernel<%d>", backward ? "bwd" : "fwd", p.DT / 4);
+        // (backward: the second argument says whether the sweeps move two columns per LDS instruction, sk_tile_bwd.hip)
+        if (backward) std::snprintf(kern, sizeof(kern), "tile_bwd_kernel<%d, %s>", p.DT / 4, p.nb + 1 < sk::kTileCols - 1 ? "true" : "false");
+        else std::snprintf(kern, sizeof(kern), "tile_fwd_kernel<%d>", p.DT / 4);
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.solo) {
         mode = "solo";

@@ -132,8 +132,10 @@ def test_launch_plan_of_the_five_configurations(lib):
     p = _plan(binding.SK_OP_FWD, 100000, 0, 64, 64, 16, 0, 0, 0, f64)
     assert p["mode"] == "tile" and p["kernel"] == "tile_fwd_kernel<4>" and p["grid"] == "256"
     p = _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
-    assert p["mode"] == "tile" and p["kernel"] == "tile_bwd_kernel<4>" and int(p["lds_bytes"]) <= 160 * 1024
-    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 7, 0, 0, 1, f64)["kernel"] == "tile_bwd_kernel<2>"
+    assert p["mode"] == "tile" and p["kernel"] == "tile_bwd_kernel<4, true>" and int(p["lds_bytes"]) <= 160 * 1024
+    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 7, 0, 0, 1, f64)["kernel"] == "tile_bwd_kernel<2, true>"
+    # 64 columns leave no zero column behind the zero column: the sweeps move one column per LDS instruction
+    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 65, 16, 0, 0, 0, f64)["kernel"] == "tile_bwd_kernel<4, false>"
     # the same shape with few channels, with dyadic refinement, or with very short paths stays with the solo kernels
     assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 3, 0, 0, 0, f64)["mode"] == "solo"
     assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 1, 1, 0, f64)["mode"] == "solo"
