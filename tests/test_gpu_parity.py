@@ -194,22 +194,28 @@ def test_tile_mode_shapes(L1, L2, d, flags, dtype):
     check_grads(host(gY), gYr, dtype, "grad_Y")
 
 
-@pytest.mark.parametrize("nx,ny,L1,L2,d,flags,sym", [(2003, 1, 64, 64, 16, 0, False), (5, 300, 34, 65, 8, 1, False),
-                                                      (301, 0, 64, 64, 16, 0, True), (302, 0, 40, 40, 9, 1, True)])
-def test_quad_mode_forward(nx, ny, L1, L2, d, flags, sym):
+@pytest.mark.parametrize("nx,ny,L1,L2,d,flags,sym,dtype", [(2003, 1, 64, 64, 16, 0, False, torch.float64),
+                                                            (5, 300, 34, 65, 8, 1, False, torch.float64),
+                                                            (301, 0, 64, 64, 16, 0, True, torch.float64),
+                                                            (302, 0, 40, 40, 9, 1, True, torch.float64),
+                                                            (330, 7, 50, 44, 12, 1, False, torch.float32),
+                                                            (203, 0, 65, 65, 16, 0, True, torch.float32)])
+def test_quad_mode_forward(nx, ny, L1, L2, d, flags, sym, dtype):
     # forward Gram calls on the tile kernels' shapes: four pairs of a Gram row per wave (16 lanes with four grid rows
     # each per pair).  Rows whose length is not a multiple of four (the last group repeats a pair and writes nothing
-    # for it), a single row, many short rows, and K(X, X), whose row m has the pairs n <= m only.
+    # for it), a single row, many short rows, K(X, X), whose row m has the pairs n <= m only, float arrays, the
+    # largest grid (64 x 64).
     rng = np.random.default_rng(900 + nx + d)
     X = np.cumsum(rng.normal(0.0, (1.0 / (d * L1)) ** 0.5, (nx, L1, d)), axis=1)
     Y = X if sym else np.cumsum(rng.normal(0.0, (1.0 / (d * L2)) ** 0.5, (ny, L2, d)), axis=1)
-    assert "mode=quad" in sk.sigkernel_describe(sk.SK_OP_GRAM, nx, Y.shape[0], L1, Y.shape[1], d, 0, 0, flags, sk.SK_F64)
-    x = dev(X)
-    K = sk.sigkernel_gram(x, x if sym else dev(Y), None, 0, 0, flags)
+    sdt = sk.SK_F64 if dtype == torch.float64 else sk.SK_F32
+    assert "mode=quad" in sk.sigkernel_describe(sk.SK_OP_GRAM, nx, Y.shape[0], L1, Y.shape[1], d, 0, 0, flags, sdt)
+    x = dev(X, dtype)
+    K = sk.sigkernel_gram(x, x if sym else dev(Y, dtype), None, 0, 0, flags)
     torch.cuda.synchronize()
-    Kref = oracle.gram(X, Y, None, 0, 0, flags)
-    Kref = Kref[0] if isinstance(Kref, tuple) else Kref
-    check_values(host(K), Kref, torch.float64, "K")
+    Xr = rounded(X, dtype)
+    Kref = oracle.gram(Xr, Xr if sym else rounded(Y, dtype), None, 0, 0, flags)
+    check_values(host(K), Kref, dtype, "K")
     if sym:
         assert torch.equal(K, K.T)
 
