@@ -273,7 +273,7 @@ int run(const Layout& lay, bool backward, const void* x, const void* y, void* k,
     if (ttag) SK_CHECK(ev.begin((backward && phase != 1) ? 1 : 0, ttag, st));   // a kept forward sweep counts as a forward launch
     if (p.band) SK_CHECK(launch_sweep_band(phase ? phase + 1 : (backward ? 1 : 0), p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.lock) SK_CHECK(launch_sweep_lockstep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
-    else if (p.quad) SK_CHECK(launch_sweep_quad(p.DT, a, p.grid, p.lds_bytes, st));
+    else if (p.quad) SK_CHECK(launch_sweep_quad(p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.tile) SK_CHECK(launch_sweep_tile(backward, p.DT, a, p.grid, p.lds_bytes, st));
     else if (p.solo) SK_CHECK(launch_sweep_solo(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
     else SK_CHECK(launch_sweep(backward, p.BL, p.DT, a, p.grid, p.lds_bytes, st));
@@ -727,7 +727,7 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
         threads = (sk::kBandStrips + 1) * sk::kWave;
     } else if (p.quad) {
         mode = "quad";
-        std::snprintf(kern, sizeof(kern), "quad_fwd_kernel<%d>", p.DT);
+        std::snprintf(kern, sizeof(kern), "quad_fwd_kernel<%d, %d, %d>", p.BL, p.DT, p.lk_M);
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.tile) {
         mode = "tile";

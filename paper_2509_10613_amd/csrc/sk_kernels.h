@@ -91,7 +91,7 @@ struct SweepArgs {
     unsigned bd_off_y, bd_off_gy, bd_off_rings;   // LDS bytes
     int tile;            // 1: tile kernels (one wave per pair, increment Gram matrix in LDS, contractions by MFMA; uses
                          // lk_NT, lk_padb, lk_off_krows / lk_off_dump as offsets inside a wave's LDS)
-    int quad;            // 1: quad kernel (forward Gram calls: four pairs per wave; uses lk_padb)
+    int quad;            // 1: quad kernel (forward Gram calls: four pairs per wave; uses lk_M, lk_padb)
     long qd_nquads;      // groups of four pairs of one Gram row in the launch's sequence
     // lock-step mode on a batch of pairs of double paths: the kernels read the caller's points and write the
     // caller's gradients themselves (no preparation and finalisation launches, no global accumulators)
@@ -150,7 +150,7 @@ hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, 
 // tile mode (a.tile != 0), defined in sk_tile.hip
 hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // quad mode (a.quad != 0; forward only), defined in sk_quad.hip
-hipError_t launch_sweep_quad(int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
+hipError_t launch_sweep_quad(int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // lock-step mode (a.lock != 0), defined in sk_lockstep.hip
 hipError_t launch_sweep_lockstep(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds,
                                  hipStream_t st);

@@ -113,8 +113,19 @@ constexpr int solo_bwd_waves_per_simd(int BL, int M) { return (BL >= 2 && M >= 2
 // kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most
 // two-way bank conflicted), kTileCols columns (-1 .. 64: a zero guard column on either side).
 constexpr int kTileStride = 66, kTileCols = 66;
-// Quad mode: a wavefront works on four pairs that share the y path, 16 lanes and four grid rows per lane each.
-constexpr int kQuadPairs = 4, kQuadRows = 4;
+// Quad mode: a wavefront works on four pairs that share the y path, 16 lanes with four or eight block rows each.
+constexpr int kQuadPairs = 4;
+// Block rows per lane the quad kernel is built for (0: none): blocks of at most 2 x 2 cells, and the increments of a
+// lane's rows in at most 128 registers.
+constexpr int quad_max_rows(int BL, int DT)
+{
+    if (BL > 1 || DT == 0) return 0;
+    if (DT == 16) return BL == 0 ? 4 : 0;
+    return DT == 8 ? 4 : 8;
+}
+// Row stride of the y copy in LDS (doubles): for an even channel count a multiple of 16 bytes that spreads the
+// 16-byte reads of lanes at consecutive rows over the banks; an odd count does that by itself.
+constexpr int quad_y_stride(int DT) { return DT % 2 ? DT : (DT == 6 ? 10 : DT + 2); }
 constexpr int kTileRowPad = 8;     // backward: node columns kept left of column 0 in the pair's bottom row (all 1)
 constexpr int kTileCkChunks = 3;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
 
@@ -402,23 +413,31 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         p.nslots = (int64_t)p.grid * kWavesPerWG;
     }
 
-    // Quad mode: forward calls on the tile kernels' shapes, for Gram matrices (the four pairs of a wavefront share
-    // the y path).  The sequence is the Gram matrix row by row (y-major) in groups of four x paths; a symmetric
-    // Gram matrix has the pairs n <= m of row m only.  Two workgroups of four waves per compute unit.
-    if (p.tile && !backward && gram) {
-        p.tile = 0; p.quad = 1;
-        if (p.tri) {
-            const int64_t J = nx / kQuadPairs, e = nx % kQuadPairs;
-            p.nquads = 2 * J * (J + 1) + e * (J + 1);
-        } else {
-            p.nquads = ny * ((nx + kQuadPairs - 1) / kQuadPairs);
+    // Quad mode: forward calls for Gram matrices (the four pairs of a wavefront share the y path) on the shapes of the
+    // tile kernels and on those of the solo kernels whose blocks hold all of the refinement.  The sequence is the Gram
+    // matrix row by row (y-major) in groups of four x paths; a symmetric Gram matrix has the pairs n <= m of row m
+    // only.  Two workgroups of four waves per compute unit.
+    if ((p.tile || p.solo) && !backward && gram && !lead_lag && p.rs1 == 0 && p.rs2 == 0) {
+        const int lanes = kWave / kQuadPairs;
+        const int M = p.mb <= 4 * lanes ? 4 : 8;
+        const size_t ycopy = align_up((size_t)(p.nb + 1) * quad_y_stride(p.DT) * elem, 256);   // the y copy and a row of zeros
+        if (M <= quad_max_rows(p.BL, p.DT) && p.mb <= M * lanes && ycopy * kWavesPerWG <= kLdsPerCU) {
+            p.tile = 0; p.solo = 0; p.quad = 1;
+            if (p.tri) {
+                const int64_t J = nx / kQuadPairs, e = nx % kQuadPairs;
+                p.nquads = 2 * J * (J + 1) + e * (J + 1);
+            } else {
+                p.nquads = ny * ((nx + kQuadPairs - 1) / kQuadPairs);
+            }
+            p.lk_M = M; p.lk_ns = 1; p.lk_NT = p.nb + lanes - 1; p.lk_padb = M * lanes - p.mb;
+            p.y_lds = 1;
+            p.lds_wave = ycopy;
+            p.lds_bytes = p.lds_wave * kWavesPerWG;
+            const int64_t want = (p.nquads + kWavesPerWG - 1) / kWavesPerWG;
+            const int64_t cap = (int64_t)kNumCU * (2 * p.lds_bytes <= kLdsPerCU ? 2 : 1);
+            p.grid = (int)(want < cap ? want : cap);
+            p.nslots = (int64_t)p.grid * kWavesPerWG;
         }
-        p.lk_M = kQuadRows;
-        p.lds_wave = align_up((size_t)(p.nb + 1) * (p.DT + 2) * elem, 256);   // the y copy and a row of zeros
-        p.lds_bytes = p.lds_wave * kWavesPerWG;
-        const int64_t want = (p.nquads + kWavesPerWG - 1) / kWavesPerWG;
-        p.grid = (int)(want < 2 * kNumCU ? want : 2 * kNumCU);
-        p.nslots = (int64_t)p.grid * kWavesPerWG;
     }
 
     // Band mode: few pairs of long paths.  The strips of a pair are spread over workgroups (bands of kBandStrips

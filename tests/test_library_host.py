@@ -114,7 +114,7 @@ def test_launch_plan_of_the_five_configurations(lib):
     assert 6 << 30 < int(p1["workspace_bytes"]) < 8 << 30          # 65536 pairs x 26 checkpoints of 8 x 64 doubles
     assert q(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64) < 1 << 30
     # tile mode keeps its checkpoints in LDS: no such form (the forward call takes the quad kernel as without the flag)
-    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, KEEP, f64)["kernel"] == "quad_fwd_kernel<16>"
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, KEEP, f64)["kernel"] == "quad_fwd_kernel<0, 16, 4>"
     assert _plan(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1 | HAVE, f32)["kernel"] == "lock_bwd_kernel<1, 5, 2, 0, 0>"
     # c1: tiny, one strip: stencil, coefficient and auxiliary wave
     p = _plan(binding.SK_OP_FWD, 8, 0, 32, 32, 2, 0, 0, 0, f64)
@@ -128,7 +128,7 @@ def test_launch_plan_of_the_five_configurations(lib):
     # has no shared y path and takes the tile kernel.  Backward: the channel contraction dominates -> tile mode,
     # increment Gram matrix of a pair in LDS, contractions on the matrix cores, one workgroup per compute unit
     p = _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
-    assert p["mode"] == "quad" and p["kernel"] == "quad_fwd_kernel<16>" and p["grid"] == "512" and p["rows_per_lane"] == "4"
+    assert p["mode"] == "quad" and p["kernel"] == "quad_fwd_kernel<0, 16, 4>" and p["grid"] == "512" and p["rows_per_lane"] == "4"
     p = _plan(binding.SK_OP_FWD, 100000, 0, 64, 64, 16, 0, 0, 0, f64)
     assert p["mode"] == "tile" and p["kernel"] == "tile_fwd_kernel<4>" and p["grid"] == "256"
     p = _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 16, 0, 0, 0, f64)
@@ -137,9 +137,18 @@ def test_launch_plan_of_the_five_configurations(lib):
     # 64 columns leave no zero column behind the zero column: the sweeps move one column per LDS instruction
     assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 65, 16, 0, 0, 0, f64)["kernel"] == "tile_bwd_kernel<4, false>"
     # the same shape with few channels, with dyadic refinement, or with very short paths stays with the solo kernels
-    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 3, 0, 0, 0, f64)["mode"] == "solo"
-    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 1, 1, 0, f64)["mode"] == "solo"
-    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 30, 64, 16, 0, 0, 0, f64)["mode"] == "solo"
+    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 3, 0, 0, 0, f64)["mode"] == "solo"
+    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 64, 64, 16, 1, 1, 0, f64)["mode"] == "solo"
+    assert _plan(binding.SK_OP_GRAM_BWD, 1024, 1024, 30, 64, 16, 0, 0, 0, f64)["mode"] == "solo"
+    # ... whose forward Gram calls take the quad kernel where its lanes can hold the rows' increments (four or eight
+    # block rows per lane, blocks of at most 2 x 2 cells that hold all of the refinement)
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 3, 0, 0, 0, f64)["kernel"] == "quad_fwd_kernel<0, 3, 4>"
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 30, 64, 16, 0, 0, 0, f64)["kernel"] == "quad_fwd_kernel<0, 16, 4>"
+    assert _plan(binding.SK_OP_GRAM, 256, 256, 128, 128, 3, 1, 1, 0, f64)["kernel"] == "quad_fwd_kernel<1, 3, 8>"   # c3
+    assert _plan(binding.SK_OP_GRAM, 1024, 1024, 64, 64, 16, 1, 1, 0, f64)["mode"] == "solo"    # 16 channels, 126 block rows
+    assert _plan(binding.SK_OP_GRAM, 256, 256, 128, 128, 3, 2, 2, 0, f64)["mode"] == "solo"     # blocks of 4 x 4 cells
+    assert _plan(binding.SK_OP_GRAM, 256, 256, 100, 128, 3, 2, 1, 0, f64)["mode"] != "quad"     # refinement above the blocks
+    assert _plan(binding.SK_OP_FWD, 5000, 0, 128, 128, 3, 1, 1, 0, f64)["mode"] == "solo"       # no shared y path
     # many pairs of longer paths (more than 128 block rows): strips chained through global rows
     p = _plan(binding.SK_OP_BWD, 4096, 0, 300, 300, 4, 0, 0, 0, f64)
     assert p["mode"] == "wave-per-pair" and p["kernel"].startswith("sweep_bwdu_kernel<0, 4,") and p["strips"] == "5"
