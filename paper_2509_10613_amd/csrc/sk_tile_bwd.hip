@@ -145,31 +145,36 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             }
             tn += S * kColBytes;
             int cl = -tpad - (kWave - 1) + 1;   // node column the last lane writes in the chunk's first macro-step
-            for (int g = 0; g < nch; ++g, tn += S * kColBytes, cl += S) {
-                if (g > 0 && g % CK == 0) {
-                    SK_LDS real* cp = ckl + (g / CK - 1) * (2 * kWave);
+            // (chunks in groups of CK, a checkpoint in front of every group but the first)
+            int g = 0;
+            for (int k = 0; g < nch; ++k) {
+                if (k > 0) {
+                    SK_LDS real* cp = ckl + (k - 1) * (2 * kWave);
                     cp[0] = f.left[1];
                     cp[kWave] = f.blc;
                 }
-                real kb[S];   // the lane's bottom values of the chunk; the last lane's are the pair's bottom row
-                real pnext = 0.0;
+                const int gend = min((k + 1) * CK, nch);
+                for (; g < gend; ++g, tn += S * kColBytes, cl += S) {
+                    real kb[S];   // the lane's bottom values of the chunk; the last lane's are the pair's bottom row
+                    real pnext = 0.0;
 #pragma unroll
-                for (int i = 0; i < S; ++i) {
-                    const real p = pq[i];
-                    // the next chunk's p (past the last step: the zero column, unused)
-                    if constexpr (!PAIRS) pq[i] = readp(tn + i * kColBytes);
-                    else if (i % 2 == 0) readp2(tn + i * kColBytes, pq[i], pnext);
-                    else pq[i] = pnext;
-                    real Ac[1], Bc[1], recv[1];
-                    TL::coef_fwd(p, Ac[0], Bc[0]);
-                    recv[0] = wave_from_above_or(f.bot[0], 1.0);
-                    f.step(recv, Ac, Bc);
-                    kb[i] = f.bot[0];
-                }
-                if (last && cl >= -kTileRowPad) {   // (further left every value is the boundary value 1)
-                    SK_LDS real* kp = krow + cl;
+                    for (int i = 0; i < S; ++i) {
+                        const real p = pq[i];
+                        // the next chunk's p (past the last step: the zero column, unused)
+                        if constexpr (!PAIRS) pq[i] = readp(tn + i * kColBytes);
+                        else if (i % 2 == 0) readp2(tn + i * kColBytes, pq[i], pnext);
+                        else pq[i] = pnext;
+                        real Ac[1], Bc[1], recv[1];
+                        TL::coef_fwd(p, Ac[0], Bc[0]);
+                        recv[0] = wave_from_above_or(f.bot[0], 1.0);
+                        f.step(recv, Ac, Bc);
+                        kb[i] = f.bot[0];
+                    }
+                    if (last && cl >= -kTileRowPad) {   // (further left every value is the boundary value 1)
+                        SK_LDS real* kp = krow + cl;
 #pragma unroll
-                    for (int i = 0; i < S; ++i) kp[i] = kb[i];
+                        for (int i = 0; i < S; ++i) kp[i] = kb[i];
+                    }
                 }
             }
             kR0 = f.left[0];
@@ -202,52 +207,56 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
                 else if (i % 2 == 0) readp2(tb + i * kColBytes, pq[i], pq[i + 1]);
             }
             int cl = (nch - 1) * S - tpad - (kWave - 1);   // node column under the last lane's block, first macro-step
-            for (int g = nch - 1; g >= 0; --g, tb -= S * kColBytes, cl -= S) {
-                // the last lane's bottom edge
-                if (cl >= -kTileRowPad) {
-                    const SK_LDS real* kp = krow + cl;
+            // (chunks in groups of CK from the right, a checkpoint behind every group but the leftmost)
+            int g = nch - 1;
+            for (int k = (nch - 1) / CK; k >= 0; --k) {
+                for (; g >= k * CK; --g, tb -= S * kColBytes, cl -= S) {
+                    // the last lane's bottom edge
+                    if (cl >= -kTileRowPad) {
+                        const SK_LDS real* kp = krow + cl;
 #pragma unroll
-                    for (int i = 0; i < S; ++i) kq[i] = kp[i];
-                } else {
+                        for (int i = 0; i < S; ++i) kq[i] = kp[i];
+                    } else {
 #pragma unroll
-                    for (int i = 0; i < S; ++i) kq[i] = 1.0;
+                        for (int i = 0; i < S; ++i) kq[i] = 1.0;
+                    }
+                    real pnext = 0.0, ghold = 0.0;
+#pragma unroll
+                    for (int i = S - 1; i >= 0; --i) {
+                        const real p = pq[i];
+                        // the next chunk's p (left of the grid: the zero column)
+                        if constexpr (!PAIRS) pq[i] = readp(tb + (i - S) * kColBytes);
+                        else if (i % 2 == 1) readp2(tb + (i - 1 - S) * kColBytes, pnext, pq[i]);
+                        else pq[i] = pnext;
+                        real Ac, Bc, iB;
+                        LK::coef_rev(p, Ac, Bc, iB);
+                        const real recv = wave_shift_down(rv.up[0]);   // nothing enters under the last lane
+                        const real recvk = wave_from_below_or(rv.ktop[0], kq[i]);
+                        // The mirror image of the step for a lane's single cell (LK::Rev::step written out), with
+                        // 6 dF/dp = g ((k[i+1,j] + k[i,j+1]) (p + 3) + k[i,j] p) in place of dF/dp: two instructions
+                        // fewer, and the factor 1/6 goes into the operands of the linear map below.
+                        const real s01 = recvk + rv.kR[0];
+                        const real e00 = fma(s01, Ac, -rv.kR[1]) * iB;   // Eq. (1) solved for its oldest term
+                        const real go = rv.accL[1] + recv;
+                        rv.accL[1] = go * Ac;
+                        rv.up[0] = fma(go, Ac, rv.corner);
+                        rv.corner = -(go * Bc);
+                        const real accP6 = go * fma(s01, p + 3.0, e00 * p);
+                        rv.kR[1] = recvk;
+                        rv.kR[0] = e00;
+                        rv.ktop[0] = e00;
+                        // right of the grid dF/dp is an exact zero (the adjoint is zero there) and lands in the zero
+                        // column; left of the grid it is not zero (the adjoint has left the grid) and lands in the
+                        // column nobody reads
+                        if constexpr (!PAIRS) writep(tb + i * kColBytes, accP6);
+                        else if (i % 2 == 1) ghold = accP6;
+                        else writep2(tb + i * kColBytes, accP6, ghold);
+                    }
                 }
-                real pnext = 0.0, ghold = 0.0;
-#pragma unroll
-                for (int i = S - 1; i >= 0; --i) {
-                    const real p = pq[i];
-                    // the next chunk's p (left of the grid: the zero column)
-                    if constexpr (!PAIRS) pq[i] = readp(tb + (i - S) * kColBytes);
-                    else if (i % 2 == 1) readp2(tb + (i - 1 - S) * kColBytes, pnext, pq[i]);
-                    else pq[i] = pnext;
-                    real Ac, Bc, iB;
-                    LK::coef_rev(p, Ac, Bc, iB);
-                    const real recv = wave_shift_down(rv.up[0]);   // nothing enters under the last lane
-                    const real recvk = wave_from_below_or(rv.ktop[0], kq[i]);
-                    // The mirror image of the step for a lane's single cell (LK::Rev::step written out), with
-                    // 6 dF/dp = g ((k[i+1,j] + k[i,j+1]) (p + 3) + k[i,j] p) in place of dF/dp: two instructions
-                    // fewer, and the factor 1/6 goes into the operands of the linear map below.
-                    const real s01 = recvk + rv.kR[0];
-                    const real e00 = fma(s01, Ac, -rv.kR[1]) * iB;   // Eq. (1) solved for its oldest term
-                    const real go = rv.accL[1] + recv;
-                    rv.accL[1] = go * Ac;
-                    rv.up[0] = fma(go, Ac, rv.corner);
-                    rv.corner = -(go * Bc);
-                    const real accP6 = go * fma(s01, p + 3.0, e00 * p);
-                    rv.kR[1] = recvk;
-                    rv.kR[0] = e00;
-                    rv.ktop[0] = e00;
-                    // right of the grid dF/dp is an exact zero (the adjoint is zero there) and lands in the zero
-                    // column; left of the grid it is not zero (the adjoint has left the grid) and lands in the
-                    // column nobody reads
-                    if constexpr (!PAIRS) writep(tb + i * kColBytes, accP6);
-                    else if (i % 2 == 1) ghold = accP6;
-                    else writep2(tb + i * kColBytes, accP6, ghold);
-                }
-                if (g > 0 && g % CK == 0) {
+                if (k > 0) {
                     // the recovered state against the exact one, which replaces it: rounding errors of the inverse
                     // recurrence cannot build up over more than CK chunks, and a drift disqualifies the pair
-                    const SK_LDS real* cp = ckl + (g / CK - 1) * (2 * kWave);
+                    const SK_LDS real* cp = ckl + (k - 1) * (2 * kWave);
                     const real e1 = cp[0];
                     const real e0 = wave_from_above_or(cp[kWave], 1.0);   // the lane above's k[a][J]; row 0 has the boundary above it
                     kscale = fmax(kscale, fmax(fabs(e0), fabs(e1)));
