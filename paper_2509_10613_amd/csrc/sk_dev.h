@@ -113,6 +113,38 @@ __device__ __forceinline__ void gram_pair(const SweepArgs& a, long q, long& xi, 
         pid2 = yi * N + xi;
     }
 }
+// The same sequence walked pair by pair: locate() divides once, next() adds and compares.
+struct PairCursor {
+    long xi, yi, pid, pid2;
+    long vr, t;   // symmetric case: virtual row and place in it
+    __device__ __forceinline__ void locate(const SweepArgs& a, long q)
+    {
+        gram_pair(a, q, xi, yi, pid, pid2);
+        vr = t = 0;
+        if (a.gramM && a.tri) {
+            vr = q / (a.gramN + 1);
+            t = q - vr * (a.gramN + 1);
+        }
+    }
+    __device__ __forceinline__ void next(const SweepArgs& a)
+    {
+        if (!a.gramM) {
+            ++xi; ++yi; ++pid; ++pid2;
+        } else if (!a.tri) {
+            ++xi;
+            pid += a.gramM;
+            if (xi == a.gramN) { xi = 0; ++yi; pid = yi; }
+            pid2 = pid;
+        } else {
+            const long N = a.gramN;
+            if (++t > N) { t = 0; ++vr; }
+            if (t <= vr) { yi = vr; xi = t; }
+            else { yi = N - 1 - vr; xi = t - vr - 1; }
+            pid = xi * N + yi;
+            pid2 = yi * N + xi;
+        }
+    }
+};
 // Upstream gradient of the pair: in the symmetric case the pair stands for both (n, m) and (m, n).
 __device__ __forceinline__ real gram_weight(const SweepArgs& a, long pid, long pid2)
 {

@@ -107,15 +107,14 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
     // Operands of the pair in work, loaded while the previous pair was in the linear map.
     real xb[4][KC];
     real gk = 0.0;
+    PairCursor cur;
     if (q0 < q1) {
-        long xi, yi, pid, pid2;
-        gram_pair(a, q0, xi, yi, pid, pid2);
-        TL::load_b(a.dx + xi * a.xstride, a.DS, padb, lane, xb);
-        gk = gram_weight(a, pid, pid2);
+        cur.locate(a, q0);
+        TL::load_b(a.dx + cur.xi * a.xstride, a.DS, padb, lane, xb);
+        gk = gram_weight(a, cur.pid, cur.pid2);
     }
     for (long q = q0; q < q1; ++q) {
-        long xi, yi, pid, pid2;
-        gram_pair(a, q, xi, yi, pid, pid2);
+        const long xi = cur.xi, yi = cur.yi, pid = cur.pid, pid2 = cur.pid2;
         if (yi != cur_y) {
             flush_gy();
             const real* dyg = a.dy + yi * a.ystride;
@@ -281,11 +280,10 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
         const real* dxg = a.dx + xi * a.xstride;
         real xc[16], xbn[4][KC], gkn = 0.0;
         if (a.want_gy && passed) TL::load_c(dxg, a.DS, padb, lane, xc);
+        cur.next(a);
         if (q + 1 < q1) {
-            long xin, yin, pidn, pidn2;
-            gram_pair(a, q + 1, xin, yin, pidn, pidn2);
-            TL::load_b(a.dx + xin * a.xstride, a.DS, padb, lane, xbn);
-            gkn = gram_weight(a, pidn, pidn2);
+            TL::load_b(a.dx + cur.xi * a.xstride, a.DS, padb, lane, xbn);
+            gkn = gram_weight(a, cur.pid, cur.pid2);
         }
 
         // ---- the linear map of Section 3.4 on the matrix cores ----
