@@ -305,13 +305,25 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
 #pragma unroll
                 for (int I = 0; I < 4; ++I)
                     acc[I] = __builtin_amdgcn_mfma_f64_16x16x4f64(gp[4 * kb * kTileStride + 16 * I], yc[kb], acc[I], 0, 0, 0);
+            // (up: rows above the lane's first one, which is row g16 - padb of the pair.  With at most four rows of
+            // padding and every channel in use only the first of the sixteen sums can lie outside the grid.)
+            if (padb <= 4 && a.d == 4 * KC) {
 #pragma unroll
-            for (int I = 0; I < 4; ++I)
+                for (int I = 0; I < 4; ++I)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int up = 16 * I + 4 * r;   // rows above the lane's first one
-                    if (lrow + up >= 0 && n16 < a.d) unsafeAtomicAdd(&gq[(long)up * a.DS], acc[I][r]);
-                }
+                    for (int r = 0; r < 4; ++r) {
+                        const int up = 16 * I + 4 * r;
+                        if (up > 0 || lrow >= 0) unsafeAtomicAdd(&gq[(long)up * a.DS], acc[I][r]);
+                    }
+            } else {
+#pragma unroll
+                for (int I = 0; I < 4; ++I)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int up = 16 * I + 4 * r;
+                        if (lrow + up >= 0 && n16 < a.d) unsafeAtomicAdd(&gq[(long)up * a.DS], acc[I][r]);
+                    }
+            }
         }
         if (a.want_gy && passed) {
             // dF/d(dy)[b, c] = sum_a G[a, b] dx[a, c]: A operand G[4 ka + l / 16][16 J + l % 16], B operand xc[ka]
