@@ -37,8 +37,14 @@ struct Tile {
             real t[KC];
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) t[kc] = rp[4 * kc];
+            // (rowoff is at most 32, the tile kernels' shapes: only the first two row tiles can reach above the grid)
+            if (T < 2) {
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) v[T][kc] = row >= 0 ? t[kc] : 0.0;
+                for (int kc = 0; kc < KC; ++kc) v[T][kc] = row >= 0 ? t[kc] : 0.0;
+            } else {
+#pragma unroll
+                for (int kc = 0; kc < KC; ++kc) v[T][kc] = t[kc];
+            }
         }
     }
     // Operand layout of the linear map: v[kk] = inc[4 kk + lane / 16 - rowoff][lane % 16] (B operand, the
@@ -58,7 +64,9 @@ struct Tile {
 #pragma unroll
         for (int kk = 0; kk < 16; ++kk) {
             const int row = 4 * kk + g16 - rowoff;
-            v[kk] = (row >= 0 && n16 < D) ? t[kk] : 0.0;
+            // (rowoff is at most 32: rows 4 kk + g16 with kk >= 8 lie inside the grid)
+            if (kk < 8) v[kk] = (row >= 0 && n16 < D) ? t[kk] : 0.0;
+            else v[kk] = n16 < D ? t[kk] : 0.0;
         }
     }
     // Delta tiles into P.  Result register r of lane l of tile (J, I) is Delta[a = 16 I + l % 16][b = 16 J + l / 16 + 4 r].

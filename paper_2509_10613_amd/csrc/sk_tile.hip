@@ -112,7 +112,7 @@ hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid
 {
     // what the kernels assume about the launch
     if (a.lk_M != 1 || a.rs1 != 0 || a.rs2 != 0 || a.mb > kWave || a.nb > kWave || a.mb < 1 || a.nb < 1 ||
-        a.lk_padb != kWave - a.mb || a.rpad < kWave || a.qpad < kWave || a.DS <= DT || a.d > DT ||
+        a.lk_padb != kWave - a.mb || a.lk_padb > kWave / 2 || a.rpad < kWave || a.qpad < kWave || a.DS <= DT || a.d > DT ||
         (backward && (!a.bad_list || !a.bad_count || (a.lk_NT % kLockS) != 0 || a.lk_NT < a.nb + kWave - 1 || a.lk_NT >= a.nb + kWave - 1 + kLockS ||
                       (size_t)a.lk_off_ck + (size_t)((a.lk_NT / kLockS - 1) / kTileCkChunks) * 2 * kWave * sizeof(real) >
                           a.lk_off_krows ||
