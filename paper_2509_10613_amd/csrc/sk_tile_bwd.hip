@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
                     cp[kWave] = f.blc;
                 }
                 const int gend = min((k + 1) * CK, nch);
-                for (; g < gend; ++g, tn += S * kColBytes, cl += S) {
+                auto chunk = [&]() __attribute__((always_inline)) {
                     real kb[S];   // the lane's bottom values of the chunk; the last lane's are the pair's bottom row
                     real pnext = 0.0;
 #pragma unroll
@@ -174,6 +174,15 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
 #pragma unroll
                         for (int i = 0; i < S; ++i) kp[i] = kb[i];
                     }
+                    ++g;
+                    tn += S * kColBytes;
+                    cl += S;
+                };
+                if (gend - g == CK) {   // a full group: straight-line code (see the reverse sweep)
+#pragma unroll
+                    for (int c = 0; c < CK; ++c) chunk();
+                } else {
+                    while (g < gend) chunk();
                 }
             }
             kR0 = f.left[0];
@@ -209,7 +218,9 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
             // (chunks in groups of CK from the right, a checkpoint behind every group but the leftmost)
             int g = nch - 1;
             for (int k = (nch - 1) / CK; k >= 0; --k) {
-                for (; g >= k * CK; --g, tb -= S * kColBytes, cl -= S) {
+                // (a full group of CK chunks runs as straight-line code: values that live from chunk to chunk then need
+                // no moves into fixed registers at every chunk's end)
+                auto chunk = [&]() __attribute__((always_inline)) {
                     // the last lane's bottom edge
                     if (cl >= -kTileRowPad) {
                         const SK_LDS real* kp = krow + cl;
@@ -251,6 +262,15 @@ __global__ __launch_bounds__(kWave, 1) void tile_bwd_kernel(SweepArgs a)
                         else if (i % 2 == 1) ghold = accP6;
                         else writep2(tb + i * kColBytes, accP6, ghold);
                     }
+                    --g;
+                    tb -= S * kColBytes;
+                    cl -= S;
+                };
+                if (g - k * CK + 1 == CK) {
+#pragma unroll
+                    for (int c = 0; c < CK; ++c) chunk();
+                } else {
+                    while (g >= k * CK) chunk();
                 }
                 if (k > 0) {
                     // the recovered state against the exact one, which replaces it: rounding errors of the inverse
