@@ -101,7 +101,7 @@ int sigkernel_fwd(const void* x, const void* y, void* k, int64_t B, int64_t L1, 
  *   grad_x[B,L1,d] = dF/dx,  grad_y[B,L2,d] = dF/dy   (either may be NULL = not wanted)
  * and, if k_out != NULL, k_out[B] = k(x[b], y[b]) (the forward values are recomputed inside).
  * By default the reverse sweep recovers the forward values it needs by inverting Eq. (1) between exact
- * checkpoints eight block steps apart (24 in one launch mode), and checks the recovered state against every
+ * checkpoints eight block steps apart (32 in one launch mode), and checks the recovered state against every
  * checkpoint and, at the left end of the grid, against the boundary value 1.  Increment inner products of order one
  * make the inverse recurrence ill-conditioned (it divides by B(p)): where the recovered state differs from the exact
  * one by more than 1e-11 of the largest forward value met along the row, the pair is left out of the gradient sums
