@@ -49,18 +49,26 @@ struct Lock {
     static constexpr int CR2 = CH2 * M * kWave * 4;   // ... reverse sweep
     static constexpr int GPH = CH2 * M * kWave;       // doubles per half of the dF/dp ring
 
-    // A(p), B(p) of Eq. (1), and 1 / B(p) for the reverse sweep (one Newton step on the hardware estimate)
+    // A(p), B(p) of Eq. (1), and 1 / B(p) for the reverse sweep
     static __device__ __forceinline__ void coef_fwd(real p, real& Ac, real& Bc)
     {
         const real q2 = p * p;
         Bc = fma(q2, -1.0 / 12.0, 1.0);
         Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
     }
+    // 1 / B without the hardware estimate (v_rcp_f64 issues at a quarter of the rate of an FMA: 20 clocks against 5
+    // in a lone wave).  With q = p^2 / 12, B = 1 - q and the inner term of A is r0 = 1 + q = (1 - q^2) / B, so
+    // e = 1 - B r0 = q^2 and 1 / B = r0 (1 + e + e^2 + ...): cut after e^2 the relative error is q^6, below one
+    // rounding error for |p| < 0.17 and below 1e-12 up to |p| = 0.35, far beyond the increments for which the inverse
+    // recurrence holds at all; a pair outside that range fails the drift check and is solved by replay.
     static __device__ __forceinline__ void coef_rev(real p, real& Ac, real& Bc, real& iB)
     {
-        coef_fwd(p, Ac, Bc);
-        const real r = __builtin_amdgcn_rcp(Bc);
-        iB = fma(fma(-Bc, r, 1.0), r, r);
+        const real q2 = p * p;
+        Bc = fma(q2, -1.0 / 12.0, 1.0);
+        const real r0 = fma(q2, 1.0 / 12.0, 1.0);
+        Ac = fma(p, 0.5, r0);
+        const real e = fma(-Bc, r0, 1.0);
+        iB = fma(fma(e, e, e), r0, r0);
     }
 
     // dF/dp ring: [macro-step][lane][M], so that a lane's M values move in one LDS instruction
@@ -221,11 +229,8 @@ struct Lock {
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
                     const real p = inner<EDGE>(m, J[i & 1], y[i & 1]);
-                    const real q2 = p * p;
-                    const real Bc = fma(q2, -1.0 / 12.0, 1.0);
-                    const real Ac = fma(p, 0.5, fma(q2, 1.0 / 12.0, 1.0));
-                    real invB = __builtin_amdgcn_rcp(Bc);
-                    invB = fma(fma(-Bc, invB, 1.0), invB, invB);
+                    real Ac, Bc, invB;
+                    coef_rev(p, Ac, Bc, invB);
                     SK_LDS real* ep = wp + (i * M + m) * (kWave * 2);
                     *(SK_LDS real2*)(ep) = real2{Ac, Bc};
                     *(SK_LDS real2*)(ep + CR2 / 2) = real2{invB, p * (1.0 / 6.0)};

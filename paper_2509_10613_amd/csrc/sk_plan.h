@@ -127,7 +127,7 @@ constexpr int quad_max_rows(int BL, int DT)
 // 16-byte reads of lanes at consecutive rows over the banks; an odd count does that by itself.
 constexpr int quad_y_stride(int DT) { return DT % 2 ? DT : (DT == 6 ? 10 : DT + 2); }
 constexpr int kTileRowPad = 8;     // backward: node columns kept left of column 0 in the pair's bottom row (all 1)
-constexpr int kTileCkChunks = 4;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
+constexpr int kTileCkChunks = 8;   // backward: chunks of 8 macro-steps between two checkpoints (kept in LDS)
 
 // Band mode: strips per workgroup, block columns per hand-over ring, coarse y columns per y ring (powers of
 // two), chunks the data-moving wave works ahead, and the bound on its polls of another workgroup's counter.
