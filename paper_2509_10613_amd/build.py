@@ -14,6 +14,9 @@ PUBLIC = ["sigkernel.h", "signature.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+# Per source file.  The tile backward kernel moves every MFMA result on (to LDS, to atomics): with the results in
+# vector registers instead of accumulation registers the copies between the two fall away (c5 backward: -1 %).
+FILE_FLAGS = {"sk_tile_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _stale(target, deps):
@@ -33,7 +36,7 @@ def build(force: bool = False, verbose: bool = False, extra_flags=()) -> str:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         if not force and not extra_flags and not _stale(obj, [os.path.join(CSRC, src)] + hdrs):
             return obj   # this object is newer than its source and every header
-        cmd = ["hipcc"] + FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = ["hipcc"] + FLAGS + FILE_FLAGS.get(src, []) + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
