@@ -106,8 +106,9 @@ constexpr int solo_max_rows(bool backward, int BL, int DT)
 }
 
 // Wavefronts per SIMD the solo backward kernel is built for: two, or one where the lane state of two block rows of
-// 4 x 4 cells needs the whole register file (accumulation registers included).
-constexpr int solo_bwd_waves_per_simd(int BL, int M) { return (BL >= 2 && M >= 2) ? 1 : 2; }
+// 4 x 4 cells, or the sums and increments of sixteen channels, need the whole register file (accumulation registers
+// included: with 256 registers the sixteen-channel kernels spill a kilobyte per lane and run four times slower).
+constexpr int solo_bwd_waves_per_simd(int BL, int M, int DT) { return ((BL >= 2 && M >= 2) || DT >= 16) ? 1 : 2; }
 
 // Tile mode: the increment Gram matrix of a pair as a 64 x 64 array of doubles in LDS, column stride
 // kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most
@@ -356,7 +357,7 @@ inline Plan make_plan(bool backward, bool gram, bool symmetric, int64_t nx, int6
         const size_t o_gyp = backward ? lds_take(ycopy) : 0;   // y-side sums of the pair in work
         const size_t o_kr = backward ? lds_take(((size_t)kWave * C + (size_t)NT * C + 2) * elem) : 0;
         const size_t o_dump = backward ? lds_take((size_t)kWave * C * elem) : 0;
-        const int maxwg = backward ? solo_bwd_waves_per_simd(p.BL, M) : 4;   // register file of the backward kernel
+        const int maxwg = backward ? solo_bwd_waves_per_simd(p.BL, M, p.DT) : 4;   // register file of the backward kernel
         if (M <= solo_max_rows(backward, p.BL, p.DT) && p.mb <= kWave * M && used * kWavesPerWG <= kLdsPerCU) {
             p.solo = 1; p.coop = 0;
             p.lk_M = M; p.lk_ns = 1; p.lk_NT = NT; p.lk_padb = kWave * M - p.mb;

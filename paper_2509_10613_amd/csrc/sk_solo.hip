@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, (D * M > 16) ? 2 : 3) void solo
 // keeps its sweep and the backward call that takes it over: checkpoints and bottom row then have a place per pair in
 // global memory (phase 1 copies the row out of LDS, phase 2 copies it in) instead of one per wave.
 template <int BL, int D, int M, int PHASE, int LL>
-__global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M)) void solo_bwd_kernel(SweepArgs a)
+__global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M, D)) void solo_bwd_kernel(SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     using LK = Lock<BL, D, M, LL>;
@@ -295,11 +295,18 @@ __global__ __launch_bounds__(kWavesPerWG* kWave, solo_bwd_waves_per_simd(BL, M))
                         }
                         if (plain) {
                             if (!EDGE || (unsigned)J[i & 1] < (unsigned)nb) {
-                                real o[D];   // every read before the first write: one wait instead of one per channel
+                                if constexpr (D <= 8) {
+                                    real o[D];   // every read before the first write: one wait instead of one per channel
 #pragma unroll
-                                for (int c = 0; c < D; ++c) o[c] = gq[c];
+                                    for (int c = 0; c < D; ++c) o[c] = gq[c];
 #pragma unroll
-                                for (int c = 0; c < D; ++c) gq[c] = o[c] + t[c];
+                                    for (int c = 0; c < D; ++c) gq[c] = o[c] + t[c];
+                                } else {
+                                    // (sixteen channels: the registers for that are not there, and spilling the lane
+                                    // state costs a factor of four)
+#pragma unroll
+                                    for (int c = 0; c < D; ++c) gq[c] += t[c];
+                                }
                             }
                         } else {
 #pragma unroll
