@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsigkernel.so")
-SOURCES = ["sk_api.hip", "sk_kernels.hip", "sk_lockstep.hip", "sk_solo.hip", "sk_tile.hip", "sk_tile_bwd.hip", "sk_quad.hip", "sk_band.hip", "sg_horner.hip", "sg_horner_bwd.hip"]
-HEADERS = ["sk_plan.h", "sk_kernels.h", "sk_dev.h", "sk_lane.h", "sk_tile.h", "sg_plan.h", "sg_kernels.h", "sg_dev.h"]
+SOURCES = ["sk_api.hip", "sk_kernels.hip", "sk_lockstep.hip", "sk_solo.hip", "sk_solo_one.hip", "sk_tile.hip", "sk_tile_bwd.hip", "sk_quad.hip", "sk_band.hip", "sg_horner.hip", "sg_horner_bwd.hip"]
+HEADERS = ["sk_plan.h", "sk_kernels.h", "sk_dev.h", "sk_lane.h", "sk_solo_impl.h", "sk_tile.h", "sg_plan.h", "sg_kernels.h", "sg_dev.h"]
 PUBLIC = ["sigkernel.h", "signature.h"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -738,7 +738,8 @@ int sigkernel_describe(int op, int64_t B_or_N, int64_t M, int64_t L1, int64_t L2
     } else if (p.solo) {
         mode = "solo";
         if (backward || phase)
-            std::snprintf(kern, sizeof(kern), "solo_bwd_kernel<%d, %d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase, p.ll);
+            std::snprintf(kern, sizeof(kern), "solo_bwd_kernel<%d, %d, %d, %d, %d, %d>", p.BL, p.DT, p.lk_M, phase, p.ll,
+                          sk::solo_bwd_shares_simd(p.BL, p.lk_M, p.DT, p.lds_bytes) ? 2 : 1);
         else std::snprintf(kern, sizeof(kern), "solo_fwd_kernel<%d, %d, %d, %d>", p.BL, p.DT, p.lk_M, p.ll);
         threads = sk::kWavesPerWG * sk::kWave;
     } else if (p.lock) {

@@ -147,6 +147,8 @@ hipError_t launch_sweep(bool backward, int BL, int DT, const SweepArgs& a, int g
 hipError_t launch_second_chance_reset(real* g1, long n1, real* g2, long n2, const int* err, hipStream_t st);
 // solo mode (a.solo != 0), defined in sk_solo.hip
 hipError_t launch_sweep_solo(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
+// the one-wave builds of the solo backward kernels (sk_solo_one.hip), called by launch_sweep_solo
+hipError_t launch_sweep_solo_one(bool backward, int BL, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // tile mode (a.tile != 0), defined in sk_tile.hip
 hipError_t launch_sweep_tile(bool backward, int DT, const SweepArgs& a, int grid, size_t lds, hipStream_t st);
 // quad mode (a.quad != 0; forward only), defined in sk_quad.hip

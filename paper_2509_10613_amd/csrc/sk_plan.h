@@ -108,7 +108,16 @@ constexpr int solo_max_rows(bool backward, int BL, int DT)
 // Wavefronts per SIMD the solo backward kernel is built for: two, or one where the lane state of two block rows of
 // 4 x 4 cells, or the sums and increments of sixteen channels, need the whole register file (accumulation registers
 // included: with 256 registers the sixteen-channel kernels spill a kilobyte per lane and run four times slower).
-constexpr int solo_bwd_waves_per_simd(int BL, int M, int DT) { return ((BL >= 2 && M >= 2) || DT >= 16) ? 1 : 2; }
+constexpr int solo_bwd_waves_per_simd(int BL, int M, int DT)
+{
+    return ((BL >= 2 && M >= 2) || DT >= 16 || (DT >= 8 && (M >= 2 || BL >= 2))) ? 1 : 2;
+}
+// Whether a launch of the solo backward kernel puts two workgroups on a compute unit (lds: bytes per workgroup); if
+// not, the kernel's one-wave build is launched, which has the whole register file.
+constexpr bool solo_bwd_shares_simd(int BL, int M, int DT, size_t lds)
+{
+    return solo_bwd_waves_per_simd(BL, M, DT) >= 2 && 2 * lds <= kLdsPerCU;
+}
 
 // Tile mode: the increment Gram matrix of a pair as a 64 x 64 array of doubles in LDS, column stride
 // kTileStride (even, not a multiple of 4: row-contiguous, skewed and transposed accesses all stay at most

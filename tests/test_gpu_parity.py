@@ -244,7 +244,7 @@ def test_short_paths_with_many_channels_stay_solo():
     rng = np.random.default_rng(78)
     X = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (nx, L, d)), axis=1)
     Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (ny, L, d)), axis=1)
-    assert "solo_bwd_kernel<0, 16, 1, 0, 0>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
+    assert "solo_bwd_kernel<0, 16, 1, 0, 0, 1>" in sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, 0, 0, 0, sk.SK_F64)
     W = workloads.upstream_weights(61, (nx, ny))
     K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), 0, 0, 0)
     torch.cuda.synchronize()

@@ -104,10 +104,10 @@ def test_launch_plan_of_the_five_configurations(lib):
     assert int(p1["workspace_bytes"]) == q(binding.SK_OP_BWD, 128, 0, 256, 256, 5, 1, 1, 1, f64)
     assert q(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1, f64) < q(binding.SK_OP_FWD, 128, 0, 256, 256, 5, 1, 1, 1 | KEEP, f64)
     # many pairs, and Gram matrices, in solo mode: checkpoints and bottom rows per pair instead of per wave
-    assert _plan(binding.SK_OP_FWD, 5000, 0, 6, 5, 2, 1, 1, KEEP, f64)["kernel"] == "solo_bwd_kernel<1, 2, 1, 1, 0>"
+    assert _plan(binding.SK_OP_FWD, 5000, 0, 6, 5, 2, 1, 1, KEEP, f64)["kernel"] == "solo_bwd_kernel<1, 2, 1, 1, 0, 2>"
     p1 = _plan(binding.SK_OP_GRAM, 256, 256, 128, 128, 3, 1, 1, KEEP, f64)
     p2 = _plan(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, HAVE, f64)
-    assert p1["kernel"] == "solo_bwd_kernel<1, 3, 2, 1, 0>" and p2["kernel"] == "solo_bwd_kernel<1, 3, 2, 2, 0>"
+    assert p1["kernel"] == "solo_bwd_kernel<1, 3, 2, 1, 0, 2>" and p2["kernel"] == "solo_bwd_kernel<1, 3, 2, 2, 0, 2>"
     assert p1["workspace_bytes"] == p2["workspace_bytes"]
     assert int(p1["workspace_bytes"]) == q(binding.SK_OP_GRAM, 256, 256, 128, 128, 3, 1, 1, KEEP, f64) \
         == q(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, HAVE, f64)
@@ -122,7 +122,7 @@ def test_launch_plan_of_the_five_configurations(lib):
     # c3 (Gram matrix with 65536 pairs of short paths): one wave per pair fills the chip, and a pair is a single
     # strip (127 block rows at two per lane)
     p = _plan(binding.SK_OP_GRAM_BWD, 256, 256, 128, 128, 3, 1, 1, 0, f64)
-    assert p["mode"] == "solo" and p["kernel"] == "solo_bwd_kernel<1, 3, 2, 0, 0>" and p["strips"] == "1"
+    assert p["mode"] == "solo" and p["kernel"] == "solo_bwd_kernel<1, 3, 2, 0, 0, 2>" and p["strips"] == "1"
     # c5 (1048576 pairs, 63 x 63 unrefined cells, 16 channels).  Forward: quad mode, four pairs of a Gram row per
     # wave (16 lanes with four grid rows each per pair), two workgroups per compute unit; a pair batch of that shape
     # has no shared y path and takes the tile kernel.  Backward: the channel contraction dominates -> tile mode,
