@@ -220,6 +220,28 @@ def test_quad_mode_forward(nx, ny, L1, L2, d, flags, sym, dtype):
         assert torch.equal(K, K.T)
 
 
+@pytest.mark.parametrize("nx,ny,L,d,lam,flags,build", [(300, 5, 128, 6, 1, 0, 1), (290, 6, 128, 5, 1, 1, 1),
+                                                         (280, 7, 100, 8, 0, 0, 1), (270, 5, 65, 8, 2, 0, 1),
+                                                         (300, 6, 64, 8, 1, 0, 2), (300, 5, 128, 3, 1, 0, 2),
+                                                         (260, 6, 40, 16, 0, 8, 1), (260, 6, 30, 16, 0, 0, 1)])
+def test_solo_backward_builds(nx, ny, L, d, lam, flags, build):
+    # The solo backward kernels exist in a build for two waves per SIMD and one for a single wave (the whole register
+    # file); the launcher takes the second where LDS leaves room for one workgroup per compute unit, and kernels with
+    # many channels have no other.  Both builds against the oracle, the build named by the launch plan.
+    rng = np.random.default_rng(1200 + L + d)
+    X = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (nx, L, d)), axis=1)
+    Y = np.cumsum(rng.normal(0.0, (1.0 / (d * L)) ** 0.5, (ny, L, d)), axis=1)
+    desc = sk.sigkernel_describe(sk.SK_OP_GRAM_BWD, nx, ny, L, L, d, lam, lam, flags, sk.SK_F64)
+    assert "mode=solo" in desc and ", %d> " % build in desc, desc
+    W = workloads.upstream_weights(61, (nx, ny))
+    K, gX, gY = sk.sigkernel_gram(dev(X), dev(Y), dev(W), lam, lam, flags)
+    torch.cuda.synchronize()
+    Kref, gXr, gYr = oracle.gram(X, Y, W, lam, lam, flags)
+    check_values(host(K), Kref, torch.float64, "K")
+    check_grads(host(gX), gXr, torch.float64, "grad_X")
+    check_grads(host(gY), gYr, torch.float64, "grad_Y")
+
+
 def test_tile_mode_pair_batch():
     # a batch of pairs (not a Gram matrix) large enough to leave lock-step mode: every pair brings its own y path
     B, L, d = 1100, 48, 16
